@@ -1,0 +1,205 @@
+/*
+ * pahq.h -- C ABI of libpahq: the ACDC edge-ablation loop under per-attention-head
+ * mixed precision (PAHQ) on one AMD MI355X (gfx950).
+ *
+ * What the library computes (citations are to the PAHQ paper):
+ *   - A transformer is a graph whose nodes are attention heads and MLP layers
+ *     (plus the embedding and the unembedding); a node's input is the sum of
+ *     the outputs of its predecessors (Appendix "Preliminaries", Circuit
+ *     Discovery).  Head inputs are split into query, key and value inputs.
+ *   - Removing an edge replaces the sender's activation at that receiver by the
+ *     activation of a run on the corrupted prompt (activation patching, same
+ *     appendix); ACDC removes an edge when the loss change stays below a
+ *     threshold tau (Eq. C = G \ {e : Delta L(e) < tau}); the loss is the KL
+ *     divergence to the clean model's output distribution (Appendix "Metrics").
+ *   - While an edge is evaluated only the investigated head runs in fp32; all
+ *     other heads, the MLPs and the unembedding run on FP8 E4M3 operands
+ *     (Sec. "Selective Precision Allocation Strategy", Eq. P_t; Sec.
+ *     "Mixed-Precision Computation Design"); the attention core, norms, residual
+ *     sums and the loss stay in fp32 (Sec. "Scheduler Implementation", Phase 3).
+ *   - Quantisation is round-to-nearest with the scale set by the absolute
+ *     maximum (Appendix "Quantization", Eq. RTN-Q), applied to the E4M3 grid
+ *     (bias 7, smallest normal 2^-6, largest 448):
+ *         scale = amax / 448 (1 if amax = 0), inv = 1 / scale, code = rne_e4m3(x * inv),
+ *     every step one IEEE binary32 operation, |x*inv| > 448 saturating.  Weights
+ *     carry one scale per slice (each head's W_Q, W_K, W_V, W_O; each layer's
+ *     W_in, W_gate, W_out; W_U), activations one scale per row of the GEMM's left
+ *     operand (per head for the attention outputs).
+ *
+ * Ids.  mu = 1 if d_mlp > 0 else 0.
+ *   senders    0 = EMBED; HEAD(l,h) = 1 + l*(H+mu) + h; MLP(l) = 1 + l*(H+mu) + H
+ *   receivers  HEADIN(l,h,c) = l*(3H+mu) + 3h + c (c: 0 query, 1 key, 2 value);
+ *              MLPIN(l) = l*(3H+mu) + 3H; OUT = L*(3H+mu)
+ *   An edge (s -> r) exists iff s is strictly upstream of r; for every receiver
+ *   these are the senders 0 .. pahq_n_upstream(r)-1.  Canonical edge order:
+ *   receivers ascending, then senders ascending.
+ *
+ * Conventions.  Every function returns 0 or a negative PAHQ_E* code; nothing is
+ * printed, nothing throws, and a failed call leaves the model state unchanged.
+ * Pointers are HOST pointers unless the comment says "device".  All device work
+ * is enqueued on the stream given to pahq_init_model; calls that return host
+ * values synchronise that stream.  The library performs no device allocation:
+ * everything lives in the caller's workspace.  Not thread-safe per model.
+ * There is no CPU fallback: without a usable HIP device every call that needs
+ * one fails with PAHQ_EHIP.
+ */
+#ifndef PAHQ_H
+#define PAHQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  PAHQ_OK = 0,
+  PAHQ_EINVAL = -1,   /* bad argument (null pointer, id out of range, shape mismatch)   */
+  PAHQ_ESTATE = -2,   /* call out of order (e.g. eval before clean_cache)               */
+  PAHQ_ENOMEM = -3,   /* workspace too small                                            */
+  PAHQ_EHIP = -4,     /* a HIP runtime call failed / no device                          */
+  PAHQ_ENAN = -5,     /* non-finite weight                                              */
+  PAHQ_EUNSUPPORTED = -6 /* valid request that this build does not implement           */
+};
+
+enum { PAHQ_NORM_LAYER = 0, PAHQ_NORM_RMS = 1 };
+enum { PAHQ_ACT_NONE = 0, PAHQ_ACT_GELU = 1, PAHQ_ACT_SWIGLU = 2 };
+enum { PAHQ_POS_LEARNED = 0, PAHQ_POS_ROPE = 1 };
+enum { PAHQ_ALL_FP32 = 0, PAHQ_ALL_FP8 = 1, PAHQ_PAHQ = 2 };
+enum { PAHQ_LOGITS_CLEAN = 0, PAHQ_LOGITS_CORRUPT = 1 };
+enum { PAHQ_MMA_FP8 = 0, PAHQ_MMA_F16_EXACT = 1 };
+enum { PAHQ_W_Q = 0, PAHQ_W_K = 1, PAHQ_W_V = 2, PAHQ_W_O = 3, PAHQ_W_IN = 4, PAHQ_W_GATE = 5,
+       PAHQ_W_OUT = 6, PAHQ_W_U = 7 };
+
+typedef struct pahq_model pahq_model;   /* opaque, owned by the library (host memory) */
+
+/* Plain data, caller-owned, copied by pahq_init_model. */
+typedef struct {
+  int32_t n_layers, n_heads, d_head, d_model;
+  int32_t d_mlp;            /* 0 = attention-only model                                         */
+  int32_t vocab, n_ctx;     /* n_ctx: rows of W_pos (learned positions); sequences must fit      */
+  int32_t norm;             /* PAHQ_NORM_*: LayerNorm (biased variance) or RMSNorm (no offset)   */
+  int32_t act;              /* PAHQ_ACT_*: GELU is the tanh form; SWIGLU = silu(x W_gate)*(x W_in) */
+  int32_t pos;              /* PAHQ_POS_*: ROPE rotates pairs (i, i + d_head/2) of q and k        */
+  float norm_eps, rope_theta;
+  int32_t split_qkv;        /* must be 1: query, key and value inputs are separate receivers      */
+  int32_t precision;        /* PAHQ_PAHQ: fp32 investigated head (the head a candidate edge feeds);
+                               PAHQ_ALL_FP8: no fp32 head (all-8-bit RTN baseline);
+                               PAHQ_ALL_FP32: not implemented -> PAHQ_EUNSUPPORTED               */
+  int32_t max_batch_edges;  /* most candidates evaluated in one device batch (>= 1)               */
+  int32_t mma;              /* how the E4M3 x E4M3 products are summed:
+                               PAHQ_MMA_FP8: the FP8 matrix-core instruction.  Its adder aligns the
+                               products of one instruction to the largest one and keeps a fixed-point
+                               window below it, so a sum can deviate from the exact one by up to about
+                               2^-13 of sum|a*w| (measured on gfx950; ~1e-5 on normally distributed rows).
+                               PAHQ_MMA_F16_EXACT: the same codes decoded to fp16 (exact) and fed to the
+                               fp16 matrix cores: exact products, fp32 accumulation, half the peak rate.
+                               Codes and scales are identical in both modes.                        */
+} pahq_config;
+
+/* fp32 master weights, row-major.  All pointers host memory (on_device = 0) or
+ * all device memory (on_device = 1); the library copies them into the workspace.
+ *   W_E [vocab][d_model]   W_pos [n_ctx][d_model] (learned positions only, else NULL)
+ *   W_Q, W_K, W_V [L][H][d_model][d_head]   b_Q, b_K, b_V [L][H][d_head]
+ *   W_O [L][H][d_head][d_model]             b_O [L][d_model]
+ *   ln1_g, ln1_b, ln2_g, ln2_b [L][d_model] lnf_g, lnf_b [d_model]  (the *_b are ignored for RMSNorm)
+ *   W_in [L][d_model][d_mlp]  b_in [L][d_mlp]  W_gate [L][d_model][d_mlp] (SwiGLU only)
+ *   W_out [L][d_mlp][d_model] b_out [L][d_model]   (all NULL when d_mlp = 0)
+ *   W_U [d_model][vocab]      b_U [vocab]
+ * b_O and b_out are constants of the residual stream, not part of any sender's output. */
+typedef struct {
+  const float *W_E, *W_pos, *W_Q, *W_K, *W_V, *W_O, *b_Q, *b_K, *b_V, *b_O;
+  const float *ln1_g, *ln1_b, *ln2_g, *ln2_b, *W_in, *b_in, *W_gate, *W_out, *b_out;
+  const float *lnf_g, *lnf_b, *W_U, *b_U;
+  int32_t on_device;
+} pahq_weights;
+
+/* One evaluated candidate of a sweep, in evaluation order. */
+typedef struct {
+  int32_t receiver, sender;
+  float kl_new;      /* KL with the candidate edge removed on top of the current removed set */
+  float kl_cur;      /* KL of the current removed set before the decision                   */
+  int32_t removed;   /* 1 if kl_new - kl_cur < tau (edge removed, kl_cur becomes kl_new)     */
+} pahq_trace_rec;
+
+/* ---- graph helpers (pure host arithmetic, no device needed) ---------------- */
+int pahq_n_senders(const pahq_config*, int32_t* out);
+int pahq_n_receivers(const pahq_config*, int32_t* out);
+int pahq_n_upstream(const pahq_config*, int32_t receiver, int32_t* out);   /* senders 0..out-1 feed it */
+int pahq_edge_count(const pahq_config*, int64_t* out);
+int pahq_edge_id(const pahq_config*, int32_t sender, int32_t receiver, int64_t* out); /* canonical index */
+int pahq_node_of_receiver(const pahq_config*, int32_t receiver, int32_t* sender_out); /* -1 for OUT */
+
+/* Bytes of device workspace pahq_init_model needs for batches of B sequences
+ * of S tokens (paper, Appendix "Integration with ACDC": all low-precision
+ * weights resident on the device; here the fp32 masters and every activation
+ * cache are resident too). */
+int pahq_workspace_bytes(const pahq_config*, int32_t B, int32_t S, size_t* out);
+
+/* Copies the fp32 masters into `workspace` (DEVICE memory, 256-byte aligned,
+ * caller-owned, must outlive the model) and quantises every weight slice to
+ * E4M3 codes + scale (Appendix "Quantization", Eq. RTN-Q).  `hip_stream` is a
+ * hipStream_t (NULL = default stream).  PAHQ_ENAN if a weight is not finite. */
+int pahq_init_model(const pahq_config*, const pahq_weights*, int32_t B, int32_t S,
+                    void* workspace, size_t workspace_bytes, void* hip_stream, pahq_model** out);
+
+/* Runs the clean and the corrupted prompt batch through the model (no fp32
+ * head) and caches every sender's output for both, their difference and the
+ * residual stream (Appendix "Integration with ACDC": first and second
+ * inference, done once instead of once per edge).  Tokens: host int32 [B][S],
+ * 0 <= id < vocab.  Resets the removed set to empty. */
+int pahq_clean_cache(pahq_model*, const int32_t* clean_tok, const int32_t* corrupt_tok);
+
+/* Evaluates n candidate edges (sender_ids[i] -> receiver) INDEPENDENTLY: the
+ * i-th result is the batch-mean KL(P_ref || P_i) at the last position, where
+ * P_i is the clean run with the current removed set plus that one edge
+ * removed, and P_ref the clean run with nothing removed, both under the
+ * precision set of `receiver` (third inference of the paper's algorithm; Eq.
+ * Delta L).  Does not modify the removed set.  kl_out: host, n floats.  Any n
+ * >= 0; batches of max_batch_edges are formed internally.  Results do not
+ * depend on n, on the other candidates or on earlier calls. */
+int pahq_eval_edges(pahq_model*, int32_t receiver, const int32_t* sender_ids, int32_t n, float* kl_out);
+
+/* KL of the current removed set itself under the precision set of `receiver`. */
+int pahq_eval_current(pahq_model*, int32_t receiver, float* kl_out);
+
+/* One reverse-topological ACDC pass from the empty removed set (Eq. C = G \
+ * {e : Delta L(e) < tau}): receivers in descending id, senders in descending
+ * id; an edge is removed iff kl_new - kl_cur < tau (then kl_cur = kl_new); a
+ * receiver whose node has no kept outgoing edge is skipped and all its in-edges
+ * are removed.  Candidates are evaluated in speculative device batches; the
+ * decisions are exactly those of the one-by-one procedure.
+ *   receivers/n_receivers  restrict the pass to these receiver ids (NULL/0 = all)
+ *   kept      host, pahq_edge_count bytes, canonical order, 1 = edge kept (may be NULL)
+ *   n_evals   number of candidates whose decision was taken (may be NULL)
+ *   trace     host array of trace_cap records, first min(n_evals, trace_cap) filled (may be NULL)
+ * The removed set of the model is left at the sweep's result. */
+int pahq_acdc_sweep(pahq_model*, float tau, const int32_t* receivers, int32_t n_receivers,
+                    uint8_t* kept, int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap);
+
+/* Removed set, canonical edge order, one byte per edge (1 = removed). */
+int pahq_set_removed(pahq_model*, const uint8_t* removed);
+int pahq_get_removed(pahq_model*, uint8_t* removed);
+
+/* ---- test hooks --------------------------------------------------------------- */
+/* E4M3 codes ([K][N] in the master's row-major layout) and scale of one weight
+ * slice: which = PAHQ_W_*; head is ignored for W_IN/W_GATE/W_OUT, layer and head for W_U. */
+int pahq_get_weight_q(pahq_model*, int32_t which, int32_t layer, int32_t head, uint8_t* codes, float* scale);
+/* The activation quantiser as a function: host x [rows][cols] -> codes, one scale per row.
+ * cols <= 16384. */
+int pahq_quantize_rows(pahq_model*, const float* x, int32_t rows, int32_t cols, uint8_t* codes, float* scales);
+/* Last-position logits [B][vocab] of the cached clean / corrupted run. */
+int pahq_get_logits(pahq_model*, int32_t which, float* out);
+/* Cached output [B*S][d_model] of one sender in the clean (which=0) or corrupted (1) run. */
+int pahq_get_sender_output(pahq_model*, int32_t which, int32_t sender, float* out);
+/* Counters since init: [0] candidate evaluations, [1] device batches, [2] forward passes of any kind. */
+int pahq_get_counters(pahq_model*, int64_t out[3]);
+
+const char* pahq_strerror(int code);
+void pahq_free(pahq_model*);            /* frees host state only; the workspace stays the caller's */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PAHQ_H */

@@ -1,0 +1,239 @@
+"""ctypes binding of libpahq.so.  Argument marshalling only: every step of the
+method runs inside the library's HIP kernels.  torch is used to allocate the
+device workspace and to provide the stream."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpahq.so")
+
+ALL_FP32, ALL_FP8, PAHQ = 0, 1, 2
+MMA_FP8, MMA_F16_EXACT = 0, 1
+W_Q, W_K, W_V, W_O, W_IN, W_GATE, W_OUT, W_U = range(8)
+
+
+class PahqError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        super().__init__(f"{what}: {lib().pahq_strerror(code).decode()} ({code})")
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "n_heads", "d_head", "d_model", "d_mlp", "vocab", "n_ctx",
+                                         "norm", "act", "pos")] + \
+               [("norm_eps", C.c_float), ("rope_theta", C.c_float)] + \
+               [(n, C.c_int32) for n in ("split_qkv", "precision", "max_batch_edges", "mma")]
+
+    @classmethod
+    def from_shape(cls, shape, precision=PAHQ, max_batch_edges=32, mma=MMA_FP8):
+        return cls(n_layers=shape.n_layers, n_heads=shape.n_heads, d_head=shape.d_head, d_model=shape.d_model,
+                   d_mlp=shape.d_mlp, vocab=shape.vocab, n_ctx=shape.n_ctx, norm=shape.norm, act=shape.act,
+                   pos=shape.pos, norm_eps=shape.norm_eps, rope_theta=shape.rope_theta, split_qkv=1,
+                   precision=precision, max_batch_edges=max_batch_edges, mma=mma)
+
+
+_W_NAMES = ("W_E", "W_pos", "W_Q", "W_K", "W_V", "W_O", "b_Q", "b_K", "b_V", "b_O", "ln1_g", "ln1_b", "ln2_g",
+            "ln2_b", "W_in", "b_in", "W_gate", "W_out", "b_out", "lnf_g", "lnf_b", "W_U", "b_U")
+
+
+class Weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _W_NAMES] + [("on_device", C.c_int32)]
+
+
+class TraceRec(C.Structure):
+    _fields_ = [("receiver", C.c_int32), ("sender", C.c_int32), ("kl_new", C.c_float), ("kl_cur", C.c_float),
+                ("removed", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads libpahq.so (built in-tree by paper_2510_23264_amd.build).  There is no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: run `python -m paper_2510_23264_amd.build` first")
+        L = C.CDLL(_LIB_PATH)
+        cfgp, i32p, i64p, u8p, f32p = C.POINTER(Config), C.POINTER(C.c_int32), C.POINTER(C.c_int64), \
+            C.POINTER(C.c_uint8), C.POINTER(C.c_float)
+        sig = {
+            "pahq_n_senders": [cfgp, i32p], "pahq_n_receivers": [cfgp, i32p],
+            "pahq_n_upstream": [cfgp, C.c_int32, i32p], "pahq_edge_count": [cfgp, i64p],
+            "pahq_edge_id": [cfgp, C.c_int32, C.c_int32, i64p], "pahq_node_of_receiver": [cfgp, C.c_int32, i32p],
+            "pahq_workspace_bytes": [cfgp, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)],
+            "pahq_init_model": [cfgp, C.POINTER(Weights), C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
+                                C.POINTER(C.c_void_p)],
+            "pahq_clean_cache": [C.c_void_p, i32p, i32p],
+            "pahq_eval_edges": [C.c_void_p, C.c_int32, i32p, C.c_int32, f32p],
+            "pahq_eval_current": [C.c_void_p, C.c_int32, f32p],
+            "pahq_acdc_sweep": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
+            "pahq_set_removed": [C.c_void_p, u8p], "pahq_get_removed": [C.c_void_p, u8p],
+            "pahq_get_weight_q": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, u8p, f32p],
+            "pahq_quantize_rows": [C.c_void_p, f32p, C.c_int32, C.c_int32, u8p, f32p],
+            "pahq_get_logits": [C.c_void_p, C.c_int32, f32p],
+            "pahq_get_sender_output": [C.c_void_p, C.c_int32, C.c_int32, f32p],
+            "pahq_get_counters": [C.c_void_p, i64p],
+        }
+        for name, args in sig.items():
+            fn = getattr(L, name)
+            fn.argtypes, fn.restype = args, C.c_int
+        L.pahq_strerror.argtypes, L.pahq_strerror.restype = [C.c_int], C.c_char_p
+        L.pahq_free.argtypes, L.pahq_free.restype = [C.c_void_p], None
+        _lib = L
+    return _lib
+
+
+def _chk(code, what):
+    if code != 0:
+        raise PahqError(code, what)
+
+
+def _ptr(a, ctype):
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+def _scalar(fn, ctype, cfg, *args):
+    out = ctype()
+    _chk(fn(C.byref(cfg), *args, C.byref(out)), fn.__name__)
+    return out.value
+
+
+def n_senders(cfg): return _scalar(lib().pahq_n_senders, C.c_int32, cfg)
+def n_receivers(cfg): return _scalar(lib().pahq_n_receivers, C.c_int32, cfg)
+def n_upstream(cfg, r): return _scalar(lib().pahq_n_upstream, C.c_int32, cfg, r)
+def edge_count(cfg): return _scalar(lib().pahq_edge_count, C.c_int64, cfg)
+def edge_id(cfg, s, r): return _scalar(lib().pahq_edge_id, C.c_int64, cfg, s, r)
+def node_of_receiver(cfg, r): return _scalar(lib().pahq_node_of_receiver, C.c_int32, cfg, r)
+def workspace_bytes(cfg, B, S): return _scalar(lib().pahq_workspace_bytes, C.c_size_t, cfg, B, S)
+
+
+class Model:
+    """pahq_init_model + the calls on the handle.  `weights`: dict of float32 numpy arrays
+    (layouts as in include/pahq.h)."""
+
+    def __init__(self, shape, weights, B, S, precision=PAHQ, max_batch_edges=32, mma=MMA_FP8, device="cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no HIP device: libpahq has no CPU path")
+        self.cfg = Config.from_shape(shape, precision, max_batch_edges, mma)
+        self.B, self.S, self.T = B, S, B * S
+        self.n_edges = edge_count(self.cfg)
+        nbytes = workspace_bytes(self.cfg, B, S)
+        self._torch = torch
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = (self.workspace.data_ptr() + 255) // 256 * 256
+        self.stream = torch.cuda.current_stream(self.device)
+        w = Weights()
+        self._keep = []
+        for n in _W_NAMES:
+            a = weights.get(n)
+            if a is None:
+                setattr(w, n, None)
+            else:
+                a = np.ascontiguousarray(a, dtype=np.float32)
+                self._keep.append(a)
+                setattr(w, n, a.ctypes.data)
+        w.on_device = 0
+        h = C.c_void_p()
+        _chk(lib().pahq_init_model(C.byref(self.cfg), C.byref(w), B, S, C.c_void_p(base), C.c_size_t(nbytes),
+                                   C.c_void_p(self.stream.cuda_stream), C.byref(h)), "pahq_init_model")
+        self.h = h
+        self._keep = []
+        self.workspace_bytes = nbytes
+
+    def close(self):
+        if getattr(self, "h", None):
+            self._torch.cuda.synchronize(self.device)
+            lib().pahq_free(self.h)
+            self.h = None
+            self.workspace = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def clean_cache(self, clean_tok, corrupt_tok):
+        a = np.ascontiguousarray(clean_tok, dtype=np.int32)
+        b = np.ascontiguousarray(corrupt_tok, dtype=np.int32)
+        if a.shape != (self.B, self.S) or b.shape != (self.B, self.S):
+            raise ValueError("token arrays must be [B][S]")
+        _chk(lib().pahq_clean_cache(self.h, _ptr(a, C.c_int32), _ptr(b, C.c_int32)), "pahq_clean_cache")
+
+    def eval_edges(self, receiver, sender_ids):
+        s = np.ascontiguousarray(sender_ids, dtype=np.int32)
+        out = np.empty(s.size, dtype=np.float32)
+        _chk(lib().pahq_eval_edges(self.h, int(receiver), _ptr(s, C.c_int32), s.size, _ptr(out, C.c_float)),
+             "pahq_eval_edges")
+        return out
+
+    def eval_current(self, receiver):
+        out = C.c_float()
+        _chk(lib().pahq_eval_current(self.h, int(receiver), C.byref(out)), "pahq_eval_current")
+        return out.value
+
+    def acdc_sweep(self, tau, receivers=None, trace_cap=None):
+        """Returns (kept uint8[n_edges], n_evals, trace structured array)."""
+        kept = np.empty(self.n_edges, dtype=np.uint8)
+        n_evals = C.c_int64()
+        cap = self.n_edges if trace_cap is None else int(trace_cap)
+        trace = (TraceRec * max(cap, 1))()
+        if receivers is None:
+            rp, rn = None, 0
+        else:
+            r = np.ascontiguousarray(receivers, dtype=np.int32)
+            rp, rn = _ptr(r, C.c_int32), r.size
+        _chk(lib().pahq_acdc_sweep(self.h, C.c_float(tau), rp, rn, _ptr(kept, C.c_uint8), C.byref(n_evals), trace,
+                                   cap), "pahq_acdc_sweep")
+        n = min(n_evals.value, cap)
+        tr = np.ctypeslib.as_array(trace)[:n].copy() if n else np.zeros(0, dtype=np.dtype(TraceRec))
+        return kept, n_evals.value, tr
+
+    def set_removed(self, removed):
+        r = np.ascontiguousarray(removed, dtype=np.uint8)
+        if r.size != self.n_edges:
+            raise ValueError("removed must have one byte per edge")
+        _chk(lib().pahq_set_removed(self.h, _ptr(r, C.c_uint8)), "pahq_set_removed")
+
+    def get_removed(self):
+        r = np.empty(self.n_edges, dtype=np.uint8)
+        _chk(lib().pahq_get_removed(self.h, _ptr(r, C.c_uint8)), "pahq_get_removed")
+        return r
+
+    def get_weight_q(self, which, layer, head, shape):
+        codes = np.empty(shape, dtype=np.uint8)
+        scale = C.c_float()
+        _chk(lib().pahq_get_weight_q(self.h, which, layer, head, _ptr(codes, C.c_uint8), C.byref(scale)),
+             "pahq_get_weight_q")
+        return codes, np.float32(scale.value)
+
+    def quantize_rows(self, x):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        rows, cols = x.shape
+        codes = np.empty((rows, cols), dtype=np.uint8)
+        scales = np.empty(rows, dtype=np.float32)
+        _chk(lib().pahq_quantize_rows(self.h, _ptr(x, C.c_float), rows, cols, _ptr(codes, C.c_uint8),
+                                      _ptr(scales, C.c_float)), "pahq_quantize_rows")
+        return codes, scales
+
+    def get_logits(self, which):
+        out = np.empty((self.B, self.cfg.vocab), dtype=np.float32)
+        _chk(lib().pahq_get_logits(self.h, which, _ptr(out, C.c_float)), "pahq_get_logits")
+        return out
+
+    def get_sender_output(self, which, sender):
+        out = np.empty((self.T, self.cfg.d_model), dtype=np.float32)
+        _chk(lib().pahq_get_sender_output(self.h, which, sender, _ptr(out, C.c_float)), "pahq_get_sender_output")
+        return out
+
+    def counters(self):
+        out = (C.c_int64 * 3)()
+        _chk(lib().pahq_get_counters(self.h, out), "pahq_get_counters")
+        return tuple(out)

@@ -1,0 +1,601 @@
+// C ABI of libpahq: model set-up, cache pass, edge evaluation, ACDC sweep.
+#include "engine.h"
+#include <algorithm>
+#include <math.h>
+#include <new>
+#include <string.h>
+
+using namespace pahq;
+
+#define HIPCHK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return PAHQ_EHIP; } while (0)
+#define PCHK(x) do { int r_ = (x); if (r_ != PAHQ_OK) return r_; } while (0)
+
+namespace {
+
+int check_config(const pahq_config* c) {
+  if (!c) return PAHQ_EINVAL;
+  if (c->n_layers < 1 || c->n_heads < 1 || c->d_head < 1 || c->d_model < 1 || c->vocab < 2) return PAHQ_EINVAL;
+  if (c->d_mlp < 0 || c->max_batch_edges < 1 || c->max_batch_edges > 4096) return PAHQ_EINVAL;
+  if (c->norm != PAHQ_NORM_LAYER && c->norm != PAHQ_NORM_RMS) return PAHQ_EINVAL;
+  if (c->pos != PAHQ_POS_LEARNED && c->pos != PAHQ_POS_ROPE) return PAHQ_EINVAL;
+  if (c->act < PAHQ_ACT_NONE || c->act > PAHQ_ACT_SWIGLU) return PAHQ_EINVAL;
+  if (c->precision < PAHQ_ALL_FP32 || c->precision > PAHQ_PAHQ) return PAHQ_EINVAL;
+  if (!(c->norm_eps >= 0.f)) return PAHQ_EINVAL;
+  if (c->mma != PAHQ_MMA_FP8 && c->mma != PAHQ_MMA_F16_EXACT) return PAHQ_EINVAL;
+  return PAHQ_OK;
+}
+// what this build of the kernels supports
+int check_supported(const pahq_config* c, int B, int S) {
+  if (c->split_qkv != 1) return PAHQ_EUNSUPPORTED;
+  if (c->precision == PAHQ_ALL_FP32) return PAHQ_EUNSUPPORTED;
+  if (c->d_model % 64 != 0 || c->d_model > 4096) return PAHQ_EUNSUPPORTED;
+  if (c->d_head % 16 != 0 || c->d_head > 128) return PAHQ_EUNSUPPORTED;
+  if (c->pos == PAHQ_POS_ROPE && (c->d_head & 1)) return PAHQ_EUNSUPPORTED;
+  if (c->d_mlp > 0 && c->act == PAHQ_ACT_NONE) return PAHQ_EUNSUPPORTED;
+  if (B < 1 || S < 1 || S > 32) return PAHQ_EUNSUPPORTED;
+  if (c->pos == PAHQ_POS_LEARNED && S > c->n_ctx) return PAHQ_EINVAL;
+  return PAHQ_OK;
+}
+
+inline int pad128(int x) { return (x + 127) / 128 * 128; }
+
+struct Bump {
+  char* base; size_t off;
+  template <class Tp> Tp* take(size_t n) {
+    off = (off + 255) / 256 * 256;
+    Tp* p = base ? (Tp*)(base + off) : nullptr;
+    off += n * sizeof(Tp);
+    return p;
+  }
+};
+
+void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
+  M->cfg = *c;
+  M->g = GraphDims(c->n_layers, c->n_heads, c->d_mlp > 0);
+  M->B = B; M->S = S; M->T = B * S; M->L = c->n_layers; M->H = c->n_heads; M->dh = c->d_head;
+  M->d = c->d_model; M->m = c->d_mlp; M->V = c->vocab;
+  M->Kd = pad128(M->d); M->Kh = pad128(M->dh); M->Km = pad128(M->m > 0 ? M->m : 1);
+  M->nmax = c->max_batch_edges; M->G = 3 * M->H + 1;
+  M->tile = (long long)M->T * M->d;
+}
+
+size_t arena_slot_bytes(const pahq_model* M) {
+  size_t Nr = M->g.Nr, Ns = M->g.Ns, L = M->L, H = M->H;
+  size_t b = Nr * sizeof(GroupDesc) + Nr * (Ns / 2 + 2) * sizeof(Term) + L * (5 * H + 8) * sizeof(GemmProb) +
+             2 * L * sizeof(CombineDesc) + L * (H + 1) * sizeof(CombineSrc) + 65536;
+  return (b + 4095) / 4096 * 4096;
+}
+
+// Carves the workspace; with base == nullptr only the total is computed.
+size_t layout(pahq_model* M, char* base) {
+  Bump b{base, 0};
+  const size_t L = M->L, H = M->H, dh = M->dh, d = M->d, m = M->m, V = M->V, T = M->T, B = M->B;
+  const size_t Kd = M->Kd, Kh = M->Kh, Km = M->Km, n = M->nmax, G = M->G, Ns = M->g.Ns, tile = M->tile;
+  const bool mlp = m > 0, swi = M->cfg.act == PAHQ_ACT_SWIGLU, learned = M->cfg.pos == PAHQ_POS_LEARNED;
+  M->W_E = b.take<float>(V * d);
+  M->W_pos = learned ? b.take<float>((size_t)M->cfg.n_ctx * d) : nullptr;
+  M->W_Q = b.take<float>(L * H * d * dh); M->W_K = b.take<float>(L * H * d * dh); M->W_V = b.take<float>(L * H * d * dh);
+  M->W_O = b.take<float>(L * H * dh * d);
+  M->b_Q = b.take<float>(L * H * dh); M->b_K = b.take<float>(L * H * dh); M->b_V = b.take<float>(L * H * dh);
+  M->b_O = b.take<float>(L * d);
+  M->ln1_g = b.take<float>(L * d); M->ln1_b = b.take<float>(L * d);
+  M->ln2_g = mlp ? b.take<float>(L * d) : nullptr; M->ln2_b = mlp ? b.take<float>(L * d) : nullptr;
+  M->W_in = mlp ? b.take<float>(L * d * m) : nullptr; M->b_in = mlp ? b.take<float>(L * m) : nullptr;
+  M->W_gate = (mlp && swi) ? b.take<float>(L * d * m) : nullptr;
+  M->W_out = mlp ? b.take<float>(L * m * d) : nullptr; M->b_out = mlp ? b.take<float>(L * d) : nullptr;
+  M->lnf_g = b.take<float>(d); M->lnf_b = b.take<float>(d);
+  M->W_U = b.take<float>(d * V); M->b_U = b.take<float>(V);
+  M->zeros_d = b.take<float>(d);
+  M->bqkv = b.take<float>(L * 3 * H * dh);
+  M->qkv_codes = b.take<uint8_t>(L * 3 * H * dh * Kd); M->qkv_scale = b.take<float>(L * 3 * H);
+  M->o_codes = b.take<uint8_t>(L * H * d * Kh); M->o_scale = b.take<float>(L * H);
+  M->in_codes = mlp ? b.take<uint8_t>(L * m * Kd) : nullptr; M->in_scale = mlp ? b.take<float>(L) : nullptr;
+  M->gate_codes = (mlp && swi) ? b.take<uint8_t>(L * m * Kd) : nullptr;
+  M->gate_scale = (mlp && swi) ? b.take<float>(L) : nullptr;
+  M->out_codes = mlp ? b.take<uint8_t>(L * d * Km) : nullptr; M->out_scale = mlp ? b.take<float>(L) : nullptr;
+  M->u_codes = b.take<uint8_t>(V * Kd); M->u_scale = b.take<float>(1);
+  M->amax_tmp = b.take<unsigned>((L * H + 4 + 3) / 4 * 4); M->flag_tmp = b.take<int>(4);
+  M->tok_clean = b.take<int>(T); M->tok_corrupt = b.take<int>(T); M->send_dev = b.take<int>(n);
+  M->clean = b.take<float>(Ns * tile); M->corrupt = b.take<float>(Ns * tile); M->delta = b.take<float>((Ns + 1) * tile);   // tile Ns stays zero
+  M->rc = b.take<float>((2 * L + 1) * tile); M->rx = b.take<float>((2 * L + 1) * tile);
+  M->logits_clean = b.take<float>(B * V); M->logits_corrupt = b.take<float>(B * V); M->logz_clean = b.take<double>(B);
+  M->cpi = b.take<float>(Ns * tile); M->rxpi = b.take<float>((2 * L + 1) * tile);
+  M->ref_logits = b.take<float>(B * V); M->ref_logz = b.take<double>(B);
+  M->xv = b.take<float>(tile);
+  M->run_a = b.take<float>(n * tile); M->run_b = b.take<float>(n * tile);
+  M->xcodes = b.take<uint8_t>(n * G * T * Kd); M->xscale = b.take<float>(n * G * T); M->xf32 = b.take<float>(n * 3 * tile);
+  M->qkv = b.take<float>(n * T * 3 * H * dh);
+  M->zcodes = b.take<uint8_t>(n * T * H * Kh); M->zscale = b.take<float>(n * T * H); M->zf32 = b.take<float>(n * T * dh);
+  M->headout = b.take<float>(n * H * tile);
+  M->mlpout = mlp ? b.take<float>(n * tile) : nullptr;
+  M->hid = mlp ? b.take<float>(n * T * m) : nullptr; M->hid2 = (mlp && swi) ? b.take<float>(n * T * m) : nullptr;
+  M->hcodes = mlp ? b.take<uint8_t>(n * T * Km) : nullptr; M->hscale = mlp ? b.take<float>(n * T) : nullptr;
+  M->lastcodes = b.take<uint8_t>(n * B * Kd); M->lastscale = b.take<float>(n * B); M->logits = b.take<float>(n * B * V);
+  M->pool_tiles = (long long)std::max<size_t>(2 * Ns, 4 * n);
+  M->slots = b.take<float>((size_t)M->pool_tiles * tile);
+  M->row_kl = b.take<double>(n * B); M->kl_dev = b.take<double>(n);
+  M->arena.slot_bytes = arena_slot_bytes(M);
+  for (int i = 0; i < Arena::SLOTS; i++) M->arena.dev[i] = b.take<char>(M->arena.slot_bytes);
+  return (b.off + 255) / 256 * 256;
+}
+
+int copy_in(pahq_model* M, float* dst, const float* src, size_t n, int on_device) {
+  if (!dst) return PAHQ_OK;
+  if (!src) return PAHQ_EINVAL;
+  HIPCHK(hipMemcpyAsync(dst, src, n * sizeof(float), on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, M->stream));
+  return PAHQ_OK;
+}
+
+// quantise n_slices contiguous slices of shape [K][N]; slice i goes to codes0 + i*codes_stride, scale0 + i*scale_stride
+int quantise_class(pahq_model* M, const float* w, int n_slices, int K, int N, uint8_t* codes0, long long codes_stride,
+                   int ldq, float* scale0, int scale_stride) {
+  HIPCHK(launch_fill_zero(M->amax_tmp, ((size_t)n_slices * 4 + 15) / 16 * 16, M->stream));
+  HIPCHK(launch_slice_absmax(w, (long long)K * N, n_slices, M->amax_tmp, M->flag_tmp, M->stream));
+  for (int i = 0; i < n_slices; i++)
+    HIPCHK(launch_quant_transpose(w + (long long)i * K * N, K, N, M->amax_tmp + i, scale0 + (long long)i * scale_stride,
+                                  codes0 + i * codes_stride, ldq, M->stream));
+  HIPCHK(hipStreamSynchronize(M->stream));       // amax_tmp is reused by the next class
+  return PAHQ_OK;
+}
+
+inline int64_t edge_index(const pahq_model* M, int s, int r) { return M->edge_off[r] + s; }
+
+bool node_is_live(const pahq_model* M, int v) {
+  int s = M->g.node_of_receiver(v);
+  if (s < 0) return true;
+  for (int r = 0; r < M->g.Nr; r++)
+    if (s < M->g.n_upstream(r) && !M->removed[edge_index(M, s, r)]) return true;
+  return false;
+}
+
+// copies a small host table to the device through the descriptor ring
+int upload_table(pahq_model* M, const void* src, size_t bytes, void** dev_out) {
+  Arena& A = M->arena;
+  if (bytes > A.slot_bytes) return PAHQ_ENOMEM;
+  int slot = A.next;
+  A.next = (A.next + 1) % Arena::SLOTS;
+  HIPCHK(hipEventSynchronize(A.ev[slot]));
+  memcpy(A.host[slot], src, bytes);
+  HIPCHK(hipMemcpyAsync(A.dev[slot], A.host[slot], bytes, hipMemcpyHostToDevice, M->stream));
+  HIPCHK(hipEventRecord(A.ev[slot], M->stream));
+  *dev_out = A.dev[slot];
+  return PAHQ_OK;
+}
+
+struct RecvCtx { int v, p0, pl, ph, n_eff; };
+
+// Brings the model into the state needed to evaluate edges into receiver v:
+// the state of v's fp32 head (corrupted run + reference distribution under that
+// precision set), the receiver plan for the current removed set, and v's
+// current input xv.
+int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
+  const GraphDims& g = M->g;
+  int kind, l, h, c;
+  g.receiver_info(v, kind, l, h, c);
+  ctx.v = v; ctx.p0 = g.pos_of_receiver(v);
+  ctx.pl = ctx.ph = -1;
+  if (M->cfg.precision == PAHQ_PAHQ && kind == 0) { ctx.pl = l; ctx.ph = h; }
+  if (ctx.pl >= 0 && (M->pi_l != ctx.pl || M->pi_h != ctx.ph)) {
+    PassArgs a; a.n = 1; a.p0 = ctx.p0; a.pl = ctx.pl; a.ph = ctx.ph; a.v = -1; a.patch_mode = 0;
+    a.kind = PI_CORRUPT; PCHK(run_pass(M, a, nullptr));
+    a.kind = PI_REF; PCHK(run_pass(M, a, nullptr));
+    M->pi_l = ctx.pl; M->pi_h = ctx.ph;
+  }
+  make_plan(M, ctx.p0, M->plan);
+  ctx.n_eff = M->nmax;
+  if (M->plan.n_slots > 0) ctx.n_eff = (int)std::min<long long>(M->nmax, M->pool_tiles / M->plan.n_slots);
+  if (ctx.n_eff < 1) return PAHQ_ENOMEM;
+  // xv = v's input under the current removed set (every sender upstream of v is cached)
+  const RecvSpec& sp = M->plan.spec[v];
+  float* base = sp.form == 2 ? corrupt_prefix(M, ctx.p0) : clean_prefix(M, ctx.p0);
+  std::vector<Term> terms;
+  for (int s : sp.senders) {
+    Term t; t.p = M->delta + (long long)s * M->tile; t.inst_stride = 0; t.sign = sp.form == 1 ? -1.f : 1.f; t.pad_ = 0;
+    terms.push_back(t);
+  }
+  void* dterms = nullptr;
+  if (!terms.empty()) PCHK(upload_table(M, terms.data(), terms.size() * sizeof(Term), &dterms));
+  HIPCHK(launch_tile_lincomb(M->xv, base, (const Term*)dterms, (int)terms.size(), M->tile, M->stream));
+  return PAHQ_OK;
+}
+
+// evaluates one device batch of candidates (senders already in send_host[0..n)); results in kl_host[0..n)
+int eval_batch(pahq_model* M, const RecvCtx& ctx, int n, int patch_mode) {
+  HIPCHK(hipMemcpyAsync(M->send_dev, M->send_host, (size_t)n * sizeof(int), hipMemcpyHostToDevice, M->stream));
+  PassArgs a; a.kind = CAND; a.p0 = ctx.p0; a.n = n; a.pl = ctx.pl; a.ph = ctx.ph; a.v = ctx.v; a.patch_mode = patch_mode;
+  PCHK(run_pass(M, a, &M->plan));
+  HIPCHK(hipMemcpyAsync(M->kl_host, M->kl_dev, (size_t)n * sizeof(double), hipMemcpyDeviceToHost, M->stream));
+  HIPCHK(hipStreamSynchronize(M->stream));
+  M->counters[0] += n; M->counters[1] += 1;
+  return PAHQ_OK;
+}
+
+int eval_state(pahq_model* M, const RecvCtx& ctx, double* kl) {
+  PassArgs a; a.kind = STATE; a.p0 = ctx.p0; a.n = 1; a.pl = ctx.pl; a.ph = ctx.ph; a.v = -1; a.patch_mode = 0;
+  PCHK(run_pass(M, a, &M->plan));
+  HIPCHK(hipMemcpyAsync(M->kl_host, M->kl_dev, sizeof(double), hipMemcpyDeviceToHost, M->stream));
+  HIPCHK(hipStreamSynchronize(M->stream));
+  *kl = M->kl_host[0];
+  return PAHQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pahq_n_senders(const pahq_config* c, int32_t* out) {
+  if (check_config(c) || !out) return PAHQ_EINVAL;
+  *out = GraphDims(c->n_layers, c->n_heads, c->d_mlp > 0).Ns; return PAHQ_OK;
+}
+int pahq_n_receivers(const pahq_config* c, int32_t* out) {
+  if (check_config(c) || !out) return PAHQ_EINVAL;
+  *out = GraphDims(c->n_layers, c->n_heads, c->d_mlp > 0).Nr; return PAHQ_OK;
+}
+int pahq_n_upstream(const pahq_config* c, int32_t r, int32_t* out) {
+  if (check_config(c) || !out) return PAHQ_EINVAL;
+  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0);
+  if (r < 0 || r >= g.Nr) return PAHQ_EINVAL;
+  *out = g.n_upstream(r); return PAHQ_OK;
+}
+int pahq_edge_count(const pahq_config* c, int64_t* out) {
+  if (check_config(c) || !out) return PAHQ_EINVAL;
+  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0);
+  int64_t n = 0;
+  for (int r = 0; r < g.Nr; r++) n += g.n_upstream(r);
+  *out = n; return PAHQ_OK;
+}
+int pahq_edge_id(const pahq_config* c, int32_t s, int32_t r, int64_t* out) {
+  if (check_config(c) || !out) return PAHQ_EINVAL;
+  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0);
+  if (r < 0 || r >= g.Nr || s < 0 || s >= g.n_upstream(r)) return PAHQ_EINVAL;
+  int64_t n = 0;
+  for (int q = 0; q < r; q++) n += g.n_upstream(q);
+  *out = n + s; return PAHQ_OK;
+}
+int pahq_node_of_receiver(const pahq_config* c, int32_t r, int32_t* out) {
+  if (check_config(c) || !out) return PAHQ_EINVAL;
+  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0);
+  if (r < 0 || r >= g.Nr) return PAHQ_EINVAL;
+  *out = g.node_of_receiver(r); return PAHQ_OK;
+}
+
+int pahq_workspace_bytes(const pahq_config* c, int32_t B, int32_t S, size_t* out) {
+  PCHK(check_config(c));
+  if (!out) return PAHQ_EINVAL;
+  PCHK(check_supported(c, B, S));
+  pahq_model* M = new (std::nothrow) pahq_model();
+  if (!M) return PAHQ_ENOMEM;
+  set_dims(M, c, B, S);
+  *out = layout(M, nullptr);
+  delete M;
+  return PAHQ_OK;
+}
+
+int pahq_init_model(const pahq_config* c, const pahq_weights* w, int32_t B, int32_t S, void* workspace,
+                    size_t workspace_bytes, void* hip_stream, pahq_model** out) {
+  PCHK(check_config(c));
+  if (!w || !workspace || !out) return PAHQ_EINVAL;
+  PCHK(check_supported(c, B, S));
+  if (((uintptr_t)workspace & 255) != 0) return PAHQ_EINVAL;
+  const bool mlp = c->d_mlp > 0, swi = c->act == PAHQ_ACT_SWIGLU, learned = c->pos == PAHQ_POS_LEARNED;
+  const float* req[] = {w->W_E, w->W_Q, w->W_K, w->W_V, w->W_O, w->b_Q, w->b_K, w->b_V, w->b_O, w->ln1_g, w->lnf_g, w->W_U, w->b_U};
+  for (const float* p : req) if (!p) return PAHQ_EINVAL;
+  if (learned && !w->W_pos) return PAHQ_EINVAL;
+  if (mlp && (!w->ln2_g || !w->W_in || !w->b_in || !w->W_out || !w->b_out)) return PAHQ_EINVAL;
+  if (mlp && swi && !w->W_gate) return PAHQ_EINVAL;
+  if (c->norm == PAHQ_NORM_LAYER && (!w->ln1_b || !w->lnf_b || (mlp && !w->ln2_b))) return PAHQ_EINVAL;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return PAHQ_EHIP;
+
+  pahq_model* M = new (std::nothrow) pahq_model();
+  if (!M) return PAHQ_ENOMEM;
+  set_dims(M, c, B, S);
+  M->stream = (hipStream_t)hip_stream;
+  size_t need = layout(M, (char*)workspace);
+  if (need > workspace_bytes) { delete M; return PAHQ_ENOMEM; }
+  M->ws = (char*)workspace; M->ws_bytes = workspace_bytes; M->ws_used = need;
+  M->kl_host = nullptr; M->send_host = nullptr;
+  for (int i = 0; i < Arena::SLOTS; i++) { M->arena.host[i] = nullptr; M->arena.ev[i] = nullptr; }
+  M->arena.next = 0;
+  int rc = PAHQ_OK;
+  auto fail = [&](int code) { pahq_free(M); return code; };
+  if (hipHostMalloc((void**)&M->kl_host, sizeof(double) * M->nmax, hipHostMallocDefault) != hipSuccess) return fail(PAHQ_EHIP);
+  if (hipHostMalloc((void**)&M->send_host, sizeof(int) * M->nmax, hipHostMallocDefault) != hipSuccess) return fail(PAHQ_EHIP);
+  for (int i = 0; i < Arena::SLOTS; i++) {
+    if (hipHostMalloc((void**)&M->arena.host[i], M->arena.slot_bytes, hipHostMallocDefault) != hipSuccess) return fail(PAHQ_EHIP);
+    if (hipEventCreateWithFlags(&M->arena.ev[i], hipEventDisableTiming) != hipSuccess) return fail(PAHQ_EHIP);
+  }
+  // zero everything (code buffers rely on zero padding), then bring the weights in
+  if (launch_fill_zero(M->ws, need, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
+  const size_t L = M->L, H = M->H, dh = M->dh, d = M->d, m = M->m, V = M->V;
+  const int od = w->on_device;
+#define CP(dst, src, n) if ((rc = copy_in(M, dst, src, n, od)) != PAHQ_OK) return fail(rc)
+  CP(M->W_E, w->W_E, V * d);
+  if (learned) CP(M->W_pos, w->W_pos, (size_t)c->n_ctx * d);
+  CP(M->W_Q, w->W_Q, L * H * d * dh); CP(M->W_K, w->W_K, L * H * d * dh); CP(M->W_V, w->W_V, L * H * d * dh);
+  CP(M->W_O, w->W_O, L * H * dh * d);
+  CP(M->b_Q, w->b_Q, L * H * dh); CP(M->b_K, w->b_K, L * H * dh); CP(M->b_V, w->b_V, L * H * dh); CP(M->b_O, w->b_O, L * d);
+  CP(M->ln1_g, w->ln1_g, L * d);
+  if (c->norm == PAHQ_NORM_LAYER) { CP(M->ln1_b, w->ln1_b, L * d); CP(M->lnf_b, w->lnf_b, d); }
+  CP(M->lnf_g, w->lnf_g, d);
+  if (mlp) {
+    CP(M->ln2_g, w->ln2_g, L * d);
+    if (c->norm == PAHQ_NORM_LAYER) CP(M->ln2_b, w->ln2_b, L * d);
+    CP(M->W_in, w->W_in, L * d * m); CP(M->b_in, w->b_in, L * m);
+    if (swi) CP(M->W_gate, w->W_gate, L * d * m);
+    CP(M->W_out, w->W_out, L * m * d); CP(M->b_out, w->b_out, L * d);
+  }
+  CP(M->W_U, w->W_U, d * V); CP(M->b_U, w->b_U, V);
+#undef CP
+  // fused projection bias [L][3][H][dh]
+  const float* bsrc[3] = {M->b_Q, M->b_K, M->b_V};
+  for (size_t l = 0; l < L; l++)
+    for (int cc = 0; cc < 3; cc++)
+      if (hipMemcpyAsync(M->bqkv + (l * 3 + cc) * H * dh, bsrc[cc] + l * H * dh, H * dh * sizeof(float),
+                         hipMemcpyDeviceToDevice, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
+  // e4m3 codes + scales of every weight slice
+  const float* wc[3] = {M->W_Q, M->W_K, M->W_V};
+  for (size_t l = 0; l < L && rc == PAHQ_OK; l++)
+    for (int cc = 0; cc < 3 && rc == PAHQ_OK; cc++)
+      rc = quantise_class(M, wc[cc] + l * H * d * dh, (int)H, (int)d, (int)dh,
+                          M->qkv_codes + (l * 3 * H * dh + (size_t)cc * H * dh) * M->Kd, (long long)dh * M->Kd, M->Kd,
+                          M->qkv_scale + l * 3 * H + (size_t)cc * H, 1);
+  if (rc == PAHQ_OK) rc = quantise_class(M, M->W_O, (int)(L * H), (int)dh, (int)d, M->o_codes, (long long)d * M->Kh, M->Kh, M->o_scale, 1);
+  if (mlp && rc == PAHQ_OK) rc = quantise_class(M, M->W_in, (int)L, (int)d, (int)m, M->in_codes, (long long)m * M->Kd, M->Kd, M->in_scale, 1);
+  if (mlp && swi && rc == PAHQ_OK) rc = quantise_class(M, M->W_gate, (int)L, (int)d, (int)m, M->gate_codes, (long long)m * M->Kd, M->Kd, M->gate_scale, 1);
+  if (mlp && rc == PAHQ_OK) rc = quantise_class(M, M->W_out, (int)L, (int)m, (int)d, M->out_codes, (long long)d * M->Km, M->Km, M->out_scale, 1);
+  if (rc == PAHQ_OK) rc = quantise_class(M, M->W_U, 1, (int)d, (int)V, M->u_codes, 0, M->Kd, M->u_scale, 1);
+  if (rc != PAHQ_OK) return fail(rc);
+  // embeddings, biases and norm parameters are used unquantised: check them too
+  {
+    struct { const float* p; size_t n; } extra[] = {{M->W_E, V * d}, {M->W_pos, learned ? (size_t)c->n_ctx * d : 0},
+      {M->bqkv, L * 3 * H * dh}, {M->b_O, L * d}, {M->ln1_g, L * d}, {M->ln1_b, L * d}, {M->ln2_g, mlp ? L * d : 0},
+      {M->ln2_b, mlp ? L * d : 0}, {M->b_in, mlp ? L * m : 0}, {M->b_out, mlp ? L * d : 0}, {M->lnf_g, d}, {M->lnf_b, d}, {M->b_U, V}};
+    for (auto& e : extra)
+      if (e.p && e.n)
+        if (launch_slice_absmax(e.p, (long long)e.n, 1, M->amax_tmp, M->flag_tmp, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
+  }
+  int flag = 0;
+  if (hipMemcpyAsync(&flag, M->flag_tmp, sizeof(int), hipMemcpyDeviceToHost, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
+  if (hipStreamSynchronize(M->stream) != hipSuccess) return fail(PAHQ_EHIP);
+  if (flag) return fail(PAHQ_ENAN);
+
+  M->edge_off.assign(M->g.Nr + 1, 0);
+  for (int r = 0; r < M->g.Nr; r++) M->edge_off[r + 1] = M->edge_off[r] + M->g.n_upstream(r);
+  M->removed.assign((size_t)M->edge_off[M->g.Nr], 0);
+  M->has_cache = false; M->pi_l = M->pi_h = -2; M->pi_p0 = -1;
+  M->counters[0] = M->counters[1] = M->counters[2] = 0;
+  *out = M;
+  return PAHQ_OK;
+}
+
+void pahq_free(pahq_model* M) {
+  if (!M) return;
+  if (M->kl_host) (void)hipHostFree(M->kl_host);
+  if (M->send_host) (void)hipHostFree(M->send_host);
+  for (int i = 0; i < Arena::SLOTS; i++) {
+    if (M->arena.host[i]) (void)hipHostFree(M->arena.host[i]);
+    if (M->arena.ev[i]) (void)hipEventDestroy(M->arena.ev[i]);
+  }
+  delete M;
+}
+
+int pahq_clean_cache(pahq_model* M, const int32_t* clean_tok, const int32_t* corrupt_tok) {
+  if (!M || !clean_tok || !corrupt_tok) return PAHQ_EINVAL;
+  for (int i = 0; i < M->T; i++)
+    if (clean_tok[i] < 0 || clean_tok[i] >= M->V || corrupt_tok[i] < 0 || corrupt_tok[i] >= M->V) return PAHQ_EINVAL;
+  HIPCHK(hipMemcpyAsync(M->tok_clean, clean_tok, M->T * sizeof(int), hipMemcpyHostToDevice, M->stream));
+  HIPCHK(hipMemcpyAsync(M->tok_corrupt, corrupt_tok, M->T * sizeof(int), hipMemcpyHostToDevice, M->stream));
+  HIPCHK(launch_embed(M->tok_clean, M->W_E, M->W_pos, M->clean, M->T, M->S, M->d, M->stream));
+  HIPCHK(launch_embed(M->tok_corrupt, M->W_E, M->W_pos, M->corrupt, M->T, M->S, M->d, M->stream));
+  PassArgs a; a.p0 = 0; a.n = 1; a.pl = a.ph = -1; a.v = -1; a.patch_mode = 0;
+  a.kind = BASE_CLEAN; PCHK(run_pass(M, a, nullptr));
+  a.kind = BASE_CORRUPT; PCHK(run_pass(M, a, nullptr));
+  HIPCHK(launch_tile_sub(M->delta, M->clean, M->corrupt, (long long)M->g.Ns * M->tile, M->stream));
+  HIPCHK(hipStreamSynchronize(M->stream));
+  std::fill(M->removed.begin(), M->removed.end(), 0);
+  M->has_cache = true; M->pi_l = M->pi_h = -2;
+  return PAHQ_OK;
+}
+
+int pahq_eval_edges(pahq_model* M, int32_t receiver, const int32_t* sender_ids, int32_t n, float* kl_out) {
+  if (!M || n < 0 || (n > 0 && (!sender_ids || !kl_out))) return PAHQ_EINVAL;
+  if (receiver < 0 || receiver >= M->g.Nr) return PAHQ_EINVAL;
+  if (!M->has_cache) return PAHQ_ESTATE;
+  const int n_up = M->g.n_upstream(receiver);
+  for (int i = 0; i < n; i++) if (sender_ids[i] < 0 || sender_ids[i] >= n_up) return PAHQ_EINVAL;
+  if (n == 0) return PAHQ_OK;
+  RecvCtx ctx;
+  PCHK(setup_receiver(M, receiver, ctx));
+  for (int pos = 0; pos < n;) {
+    int nb = std::min(ctx.n_eff, n - pos);
+    // an edge that is already removed adds nothing: such a candidate patches with the all-zero tile
+    for (int i = 0; i < nb; i++) {
+      int u = sender_ids[pos + i];
+      M->send_host[i] = M->removed[edge_index(M, u, receiver)] ? M->g.Ns : u;
+    }
+    PCHK(eval_batch(M, ctx, nb, 1));
+    for (int i = 0; i < nb; i++) kl_out[pos + i] = (float)M->kl_host[i];
+    pos += nb;
+  }
+  return PAHQ_OK;
+}
+
+int pahq_eval_current(pahq_model* M, int32_t receiver, float* kl_out) {
+  if (!M || !kl_out || receiver < 0 || receiver >= M->g.Nr) return PAHQ_EINVAL;
+  if (!M->has_cache) return PAHQ_ESTATE;
+  RecvCtx ctx;
+  PCHK(setup_receiver(M, receiver, ctx));
+  double kl;
+  PCHK(eval_state(M, ctx, &kl));
+  *kl_out = (float)kl;
+  return PAHQ_OK;
+}
+
+int pahq_acdc_sweep(pahq_model* M, float tau, const int32_t* receivers, int32_t n_receivers, uint8_t* kept,
+                    int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap) {
+  if (!M || n_receivers < 0 || (n_receivers > 0 && !receivers) || trace_cap < 0 || (trace_cap > 0 && !trace)) return PAHQ_EINVAL;
+  if (tau != tau) return PAHQ_EINVAL;
+  if (!M->has_cache) return PAHQ_ESTATE;
+  const GraphDims& g = M->g;
+  std::vector<int> order;
+  if (n_receivers == 0) { for (int r = g.Nr - 1; r >= 0; r--) order.push_back(r); }
+  else {
+    for (int i = 0; i < n_receivers; i++) { if (receivers[i] < 0 || receivers[i] >= g.Nr) return PAHQ_EINVAL; order.push_back(receivers[i]); }
+    std::sort(order.begin(), order.end(), [](int x, int y) { return x > y; });
+    order.erase(std::unique(order.begin(), order.end()), order.end());
+  }
+  std::fill(M->removed.begin(), M->removed.end(), 0);
+  int64_t evals = 0;
+  const double tau_d = (double)tau;
+  for (int v : order) {
+    const int n_up = g.n_upstream(v);
+    uint8_t* row = M->removed.data() + M->edge_off[v];
+    if (!node_is_live(M, v)) { memset(row, 1, n_up); continue; }
+    RecvCtx ctx;
+    PCHK(setup_receiver(M, v, ctx));
+    double kl_cur;
+    PCHK(eval_state(M, ctx, &kl_cur));
+    int pos = 0;                      // candidates are senders n_up-1-pos, descending
+    int bs = ctx.n_eff;
+    int recent_rm = 1, recent_n = 1;  // decision history of this receiver (start optimistic: most edges go)
+    while (pos < n_up) {
+      int nb = std::min(std::min(bs, ctx.n_eff), n_up - pos);
+      // cumulative candidates pay off when removals dominate, independent ones when keeps do
+      int mode = (2 * recent_rm >= recent_n) ? 2 : 1;
+      for (int i = 0; i < nb; i++) M->send_host[i] = n_up - 1 - (pos + i);
+      PCHK(eval_batch(M, ctx, nb, mode));
+      int used = 0, n_rm = 0;
+      for (int i = 0; i < nb; i++) {
+        double kn = M->kl_host[i];
+        bool rm = (kn - kl_cur) < tau_d;
+        int u = M->send_host[i];
+        if (evals < trace_cap) {
+          pahq_trace_rec& t = trace[evals];
+          t.receiver = v; t.sender = u; t.kl_new = (float)kn; t.kl_cur = (float)kl_cur; t.removed = rm ? 1 : 0;
+        }
+        evals++; used++; recent_n++;
+        if (rm) { row[u] = 1; kl_cur = kn; n_rm++; recent_rm++; }
+        // cumulative: later candidates assumed this edge gone -> stop at the first kept edge;
+        // independent: later candidates assumed this edge present -> stop at the first removed edge
+        if ((mode == 2 && !rm) || (mode == 1 && rm)) break;
+      }
+      if (n_rm > 0) {
+        // removed edges of this batch: in cumulative mode the first n_rm candidates, in independent mode the last used
+        if (mode == 2) {
+          HIPCHK(launch_xv_advance(M->xv, M->delta, M->tile, M->send_dev, n_rm, M->tile, M->stream));
+        } else {
+          HIPCHK(launch_xv_advance(M->xv, M->delta, M->tile, M->send_dev + (used - 1), 1, M->tile, M->stream));
+        }
+      }
+      pos += used;
+      bs = (used == nb) ? std::min(ctx.n_eff, std::max(2 * bs, 2)) : std::max(1, std::min(ctx.n_eff, 2 * used));
+    }
+  }
+  if (kept) for (size_t i = 0; i < M->removed.size(); i++) kept[i] = M->removed[i] ? 0 : 1;
+  if (n_evals) *n_evals = evals;
+  HIPCHK(hipStreamSynchronize(M->stream));
+  return PAHQ_OK;
+}
+
+int pahq_set_removed(pahq_model* M, const uint8_t* removed) {
+  if (!M || !removed) return PAHQ_EINVAL;
+  for (size_t i = 0; i < M->removed.size(); i++) if (removed[i] > 1) return PAHQ_EINVAL;
+  memcpy(M->removed.data(), removed, M->removed.size());
+  return PAHQ_OK;
+}
+int pahq_get_removed(pahq_model* M, uint8_t* removed) {
+  if (!M || !removed) return PAHQ_EINVAL;
+  memcpy(removed, M->removed.data(), M->removed.size());
+  return PAHQ_OK;
+}
+
+int pahq_get_weight_q(pahq_model* M, int32_t which, int32_t layer, int32_t head, uint8_t* codes, float* scale) {
+  if (!M || !codes || !scale) return PAHQ_EINVAL;
+  const uint8_t* src; const float* ssrc; int K, N, ldq;
+  const int L = M->L, H = M->H, dh = M->dh, d = M->d, m = M->m, V = M->V;
+  if (which >= PAHQ_W_Q && which <= PAHQ_W_O) { if (layer < 0 || layer >= L || head < 0 || head >= H) return PAHQ_EINVAL; }
+  else if (which >= PAHQ_W_IN && which <= PAHQ_W_OUT) { if (layer < 0 || layer >= L || m == 0) return PAHQ_EINVAL; }
+  switch (which) {
+    case PAHQ_W_Q: case PAHQ_W_K: case PAHQ_W_V: {
+      int cc = which - PAHQ_W_Q;
+      K = d; N = dh; ldq = M->Kd;
+      src = M->qkv_codes + ((long long)layer * 3 * H * dh + ((long long)cc * H + head) * dh) * M->Kd;
+      ssrc = M->qkv_scale + (long long)layer * 3 * H + cc * H + head; break; }
+    case PAHQ_W_O: K = dh; N = d; ldq = M->Kh; src = M->o_codes + ((long long)layer * H + head) * d * M->Kh; ssrc = M->o_scale + layer * H + head; break;
+    case PAHQ_W_IN: K = d; N = m; ldq = M->Kd; src = M->in_codes + (long long)layer * m * M->Kd; ssrc = M->in_scale + layer; break;
+    case PAHQ_W_GATE: if (!M->gate_codes) return PAHQ_EINVAL;
+      K = d; N = m; ldq = M->Kd; src = M->gate_codes + (long long)layer * m * M->Kd; ssrc = M->gate_scale + layer; break;
+    case PAHQ_W_OUT: K = m; N = d; ldq = M->Km; src = M->out_codes + (long long)layer * d * M->Km; ssrc = M->out_scale + layer; break;
+    case PAHQ_W_U: K = d; N = V; ldq = M->Kd; src = M->u_codes; ssrc = M->u_scale; break;
+    default: return PAHQ_EINVAL;
+  }
+  std::vector<uint8_t> tmp((size_t)N * ldq);
+  HIPCHK(hipMemcpyAsync(tmp.data(), src, tmp.size(), hipMemcpyDeviceToHost, M->stream));
+  HIPCHK(hipMemcpyAsync(scale, ssrc, sizeof(float), hipMemcpyDeviceToHost, M->stream));
+  HIPCHK(hipStreamSynchronize(M->stream));
+  for (int k = 0; k < K; k++)
+    for (int n = 0; n < N; n++) codes[(size_t)k * N + n] = tmp[(size_t)n * ldq + k];
+  return PAHQ_OK;
+}
+
+int pahq_quantize_rows(pahq_model* M, const float* x, int32_t rows, int32_t cols, uint8_t* codes, float* scales) {
+  if (!M || !x || !codes || !scales || rows < 0 || cols < 1 || cols > 16384) return PAHQ_EINVAL;
+  if (rows == 0) return PAHQ_OK;
+  // staged through the candidate buffers: fp32 rows in `logits`, codes in `xcodes`, scales in `xscale`
+  size_t cap_f = (size_t)M->nmax * M->B * M->V, cap_c = (size_t)M->nmax * M->G * M->T * M->Kd, cap_s = (size_t)M->nmax * M->G * M->T;
+  size_t chunk = std::min(std::min(cap_f / cols, cap_c / cols), cap_s);
+  if (chunk < 1) return PAHQ_ENOMEM;
+  for (size_t r0 = 0; r0 < (size_t)rows; r0 += chunk) {
+    size_t nr = std::min(chunk, (size_t)rows - r0);
+    HIPCHK(hipMemcpyAsync(M->logits, x + r0 * cols, nr * cols * sizeof(float), hipMemcpyHostToDevice, M->stream));
+    HIPCHK(launch_quant_rows_plain(M->logits, (int)nr, cols, M->xcodes, M->xscale, M->stream));
+    HIPCHK(hipMemcpyAsync(codes + r0 * cols, M->xcodes, nr * cols, hipMemcpyDeviceToHost, M->stream));
+    HIPCHK(hipMemcpyAsync(scales + r0, M->xscale, nr * sizeof(float), hipMemcpyDeviceToHost, M->stream));
+    HIPCHK(hipStreamSynchronize(M->stream));
+  }
+  // the staging area doubles as zero-padded code storage: restore the zeros
+  size_t used = std::min((size_t)rows, chunk) * cols;
+  HIPCHK(launch_fill_zero(M->xcodes, std::min(cap_c, (used + 15) / 16 * 16), M->stream));
+  HIPCHK(hipStreamSynchronize(M->stream));
+  return PAHQ_OK;
+}
+
+int pahq_get_logits(pahq_model* M, int32_t which, float* out) {
+  if (!M || !out || (which != PAHQ_LOGITS_CLEAN && which != PAHQ_LOGITS_CORRUPT)) return PAHQ_EINVAL;
+  if (!M->has_cache) return PAHQ_ESTATE;
+  const float* src = which == PAHQ_LOGITS_CLEAN ? M->logits_clean : M->logits_corrupt;
+  HIPCHK(hipMemcpyAsync(out, src, (size_t)M->B * M->V * sizeof(float), hipMemcpyDeviceToHost, M->stream));
+  HIPCHK(hipStreamSynchronize(M->stream));
+  return PAHQ_OK;
+}
+
+int pahq_get_sender_output(pahq_model* M, int32_t which, int32_t sender, float* out) {
+  if (!M || !out || (which != 0 && which != 1) || sender < 0 || sender >= M->g.Ns) return PAHQ_EINVAL;
+  if (!M->has_cache) return PAHQ_ESTATE;
+  const float* src = (which == 0 ? M->clean : M->corrupt) + (long long)sender * M->tile;
+  HIPCHK(hipMemcpyAsync(out, src, (size_t)M->tile * sizeof(float), hipMemcpyDeviceToHost, M->stream));
+  HIPCHK(hipStreamSynchronize(M->stream));
+  return PAHQ_OK;
+}
+
+int pahq_get_counters(pahq_model* M, int64_t out[3]) {
+  if (!M || !out) return PAHQ_EINVAL;
+  out[0] = M->counters[0]; out[1] = M->counters[1]; out[2] = M->counters[2];
+  return PAHQ_OK;
+}
+
+const char* pahq_strerror(int code) {
+  switch (code) {
+    case PAHQ_OK: return "ok";
+    case PAHQ_EINVAL: return "invalid argument";
+    case PAHQ_ESTATE: return "call out of order (run pahq_clean_cache first)";
+    case PAHQ_ENOMEM: return "workspace too small";
+    case PAHQ_EHIP: return "HIP runtime error or no device";
+    case PAHQ_ENAN: return "non-finite weight";
+    case PAHQ_EUNSUPPORTED: return "not supported by this build";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

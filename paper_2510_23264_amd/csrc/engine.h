@@ -1,0 +1,107 @@
+// Host-side state of one model and the pass executor.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <vector>
+#include "../../include/pahq.h"
+#include "graph.h"
+#include "kernels.h"
+
+namespace pahq {
+
+enum PassKind { BASE_CLEAN = 0, BASE_CORRUPT, PI_CORRUPT, PI_REF, STATE, CAND };
+
+// How one recomputed receiver forms its input from the residual streams.
+struct RecvSpec {
+  int form;                    // 0 dense (running stream only), 1 removed form, 2 kept form
+  std::vector<int> senders;    // removed senders (form 1) or kept senders (form 2), ascending
+};
+
+struct RecvPlan {
+  int p0 = -1;
+  std::vector<RecvSpec> spec;  // indexed by receiver id (only receivers at positions >= p0 are filled)
+  std::vector<int> slot_of;    // per sender: slot index or -1
+  int n_slots = 0;
+};
+
+struct PassArgs {
+  PassKind kind;
+  int p0;              // first position recomputed
+  int n;               // instances
+  int pl, ph;          // fp32 head (layer, head) or -1
+  int v;               // patched receiver (CAND) or -1
+  int patch_mode;      // 1 independent, 2 cumulative
+};
+
+struct Arena {          // descriptor staging: pinned host mirror + device copy, a small ring
+  static const int SLOTS = 4;
+  char* host[SLOTS];
+  char* dev[SLOTS];
+  hipEvent_t ev[SLOTS];
+  size_t slot_bytes;
+  int next;
+};
+
+}  // namespace pahq
+
+struct pahq_model {
+  pahq_config cfg;
+  pahq::GraphDims g;
+  int B, S, T, L, H, dh, d, m, V;
+  int Kd, Kh, Km;        // K extents padded to multiples of 128
+  int nmax, G;           // max instances; max groups per layer (3H + 1)
+  long long tile;        // T * d
+  hipStream_t stream;
+
+  // device memory (all inside the caller's workspace)
+  char* ws; size_t ws_bytes, ws_used;
+  float *W_E, *W_pos, *W_Q, *W_K, *W_V, *W_O, *b_Q, *b_K, *b_V, *b_O;
+  float *ln1_g, *ln1_b, *ln2_g, *ln2_b, *W_in, *b_in, *W_gate, *W_out, *b_out, *lnf_g, *lnf_b, *W_U, *b_U;
+  float* zeros_d;                         // [max(d, 64)] zeros (norm offset for RMSNorm)
+  float* bqkv;                            // [L][3][H][dh] fused projection bias
+  uint8_t *qkv_codes, *o_codes, *in_codes, *gate_codes, *out_codes, *u_codes;
+  float *qkv_scale, *o_scale, *in_scale, *gate_scale, *out_scale, *u_scale;
+  unsigned* amax_tmp; int* flag_tmp;
+  int *tok_clean, *tok_corrupt, *send_dev;
+  float *clean, *corrupt, *delta;         // [Ns] tiles each (delta has one more, all zero)
+  float *rc, *rx;                         // [2L+1] residual prefixes (entry 0 unused: it is sender 0's tile)
+  float *logits_clean, *logits_corrupt;   // [B][V]
+  double* logz_clean;                     // [B]
+  float *cpi, *rxpi, *ref_logits; double* ref_logz;   // state of the current fp32 head
+  float* xv;                              // current input of the receiver under evaluation
+  float *run_a, *run_b;                   // [nmax] tiles each
+  uint8_t* xcodes; float* xscale; float* xf32;
+  float* qkv; uint8_t* zcodes; float* zscale; float* zf32;
+  float *headout, *mlpout, *hid, *hid2; uint8_t* hcodes; float* hscale;
+  uint8_t* lastcodes; float* lastscale; float* logits;
+  float* slots; long long pool_tiles;
+  double *row_kl, *kl_dev;
+  double* kl_host;                        // pinned
+  int* send_host;                         // pinned
+  pahq::Arena arena;
+
+  // host state
+  std::vector<uint8_t> removed;           // canonical edge order
+  std::vector<int64_t> edge_off;          // [Nr + 1]
+  bool has_cache;
+  int pi_l, pi_h, pi_p0;                  // fp32 head whose state (cpi, rxpi, ref_*) is current; -2 = none
+  pahq::RecvPlan plan;
+  int64_t counters[3];
+};
+
+namespace pahq {
+// Residual-stream prefix tiles of the cached clean / corrupted run.  Position 0
+// is the embedding's own tile; in attention-only models the position before
+// layer l+1 is the position after the heads of layer l.
+static inline int canon_pos(const pahq_model* M, int p) {
+  return (M->g.mu == 0 && p > 0 && (p & 1) == 0) ? p - 1 : p;
+}
+static inline float* clean_prefix(pahq_model* M, int p) {
+  return p == 0 ? M->clean : M->rc + (long long)canon_pos(M, p) * M->tile;
+}
+static inline float* corrupt_prefix(pahq_model* M, int p) {
+  return p == 0 ? M->corrupt : M->rx + (long long)canon_pos(M, p) * M->tile;
+}
+int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan);
+void make_plan(pahq_model* M, int p0, RecvPlan& out);
+}  // namespace pahq

@@ -1,0 +1,424 @@
+// The pass executor: one function runs every kind of forward pass the method
+// needs (cache passes, passes under a precision set, the state pass and the
+// edge-batched candidate pass) from a residual-stream position onwards, for n
+// instances at once.  The host only builds descriptor tables; every step of the
+// computation runs in the kernels.
+//
+// Receiver inputs.  Paper, Appendix "Preliminaries": a receiver reads the sum
+// of its upstream senders' outputs, a removed edge carrying the corrupted
+// run's output instead.  With r the running clean stream, c the corrupted
+// run's stream at the same position and D_s = out_s - corrupt_s this sum is
+//     removed form  x = r - sum_{s removed} D_s      (few removed edges)
+//     kept form     x = c + sum_{s kept}    D_s      (few kept edges)
+// and the cheaper form is chosen per receiver.  D_s of senders below the start
+// position comes from the cache (clean - corrupt); for recomputed senders it is
+// written by the kernel that adds the sender's output to the stream.
+#include "engine.h"
+#include <map>
+#include <string.h>
+
+namespace pahq {
+
+#define HIPCHK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return PAHQ_EHIP; } while (0)
+
+static inline int canon(const pahq_model* M, int p) { return canon_pos(M, p); }
+
+void make_plan(pahq_model* M, int p0, RecvPlan& out) {
+  const GraphDims& g = M->g;
+  out.p0 = p0;
+  out.spec.assign(g.Nr, RecvSpec());
+  out.slot_of.assign(g.Ns, -1);
+  out.n_slots = 0;
+  const int nstat = g.n_static(p0);
+  for (int w = 0; w < g.Nr; w++) {
+    if (g.pos_of_receiver(w) < p0) continue;
+    const int n_up = g.n_upstream(w);
+    const uint8_t* row = M->removed.data() + M->edge_off[w];
+    int n_rem = 0;
+    for (int s = 0; s < n_up; s++) n_rem += row[s];
+    RecvSpec& sp = out.spec[w];
+    if (n_rem == 0) { sp.form = 0; continue; }
+    if (n_rem <= n_up - n_rem) {
+      sp.form = 1;
+      for (int s = 0; s < n_up; s++) if (row[s]) sp.senders.push_back(s);
+    } else {
+      sp.form = 2;
+      for (int s = 0; s < n_up; s++) if (!row[s]) sp.senders.push_back(s);
+    }
+    for (int s : sp.senders)
+      if (s >= nstat && out.slot_of[s] < 0) out.slot_of[s] = out.n_slots++;
+  }
+}
+
+namespace {
+
+enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL };
+struct Op { OpType t; int i0, i1, i2, i3; void* p0; void* p1; };
+
+struct Stream { float* p; long long is; };
+
+struct Builder {
+  pahq_model* M;
+  const PassArgs& a;
+  const RecvPlan* plan;
+  std::vector<GroupDesc> groups;
+  std::vector<Term> terms;
+  std::vector<GemmProb> probs;
+  std::vector<CombineDesc> cdescs;
+  std::vector<CombineSrc> csrcs;
+  std::vector<Op> ops;
+  bool general, has_pi;
+  int nstat;
+
+  Builder(pahq_model* M_, const PassArgs& a_, const RecvPlan* p_) : M(M_), a(a_), plan(p_) {
+    general = (a.kind == STATE || a.kind == CAND);
+    has_pi = a.pl >= 0;
+    nstat = M->g.n_static(a.p0);
+  }
+
+  float* corrupt_prefix_pi(int p) {
+    if (has_pi && p > a.p0) return M->rxpi + (long long)canon(M, p) * M->tile;
+    return corrupt_prefix(M, p);
+  }
+  float* corrupt_ref_tile(int s) {      // corrupted-run output of a recomputed sender under the current precision set
+    return (has_pi ? M->cpi : M->corrupt) + (long long)s * M->tile;
+  }
+
+  // fills base / run / terms of a group from a receiver spec
+  void fill_input(GroupDesc& gd, const RecvSpec* sp, int pw, Stream run) {
+    gd.base = nullptr; gd.base_is = 0; gd.run = nullptr; gd.run_is = 0;
+    gd.term_begin = (int)terms.size(); gd.term_count = 0;
+    int form = sp ? sp->form : 0;
+    if (form == 2) { gd.base = corrupt_prefix_pi(pw); }
+    else { gd.run = run.p; gd.run_is = run.is; }
+    if (form != 0) {
+      float sign = form == 1 ? -1.f : 1.f;
+      for (int s : sp->senders) {
+        Term t;
+        if (s < nstat) { t.p = M->delta + (long long)s * M->tile; t.inst_stride = 0; }
+        else { t.p = M->slots + (long long)plan->slot_of[s] * M->tile; t.inst_stride = (long long)plan->n_slots * M->tile; }
+        t.sign = sign; t.pad_ = 0;
+        terms.push_back(t);
+      }
+      gd.term_count = (int)sp->senders.size();
+    }
+  }
+
+  GemmProb prob8(const void* A, long long a_is, int lda, const float* as, long long as_is, int as_stride,
+                 const void* W, int ldw, const float* ws, int ws_block, const float* bias, float* C, long long c_is,
+                 int ldc, int act, int Mr, int N, int K) {
+    GemmProb p; memset(&p, 0, sizeof(p));
+    p.A = A; p.a_is = a_is; p.lda = lda; p.ascale = as; p.as_is = as_is; p.as_stride = as_stride;
+    p.W = W; p.ldw = ldw; p.wscale = ws; p.wscale_block = ws_block; p.bias = bias;
+    p.C = C; p.c_is = c_is; p.ldc = ldc; p.act = act; p.M = Mr; p.N = N; p.K = K;
+    return p;
+  }
+
+  void add_op(OpType t, int i0 = 0, int i1 = 0, int i2 = 0, int i3 = 0, void* p0 = nullptr, void* p1 = nullptr) {
+    Op o; o.t = t; o.i0 = i0; o.i1 = i1; o.i2 = i2; o.i3 = i3; o.p0 = p0; o.p1 = p1;
+    ops.push_back(o);
+  }
+
+  // where a recomputed sender's raw output goes
+  Stream sender_dest(int s, float* scratch, long long scratch_is) {
+    Stream d;
+    switch (a.kind) {
+      case BASE_CLEAN: d.p = M->clean + (long long)s * M->tile; d.is = 0; break;
+      case BASE_CORRUPT: d.p = M->corrupt + (long long)s * M->tile; d.is = 0; break;
+      case PI_CORRUPT: d.p = M->cpi + (long long)s * M->tile; d.is = 0; break;
+      default: d.p = scratch; d.is = scratch_is; break;
+    }
+    return d;
+  }
+  // where the stream after a block is written
+  Stream next_run(int p_after, float* scratch) {
+    Stream r;
+    switch (a.kind) {
+      case BASE_CLEAN: r.p = M->rc + (long long)canon(M, p_after) * M->tile; r.is = 0; break;
+      case BASE_CORRUPT: r.p = M->rx + (long long)canon(M, p_after) * M->tile; r.is = 0; break;
+      case PI_CORRUPT: r.p = M->rxpi + (long long)canon(M, p_after) * M->tile; r.is = 0; break;
+      default: r.p = scratch; r.is = M->tile; break;
+    }
+    return r;
+  }
+
+  void norm_params(GroupDesc& gd, const float* gain, const float* offset) {
+    gd.gain = gain;
+    gd.offset = (M->cfg.norm == PAHQ_NORM_RMS || !offset) ? M->zeros_d : offset;
+  }
+
+  void attention_block(int l, Stream& run) {
+    const GraphDims& g = M->g;
+    const int H = M->H, dh = M->dh, d = M->d, T = M->T, Kd = M->Kd, Kh = M->Kh, G = M->G;
+    const bool pi_layer = has_pi && l == a.pl;
+    // ---- groups
+    std::map<std::pair<int, std::vector<int>>, int> seen;
+    std::vector<int> grp_of(3 * H, -1);          // index into `groups` per (h, c) block
+    int g_begin = (int)groups.size(), n_f32 = 0, patch_group = -1;
+    for (int h = 0; h < H; h++)
+      for (int c = 0; c < 3; c++) {
+        int w = g.headin(l, h, c);
+        const bool is_pi = pi_layer && h == a.ph;
+        int gi;
+        if (a.kind == CAND && w == a.v) {
+          GroupDesc gd; memset(&gd, 0, sizeof(gd));
+          norm_params(gd, M->ln1_g + (long long)l * d, M->ln1_b + (long long)l * d);
+          gi = (int)groups.size(); groups.push_back(gd); patch_group = gi;
+        } else {
+          const RecvSpec* sp = general ? &plan->spec[w] : nullptr;
+          std::pair<int, std::vector<int>> key(sp ? sp->form : 0, sp ? sp->senders : std::vector<int>());
+          auto it = seen.find(key);
+          if (it == seen.end()) {
+            GroupDesc gd; memset(&gd, 0, sizeof(gd));
+            fill_input(gd, sp, 2 * l, run);
+            norm_params(gd, M->ln1_g + (long long)l * d, M->ln1_b + (long long)l * d);
+            gi = (int)groups.size(); groups.push_back(gd); seen[key] = gi;
+          } else gi = it->second;
+        }
+        grp_of[c * H + h] = gi;
+        GroupDesc& gd = groups[gi];
+        int local = gi - g_begin;
+        if (is_pi) {
+          if (!gd.out_f32) { gd.out_f32 = M->xf32 + (long long)n_f32 * M->tile; gd.out_f32_is = 3 * M->tile; n_f32++; }
+        } else if (!gd.out_codes) {
+          gd.out_codes = M->xcodes + (long long)local * T * Kd; gd.out_codes_is = (long long)G * T * Kd;
+          gd.out_scale = M->xscale + (long long)local * T; gd.out_scale_is = (long long)G * T;
+        }
+      }
+    int n_groups = (int)groups.size() - g_begin;
+    add_op(OP_BUILD, g_begin, n_groups, patch_group);
+    // ---- fp8 projections: runs of consecutive column blocks that read the same quantised group
+    int pb = (int)probs.size(), maxN = 0;
+    const long long qkv_ld = 3LL * H * dh;
+    for (int nb = 0; nb < 3 * H;) {
+      int gi = grp_of[nb];
+      if (!groups[gi].out_codes) { nb++; continue; }
+      int e = nb + 1;
+      while (e < 3 * H && grp_of[e] == gi) e++;
+      const GroupDesc& gd = groups[gi];
+      probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
+                            M->qkv_codes + ((long long)l * 3 * H * dh + (long long)nb * dh) * Kd, Kd,
+                            M->qkv_scale + (long long)l * 3 * H + nb, dh, M->bqkv + (long long)l * 3 * H * dh + (long long)nb * dh,
+                            M->qkv + (long long)nb * dh, (long long)T * qkv_ld, (int)qkv_ld, 0, T, (e - nb) * dh, Kd));
+      if ((e - nb) * dh > maxN) maxN = (e - nb) * dh;
+      nb = e;
+    }
+    if ((int)probs.size() > pb) add_op(OP_GEMM8, pb, (int)probs.size() - pb, T, maxN);
+    // ---- fp32 projections of the investigated head
+    if (pi_layer) {
+      int pf = (int)probs.size();
+      const float* Wc[3] = {M->W_Q, M->W_K, M->W_V};
+      const float* bc[3] = {M->b_Q, M->b_K, M->b_V};
+      for (int c = 0; c < 3; c++) {
+        const GroupDesc& gd = groups[grp_of[c * H + a.ph]];
+        long long hoff = (long long)l * H + a.ph;
+        probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1,
+                              bc[c] + hoff * dh, M->qkv + ((long long)c * H + a.ph) * dh, (long long)T * qkv_ld,
+                              (int)qkv_ld, 0, T, dh, d));
+      }
+      add_op(OP_GEMM32, pf, 3, T, dh);
+    }
+    add_op(OP_ATTN, pi_layer ? a.ph : -1);
+    // ---- output projections, one sender output per head
+    int po = (int)probs.size();
+    std::vector<Stream> dest(H);
+    for (int h = 0; h < H; h++) {
+      dest[h] = sender_dest(g.head(l, h), M->headout + (long long)h * M->tile, (long long)H * M->tile);
+      if (pi_layer && h == a.ph) continue;
+      probs.push_back(prob8(M->zcodes + (long long)h * Kh, (long long)T * H * Kh, H * Kh, M->zscale + h, (long long)T * H, H,
+                            M->o_codes + ((long long)l * H + h) * d * Kh, Kh, M->o_scale + (long long)l * H + h, d, nullptr,
+                            dest[h].p, dest[h].is, d, 0, T, d, Kh));
+    }
+    if ((int)probs.size() > po) add_op(OP_GEMM8, po, (int)probs.size() - po, T, d);
+    if (pi_layer) {
+      int pf = (int)probs.size();
+      probs.push_back(prob8(M->zf32, (long long)T * dh, dh, nullptr, 0, 0, M->W_O + ((long long)l * H + a.ph) * dh * d, d,
+                            nullptr, 1, nullptr, dest[a.ph].p, dest[a.ph].is, d, 0, T, d, dh));
+      add_op(OP_GEMM32, pf, 1, T, d);
+    }
+    // ---- add the heads to the stream
+    Stream nxt = next_run(2 * l + 1, run.p == M->run_a ? M->run_b : M->run_a);
+    CombineDesc cd; memset(&cd, 0, sizeof(cd));
+    cd.run_in = run.p; cd.run_in_is = run.is; cd.run_out = nxt.p; cd.run_out_is = nxt.is;
+    cd.bias = M->b_O + (long long)l * d; cd.src_begin = (int)csrcs.size(); cd.n_src = H;
+    for (int h = 0; h < H; h++) {
+      CombineSrc cs; memset(&cs, 0, sizeof(cs));
+      cs.src = dest[h].p; cs.src_is = dest[h].is;
+      int s = g.head(l, h);
+      if (general && plan->slot_of[s] >= 0) {
+        cs.slot = M->slots + (long long)plan->slot_of[s] * M->tile; cs.slot_is = (long long)plan->n_slots * M->tile;
+        cs.sub = corrupt_ref_tile(s);
+      }
+      csrcs.push_back(cs);
+    }
+    cdescs.push_back(cd);
+    add_op(OP_COMBINE, (int)cdescs.size() - 1);
+    run = nxt;
+  }
+
+  void mlp_block(int l, Stream& run) {
+    const GraphDims& g = M->g;
+    const int d = M->d, T = M->T, Kd = M->Kd, Km = M->Km, m = M->m, G = M->G;
+    int w = g.mlpin(l), s = g.mlp(l);
+    GroupDesc gd; memset(&gd, 0, sizeof(gd));
+    int patch_group = -1, gi = (int)groups.size();
+    if (a.kind == CAND && w == a.v) patch_group = gi;
+    else fill_input(gd, general ? &plan->spec[w] : nullptr, 2 * l + 1, run);
+    norm_params(gd, M->ln2_g + (long long)l * d, M->ln2_b + (long long)l * d);
+    gd.out_codes = M->xcodes; gd.out_codes_is = (long long)G * T * Kd;
+    gd.out_scale = M->xscale; gd.out_scale_is = (long long)G * T;
+    groups.push_back(gd);
+    add_op(OP_BUILD, gi, 1, patch_group);
+    const bool swiglu = M->cfg.act == PAHQ_ACT_SWIGLU;
+    int pb = (int)probs.size();
+    probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
+                          M->in_codes + (long long)l * m * Kd, Kd, M->in_scale + l, m, M->b_in + (long long)l * m, M->hid,
+                          (long long)T * m, m, M->cfg.act == PAHQ_ACT_GELU ? 1 : 0, T, m, Kd));
+    if (swiglu)
+      probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
+                            M->gate_codes + (long long)l * m * Kd, Kd, M->gate_scale + l, m, nullptr, M->hid2,
+                            (long long)T * m, m, 0, T, m, Kd));
+    add_op(OP_GEMM8, pb, swiglu ? 2 : 1, T, m);
+    add_op(OP_HIDQ, swiglu ? 1 : 0);
+    Stream dest = sender_dest(s, M->mlpout, M->tile);
+    pb = (int)probs.size();
+    probs.push_back(prob8(M->hcodes, (long long)T * Km, Km, M->hscale, T, 1, M->out_codes + (long long)l * d * Km, Km,
+                          M->out_scale + l, d, nullptr, dest.p, dest.is, d, 0, T, d, Km));
+    add_op(OP_GEMM8, pb, 1, T, d);
+    Stream nxt = next_run(2 * l + 2, run.p == M->run_a ? M->run_b : M->run_a);
+    CombineDesc cd; memset(&cd, 0, sizeof(cd));
+    cd.run_in = run.p; cd.run_in_is = run.is; cd.run_out = nxt.p; cd.run_out_is = nxt.is;
+    cd.bias = M->b_out + (long long)l * d; cd.src_begin = (int)csrcs.size(); cd.n_src = 1;
+    CombineSrc cs; memset(&cs, 0, sizeof(cs));
+    cs.src = dest.p; cs.src_is = dest.is;
+    if (general && plan->slot_of[s] >= 0) {
+      cs.slot = M->slots + (long long)plan->slot_of[s] * M->tile; cs.slot_is = (long long)plan->n_slots * M->tile;
+      cs.sub = corrupt_ref_tile(s);
+    }
+    csrcs.push_back(cs);
+    cdescs.push_back(cd);
+    add_op(OP_COMBINE, (int)cdescs.size() - 1);
+    run = nxt;
+  }
+
+  void final_block(Stream run) {
+    const GraphDims& g = M->g;
+    const int d = M->d, B = M->B, Kd = M->Kd, V = M->V;
+    if (a.kind == PI_CORRUPT) return;           // only the sender outputs are needed
+    int w = g.out();
+    GroupDesc gd; memset(&gd, 0, sizeof(gd));
+    int patch_group = -1, gi = (int)groups.size();
+    if (a.kind == CAND && w == a.v) patch_group = gi;
+    else fill_input(gd, general ? &plan->spec[w] : nullptr, 2 * M->L, run);
+    norm_params(gd, M->lnf_g, M->lnf_b);
+    gd.last_only = 1;
+    gd.out_codes = M->lastcodes; gd.out_codes_is = (long long)B * Kd;
+    gd.out_scale = M->lastscale; gd.out_scale_is = B;
+    groups.push_back(gd);
+    add_op(OP_BUILD, gi, 1, patch_group);
+    float* lg; long long lg_is = 0;
+    switch (a.kind) {
+      case BASE_CLEAN: lg = M->logits_clean; break;
+      case BASE_CORRUPT: lg = M->logits_corrupt; break;
+      case PI_REF: lg = M->ref_logits; break;
+      default: lg = M->logits; lg_is = (long long)B * V; break;
+    }
+    int pb = (int)probs.size();
+    probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1, M->u_codes, Kd,
+                          M->u_scale, V, M->b_U, lg, lg_is, V, 0, B, V, Kd));
+    add_op(OP_GEMM8, pb, 1, B, V);
+    if (a.kind == BASE_CLEAN) add_op(OP_LOGZ, 0, 0, 0, 0, M->logits_clean, M->logz_clean);
+    else if (a.kind == PI_REF) add_op(OP_LOGZ, 0, 0, 0, 0, M->ref_logits, M->ref_logz);
+    else if (general) add_op(OP_KL, 0, 0, 0, 0, has_pi ? (void*)M->ref_logits : (void*)M->logits_clean,
+                             has_pi ? (void*)M->ref_logz : (void*)M->logz_clean);
+  }
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
+  if (a.n < 1 || a.n > M->nmax) return PAHQ_EINVAL;
+  Builder b(M, a, plan);
+  const int L = M->L;
+  Stream run;
+  const bool corrupt_tokens = (a.kind == BASE_CORRUPT || a.kind == PI_CORRUPT);
+  run.p = corrupt_tokens ? corrupt_prefix(M, a.p0) : clean_prefix(M, a.p0);
+  run.is = 0;
+  for (int l = a.p0 / 2; l < L; l++) {
+    if (a.p0 <= 2 * l) b.attention_block(l, run);
+    if (M->g.mu && a.p0 <= 2 * l + 1) b.mlp_block(l, run);
+  }
+  b.final_block(run);
+
+  // ---- upload the descriptor tables
+  Arena& A = M->arena;
+  int slot = A.next;
+  A.next = (A.next + 1) % Arena::SLOTS;
+  HIPCHK(hipEventSynchronize(A.ev[slot]));
+  size_t o_groups = 0;
+  size_t o_terms = align_up(o_groups + b.groups.size() * sizeof(GroupDesc), 256);
+  size_t o_probs = align_up(o_terms + b.terms.size() * sizeof(Term), 256);
+  size_t o_cdesc = align_up(o_probs + b.probs.size() * sizeof(GemmProb), 256);
+  size_t o_csrc = align_up(o_cdesc + b.cdescs.size() * sizeof(CombineDesc), 256);
+  size_t total = align_up(o_csrc + b.csrcs.size() * sizeof(CombineSrc), 256);
+  if (total > A.slot_bytes) return PAHQ_ENOMEM;
+  char* h = A.host[slot];
+  if (!b.groups.empty()) memcpy(h + o_groups, b.groups.data(), b.groups.size() * sizeof(GroupDesc));
+  if (!b.terms.empty()) memcpy(h + o_terms, b.terms.data(), b.terms.size() * sizeof(Term));
+  if (!b.probs.empty()) memcpy(h + o_probs, b.probs.data(), b.probs.size() * sizeof(GemmProb));
+  if (!b.cdescs.empty()) memcpy(h + o_cdesc, b.cdescs.data(), b.cdescs.size() * sizeof(CombineDesc));
+  if (!b.csrcs.empty()) memcpy(h + o_csrc, b.csrcs.data(), b.csrcs.size() * sizeof(CombineSrc));
+  HIPCHK(hipMemcpyAsync(A.dev[slot], h, total, hipMemcpyHostToDevice, M->stream));
+  HIPCHK(hipEventRecord(A.ev[slot], M->stream));
+  const GroupDesc* d_groups = (const GroupDesc*)(A.dev[slot] + o_groups);
+  const Term* d_terms = (const Term*)(A.dev[slot] + o_terms);
+  const GemmProb* d_probs = (const GemmProb*)(A.dev[slot] + o_probs);
+  const CombineDesc* d_cdesc = (const CombineDesc*)(A.dev[slot] + o_cdesc);
+  const CombineSrc* d_csrc = (const CombineSrc*)(A.dev[slot] + o_csrc);
+
+  // ---- launch
+  const int n = a.n, T = M->T, B = M->B, S = M->S, d = M->d;
+  hipStream_t st = M->stream;
+  for (const Op& o : b.ops) {
+    switch (o.t) {
+      case OP_BUILD: {
+        // the patched receiver's group (if any) is built by the edge-batched patch kernel
+        int pg = o.i2;
+        if (pg < 0) {
+          HIPCHK(launch_build_inputs(d_groups + o.i0, o.i1, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
+        } else {
+          if (pg > o.i0)
+            HIPCHK(launch_build_inputs(d_groups + o.i0, pg - o.i0, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
+          if (o.i0 + o.i1 > pg + 1)
+            HIPCHK(launch_build_inputs(d_groups + pg + 1, o.i0 + o.i1 - pg - 1, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
+          HIPCHK(launch_patch_build(d_groups + pg, M->xv, M->delta, M->tile, M->send_dev, n, a.patch_mode, T, B, S, d,
+                                    M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
+        }
+        break;
+      }
+      case OP_GEMM8: HIPCHK(launch_gemm_fp8(d_probs + o.i0, o.i1, n, o.i2, o.i3, M->cfg.mma == PAHQ_MMA_F16_EXACT, st)); break;
+      case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, n, o.i2, o.i3, st)); break;
+      case OP_ATTN:
+        HIPCHK(launch_attention(M->qkv, (long long)T * 3 * M->H * M->dh, M->zcodes, (long long)T * M->H * M->Kh,
+                                M->zscale, (long long)T * M->H, M->zf32, (long long)T * M->dh, o.i0, n, B, S, M->H,
+                                M->dh, M->Kh, M->cfg.pos == PAHQ_POS_ROPE, M->cfg.rope_theta, st));
+        break;
+      case OP_COMBINE: HIPCHK(launch_combine(d_cdesc, o.i0, d_csrc, n, M->tile, d, st)); break;
+      case OP_HIDQ:
+        HIPCHK(launch_hidden_quant(M->hid, o.i0 ? M->hid2 : nullptr, (long long)T * M->m, M->hcodes, (long long)T * M->Km,
+                                   M->hscale, T, n, T, M->m, M->Km, o.i0, st));
+        break;
+      case OP_LOGZ: HIPCHK(launch_logz((const float*)o.p0, B, M->V, (double*)o.p1, st)); break;
+      case OP_KL:
+        HIPCHK(launch_kl(M->logits, (long long)B * M->V, (const float*)o.p0, (const double*)o.p1, M->row_kl, M->kl_dev,
+                         n, B, M->V, st));
+        break;
+    }
+  }
+  M->counters[2]++;
+  return PAHQ_OK;
+}
+
+}  // namespace pahq

@@ -1,0 +1,118 @@
+// Device-side building blocks of libpahq (gfx950 only).  Every launcher
+// enqueues on the given stream and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pahq {
+
+// One additive term of a receiver input: sign * tile[instance][row][col].
+struct Term {
+  const float* p;
+  long long inst_stride;   // elements between instances (0 = shared by all instances)
+  float sign;
+  int pad_;
+};
+
+// A receiver-input group: every receiver of one layer whose input is the same
+// sum shares one normalised / quantised copy of it.
+//   x = base + run + sum(terms);  y = norm(x) * gain + offset
+struct GroupDesc {
+  const float* base;  long long base_is;
+  const float* run;   long long run_is;
+  int term_begin, term_count;
+  const float* gain;  const float* offset;      // norm parameters [d]
+  float* out_f32;     long long out_f32_is;     // normalised rows, stride d (may be null)
+  uint8_t* out_codes; long long out_codes_is;   // e4m3 codes, row stride ldq (may be null)
+  float* out_scale;   long long out_scale_is;   // one scale per row
+  int last_only;      // 1: only the last position of each sequence (B rows per instance)
+  int pad_;
+};
+
+// C[inst][m][n] = act((sum_k A[inst][m][k] * W[n][k]) * ascale[inst][m] * wscale[n / wscale_block] + bias[n])
+// A, W: e4m3 codes, K contiguous, K a multiple of 128 (zero padded).
+struct GemmProb {
+  const void* A;       long long a_is;  int lda;  int pad0_;
+  const float* ascale; long long as_is; int as_stride; int pad1_;
+  const void* W;       int ldw;  int wscale_block;
+  const float* wscale;
+  const float* bias;
+  float* C;            long long c_is;  int ldc;  int act;   // act: 0 none, 1 tanh-GELU
+  int M, N, K, pad2_;
+};
+// For the fp32 GEMM the same struct is used with A = float [M][lda], W = float
+// [K][ldw] (row-major, K rows), ascale / wscale unused (null).
+
+struct CombineSrc {
+  const float* src;  long long src_is;
+  float* slot;       long long slot_is;   // optional: slot = src - sub
+  const float* sub;                       // instance-independent tile (may be null -> slot = src)
+};
+// run_out = run_in + bias + sum(src), element-wise over T*d
+struct CombineDesc {
+  const float* run_in; long long run_in_is;
+  float* run_out;      long long run_out_is;
+  const float* bias;   // [d] or null
+  int src_begin, n_src;
+};
+
+// ---- launchers ---------------------------------------------------------------
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+
+hipError_t launch_slice_absmax(const float* w, long long slice_elems, int n_slices, unsigned* amax_bits,
+                               int* nonfinite_flag, hipStream_t s);
+// codes_out[(n_off + n) * ldq + k] = e4m3(W[slice][k][n] / scale[slice]),  W slice is [K][N] row-major
+hipError_t launch_quant_transpose(const float* w, int K, int N, const unsigned* amax_bits, float* scale_out,
+                                  uint8_t* codes_out, int ldq, hipStream_t s);
+
+hipError_t launch_embed(const int* tok, const float* W_E, const float* W_pos, float* out, int T, int S, int d,
+                        hipStream_t s);
+
+hipError_t launch_build_inputs(const GroupDesc* groups, int n_groups, const Term* terms, int n_inst, int T, int B,
+                               int S, int d, int ldq, int norm_kind, float eps, hipStream_t s);
+
+// Edge-batched patch: instance i reads x_i = xv - delta[send[i]] (mode 1) or
+// x_i = x_{i-1} - delta[send[i]] with x_{-1} = xv (mode 2), then norm and
+// fp32 / e4m3 output as in GroupDesc (base/run/terms of g are ignored).
+hipError_t launch_patch_build(const GroupDesc* g, const float* xv, const float* delta0, long long delta_stride,
+                              const int* send, int n_inst, int mode, int T, int B, int S, int d, int ldq,
+                              int norm_kind, float eps, hipStream_t s);
+// xv -= delta[send[0]]; xv -= delta[send[1]]; ... (k terms, same order as mode 2 above)
+hipError_t launch_xv_advance(float* xv, const float* delta0, long long delta_stride, const int* send, int k,
+                             long long n_elem, hipStream_t s);
+// out = base + sum(terms) over n_elem elements (instance 0 of every term)
+hipError_t launch_tile_lincomb(float* out, const float* base, const Term* terms, int n_terms, long long n_elem,
+                               hipStream_t s);
+hipError_t launch_tile_sub(float* out, const float* a, const float* b, long long n_elem, hipStream_t s);
+
+// exact = 0: FP8 matrix-core instruction; exact = 1: codes decoded to fp16, fp16 matrix cores (exact
+// products, fp32 sums).
+hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int n_inst, int max_M, int max_N, int exact,
+                           hipStream_t s);
+hipError_t launch_gemm_f32(const GemmProb* probs, int n_probs, int n_inst, int max_M, int max_N, hipStream_t s);
+
+// Causal attention per (instance, sequence, head).  qkv row layout: [3][H][dh].
+// Heads other than f32_head: z rows quantised per head -> zcodes [inst][T][H][ldz], zscale [inst][T][H].
+// f32_head (or -1): z written unquantised to zf32 [inst][T][dh].
+hipError_t launch_attention(const float* qkv, long long qkv_is, uint8_t* zcodes, long long zc_is, float* zscale,
+                            long long zs_is, float* zf32, long long zf_is, int f32_head, int n_inst, int B, int S,
+                            int H, int dh, int ldz, int rope, float rope_theta, hipStream_t s);
+
+hipError_t launch_combine(const CombineDesc* descs, int desc_index, const CombineSrc* srcs, int n_inst,
+                          long long n_elem, int d, hipStream_t s);
+
+// hidden rows [inst][T][m]: h = up (act 0/1: already activated) or silu(gate) * up (act 2); row-quantise.
+hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_is, uint8_t* codes, long long c_is,
+                               float* scale, long long s_is, int n_inst, int T, int m, int ldq, int swiglu,
+                               hipStream_t s);
+
+// logz[b] = log(sum_v exp(logits[b][v]))  (double)
+hipError_t launch_logz(const float* logits, int rows, int V, double* logz, hipStream_t s);
+// kl[inst] = mean_b sum_v p_ref (log p_ref - log p_inst)
+hipError_t launch_kl(const float* logits, long long l_is, const float* ref_logits, const double* ref_logz,
+                     double* row_kl, double* kl, int n_inst, int B, int V, hipStream_t s);
+
+hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales,
+                                   hipStream_t s);
+
+}  // namespace pahq

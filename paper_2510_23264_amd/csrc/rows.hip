@@ -1,0 +1,361 @@
+// Row-wise kernels: receiver-input gather + norm + e4m3 row quantisation, the
+// edge-batched patch, hidden-activation quantisation, tile arithmetic,
+// embedding lookup and weight quantisation.  All are HBM-bound streaming
+// kernels: one 64-lane wavefront owns one row of d_model floats, loads are
+// coalesced along the row, reductions are wave shuffles in a fixed order.
+#include "kernels.h"
+#include "device_util.h"
+
+namespace pahq {
+
+// ------------------------------------------------------------------ fill
+__global__ void fill_zero_k(uint4* p, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  uint4 z = {0, 0, 0, 0};
+  for (; i < n16; i += stride) p[i] = z;
+}
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  size_t n16 = bytes / 16;          // callers pass 16-byte multiples
+  if (n16 == 0) return hipSuccess;
+  int blocks = (int)((n16 + 255) / 256 < 65535 ? (n16 + 255) / 256 : 65535);
+  hipLaunchKernelGGL(fill_zero_k, dim3(blocks), dim3(256), 0, s, (uint4*)p, n16);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ weight quantisation
+// amax over each contiguous slice, as the bit pattern of a non-negative float
+// (unsigned integer order = float order, so atomicMax is exact and order-free).
+__global__ void slice_absmax_k(const float* w, long long slice_elems, unsigned* amax_bits, int* nonfinite) {
+  int sl = blockIdx.y;
+  const float* p = w + (long long)sl * slice_elems;
+  float m = 0.f;
+  int bad = 0;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < slice_elems;
+       i += (long long)gridDim.x * blockDim.x) {
+    float v = p[i];
+    if (!(fabsf(v) <= 3.0e38f)) bad = 1;     // catches NaN and infinities
+    m = fmaxf(m, fabsf(v));
+  }
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) atomicMax(&amax_bits[sl], __float_as_uint(m));
+  if (bad) atomicOr(nonfinite, 1);
+}
+hipError_t launch_slice_absmax(const float* w, long long slice_elems, int n_slices, unsigned* amax_bits,
+                               int* nonfinite_flag, hipStream_t s) {
+  long long per = (slice_elems + 255) / 256;
+  int bx = (int)(per < 1024 ? (per < 1 ? 1 : per) : 1024);
+  hipLaunchKernelGGL(slice_absmax_k, dim3(bx, n_slices), dim3(256), 0, s, w, slice_elems, amax_bits,
+                     nonfinite_flag);
+  return hipGetLastError();
+}
+
+// W slice [K][N] row-major -> codes [N][ldq] (K contiguous), through a 32x32 LDS transpose.
+__global__ void quant_transpose_k(const float* w, int K, int N, const unsigned* amax_bits, float* scale_out,
+                                  uint8_t* codes, int ldq) {
+  __shared__ float tile[32][33];
+  float amax = __uint_as_float(*amax_bits);
+  float scale = (amax == 0.f) ? 1.0f : amax / 448.0f;
+  float inv = 1.0f / scale;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && threadIdx.y == 0) *scale_out = scale;
+  int k0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+  for (int r = threadIdx.y; r < 32; r += 8) {
+    int k = k0 + r, n = n0 + threadIdx.x;
+    tile[r][threadIdx.x] = (k < K && n < N) ? w[(long long)k * N + n] : 0.f;
+  }
+  __syncthreads();
+  for (int r = threadIdx.y; r < 32; r += 8) {
+    int n = n0 + r, k = k0 + threadIdx.x;
+    if (n < N && k < K) codes[(long long)n * ldq + k] = (uint8_t)e4m3_encode(tile[threadIdx.x][r] * inv);
+  }
+}
+hipError_t launch_quant_transpose(const float* w, int K, int N, const unsigned* amax_bits, float* scale_out,
+                                  uint8_t* codes_out, int ldq, hipStream_t s) {
+  hipLaunchKernelGGL(quant_transpose_k, dim3((N + 31) / 32, (K + 31) / 32), dim3(32, 8), 0, s, w, K, N,
+                     amax_bits, scale_out, codes_out, ldq);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ embedding
+__global__ void embed_k(const int* tok, const float* W_E, const float* W_pos, float* out, int T, int S, int d) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long long)T * d) return;
+  int t = (int)(i / d), e = (int)(i % d);
+  float v = W_E[(long long)tok[t] * d + e];
+  if (W_pos) v += W_pos[(long long)(t % S) * d + e];
+  out[i] = v;
+}
+hipError_t launch_embed(const int* tok, const float* W_E, const float* W_pos, float* out, int T, int S, int d,
+                        hipStream_t s) {
+  long long n = (long long)T * d;
+  hipLaunchKernelGGL(embed_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, tok, W_E, W_pos, out, T, S, d);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ norm + quantise of one row held by a wave
+// x[j] is element (lane + 64*j) of the row, j < E.
+template <int MAXE>
+__device__ __forceinline__ void norm_row(float (&x)[MAXE], int E, int d, int lane, int norm_kind, float eps,
+                                         const float* gain, const float* offset) {
+  float inv_d = 1.0f / (float)d;
+  if (norm_kind == 0) {
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) s += x[j];
+    float mean = wave_sum(s) * inv_d;
+    float v = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) { x[j] -= mean; v += x[j] * x[j]; }
+    float rstd = 1.0f / sqrtf(wave_sum(v) * inv_d + eps);
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) {
+      int e = lane + 64 * j;
+      x[j] = x[j] * rstd * gain[e] + offset[e];
+    }
+  } else {
+    float v = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) v += x[j] * x[j];
+    float rstd = 1.0f / sqrtf(wave_sum(v) * inv_d + eps);
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) x[j] = x[j] * rstd * gain[lane + 64 * j];
+  }
+}
+
+template <int MAXE>
+__device__ __forceinline__ void emit_row(const float (&y)[MAXE], int E, int d, int lane, const GroupDesc& g,
+                                         int inst, int row, int ldq) {
+  if (g.out_f32) {
+    float* o = g.out_f32 + inst * g.out_f32_is + (long long)row * d;
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) o[lane + 64 * j] = y[j];
+  }
+  if (g.out_codes) {
+    float am = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) am = fmaxf(am, fabsf(y[j]));
+    am = wave_max(am);
+    float scale = (am == 0.f) ? 1.0f : am / 448.0f;
+    float inv = 1.0f / scale;
+    uint8_t* o = g.out_codes + inst * g.out_codes_is + (long long)row * ldq;
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) o[lane + 64 * j] = (uint8_t)e4m3_encode(y[j] * inv);
+    if (lane == 0) g.out_scale[inst * g.out_scale_is + row] = scale;
+  }
+}
+
+template <int MAXE>
+__global__ __launch_bounds__(256) void build_inputs_k(const GroupDesc* groups, const Term* terms, int T, int B,
+                                                       int S, int d, int ldq, int norm_kind, float eps) {
+  GroupDesc g = groups[blockIdx.y];
+  int inst = blockIdx.z;
+  int lane = threadIdx.x & 63;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int rows = g.last_only ? B : T;
+  if (row >= rows) return;
+  long long src = (long long)(g.last_only ? row * S + S - 1 : row) * d;
+  int E = d >> 6;
+  float x[MAXE];
+#pragma unroll
+  for (int j = 0; j < MAXE; j++) x[j] = 0.f;
+  if (g.base) {
+    const float* p = g.base + inst * g.base_is + src;
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) x[j] = p[lane + 64 * j];
+  }
+  if (g.run) {
+    const float* p = g.run + inst * g.run_is + src;
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) x[j] += p[lane + 64 * j];
+  }
+  for (int t = 0; t < g.term_count; t++) {
+    Term tm = terms[g.term_begin + t];
+    const float* p = tm.p + inst * tm.inst_stride + src;
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) x[j] += tm.sign * p[lane + 64 * j];
+  }
+  norm_row<MAXE>(x, E, d, lane, norm_kind, eps, g.gain, g.offset);
+  emit_row<MAXE>(x, E, d, lane, g, inst, row, ldq);
+}
+
+template <int MAXE>
+__global__ __launch_bounds__(256) void patch_build_k(const GroupDesc* gp, const float* xv, const float* delta0,
+                                                      long long delta_stride, const int* send, int n_inst, int mode,
+                                                      int T, int B, int S, int d, int ldq, int norm_kind,
+                                                      float eps) {
+  GroupDesc g = *gp;
+  int lane = threadIdx.x & 63;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int rows = g.last_only ? B : T;
+  if (row >= rows) return;
+  long long src = (long long)(g.last_only ? row * S + S - 1 : row) * d;
+  int E = d >> 6;
+  float x0[MAXE], y[MAXE];
+#pragma unroll
+  for (int j = 0; j < MAXE; j++) x0[j] = (j < E) ? xv[src + lane + 64 * j] : 0.f;
+  for (int i = 0; i < n_inst; i++) {
+    const float* dp = delta0 + (long long)send[i] * delta_stride + src;
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) y[j] = x0[j] - dp[lane + 64 * j];
+    if (mode == 2) {
+#pragma unroll
+      for (int j = 0; j < MAXE; j++) x0[j] = y[j];
+    }
+    norm_row<MAXE>(y, E, d, lane, norm_kind, eps, g.gain, g.offset);
+    emit_row<MAXE>(y, E, d, lane, g, i, row, ldq);
+  }
+}
+
+#define PAHQ_DISPATCH_E(E, CALL)                                    \
+  do {                                                              \
+    if ((E) <= 1) { CALL(1); }                                      \
+    else if ((E) <= 4) { CALL(4); }                                 \
+    else if ((E) <= 8) { CALL(8); }                                 \
+    else if ((E) <= 12) { CALL(12); }                               \
+    else if ((E) <= 16) { CALL(16); }                               \
+    else if ((E) <= 32) { CALL(32); }                               \
+    else { CALL(64); }                                              \
+  } while (0)
+
+hipError_t launch_build_inputs(const GroupDesc* groups, int n_groups, const Term* terms, int n_inst, int T, int B,
+                               int S, int d, int ldq, int norm_kind, float eps, hipStream_t s) {
+  if (n_groups == 0 || n_inst == 0) return hipSuccess;
+  dim3 grid((T + 3) / 4, n_groups, n_inst);
+#define CALL(M) hipLaunchKernelGGL(build_inputs_k<M>, grid, dim3(256), 0, s, groups, terms, T, B, S, d, ldq, norm_kind, eps)
+  PAHQ_DISPATCH_E(d / 64, CALL);
+#undef CALL
+  return hipGetLastError();
+}
+
+hipError_t launch_patch_build(const GroupDesc* g, const float* xv, const float* delta0, long long delta_stride,
+                              const int* send, int n_inst, int mode, int T, int B, int S, int d, int ldq,
+                              int norm_kind, float eps, hipStream_t s) {
+  if (n_inst == 0) return hipSuccess;
+  dim3 grid((T + 3) / 4);
+#define CALL(M) hipLaunchKernelGGL(patch_build_k<M>, grid, dim3(256), 0, s, g, xv, delta0, delta_stride, send, n_inst, mode, T, B, S, d, ldq, norm_kind, eps)
+  PAHQ_DISPATCH_E(d / 64, CALL);
+#undef CALL
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ tile arithmetic
+__global__ void xv_advance_k(float* xv, const float* delta0, long long delta_stride, const int* send, int k,
+                             long long n) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float x = xv[i];
+  for (int j = 0; j < k; j++) x -= delta0[(long long)send[j] * delta_stride + i];
+  xv[i] = x;
+}
+hipError_t launch_xv_advance(float* xv, const float* delta0, long long delta_stride, const int* send, int k,
+                             long long n_elem, hipStream_t s) {
+  if (k == 0) return hipSuccess;
+  hipLaunchKernelGGL(xv_advance_k, dim3((unsigned)((n_elem + 255) / 256)), dim3(256), 0, s, xv, delta0,
+                     delta_stride, send, k, n_elem);
+  return hipGetLastError();
+}
+
+__global__ void tile_lincomb_k(float* out, const float* base, const Term* terms, int n_terms, long long n) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float x = base ? base[i] : 0.f;
+  for (int t = 0; t < n_terms; t++) x += terms[t].sign * terms[t].p[i];
+  out[i] = x;
+}
+hipError_t launch_tile_lincomb(float* out, const float* base, const Term* terms, int n_terms, long long n_elem,
+                               hipStream_t s) {
+  hipLaunchKernelGGL(tile_lincomb_k, dim3((unsigned)((n_elem + 255) / 256)), dim3(256), 0, s, out, base, terms,
+                     n_terms, n_elem);
+  return hipGetLastError();
+}
+
+__global__ void tile_sub_k(float4* out, const float4* a, const float4* b, long long n4) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  float4 x = a[i], y = b[i];
+  out[i] = make_float4(x.x - y.x, x.y - y.y, x.z - y.z, x.w - y.w);
+}
+hipError_t launch_tile_sub(float* out, const float* a, const float* b, long long n_elem, hipStream_t s) {
+  long long n4 = n_elem / 4;
+  hipLaunchKernelGGL(tile_sub_k, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, (float4*)out,
+                     (const float4*)a, (const float4*)b, n4);
+  return hipGetLastError();
+}
+
+// run_out = run_in + bias + sum_k src_k ; slot_k = src_k - sub_k
+__global__ void combine_k(const CombineDesc* descs, int di, const CombineSrc* srcs, long long n4, int d) {
+  CombineDesc D = descs[di];
+  int inst = blockIdx.y;
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  long long e = i * 4;
+  float4 acc = *(const float4*)(D.run_in + inst * D.run_in_is + e);
+  if (D.bias) {
+    float4 b = *(const float4*)(D.bias + (e % d));
+    acc.x += b.x; acc.y += b.y; acc.z += b.z; acc.w += b.w;
+  }
+  for (int k = 0; k < D.n_src; k++) {
+    CombineSrc s = srcs[D.src_begin + k];
+    float4 v = *(const float4*)(s.src + inst * s.src_is + e);
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    if (s.slot) {
+      if (s.sub) {
+        float4 u = *(const float4*)(s.sub + e);
+        v.x -= u.x; v.y -= u.y; v.z -= u.z; v.w -= u.w;
+      }
+      *(float4*)(s.slot + inst * s.slot_is + e) = v;
+    }
+  }
+  *(float4*)(D.run_out + inst * D.run_out_is + e) = acc;
+}
+hipError_t launch_combine(const CombineDesc* descs, int desc_index, const CombineSrc* srcs, int n_inst,
+                          long long n_elem, int d, hipStream_t s) {
+  long long n4 = n_elem / 4;
+  hipLaunchKernelGGL(combine_k, dim3((unsigned)((n4 + 255) / 256), n_inst), dim3(256), 0, s, descs, desc_index,
+                     srcs, n4, d);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ generic row quantiser (one block per row)
+__device__ __forceinline__ float hidden_value(const float* up, const float* gate, long long i, int swiglu) {
+  float u = up[i];
+  if (!swiglu) return u;
+  float g = gate[i];
+  return g / (1.0f + expf(-g)) * u;
+}
+
+__global__ __launch_bounds__(256) void hidden_quant_k(const float* up, const float* gate, long long h_is,
+                                                      uint8_t* codes, long long c_is, float* scale, long long s_is,
+                                                      int T, int m, int ldq, int swiglu) {
+  __shared__ float red[4];
+  int inst = blockIdx.y, row = blockIdx.x;
+  const float* pu = up + inst * h_is + (long long)row * m;
+  const float* pg = gate ? gate + inst * h_is + (long long)row * m : nullptr;
+  float am = 0.f;
+  for (int i = threadIdx.x; i < m; i += 256) am = fmaxf(am, fabsf(hidden_value(pu, pg, i, swiglu)));
+  am = wave_max(am);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = am;
+  __syncthreads();
+  am = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float sc = (am == 0.f) ? 1.0f : am / 448.0f;
+  float inv = 1.0f / sc;
+  uint8_t* o = codes + inst * c_is + (long long)row * ldq;
+  for (int i = threadIdx.x; i < m; i += 256) o[i] = (uint8_t)e4m3_encode(hidden_value(pu, pg, i, swiglu) * inv);
+  if (threadIdx.x == 0) scale[inst * s_is + row] = sc;
+}
+hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_is, uint8_t* codes, long long c_is,
+                               float* scale, long long s_is, int n_inst, int T, int m, int ldq, int swiglu,
+                               hipStream_t s) {
+  hipLaunchKernelGGL(hidden_quant_k, dim3(T, n_inst), dim3(256), 0, s, up, gate, h_is, codes, c_is, scale, s_is,
+                     T, m, ldq, swiglu);
+  return hipGetLastError();
+}
+
+hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales,
+                                   hipStream_t s) {
+  hipLaunchKernelGGL(hidden_quant_k, dim3(rows, 1), dim3(256), 0, s, x, (const float*)nullptr, 0LL, codes, 0LL,
+                     scales, 0LL, rows, cols, cols, 0);
+  return hipGetLastError();
+}
+
+}  // namespace pahq
