@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the PAHQ / ACDC edge-ablation hot path on one MI355X.
+
+Workload (config 3, GPT-2-small shape, seeded synthetic weights and tokens):
+one step = one pass over the whole split-QKV graph, every one of its 32 491
+edges evaluated once by pahq_eval_edges against the empty removed set under
+PAHQ precision (fp32 investigated head, everything else FP8 E4M3 operands).
+That is one patched forward + KL per edge: the paper's per-edge cost
+(Appendix "Integration with ACDC", third inference; Eq. Delta L), with the
+clean / corrupted runs cached once.  value = edges evaluated per second.
+
+The ACDC sweeps at the thresholds the config names are timed as well and
+reported under "sweep" (on random-initialised weights every threshold of the
+config exceeds the total clean-vs-corrupt KL, so those sweeps remove every
+edge they evaluate and finish after the 157 in-edges of the output node).
+
+Prints ONE JSON line.  --gpus above 1 is refused: this build is single-GPU.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAKS = {"gemm_fp8": ("mfma", 5000.0, "TFLOP/s"), "gemm_f32": ("mfma", 157.3, "TFLOP/s")}
+HBM_PEAK = 8000.0  # GB/s
+
+
+def all_edges_pass(gm, P, cfg, n_recv):
+    n = 0
+    for r in range(n_recv - 1, -1, -1):
+        senders = np.arange(P.n_upstream(cfg, r), dtype=np.int32)
+        gm.eval_edges(r, senders)
+        n += senders.size
+    return n
+
+
+def cpu_baseline(name, shape, w, clean, corrupt):
+    """The oracle's cached fast path, timed on the host cores, on a bounded sample."""
+    from oracle.model import Model as OModel
+    from oracle.acdc import Acdc
+    t0 = time.time()
+    oa = Acdc(OModel(shape, w), clean, corrupt)
+    oa.base()
+    t_base = time.time() - t0
+    g = oa.g
+    L = shape.n_layers
+    lv = max(0, (2 * L) // 3)          # edge-weighted mean depth of a candidate's receiver
+    v = g.headin(lv, 0, 1)
+    oa.kl_fast(v, g.empty_removed())   # state of the receiver's fp32 head (shared by its candidates)
+    senders = [g.n_upstream(v) - 1, 0]
+    t1 = time.time()
+    for u in senders:
+        oa.kl_edge(v, u)
+    dt = time.time() - t1
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": len(senders) / dt, "unit": "edges/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{name}: {len(senders)} candidate edges into the key input of head ({lv},0) "
+                      f"({L - lv} of {L} layers recomputed, close to the edge-weighted mean of the full pass), "
+                      f"oracle cached fast path, fp64 numpy; the one-off clean/corrupt cache "
+                      f"({t_base:.0f} s) and the head's precision state are not in the timed part"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="cfg3")
+    ap.add_argument("--batch", type=int, default=64, help="candidates per device batch")
+    ap.add_argument("--mma", type=int, default=0, help="0 FP8 matrix cores, 1 fp16 matrix cores on decoded codes")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(candidates are independent and would be sharded across GPUs, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    import paper_2510_23264_amd as P
+
+    if not torch.cuda.is_available():
+        print("bench.py: no HIP device", file=sys.stderr)
+        sys.exit(1)
+    shape, w, clean, corrupt, spec = synth.make_workload(args.config)
+    gm = P.Model(shape, w, spec["B"], spec["S"], precision=P.PAHQ, max_batch_edges=args.batch, mma=args.mma)
+    cfg = gm.cfg
+    n_recv = P.n_receivers(cfg)
+    gm.clean_cache(clean, corrupt)
+
+    for _ in range(args.warmup):
+        all_edges_pass(gm, P, cfg, n_recv)
+    torch.cuda.synchronize()
+    gm.set_profiling(True)
+    t0 = time.perf_counter()
+    n_evals = 0
+    for _ in range(args.steps):
+        n_evals += all_edges_pass(gm, P, cfg, n_recv)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = gm.get_profile()
+    gm.set_profiling(False)
+
+    kernels = {}
+    for k, s in prof.items():
+        if s["launches"] == 0:
+            continue
+        e = {"launches": s["launches"], "ms_total": round(s["ms"], 3), "us_avg": round(1e3 * s["ms"] / s["launches"], 2)}
+        if s["flops"] > 0:
+            e["TFLOP/s"] = round(s["flops"] / (s["ms"] * 1e-3) / 1e12, 2)
+        if s["bytes"] > 0:
+            e["GB/s"] = round(s["bytes"] / (s["ms"] * 1e-3) / 1e9, 1)
+        kernels[k] = e
+    dom = max(prof, key=lambda k: prof[k]["ms"])
+    s = prof[dom]
+    if dom in PEAKS:
+        bound, peak, unit = PEAKS[dom]
+        ach = s["flops"] / (s["ms"] * 1e-3) / 1e12
+    else:
+        bound, peak, unit = "hbm", HBM_PEAK, "GB/s"
+        ach = s["bytes"] / (s["ms"] * 1e-3) / 1e9
+    roofline = {"kernel": dom, "bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit,
+                "frac": round(ach / peak, 4), "traffic": None,
+                "avg_launch_us": round(1e3 * s["ms"] / s["launches"], 2), "launches": s["launches"],
+                "share_of_kernel_time": round(s["ms"] / sum(v["ms"] for v in prof.values()), 3)}
+
+    sweeps = {}
+    if not args.no_sweep:
+        for tau in spec["taus"]:
+            gm.clean_cache(clean, corrupt)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            kept, ne, _ = gm.acdc_sweep(tau, trace_cap=0)
+            ts = time.perf_counter() - t1
+            sweeps[str(tau)] = {"s": round(ts, 4), "evals": int(ne), "kept_edges": int(kept.sum()),
+                                "edges_decided_per_s": round(gm.n_edges / ts, 1)}
+
+    out = {
+        "metric": "patched edge evals/sec (GPT-2-small shape)", "value": round(n_evals / dt, 1), "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(1e3 * dt / args.steps, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8_e4m3" if args.mma == 0 else "fp8_e4m3 operands on fp16 matrix cores",
+        "data": "synthetic",
+        "config": {"workload": f"{args.config}: every edge of the split-QKV graph ({gm.n_edges} edges) evaluated once "
+                               f"at the empty removed set, PAHQ precision (fp32 investigated head)",
+                   "B": spec["B"], "S": spec["S"], "batch_edges": args.batch, "edges_per_step": n_evals // args.steps,
+                   "seed": spec["seed"]},
+        "roofline": roofline, "kernels": kernels, "sweep": sweeps,
+    }
+    if not args.no_cpu_baseline:
+        gm.close()
+        out["cpu_baseline"] = cpu_baseline(args.config, shape, w, clean, corrupt)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

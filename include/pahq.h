@@ -196,6 +196,25 @@ int pahq_get_sender_output(pahq_model*, int32_t which, int32_t sender, float* ou
 /* Counters since init: [0] candidate evaluations, [1] device batches, [2] forward passes of any kind. */
 int pahq_get_counters(pahq_model*, int64_t out[3]);
 
+/* ---- measurement hooks --------------------------------------------------------
+ * With profiling on, every kernel launch of the passes is bracketed by a pair of
+ * HIP events on the model's stream; pahq_get_profile synchronises and returns,
+ * per kernel class, the number of launches, the summed event time and the
+ * algorithmic work (floating-point operations of the contraction for the
+ * matrix-core kernels; bytes that must be read and written for the streaming
+ * kernels).  Classes: 0 gather+norm+quantise, 1 edge patch, 2 fp8 GEMM,
+ * 3 fp32 GEMM, 4 attention, 5 stream update, 6 hidden quantise, 7 log-sum-exp,
+ * 8 KL.  Turning profiling on resets the counters. */
+typedef struct {
+  int64_t launches;
+  double ms;        /* sum of event-to-event times                                   */
+  double flops;     /* algorithmic flops (classes 2, 3), else 0                      */
+  double bytes;     /* algorithmic bytes read + written (classes 0, 1, 5, 6, 7, 8)   */
+} pahq_kernel_stat;
+enum { PAHQ_N_KERNEL_CLASSES = 9 };
+int pahq_set_profiling(pahq_model*, int32_t on);
+int pahq_get_profile(pahq_model*, pahq_kernel_stat out[PAHQ_N_KERNEL_CLASSES]);
+
 const char* pahq_strerror(int code);
 void pahq_free(pahq_model*);            /* frees host state only; the workspace stays the caller's */
 

@@ -48,6 +48,13 @@ class TraceRec(C.Structure):
                 ("removed", C.c_int32)]
 
 
+class KernelStat(C.Structure):
+    _fields_ = [("launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double), ("bytes", C.c_double)]
+
+
+KERNEL_CLASSES = ("gather_norm_quant", "edge_patch", "gemm_fp8", "gemm_f32", "attention", "stream_update",
+                  "hidden_quant", "logsumexp", "kl")
+
 _lib = None
 
 
@@ -77,6 +84,8 @@ def lib():
             "pahq_get_logits": [C.c_void_p, C.c_int32, f32p],
             "pahq_get_sender_output": [C.c_void_p, C.c_int32, C.c_int32, f32p],
             "pahq_get_counters": [C.c_void_p, i64p],
+            "pahq_set_profiling": [C.c_void_p, C.c_int32],
+            "pahq_get_profile": [C.c_void_p, C.POINTER(KernelStat)],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -232,6 +241,16 @@ class Model:
         out = np.empty((self.T, self.cfg.d_model), dtype=np.float32)
         _chk(lib().pahq_get_sender_output(self.h, which, sender, _ptr(out, C.c_float)), "pahq_get_sender_output")
         return out
+
+    def set_profiling(self, on):
+        _chk(lib().pahq_set_profiling(self.h, 1 if on else 0), "pahq_set_profiling")
+
+    def get_profile(self):
+        """dict: kernel class -> (launches, ms, algorithmic flops, algorithmic bytes)."""
+        out = (KernelStat * len(KERNEL_CLASSES))()
+        _chk(lib().pahq_get_profile(self.h, out), "pahq_get_profile")
+        return {n: dict(launches=o.launches, ms=o.ms, flops=o.flops, bytes=o.bytes)
+                for n, o in zip(KERNEL_CLASSES, out)}
 
     def counters(self):
         out = (C.c_int64 * 3)()

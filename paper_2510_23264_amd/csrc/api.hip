@@ -365,6 +365,7 @@ int pahq_init_model(const pahq_config* c, const pahq_weights* w, int32_t B, int3
   M->removed.assign((size_t)M->edge_off[M->g.Nr], 0);
   M->has_cache = false; M->pi_l = M->pi_h = -2; M->pi_p0 = -1;
   M->counters[0] = M->counters[1] = M->counters[2] = 0;
+  M->prof_on = false; M->prof_used = 0; memset(M->prof, 0, sizeof(M->prof));
   *out = M;
   return PAHQ_OK;
 }
@@ -373,6 +374,7 @@ void pahq_free(pahq_model* M) {
   if (!M) return;
   if (M->kl_host) (void)hipHostFree(M->kl_host);
   if (M->send_host) (void)hipHostFree(M->send_host);
+  for (hipEvent_t e : M->prof_ev) (void)hipEventDestroy(e);
   for (int i = 0; i < Arena::SLOTS; i++) {
     if (M->arena.host[i]) (void)hipHostFree(M->arena.host[i]);
     if (M->arena.ev[i]) (void)hipEventDestroy(M->arena.ev[i]);
@@ -582,6 +584,26 @@ int pahq_get_sender_output(pahq_model* M, int32_t which, int32_t sender, float* 
 int pahq_get_counters(pahq_model* M, int64_t out[3]) {
   if (!M || !out) return PAHQ_EINVAL;
   out[0] = M->counters[0]; out[1] = M->counters[1]; out[2] = M->counters[2];
+  return PAHQ_OK;
+}
+
+int pahq_set_profiling(pahq_model* M, int32_t on) {
+  if (!M) return PAHQ_EINVAL;
+  if (on && M->prof_ev.empty()) {
+    const int pairs = 4096;
+    M->prof_ev.resize(2 * pairs); M->prof_cls.assign(pairs, 0);
+    for (auto& e : M->prof_ev)
+      if (hipEventCreate(&e) != hipSuccess) { M->prof_ev.clear(); return PAHQ_EHIP; }
+  }
+  if (M->prof_on) PCHK(prof_harvest(M));
+  if (on) memset(M->prof, 0, sizeof(M->prof));
+  M->prof_on = on != 0;
+  return PAHQ_OK;
+}
+int pahq_get_profile(pahq_model* M, pahq_kernel_stat out[PAHQ_N_KERNEL_CLASSES]) {
+  if (!M || !out) return PAHQ_EINVAL;
+  if (M->prof_on) PCHK(prof_harvest(M));
+  memcpy(out, M->prof, sizeof(M->prof));
   return PAHQ_OK;
 }
 

@@ -87,6 +87,13 @@ struct pahq_model {
   int pi_l, pi_h, pi_p0;                  // fp32 head whose state (cpi, rxpi, ref_*) is current; -2 = none
   pahq::RecvPlan plan;
   int64_t counters[3];
+
+  // optional per-kernel-class timing with HIP events
+  bool prof_on;
+  std::vector<hipEvent_t> prof_ev;        // pairs (start, stop)
+  std::vector<int> prof_cls;              // class of each recorded pair
+  int prof_used;                          // pairs recorded since the last harvest
+  pahq_kernel_stat prof[PAHQ_N_KERNEL_CLASSES];
 };
 
 namespace pahq {
@@ -104,4 +111,5 @@ static inline float* corrupt_prefix(pahq_model* M, int p) {
 }
 int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan);
 void make_plan(pahq_model* M, int p0, RecvPlan& out);
+int prof_harvest(pahq_model* M);     // synchronises the stream and folds recorded event pairs into M->prof
 }  // namespace pahq

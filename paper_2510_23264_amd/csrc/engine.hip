@@ -52,8 +52,8 @@ void make_plan(pahq_model* M, int p0, RecvPlan& out) {
 
 namespace {
 
-enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL };
-struct Op { OpType t; int i0, i1, i2, i3; void* p0; void* p1; };
+enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH };
+struct Op { OpType t; int i0, i1, i2, i3; void* p0; void* p1; double flops, bytes; };
 
 struct Stream { float* p; long long is; };
 
@@ -115,8 +115,37 @@ struct Builder {
   }
 
   void add_op(OpType t, int i0 = 0, int i1 = 0, int i2 = 0, int i3 = 0, void* p0 = nullptr, void* p1 = nullptr) {
-    Op o; o.t = t; o.i0 = i0; o.i1 = i1; o.i2 = i2; o.i3 = i3; o.p0 = p0; o.p1 = p1;
+    Op o; o.t = t; o.i0 = i0; o.i1 = i1; o.i2 = i2; o.i3 = i3; o.p0 = p0; o.p1 = p1; o.flops = 0; o.bytes = 0;
     ops.push_back(o);
+  }
+  // algorithmic work of the ops just added (per instance; scaled by n at launch)
+  void work_gemm(int pb, int k_real) {
+    double f = 0;
+    for (size_t i = pb; i < probs.size(); i++) f += 2.0 * probs[i].M * probs[i].N * (double)k_real;
+    ops.back().flops = f;
+  }
+  void work_build(int g0, int n_groups, int skip = -1) {
+    double by = 0;
+    for (int i = g0; i < g0 + n_groups; i++) {
+      if (i == skip) continue;
+      const GroupDesc& gd = groups[i];
+      double rows = gd.last_only ? M->B : M->T, d = M->d;
+      double reads = (gd.base ? 1 : 0) + (gd.run ? 1 : 0) + gd.term_count;
+      by += rows * d * 4.0 * reads + (gd.out_f32 ? rows * d * 4.0 : 0) + (gd.out_codes ? rows * (d + 4.0) : 0);
+    }
+    ops.back().bytes = by;
+  }
+  // the edge-batched patch of group gi: per instance one delta tile (+ the shared current input once)
+  void add_patch(int gi) {
+    add_op(OP_PATCH, gi);
+    const GroupDesc& gd = groups[gi];
+    double rows = gd.last_only ? M->B : M->T, d = M->d;
+    ops.back().bytes = rows * d * 4.0 * (1.0 + 1.0 / a.n) + (gd.out_f32 ? rows * d * 4.0 : 0) +
+                       (gd.out_codes ? rows * (d + 4.0) : 0);
+  }
+  void add_build(int g0, int n_groups, int patch_group) {
+    if (n_groups - (patch_group >= 0 ? 1 : 0) > 0) { add_op(OP_BUILD, g0, n_groups, patch_group); work_build(g0, n_groups, patch_group); }
+    if (patch_group >= 0) add_patch(patch_group);
   }
 
   // where a recomputed sender's raw output goes
@@ -186,7 +215,7 @@ struct Builder {
         }
       }
     int n_groups = (int)groups.size() - g_begin;
-    add_op(OP_BUILD, g_begin, n_groups, patch_group);
+    add_build(g_begin, n_groups, patch_group);
     // ---- fp8 projections: runs of consecutive column blocks that read the same quantised group
     int pb = (int)probs.size(), maxN = 0;
     const long long qkv_ld = 3LL * H * dh;
@@ -203,7 +232,7 @@ struct Builder {
       if ((e - nb) * dh > maxN) maxN = (e - nb) * dh;
       nb = e;
     }
-    if ((int)probs.size() > pb) add_op(OP_GEMM8, pb, (int)probs.size() - pb, T, maxN);
+    if ((int)probs.size() > pb) { add_op(OP_GEMM8, pb, (int)probs.size() - pb, T, maxN); work_gemm(pb, d); }
     // ---- fp32 projections of the investigated head
     if (pi_layer) {
       int pf = (int)probs.size();
@@ -216,7 +245,7 @@ struct Builder {
                               bc[c] + hoff * dh, M->qkv + ((long long)c * H + a.ph) * dh, (long long)T * qkv_ld,
                               (int)qkv_ld, 0, T, dh, d));
       }
-      add_op(OP_GEMM32, pf, 3, T, dh);
+      add_op(OP_GEMM32, pf, 3, T, dh); work_gemm(pf, d);
     }
     add_op(OP_ATTN, pi_layer ? a.ph : -1);
     // ---- output projections, one sender output per head
@@ -229,12 +258,12 @@ struct Builder {
                             M->o_codes + ((long long)l * H + h) * d * Kh, Kh, M->o_scale + (long long)l * H + h, d, nullptr,
                             dest[h].p, dest[h].is, d, 0, T, d, Kh));
     }
-    if ((int)probs.size() > po) add_op(OP_GEMM8, po, (int)probs.size() - po, T, d);
+    if ((int)probs.size() > po) { add_op(OP_GEMM8, po, (int)probs.size() - po, T, d); work_gemm(po, dh); }
     if (pi_layer) {
       int pf = (int)probs.size();
       probs.push_back(prob8(M->zf32, (long long)T * dh, dh, nullptr, 0, 0, M->W_O + ((long long)l * H + a.ph) * dh * d, d,
                             nullptr, 1, nullptr, dest[a.ph].p, dest[a.ph].is, d, 0, T, d, dh));
-      add_op(OP_GEMM32, pf, 1, T, d);
+      add_op(OP_GEMM32, pf, 1, T, d); work_gemm(pf, dh);
     }
     // ---- add the heads to the stream
     Stream nxt = next_run(2 * l + 1, run.p == M->run_a ? M->run_b : M->run_a);
@@ -253,6 +282,7 @@ struct Builder {
     }
     cdescs.push_back(cd);
     add_op(OP_COMBINE, (int)cdescs.size() - 1);
+    ops.back().bytes = (double)M->tile * 4.0 * (H + 2);
     run = nxt;
   }
 
@@ -268,7 +298,7 @@ struct Builder {
     gd.out_codes = M->xcodes; gd.out_codes_is = (long long)G * T * Kd;
     gd.out_scale = M->xscale; gd.out_scale_is = (long long)G * T;
     groups.push_back(gd);
-    add_op(OP_BUILD, gi, 1, patch_group);
+    add_build(gi, 1, patch_group);
     const bool swiglu = M->cfg.act == PAHQ_ACT_SWIGLU;
     int pb = (int)probs.size();
     probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
@@ -278,13 +308,14 @@ struct Builder {
       probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
                             M->gate_codes + (long long)l * m * Kd, Kd, M->gate_scale + l, m, nullptr, M->hid2,
                             (long long)T * m, m, 0, T, m, Kd));
-    add_op(OP_GEMM8, pb, swiglu ? 2 : 1, T, m);
+    add_op(OP_GEMM8, pb, swiglu ? 2 : 1, T, m); work_gemm(pb, d);
     add_op(OP_HIDQ, swiglu ? 1 : 0);
+    ops.back().bytes = (double)T * m * ((swiglu ? 8.0 : 4.0) + 1.0);
     Stream dest = sender_dest(s, M->mlpout, M->tile);
     pb = (int)probs.size();
     probs.push_back(prob8(M->hcodes, (long long)T * Km, Km, M->hscale, T, 1, M->out_codes + (long long)l * d * Km, Km,
                           M->out_scale + l, d, nullptr, dest.p, dest.is, d, 0, T, d, Km));
-    add_op(OP_GEMM8, pb, 1, T, d);
+    add_op(OP_GEMM8, pb, 1, T, d); work_gemm(pb, m);
     Stream nxt = next_run(2 * l + 2, run.p == M->run_a ? M->run_b : M->run_a);
     CombineDesc cd; memset(&cd, 0, sizeof(cd));
     cd.run_in = run.p; cd.run_in_is = run.is; cd.run_out = nxt.p; cd.run_out_is = nxt.is;
@@ -298,6 +329,7 @@ struct Builder {
     csrcs.push_back(cs);
     cdescs.push_back(cd);
     add_op(OP_COMBINE, (int)cdescs.size() - 1);
+    ops.back().bytes = (double)M->tile * 4.0 * 3;
     run = nxt;
   }
 
@@ -315,7 +347,7 @@ struct Builder {
     gd.out_codes = M->lastcodes; gd.out_codes_is = (long long)B * Kd;
     gd.out_scale = M->lastscale; gd.out_scale_is = B;
     groups.push_back(gd);
-    add_op(OP_BUILD, gi, 1, patch_group);
+    add_build(gi, 1, patch_group);
     float* lg; long long lg_is = 0;
     switch (a.kind) {
       case BASE_CLEAN: lg = M->logits_clean; break;
@@ -326,11 +358,15 @@ struct Builder {
     int pb = (int)probs.size();
     probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1, M->u_codes, Kd,
                           M->u_scale, V, M->b_U, lg, lg_is, V, 0, B, V, Kd));
-    add_op(OP_GEMM8, pb, 1, B, V);
+    add_op(OP_GEMM8, pb, 1, B, V); work_gemm(pb, d);
     if (a.kind == BASE_CLEAN) add_op(OP_LOGZ, 0, 0, 0, 0, M->logits_clean, M->logz_clean);
     else if (a.kind == PI_REF) add_op(OP_LOGZ, 0, 0, 0, 0, M->ref_logits, M->ref_logz);
-    else if (general) add_op(OP_KL, 0, 0, 0, 0, has_pi ? (void*)M->ref_logits : (void*)M->logits_clean,
-                             has_pi ? (void*)M->ref_logz : (void*)M->logz_clean);
+    else if (general) {
+      add_op(OP_KL, 0, 0, 0, 0, has_pi ? (void*)M->ref_logits : (void*)M->logits_clean,
+             has_pi ? (void*)M->ref_logz : (void*)M->logz_clean);
+      ops.back().bytes = (double)B * V * 4.0 * (1.0 + 1.0 / a.n);   // candidate logits + the shared reference
+    }
+    if (ops.back().t == OP_LOGZ) ops.back().bytes = (double)B * V * 4.0;
   }
 };
 
@@ -381,7 +417,19 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
   // ---- launch
   const int n = a.n, T = M->T, B = M->B, S = M->S, d = M->d;
   hipStream_t st = M->stream;
+  static const int cls_of[] = {0, 2, 3, 4, 5, 6, 7, 8, 1};   // OpType -> kernel class
   for (const Op& o : b.ops) {
+    int pair = -1;
+    if (M->prof_on) {
+      if (M->prof_used * 2 + 2 > (int)M->prof_ev.size()) { int r = prof_harvest(M); if (r != PAHQ_OK) return r; }
+      pair = M->prof_used++;
+      int cls = cls_of[o.t];
+      M->prof_cls[pair] = cls;
+      M->prof[cls].launches += 1;
+      M->prof[cls].flops += o.flops * n;
+      M->prof[cls].bytes += o.bytes * n;
+      HIPCHK(hipEventRecord(M->prof_ev[2 * pair], st));
+    }
     switch (o.t) {
       case OP_BUILD: {
         // the patched receiver's group (if any) is built by the edge-batched patch kernel
@@ -393,11 +441,13 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
             HIPCHK(launch_build_inputs(d_groups + o.i0, pg - o.i0, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
           if (o.i0 + o.i1 > pg + 1)
             HIPCHK(launch_build_inputs(d_groups + pg + 1, o.i0 + o.i1 - pg - 1, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
-          HIPCHK(launch_patch_build(d_groups + pg, M->xv, M->delta, M->tile, M->send_dev, n, a.patch_mode, T, B, S, d,
-                                    M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
         }
         break;
       }
+      case OP_PATCH:
+        HIPCHK(launch_patch_build(d_groups + o.i0, M->xv, M->delta, M->tile, M->send_dev, n, a.patch_mode, T, B, S, d,
+                                  M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
+        break;
       case OP_GEMM8: HIPCHK(launch_gemm_fp8(d_probs + o.i0, o.i1, n, o.i2, o.i3, M->cfg.mma == PAHQ_MMA_F16_EXACT, st)); break;
       case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, n, o.i2, o.i3, st)); break;
       case OP_ATTN:
@@ -416,8 +466,21 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
                          n, B, M->V, st));
         break;
     }
+    if (pair >= 0) HIPCHK(hipEventRecord(M->prof_ev[2 * pair + 1], st));
   }
   M->counters[2]++;
+  return PAHQ_OK;
+}
+
+
+int prof_harvest(pahq_model* M) {
+  HIPCHK(hipStreamSynchronize(M->stream));
+  for (int i = 0; i < M->prof_used; i++) {
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, M->prof_ev[2 * i], M->prof_ev[2 * i + 1]));
+    M->prof[M->prof_cls[i]].ms += ms;
+  }
+  M->prof_used = 0;
   return PAHQ_OK;
 }
 
