@@ -27,7 +27,8 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAKS = {"gemm_fp8": ("mfma", 5000.0, "TFLOP/s"), "gemm_f32": ("mfma", 157.3, "TFLOP/s")}
+PEAKS = {"gemm_fp8": ("mfma", 5000.0, "TFLOP/s"), "oproj_fused": ("mfma", 5000.0, "TFLOP/s"),
+         "gemm_f32": ("mfma", 157.3, "TFLOP/s")}
 HBM_PEAK = 8000.0  # GB/s
 
 

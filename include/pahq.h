@@ -204,14 +204,14 @@ int pahq_get_counters(pahq_model*, int64_t out[3]);
  * matrix-core kernels; bytes that must be read and written for the streaming
  * kernels).  Classes: 0 gather+norm+quantise, 1 edge patch, 2 fp8 GEMM,
  * 3 fp32 GEMM, 4 attention, 5 stream update, 6 hidden quantise, 7 log-sum-exp,
- * 8 KL.  Turning profiling on resets the counters. */
+ * 8 KL, 9 fused output projection + stream update (fp8 matrix cores).  Turning profiling on resets the counters. */
 typedef struct {
   int64_t launches;
   double ms;        /* sum of event-to-event times                                   */
-  double flops;     /* algorithmic flops (classes 2, 3), else 0                      */
+  double flops;     /* algorithmic flops (classes 2, 3, 9), else 0                      */
   double bytes;     /* algorithmic bytes read + written (classes 0, 1, 5, 6, 7, 8)   */
 } pahq_kernel_stat;
-enum { PAHQ_N_KERNEL_CLASSES = 9 };
+enum { PAHQ_N_KERNEL_CLASSES = 10 };
 int pahq_set_profiling(pahq_model*, int32_t on);
 int pahq_get_profile(pahq_model*, pahq_kernel_stat out[PAHQ_N_KERNEL_CLASSES]);
 

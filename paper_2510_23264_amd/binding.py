@@ -53,7 +53,7 @@ class KernelStat(C.Structure):
 
 
 KERNEL_CLASSES = ("gather_norm_quant", "edge_patch", "gemm_fp8", "gemm_f32", "attention", "stream_update",
-                  "hidden_quant", "logsumexp", "kl")
+                  "hidden_quant", "logsumexp", "kl", "oproj_fused")
 
 _lib = None
 

@@ -6,7 +6,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpahq.so")
-SOURCES = ["rows.hip", "gemm.hip", "attn_kl.hip", "engine.hip", "api.hip"]
+SOURCES = ["rows.hip", "gemm.hip", "oproj.hip", "attn_kl.hip", "engine.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -20,7 +20,7 @@ def _compile(src):
 
 def build(verbose=False):
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True,
                    stdout=subprocess.PIPE, stderr=subprocess.STDOUT)

@@ -29,7 +29,7 @@ int check_supported(const pahq_config* c, int B, int S) {
   if (c->split_qkv != 1) return PAHQ_EUNSUPPORTED;
   if (c->precision == PAHQ_ALL_FP32) return PAHQ_EUNSUPPORTED;
   if (c->d_model % 64 != 0 || c->d_model > 4096) return PAHQ_EUNSUPPORTED;
-  if (c->d_head % 16 != 0 || c->d_head > 128) return PAHQ_EUNSUPPORTED;
+  if (c->d_head != 16 && c->d_head != 32 && c->d_head != 64 && c->d_head != 128) return PAHQ_EUNSUPPORTED;
   if (c->pos == PAHQ_POS_ROPE && (c->d_head & 1)) return PAHQ_EUNSUPPORTED;
   if (c->d_mlp > 0 && c->act == PAHQ_ACT_NONE) return PAHQ_EUNSUPPORTED;
   if (B < 1 || S < 1 || S > 32) return PAHQ_EUNSUPPORTED;
@@ -62,7 +62,8 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
 size_t arena_slot_bytes(const pahq_model* M) {
   size_t Nr = M->g.Nr, Ns = M->g.Ns, L = M->L, H = M->H;
   size_t b = Nr * sizeof(GroupDesc) + Nr * (Ns / 2 + 2) * sizeof(Term) + L * (5 * H + 8) * sizeof(GemmProb) +
-             2 * L * sizeof(CombineDesc) + L * (H + 1) * sizeof(CombineSrc) + 65536;
+             2 * L * sizeof(CombineDesc) + L * (H + 1) * sizeof(CombineSrc) + L * sizeof(OprojDesc) +
+             L * H * sizeof(HeadAux) + 65536;
   return (b + 4095) / 4096 * 4096;
 }
 

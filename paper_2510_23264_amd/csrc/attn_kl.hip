@@ -1,94 +1,168 @@
-// Short-sequence causal attention (one wavefront per sequence and head) and the
-// fused log-softmax + KL reduction.
+// Short-sequence causal attention (one wavefront per sequence and head, fp32
+// matrix cores) and the fused log-softmax + KL reduction.
 #include "kernels.h"
 #include "device_util.h"
 
 namespace pahq {
 
-// One wavefront handles one (instance, sequence, head): S <= 32 rows of d_head
-// <= 128.  q, k, v are staged in LDS; lane c owns output columns c, c + 64;
-// scores and the softmax are fp32, reductions are over LDS rows in a fixed
-// order.  The head's output rows are either written in fp32 (investigated
-// head) or row-quantised to e4m3 (one scale per token and head) for the fp8
-// output projection.
-template <int MAXS, int MAXD>
-__global__ __launch_bounds__(64) void attention_k(const float* qkv, long long qkv_is, uint8_t* zcodes,
-                                                   long long zc_is, float* zscale, long long zs_is, float* zf32,
-                                                   long long zf_is, int f32_head, int B, int S, int H, int dh,
-                                                   int ldz, int rope, float rope_theta) {
-  __shared__ float sq[MAXS][MAXD + 1], sk[MAXS][MAXD + 1], sv[MAXS][MAXD + 1];
-  __shared__ float sp[MAXS][MAXS + 1];
-  const int inst = blockIdx.x / B, b = blockIdx.x % B, h = blockIdx.y;
-  const int lane = threadIdx.x;
-  const int ld = 3 * H * dh;
-  const float* base = qkv + inst * qkv_is + (long long)b * S * ld;
-  for (int idx = lane; idx < S * dh; idx += 64) {
-    int i = idx / dh, c = idx % dh;
-    const float* row = base + (long long)i * ld + h * dh + c;
-    sq[i][c] = row[0];
-    sk[i][c] = row[H * dh];
-    sv[i][c] = row[2 * H * dh];
+// Causal attention on the fp32 matrix cores, one wavefront per (instance,
+// sequence, head), no LDS.  S <= 32 is covered by ST = 1 or 2 tiles of 16
+// positions; lane = 16*g + i.
+//   scores  S^T = K Q^T with V_MFMA_F32_16X16X4_F32: lane (i, g) feeds row i of a
+//           K tile and of a Q tile (its own d_head/4 consecutive columns, the
+//           same k order for both operands) and receives S[query i][key 4g + r].
+//   softmax per query: over the lane's registers and the four lanes i, i+16, i+32, i+48.
+//   output  Z = P V: the score registers are exactly the A operand (query i, key
+//           4g + r); lane (i, g) loads V[key 4g + r][16t + i] as B and receives
+//           Z[query 4g + r][16t + i].
+// Rotary embedding pairs column c with c + d_head/2, which lives in lane g ^ 2.
+// Output rows are either written in fp32 (investigated head) or row-quantised
+// to e4m3 (one scale per token and head) for the fp8 output projection.
+typedef float v4f_a __attribute__((ext_vector_type(4)));
+
+template <int ST, int DH>
+__global__ __launch_bounds__(256) void attention_mfma_k(const float* qkv, long long qkv_is, uint8_t* zcodes,
+                                                         long long zc_is, float* zscale, long long zs_is, float* zf32,
+                                                         long long zf_is, int f32_head, int n_pairs, int B, int S, int H,
+                                                         int ldz, int rope, float rope_theta) {
+  constexpr int CH = DH / 4;        // columns of q / k per lane
+  constexpr int NT = DH / 16;       // output column tiles
+  const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (pair >= n_pairs) return;
+  const int h = pair % H, sb = pair / H;          // sb = inst * B + b
+  const int inst = sb / B, b = sb % B;
+  const int lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
+  const int ld = 3 * H * DH;
+  const float* base = qkv + inst * qkv_is + (long long)b * S * ld + h * DH;
+
+  float q[ST][CH], k[ST][CH];
+#pragma unroll
+  for (int a = 0; a < ST; a++) {
+    int pos = 16 * a + i;
+    const float* row = base + (long long)pos * ld + CH * g;
+#pragma unroll
+    for (int c = 0; c < CH; c += 4) {
+      float4 vq = make_float4(0, 0, 0, 0), vk = vq;
+      if (pos < S) { vq = *(const float4*)(row + c); vk = *(const float4*)(row + H * DH + c); }
+      q[a][c] = vq.x; q[a][c + 1] = vq.y; q[a][c + 2] = vq.z; q[a][c + 3] = vq.w;
+      k[a][c] = vk.x; k[a][c + 1] = vk.y; k[a][c + 2] = vk.z; k[a][c + 3] = vk.w;
+    }
   }
-  __syncthreads();
   if (rope) {
-    int half = dh >> 1;
-    for (int idx = lane; idx < S * half; idx += 64) {
-      int i = idx / half, c = idx % half;
-      double ang = (double)i * pow((double)rope_theta, -2.0 * (double)c / (double)dh);
-      float sn = (float)sin(ang), cs = (float)cos(ang);
-      float a = sq[i][c], bq = sq[i][c + half];
-      sq[i][c] = a * cs - bq * sn;
-      sq[i][c + half] = bq * cs + a * sn;
-      a = sk[i][c]; bq = sk[i][c + half];
-      sk[i][c] = a * cs - bq * sn;
-      sk[i][c + half] = bq * cs + a * sn;
+#pragma unroll
+    for (int a = 0; a < ST; a++) {
+      int pos = 16 * a + i;
+#pragma unroll
+      for (int c = 0; c < CH; c++) {
+        int col = (CH * g + c) % (DH / 2);
+        double ang = (double)pos * pow((double)rope_theta, -2.0 * (double)col / (double)DH);
+        float sn = (float)sin(ang), cs = (float)cos(ang);
+        float pq = __shfl_xor(q[a][c], 32, 64), pk = __shfl_xor(k[a][c], 32, 64);
+        // first half: x cos - y sin ; second half: x cos + y sin (y = the partner column)
+        float sg = (g < 2) ? -sn : sn;
+        q[a][c] = q[a][c] * cs + pq * sg;
+        k[a][c] = k[a][c] * cs + pk * sg;
+      }
     }
-    __syncthreads();
   }
-  const float scl = 1.0f / sqrtf((float)dh);
-  for (int idx = lane; idx < S * S; idx += 64) {
-    int i = idx / S, j = idx % S;
-    float a = 0.f;
-    if (j <= i) {
-      for (int c = 0; c < dh; c++) a += sq[i][c] * sk[j][c];
-      a *= scl;
+
+  // scores[a][bk][r] = S[query 16a + i][key 16bk + 4g + r]
+  v4f_a sc[ST][ST];
+  const float scl = 1.0f / sqrtf((float)DH);
+#pragma unroll
+  for (int a = 0; a < ST; a++)
+#pragma unroll
+    for (int bk = 0; bk <= a; bk++) {
+      v4f_a acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < CH; c++) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(k[bk][c], q[a][c], acc, 0, 0, 0);
+      sc[a][bk] = acc;
     }
-    sp[i][j] = a;
-  }
-  __syncthreads();
-  if (lane < S) {                 // softmax of row `lane` over j <= lane
-    int i = lane;
-    float mx = sp[i][0];
-    for (int j = 1; j <= i; j++) mx = fmaxf(mx, sp[i][j]);
+#pragma unroll
+  for (int a = 0; a < ST; a++) {
+    const int qpos = 16 * a + i;
+    float mx = -3.0e38f;
+#pragma unroll
+    for (int bk = 0; bk <= a; bk++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        int kpos = 16 * bk + 4 * g + r;
+        float v = sc[a][bk][r] * scl;
+        bool ok = kpos <= qpos && kpos < S;
+        sc[a][bk][r] = ok ? v : -3.0e38f;
+        if (ok) mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     float sum = 0.f;
-    for (int j = 0; j <= i; j++) { float e = expf(sp[i][j] - mx); sp[i][j] = e; sum += e; }
-    float r = 1.0f / sum;
-    for (int j = 0; j <= i; j++) sp[i][j] *= r;
+#pragma unroll
+    for (int bk = 0; bk <= a; bk++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        float e = (sc[a][bk][r] > -1.0e38f) ? expf(sc[a][bk][r] - mx) : 0.f;
+        sc[a][bk][r] = e;
+        sum += e;
+      }
+    sum += __shfl_xor(sum, 16, 64);
+    sum += __shfl_xor(sum, 32, 64);
+    float rs = (sum > 0.f) ? 1.0f / sum : 0.f;
+#pragma unroll
+    for (int bk = 0; bk <= a; bk++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) sc[a][bk][r] *= rs;
   }
-  __syncthreads();
-  const bool f32 = (h == f32_head);
-  for (int i = 0; i < S; i++) {
-    float z0 = 0.f, z1 = 0.f;
-    const int c0 = lane, c1 = lane + 64;
-    for (int j = 0; j <= i; j++) {
-      float p = sp[i][j];
-      if (c0 < dh) z0 += p * sv[j][c0];
-      if (c1 < dh) z1 += p * sv[j][c1];
+
+  // values: vv[bk][r][t] = V[key 16bk + 4g + r][16t + i]
+  float vv[ST][4][NT];
+#pragma unroll
+  for (int bk = 0; bk < ST; bk++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      int kpos = 16 * bk + 4 * g + r;
+      const float* row = base + (long long)kpos * ld + 2 * H * DH + i;
+#pragma unroll
+      for (int t = 0; t < NT; t++) vv[bk][r][t] = (kpos < S) ? row[16 * t] : 0.f;
     }
-    long long t = (long long)b * S + i;
-    if (f32) {
-      float* o = zf32 + inst * zf_is + t * dh;
-      if (c0 < dh) o[c0] = z0;
-      if (c1 < dh) o[c1] = z1;
-    } else {
-      float am = fmaxf(c0 < dh ? fabsf(z0) : 0.f, c1 < dh ? fabsf(z1) : 0.f);
-      am = wave_max(am);
-      float sc = (am == 0.f) ? 1.0f : am / 448.0f;
-      float inv = 1.0f / sc;
-      uint8_t* o = zcodes + inst * zc_is + (t * H + h) * ldz;
-      if (c0 < dh) o[c0] = (uint8_t)e4m3_encode(z0 * inv);
-      if (c1 < dh) o[c1] = (uint8_t)e4m3_encode(z1 * inv);
-      if (lane == 0) zscale[inst * zs_is + t * H + h] = sc;
+
+  const bool f32 = (h == f32_head);
+#pragma unroll
+  for (int a = 0; a < ST; a++) {
+    v4f_a z[NT];
+#pragma unroll
+    for (int t = 0; t < NT; t++) {
+      v4f_a acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int bk = 0; bk <= a; bk++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(sc[a][bk][r], vv[bk][r][t], acc, 0, 0, 0);
+      z[t] = acc;
+    }
+    // lane (i, g) holds Z[query 16a + 4g + rr][16t + i]
+#pragma unroll
+    for (int rr = 0; rr < 4; rr++) {
+      int pos = 16 * a + 4 * g + rr;
+      long long tok = (long long)b * S + pos;
+      if (f32) {
+        if (pos < S) {
+          float* o = zf32 + inst * zf_is + tok * DH + i;
+#pragma unroll
+          for (int t = 0; t < NT; t++) o[16 * t] = z[t][rr];
+        }
+      } else {
+        float am = 0.f;
+#pragma unroll
+        for (int t = 0; t < NT; t++) am = fmaxf(am, fabsf(z[t][rr]));
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) am = fmaxf(am, __shfl_xor(am, o, 64));
+        float scale = (am == 0.f) ? 1.0f : am / 448.0f;
+        float inv = 1.0f / scale;
+        if (pos < S) {
+          uint8_t* o = zcodes + inst * zc_is + (tok * H + h) * ldz + i;
+#pragma unroll
+          for (int t = 0; t < NT; t++) o[16 * t] = (uint8_t)e4m3_encode(z[t][rr] * inv);
+          if (i == 0) zscale[inst * zs_is + tok * H + h] = scale;
+        }
+      }
     }
   }
 }
@@ -97,14 +171,19 @@ hipError_t launch_attention(const float* qkv, long long qkv_is, uint8_t* zcodes,
                             long long zs_is, float* zf32, long long zf_is, int f32_head, int n_inst, int B, int S,
                             int H, int dh, int ldz, int rope, float rope_theta, hipStream_t s) {
   if (n_inst == 0) return hipSuccess;
-  if (S > 32 || dh > 128) return hipErrorInvalidValue;
-  dim3 grid(n_inst * B, H);
-  if (dh <= 64)
-    hipLaunchKernelGGL((attention_k<32, 64>), grid, dim3(64), 0, s, qkv, qkv_is, zcodes, zc_is, zscale, zs_is, zf32,
-                       zf_is, f32_head, B, S, H, dh, ldz, rope, rope_theta);
-  else
-    hipLaunchKernelGGL((attention_k<32, 128>), grid, dim3(64), 0, s, qkv, qkv_is, zcodes, zc_is, zscale, zs_is,
-                       zf32, zf_is, f32_head, B, S, H, dh, ldz, rope, rope_theta);
+  if (S > 32) return hipErrorInvalidValue;
+  int n_pairs = n_inst * B * H;
+  dim3 grid((n_pairs + 3) / 4);
+#define ATT(ST_, DH_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_>), grid, dim3(256), 0, s, qkv, qkv_is, zcodes, zc_is, \
+                                         zscale, zs_is, zf32, zf_is, f32_head, n_pairs, B, S, H, ldz, rope, rope_theta)
+  if (S <= 16) {
+    if (dh == 16) ATT(1, 16); else if (dh == 32) ATT(1, 32); else if (dh == 64) ATT(1, 64);
+    else if (dh == 128) ATT(1, 128); else return hipErrorInvalidValue;
+  } else {
+    if (dh == 16) ATT(2, 16); else if (dh == 32) ATT(2, 32); else if (dh == 64) ATT(2, 64);
+    else if (dh == 128) ATT(2, 128); else return hipErrorInvalidValue;
+  }
+#undef ATT
   return hipGetLastError();
 }
 

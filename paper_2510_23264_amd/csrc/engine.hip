@@ -52,7 +52,7 @@ void make_plan(pahq_model* M, int p0, RecvPlan& out) {
 
 namespace {
 
-enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH };
+enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH, OP_OPROJ };
 struct Op { OpType t; int i0, i1, i2, i3; void* p0; void* p1; double flops, bytes; };
 
 struct Stream { float* p; long long is; };
@@ -66,6 +66,8 @@ struct Builder {
   std::vector<GemmProb> probs;
   std::vector<CombineDesc> cdescs;
   std::vector<CombineSrc> csrcs;
+  std::vector<OprojDesc> odescs;
+  std::vector<HeadAux> haux;
   std::vector<Op> ops;
   bool general, has_pi;
   int nstat;
@@ -104,13 +106,14 @@ struct Builder {
     }
   }
 
+  // Mr rows per instance; the problem covers all a.n instances (rows numbered across instances)
   GemmProb prob8(const void* A, long long a_is, int lda, const float* as, long long as_is, int as_stride,
                  const void* W, int ldw, const float* ws, int ws_block, const float* bias, float* C, long long c_is,
-                 int ldc, int act, int Mr, int N, int K) {
+                 int ldc, int act, int Mr, int N, int K, int k_real) {
     GemmProb p; memset(&p, 0, sizeof(p));
     p.A = A; p.a_is = a_is; p.lda = lda; p.ascale = as; p.as_is = as_is; p.as_stride = as_stride;
     p.W = W; p.ldw = ldw; p.wscale = ws; p.wscale_block = ws_block; p.bias = bias;
-    p.C = C; p.c_is = c_is; p.ldc = ldc; p.act = act; p.M = Mr; p.N = N; p.K = K;
+    p.C = C; p.c_is = c_is; p.ldc = ldc; p.act = act; p.rpi = Mr; p.M = Mr * a.n; p.N = N; p.K = K; p.k_real = k_real;
     return p;
   }
 
@@ -118,10 +121,10 @@ struct Builder {
     Op o; o.t = t; o.i0 = i0; o.i1 = i1; o.i2 = i2; o.i3 = i3; o.p0 = p0; o.p1 = p1; o.flops = 0; o.bytes = 0;
     ops.push_back(o);
   }
-  // algorithmic work of the ops just added (per instance; scaled by n at launch)
-  void work_gemm(int pb, int k_real) {
+  // algorithmic work of the op just added (all instances)
+  void work_gemm(int pb) {
     double f = 0;
-    for (size_t i = pb; i < probs.size(); i++) f += 2.0 * probs[i].M * probs[i].N * (double)k_real;
+    for (size_t i = pb; i < probs.size(); i++) f += 2.0 * probs[i].M * probs[i].N * (double)probs[i].k_real;
     ops.back().flops = f;
   }
   void work_build(int g0, int n_groups, int skip = -1) {
@@ -133,15 +136,15 @@ struct Builder {
       double reads = (gd.base ? 1 : 0) + (gd.run ? 1 : 0) + gd.term_count;
       by += rows * d * 4.0 * reads + (gd.out_f32 ? rows * d * 4.0 : 0) + (gd.out_codes ? rows * (d + 4.0) : 0);
     }
-    ops.back().bytes = by;
+    ops.back().bytes = by * a.n;
   }
   // the edge-batched patch of group gi: per instance one delta tile (+ the shared current input once)
   void add_patch(int gi) {
     add_op(OP_PATCH, gi);
     const GroupDesc& gd = groups[gi];
     double rows = gd.last_only ? M->B : M->T, d = M->d;
-    ops.back().bytes = rows * d * 4.0 * (1.0 + 1.0 / a.n) + (gd.out_f32 ? rows * d * 4.0 : 0) +
-                       (gd.out_codes ? rows * (d + 4.0) : 0);
+    ops.back().bytes = a.n * (rows * d * 4.0 * (1.0 + 1.0 / a.n) + (gd.out_f32 ? rows * d * 4.0 : 0) +
+                              (gd.out_codes ? rows * (d + 4.0) : 0));
   }
   void add_build(int g0, int n_groups, int patch_group) {
     if (n_groups - (patch_group >= 0 ? 1 : 0) > 0) { add_op(OP_BUILD, g0, n_groups, patch_group); work_build(g0, n_groups, patch_group); }
@@ -178,7 +181,7 @@ struct Builder {
 
   void attention_block(int l, Stream& run) {
     const GraphDims& g = M->g;
-    const int H = M->H, dh = M->dh, d = M->d, T = M->T, Kd = M->Kd, Kh = M->Kh, G = M->G;
+    const int H = M->H, dh = M->dh, d = M->d, T = M->T, Kd = M->Kd, Kh = M->Kh;
     const bool pi_layer = has_pi && l == a.pl;
     // ---- groups
     std::map<std::pair<int, std::vector<int>>, int> seen;
@@ -208,10 +211,10 @@ struct Builder {
         GroupDesc& gd = groups[gi];
         int local = gi - g_begin;
         if (is_pi) {
-          if (!gd.out_f32) { gd.out_f32 = M->xf32 + (long long)n_f32 * M->tile; gd.out_f32_is = 3 * M->tile; n_f32++; }
+          if (!gd.out_f32) { gd.out_f32 = M->xf32 + (long long)n_f32 * M->nmax * M->tile; gd.out_f32_is = M->tile; n_f32++; }
         } else if (!gd.out_codes) {
-          gd.out_codes = M->xcodes + (long long)local * T * Kd; gd.out_codes_is = (long long)G * T * Kd;
-          gd.out_scale = M->xscale + (long long)local * T; gd.out_scale_is = (long long)G * T;
+          gd.out_codes = M->xcodes + (long long)local * M->nmax * T * Kd; gd.out_codes_is = (long long)T * Kd;
+          gd.out_scale = M->xscale + (long long)local * M->nmax * T; gd.out_scale_is = T;
         }
       }
     int n_groups = (int)groups.size() - g_begin;
@@ -228,11 +231,11 @@ struct Builder {
       probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
                             M->qkv_codes + ((long long)l * 3 * H * dh + (long long)nb * dh) * Kd, Kd,
                             M->qkv_scale + (long long)l * 3 * H + nb, dh, M->bqkv + (long long)l * 3 * H * dh + (long long)nb * dh,
-                            M->qkv + (long long)nb * dh, (long long)T * qkv_ld, (int)qkv_ld, 0, T, (e - nb) * dh, Kd));
+                            M->qkv + (long long)nb * dh, (long long)T * qkv_ld, (int)qkv_ld, 0, T, (e - nb) * dh, Kd, d));
       if ((e - nb) * dh > maxN) maxN = (e - nb) * dh;
       nb = e;
     }
-    if ((int)probs.size() > pb) { add_op(OP_GEMM8, pb, (int)probs.size() - pb, T, maxN); work_gemm(pb, d); }
+    if ((int)probs.size() > pb) { add_op(OP_GEMM8, pb, (int)probs.size() - pb, T * a.n, maxN); work_gemm(pb); }
     // ---- fp32 projections of the investigated head
     if (pi_layer) {
       int pf = (int)probs.size();
@@ -243,93 +246,95 @@ struct Builder {
         long long hoff = (long long)l * H + a.ph;
         probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1,
                               bc[c] + hoff * dh, M->qkv + ((long long)c * H + a.ph) * dh, (long long)T * qkv_ld,
-                              (int)qkv_ld, 0, T, dh, d));
+                              (int)qkv_ld, 0, T, dh, d, d));
       }
-      add_op(OP_GEMM32, pf, 3, T, dh); work_gemm(pf, d);
+      add_op(OP_GEMM32, pf, 3, T * a.n, dh); work_gemm(pf);
     }
     add_op(OP_ATTN, pi_layer ? a.ph : -1);
-    // ---- output projections, one sender output per head
-    int po = (int)probs.size();
-    std::vector<Stream> dest(H);
-    for (int h = 0; h < H; h++) {
-      dest[h] = sender_dest(g.head(l, h), M->headout + (long long)h * M->tile, (long long)H * M->tile);
-      if (pi_layer && h == a.ph) continue;
-      probs.push_back(prob8(M->zcodes + (long long)h * Kh, (long long)T * H * Kh, H * Kh, M->zscale + h, (long long)T * H, H,
-                            M->o_codes + ((long long)l * H + h) * d * Kh, Kh, M->o_scale + (long long)l * H + h, d, nullptr,
-                            dest[h].p, dest[h].is, d, 0, T, d, Kh));
-    }
-    if ((int)probs.size() > po) { add_op(OP_GEMM8, po, (int)probs.size() - po, T, d); work_gemm(po, dh); }
-    if (pi_layer) {
-      int pf = (int)probs.size();
-      probs.push_back(prob8(M->zf32, (long long)T * dh, dh, nullptr, 0, 0, M->W_O + ((long long)l * H + a.ph) * dh * d, d,
-                            nullptr, 1, nullptr, dest[a.ph].p, dest[a.ph].is, d, 0, T, d, dh));
-      add_op(OP_GEMM32, pf, 1, T, d); work_gemm(pf, dh);
-    }
-    // ---- add the heads to the stream
+    // ---- output projections of all heads fused with the stream update.  Only heads whose
+    // individual output is needed (cache passes; a downstream receiver that treats the head's
+    // edge differently from the stream) are written out.
     Stream nxt = next_run(2 * l + 1, run.p == M->run_a ? M->run_b : M->run_a);
-    CombineDesc cd; memset(&cd, 0, sizeof(cd));
-    cd.run_in = run.p; cd.run_in_is = run.is; cd.run_out = nxt.p; cd.run_out_is = nxt.is;
-    cd.bias = M->b_O + (long long)l * d; cd.src_begin = (int)csrcs.size(); cd.n_src = H;
+    const bool store_raw = (a.kind == BASE_CLEAN || a.kind == BASE_CORRUPT || a.kind == PI_CORRUPT);
+    OprojDesc od; memset(&od, 0, sizeof(od));
+    od.zc = M->zcodes; od.zc_is = (long long)T * H * Kh; od.zs = M->zscale; od.zs_is = (long long)T * H;
+    od.W = M->o_codes + (long long)l * H * d * Kh; od.ws = M->o_scale + (long long)l * H;
+    od.run_in = run.p; od.run_in_is = run.is; od.run_out = nxt.p; od.run_out_is = nxt.is;
+    od.bias = M->b_O + (long long)l * d;
+    od.H = H; od.Kh = Kh; od.skip_head = pi_layer ? a.ph : -1; od.rpi = T; od.M = T * a.n; od.N = d;
+    od.aux_begin = -1;
+    bool any_aux = false;
+    std::vector<HeadAux> hx(H);
     for (int h = 0; h < H; h++) {
-      CombineSrc cs; memset(&cs, 0, sizeof(cs));
-      cs.src = dest[h].p; cs.src_is = dest[h].is;
       int s = g.head(l, h);
-      if (general && plan->slot_of[s] >= 0) {
-        cs.slot = M->slots + (long long)plan->slot_of[s] * M->tile; cs.slot_is = (long long)plan->n_slots * M->tile;
-        cs.sub = corrupt_ref_tile(s);
+      hx[h].dst = nullptr; hx[h].dst_is = 0; hx[h].sub = nullptr;
+      if (store_raw) { Stream dst = sender_dest(s, nullptr, 0); hx[h].dst = dst.p; hx[h].dst_is = dst.is; }
+      else if (general && plan->slot_of[s] >= 0) {
+        hx[h].dst = M->slots + (long long)plan->slot_of[s] * M->tile; hx[h].dst_is = (long long)plan->n_slots * M->tile;
+        hx[h].sub = corrupt_ref_tile(s);
       }
-      csrcs.push_back(cs);
+      if (hx[h].dst) any_aux = true;
     }
-    cdescs.push_back(cd);
-    add_op(OP_COMBINE, (int)cdescs.size() - 1);
-    ops.back().bytes = (double)M->tile * 4.0 * (H + 2);
+    if (pi_layer) {
+      // the investigated head's projection in fp32; its output goes to scratch (added by the fused
+      // kernel) and, where needed, to its cache tile / slot through the second output
+      int pf = (int)probs.size();
+      GemmProb pp = prob8(M->zf32, (long long)T * dh, dh, nullptr, 0, 0, M->W_O + ((long long)l * H + a.ph) * dh * d, d,
+                          nullptr, 1, nullptr, M->headout, M->tile, d, 0, T, d, dh, dh);
+      pp.aux = hx[a.ph].dst; pp.aux_is = hx[a.ph].dst_is; pp.aux_sub = hx[a.ph].sub;
+      probs.push_back(pp);
+      add_op(OP_GEMM32, pf, 1, T * a.n, d); work_gemm(pf);
+      od.extra = M->headout; od.extra_is = M->tile;
+    }
+    if (any_aux) { od.aux_begin = (int)haux.size(); haux.insert(haux.end(), hx.begin(), hx.end()); }
+    odescs.push_back(od);
+    add_op(OP_OPROJ, (int)odescs.size() - 1, T * a.n, d);
+    ops.back().flops = 2.0 * T * a.n * d * dh * (H - (pi_layer ? 1 : 0));
     run = nxt;
   }
 
   void mlp_block(int l, Stream& run) {
     const GraphDims& g = M->g;
-    const int d = M->d, T = M->T, Kd = M->Kd, Km = M->Km, m = M->m, G = M->G;
+    const int d = M->d, T = M->T, Kd = M->Kd, Km = M->Km, m = M->m;
     int w = g.mlpin(l), s = g.mlp(l);
     GroupDesc gd; memset(&gd, 0, sizeof(gd));
     int patch_group = -1, gi = (int)groups.size();
     if (a.kind == CAND && w == a.v) patch_group = gi;
     else fill_input(gd, general ? &plan->spec[w] : nullptr, 2 * l + 1, run);
     norm_params(gd, M->ln2_g + (long long)l * d, M->ln2_b + (long long)l * d);
-    gd.out_codes = M->xcodes; gd.out_codes_is = (long long)G * T * Kd;
-    gd.out_scale = M->xscale; gd.out_scale_is = (long long)G * T;
+    gd.out_codes = M->xcodes; gd.out_codes_is = (long long)T * Kd;
+    gd.out_scale = M->xscale; gd.out_scale_is = T;
     groups.push_back(gd);
     add_build(gi, 1, patch_group);
     const bool swiglu = M->cfg.act == PAHQ_ACT_SWIGLU;
     int pb = (int)probs.size();
     probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
                           M->in_codes + (long long)l * m * Kd, Kd, M->in_scale + l, m, M->b_in + (long long)l * m, M->hid,
-                          (long long)T * m, m, M->cfg.act == PAHQ_ACT_GELU ? 1 : 0, T, m, Kd));
+                          (long long)T * m, m, M->cfg.act == PAHQ_ACT_GELU ? 1 : 0, T, m, Kd, d));
     if (swiglu)
       probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
                             M->gate_codes + (long long)l * m * Kd, Kd, M->gate_scale + l, m, nullptr, M->hid2,
-                            (long long)T * m, m, 0, T, m, Kd));
-    add_op(OP_GEMM8, pb, swiglu ? 2 : 1, T, m); work_gemm(pb, d);
+                            (long long)T * m, m, 0, T, m, Kd, d));
+    add_op(OP_GEMM8, pb, swiglu ? 2 : 1, T * a.n, m); work_gemm(pb);
     add_op(OP_HIDQ, swiglu ? 1 : 0);
-    ops.back().bytes = (double)T * m * ((swiglu ? 8.0 : 4.0) + 1.0);
-    Stream dest = sender_dest(s, M->mlpout, M->tile);
-    pb = (int)probs.size();
-    probs.push_back(prob8(M->hcodes, (long long)T * Km, Km, M->hscale, T, 1, M->out_codes + (long long)l * d * Km, Km,
-                          M->out_scale + l, d, nullptr, dest.p, dest.is, d, 0, T, d, Km));
-    add_op(OP_GEMM8, pb, 1, T, d); work_gemm(pb, m);
+    ops.back().bytes = (double)a.n * T * m * ((swiglu ? 8.0 : 4.0) + 1.0);
+    // output projection fused with the stream update: next = run + b_out + out; the sender's own
+    // output (cache passes) or its difference to the corrupted run (a slot some receiver reads)
+    // leaves through the second output
     Stream nxt = next_run(2 * l + 2, run.p == M->run_a ? M->run_b : M->run_a);
-    CombineDesc cd; memset(&cd, 0, sizeof(cd));
-    cd.run_in = run.p; cd.run_in_is = run.is; cd.run_out = nxt.p; cd.run_out_is = nxt.is;
-    cd.bias = M->b_out + (long long)l * d; cd.src_begin = (int)csrcs.size(); cd.n_src = 1;
-    CombineSrc cs; memset(&cs, 0, sizeof(cs));
-    cs.src = dest.p; cs.src_is = dest.is;
-    if (general && plan->slot_of[s] >= 0) {
-      cs.slot = M->slots + (long long)plan->slot_of[s] * M->tile; cs.slot_is = (long long)plan->n_slots * M->tile;
-      cs.sub = corrupt_ref_tile(s);
+    pb = (int)probs.size();
+    GemmProb po = prob8(M->hcodes, (long long)T * Km, Km, M->hscale, T, 1, M->out_codes + (long long)l * d * Km, Km,
+                        M->out_scale + l, d, M->b_out + (long long)l * d, nxt.p, nxt.is, d, 0, T, d, Km, m);
+    po.add = run.p; po.add_is = run.is;
+    if (a.kind == BASE_CLEAN || a.kind == BASE_CORRUPT || a.kind == PI_CORRUPT) {
+      Stream dest = sender_dest(s, nullptr, 0);
+      po.aux = dest.p; po.aux_is = dest.is;
+    } else if (general && plan->slot_of[s] >= 0) {
+      po.aux = M->slots + (long long)plan->slot_of[s] * M->tile; po.aux_is = (long long)plan->n_slots * M->tile;
+      po.aux_sub = corrupt_ref_tile(s);
     }
-    csrcs.push_back(cs);
-    cdescs.push_back(cd);
-    add_op(OP_COMBINE, (int)cdescs.size() - 1);
-    ops.back().bytes = (double)M->tile * 4.0 * 3;
+    probs.push_back(po);
+    add_op(OP_GEMM8, pb, 1, T * a.n, d); work_gemm(pb);
     run = nxt;
   }
 
@@ -357,14 +362,14 @@ struct Builder {
     }
     int pb = (int)probs.size();
     probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1, M->u_codes, Kd,
-                          M->u_scale, V, M->b_U, lg, lg_is, V, 0, B, V, Kd));
-    add_op(OP_GEMM8, pb, 1, B, V); work_gemm(pb, d);
+                          M->u_scale, V, M->b_U, lg, lg_is, V, 0, B, V, Kd, d));
+    add_op(OP_GEMM8, pb, 1, B * a.n, V); work_gemm(pb);
     if (a.kind == BASE_CLEAN) add_op(OP_LOGZ, 0, 0, 0, 0, M->logits_clean, M->logz_clean);
     else if (a.kind == PI_REF) add_op(OP_LOGZ, 0, 0, 0, 0, M->ref_logits, M->ref_logz);
     else if (general) {
       add_op(OP_KL, 0, 0, 0, 0, has_pi ? (void*)M->ref_logits : (void*)M->logits_clean,
              has_pi ? (void*)M->ref_logz : (void*)M->logz_clean);
-      ops.back().bytes = (double)B * V * 4.0 * (1.0 + 1.0 / a.n);   // candidate logits + the shared reference
+      ops.back().bytes = (double)a.n * B * V * 4.0 * (1.0 + 1.0 / a.n);   // candidate logits + the shared reference
     }
     if (ops.back().t == OP_LOGZ) ops.back().bytes = (double)B * V * 4.0;
   }
@@ -398,7 +403,9 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
   size_t o_probs = align_up(o_terms + b.terms.size() * sizeof(Term), 256);
   size_t o_cdesc = align_up(o_probs + b.probs.size() * sizeof(GemmProb), 256);
   size_t o_csrc = align_up(o_cdesc + b.cdescs.size() * sizeof(CombineDesc), 256);
-  size_t total = align_up(o_csrc + b.csrcs.size() * sizeof(CombineSrc), 256);
+  size_t o_odesc = align_up(o_csrc + b.csrcs.size() * sizeof(CombineSrc), 256);
+  size_t o_haux = align_up(o_odesc + b.odescs.size() * sizeof(OprojDesc), 256);
+  size_t total = align_up(o_haux + b.haux.size() * sizeof(HeadAux), 256);
   if (total > A.slot_bytes) return PAHQ_ENOMEM;
   char* h = A.host[slot];
   if (!b.groups.empty()) memcpy(h + o_groups, b.groups.data(), b.groups.size() * sizeof(GroupDesc));
@@ -406,6 +413,8 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
   if (!b.probs.empty()) memcpy(h + o_probs, b.probs.data(), b.probs.size() * sizeof(GemmProb));
   if (!b.cdescs.empty()) memcpy(h + o_cdesc, b.cdescs.data(), b.cdescs.size() * sizeof(CombineDesc));
   if (!b.csrcs.empty()) memcpy(h + o_csrc, b.csrcs.data(), b.csrcs.size() * sizeof(CombineSrc));
+  if (!b.odescs.empty()) memcpy(h + o_odesc, b.odescs.data(), b.odescs.size() * sizeof(OprojDesc));
+  if (!b.haux.empty()) memcpy(h + o_haux, b.haux.data(), b.haux.size() * sizeof(HeadAux));
   HIPCHK(hipMemcpyAsync(A.dev[slot], h, total, hipMemcpyHostToDevice, M->stream));
   HIPCHK(hipEventRecord(A.ev[slot], M->stream));
   const GroupDesc* d_groups = (const GroupDesc*)(A.dev[slot] + o_groups);
@@ -413,11 +422,13 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
   const GemmProb* d_probs = (const GemmProb*)(A.dev[slot] + o_probs);
   const CombineDesc* d_cdesc = (const CombineDesc*)(A.dev[slot] + o_cdesc);
   const CombineSrc* d_csrc = (const CombineSrc*)(A.dev[slot] + o_csrc);
+  const OprojDesc* d_odesc = (const OprojDesc*)(A.dev[slot] + o_odesc);
+  const HeadAux* d_haux = (const HeadAux*)(A.dev[slot] + o_haux);
 
   // ---- launch
   const int n = a.n, T = M->T, B = M->B, S = M->S, d = M->d;
   hipStream_t st = M->stream;
-  static const int cls_of[] = {0, 2, 3, 4, 5, 6, 7, 8, 1};   // OpType -> kernel class
+  static const int cls_of[] = {0, 2, 3, 4, 5, 6, 7, 8, 1, 9};   // OpType -> kernel class
   for (const Op& o : b.ops) {
     int pair = -1;
     if (M->prof_on) {
@@ -426,8 +437,8 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
       int cls = cls_of[o.t];
       M->prof_cls[pair] = cls;
       M->prof[cls].launches += 1;
-      M->prof[cls].flops += o.flops * n;
-      M->prof[cls].bytes += o.bytes * n;
+      M->prof[cls].flops += o.flops;
+      M->prof[cls].bytes += o.bytes;
       HIPCHK(hipEventRecord(M->prof_ev[2 * pair], st));
     }
     switch (o.t) {
@@ -448,14 +459,20 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         HIPCHK(launch_patch_build(d_groups + o.i0, M->xv, M->delta, M->tile, M->send_dev, n, a.patch_mode, T, B, S, d,
                                   M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
         break;
-      case OP_GEMM8: HIPCHK(launch_gemm_fp8(d_probs + o.i0, o.i1, n, o.i2, o.i3, M->cfg.mma == PAHQ_MMA_F16_EXACT, st)); break;
-      case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, n, o.i2, o.i3, st)); break;
+      case OP_GEMM8:
+        HIPCHK(launch_gemm_fp8(d_probs + o.i0, o.i1, o.i2, o.i3, M->cfg.mma == PAHQ_MMA_F16_EXACT,
+                               0, st));
+        break;
+      case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, o.i2, o.i3, st)); break;
       case OP_ATTN:
         HIPCHK(launch_attention(M->qkv, (long long)T * 3 * M->H * M->dh, M->zcodes, (long long)T * M->H * M->Kh,
                                 M->zscale, (long long)T * M->H, M->zf32, (long long)T * M->dh, o.i0, n, B, S, M->H,
                                 M->dh, M->Kh, M->cfg.pos == PAHQ_POS_ROPE, M->cfg.rope_theta, st));
         break;
       case OP_COMBINE: HIPCHK(launch_combine(d_cdesc, o.i0, d_csrc, n, M->tile, d, st)); break;
+      case OP_OPROJ:
+        HIPCHK(launch_oproj_fused(d_odesc, o.i0, d_haux, o.i1, o.i2, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
+        break;
       case OP_HIDQ:
         HIPCHK(launch_hidden_quant(M->hid, o.i0 ? M->hid2 : nullptr, (long long)T * M->m, M->hcodes, (long long)T * M->Km,
                                    M->hscale, T, n, T, M->m, M->Km, o.i0, st));

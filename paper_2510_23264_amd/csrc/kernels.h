@@ -29,18 +29,26 @@ struct GroupDesc {
   int pad_;
 };
 
-// C[inst][m][n] = act((sum_k A[inst][m][k] * W[n][k]) * ascale[inst][m] * wscale[n / wscale_block] + bias[n])
+// One GEMM problem.  Rows are numbered 0 .. M-1 over all instances: row m belongs
+// to instance m / rpi and is row m % rpi of it, so a launch needs no instance
+// dimension and row tiles may straddle instances.
+//   val[m][n] = (sum_k A[m][k] * W[n][k]) * ascale[m] * wscale[n / wscale_block]
+//   C[m][n]   = act(val + bias[n]) + add[m][n]
+//   aux[m][n] = val - aux_sub[m % rpi][n]            (optional second output)
 // A, W: e4m3 codes, K contiguous, K a multiple of 128 (zero padded).
 struct GemmProb {
-  const void* A;       long long a_is;  int lda;  int pad0_;
-  const float* ascale; long long as_is; int as_stride; int pad1_;
+  const void* A;       long long a_is;  int lda;  int rpi;          // rows per instance
+  const float* ascale; long long as_is; int as_stride; int k_real;  // unpadded K (for flop counts)
   const void* W;       int ldw;  int wscale_block;
   const float* wscale;
   const float* bias;
   float* C;            long long c_is;  int ldc;  int act;   // act: 0 none, 1 tanh-GELU
-  int M, N, K, pad2_;
+  const float* add;    long long add_is;                     // row stride ldc; may be null
+  float* aux;          long long aux_is;                     // row stride ldc; may be null
+  const float* aux_sub;                                      // instance-independent, row stride ldc; may be null
+  int M, N, K, pad_;
 };
-// For the fp32 GEMM the same struct is used with A = float [M][lda], W = float
+// For the fp32 GEMM the same struct is used with A = float [..][lda], W = float
 // [K][ldw] (row-major, K rows), ascale / wscale unused (null).
 
 struct CombineSrc {
@@ -54,6 +62,20 @@ struct CombineDesc {
   float* run_out;      long long run_out_is;
   const float* bias;   // [d] or null
   int src_begin, n_src;
+};
+
+// Fused output projection + stream update of one layer (see oproj.hip).
+struct HeadAux { float* dst; long long dst_is; const float* sub; };   // per head: dst = out_h - sub (sub may be null)
+struct OprojDesc {
+  const uint8_t* zc;  long long zc_is;      // attention outputs, codes [inst][rpi][H][Kh]
+  const float* zs;    long long zs_is;      // their scales [inst][rpi][H]
+  const uint8_t* W;   const float* ws;      // W_O codes [H][N][Kh], scales [H]
+  const float* extra; long long extra_is;   // fp32 head's output [inst][rpi][N] or null
+  const float* run_in; long long run_in_is;
+  float* run_out;      long long run_out_is;
+  const float* bias;                        // [N] or null
+  int H, Kh, skip_head, rpi;                // skip_head: the fp32 head (or -1)
+  int M, N, aux_begin, pad_;                // M = rows over all instances; aux_begin: first of H HeadAux, or -1
 };
 
 // ---- launchers ---------------------------------------------------------------
@@ -87,9 +109,12 @@ hipError_t launch_tile_sub(float* out, const float* a, const float* b, long long
 
 // exact = 0: FP8 matrix-core instruction; exact = 1: codes decoded to fp16, fp16 matrix cores (exact
 // products, fp32 sums).
-hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int n_inst, int max_M, int max_N, int exact,
+// big = 1 selects the 256 x 128 tile (for N >= 128 and many rows), else 128 x 64.
+hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, int big,
                            hipStream_t s);
-hipError_t launch_gemm_f32(const GemmProb* probs, int n_probs, int n_inst, int max_M, int max_N, hipStream_t s);
+hipError_t launch_gemm_f32(const GemmProb* probs, int n_probs, int max_M, int max_N, hipStream_t s);
+hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const HeadAux* auxs, int M, int N, int exact,
+                              hipStream_t s);
 
 // Causal attention per (instance, sequence, head).  qkv row layout: [3][H][dh].
 // Heads other than f32_head: z rows quantised per head -> zcodes [inst][T][H][ldz], zscale [inst][T][H].

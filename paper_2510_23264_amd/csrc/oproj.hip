@@ -1,0 +1,206 @@
+// Output projection of all heads of a layer fused with the stream update:
+//   next[m][:] = run[m][:] + b_O + extra[m][:] + sum_h (z_h[m] W_O^h) * s_z[m][h] * s_w[h]
+// Each head is one K slab (d_head <= 128 codes, zero padded to 128) with its
+// own row and weight scale, so the MFMA result of a head is scaled and added to
+// the running total in registers; the per-head sender outputs never go to HBM
+// unless a receiver needs one (HeadAux: the head's output, optionally minus the
+// corrupted run's, is written next to the total).  `extra` carries the fp32
+// head's contribution, computed by the fp32 GEMM.
+// Tile 128 x 64, four wavefronts of 32 x 64; operands staged through LDS as in
+// the fp8 GEMM (144-byte rows), next head prefetched into registers.
+#include "kernels.h"
+#include "device_util.h"
+
+namespace pahq {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ v8h decode8_o(uint32_t w0, uint32_t w1) {
+  union { v8h h; uint32_t u[4]; v2h p[4]; } r;
+  uint32_t w[2] = {w0, w1};
+#pragma unroll
+  for (int q = 0; q < 2; q++) {
+    uint32_t x = w[q];
+    uint32_t b0 = x & 0xFFu, b1 = (x >> 8) & 0xFFu, b2 = (x >> 16) & 0xFFu, b3 = x >> 24;
+    r.u[2 * q] = (((b0 & 0x7Fu) << 7) | ((b0 & 0x80u) << 8)) | ((((b1 & 0x7Fu) << 7) | ((b1 & 0x80u) << 8)) << 16);
+    r.u[2 * q + 1] = (((b2 & 0x7Fu) << 7) | ((b2 & 0x80u) << 8)) | ((((b3 & 0x7Fu) << 7) | ((b3 & 0x80u) << 8)) << 16);
+  }
+  const v2h k256 = {(_Float16)256.0f, (_Float16)256.0f};
+#pragma unroll
+  for (int q = 0; q < 4; q++) r.p[q] = r.p[q] * k256;
+  return r.h;
+}
+
+#define LDS_ROW 144
+
+template <bool EXACT>
+__global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int di, const HeadAux* auxs) {
+  constexpr int BM = 128, BN = 64, TM = 2, TN = 4;
+  __shared__ __attribute__((aligned(16))) uint8_t sA[BM * LDS_ROW];
+  __shared__ __attribute__((aligned(16))) uint8_t sB[BN * LDS_ROW];
+  const OprojDesc D = descs[di];
+  const int mt = (D.M + BM - 1) / BM, nt = (D.N + BN - 1) / BN;
+  const int chunk = (mt * nt + 7) >> 3;
+  const int lin = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+  if (lin >= mt * nt) return;
+  const int m0 = (lin / nt) * BM, n0 = (lin % nt) * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lg = lane >> 4;
+
+  // this thread's chunks: A rows (tid>>3) + 32c, B rows (tid>>3) + 32c; 16-byte column kc
+  const int kc = tid & 7;
+  const uint8_t* pa[4];
+  const uint8_t* pb[2];
+#pragma unroll
+  for (int c = 0; c < 4; c++) {
+    int m = m0 + (tid >> 3) + 32 * c;
+    pa[c] = (m < D.M) ? D.zc + (long long)(m / D.rpi) * D.zc_is + (long long)(m % D.rpi) * D.H * D.Kh + kc * 16 : nullptr;
+  }
+#pragma unroll
+  for (int c = 0; c < 2; c++) {
+    int n = n0 + (tid >> 3) + 32 * c;
+    pb[c] = (n < D.N) ? D.W + (long long)n * D.Kh + kc * 16 : nullptr;
+  }
+  uint4 ra[4], rb[2];
+  auto load_head = [&](int h) {
+#pragma unroll
+    for (int c = 0; c < 4; c++) ra[c] = pa[c] ? *(const uint4*)(pa[c] + (long long)h * D.Kh) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int c = 0; c < 2; c++) rb[c] = pb[c] ? *(const uint4*)(pb[c] + (long long)h * D.N * D.Kh) : make_uint4(0, 0, 0, 0);
+  };
+  auto next_head = [&](int h) { h++; if (h == D.skip_head) h++; return h; };
+
+  // rows of this lane's results and their scale pointers
+  int row_m[TM][4];
+  const float* zs_p[TM][4];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      int m = m0 + wave * 32 + i * 16 + lg * 4 + r;
+      row_m[i][r] = m;
+      int mm = m < D.M ? m : D.M - 1;
+      zs_p[i][r] = D.zs + (long long)(mm / D.rpi) * D.zs_is + (long long)(mm % D.rpi) * D.H;
+    }
+
+  v4f tot[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++) tot[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+  int h = (D.skip_head == 0) ? 1 : 0;
+  if (h < D.H) load_head(h);
+  for (; h < D.H; h = next_head(h)) {
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 4; c++) *(uint4*)(sA + ((tid >> 3) + 32 * c) * LDS_ROW + kc * 16) = ra[c];
+#pragma unroll
+    for (int c = 0; c < 2; c++) *(uint4*)(sB + ((tid >> 3) + 32 * c) * LDS_ROW + kc * 16) = rb[c];
+    __syncthreads();
+    int hn = next_head(h);
+    if (hn < D.H) load_head(hn);
+
+    v4f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+    if (EXACT) {
+#pragma unroll
+      for (int kk = 0; kk < 4; kk++) {
+        v8h ha[TM];
+#pragma unroll
+        for (int i = 0; i < TM; i++) {
+          uint2 w = *(const uint2*)(sA + (wave * 32 + i * 16 + li) * LDS_ROW + kk * 32 + lg * 8);
+          ha[i] = decode8_o(w.x, w.y);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; j++) {
+          uint2 w = *(const uint2*)(sB + (j * 16 + li) * LDS_ROW + kk * 32 + lg * 8);
+          v8h hb = decode8_o(w.x, w.y);
+#pragma unroll
+          for (int i = 0; i < TM; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ha[i], hb, acc[i][j], 0, 0, 0);
+        }
+      }
+    } else {
+      v8i fa[TM];
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        const uint8_t* p = sA + (wave * 32 + i * 16 + li) * LDS_ROW + lg * 32;
+        uint4 lo = *(const uint4*)p, hi = *(const uint4*)(p + 16);
+        fa[i] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+      }
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        const uint8_t* p = sB + (j * 16 + li) * LDS_ROW + lg * 32;
+        uint4 lo = *(const uint4*)p, hi = *(const uint4*)(p + 16);
+        v8i fb = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+#pragma unroll
+        for (int i = 0; i < TM; i++)
+          acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fa[i], fb, acc[i][j], 0, 0, 0, 0x7F7F7F7F, 0,
+                                                                       0x7F7F7F7F);
+      }
+    }
+    // scale this head's result, add it to the total, and hand it out if some receiver needs it
+    const float sw = D.ws[h];
+    HeadAux ax; ax.dst = nullptr; ax.dst_is = 0; ax.sub = nullptr;
+    if (D.aux_begin >= 0) ax = auxs[D.aux_begin + h];
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        float sc = zs_p[i][r][h] * sw;
+        int m = row_m[i][r];
+#pragma unroll
+        for (int j = 0; j < TN; j++) {
+          float val = acc[i][j][r] * sc;
+          tot[i][j][r] += val;
+          if (ax.dst) {
+            int n = n0 + j * 16 + li;
+            if (m < D.M && n < D.N) {
+              long long off = (long long)(m % D.rpi) * D.N + n;
+              float x = val;
+              if (ax.sub) x -= ax.sub[off];
+              ax.dst[(long long)(m / D.rpi) * ax.dst_is + off] = x;
+            }
+          }
+        }
+      }
+  }
+
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      int m = row_m[i][r];
+      if (m >= D.M) continue;
+      int inst = m / D.rpi;
+      long long roff = (long long)(m % D.rpi) * D.N;
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        int n = n0 + j * 16 + li;
+        if (n >= D.N) continue;
+        float v = D.run_in[inst * D.run_in_is + roff + n];
+        if (D.bias) v += D.bias[n];
+        if (D.extra) v += D.extra[inst * D.extra_is + roff + n];
+        v += tot[i][j][r];
+        D.run_out[inst * D.run_out_is + roff + n] = v;
+      }
+    }
+}
+
+hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const HeadAux* auxs, int M, int N, int exact,
+                              hipStream_t s) {
+  if (M == 0) return hipSuccess;
+  int tiles = ((M + 127) / 128) * ((N + 63) / 64);
+  dim3 grid((tiles + 7) / 8 * 8);
+  if (exact) hipLaunchKernelGGL(oproj_fused_k<true>, grid, dim3(256), 0, s, descs, desc_index, auxs);
+  else hipLaunchKernelGGL(oproj_fused_k<false>, grid, dim3(256), 0, s, descs, desc_index, auxs);
+  return hipGetLastError();
+}
+
+}  // namespace pahq

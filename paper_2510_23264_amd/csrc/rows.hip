@@ -206,6 +206,27 @@ __global__ __launch_bounds__(256) void patch_build_k(const GroupDesc* gp, const 
   }
 }
 
+// Independent candidates (x_i = xv - delta[send[i]]): one wavefront per (row, instance).
+template <int MAXE>
+__global__ __launch_bounds__(256) void patch_indep_k(const GroupDesc* gp, const float* xv, const float* delta0,
+                                                      long long delta_stride, const int* send, int T, int B, int S,
+                                                      int d, int ldq, int norm_kind, float eps) {
+  GroupDesc g = *gp;
+  int lane = threadIdx.x & 63;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int inst = blockIdx.y;
+  int rows = g.last_only ? B : T;
+  if (row >= rows) return;
+  long long src = (long long)(g.last_only ? row * S + S - 1 : row) * d;
+  int E = d >> 6;
+  const float* dp = delta0 + (long long)send[inst] * delta_stride + src;
+  float y[MAXE];
+#pragma unroll
+  for (int j = 0; j < MAXE; j++) y[j] = (j < E) ? xv[src + lane + 64 * j] - dp[lane + 64 * j] : 0.f;
+  norm_row<MAXE>(y, E, d, lane, norm_kind, eps, g.gain, g.offset);
+  emit_row<MAXE>(y, E, d, lane, g, inst, row, ldq);
+}
+
 #define PAHQ_DISPATCH_E(E, CALL)                                    \
   do {                                                              \
     if ((E) <= 1) { CALL(1); }                                      \
@@ -231,6 +252,13 @@ hipError_t launch_patch_build(const GroupDesc* g, const float* xv, const float* 
                               const int* send, int n_inst, int mode, int T, int B, int S, int d, int ldq,
                               int norm_kind, float eps, hipStream_t s) {
   if (n_inst == 0) return hipSuccess;
+  if (mode == 1) {
+    dim3 grid2((T + 3) / 4, n_inst);
+#define CALL(M) hipLaunchKernelGGL(patch_indep_k<M>, grid2, dim3(256), 0, s, g, xv, delta0, delta_stride, send, T, B, S, d, ldq, norm_kind, eps)
+    PAHQ_DISPATCH_E(d / 64, CALL);
+#undef CALL
+    return hipGetLastError();
+  }
   dim3 grid((T + 3) / 4);
 #define CALL(M) hipLaunchKernelGGL(patch_build_k<M>, grid, dim3(256), 0, s, g, xv, delta0, delta_stride, send, n_inst, mode, T, B, S, d, ldq, norm_kind, eps)
   PAHQ_DISPATCH_E(d / 64, CALL);
