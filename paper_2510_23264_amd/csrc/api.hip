@@ -55,6 +55,7 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
   M->B = B; M->S = S; M->T = B * S; M->L = c->n_layers; M->H = c->n_heads; M->dh = c->d_head;
   M->d = c->d_model; M->m = c->d_mlp; M->V = c->vocab;
   M->Kd = pad128(M->d); M->Kh = pad128(M->dh); M->Km = pad128(M->m > 0 ? M->m : 1);
+  M->Vp = (M->V + 3) / 4 * 4;
   M->nmax = c->max_batch_edges; M->G = 3 * M->H + 1;
   M->tile = (long long)M->T * M->d;
 }
@@ -71,7 +72,7 @@ size_t arena_slot_bytes(const pahq_model* M) {
 size_t layout(pahq_model* M, char* base) {
   Bump b{base, 0};
   const size_t L = M->L, H = M->H, dh = M->dh, d = M->d, m = M->m, V = M->V, T = M->T, B = M->B;
-  const size_t Kd = M->Kd, Kh = M->Kh, Km = M->Km, n = M->nmax, G = M->G, Ns = M->g.Ns, tile = M->tile;
+  const size_t Kd = M->Kd, Kh = M->Kh, Km = M->Km, n = M->nmax, G = M->G, Ns = M->g.Ns, tile = M->tile, Vp = M->Vp;
   const bool mlp = m > 0, swi = M->cfg.act == PAHQ_ACT_SWIGLU, learned = M->cfg.pos == PAHQ_POS_LEARNED;
   M->W_E = b.take<float>(V * d);
   M->W_pos = learned ? b.take<float>((size_t)M->cfg.n_ctx * d) : nullptr;
@@ -99,9 +100,9 @@ size_t layout(pahq_model* M, char* base) {
   M->tok_clean = b.take<int>(T); M->tok_corrupt = b.take<int>(T); M->send_dev = b.take<int>(n);
   M->clean = b.take<float>(Ns * tile); M->corrupt = b.take<float>(Ns * tile); M->delta = b.take<float>((Ns + 1) * tile);   // tile Ns stays zero
   M->rc = b.take<float>((2 * L + 1) * tile); M->rx = b.take<float>((2 * L + 1) * tile);
-  M->logits_clean = b.take<float>(B * V); M->logits_corrupt = b.take<float>(B * V); M->logz_clean = b.take<double>(B);
+  M->logits_clean = b.take<float>(B * Vp); M->logits_corrupt = b.take<float>(B * Vp); M->logz_clean = b.take<double>(B);
   M->cpi = b.take<float>(Ns * tile); M->rxpi = b.take<float>((2 * L + 1) * tile);
-  M->ref_logits = b.take<float>(B * V); M->ref_logz = b.take<double>(B);
+  M->ref_logits = b.take<float>(B * Vp); M->ref_logz = b.take<double>(B);
   M->xv = b.take<float>(tile);
   M->run_a = b.take<float>(n * tile); M->run_b = b.take<float>(n * tile);
   M->xcodes = b.take<uint8_t>(n * G * T * Kd); M->xscale = b.take<float>(n * G * T); M->xf32 = b.take<float>(n * 3 * tile);
@@ -111,7 +112,7 @@ size_t layout(pahq_model* M, char* base) {
   M->mlpout = mlp ? b.take<float>(n * tile) : nullptr;
   M->hid = mlp ? b.take<float>(n * T * m) : nullptr; M->hid2 = (mlp && swi) ? b.take<float>(n * T * m) : nullptr;
   M->hcodes = mlp ? b.take<uint8_t>(n * T * Km) : nullptr; M->hscale = mlp ? b.take<float>(n * T) : nullptr;
-  M->lastcodes = b.take<uint8_t>(n * B * Kd); M->lastscale = b.take<float>(n * B); M->logits = b.take<float>(n * B * V);
+  M->lastcodes = b.take<uint8_t>(n * B * Kd); M->lastscale = b.take<float>(n * B); M->logits = b.take<float>(n * B * Vp);
   M->pool_tiles = (long long)std::max<size_t>(2 * Ns, 4 * n);
   M->slots = b.take<float>((size_t)M->pool_tiles * tile);
   M->row_kl = b.take<double>(n * B); M->kl_dev = b.take<double>(n);
@@ -546,7 +547,7 @@ int pahq_quantize_rows(pahq_model* M, const float* x, int32_t rows, int32_t cols
   if (!M || !x || !codes || !scales || rows < 0 || cols < 1 || cols > 16384) return PAHQ_EINVAL;
   if (rows == 0) return PAHQ_OK;
   // staged through the candidate buffers: fp32 rows in `logits`, codes in `xcodes`, scales in `xscale`
-  size_t cap_f = (size_t)M->nmax * M->B * M->V, cap_c = (size_t)M->nmax * M->G * M->T * M->Kd, cap_s = (size_t)M->nmax * M->G * M->T;
+  size_t cap_f = (size_t)M->nmax * M->B * M->Vp, cap_c = (size_t)M->nmax * M->G * M->T * M->Kd, cap_s = (size_t)M->nmax * M->G * M->T;
   size_t chunk = std::min(std::min(cap_f / cols, cap_c / cols), cap_s);
   if (chunk < 1) return PAHQ_ENOMEM;
   for (size_t r0 = 0; r0 < (size_t)rows; r0 += chunk) {
@@ -568,7 +569,8 @@ int pahq_get_logits(pahq_model* M, int32_t which, float* out) {
   if (!M || !out || (which != PAHQ_LOGITS_CLEAN && which != PAHQ_LOGITS_CORRUPT)) return PAHQ_EINVAL;
   if (!M->has_cache) return PAHQ_ESTATE;
   const float* src = which == PAHQ_LOGITS_CLEAN ? M->logits_clean : M->logits_corrupt;
-  HIPCHK(hipMemcpyAsync(out, src, (size_t)M->B * M->V * sizeof(float), hipMemcpyDeviceToHost, M->stream));
+  HIPCHK(hipMemcpy2DAsync(out, (size_t)M->V * sizeof(float), src, (size_t)M->Vp * sizeof(float), (size_t)M->V * sizeof(float),
+                          M->B, hipMemcpyDeviceToHost, M->stream));
   HIPCHK(hipStreamSynchronize(M->stream));
   return PAHQ_OK;
 }

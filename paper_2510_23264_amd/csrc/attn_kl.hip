@@ -203,24 +203,46 @@ __device__ __forceinline__ float block_max_f(float v, float* red) {
   return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
+// log-sum-exp of one row in a single sweep: every thread keeps a running maximum
+// and a sum rescaled to it; the partial (max, sum) pairs are merged in a fixed order.
 __device__ __forceinline__ double row_logz(const float* x, int V, float* redf, double* redd) {
   float mx = -3.0e38f;
-  for (int i = threadIdx.x; i < V; i += 256) mx = fmaxf(mx, x[i]);
-  mx = block_max_f(mx, redf);
-  double s = 0.0;
-  for (int i = threadIdx.x; i < V; i += 256) s += (double)expf(x[i] - mx);
-  s = block_sum_d(s, redd);
-  return (double)mx + log(s);
+  float s = 0.f;
+  int i = threadIdx.x * 4;
+  if ((((uintptr_t)x) & 15) == 0) {
+    for (; i + 3 < V; i += 1024) {
+      float4 v = *(const float4*)(x + i);
+      float m4 = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
+      if (m4 > mx) { s *= expf(mx - m4); mx = m4; }
+      s += expf(v.x - mx) + expf(v.y - mx) + expf(v.z - mx) + expf(v.w - mx);
+    }
+  }
+  for (int e = i; e < V && e < i + 4; e++) {           // ragged tail of the strided sweep (or unaligned rows)
+    float v = x[e];
+    if (v > mx) { s *= expf(mx - v); mx = v; }
+    s += expf(v - mx);
+  }
+  if ((((uintptr_t)x) & 15) != 0)
+    for (int e = i + 1024; e < V; e += 1024)
+      for (int q = e; q < V && q < e + 4; q++) {
+        float v = x[q];
+        if (v > mx) { s *= expf(mx - v); mx = v; }
+        s += expf(v - mx);
+      }
+  float gm = block_max_f(mx, redf);
+  double sd = (double)s * (double)expf(mx - gm);
+  sd = block_sum_d(sd, redd);
+  return (double)gm + log(sd);
 }
 
-__global__ __launch_bounds__(256) void logz_k(const float* logits, int V, double* logz) {
+__global__ __launch_bounds__(256) void logz_k(const float* logits, int V, int ldv, double* logz) {
   __shared__ float redf[4];
   __shared__ double redd[4];
-  double z = row_logz(logits + (long long)blockIdx.x * V, V, redf, redd);
+  double z = row_logz(logits + (long long)blockIdx.x * ldv, V, redf, redd);
   if (threadIdx.x == 0) logz[blockIdx.x] = z;
 }
-hipError_t launch_logz(const float* logits, int rows, int V, double* logz, hipStream_t s) {
-  hipLaunchKernelGGL(logz_k, dim3(rows), dim3(256), 0, s, logits, V, logz);
+hipError_t launch_logz(const float* logits, int rows, int V, int ldv, double* logz, hipStream_t s) {
+  hipLaunchKernelGGL(logz_k, dim3(rows), dim3(256), 0, s, logits, V, ldv, logz);
   return hipGetLastError();
 }
 
@@ -228,21 +250,38 @@ hipError_t launch_logz(const float* logits, int rows, int V, double* logz, hipSt
 // Differences of logits (O(1) numbers) are taken before anything of the size
 // of log V enters, and the sums run in fp64, so identical logits give exactly 0.
 __global__ __launch_bounds__(256) void kl_rows_k(const float* logits, long long l_is, const float* ref_logits,
-                                                  const double* ref_logz, double* row_kl, int B, int V) {
+                                                  const double* ref_logz, double* row_kl, int B, int V, int ldv) {
   __shared__ float redf[4];
   __shared__ double redd[4];
   int b = blockIdx.x, inst = blockIdx.y;
-  const float* x = logits + inst * l_is + (long long)b * V;
-  const float* xr = ref_logits + (long long)b * V;
+  const float* x = logits + inst * l_is + (long long)b * ldv;
+  const float* xr = ref_logits + (long long)b * ldv;
   double lz = row_logz(x, V, redf, redd);
   double lzr = ref_logz[b];
   float lzr_f = (float)lzr;
   double a = 0.0, psum = 0.0;
-  for (int i = threadIdx.x; i < V; i += 256) {
-    float r = xr[i];
-    double p = (double)expf(r - lzr_f);
-    a += p * (double)(r - x[i]);
-    psum += p;
+  if (((((uintptr_t)x) | ((uintptr_t)xr)) & 15) == 0) {
+    int i = threadIdx.x * 4;
+    for (; i + 3 < V; i += 1024) {
+      float4 r = *(const float4*)(xr + i), c = *(const float4*)(x + i);
+      float p0 = expf(r.x - lzr_f), p1 = expf(r.y - lzr_f), p2 = expf(r.z - lzr_f), p3 = expf(r.w - lzr_f);
+      a += (double)p0 * (double)(r.x - c.x) + (double)p1 * (double)(r.y - c.y) + (double)p2 * (double)(r.z - c.z) +
+           (double)p3 * (double)(r.w - c.w);
+      psum += (double)p0 + (double)p1 + (double)p2 + (double)p3;
+    }
+    for (int e = i; e < V && e < i + 4; e++) {
+      float r = xr[e];
+      double p = (double)expf(r - lzr_f);
+      a += p * (double)(r - x[e]);
+      psum += p;
+    }
+  } else {
+    for (int i = threadIdx.x; i < V; i += 256) {
+      float r = xr[i];
+      double p = (double)expf(r - lzr_f);
+      a += p * (double)(r - x[i]);
+      psum += p;
+    }
   }
   a = block_sum_d(a, redd);
   psum = block_sum_d(psum, redd);
@@ -256,9 +295,9 @@ __global__ void kl_mean_k(const double* row_kl, double* kl, int n_inst, int B) {
   kl[i] = s / (double)B;
 }
 hipError_t launch_kl(const float* logits, long long l_is, const float* ref_logits, const double* ref_logz,
-                     double* row_kl, double* kl, int n_inst, int B, int V, hipStream_t s) {
+                     double* row_kl, double* kl, int n_inst, int B, int V, int ldv, hipStream_t s) {
   if (n_inst == 0) return hipSuccess;
-  hipLaunchKernelGGL(kl_rows_k, dim3(B, n_inst), dim3(256), 0, s, logits, l_is, ref_logits, ref_logz, row_kl, B, V);
+  hipLaunchKernelGGL(kl_rows_k, dim3(B, n_inst), dim3(256), 0, s, logits, l_is, ref_logits, ref_logz, row_kl, B, V, ldv);
   hipLaunchKernelGGL(kl_mean_k, dim3((n_inst + 63) / 64), dim3(64), 0, s, row_kl, kl, n_inst, B);
   return hipGetLastError();
 }

@@ -49,6 +49,7 @@ struct pahq_model {
   pahq::GraphDims g;
   int B, S, T, L, H, dh, d, m, V;
   int Kd, Kh, Km;        // K extents padded to multiples of 128
+  int Vp;                // row stride of logits buffers (vocab rounded up to 4 floats)
   int nmax, G;           // max instances; max groups per layer (3H + 1)
   long long tile;        // T * d
   hipStream_t stream;

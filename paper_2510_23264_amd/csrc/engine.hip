@@ -340,7 +340,7 @@ struct Builder {
 
   void final_block(Stream run) {
     const GraphDims& g = M->g;
-    const int d = M->d, B = M->B, Kd = M->Kd, V = M->V;
+    const int d = M->d, B = M->B, Kd = M->Kd, V = M->V, Vp = M->Vp;
     if (a.kind == PI_CORRUPT) return;           // only the sender outputs are needed
     int w = g.out();
     GroupDesc gd; memset(&gd, 0, sizeof(gd));
@@ -358,11 +358,11 @@ struct Builder {
       case BASE_CLEAN: lg = M->logits_clean; break;
       case BASE_CORRUPT: lg = M->logits_corrupt; break;
       case PI_REF: lg = M->ref_logits; break;
-      default: lg = M->logits; lg_is = (long long)B * V; break;
+      default: lg = M->logits; lg_is = (long long)B * Vp; break;
     }
     int pb = (int)probs.size();
     probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1, M->u_codes, Kd,
-                          M->u_scale, V, M->b_U, lg, lg_is, V, 0, B, V, Kd, d));
+                          M->u_scale, V, M->b_U, lg, lg_is, Vp, 0, B, V, Kd, d));
     add_op(OP_GEMM8, pb, 1, B * a.n, V); work_gemm(pb);
     if (a.kind == BASE_CLEAN) add_op(OP_LOGZ, 0, 0, 0, 0, M->logits_clean, M->logz_clean);
     else if (a.kind == PI_REF) add_op(OP_LOGZ, 0, 0, 0, 0, M->ref_logits, M->ref_logz);
@@ -477,10 +477,10 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         HIPCHK(launch_hidden_quant(M->hid, o.i0 ? M->hid2 : nullptr, (long long)T * M->m, M->hcodes, (long long)T * M->Km,
                                    M->hscale, T, n, T, M->m, M->Km, o.i0, st));
         break;
-      case OP_LOGZ: HIPCHK(launch_logz((const float*)o.p0, B, M->V, (double*)o.p1, st)); break;
+      case OP_LOGZ: HIPCHK(launch_logz((const float*)o.p0, B, M->V, M->Vp, (double*)o.p1, st)); break;
       case OP_KL:
-        HIPCHK(launch_kl(M->logits, (long long)B * M->V, (const float*)o.p0, (const double*)o.p1, M->row_kl, M->kl_dev,
-                         n, B, M->V, st));
+        HIPCHK(launch_kl(M->logits, (long long)B * M->Vp, (const float*)o.p0, (const double*)o.p1, M->row_kl, M->kl_dev,
+                         n, B, M->V, M->Vp, st));
         break;
     }
     if (pair >= 0) HIPCHK(hipEventRecord(M->prof_ev[2 * pair + 1], st));

@@ -63,7 +63,7 @@ __device__ __forceinline__ int xcd_tile(int wg, int total) {
 // The epilogue for one result element block of a lane: rows m (4 consecutive), column n.
 __device__ __forceinline__ void epilogue_store(const GemmProb& P, int m, int n, float acc, float sa, float sw, int inst,
                                                int r) {
-  float val = acc * sa * sw;
+  float val = acc * (sa * sw);
   float v = val;
   if (P.bias) v += P.bias[n];
   if (P.act == 1) v = gelu_tanh(v);
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_k(const GemmPr
           v8h hb = decode8(w.x, w.y);
 #pragma unroll
           for (int i = 0; i < TM; i++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ha[i], hb, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb, ha[i], acc[i][j], 0, 0, 0);
         }
       }
       continue;
@@ -184,24 +184,43 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_k(const GemmPr
       v8i fb = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
 #pragma unroll
       for (int i = 0; i < TM; i++)
-        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fa[i], fb, acc[i][j], 0, 0, 0, 0x7F7F7F7F, 0,
+        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb, fa[i], acc[i][j], 0, 0, 0, 0x7F7F7F7F, 0,
                                                                      0x7F7F7F7F);
     }
   }
 
+  // W is fed as the first MFMA operand, so the accumulators hold the transposed tile: lane
+  // (i, g) owns row i of a 16-row tile and the four consecutive columns 4g .. 4g+3 -> 16-byte stores.
+  const bool vec = ((P.ldc & 3) == 0) && ((P.wscale_block & 3) == 0) && (((P.c_is | P.add_is | P.aux_is) & 3) == 0) &&
+                   ((((uintptr_t)P.C | (uintptr_t)P.add | (uintptr_t)P.aux | (uintptr_t)P.aux_sub | (uintptr_t)P.bias) & 15) == 0);
 #pragma unroll
   for (int i = 0; i < TM; i++) {
+    int m = m0 + wm * WM + i * 16 + li;
+    if (m >= P.M) continue;
+    int inst = m / P.rpi, row = m % P.rpi;
+    float sa = P.ascale[inst * P.as_is + (long long)row * P.as_stride];
 #pragma unroll
-    for (int r = 0; r < 4; r++) {
-      int m = m0 + wm * WM + i * 16 + lg * 4 + r;
-      if (m >= P.M) continue;
-      int inst = m / P.rpi, row = m % P.rpi;
-      float sa = P.ascale[inst * P.as_is + (long long)row * P.as_stride];
+    for (int j = 0; j < TN; j++) {
+      int nb = n0 + wn * WN + j * 16 + lg * 4;
+      if (nb >= P.N) continue;
+      if (vec && nb + 3 < P.N) {
+        float s2 = sa * P.wscale[nb / P.wscale_block];
+        float4 val = make_float4(acc[i][j][0] * s2, acc[i][j][1] * s2, acc[i][j][2] * s2, acc[i][j][3] * s2);
+        float4 v = val;
+        if (P.bias) { float4 b = *(const float4*)(P.bias + nb); v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w; }
+        if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
+        long long off = (long long)row * P.ldc + nb;
+        if (P.add) { float4 a = *(const float4*)(P.add + inst * P.add_is + off); v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w; }
+        *(float4*)(P.C + inst * P.c_is + off) = v;
+        if (P.aux) {
+          if (P.aux_sub) { float4 u = *(const float4*)(P.aux_sub + off); val.x -= u.x; val.y -= u.y; val.z -= u.z; val.w -= u.w; }
+          *(float4*)(P.aux + inst * P.aux_is + off) = val;
+        }
+      } else {
 #pragma unroll
-      for (int j = 0; j < TN; j++) {
-        int n = n0 + wn * WN + j * 16 + li;
-        if (n >= P.N) continue;
-        epilogue_store(P, m, n, acc[i][j][r], sa, P.wscale[n / P.wscale_block], inst, row);
+        for (int r = 0; r < 4; r++)
+          if (nb + r < P.N)
+            epilogue_store(P, m, nb + r, acc[i][j][r], sa, P.wscale[(nb + r) / P.wscale_block], inst, row);
       }
     }
   }

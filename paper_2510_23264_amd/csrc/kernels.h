@@ -132,10 +132,10 @@ hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_i
                                hipStream_t s);
 
 // logz[b] = log(sum_v exp(logits[b][v]))  (double)
-hipError_t launch_logz(const float* logits, int rows, int V, double* logz, hipStream_t s);
+hipError_t launch_logz(const float* logits, int rows, int V, int ldv, double* logz, hipStream_t s);
 // kl[inst] = mean_b sum_v p_ref (log p_ref - log p_inst)
 hipError_t launch_kl(const float* logits, long long l_is, const float* ref_logits, const double* ref_logz,
-                     double* row_kl, double* kl, int n_inst, int B, int V, hipStream_t s);
+                     double* row_kl, double* kl, int n_inst, int B, int V, int ldv, hipStream_t s);
 
 hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales,
                                    hipStream_t s);

@@ -73,18 +73,16 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
   };
   auto next_head = [&](int h) { h++; if (h == D.skip_head) h++; return h; };
 
-  // rows of this lane's results and their scale pointers
-  int row_m[TM][4];
-  const float* zs_p[TM][4];
+  // W is the first MFMA operand, so lane (i, g) owns row i of a 16-row tile and columns 4g .. 4g+3
+  int row_m[TM];
+  const float* zs_p[TM];
 #pragma unroll
-  for (int i = 0; i < TM; i++)
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-      int m = m0 + wave * 32 + i * 16 + lg * 4 + r;
-      row_m[i][r] = m;
-      int mm = m < D.M ? m : D.M - 1;
-      zs_p[i][r] = D.zs + (long long)(mm / D.rpi) * D.zs_is + (long long)(mm % D.rpi) * D.H;
-    }
+  for (int i = 0; i < TM; i++) {
+    int m = m0 + wave * 32 + i * 16 + li;
+    row_m[i] = m;
+    int mm = m < D.M ? m : D.M - 1;
+    zs_p[i] = D.zs + (long long)(mm / D.rpi) * D.zs_is + (long long)(mm % D.rpi) * D.H;
+  }
 
   v4f tot[TM][TN];
 #pragma unroll
@@ -123,7 +121,7 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
           uint2 w = *(const uint2*)(sB + (j * 16 + li) * LDS_ROW + kk * 32 + lg * 8);
           v8h hb = decode8_o(w.x, w.y);
 #pragma unroll
-          for (int i = 0; i < TM; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ha[i], hb, acc[i][j], 0, 0, 0);
+          for (int i = 0; i < TM; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb, ha[i], acc[i][j], 0, 0, 0);
         }
       }
     } else {
@@ -141,7 +139,7 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
         v8i fb = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
 #pragma unroll
         for (int i = 0; i < TM; i++)
-          acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fa[i], fb, acc[i][j], 0, 0, 0, 0x7F7F7F7F, 0,
+          acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb, fa[i], acc[i][j], 0, 0, 0, 0x7F7F7F7F, 0,
                                                                        0x7F7F7F7F);
       }
     }
@@ -150,47 +148,42 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
     HeadAux ax; ax.dst = nullptr; ax.dst_is = 0; ax.sub = nullptr;
     if (D.aux_begin >= 0) ax = auxs[D.aux_begin + h];
 #pragma unroll
-    for (int i = 0; i < TM; i++)
+    for (int i = 0; i < TM; i++) {
+      float sc = zs_p[i][h] * sw;
+      int m = row_m[i];
 #pragma unroll
-      for (int r = 0; r < 4; r++) {
-        float sc = zs_p[i][r][h] * sw;
-        int m = row_m[i][r];
-#pragma unroll
-        for (int j = 0; j < TN; j++) {
-          float val = acc[i][j][r] * sc;
-          tot[i][j][r] += val;
-          if (ax.dst) {
-            int n = n0 + j * 16 + li;
-            if (m < D.M && n < D.N) {
-              long long off = (long long)(m % D.rpi) * D.N + n;
-              float x = val;
-              if (ax.sub) x -= ax.sub[off];
-              ax.dst[(long long)(m / D.rpi) * ax.dst_is + off] = x;
-            }
+      for (int j = 0; j < TN; j++) {
+        float4 val = make_float4(acc[i][j][0] * sc, acc[i][j][1] * sc, acc[i][j][2] * sc, acc[i][j][3] * sc);
+        tot[i][j][0] += val.x; tot[i][j][1] += val.y; tot[i][j][2] += val.z; tot[i][j][3] += val.w;
+        if (ax.dst) {
+          int nb = n0 + j * 16 + lg * 4;
+          if (m < D.M && nb < D.N) {
+            long long off = (long long)(m % D.rpi) * D.N + nb;
+            if (ax.sub) { float4 u = *(const float4*)(ax.sub + off); val.x -= u.x; val.y -= u.y; val.z -= u.z; val.w -= u.w; }
+            *(float4*)(ax.dst + (long long)(m / D.rpi) * ax.dst_is + off) = val;
           }
         }
       }
+    }
   }
 
 #pragma unroll
-  for (int i = 0; i < TM; i++)
+  for (int i = 0; i < TM; i++) {
+    int m = row_m[i];
+    if (m >= D.M) continue;
+    int inst = m / D.rpi;
+    long long roff = (long long)(m % D.rpi) * D.N;
 #pragma unroll
-    for (int r = 0; r < 4; r++) {
-      int m = row_m[i][r];
-      if (m >= D.M) continue;
-      int inst = m / D.rpi;
-      long long roff = (long long)(m % D.rpi) * D.N;
-#pragma unroll
-      for (int j = 0; j < TN; j++) {
-        int n = n0 + j * 16 + li;
-        if (n >= D.N) continue;
-        float v = D.run_in[inst * D.run_in_is + roff + n];
-        if (D.bias) v += D.bias[n];
-        if (D.extra) v += D.extra[inst * D.extra_is + roff + n];
-        v += tot[i][j][r];
-        D.run_out[inst * D.run_out_is + roff + n] = v;
-      }
+    for (int j = 0; j < TN; j++) {
+      int nb = n0 + j * 16 + lg * 4;
+      if (nb >= D.N) continue;
+      float4 v = *(const float4*)(D.run_in + inst * D.run_in_is + roff + nb);
+      if (D.bias) { float4 b = *(const float4*)(D.bias + nb); v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w; }
+      if (D.extra) { float4 e = *(const float4*)(D.extra + inst * D.extra_is + roff + nb); v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w; }
+      v.x += tot[i][j][0]; v.y += tot[i][j][1]; v.z += tot[i][j][2]; v.w += tot[i][j][3];
+      *(float4*)(D.run_out + inst * D.run_out_is + roff + nb) = v;
     }
+  }
 }
 
 hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const HeadAux* auxs, int M, int N, int exact,
