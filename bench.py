@@ -32,9 +32,9 @@ PEAKS = {"gemm_fp8": ("mfma", 5000.0, "TFLOP/s"), "oproj_fused": ("mfma", 5000.0
 HBM_PEAK = 8000.0  # GB/s
 
 
-def all_edges_pass(gm, P, cfg, n_recv):
+def all_edges_pass(gm, P, cfg, n_recv, stride=1):
     n = 0
-    for r in range(n_recv - 1, -1, -1):
+    for r in range(n_recv - 1, -1, -stride):
         senders = np.arange(P.n_upstream(cfg, r), dtype=np.int32)
         gm.eval_edges(r, senders)
         n += senders.size
@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--mma", type=int, default=0, help="0 FP8 matrix cores, 1 fp16 matrix cores on decoded codes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--recv-stride", type=int, default=1,
+                    help="evaluate only every k-th receiver (short runs under a profiler; the headline uses 1)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -101,13 +103,13 @@ def main():
     gm.clean_cache(clean, corrupt)
 
     for _ in range(args.warmup):
-        all_edges_pass(gm, P, cfg, n_recv)
+        all_edges_pass(gm, P, cfg, n_recv, args.recv_stride)
     torch.cuda.synchronize()
     gm.set_profiling(True)
     t0 = time.perf_counter()
     n_evals = 0
     for _ in range(args.steps):
-        n_evals += all_edges_pass(gm, P, cfg, n_recv)
+        n_evals += all_edges_pass(gm, P, cfg, n_recv, args.recv_stride)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = gm.get_profile()
@@ -155,7 +157,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.config}: every edge of the split-QKV graph ({gm.n_edges} edges) evaluated once "
                                f"at the empty removed set, PAHQ precision (fp32 investigated head)",
-                   "B": spec["B"], "S": spec["S"], "batch_edges": args.batch, "edges_per_step": n_evals // args.steps,
+                   "B": spec["B"], "S": spec["S"], "batch_edges": args.batch, "recv_stride": args.recv_stride, "edges_per_step": n_evals // args.steps,
                    "seed": spec["seed"]},
         "roofline": roofline, "kernels": kernels, "sweep": sweeps,
     }

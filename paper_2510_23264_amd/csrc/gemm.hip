@@ -244,12 +244,13 @@ hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int ma
 }
 
 // ------------------------------------------------------------------ fp32
-// 64 x 64 tile, K slabs of 16, four waves as 2 x 2, each 32 x 32 (2 x 2 MFMA tiles).
+// 64 x 64 tile, K slabs of 32, four waves as 2 x 2, each 32 x 32 (2 x 2 MFMA tiles).
 // MFMA 16x16x4 f32: A operand of lane (i, g) = A[i][g], B operand = B[g][i],
-// result lane (i, g) holds C[4g + r][i].
+// result lane (i, g) holds C[4g + r][i].  Requires K % 4 == 0 and 16-byte aligned rows
+// (true for d_model and d_head here); global loads are 16 bytes per lane.
 __global__ __launch_bounds__(256) void gemm_f32_k(const GemmProb* probs) {
-  __shared__ float sA[64][17];
-  __shared__ float sB[16][65];
+  __shared__ float sA[64][33];
+  __shared__ float sB[32][65];
   const GemmProb P = probs[blockIdx.z];
   const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
   if (m0 >= P.M || n0 >= P.N) return;
@@ -257,34 +258,52 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const GemmProb* probs) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
   const int wm = wave >> 1, wn = wave & 1;
-  const float* pa[4];
+  // A tile 64 x 32 floats = 512 float4: thread -> rows (tid >> 3) and (tid >> 3) + 32, float4 column tid & 7
+  const float* pa[2];
 #pragma unroll
-  for (int c = 0; c < 4; c++) {
-    int idx = tid + c * 256, r = idx >> 4, k = idx & 15;
-    int m = m0 + r;
-    pa[c] = (m < P.M) ? (const float*)P.A + (long long)(m / P.rpi) * P.a_is + (long long)(m % P.rpi) * P.lda + k : nullptr;
+  for (int c = 0; c < 2; c++) {
+    int m = m0 + (tid >> 3) + 32 * c;
+    pa[c] = (m < P.M) ? (const float*)P.A + (long long)(m / P.rpi) * P.a_is + (long long)(m % P.rpi) * P.lda + (tid & 7) * 4
+                      : nullptr;
   }
+  // B tile 32 x 64 floats = 512 float4: thread -> k rows (tid >> 4) and (tid >> 4) + 16, float4 column tid & 15
+  const int bn = n0 + (tid & 15) * 4;
   v4f acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; i++)
 #pragma unroll
     for (int j = 0; j < 2; j++) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-  for (int k0 = 0; k0 < P.K; k0 += 16) {
+  for (int k0 = 0; k0 < P.K; k0 += 32) {
+    float4 va[2], vb[2];
+#pragma unroll
+    for (int c = 0; c < 2; c++) {
+      int k = k0 + (tid & 7) * 4;
+      va[c] = (pa[c] && k + 3 < P.K) ? *(const float4*)(pa[c] + k0) : make_float4(0, 0, 0, 0);
+      if (pa[c] && k < P.K && k + 3 >= P.K) {             // ragged K tail
+        float t[4] = {0, 0, 0, 0};
+        for (int q = 0; q < 4 && k + q < P.K; q++) t[q] = pa[c][k0 + q];
+        va[c] = make_float4(t[0], t[1], t[2], t[3]);
+      }
+      int kb = k0 + (tid >> 4) + 16 * c;
+      if (kb < P.K && bn + 3 < P.N && ((P.ldw & 3) == 0)) vb[c] = *(const float4*)(W + (long long)kb * P.ldw + bn);
+      else {
+        float t[4] = {0, 0, 0, 0};
+        if (kb < P.K) for (int q = 0; q < 4 && bn + q < P.N; q++) t[q] = W[(long long)kb * P.ldw + bn + q];
+        vb[c] = make_float4(t[0], t[1], t[2], t[3]);
+      }
+    }
     __syncthreads();
 #pragma unroll
-    for (int c = 0; c < 4; c++) {               // A tile 64 x 16
-      int idx = tid + c * 256, r = idx >> 4, k = idx & 15;
-      sA[r][k] = (pa[c] && k0 + k < P.K) ? pa[c][k0] : 0.f;
-    }
-#pragma unroll
-    for (int c = 0; c < 4; c++) {               // B tile 16 x 64
-      int idx = tid + c * 256, k = idx >> 6, n = idx & 63;
-      sB[k][n] = (n0 + n < P.N && k0 + k < P.K) ? W[(long long)(k0 + k) * P.ldw + n0 + n] : 0.f;
+    for (int c = 0; c < 2; c++) {
+      int r = (tid >> 3) + 32 * c, k = (tid & 7) * 4;
+      sA[r][k] = va[c].x; sA[r][k + 1] = va[c].y; sA[r][k + 2] = va[c].z; sA[r][k + 3] = va[c].w;
+      int kb = (tid >> 4) + 16 * c, n = (tid & 15) * 4;
+      sB[kb][n] = vb[c].x; sB[kb][n + 1] = vb[c].y; sB[kb][n + 2] = vb[c].z; sB[kb][n + 3] = vb[c].w;
     }
     __syncthreads();
 #pragma unroll
-    for (int kk = 0; kk < 16; kk += 4) {
+    for (int kk = 0; kk < 32; kk += 4) {
       float fa[2], fb[2];
 #pragma unroll
       for (int i = 0; i < 2; i++) fa[i] = sA[wm * 32 + i * 16 + li][kk + lg];
