@@ -104,6 +104,8 @@ size_t layout(pahq_model* M, char* base) {
   M->cpi = b.take<float>(Ns * tile); M->rxpi = b.take<float>((2 * L + 1) * tile);
   M->ref_logits = b.take<float>(B * Vp); M->ref_logz = b.take<double>(B);
   M->xv = b.take<float>(tile);
+  M->qkv_sh = b.take<float>(T * 3 * H * dh); M->oth = b.take<float>(tile); M->sh_slots = b.take<float>(H * tile);
+  M->qv = b.take<float>(n * T * dh);
   M->run_a = b.take<float>(n * tile); M->run_b = b.take<float>(n * tile);
   M->xcodes = b.take<uint8_t>(n * G * T * Kd); M->xscale = b.take<float>(n * G * T); M->xf32 = b.take<float>(n * 3 * tile);
   M->qkv = b.take<float>(n * T * 3 * H * dh);
@@ -183,7 +185,7 @@ int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
     a.kind = PI_REF; PCHK(run_pass(M, a, nullptr));
     M->pi_l = ctx.pl; M->pi_h = ctx.ph;
   }
-  make_plan(M, ctx.p0, M->plan);
+  make_plan(M, ctx.p0, v, M->plan);
   ctx.n_eff = M->nmax;
   if (M->plan.n_slots > 0) ctx.n_eff = (int)std::min<long long>(M->nmax, M->pool_tiles / M->plan.n_slots);
   if (ctx.n_eff < 1) return PAHQ_ENOMEM;
@@ -198,6 +200,12 @@ int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
   void* dterms = nullptr;
   if (!terms.empty()) PCHK(upload_table(M, terms.data(), terms.size() * sizeof(Term), &dterms));
   HIPCHK(launch_tile_lincomb(M->xv, base, (const Term*)dterms, (int)terms.size(), M->tile, M->stream));
+  if (M->plan.split_first) {
+    // everything in v's layer that does not depend on the candidate: the other heads, and the
+    // investigated head's two unpatched inputs
+    PassArgs a; a.kind = PREFIX; a.p0 = ctx.p0; a.n = 1; a.pl = ctx.pl; a.ph = ctx.ph; a.v = v; a.patch_mode = 0;
+    PCHK(run_pass(M, a, &M->plan));
+  }
   return PAHQ_OK;
 }
 

@@ -20,8 +20,11 @@ namespace pahq {
 // to e4m3 (one scale per token and head) for the fp8 output projection.
 typedef float v4f_a __attribute__((ext_vector_type(4)));
 
+// q, k and v each come with their own base pointer, instance stride and row
+// stride (AttnSrc), so one head can take a per-candidate query, key or value
+// while the other two are shared by all instances.
 template <int ST, int DH>
-__global__ __launch_bounds__(256) void attention_mfma_k(const float* qkv, long long qkv_is, uint8_t* zcodes,
+__global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zcodes,
                                                          long long zc_is, float* zscale, long long zs_is, float* zf32,
                                                          long long zf_is, int f32_head, int n_pairs, int B, int S, int H,
                                                          int ldz, int rope, float rope_theta) {
@@ -29,21 +32,24 @@ __global__ __launch_bounds__(256) void attention_mfma_k(const float* qkv, long l
   constexpr int NT = DH / 16;       // output column tiles
   const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (pair >= n_pairs) return;
-  const int h = pair % H, sb = pair / H;          // sb = inst * B + b
+  const int hl = pair % src.n_heads, sb = pair / src.n_heads;          // sb = inst * B + b
+  const int h = src.h0 + hl;                                           // head index in the outputs
   const int inst = sb / B, b = sb % B;
   const int lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
-  const int ld = 3 * H * DH;
-  const float* base = qkv + inst * qkv_is + (long long)b * S * ld + h * DH;
+  const float* qb = src.q + inst * src.q_is + (long long)b * S * src.q_ld + hl * src.head_cols;
+  const float* kb = src.k + inst * src.k_is + (long long)b * S * src.k_ld + hl * src.head_cols;
+  const float* vb = src.v + inst * src.v_is + (long long)b * S * src.v_ld + hl * src.head_cols;
 
   float q[ST][CH], k[ST][CH];
 #pragma unroll
   for (int a = 0; a < ST; a++) {
     int pos = 16 * a + i;
-    const float* row = base + (long long)pos * ld + CH * g;
+    const float* qrow = qb + (long long)pos * src.q_ld + CH * g;
+    const float* krow = kb + (long long)pos * src.k_ld + CH * g;
 #pragma unroll
     for (int c = 0; c < CH; c += 4) {
       float4 vq = make_float4(0, 0, 0, 0), vk = vq;
-      if (pos < S) { vq = *(const float4*)(row + c); vk = *(const float4*)(row + H * DH + c); }
+      if (pos < S) { vq = *(const float4*)(qrow + c); vk = *(const float4*)(krow + c); }
       q[a][c] = vq.x; q[a][c + 1] = vq.y; q[a][c + 2] = vq.z; q[a][c + 3] = vq.w;
       k[a][c] = vk.x; k[a][c + 1] = vk.y; k[a][c + 2] = vk.z; k[a][c + 3] = vk.w;
     }
@@ -119,7 +125,7 @@ __global__ __launch_bounds__(256) void attention_mfma_k(const float* qkv, long l
 #pragma unroll
     for (int r = 0; r < 4; r++) {
       int kpos = 16 * bk + 4 * g + r;
-      const float* row = base + (long long)kpos * ld + 2 * H * DH + i;
+      const float* row = vb + (long long)kpos * src.v_ld + i;
 #pragma unroll
       for (int t = 0; t < NT; t++) vv[bk][r][t] = (kpos < S) ? row[16 * t] : 0.f;
     }
@@ -167,14 +173,14 @@ __global__ __launch_bounds__(256) void attention_mfma_k(const float* qkv, long l
   }
 }
 
-hipError_t launch_attention(const float* qkv, long long qkv_is, uint8_t* zcodes, long long zc_is, float* zscale,
+hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is, float* zscale,
                             long long zs_is, float* zf32, long long zf_is, int f32_head, int n_inst, int B, int S,
                             int H, int dh, int ldz, int rope, float rope_theta, hipStream_t s) {
   if (n_inst == 0) return hipSuccess;
   if (S > 32) return hipErrorInvalidValue;
-  int n_pairs = n_inst * B * H;
+  int n_pairs = n_inst * B * src.n_heads;
   dim3 grid((n_pairs + 3) / 4);
-#define ATT(ST_, DH_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_>), grid, dim3(256), 0, s, qkv, qkv_is, zcodes, zc_is, \
+#define ATT(ST_, DH_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_>), grid, dim3(256), 0, s, src, zcodes, zc_is, \
                                          zscale, zs_is, zf32, zf_is, f32_head, n_pairs, B, S, H, ldz, rope, rope_theta)
   if (S <= 16) {
     if (dh == 16) ATT(1, 16); else if (dh == 32) ATT(1, 32); else if (dh == 64) ATT(1, 64);

@@ -9,7 +9,7 @@
 
 namespace pahq {
 
-enum PassKind { BASE_CLEAN = 0, BASE_CORRUPT, PI_CORRUPT, PI_REF, STATE, CAND };
+enum PassKind { BASE_CLEAN = 0, BASE_CORRUPT, PI_CORRUPT, PI_REF, STATE, CAND, PREFIX };
 
 // How one recomputed receiver forms its input from the residual streams.
 struct RecvSpec {
@@ -21,7 +21,10 @@ struct RecvPlan {
   int p0 = -1;
   std::vector<RecvSpec> spec;  // indexed by receiver id (only receivers at positions >= p0 are filled)
   std::vector<int> slot_of;    // per sender: slot index or -1
-  int n_slots = 0;
+  std::vector<char> shared;    // per sender: its slot is the same for every instance (see split_first)
+  int n_slots = 0;             // per-instance slots
+  int n_shared = 0;            // instance-independent slots
+  bool split_first = false;    // candidates recompute only the investigated head in their first layer
 };
 
 struct PassArgs {
@@ -70,6 +73,7 @@ struct pahq_model {
   double* logz_clean;                     // [B]
   float *cpi, *rxpi, *ref_logits; double* ref_logz;   // state of the current fp32 head
   float* xv;                              // current input of the receiver under evaluation
+  float *qkv_sh, *oth, *sh_slots, *qv;    // first-layer state shared by all candidates of a receiver
   float *run_a, *run_b;                   // [nmax] tiles each
   uint8_t* xcodes; float* xscale; float* xf32;
   float* qkv; uint8_t* zcodes; float* zscale; float* zf32;
@@ -111,6 +115,6 @@ static inline float* corrupt_prefix(pahq_model* M, int p) {
   return p == 0 ? M->corrupt : M->rx + (long long)canon_pos(M, p) * M->tile;
 }
 int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan);
-void make_plan(pahq_model* M, int p0, RecvPlan& out);
+void make_plan(pahq_model* M, int p0, int v, RecvPlan& out);
 int prof_harvest(pahq_model* M);     // synchronises the stream and folds recorded event pairs into M->prof
 }  // namespace pahq

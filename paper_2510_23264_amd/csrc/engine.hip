@@ -23,12 +23,20 @@ namespace pahq {
 
 static inline int canon(const pahq_model* M, int p) { return canon_pos(M, p); }
 
-void make_plan(pahq_model* M, int p0, RecvPlan& out) {
+void make_plan(pahq_model* M, int p0, int v, RecvPlan& out) {
   const GraphDims& g = M->g;
   out.p0 = p0;
   out.spec.assign(g.Nr, RecvSpec());
   out.slot_of.assign(g.Ns, -1);
+  out.shared.assign(g.Ns, 0);
   out.n_slots = 0;
+  out.n_shared = 0;
+  // With an fp32 investigated head, a candidate into a head input changes, inside its own layer,
+  // only that head: the other heads of the layer are the same for every candidate.
+  int vk, vl, vh, vc;
+  g.receiver_info(v, vk, vl, vh, vc);
+  out.split_first = (vk == 0 && M->cfg.precision == PAHQ_PAHQ);
+  const int v_node = g.node_of_receiver(v);
   const int nstat = g.n_static(p0);
   for (int w = 0; w < g.Nr; w++) {
     if (g.pos_of_receiver(w) < p0) continue;
@@ -46,7 +54,11 @@ void make_plan(pahq_model* M, int p0, RecvPlan& out) {
       for (int s = 0; s < n_up; s++) if (!row[s]) sp.senders.push_back(s);
     }
     for (int s : sp.senders)
-      if (s >= nstat && out.slot_of[s] < 0) out.slot_of[s] = out.n_slots++;
+      if (s >= nstat && out.slot_of[s] < 0) {
+        bool sh = out.split_first && s != v_node && g.pos_after_sender(s) == p0 + 1;   // another head of v's layer
+        out.shared[s] = sh ? 1 : 0;
+        out.slot_of[s] = sh ? out.n_shared++ : out.n_slots++;
+      }
   }
 }
 
@@ -68,12 +80,13 @@ struct Builder {
   std::vector<CombineSrc> csrcs;
   std::vector<OprojDesc> odescs;
   std::vector<HeadAux> haux;
+  std::vector<AttnSrc> asrcs;
   std::vector<Op> ops;
   bool general, has_pi;
   int nstat;
 
   Builder(pahq_model* M_, const PassArgs& a_, const RecvPlan* p_) : M(M_), a(a_), plan(p_) {
-    general = (a.kind == STATE || a.kind == CAND);
+    general = (a.kind == STATE || a.kind == CAND || a.kind == PREFIX);
     has_pi = a.pl >= 0;
     nstat = M->g.n_static(a.p0);
   }
@@ -82,6 +95,12 @@ struct Builder {
     if (has_pi && p > a.p0) return M->rxpi + (long long)canon(M, p) * M->tile;
     return corrupt_prefix(M, p);
   }
+  // slot of a recomputed sender that some receiver reads: per instance, or one for all instances
+  float* slot_ptr(int s) {
+    return plan->shared[s] ? M->sh_slots + (long long)plan->slot_of[s] * M->tile
+                           : M->slots + (long long)plan->slot_of[s] * M->tile;
+  }
+  long long slot_is(int s) { return plan->shared[s] ? 0 : (long long)plan->n_slots * M->tile; }
   float* corrupt_ref_tile(int s) {      // corrupted-run output of a recomputed sender under the current precision set
     return (has_pi ? M->cpi : M->corrupt) + (long long)s * M->tile;
   }
@@ -98,7 +117,7 @@ struct Builder {
       for (int s : sp->senders) {
         Term t;
         if (s < nstat) { t.p = M->delta + (long long)s * M->tile; t.inst_stride = 0; }
-        else { t.p = M->slots + (long long)plan->slot_of[s] * M->tile; t.inst_stride = (long long)plan->n_slots * M->tile; }
+        else { t.p = slot_ptr(s); t.inst_stride = slot_is(s); }
         t.sign = sign; t.pad_ = 0;
         terms.push_back(t);
       }
@@ -179,10 +198,59 @@ struct Builder {
     gd.offset = (M->cfg.norm == PAHQ_NORM_RMS || !offset) ? M->zeros_d : offset;
   }
 
+  void add_attention(const AttnSrc& src, int f32_head) {
+    asrcs.push_back(src);
+    add_op(OP_ATTN, (int)asrcs.size() - 1, f32_head);
+  }
+
+  // First layer of a candidate pass into a head input (fp32 investigated head): the PREFIX pass
+  // has left the layer's q/k/v (qkv_sh) and the stream plus all other heads (oth); only the
+  // patched input's projection, the investigated head's attention and its output projection
+  // are per candidate.
+  void first_block_split(int l, Stream& run) {
+    const GraphDims& g = M->g;
+    const int H = M->H, dh = M->dh, d = M->d, T = M->T;
+    int vk, vl, hv, cv;
+    g.receiver_info(a.v, vk, vl, hv, cv);
+    GroupDesc gd; memset(&gd, 0, sizeof(gd));
+    norm_params(gd, M->ln1_g + (long long)l * d, M->ln1_b + (long long)l * d);
+    gd.out_f32 = M->xf32; gd.out_f32_is = M->tile;
+    int gi = (int)groups.size();
+    groups.push_back(gd);
+    add_patch(gi);
+    const float* Wc[3] = {M->W_Q, M->W_K, M->W_V};
+    const float* bc[3] = {M->b_Q, M->b_K, M->b_V};
+    const long long hoff = (long long)l * H + hv;
+    int pf = (int)probs.size();
+    probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, Wc[cv] + hoff * d * dh, dh, nullptr, 1,
+                          bc[cv] + hoff * dh, M->qv, (long long)T * dh, dh, 0, T, dh, d, d));
+    add_op(OP_GEMM32, pf, 1, T * a.n, dh); work_gemm(pf);
+    AttnSrc src; memset(&src, 0, sizeof(src));
+    const float* shared0 = M->qkv_sh + (long long)hv * dh;
+    const int ld_sh = 3 * H * dh;
+    src.q = cv == 0 ? M->qv : shared0;               src.q_is = cv == 0 ? (long long)T * dh : 0; src.q_ld = cv == 0 ? dh : ld_sh;
+    src.k = cv == 1 ? M->qv : shared0 + H * dh;      src.k_is = cv == 1 ? (long long)T * dh : 0; src.k_ld = cv == 1 ? dh : ld_sh;
+    src.v = cv == 2 ? M->qv : shared0 + 2 * H * dh;  src.v_is = cv == 2 ? (long long)T * dh : 0; src.v_ld = cv == 2 ? dh : ld_sh;
+    src.n_heads = 1; src.h0 = hv; src.head_cols = 0;
+    add_attention(src, hv);
+    Stream nxt = next_run(2 * l + 1, run.p == M->run_a ? M->run_b : M->run_a);
+    int s = g.head(l, hv);
+    pf = (int)probs.size();
+    GemmProb pp = prob8(M->zf32, (long long)T * dh, dh, nullptr, 0, 0, M->W_O + hoff * dh * d, d, nullptr, 1, nullptr,
+                        nxt.p, nxt.is, d, 0, T, d, dh, dh);
+    pp.add = M->oth; pp.add_is = 0;
+    if (plan->slot_of[s] >= 0) { pp.aux = slot_ptr(s); pp.aux_is = slot_is(s); pp.aux_sub = corrupt_ref_tile(s); }
+    probs.push_back(pp);
+    add_op(OP_GEMM32, pf, 1, T * a.n, d); work_gemm(pf);
+    run = nxt;
+  }
+
   void attention_block(int l, Stream& run) {
     const GraphDims& g = M->g;
     const int H = M->H, dh = M->dh, d = M->d, T = M->T, Kd = M->Kd, Kh = M->Kh;
     const bool pi_layer = has_pi && l == a.pl;
+    const bool prefix = a.kind == PREFIX;
+    float* const qkv_buf = prefix ? M->qkv_sh : M->qkv;
     // ---- groups
     std::map<std::pair<int, std::vector<int>>, int> seen;
     std::vector<int> grp_of(3 * H, -1);          // index into `groups` per (h, c) block
@@ -231,7 +299,7 @@ struct Builder {
       probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
                             M->qkv_codes + ((long long)l * 3 * H * dh + (long long)nb * dh) * Kd, Kd,
                             M->qkv_scale + (long long)l * 3 * H + nb, dh, M->bqkv + (long long)l * 3 * H * dh + (long long)nb * dh,
-                            M->qkv + (long long)nb * dh, (long long)T * qkv_ld, (int)qkv_ld, 0, T, (e - nb) * dh, Kd, d));
+                            qkv_buf + (long long)nb * dh, (long long)T * qkv_ld, (int)qkv_ld, 0, T, (e - nb) * dh, Kd, d));
       if ((e - nb) * dh > maxN) maxN = (e - nb) * dh;
       nb = e;
     }
@@ -245,16 +313,24 @@ struct Builder {
         const GroupDesc& gd = groups[grp_of[c * H + a.ph]];
         long long hoff = (long long)l * H + a.ph;
         probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1,
-                              bc[c] + hoff * dh, M->qkv + ((long long)c * H + a.ph) * dh, (long long)T * qkv_ld,
+                              bc[c] + hoff * dh, qkv_buf + ((long long)c * H + a.ph) * dh, (long long)T * qkv_ld,
                               (int)qkv_ld, 0, T, dh, d, d));
       }
       add_op(OP_GEMM32, pf, 3, T * a.n, dh); work_gemm(pf);
     }
-    add_op(OP_ATTN, pi_layer ? a.ph : -1);
+    {
+      AttnSrc src; memset(&src, 0, sizeof(src));
+      src.q = qkv_buf; src.k = qkv_buf + H * dh; src.v = qkv_buf + 2 * H * dh;
+      src.q_is = src.k_is = src.v_is = (long long)T * qkv_ld;
+      src.q_ld = src.k_ld = src.v_ld = (int)qkv_ld;
+      src.n_heads = H; src.h0 = 0; src.head_cols = dh;
+      add_attention(src, pi_layer ? a.ph : -1);
+    }
     // ---- output projections of all heads fused with the stream update.  Only heads whose
     // individual output is needed (cache passes; a downstream receiver that treats the head's
     // edge differently from the stream) are written out.
     Stream nxt = next_run(2 * l + 1, run.p == M->run_a ? M->run_b : M->run_a);
+    if (prefix) { nxt.p = M->oth; nxt.is = 0; }       // stream + bias + every head but the investigated one
     const bool store_raw = (a.kind == BASE_CLEAN || a.kind == BASE_CORRUPT || a.kind == PI_CORRUPT);
     OprojDesc od; memset(&od, 0, sizeof(od));
     od.zc = M->zcodes; od.zc_is = (long long)T * H * Kh; od.zs = M->zscale; od.zs_is = (long long)T * H;
@@ -270,12 +346,12 @@ struct Builder {
       hx[h].dst = nullptr; hx[h].dst_is = 0; hx[h].sub = nullptr;
       if (store_raw) { Stream dst = sender_dest(s, nullptr, 0); hx[h].dst = dst.p; hx[h].dst_is = dst.is; }
       else if (general && plan->slot_of[s] >= 0) {
-        hx[h].dst = M->slots + (long long)plan->slot_of[s] * M->tile; hx[h].dst_is = (long long)plan->n_slots * M->tile;
+        hx[h].dst = slot_ptr(s); hx[h].dst_is = slot_is(s);
         hx[h].sub = corrupt_ref_tile(s);
       }
       if (hx[h].dst) any_aux = true;
     }
-    if (pi_layer) {
+    if (pi_layer && !prefix) {
       // the investigated head's projection in fp32; its output goes to scratch (added by the fused
       // kernel) and, where needed, to its cache tile / slot through the second output
       int pf = (int)probs.size();
@@ -330,7 +406,7 @@ struct Builder {
       Stream dest = sender_dest(s, nullptr, 0);
       po.aux = dest.p; po.aux_is = dest.is;
     } else if (general && plan->slot_of[s] >= 0) {
-      po.aux = M->slots + (long long)plan->slot_of[s] * M->tile; po.aux_is = (long long)plan->n_slots * M->tile;
+      po.aux = slot_ptr(s); po.aux_is = slot_is(s);
       po.aux_sub = corrupt_ref_tile(s);
     }
     probs.push_back(po);
@@ -387,11 +463,18 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
   const bool corrupt_tokens = (a.kind == BASE_CORRUPT || a.kind == PI_CORRUPT);
   run.p = corrupt_tokens ? corrupt_prefix(M, a.p0) : clean_prefix(M, a.p0);
   run.is = 0;
-  for (int l = a.p0 / 2; l < L; l++) {
-    if (a.p0 <= 2 * l) b.attention_block(l, run);
-    if (M->g.mu && a.p0 <= 2 * l + 1) b.mlp_block(l, run);
+  if (a.kind == PREFIX) {
+    b.attention_block(a.p0 / 2, run);
+  } else {
+    for (int l = a.p0 / 2; l < L; l++) {
+      if (a.p0 <= 2 * l) {
+        if (a.kind == CAND && plan->split_first && 2 * l == a.p0) b.first_block_split(l, run);
+        else b.attention_block(l, run);
+      }
+      if (M->g.mu && a.p0 <= 2 * l + 1) b.mlp_block(l, run);
+    }
+    b.final_block(run);
   }
-  b.final_block(run);
 
   // ---- upload the descriptor tables
   Arena& A = M->arena;
@@ -465,8 +548,8 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         break;
       case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, o.i2, o.i3, st)); break;
       case OP_ATTN:
-        HIPCHK(launch_attention(M->qkv, (long long)T * 3 * M->H * M->dh, M->zcodes, (long long)T * M->H * M->Kh,
-                                M->zscale, (long long)T * M->H, M->zf32, (long long)T * M->dh, o.i0, n, B, S, M->H,
+        HIPCHK(launch_attention(b.asrcs[o.i0], M->zcodes, (long long)T * M->H * M->Kh,
+                                M->zscale, (long long)T * M->H, M->zf32, (long long)T * M->dh, o.i1, n, B, S, M->H,
                                 M->dh, M->Kh, M->cfg.pos == PAHQ_POS_ROPE, M->cfg.rope_theta, st));
         break;
       case OP_COMBINE: HIPCHK(launch_combine(d_cdesc, o.i0, d_csrc, n, M->tile, d, st)); break;

@@ -116,10 +116,17 @@ hipError_t launch_gemm_f32(const GemmProb* probs, int n_probs, int max_M, int ma
 hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const HeadAux* auxs, int M, int N, int exact,
                               hipStream_t s);
 
-// Causal attention per (instance, sequence, head).  qkv row layout: [3][H][dh].
+// Causal attention per (instance, sequence, head).  q, k, v: fp32 rows [inst][T][..]; head hl of the
+// launch reads columns hl * head_cols .. + dh of each and writes output head h0 + hl (of H).
 // Heads other than f32_head: z rows quantised per head -> zcodes [inst][T][H][ldz], zscale [inst][T][H].
 // f32_head (or -1): z written unquantised to zf32 [inst][T][dh].
-hipError_t launch_attention(const float* qkv, long long qkv_is, uint8_t* zcodes, long long zc_is, float* zscale,
+struct AttnSrc {
+  const float* q; long long q_is; int q_ld; int pad0_;
+  const float* k; long long k_is; int k_ld; int pad1_;
+  const float* v; long long v_is; int v_ld; int pad2_;
+  int n_heads, h0, head_cols, pad3_;
+};
+hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is, float* zscale,
                             long long zs_is, float* zf32, long long zf_is, int f32_head, int n_inst, int B, int S,
                             int H, int dh, int ldz, int rope, float rope_theta, hipStream_t s);
 

@@ -179,8 +179,10 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
       if (nb >= D.N) continue;
       float4 v = *(const float4*)(D.run_in + inst * D.run_in_is + roff + nb);
       if (D.bias) { float4 b = *(const float4*)(D.bias + nb); v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w; }
-      if (D.extra) { float4 e = *(const float4*)(D.extra + inst * D.extra_is + roff + nb); v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w; }
       v.x += tot[i][j][0]; v.y += tot[i][j][1]; v.z += tot[i][j][2]; v.w += tot[i][j][3];
+      // the fp32 head goes in last: (stream + bias + other heads) + fp32 head, the same association
+      // the candidate path uses when it adds that head to a precomputed sum of the others
+      if (D.extra) { float4 e = *(const float4*)(D.extra + inst * D.extra_is + roff + nb); v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w; }
       *(float4*)(D.run_out + inst * D.run_out_is + roff + nb) = v;
     }
   }
