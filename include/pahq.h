@@ -89,12 +89,14 @@ typedef struct {
                                PAHQ_ALL_FP32: not implemented -> PAHQ_EUNSUPPORTED               */
   int32_t max_batch_edges;  /* most candidates evaluated in one device batch (>= 1)               */
   int32_t mma;              /* how the E4M3 x E4M3 products are summed:
+                               PAHQ_MMA_F16_EXACT (recommended): the codes are converted to fp16 in
+                               registers (exact) and fed to the fp16 matrix cores: exact products,
+                               fp32 accumulation.  This is the arithmetic the method defines.
                                PAHQ_MMA_FP8: the FP8 matrix-core instruction.  Its adder aligns the
-                               products of one instruction to the largest one and keeps a fixed-point
-                               window below it, so a sum can deviate from the exact one by up to about
-                               2^-13 of sum|a*w| (measured on gfx950; ~1e-5 on normally distributed rows).
-                               PAHQ_MMA_F16_EXACT: the same codes decoded to fp16 (exact) and fed to the
-                               fp16 matrix cores: exact products, fp32 accumulation, half the peak rate.
+                               products of one instruction to the largest one and drops what falls
+                               below a window of about 14 bits (measured on gfx950: up to 2^-13 of
+                               sum|a*w| per sum, truncating toward zero), which makes every KL come out
+                               about 1.3 % low.  About 6 % faster end to end.
                                Codes and scales are identical in both modes.                        */
 } pahq_config;
 

@@ -28,7 +28,7 @@ class Config(C.Structure):
                [(n, C.c_int32) for n in ("split_qkv", "precision", "max_batch_edges", "mma")]
 
     @classmethod
-    def from_shape(cls, shape, precision=PAHQ, max_batch_edges=32, mma=MMA_FP8):
+    def from_shape(cls, shape, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT):
         return cls(n_layers=shape.n_layers, n_heads=shape.n_heads, d_head=shape.d_head, d_model=shape.d_model,
                    d_mlp=shape.d_mlp, vocab=shape.vocab, n_ctx=shape.n_ctx, norm=shape.norm, act=shape.act,
                    pos=shape.pos, norm_eps=shape.norm_eps, rope_theta=shape.rope_theta, split_qkv=1,
@@ -124,7 +124,7 @@ class Model:
     """pahq_init_model + the calls on the handle.  `weights`: dict of float32 numpy arrays
     (layouts as in include/pahq.h)."""
 
-    def __init__(self, shape, weights, B, S, precision=PAHQ, max_batch_edges=32, mma=MMA_FP8, device="cuda:0"):
+    def __init__(self, shape, weights, B, S, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, device="cuda:0"):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no HIP device: libpahq has no CPU path")

@@ -18,19 +18,15 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 
+// Eight e4m3 codes (two 32-bit words) -> eight fp16 values with the hardware
+// converter (V_CVT_SCALEF32_PK_F16_FP8, scale 1): exact for every finite code,
+// subnormals and signed zero included (checked over all 254 codes on gfx950).
 __device__ __forceinline__ v8h decode8_o(uint32_t w0, uint32_t w1) {
-  union { v8h h; uint32_t u[4]; v2h p[4]; } r;
-  uint32_t w[2] = {w0, w1};
-#pragma unroll
-  for (int q = 0; q < 2; q++) {
-    uint32_t x = w[q];
-    uint32_t b0 = x & 0xFFu, b1 = (x >> 8) & 0xFFu, b2 = (x >> 16) & 0xFFu, b3 = x >> 24;
-    r.u[2 * q] = (((b0 & 0x7Fu) << 7) | ((b0 & 0x80u) << 8)) | ((((b1 & 0x7Fu) << 7) | ((b1 & 0x80u) << 8)) << 16);
-    r.u[2 * q + 1] = (((b2 & 0x7Fu) << 7) | ((b2 & 0x80u) << 8)) | ((((b3 & 0x7Fu) << 7) | ((b3 & 0x80u) << 8)) << 16);
-  }
-  const v2h k256 = {(_Float16)256.0f, (_Float16)256.0f};
-#pragma unroll
-  for (int q = 0; q < 4; q++) r.p[q] = r.p[q] * k256;
+  union { v8h h; v2h p[4]; } r;
+  r.p[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w0, 1.0f, false);
+  r.p[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w0, 1.0f, true);
+  r.p[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w1, 1.0f, false);
+  r.p[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w1, 1.0f, true);
   return r.h;
 }
 
