@@ -65,6 +65,11 @@ CONFIGS = {
     "cfg5": dict(shape=dict(n_layers=32, n_heads=32, d_head=128, d_model=4096, d_mlp=11008, vocab=32000,
                             n_ctx=32, norm=NORM_RMS, act=ACT_SWIGLU, pos=POS_ROPE, norm_eps=1e-6),
                  B=16, S=32, law="zipf", k=4, shared_pos=True, taus=(0.01,), n_recv=64, seed=505),
+    # cfg5's layer shape, batch and tokens at depth 2: small enough for a CPU check of every
+    # kernel shape cfg5 launches (depth only repeats them)
+    "cfg5_L2": dict(shape=dict(n_layers=2, n_heads=32, d_head=128, d_model=4096, d_mlp=11008, vocab=32000,
+                               n_ctx=32, norm=NORM_RMS, act=ACT_SWIGLU, pos=POS_ROPE, norm_eps=1e-6),
+                    B=16, S=32, law="zipf", k=4, shared_pos=True, taus=(0.01,), n_recv=0, seed=506),
 }
 
 

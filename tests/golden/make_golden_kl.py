@@ -10,7 +10,7 @@ reaches that receiver.  The GPU tests rebuild the same workload and removed
 sets and compare libpahq's pahq_eval_edges / pahq_eval_current against these
 numbers.
 
-usage: python tests/golden/make_golden_kl.py cfg3 [cfg4 ...]
+usage: python tests/golden/make_golden_kl.py [--out-dir DIR] cfg3 [cfg4 cfg5_L2]
 """
 import json
 import os
@@ -38,40 +38,61 @@ def removed_set(g, frac, seed, from_receiver):
 
 
 def cases_for(name, g, L, H):
-    """(receiver, frac, seed, senders) -- late layers for the large configs keep the oracle's cost bounded."""
+    """(receiver, frac, seed, number of senders) -- late layers for the large configs keep the
+    oracle's cost bounded.  Senders are picked by pick_senders below."""
     top = L - 1
     if name == "cfg3":
-        return [(g.OUT, 0.0, 0, [0, 77, 156]), (g.OUT, 0.5, 1, [3, 100, 150]),
-                (g.mlpin(top), 0.0, 0, [0, 140, 155]), (g.headin(top, 3, 1), 0.0, 0, [0, 90, 143]),
-                (g.headin(8, 5, 2), 0.9, 2, [1, 50, 104]), (g.headin(6, 0, 0), 0.0, 0, [0, 40, 78]),
-                (g.headin(9, 11, 1), 0.3, 3, [5, 60, 117])]
+        return [(g.OUT, 0.0, 0, 3), (g.OUT, 0.5, 1, 3), (g.mlpin(top), 0.0, 0, 3), (g.headin(top, 3, 1), 0.0, 0, 3),
+                (g.headin(8, 5, 2), 0.9, 2, 2), (g.headin(6, 0, 0), 0.0, 0, 3), (g.headin(9, 11, 1), 0.3, 3, 2)]
     if name == "cfg4":
-        n = g.n_senders
-        return [(g.OUT, 0.0, 0, [0, n // 2, n - 1]), (g.OUT, 0.9, 1, [7, n // 3, n - 2]),
-                (g.mlpin(top), 0.0, 0, [0, n - 3]), (g.headin(top, 5, 1), 0.0, 0, [0, n // 2]),
-                (g.headin(top - 1, 9, 2), 0.5, 2, [1, n // 2])]
-    if name == "cfg5":
-        n = g.n_senders
-        return [(g.OUT, 0.0, 0, [0, n // 2, n - 1]), (g.mlpin(top), 0.0, 0, [0, n - 2]),
-                (g.headin(top, 7, 1), 0.0, 0, [0, n // 2]), (g.headin(top, 20, 2), 0.9, 1, [3, n // 3])]
+        return [(g.OUT, 0.0, 0, 3), (g.OUT, 0.9, 1, 3), (g.mlpin(top), 0.0, 0, 2), (g.headin(top, 5, 1), 0.0, 0, 2),
+                (g.headin(top - 1, 9, 2), 0.5, 2, 2), (g.headin(top - 2, 0, 0), 0.0, 0, 2)]
+    if name == "cfg5_L2":
+        return [(g.OUT, 0.0, 0, 3), (g.OUT, 0.5, 1, 2), (g.mlpin(1), 0.0, 0, 3), (g.headin(1, 7, 1), 0.0, 0, 3),
+                (g.headin(1, 20, 2), 0.5, 3, 2), (g.mlpin(0), 0.3, 2, 2), (g.headin(0, 31, 0), 0.0, 0, 1),
+                (g.headin(0, 5, 2), 0.3, 4, 1)]
     raise SystemExit("no sample defined for " + name)
 
 
+def pick_senders(R, r, n_up, k):
+    """k kept senders spread over the kept in-edges of r (first, ..., last), plus one already
+    removed sender when there is one (its candidate equals the current state)."""
+    kept = np.flatnonzero(~R[r, :n_up])
+    rem = np.flatnonzero(R[r, :n_up])
+    picks = [int(kept[i]) for i in np.unique(np.linspace(0, len(kept) - 1, k).round().astype(int))] if len(kept) else []
+    if len(rem):
+        picks.append(int(rem[len(rem) // 2]))
+    return picks
+
+
 def main():
-    for name in sys.argv[1:]:
+    args = sys.argv[1:]
+    out_dir = os.path.dirname(os.path.abspath(__file__))
+    if args and args[0] == "--out-dir":
+        out_dir = args[1]
+        args = args[2:]
+        os.makedirs(out_dir, exist_ok=True)
+    for name in args:
         t0 = time.time()
         shape, w, clean, corrupt, spec = synth.make_workload(name)
+        print(name, "workload made t=%.0fs" % (time.time() - t0), flush=True)
         oa = Acdc(Model(shape, w, cache_decoded_bytes=2 << 30), clean, corrupt)
         g = oa.g
+        print(name, "weights quantised t=%.0fs" % (time.time() - t0), flush=True)
         out = {"config": name, "seed": spec["seed"], "mode": "PAHQ", "cases": []}
-        for (r, frac, seed, senders) in cases_for(name, g, shape.n_layers, shape.n_heads):
+        for (r, frac, seed, k) in cases_for(name, g, shape.n_layers, shape.n_heads):
             R = removed_set(g, frac, seed, r)
+            senders = pick_senders(R, r, g.n_upstream(r), k)
             cur = oa.kl_fast(r, R)
-            kls = [oa.kl_edge(r, int(u), removed=R) for u in senders]
+            print(name, "receiver", r, "current state done t=%.0fs" % (time.time() - t0), flush=True)
+            kls = []
+            for u in senders:
+                kls.append(oa.kl_edge(r, int(u), removed=R))
+                print(name, "receiver", r, "sender", u, "done t=%.0fs" % (time.time() - t0), flush=True)
             out["cases"].append({"receiver": int(r), "frac": frac, "rseed": seed, "senders": [int(u) for u in senders],
                                  "kl_current": cur, "kl_new": kls})
             print(name, "receiver", r, "frac", frac, "cur", cur, "kl", kls, "t=%.0fs" % (time.time() - t0), flush=True)
-        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "kl_%s.json" % name)
+        path = os.path.join(out_dir, "kl_%s.json" % name)
         with open(path, "w") as f:
             json.dump(out, f, indent=1)
         print("wrote", path, "in %.0f s" % (time.time() - t0), flush=True)

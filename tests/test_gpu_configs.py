@@ -74,8 +74,55 @@ def test_cfg4_sampled_edges():
     run_config("cfg4", 16)
 
 
-def test_cfg5_sampled_edges():
-    run_config("cfg5", 8)
+def test_cfg5_layer_shape_depth2_sampled_edges():
+    """Config 5's layer shape, batch and token recipe at depth 2 (the CPU check of 32 such
+    layers takes hours): every kernel shape config 5 launches, against the CPU values."""
+    run_config("cfg5_L2", 8)
+
+
+@pytest.mark.timeout(1000)
+def test_cfg5_full_size_properties():
+    """Config 5 at full depth, through properties that need no CPU value: the clean run
+    patched with nothing has KL exactly 0; a candidate whose edge is already removed equals
+    the current state bit for bit; results do not depend on how candidates are batched;
+    removing edges moves the KL away from 0 and never gives NaN."""
+    import paper_2510_23264_amd as P
+    shape, w, clean, corrupt, spec = synth.make_workload("cfg5")
+    print("cfg5: weights drawn", flush=True)
+    gm = P.Model(shape, w, spec["B"], spec["S"], precision=P.PAHQ, max_batch_edges=8)
+    try:
+        del w
+        print("cfg5: model on the device", flush=True)
+        gm.clean_cache(clean, corrupt)
+        print("cfg5: caches filled", flush=True)
+        from oracle.graph import Graph
+        g = Graph(shape.n_layers, shape.n_heads, shape.d_mlp > 0)
+        out_r = g.OUT
+        top = shape.n_layers - 1
+        key_r = g.headin(top, 20, 1)
+        for r in (out_r, key_r):
+            assert gm.eval_current(r) == 0.0
+        n_up = P.n_upstream(gm.cfg, out_r)
+        senders = np.array([0, 1, n_up // 2, n_up - 2, n_up - 1], np.int32)
+        a = gm.eval_edges(out_r, senders)
+        assert np.isfinite(a).all() and a[0] == 0.0 and (a[1:] > 0).all()       # EMBED -> OUT: same tokens
+        one = np.array([gm.eval_edges(out_r, senders[i:i + 1])[0] for i in range(len(senders))])
+        assert np.array_equal(a, one)
+        rem = removed_flat(gm.cfg, P, 0.5, 1, key_r)
+        gm.set_removed(rem)
+        cur = gm.eval_current(key_r)
+        assert np.isfinite(cur) and cur > 0
+        off = int(g.edge_offsets()[key_r])
+        nk = P.n_upstream(gm.cfg, key_r)
+        gone = np.flatnonzero(rem[off:off + nk])[:2].astype(np.int32)
+        kept = np.flatnonzero(rem[off:off + nk] == 0)[:3].astype(np.int32)
+        got = gm.eval_edges(key_r, np.concatenate([gone, kept]))
+        assert got[0] == cur and got[1] == cur
+        assert np.isfinite(got).all()
+        again = gm.eval_edges(key_r, kept[::-1].copy())
+        assert np.array_equal(again[::-1], got[2:])
+    finally:
+        gm.close()
 
 
 def test_cfg2_restricted_sweep_matches_oracle_trace():
