@@ -55,7 +55,7 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
   M->B = B; M->S = S; M->T = B * S; M->L = c->n_layers; M->H = c->n_heads; M->dh = c->d_head;
   M->d = c->d_model; M->m = c->d_mlp; M->V = c->vocab;
   M->Kd = pad128(M->d); M->Kh = pad128(M->dh); M->Km = pad128(M->m > 0 ? M->m : 1);
-  M->Vp = (M->V + 3) / 4 * 4;
+  M->Vp = (M->V + 31) / 32 * 32;      // logits rows start on 128-byte boundaries
   M->nmax = c->max_batch_edges; M->G = 3 * M->H + 1;
   M->tile = (long long)M->T * M->d;
 }

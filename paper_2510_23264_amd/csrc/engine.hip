@@ -338,7 +338,7 @@ struct Builder {
     od.run_in = run.p; od.run_in_is = run.is; od.run_out = nxt.p; od.run_out_is = nxt.is;
     od.bias = M->b_O + (long long)l * d;
     od.H = H; od.Kh = Kh; od.skip_head = pi_layer ? a.ph : -1; od.rpi = T; od.M = T * a.n; od.N = d;
-    od.aux_begin = -1;
+    od.aux_begin = -1; od.dh = M->dh;
     bool any_aux = false;
     std::vector<HeadAux> hx(H);
     for (int h = 0; h < H; h++) {
@@ -543,8 +543,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
                                   M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
         break;
       case OP_GEMM8:
-        HIPCHK(launch_gemm_fp8(d_probs + o.i0, o.i1, o.i2, o.i3, M->cfg.mma == PAHQ_MMA_F16_EXACT,
-                               0, st));
+        HIPCHK(launch_gemm_fp8(d_probs + o.i0, o.i1, o.i2, o.i3, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
         break;
       case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, o.i2, o.i3, st)); break;
       case OP_ATTN:

@@ -1,23 +1,28 @@
 // Grouped GEMMs on the CDNA4 matrix cores.
 //
 // gemm_fp8: val = (A_codes * W_codes^T) * row_scale * col_scale, then the
-//   epilogue of GemmProb (bias, GELU, residual add, second output).
-//   Both operands are FP8 E4M3 codes with K contiguous.  The products are
-//   formed by V_MFMA_SCALE_F32_16X16X128_F8F6F4 with both block scales fixed
-//   at 2^0, accumulating in fp32.  A workgroup owns a BM x BN output tile; K
-//   advances in slabs of 128 bytes staged through LDS (rows padded to 144
-//   bytes so that the 16 rows a quarter-wave reads fall into distinct banks);
-//   the next slab is prefetched into registers while the current one feeds the
-//   MFMAs.  Two tile shapes: 256 x 128 with 8 wavefronts (4 x 2, 64 x 64 each)
-//   for the large problems, 128 x 64 with 4 wavefronts (32 x 64 each) for the
-//   per-head ones.  The workgroup -> tile map gives each XCD (workgroup id mod
-//   8) a contiguous range of row tiles, with column tiles innermost, so the A
-//   rows of a tile are fetched into one L2 only.
-//   Lane layout of the instruction (lane = 16*g + i): the A operand of lane
-//   (i, g) is row i, bytes [32g, 32g+32) of the slab; B likewise for column i;
-//   the result lane (i, g) holds C[4g + r][i], r = 0..3.  Only the pairing of
-//   A's and B's k positions matters for the product, and both operands are
-//   loaded with the same byte -> (g, position) map.
+//   epilogue of GemmProb (bias, GELU, residual add, second output).  Both
+//   operands are FP8 E4M3 codes with K contiguous, K padded with zero codes to
+//   a multiple of 128.  Two kernels:
+//
+//   gemm_x_k (exact sums, the default): codes are decoded to fp16 in registers
+//   (V_CVT_SCALEF32_PK_F16_FP8, exact) and multiplied by V_MFMA_F32_16X16X32_F16:
+//   exact products, fp32 sums.  Slabs of 128 K-bytes go from global memory
+//   straight into LDS (GLOBAL_LOAD_LDS_DWORDX4), two stages, one barrier per
+//   slab.  128 x 128 tile, four wavefronts of 64 x 64 (two decodes per MFMA; a
+//   smaller wave tile is bound by instruction issue, not by the matrix cores).
+//
+//   gemm_fp8_k (PAHQ_MMA_FP8): V_MFMA_SCALE_F32_16X16X128_F8F6F4 with unit block
+//   scales; its adder keeps a fixed-point window below the largest product of
+//   an instruction (about 2^-13 of sum |a w| in the worst case).  128 x 64 tile,
+//   slabs staged through registers into LDS rows padded to 144 bytes.
+//
+//   In both, W is the first MFMA operand, so a lane owns one output row of a
+//   16 x 16 tile and four consecutive columns (16-byte stores); row scales,
+//   column scales and the instance / row split are fetched before the K loop so
+//   that the epilogue does not wait on them.  The workgroup -> tile map gives
+//   each XCD (workgroup id mod 8) a contiguous range of tiles, column tiles
+//   innermost, so the A rows of a tile are fetched into one L2 only.
 //
 // gemm_f32: plain fp32 C = A * W (+ bias) with V_MFMA_F32_16X16X4_F32 (true
 //   fp32 multiply-accumulate) for the investigated head.
@@ -43,7 +48,7 @@ __device__ __forceinline__ v8h decode8(uint32_t w0, uint32_t w1) {
   return r.h;
 }
 
-#define LDS_ROW 144   // 128 data bytes + 16 pad
+#define LDS_ROW 144   // gemm_fp8_k: 128 data bytes + 16 pad
 
 // XCD-aware tile order: workgroup id w runs on XCD w % 8; that XCD gets the
 // contiguous range [x * chunk, (x+1) * chunk) of the linear tile index.
@@ -52,8 +57,8 @@ __device__ __forceinline__ int xcd_tile(int wg, int total) {
   return (wg & 7) * chunk + (wg >> 3);
 }
 
-// The epilogue for one result element block of a lane: rows m (4 consecutive), column n.
-__device__ __forceinline__ void epilogue_store(const GemmProb& P, int m, int n, float acc, float sa, float sw, int inst,
+// One result element (the slow path: ragged column tail or unaligned rows).
+__device__ __forceinline__ void epilogue_store(const GemmProb& P, int n, float acc, float sa, float sw, int inst,
                                                int r) {
   float val = acc * (sa * sw);
   float v = val;
@@ -69,12 +74,186 @@ __device__ __forceinline__ void epilogue_store(const GemmProb& P, int m, int n, 
   }
 }
 
-// EXACT = false: FP8 matrix-core instruction (its adder keeps a fixed-point
-// window below the largest product, about 2^-13 of sum|a*w| in the worst case).
-// EXACT = true: the same codes decoded to fp16 and multiplied by
-// V_MFMA_F32_16X16X32_F16: products exact, sums in fp32.
-// WAVES_M x WAVES_N wavefronts; each owns a (BM / WAVES_M) x (BN / WAVES_N) sub-tile.
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool EXACT>
+// What the epilogue needs besides the accumulators: fetched before the K loop.
+template <int TM, int TN>
+struct EpiPre {
+  float sa[TM];      // row scale of row (mbase + 16 i + li)
+  int inst[TM];      // its instance and row within the instance
+  int row[TM];
+  float sw[TN];      // column scale of columns nbase + 16 j + 4 lg .. + 3 (one slice when the fast path applies)
+};
+template <int TM, int TN>
+__device__ __forceinline__ void epi_prefetch(EpiPre<TM, TN>& E, const GemmProb& P, int mbase, int nbase, int li,
+                                             int lg) {
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    int m = min(mbase + i * 16 + li, P.M - 1);
+    E.inst[i] = m / P.rpi;
+    E.row[i] = m - E.inst[i] * P.rpi;
+    E.sa[i] = P.ascale[E.inst[i] * P.as_is + (long long)E.row[i] * P.as_stride];
+  }
+#pragma unroll
+  for (int j = 0; j < TN; j++) {
+    int nb = min(nbase + j * 16 + lg * 4, P.N - 1);
+    E.sw[j] = P.wscale[nb / P.wscale_block];
+  }
+}
+// acc[i][j] holds, for lane (li, lg), row mbase + 16 i + li and columns nbase + 16 j + 4 lg .. + 3.
+template <int TM, int TN>
+__device__ __forceinline__ void epi_store(const EpiPre<TM, TN>& E, const GemmProb& P, const v4f (&acc)[TM][TN],
+                                          int mbase, int nbase, int li, int lg) {
+  const bool vec = ((P.ldc & 3) == 0) && ((P.wscale_block & 3) == 0) && (((P.c_is | P.add_is | P.aux_is) & 3) == 0) &&
+                   ((((uintptr_t)P.C | (uintptr_t)P.add | (uintptr_t)P.aux | (uintptr_t)P.aux_sub | (uintptr_t)P.bias) & 15) == 0);
+  float4 bias[TN];
+#pragma unroll
+  for (int j = 0; j < TN; j++) {
+    int nb = nbase + j * 16 + lg * 4;
+    bias[j] = (P.bias && vec && nb + 3 < P.N) ? *(const float4*)(P.bias + nb) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    if (mbase + i * 16 + li >= P.M) continue;
+    const int inst = E.inst[i], row = E.row[i];
+    const float sa = E.sa[i];
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      int nb = nbase + j * 16 + lg * 4;
+      if (nb >= P.N) continue;
+      if (vec && nb + 3 < P.N) {
+        float s2 = sa * E.sw[j];
+        float4 val = make_float4(acc[i][j][0] * s2, acc[i][j][1] * s2, acc[i][j][2] * s2, acc[i][j][3] * s2);
+        float4 v = make_float4(val.x + bias[j].x, val.y + bias[j].y, val.z + bias[j].z, val.w + bias[j].w);
+        if (!P.bias) v = val;                  // keeps the sign of a zero result when there is no bias
+        if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
+        long long off = (long long)row * P.ldc + nb;
+        if (P.add) { float4 a = *(const float4*)(P.add + inst * P.add_is + off); v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w; }
+        *(float4*)(P.C + inst * P.c_is + off) = v;
+        if (P.aux) {
+          if (P.aux_sub) { float4 u = *(const float4*)(P.aux_sub + off); val.x -= u.x; val.y -= u.y; val.z -= u.z; val.w -= u.w; }
+          *(float4*)(P.aux + inst * P.aux_is + off) = val;
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; r++)
+          if (nb + r < P.N)
+            epilogue_store(P, nb + r, acc[i][j][r], sa, P.wscale[(nb + r) / P.wscale_block], inst, row);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ exact sums (fp16 matrix cores)
+// LDS rows are 128 bytes without padding; the 16-byte chunk c of row r sits at chunk position
+// c ^ (r & 7), so the 16-byte operand reads of 8 consecutive rows cover all 32 banks.  A load
+// instruction fills 8 rows: lane l writes LDS bytes [16 l, 16 l + 16) behind a wave-uniform base,
+// i.e. row l >> 3, position l & 7, and therefore fetches chunk (l & 7) ^ (l >> 3) of its row.
+// Rows past M or N are clamped to the last valid row: they feed only results that are never stored.
+// One 16-byte operand read feeds two MFMA steps: step 2 q + s takes bytes [64 q + 16 g + 8 s, + 8)
+// of every row, the same k positions for both operands.
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <int WAVES_M, int WAVES_N, int TM, int TN>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmProb* probs) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int BM = WAVES_M * TM * 16, BN = WAVES_N * TN * 16, ROWS = BM + BN;
+  constexpr int NI = ROWS / 8 / NW;            // load instructions per wave and slab (8 rows each)
+  constexpr int STAGE = ROWS * 128;
+  static_assert(ROWS % (8 * NW) == 0, "rows must split evenly over the waves");
+  // two arrays, always addressed statically: the compiler then knows that the loads in flight
+  // into one stage cannot alias the operand reads of the other and does not wait for them
+  __shared__ __attribute__((aligned(1024))) uint8_t st0[STAGE];
+  __shared__ __attribute__((aligned(1024))) uint8_t st1[STAGE];
+
+  const GemmProb P = probs[blockIdx.y];
+  const int mt = (P.M + BM - 1) / BM, nt = (P.N + BN - 1) / BN;
+  const int lin = xcd_tile(blockIdx.x, mt * nt);
+  if (lin >= mt * nt) return;
+  const int m0 = (lin / nt) * BM, n0 = (lin % nt) * BN;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int li = lane & 15, lg = lane >> 4;
+
+  const uint8_t* src[NI];
+  const int cg = ((lane & 7) ^ (lane >> 3)) * 16;
+#pragma unroll
+  for (int t = 0; t < NI; t++) {
+    int r = 8 * (wave * NI + t) + (lane >> 3);
+    if (r < BM) {
+      int m = min(m0 + r, P.M - 1);
+      src[t] = (const uint8_t*)P.A + (long long)(m / P.rpi) * P.a_is + (long long)(m % P.rpi) * P.lda + cg;
+    } else {
+      int n = min(n0 + r - BM, P.N - 1);
+      src[t] = (const uint8_t*)P.W + (long long)n * P.ldw + cg;
+    }
+  }
+  auto issue = [&](uint8_t* st, int k0) {
+#pragma unroll
+    for (int t = 0; t < NI; t++)
+      __builtin_amdgcn_global_load_lds((gptr_t)(src[t] + k0), (lptr_t)(st + (wave * NI + t) * 1024), 16, 0, 0);
+  };
+  issue(st0, 0);
+
+  const int mbase = m0 + wm * TM * 16, nbase = n0 + wn * TN * 16;
+  EpiPre<TM, TN> E;
+  epi_prefetch<TM, TN>(E, P, mbase, nbase, li, lg);
+
+  const int offA = (wm * TM * 16 + li) * 128, offB = (BM + wn * TN * 16 + li) * 128;
+  const int sw0 = (lg ^ (li & 7)) * 16, sw1 = ((4 + lg) ^ (li & 7)) * 16;
+
+  v4f acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+  auto compute = [&](const uint8_t* st) {
+    const uint8_t* sA = st + offA;
+    const uint8_t* sB = st + offB;
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      const int sw = q ? sw1 : sw0;
+      v8h ha[TM][2];
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        uint4 w = *(const uint4*)(sA + i * 2048 + sw);
+        ha[i][0] = decode8(w.x, w.y);
+        ha[i][1] = decode8(w.z, w.w);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        uint4 w = *(const uint4*)(sB + j * 2048 + sw);
+        v8h hb0 = decode8(w.x, w.y), hb1 = decode8(w.z, w.w);
+#pragma unroll
+        for (int i = 0; i < TM; i++) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb0, ha[i][0], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb1, ha[i][1], acc[i][j], 0, 0, 0);
+        }
+      }
+    }
+  };
+
+  // vmcnt(0) also covers the scale loads above; 0x0F70 = vmcnt 0, expcnt and lgkmcnt left alone
+  for (int k0 = 0; k0 < P.K; k0 += 256) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // this wave's part of the slab has landed
+    __syncthreads();                             // ... everyone's has, and the other stage is free
+    if (k0 + 128 < P.K) issue(st1, k0 + 128);
+    compute(st0);
+    if (k0 + 128 >= P.K) break;
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (k0 + 256 < P.K) issue(st0, k0 + 256);
+    compute(st1);
+  }
+  epi_store<TM, TN>(E, P, acc, mbase, nbase, li, lg);
+}
+
+// ------------------------------------------------------------------ FP8 matrix-core instruction
+// Lane layout of the instruction (lane = 16*g + i): the operand of lane (i, g) is row i, bytes
+// [32g, 32g+32) of the slab.  WAVES_M x WAVES_N wavefronts; each owns a (BM / WAVES_M) x
+// (BN / WAVES_N) sub-tile.
+template <int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_k(const GemmProb* probs) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -137,31 +316,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_k(const GemmPr
     for (int j = 0; j < TN; j++) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 
   load_slab(0);
+  const int mbase = m0 + wm * WM, nbase = n0 + wn * WN;
+  EpiPre<TM, TN> E;
+  epi_prefetch<TM, TN>(E, P, mbase, nbase, li, lg);
   for (int k0 = 0; k0 < P.K; k0 += 128) {
     __syncthreads();                 // previous slab fully consumed
     store_slab();
     __syncthreads();
     if (k0 + 128 < P.K) load_slab(k0 + 128);
-    if (EXACT) {
-#pragma unroll
-      for (int kk = 0; kk < 4; kk++) {
-        v8h ha[TM];
-#pragma unroll
-        for (int i = 0; i < TM; i++) {
-          uint2 w = *(const uint2*)(sA + (wm * WM + i * 16 + li) * LDS_ROW + kk * 32 + lg * 8);
-          ha[i] = decode8(w.x, w.y);
-        }
-#pragma unroll
-        for (int j = 0; j < TN; j++) {
-          uint2 w = *(const uint2*)(sB + (wn * WN + j * 16 + li) * LDS_ROW + kk * 32 + lg * 8);
-          v8h hb = decode8(w.x, w.y);
-#pragma unroll
-          for (int i = 0; i < TM; i++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb, ha[i], acc[i][j], 0, 0, 0);
-        }
-      }
-      continue;
-    }
     v8i fa[TM];
 #pragma unroll
     for (int i = 0; i < TM; i++) {
@@ -180,57 +342,20 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_k(const GemmPr
                                                                      0x7F7F7F7F);
     }
   }
-
-  // W is fed as the first MFMA operand, so the accumulators hold the transposed tile: lane
-  // (i, g) owns row i of a 16-row tile and the four consecutive columns 4g .. 4g+3 -> 16-byte stores.
-  const bool vec = ((P.ldc & 3) == 0) && ((P.wscale_block & 3) == 0) && (((P.c_is | P.add_is | P.aux_is) & 3) == 0) &&
-                   ((((uintptr_t)P.C | (uintptr_t)P.add | (uintptr_t)P.aux | (uintptr_t)P.aux_sub | (uintptr_t)P.bias) & 15) == 0);
-#pragma unroll
-  for (int i = 0; i < TM; i++) {
-    int m = m0 + wm * WM + i * 16 + li;
-    if (m >= P.M) continue;
-    int inst = m / P.rpi, row = m % P.rpi;
-    float sa = P.ascale[inst * P.as_is + (long long)row * P.as_stride];
-#pragma unroll
-    for (int j = 0; j < TN; j++) {
-      int nb = n0 + wn * WN + j * 16 + lg * 4;
-      if (nb >= P.N) continue;
-      if (vec && nb + 3 < P.N) {
-        float s2 = sa * P.wscale[nb / P.wscale_block];
-        float4 val = make_float4(acc[i][j][0] * s2, acc[i][j][1] * s2, acc[i][j][2] * s2, acc[i][j][3] * s2);
-        float4 v = val;
-        if (P.bias) { float4 b = *(const float4*)(P.bias + nb); v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w; }
-        if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
-        long long off = (long long)row * P.ldc + nb;
-        if (P.add) { float4 a = *(const float4*)(P.add + inst * P.add_is + off); v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w; }
-        *(float4*)(P.C + inst * P.c_is + off) = v;
-        if (P.aux) {
-          if (P.aux_sub) { float4 u = *(const float4*)(P.aux_sub + off); val.x -= u.x; val.y -= u.y; val.z -= u.z; val.w -= u.w; }
-          *(float4*)(P.aux + inst * P.aux_is + off) = val;
-        }
-      } else {
-#pragma unroll
-        for (int r = 0; r < 4; r++)
-          if (nb + r < P.N)
-            epilogue_store(P, m, nb + r, acc[i][j][r], sa, P.wscale[(nb + r) / P.wscale_block], inst, row);
-      }
-    }
-  }
+  epi_store<TM, TN>(E, P, acc, mbase, nbase, li, lg);
 }
 
-hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, int big,
-                           hipStream_t s) {
+hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, hipStream_t s) {
   if (n_probs == 0 || max_M == 0 || max_N == 0) return hipSuccess;
-  if (big) {
-    int tiles = ((max_M + 255) / 256) * ((max_N + 127) / 128);
+  if (exact && max_N > 64) {
+    int tiles = ((max_M + 127) / 128) * ((max_N + 127) / 128);
     dim3 grid((tiles + 7) / 8 * 8, n_probs);
-    if (exact) hipLaunchKernelGGL((gemm_fp8_k<256, 128, 4, 2, true>), grid, dim3(512), 0, s, probs);
-    else hipLaunchKernelGGL((gemm_fp8_k<256, 128, 4, 2, false>), grid, dim3(512), 0, s, probs);
+    hipLaunchKernelGGL((gemm_x_k<2, 2, 4, 4>), grid, dim3(256), 0, s, probs);
   } else {
     int tiles = ((max_M + 127) / 128) * ((max_N + 63) / 64);
     dim3 grid((tiles + 7) / 8 * 8, n_probs);
-    if (exact) hipLaunchKernelGGL((gemm_fp8_k<128, 64, 4, 1, true>), grid, dim3(256), 0, s, probs);
-    else hipLaunchKernelGGL((gemm_fp8_k<128, 64, 4, 1, false>), grid, dim3(256), 0, s, probs);
+    if (exact) hipLaunchKernelGGL((gemm_x_k<4, 1, 2, 4>), grid, dim3(256), 0, s, probs);
+    else hipLaunchKernelGGL((gemm_fp8_k<128, 64, 4, 1>), grid, dim3(256), 0, s, probs);
   }
   return hipGetLastError();
 }
@@ -318,7 +443,7 @@ __global__ __launch_bounds__(256) void gemm_f32_k(const GemmProb* probs) {
       for (int j = 0; j < 2; j++) {
         int n = n0 + wn * 32 + j * 16 + li;
         if (n >= P.N) continue;
-        epilogue_store(P, m, n, acc[i][j][r], 1.0f, 1.0f, inst, row);
+        epilogue_store(P, n, acc[i][j][r], 1.0f, 1.0f, inst, row);
       }
     }
 }

@@ -75,7 +75,7 @@ struct OprojDesc {
   float* run_out;      long long run_out_is;
   const float* bias;                        // [N] or null
   int H, Kh, skip_head, rpi;                // skip_head: the fp32 head (or -1)
-  int M, N, aux_begin, pad_;                // M = rows over all instances; aux_begin: first of H HeadAux, or -1
+  int M, N, aux_begin, dh;                  // M = rows over all instances; aux_begin: first of H HeadAux, or -1; dh = d_head (Kh = dh padded to 128)
 };
 
 // ---- launchers ---------------------------------------------------------------
@@ -109,9 +109,7 @@ hipError_t launch_tile_sub(float* out, const float* a, const float* b, long long
 
 // exact = 0: FP8 matrix-core instruction; exact = 1: codes decoded to fp16, fp16 matrix cores (exact
 // products, fp32 sums).
-// big = 1 selects the 256 x 128 tile (for N >= 128 and many rows), else 128 x 64.
-hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, int big,
-                           hipStream_t s);
+hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, hipStream_t s);
 hipError_t launch_gemm_f32(const GemmProb* probs, int n_probs, int max_M, int max_N, hipStream_t s);
 hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const HeadAux* auxs, int M, int N, int exact,
                               hipStream_t s);

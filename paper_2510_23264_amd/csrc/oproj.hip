@@ -61,11 +61,16 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
     pb[c] = (n < D.N) ? D.W + (long long)n * D.Kh + kc * 16 : nullptr;
   }
   uint4 ra[4], rb[2];
+  // codes beyond d_head are zero padding: neither loaded nor (with the fp16 matrix cores) multiplied
+  const bool real_chunk = kc * 16 < D.dh;
+  const int nkk = (D.dh + 31) >> 5;
   auto load_head = [&](int h) {
 #pragma unroll
-    for (int c = 0; c < 4; c++) ra[c] = pa[c] ? *(const uint4*)(pa[c] + (long long)h * D.Kh) : make_uint4(0, 0, 0, 0);
+    for (int c = 0; c < 4; c++)
+      ra[c] = (pa[c] && real_chunk) ? *(const uint4*)(pa[c] + (long long)h * D.Kh) : make_uint4(0, 0, 0, 0);
 #pragma unroll
-    for (int c = 0; c < 2; c++) rb[c] = pb[c] ? *(const uint4*)(pb[c] + (long long)h * D.N * D.Kh) : make_uint4(0, 0, 0, 0);
+    for (int c = 0; c < 2; c++)
+      rb[c] = (pb[c] && real_chunk) ? *(const uint4*)(pb[c] + (long long)h * D.N * D.Kh) : make_uint4(0, 0, 0, 0);
   };
   auto next_head = [&](int h) { h++; if (h == D.skip_head) h++; return h; };
 
@@ -106,6 +111,7 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
     if (EXACT) {
 #pragma unroll
       for (int kk = 0; kk < 4; kk++) {
+        if (kk >= nkk) break;
         v8h ha[TM];
 #pragma unroll
         for (int i = 0; i < TM; i++) {

@@ -93,11 +93,60 @@ hipError_t launch_embed(const int* tok, const float* W_E, const float* W_pos, fl
 }
 
 // ------------------------------------------------------------------ norm + quantise of one row held by a wave
-// x[j] is element (lane + 64*j) of the row, j < E.
-template <int MAXE>
+// A wavefront holds one row of d = 64 E floats in registers x[0 .. E).  Two
+// element-to-lane maps: the plain one (x[j] = element lane + 64 j, any E) and
+// the vector one for E % 4 == 0 (x[4q + c] = element 4 (64 q + lane) + c), where
+// every access is a 16-byte load or store and four codes leave as one word.
+// All kernels of a launch family use the same map, so a row that enters two of
+// them with the same values leaves with the same bits.
+template <int MAXE, bool VEC>
+__device__ __forceinline__ void row_load(float (&x)[MAXE], const float* p, int E, int lane) {
+  if (VEC) {
+#pragma unroll
+    for (int q = 0; q < MAXE / 4; q++) if (4 * q < E) {
+      float4 v = *(const float4*)(p + (q * 64 + lane) * 4);
+      x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) x[j] = p[lane + 64 * j];
+  }
+}
+// x += sign * p   (sign = +-1: the product is exact)
+template <int MAXE, bool VEC>
+__device__ __forceinline__ void row_axpy(float (&x)[MAXE], float sign, const float* p, int E, int lane) {
+  if (VEC) {
+#pragma unroll
+    for (int q = 0; q < MAXE / 4; q++) if (4 * q < E) {
+      float4 v = *(const float4*)(p + (q * 64 + lane) * 4);
+      x[4 * q] += sign * v.x; x[4 * q + 1] += sign * v.y; x[4 * q + 2] += sign * v.z; x[4 * q + 3] += sign * v.w;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) x[j] += sign * p[lane + 64 * j];
+  }
+}
+// y = a - p
+template <int MAXE, bool VEC>
+__device__ __forceinline__ void row_sub(float (&y)[MAXE], const float (&a)[MAXE], const float* p, int E, int lane) {
+  if (VEC) {
+#pragma unroll
+    for (int q = 0; q < MAXE / 4; q++) if (4 * q < E) {
+      float4 v = *(const float4*)(p + (q * 64 + lane) * 4);
+      y[4 * q] = a[4 * q] - v.x; y[4 * q + 1] = a[4 * q + 1] - v.y;
+      y[4 * q + 2] = a[4 * q + 2] - v.z; y[4 * q + 3] = a[4 * q + 3] - v.w;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) y[j] = a[j] - p[lane + 64 * j];
+  }
+}
+
+template <int MAXE, bool VEC>
 __device__ __forceinline__ void norm_row(float (&x)[MAXE], int E, int d, int lane, int norm_kind, float eps,
                                          const float* gain, const float* offset) {
   float inv_d = 1.0f / (float)d;
+  float rstd;
   if (norm_kind == 0) {
     float s = 0.f;
 #pragma unroll
@@ -106,29 +155,38 @@ __device__ __forceinline__ void norm_row(float (&x)[MAXE], int E, int d, int lan
     float v = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXE; j++) if (j < E) { x[j] -= mean; v += x[j] * x[j]; }
-    float rstd = 1.0f / sqrtf(wave_sum(v) * inv_d + eps);
-#pragma unroll
-    for (int j = 0; j < MAXE; j++) if (j < E) {
-      int e = lane + 64 * j;
-      x[j] = x[j] * rstd * gain[e] + offset[e];
-    }
+    rstd = 1.0f / sqrtf(wave_sum(v) * inv_d + eps);
   } else {
     float v = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXE; j++) if (j < E) v += x[j] * x[j];
-    float rstd = 1.0f / sqrtf(wave_sum(v) * inv_d + eps);
+    rstd = 1.0f / sqrtf(wave_sum(v) * inv_d + eps);
+  }
+  float gn[MAXE], of[MAXE];
+  row_load<MAXE, VEC>(gn, gain, E, lane);
+  if (norm_kind == 0) {
+    row_load<MAXE, VEC>(of, offset, E, lane);
 #pragma unroll
-    for (int j = 0; j < MAXE; j++) if (j < E) x[j] = x[j] * rstd * gain[lane + 64 * j];
+    for (int j = 0; j < MAXE; j++) if (j < E) x[j] = x[j] * rstd * gn[j] + of[j];
+  } else {
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) if (j < E) x[j] = x[j] * rstd * gn[j];
   }
 }
 
-template <int MAXE>
+template <int MAXE, bool VEC>
 __device__ __forceinline__ void emit_row(const float (&y)[MAXE], int E, int d, int lane, const GroupDesc& g,
                                          int inst, int row, int ldq) {
   if (g.out_f32) {
     float* o = g.out_f32 + inst * g.out_f32_is + (long long)row * d;
+    if (VEC) {
 #pragma unroll
-    for (int j = 0; j < MAXE; j++) if (j < E) o[lane + 64 * j] = y[j];
+      for (int q = 0; q < MAXE / 4; q++) if (4 * q < E)
+        *(float4*)(o + (q * 64 + lane) * 4) = make_float4(y[4 * q], y[4 * q + 1], y[4 * q + 2], y[4 * q + 3]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < MAXE; j++) if (j < E) o[lane + 64 * j] = y[j];
+    }
   }
   if (g.out_codes) {
     float am = 0.f;
@@ -138,13 +196,22 @@ __device__ __forceinline__ void emit_row(const float (&y)[MAXE], int E, int d, i
     float scale = (am == 0.f) ? 1.0f : am / 448.0f;
     float inv = 1.0f / scale;
     uint8_t* o = g.out_codes + inst * g.out_codes_is + (long long)row * ldq;
+    if (VEC) {
 #pragma unroll
-    for (int j = 0; j < MAXE; j++) if (j < E) o[lane + 64 * j] = (uint8_t)e4m3_encode(y[j] * inv);
+      for (int q = 0; q < MAXE / 4; q++) if (4 * q < E) {
+        uint32_t w = e4m3_encode(y[4 * q] * inv) | (e4m3_encode(y[4 * q + 1] * inv) << 8) |
+                     (e4m3_encode(y[4 * q + 2] * inv) << 16) | (e4m3_encode(y[4 * q + 3] * inv) << 24);
+        *(uint32_t*)(o + (q * 64 + lane) * 4) = w;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < MAXE; j++) if (j < E) o[lane + 64 * j] = (uint8_t)e4m3_encode(y[j] * inv);
+    }
     if (lane == 0) g.out_scale[inst * g.out_scale_is + row] = scale;
   }
 }
 
-template <int MAXE>
+template <int MAXE, bool VEC>
 __global__ __launch_bounds__(256) void build_inputs_k(const GroupDesc* groups, const Term* terms, int T, int B,
                                                        int S, int d, int ldq, int norm_kind, float eps) {
   GroupDesc g = groups[blockIdx.y];
@@ -158,27 +225,17 @@ __global__ __launch_bounds__(256) void build_inputs_k(const GroupDesc* groups, c
   float x[MAXE];
 #pragma unroll
   for (int j = 0; j < MAXE; j++) x[j] = 0.f;
-  if (g.base) {
-    const float* p = g.base + inst * g.base_is + src;
-#pragma unroll
-    for (int j = 0; j < MAXE; j++) if (j < E) x[j] = p[lane + 64 * j];
-  }
-  if (g.run) {
-    const float* p = g.run + inst * g.run_is + src;
-#pragma unroll
-    for (int j = 0; j < MAXE; j++) if (j < E) x[j] += p[lane + 64 * j];
-  }
+  if (g.base) row_load<MAXE, VEC>(x, g.base + inst * g.base_is + src, E, lane);
+  if (g.run) row_axpy<MAXE, VEC>(x, 1.0f, g.run + inst * g.run_is + src, E, lane);
   for (int t = 0; t < g.term_count; t++) {
     Term tm = terms[g.term_begin + t];
-    const float* p = tm.p + inst * tm.inst_stride + src;
-#pragma unroll
-    for (int j = 0; j < MAXE; j++) if (j < E) x[j] += tm.sign * p[lane + 64 * j];
+    row_axpy<MAXE, VEC>(x, tm.sign, tm.p + inst * tm.inst_stride + src, E, lane);
   }
-  norm_row<MAXE>(x, E, d, lane, norm_kind, eps, g.gain, g.offset);
-  emit_row<MAXE>(x, E, d, lane, g, inst, row, ldq);
+  norm_row<MAXE, VEC>(x, E, d, lane, norm_kind, eps, g.gain, g.offset);
+  emit_row<MAXE, VEC>(x, E, d, lane, g, inst, row, ldq);
 }
 
-template <int MAXE>
+template <int MAXE, bool VEC>
 __global__ __launch_bounds__(256) void patch_build_k(const GroupDesc* gp, const float* xv, const float* delta0,
                                                       long long delta_stride, const int* send, int n_inst, int mode,
                                                       int T, int B, int S, int d, int ldq, int norm_kind,
@@ -192,22 +249,23 @@ __global__ __launch_bounds__(256) void patch_build_k(const GroupDesc* gp, const 
   int E = d >> 6;
   float x0[MAXE], y[MAXE];
 #pragma unroll
-  for (int j = 0; j < MAXE; j++) x0[j] = (j < E) ? xv[src + lane + 64 * j] : 0.f;
+  for (int j = 0; j < MAXE; j++) x0[j] = 0.f;
+  row_load<MAXE, VEC>(x0, xv + src, E, lane);
   for (int i = 0; i < n_inst; i++) {
-    const float* dp = delta0 + (long long)send[i] * delta_stride + src;
 #pragma unroll
-    for (int j = 0; j < MAXE; j++) if (j < E) y[j] = x0[j] - dp[lane + 64 * j];
+    for (int j = 0; j < MAXE; j++) y[j] = 0.f;
+    row_sub<MAXE, VEC>(y, x0, delta0 + (long long)send[i] * delta_stride + src, E, lane);
     if (mode == 2) {
 #pragma unroll
       for (int j = 0; j < MAXE; j++) x0[j] = y[j];
     }
-    norm_row<MAXE>(y, E, d, lane, norm_kind, eps, g.gain, g.offset);
-    emit_row<MAXE>(y, E, d, lane, g, i, row, ldq);
+    norm_row<MAXE, VEC>(y, E, d, lane, norm_kind, eps, g.gain, g.offset);
+    emit_row<MAXE, VEC>(y, E, d, lane, g, i, row, ldq);
   }
 }
 
 // Independent candidates (x_i = xv - delta[send[i]]): one wavefront per (row, instance).
-template <int MAXE>
+template <int MAXE, bool VEC>
 __global__ __launch_bounds__(256) void patch_indep_k(const GroupDesc* gp, const float* xv, const float* delta0,
                                                       long long delta_stride, const int* send, int T, int B, int S,
                                                       int d, int ldq, int norm_kind, float eps) {
@@ -219,30 +277,39 @@ __global__ __launch_bounds__(256) void patch_indep_k(const GroupDesc* gp, const 
   if (row >= rows) return;
   long long src = (long long)(g.last_only ? row * S + S - 1 : row) * d;
   int E = d >> 6;
-  const float* dp = delta0 + (long long)send[inst] * delta_stride + src;
-  float y[MAXE];
+  float x0[MAXE], y[MAXE];
 #pragma unroll
-  for (int j = 0; j < MAXE; j++) y[j] = (j < E) ? xv[src + lane + 64 * j] - dp[lane + 64 * j] : 0.f;
-  norm_row<MAXE>(y, E, d, lane, norm_kind, eps, g.gain, g.offset);
-  emit_row<MAXE>(y, E, d, lane, g, inst, row, ldq);
+  for (int j = 0; j < MAXE; j++) { x0[j] = 0.f; y[j] = 0.f; }
+  row_load<MAXE, VEC>(x0, xv + src, E, lane);
+  row_sub<MAXE, VEC>(y, x0, delta0 + (long long)send[inst] * delta_stride + src, E, lane);
+  norm_row<MAXE, VEC>(y, E, d, lane, norm_kind, eps, g.gain, g.offset);
+  emit_row<MAXE, VEC>(y, E, d, lane, g, inst, row, ldq);
 }
 
+// E % 4 == 0 takes the vector element map (all tiles, gains and code rows are 16-byte aligned
+// there: d is a multiple of 256 floats and every buffer starts on a 256-byte boundary).
 #define PAHQ_DISPATCH_E(E, CALL)                                    \
   do {                                                              \
-    if ((E) <= 1) { CALL(1); }                                      \
-    else if ((E) <= 4) { CALL(4); }                                 \
-    else if ((E) <= 8) { CALL(8); }                                 \
-    else if ((E) <= 12) { CALL(12); }                               \
-    else if ((E) <= 16) { CALL(16); }                               \
-    else if ((E) <= 32) { CALL(32); }                               \
-    else { CALL(64); }                                              \
+    if ((E) == 4) { CALL(4, true); }                                \
+    else if ((E) == 8) { CALL(8, true); }                           \
+    else if ((E) == 12) { CALL(12, true); }                         \
+    else if ((E) == 16) { CALL(16, true); }                         \
+    else if ((E) % 4 == 0 && (E) <= 32) { CALL(32, true); }         \
+    else if ((E) % 4 == 0) { CALL(64, true); }                      \
+    else if ((E) <= 1) { CALL(1, false); }                          \
+    else if ((E) <= 4) { CALL(4, false); }                          \
+    else if ((E) <= 8) { CALL(8, false); }                          \
+    else if ((E) <= 12) { CALL(12, false); }                        \
+    else if ((E) <= 16) { CALL(16, false); }                        \
+    else if ((E) <= 32) { CALL(32, false); }                        \
+    else { CALL(64, false); }                                       \
   } while (0)
 
 hipError_t launch_build_inputs(const GroupDesc* groups, int n_groups, const Term* terms, int n_inst, int T, int B,
                                int S, int d, int ldq, int norm_kind, float eps, hipStream_t s) {
   if (n_groups == 0 || n_inst == 0) return hipSuccess;
   dim3 grid((T + 3) / 4, n_groups, n_inst);
-#define CALL(M) hipLaunchKernelGGL(build_inputs_k<M>, grid, dim3(256), 0, s, groups, terms, T, B, S, d, ldq, norm_kind, eps)
+#define CALL(M, V) hipLaunchKernelGGL((build_inputs_k<M, V>), grid, dim3(256), 0, s, groups, terms, T, B, S, d, ldq, norm_kind, eps)
   PAHQ_DISPATCH_E(d / 64, CALL);
 #undef CALL
   return hipGetLastError();
@@ -254,13 +321,13 @@ hipError_t launch_patch_build(const GroupDesc* g, const float* xv, const float* 
   if (n_inst == 0) return hipSuccess;
   if (mode == 1) {
     dim3 grid2((T + 3) / 4, n_inst);
-#define CALL(M) hipLaunchKernelGGL(patch_indep_k<M>, grid2, dim3(256), 0, s, g, xv, delta0, delta_stride, send, T, B, S, d, ldq, norm_kind, eps)
+#define CALL(M, V) hipLaunchKernelGGL((patch_indep_k<M, V>), grid2, dim3(256), 0, s, g, xv, delta0, delta_stride, send, T, B, S, d, ldq, norm_kind, eps)
     PAHQ_DISPATCH_E(d / 64, CALL);
 #undef CALL
     return hipGetLastError();
   }
   dim3 grid((T + 3) / 4);
-#define CALL(M) hipLaunchKernelGGL(patch_build_k<M>, grid, dim3(256), 0, s, g, xv, delta0, delta_stride, send, n_inst, mode, T, B, S, d, ldq, norm_kind, eps)
+#define CALL(M, V) hipLaunchKernelGGL((patch_build_k<M, V>), grid, dim3(256), 0, s, g, xv, delta0, delta_stride, send, n_inst, mode, T, B, S, d, ldq, norm_kind, eps)
   PAHQ_DISPATCH_E(d / 64, CALL);
 #undef CALL
   return hipGetLastError();
@@ -371,19 +438,84 @@ __global__ __launch_bounds__(256) void hidden_quant_k(const float* up, const flo
   for (int i = threadIdx.x; i < m; i += 256) o[i] = (uint8_t)e4m3_encode(hidden_value(pu, pg, i, swiglu) * inv);
   if (threadIdx.x == 0) scale[inst * s_is + row] = sc;
 }
+// The same quantiser for rows of 4-float multiples: TPR threads own a row (a wavefront, or the
+// whole block for long rows), the row is read once with 16-byte loads and stays in registers
+// between the abs-max and the encode, and four codes leave as one 32-bit store.
+template <int TPR, int NV>
+__global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const float* gate, long long h_is,
+                                                          uint8_t* codes, long long c_is, float* scale,
+                                                          long long s_is, int T, int m, int ldq, int swiglu) {
+  constexpr int RPB = 256 / TPR;
+  __shared__ float red[4];
+  const int inst = blockIdx.y;
+  const int row = blockIdx.x * RPB + (TPR == 64 ? (int)(threadIdx.x >> 6) : 0);
+  const int t = (TPR == 64) ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
+  const bool live = row < T;
+  const float* pu = up + inst * h_is + (long long)row * m;
+  const float* pg = gate ? gate + inst * h_is + (long long)row * m : nullptr;
+  float4 v[NV];
+  float am = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; j++) {
+    int e = (j * TPR + t) * 4;
+    v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (live && e < m) {
+      v[j] = *(const float4*)(pu + e);
+      if (swiglu) {
+        float4 g = *(const float4*)(pg + e);
+        v[j].x = g.x / (1.0f + expf(-g.x)) * v[j].x;
+        v[j].y = g.y / (1.0f + expf(-g.y)) * v[j].y;
+        v[j].z = g.z / (1.0f + expf(-g.z)) * v[j].z;
+        v[j].w = g.w / (1.0f + expf(-g.w)) * v[j].w;
+      }
+    }
+    am = fmaxf(fmaxf(am, fmaxf(fabsf(v[j].x), fabsf(v[j].y))), fmaxf(fabsf(v[j].z), fabsf(v[j].w)));
+  }
+  am = wave_max(am);
+  if (TPR == 256) {
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = am;
+    __syncthreads();
+    am = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  }
+  if (!live) return;
+  const float sc = (am == 0.f) ? 1.0f : am / 448.0f;
+  const float inv = 1.0f / sc;
+  uint8_t* o = codes + inst * c_is + (long long)row * ldq;
+#pragma unroll
+  for (int j = 0; j < NV; j++) {
+    int e = (j * TPR + t) * 4;
+    if (e < m) {
+      uint32_t w = e4m3_encode(v[j].x * inv) | (e4m3_encode(v[j].y * inv) << 8) | (e4m3_encode(v[j].z * inv) << 16) |
+                   (e4m3_encode(v[j].w * inv) << 24);
+      *(uint32_t*)(o + e) = w;
+    }
+  }
+  if (t == 0) scale[inst * s_is + row] = sc;
+}
+
 hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_is, uint8_t* codes, long long c_is,
                                float* scale, long long s_is, int n_inst, int T, int m, int ldq, int swiglu,
                                hipStream_t s) {
-  hipLaunchKernelGGL(hidden_quant_k, dim3(T, n_inst), dim3(256), 0, s, up, gate, h_is, codes, c_is, scale, s_is,
-                     T, m, ldq, swiglu);
+  const bool vec = (m % 4 == 0) && (ldq % 4 == 0) && (h_is % 4 == 0) && (c_is % 4 == 0) &&
+                   ((((uintptr_t)up) | ((uintptr_t)gate)) % 16 == 0) && (((uintptr_t)codes) % 4 == 0);
+#define HQV(TPR_, NV_)                                                                                              \
+  hipLaunchKernelGGL((hidden_quant_vec_k<TPR_, NV_>), dim3((T + 256 / TPR_ - 1) / (256 / TPR_), n_inst), dim3(256), \
+                     0, s, up, gate, h_is, codes, c_is, scale, s_is, T, m, ldq, swiglu)
+  if (vec && m <= 64 * 4 * 8) HQV(64, 8);
+  else if (vec && m <= 64 * 4 * 12) HQV(64, 12);
+  else if (vec && m <= 64 * 4 * 16) HQV(64, 16);
+  else if (vec && m <= 256 * 4 * 8) HQV(256, 8);
+  else if (vec && m <= 256 * 4 * 12) HQV(256, 12);
+  else
+    hipLaunchKernelGGL(hidden_quant_k, dim3(T, n_inst), dim3(256), 0, s, up, gate, h_is, codes, c_is, scale, s_is,
+                       T, m, ldq, swiglu);
+#undef HQV
   return hipGetLastError();
 }
 
 hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales,
                                    hipStream_t s) {
-  hipLaunchKernelGGL(hidden_quant_k, dim3(rows, 1), dim3(256), 0, s, x, (const float*)nullptr, 0LL, codes, 0LL,
-                     scales, 0LL, rows, cols, cols, 0);
-  return hipGetLastError();
+  return launch_hidden_quant(x, nullptr, 0LL, codes, 0LL, scales, 0LL, 1, rows, cols, cols, 0, s);
 }
 
 }  // namespace pahq

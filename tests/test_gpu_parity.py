@@ -96,7 +96,7 @@ def test_weight_codes_and_scales_bit_exact(cfg1, mid_llama):
 
 def test_row_quantiser_bit_exact(cfg1):
     rng = np.random.default_rng(5)
-    for cols in (64, 100, 768, 3072, 11008):
+    for cols in (64, 100, 101, 768, 3072, 4096, 11008, 12290):
         x = (rng.standard_normal((37, cols)) * rng.uniform(1e-4, 300, (37, 1))).astype(np.float32)
         x[3] = 0
         x[4, :] = np.float32(1e-30)                     # tiny row
