@@ -14,6 +14,7 @@
 // position comes from the cache (clean - corrupt); for recomputed senders it is
 // written by the kernel that adds the sender's output to the stream.
 #include "engine.h"
+#include <stdio.h>
 #include <map>
 #include <string.h>
 
@@ -543,6 +544,13 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
                                   M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
         break;
       case OP_GEMM8:
+        for (int q = 0; q < o.i1; q++)
+          if (!gemm8_prob_ok(b.probs[o.i0 + q])) {
+            const GemmProb& p = b.probs[o.i0 + q];
+            fprintf(stderr, "pahq: fp8 GEMM problem rejected: M %d N %d K %d lda %d ldw %d ldc %d a_is %lld c_is %lld add_is %lld aux_is %lld wsb %d A %p W %p C %p add %p aux %p sub %p bias %p\n",
+                    p.M, p.N, p.K, p.lda, p.ldw, p.ldc, p.a_is, p.c_is, p.add_is, p.aux_is, p.wscale_block, p.A, p.W, (void*)p.C, (void*)p.add, (void*)p.aux, (void*)p.aux_sub, (void*)p.bias);
+            return PAHQ_EINVAL;
+          }
         HIPCHK(launch_gemm_fp8(d_probs + o.i0, o.i1, o.i2, o.i3, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
         break;
       case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, o.i2, o.i3, st)); break;

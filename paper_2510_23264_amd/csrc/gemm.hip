@@ -50,6 +50,19 @@ __device__ __forceinline__ v8h decode8(uint32_t w0, uint32_t w1) {
 
 #define LDS_ROW 144   // gemm_fp8_k: 128 data bytes + 16 pad
 
+// Pointers that arrive inside GemmProb are generic to the compiler; every one of them points to
+// global memory.  Saying so turns FLAT accesses (which may touch LDS and therefore wait for the
+// slab loads in flight) into GLOBAL ones.
+#define GCF(p) ((const __attribute__((address_space(1))) float*)(p))
+#define GF(p) ((__attribute__((address_space(1))) float*)(p))
+__device__ __forceinline__ float4 gload4(const float* p) {
+  v4f v = *(const __attribute__((address_space(1))) v4f*)p;
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void gstore4(float* p, float4 v) {
+  *(__attribute__((address_space(1))) v4f*)p = (v4f){v.x, v.y, v.z, v.w};
+}
+
 // XCD-aware tile order: workgroup id w runs on XCD w % 8; that XCD gets the
 // contiguous range [x * chunk, (x+1) * chunk) of the linear tile index.
 __device__ __forceinline__ int xcd_tile(int wg, int total) {
@@ -62,15 +75,15 @@ __device__ __forceinline__ void epilogue_store(const GemmProb& P, int n, float a
                                                int r) {
   float val = acc * (sa * sw);
   float v = val;
-  if (P.bias) v += P.bias[n];
+  if (P.bias) v += GCF(P.bias)[n];
   if (P.act == 1) v = gelu_tanh(v);
   long long off = (long long)r * P.ldc + n;
-  if (P.add) v += P.add[inst * P.add_is + off];
-  P.C[inst * P.c_is + off] = v;
+  if (P.add) v += GCF(P.add)[inst * P.add_is + off];
+  GF(P.C)[inst * P.c_is + off] = v;
   if (P.aux) {
     float x = val;
-    if (P.aux_sub) x -= P.aux_sub[off];
-    P.aux[inst * P.aux_is + off] = x;
+    if (P.aux_sub) x -= GCF(P.aux_sub)[off];
+    GF(P.aux)[inst * P.aux_is + off] = x;
   }
 }
 
@@ -90,25 +103,32 @@ __device__ __forceinline__ void epi_prefetch(EpiPre<TM, TN>& E, const GemmProb& 
     int m = min(mbase + i * 16 + li, P.M - 1);
     E.inst[i] = m / P.rpi;
     E.row[i] = m - E.inst[i] * P.rpi;
-    E.sa[i] = P.ascale[E.inst[i] * P.as_is + (long long)E.row[i] * P.as_stride];
+    E.sa[i] = GCF(P.ascale)[E.inst[i] * P.as_is + (long long)E.row[i] * P.as_stride];
   }
 #pragma unroll
   for (int j = 0; j < TN; j++) {
     int nb = min(nbase + j * 16 + lg * 4, P.N - 1);
-    E.sw[j] = P.wscale[nb / P.wscale_block];
+    E.sw[j] = GCF(P.wscale)[nb / P.wscale_block];
   }
 }
 // acc[i][j] holds, for lane (li, lg), row mbase + 16 i + li and columns nbase + 16 j + 4 lg .. + 3.
+// Every store is 16 bytes: rows, instance strides and pointers are 16-byte aligned and a last,
+// partial group of columns is written whole into the padding the row has behind column N
+// (gemm8_prob_ok on the host guarantees all of this).
 template <int TM, int TN>
 __device__ __forceinline__ void epi_store(const EpiPre<TM, TN>& E, const GemmProb& P, const v4f (&acc)[TM][TN],
                                           int mbase, int nbase, int li, int lg) {
-  const bool vec = ((P.ldc & 3) == 0) && ((P.wscale_block & 3) == 0) && (((P.c_is | P.add_is | P.aux_is) & 3) == 0) &&
-                   ((((uintptr_t)P.C | (uintptr_t)P.add | (uintptr_t)P.aux | (uintptr_t)P.aux_sub | (uintptr_t)P.bias) & 15) == 0);
   float4 bias[TN];
 #pragma unroll
   for (int j = 0; j < TN; j++) {
     int nb = nbase + j * 16 + lg * 4;
-    bias[j] = (P.bias && vec && nb + 3 < P.N) ? *(const float4*)(P.bias + nb) : make_float4(0.f, 0.f, 0.f, 0.f);
+    bias[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (P.bias && nb + 3 < P.N) bias[j] = gload4(P.bias + nb);
+    else if (P.bias && nb < P.N) {
+      bias[j].x = GCF(P.bias)[nb];
+      if (nb + 1 < P.N) bias[j].y = GCF(P.bias)[nb + 1];
+      if (nb + 2 < P.N) bias[j].z = GCF(P.bias)[nb + 2];
+    }
   }
 #pragma unroll
   for (int i = 0; i < TM; i++) {
@@ -119,24 +139,17 @@ __device__ __forceinline__ void epi_store(const EpiPre<TM, TN>& E, const GemmPro
     for (int j = 0; j < TN; j++) {
       int nb = nbase + j * 16 + lg * 4;
       if (nb >= P.N) continue;
-      if (vec && nb + 3 < P.N) {
-        float s2 = sa * E.sw[j];
-        float4 val = make_float4(acc[i][j][0] * s2, acc[i][j][1] * s2, acc[i][j][2] * s2, acc[i][j][3] * s2);
-        float4 v = make_float4(val.x + bias[j].x, val.y + bias[j].y, val.z + bias[j].z, val.w + bias[j].w);
-        if (!P.bias) v = val;                  // keeps the sign of a zero result when there is no bias
-        if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
-        long long off = (long long)row * P.ldc + nb;
-        if (P.add) { float4 a = *(const float4*)(P.add + inst * P.add_is + off); v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w; }
-        *(float4*)(P.C + inst * P.c_is + off) = v;
-        if (P.aux) {
-          if (P.aux_sub) { float4 u = *(const float4*)(P.aux_sub + off); val.x -= u.x; val.y -= u.y; val.z -= u.z; val.w -= u.w; }
-          *(float4*)(P.aux + inst * P.aux_is + off) = val;
-        }
-      } else {
-#pragma unroll
-        for (int r = 0; r < 4; r++)
-          if (nb + r < P.N)
-            epilogue_store(P, nb + r, acc[i][j][r], sa, P.wscale[(nb + r) / P.wscale_block], inst, row);
+      float s2 = sa * E.sw[j];
+      float4 val = make_float4(acc[i][j][0] * s2, acc[i][j][1] * s2, acc[i][j][2] * s2, acc[i][j][3] * s2);
+      float4 v = val;
+      if (P.bias) { v.x += bias[j].x; v.y += bias[j].y; v.z += bias[j].z; v.w += bias[j].w; }
+      if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
+      long long off = (long long)row * P.ldc + nb;
+      if (P.add) { float4 a = gload4(P.add + inst * P.add_is + off); v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w; }
+      gstore4(P.C + inst * P.c_is + off, v);
+      if (P.aux) {
+        if (P.aux_sub) { float4 u = gload4(P.aux_sub + off); val.x -= u.x; val.y -= u.y; val.z -= u.z; val.w -= u.w; }
+        gstore4(P.aux + inst * P.aux_is + off, val);
       }
     }
   }
@@ -150,8 +163,42 @@ __device__ __forceinline__ void epi_store(const EpiPre<TM, TN>& E, const GemmPro
 // Rows past M or N are clamped to the last valid row: they feed only results that are never stored.
 // One 16-byte operand read feeds two MFMA steps: step 2 q + s takes bytes [64 q + 16 g + 8 s, + 8)
 // of every row, the same k positions for both operands.
-typedef __attribute__((address_space(1))) const void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
+//
+// Workgroups are persistent: the gridDim.x / 8 workgroups of an XCD walk that XCD's tile range
+// round-robin.  When a tile's K loop ends, the first slab of the next tile is requested before
+// the results of this one are stored, and for plain problems (no residual add, no second
+// output, interior tile) the next K loop starts while those stores are still in flight: the
+// vector-memory counter retires in issue order, so "at most TM * TN outstanding" means that
+// everything issued before the TM * TN stores -- the slab -- has arrived.
+//
+// The slab loads, the waits for them and the workgroup barriers are written as volatile assembly
+// with a memory clobber.  The compiler's own wait insertion treats a load into LDS as something
+// every later LDS read may depend on wherever control flow merges, and waits for all of them
+// (and for the stores in flight) at exactly the points where this kernel wants them outstanding;
+// __syncthreads() adds a fence that waits for every global store.  What must be ordered is spelled
+// out instead: a wave waits for its own slab loads (s_waitcnt vmcnt) before the barrier that
+// publishes a stage, and has consumed its operand reads (their values fed MFMAs) before the
+// barrier that frees it.  Waits the compiler adds for ordinary loads count fewer operations than
+// are in flight, which only makes them stricter.
+__device__ __forceinline__ void slab_load16(const uint8_t* g, uint32_t lds_addr) {
+  // M0 = wave-uniform LDS base; lane l writes bytes [16 l, 16 l + 16) behind it
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm_then_barrier() {     // at most N vector-memory operations outstanding
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+// "Everything has arrived" is said with the builtin, so that the compiler also knows that its own
+// loads (scales, bias) are complete and does not wait for them again in the middle of a slab.
+// 0x0F70: vmcnt(0), expcnt and lgkmcnt left at their maxima.
+__device__ __forceinline__ void wait_all_then_barrier() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  wg_barrier();
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
 
 template <int WAVES_M, int WAVES_N, int TM, int TN>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmProb* probs) {
@@ -160,16 +207,16 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
   constexpr int NI = ROWS / 8 / NW;            // load instructions per wave and slab (8 rows each)
   constexpr int STAGE = ROWS * 128;
   static_assert(ROWS % (8 * NW) == 0, "rows must split evenly over the waves");
-  // two arrays, always addressed statically: the compiler then knows that the loads in flight
-  // into one stage cannot alias the operand reads of the other and does not wait for them
+  static_assert(TM * TN < 64, "vmcnt has six bits");
   __shared__ __attribute__((aligned(1024))) uint8_t st0[STAGE];
   __shared__ __attribute__((aligned(1024))) uint8_t st1[STAGE];
 
   const GemmProb P = probs[blockIdx.y];
-  const int mt = (P.M + BM - 1) / BM, nt = (P.N + BN - 1) / BN;
-  const int lin = xcd_tile(blockIdx.x, mt * nt);
-  if (lin >= mt * nt) return;
-  const int m0 = (lin / nt) * BM, n0 = (lin % nt) * BN;
+  const int mt = (P.M + BM - 1) / BM, nt = (P.N + BN - 1) / BN, total = mt * nt;
+  const int chunk = (total + 7) >> 3, xcd = blockIdx.x & 7, per = gridDim.x >> 3;
+  const int jend = min(chunk, total - xcd * chunk);
+  int j = blockIdx.x >> 3;
+  if (j >= jend) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -177,37 +224,28 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
 
   const uint8_t* src[NI];
   const int cg = ((lane & 7) ^ (lane >> 3)) * 16;
+  auto set_src = [&](int m0, int n0) {
 #pragma unroll
-  for (int t = 0; t < NI; t++) {
-    int r = 8 * (wave * NI + t) + (lane >> 3);
-    if (r < BM) {
-      int m = min(m0 + r, P.M - 1);
-      src[t] = (const uint8_t*)P.A + (long long)(m / P.rpi) * P.a_is + (long long)(m % P.rpi) * P.lda + cg;
-    } else {
-      int n = min(n0 + r - BM, P.N - 1);
-      src[t] = (const uint8_t*)P.W + (long long)n * P.ldw + cg;
+    for (int t = 0; t < NI; t++) {
+      int r = 8 * (wave * NI + t) + (lane >> 3);
+      if (r < BM) {
+        int m = min(m0 + r, P.M - 1);
+        src[t] = (const uint8_t*)P.A + (long long)(m / P.rpi) * P.a_is + (long long)(m % P.rpi) * P.lda + cg;
+      } else {
+        int n = min(n0 + r - BM, P.N - 1);
+        src[t] = (const uint8_t*)P.W + (long long)n * P.ldw + cg;
+      }
     }
-  }
-  auto issue = [&](uint8_t* st, int k0) {
-#pragma unroll
-    for (int t = 0; t < NI; t++)
-      __builtin_amdgcn_global_load_lds((gptr_t)(src[t] + k0), (lptr_t)(st + (wave * NI + t) * 1024), 16, 0, 0);
   };
-  issue(st0, 0);
-
-  const int mbase = m0 + wm * TM * 16, nbase = n0 + wn * TN * 16;
-  EpiPre<TM, TN> E;
-  epi_prefetch<TM, TN>(E, P, mbase, nbase, li, lg);
+  auto issue = [&](const uint8_t* st, int k0) {
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_addr_of(st) + wave * NI * 1024);
+#pragma unroll
+    for (int t = 0; t < NI; t++) slab_load16(src[t] + k0, base + t * 1024);
+  };
 
   const int offA = (wm * TM * 16 + li) * 128, offB = (BM + wn * TN * 16 + li) * 128;
   const int sw0 = (lg ^ (li & 7)) * 16, sw1 = ((4 + lg) ^ (li & 7)) * 16;
-
   v4f acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; i++)
-#pragma unroll
-    for (int j = 0; j < TN; j++) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
-
   auto compute = [&](const uint8_t* st) {
     const uint8_t* sA = st + offA;
     const uint8_t* sB = st + offB;
@@ -222,31 +260,90 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
         ha[i][1] = decode8(w.z, w.w);
       }
 #pragma unroll
-      for (int j = 0; j < TN; j++) {
-        uint4 w = *(const uint4*)(sB + j * 2048 + sw);
+      for (int jj = 0; jj < TN; jj++) {
+        uint4 w = *(const uint4*)(sB + jj * 2048 + sw);
         v8h hb0 = decode8(w.x, w.y), hb1 = decode8(w.z, w.w);
 #pragma unroll
         for (int i = 0; i < TM; i++) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb0, ha[i][0], acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb1, ha[i][1], acc[i][j], 0, 0, 0);
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb0, ha[i][0], acc[i][jj], 0, 0, 0);
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb1, ha[i][1], acc[i][jj], 0, 0, 0);
         }
       }
     }
   };
 
-  // vmcnt(0) also covers the scale loads above; 0x0F70 = vmcnt 0, expcnt and lgkmcnt left alone
-  for (int k0 = 0; k0 < P.K; k0 += 256) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);          // this wave's part of the slab has landed
-    __syncthreads();                             // ... everyone's has, and the other stage is free
-    if (k0 + 128 < P.K) issue(st1, k0 + 128);
+  const bool plain = !P.add && !P.aux;
+
+  int lin = xcd * chunk + j;
+  int m0 = (lin / nt) * BM, n0 = (lin % nt) * BN;
+  set_src(m0, n0);
+  issue(st0, 0);
+  EpiPre<TM, TN> E;
+  epi_prefetch<TM, TN>(E, P, m0 + wm * TM * 16, n0 + wn * TN * 16, li, lg);
+  bool stores_in_flight = false;
+
+  for (;;) {
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int jj = 0; jj < TN; jj++) acc[i][jj] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    // slab 0 of this tile has landed for every wave (the stores of the previous tile, issued after
+    // it was requested, may still be in flight); st1 is free
+    if (stores_in_flight) wait_vm_then_barrier<TM * TN>();
+    else wait_all_then_barrier();
+    if (128 < P.K) issue(st1, 128);
     compute(st0);
-    if (k0 + 128 >= P.K) break;
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-    if (k0 + 256 < P.K) issue(st0, k0 + 256);
-    compute(st1);
+    for (int k0 = 128; k0 < P.K; k0 += 256) {        // slabs k0 (in st1) and k0 + 128 (in st0)
+      wait_all_then_barrier();                     // the slab has landed for everyone, the other stage is free
+      if (k0 + 128 < P.K) issue(st0, k0 + 128);
+      compute(st1);
+      if (k0 + 128 >= P.K) break;
+      wait_all_then_barrier();
+      if (k0 + 256 < P.K) issue(st1, k0 + 256);
+      compute(st0);
+    }
+
+    const int mbase = m0 + wm * TM * 16, nbase = n0 + wn * TN * 16;
+    const bool interior = (m0 + BM <= P.M) && (n0 + BN <= P.N);
+    const int jn = j + per;
+    const bool more = jn < jend;
+    int m0n = 0, n0n = 0;
+    if (more) { int l2 = xcd * chunk + jn; m0n = (l2 / nt) * BM; n0n = (l2 % nt) * BN; }
+    EpiPre<TM, TN> En = E;
+
+    if (plain && interior) {
+      // everything the stores need is fetched first, then the next slab is requested, then exactly
+      // TM * TN stores are issued by every wave
+      float4 bias[TN];
+#pragma unroll
+      for (int jj = 0; jj < TN; jj++)
+        bias[jj] = P.bias ? gload4(P.bias + nbase + jj * 16 + lg * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+      if (more) epi_prefetch<TM, TN>(En, P, m0n + wm * TM * 16, n0n + wn * TN * 16, li, lg);
+      wait_all_then_barrier();                   // scales and bias are here; every wave is done with both stages
+      if (more) { set_src(m0n, n0n); issue(st0, 0); }
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        float* crow = P.C + E.inst[i] * P.c_is + (long long)E.row[i] * P.ldc + nbase + lg * 4;
+#pragma unroll
+        for (int jj = 0; jj < TN; jj++) {
+          float s2 = E.sa[i] * E.sw[jj];
+          float4 v = make_float4(acc[i][jj][0] * s2, acc[i][jj][1] * s2, acc[i][jj][2] * s2, acc[i][jj][3] * s2);
+          if (P.bias) { v.x += bias[jj].x; v.y += bias[jj].y; v.z += bias[jj].z; v.w += bias[jj].w; }
+          if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
+          gstore4(crow + jj * 16, v);
+        }
+      }
+      stores_in_flight = true;
+    } else {
+      wg_barrier();
+      if (more) { set_src(m0n, n0n); issue(st0, 0); epi_prefetch<TM, TN>(En, P, m0n + wm * TM * 16, n0n + wn * TN * 16, li, lg); }
+      epi_store<TM, TN>(E, P, acc, mbase, nbase, li, lg);
+      stores_in_flight = false;
+    }
+    if (!more) break;
+    E = En; j = jn; m0 = m0n; n0 = n0n;
   }
-  epi_store<TM, TN>(E, P, acc, mbase, nbase, li, lg);
 }
 
 // ------------------------------------------------------------------ FP8 matrix-core instruction
@@ -347,15 +444,19 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_k(const GemmPr
 
 hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, hipStream_t s) {
   if (n_probs == 0 || max_M == 0 || max_N == 0) return hipSuccess;
-  if (exact && max_N > 64) {
-    int tiles = ((max_M + 127) / 128) * ((max_N + 127) / 128);
-    dim3 grid((tiles + 7) / 8 * 8, n_probs);
-    hipLaunchKernelGGL((gemm_x_k<2, 2, 4, 4>), grid, dim3(256), 0, s, probs);
+  if (exact) {
+    // persistent: at most two workgroups per compute unit (64 KB of LDS each), 256 compute units
+    const bool wide = max_N > 64;
+    int tiles = ((max_M + 127) / 128) * (wide ? (max_N + 127) / 128 : (max_N + 63) / 64);
+    int gx = (tiles + 7) / 8 * 8;
+    if (gx > 512) gx = 512;
+    dim3 grid(gx, n_probs);
+    if (wide) hipLaunchKernelGGL((gemm_x_k<2, 2, 4, 4>), grid, dim3(256), 0, s, probs);
+    else hipLaunchKernelGGL((gemm_x_k<4, 1, 2, 4>), grid, dim3(256), 0, s, probs);
   } else {
     int tiles = ((max_M + 127) / 128) * ((max_N + 63) / 64);
     dim3 grid((tiles + 7) / 8 * 8, n_probs);
-    if (exact) hipLaunchKernelGGL((gemm_x_k<4, 1, 2, 4>), grid, dim3(256), 0, s, probs);
-    else hipLaunchKernelGGL((gemm_fp8_k<128, 64, 4, 1>), grid, dim3(256), 0, s, probs);
+    hipLaunchKernelGGL((gemm_fp8_k<128, 64, 4, 1>), grid, dim3(256), 0, s, probs);
   }
   return hipGetLastError();
 }

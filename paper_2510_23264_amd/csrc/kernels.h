@@ -48,6 +48,16 @@ struct GemmProb {
   const float* aux_sub;                                      // instance-independent, row stride ldc; may be null
   int M, N, K, pad_;
 };
+// What the fp8 GEMM kernels assume of a problem (checked on the host before a launch): 16-byte
+// aligned operands and outputs, K a multiple of 128, groups of four columns that share one weight
+// scale, and a row of C that has room for a last partial group of four columns.
+inline bool gemm8_prob_ok(const GemmProb& p) {
+  auto a16 = [](const void* q) { return (((uintptr_t)q) & 15) == 0; };
+  return p.M >= 0 && p.N >= 1 && p.K >= 128 && p.K % 128 == 0 && p.rpi >= 1 && p.lda % 16 == 0 && p.ldw % 16 == 0 &&
+         p.a_is % 16 == 0 && a16(p.A) && a16(p.W) && p.ldc % 4 == 0 && p.c_is % 4 == 0 && p.add_is % 4 == 0 &&
+         p.aux_is % 4 == 0 && (p.wscale_block % 4 == 0 || p.wscale_block >= p.N) && a16(p.C) && a16(p.add) && a16(p.aux) && a16(p.aux_sub) &&
+         a16(p.bias) && (p.N + 3) / 4 * 4 <= p.ldc && p.lda >= p.K && p.ldw >= p.K;
+}
 // For the fp32 GEMM the same struct is used with A = float [..][lda], W = float
 // [K][ldw] (row-major, K rows), ascale / wscale unused (null).
 
