@@ -86,7 +86,7 @@ size_t layout(pahq_model* M, char* base) {
   M->W_gate = (mlp && swi) ? b.take<float>(L * d * m) : nullptr;
   M->W_out = mlp ? b.take<float>(L * m * d) : nullptr; M->b_out = mlp ? b.take<float>(L * d) : nullptr;
   M->lnf_g = b.take<float>(d); M->lnf_b = b.take<float>(d);
-  M->W_U = b.take<float>(d * V); M->b_U = b.take<float>(V);
+  M->W_U = b.take<float>(d * V); M->b_U = b.take<float>(V + 4);     // the GEMM epilogue reads bias in groups of four
   M->zeros_d = b.take<float>(d);
   M->bqkv = b.take<float>(L * 3 * H * dh);
   M->qkv_codes = b.take<uint8_t>(L * 3 * H * dh * Kd); M->qkv_scale = b.take<float>(L * 3 * H);

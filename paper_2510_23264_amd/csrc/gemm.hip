@@ -93,7 +93,8 @@ struct EpiPre {
   float sa[TM];      // row scale of row (mbase + 16 i + li)
   int inst[TM];      // its instance and row within the instance
   int row[TM];
-  float sw[TN];      // column scale of columns nbase + 16 j + 4 lg .. + 3 (one slice when the fast path applies)
+  float sw[TN];      // column scale of columns nbase + 16 j + 4 lg .. + 3 (they share one weight slice)
+  float4 bias[TN];   // bias of those columns (zero without a bias)
 };
 template <int TM, int TN>
 __device__ __forceinline__ void epi_prefetch(EpiPre<TM, TN>& E, const GemmProb& P, int mbase, int nbase, int li,
@@ -107,8 +108,13 @@ __device__ __forceinline__ void epi_prefetch(EpiPre<TM, TN>& E, const GemmProb& 
   }
 #pragma unroll
   for (int j = 0; j < TN; j++) {
-    int nb = min(nbase + j * 16 + lg * 4, P.N - 1);
-    E.sw[j] = GCF(P.wscale)[nb / P.wscale_block];
+    int nb = nbase + j * 16 + lg * 4;
+    E.sw[j] = GCF(P.wscale)[min(nb, P.N - 1) / P.wscale_block];
+    // one 16-byte load, no divergence: a group past the last one re-reads the last one (its results are
+    // never stored), and the last group may read up to three floats behind bias[N - 1] (the bias
+    // arrays of this library are followed by padding; the values land in the padding of the C row)
+    E.bias[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (P.bias) E.bias[j] = gload4(P.bias + min(nb, (P.N - 1) & ~3));
   }
 }
 // acc[i][j] holds, for lane (li, lg), row mbase + 16 i + li and columns nbase + 16 j + 4 lg .. + 3.
@@ -118,18 +124,6 @@ __device__ __forceinline__ void epi_prefetch(EpiPre<TM, TN>& E, const GemmProb& 
 template <int TM, int TN>
 __device__ __forceinline__ void epi_store(const EpiPre<TM, TN>& E, const GemmProb& P, const v4f (&acc)[TM][TN],
                                           int mbase, int nbase, int li, int lg) {
-  float4 bias[TN];
-#pragma unroll
-  for (int j = 0; j < TN; j++) {
-    int nb = nbase + j * 16 + lg * 4;
-    bias[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (P.bias && nb + 3 < P.N) bias[j] = gload4(P.bias + nb);
-    else if (P.bias && nb < P.N) {
-      bias[j].x = GCF(P.bias)[nb];
-      if (nb + 1 < P.N) bias[j].y = GCF(P.bias)[nb + 1];
-      if (nb + 2 < P.N) bias[j].z = GCF(P.bias)[nb + 2];
-    }
-  }
 #pragma unroll
   for (int i = 0; i < TM; i++) {
     if (mbase + i * 16 + li >= P.M) continue;
@@ -142,7 +136,7 @@ __device__ __forceinline__ void epi_store(const EpiPre<TM, TN>& E, const GemmPro
       float s2 = sa * E.sw[j];
       float4 val = make_float4(acc[i][j][0] * s2, acc[i][j][1] * s2, acc[i][j][2] * s2, acc[i][j][3] * s2);
       float4 v = val;
-      if (P.bias) { v.x += bias[j].x; v.y += bias[j].y; v.z += bias[j].z; v.w += bias[j].w; }
+      if (P.bias) { v.x += E.bias[j].x; v.y += E.bias[j].y; v.z += E.bias[j].z; v.w += E.bias[j].w; }
       if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
       long long off = (long long)row * P.ldc + nb;
       if (P.add) { float4 a = gload4(P.add + inst * P.add_is + off); v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w; }
@@ -165,11 +159,9 @@ __device__ __forceinline__ void epi_store(const EpiPre<TM, TN>& E, const GemmPro
 // of every row, the same k positions for both operands.
 //
 // Workgroups are persistent: the gridDim.x / 8 workgroups of an XCD walk that XCD's tile range
-// round-robin.  When a tile's K loop ends, the first slab of the next tile is requested before
-// the results of this one are stored, and for plain problems (no residual add, no second
-// output, interior tile) the next K loop starts while those stores are still in flight: the
-// vector-memory counter retires in issue order, so "at most TM * TN outstanding" means that
-// everything issued before the TM * TN stores -- the slab -- has arrived.
+// round-robin, so that the first slab of the next tile, its scales and its bias can be requested
+// while the last slab of this tile is multiplied, and the next K loop starts while the stores of
+// this tile are still in flight.
 //
 // The slab loads, the waits for them and the workgroup barriers are written as volatile assembly
 // with a memory clobber.  The compiler's own wait insertion treats a load into LDS as something
@@ -184,15 +176,12 @@ __device__ __forceinline__ void slab_load16(const uint8_t* g, uint32_t lds_addr)
   // M0 = wave-uniform LDS base; lane l writes bytes [16 l, 16 l + 16) behind it
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
 }
-template <int N>
-__device__ __forceinline__ void wait_vm_then_barrier() {     // at most N vector-memory operations outstanding
-  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
-}
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 // "Everything has arrived" is said with the builtin, so that the compiler also knows that its own
 // loads (scales, bias) are complete and does not wait for them again in the middle of a slab.
 // 0x0F70: vmcnt(0), expcnt and lgkmcnt left at their maxima.
 __device__ __forceinline__ void wait_all_then_barrier() {
+  asm volatile("" ::: "memory");       // no load may be moved below the wait
   __builtin_amdgcn_s_waitcnt(0x0F70);
   wg_barrier();
 }
@@ -272,15 +261,17 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
     }
   };
 
-  const bool plain = !P.add && !P.aux;
-
   int lin = xcd * chunk + j;
   int m0 = (lin / nt) * BM, n0 = (lin % nt) * BN;
   set_src(m0, n0);
   issue(st0, 0);
-  EpiPre<TM, TN> E;
-  epi_prefetch<TM, TN>(E, P, m0 + wm * TM * 16, n0 + wn * TN * 16, li, lg);
-  bool stores_in_flight = false;
+  // With an even number of slabs the last slab of a tile sits in st1 while st0 is idle: the first
+  // slab of the next tile is requested there, a whole slab of MFMAs before it is needed, and the
+  // K loop of the next tile starts with nothing but a barrier while the stores of this tile are
+  // still in flight.  Row scales, column scales and bias of a tile are requested when its K loop
+  // starts and are waited for together with its second slab.
+  const bool even = (P.K & 255) == 0;
+  bool slab0_here = false;           // this wave's part of slab 0 of the current tile has been waited for
 
   for (;;) {
 #pragma unroll
@@ -288,61 +279,44 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
 #pragma unroll
       for (int jj = 0; jj < TN; jj++) acc[i][jj] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    // slab 0 of this tile has landed for every wave (the stores of the previous tile, issued after
-    // it was requested, may still be in flight); st1 is free
-    if (stores_in_flight) wait_vm_then_barrier<TM * TN>();
+    const int mbase = m0 + wm * TM * 16, nbase = n0 + wn * TN * 16;
+    const int jn = j + per;
+    const bool more = jn < jend;
+    int m0n = 0, n0n = 0;
+    if (more) { int l2 = xcd * chunk + jn; m0n = (l2 / nt) * BM; n0n = (l2 % nt) * BN; }
+    const bool early = even && more;
+
+    // slab 0 has landed for every wave; st1 is free
+    if (slab0_here) wg_barrier();
     else wait_all_then_barrier();
     if (128 < P.K) issue(st1, 128);
+    EpiPre<TM, TN> E;
+    epi_prefetch<TM, TN>(E, P, mbase, nbase, li, lg);
     compute(st0);
     for (int k0 = 128; k0 < P.K; k0 += 256) {        // slabs k0 (in st1) and k0 + 128 (in st0)
-      wait_all_then_barrier();                     // the slab has landed for everyone, the other stage is free
-      if (k0 + 128 < P.K) issue(st0, k0 + 128);
+      wait_all_then_barrier();                       // the slab has landed for everyone, the other stage is free
+      const bool last = k0 + 128 >= P.K;
+      if (!last) issue(st0, k0 + 128);
+      else if (early) { set_src(m0n, n0n); issue(st0, 0); }
       compute(st1);
-      if (k0 + 128 >= P.K) break;
+      if (last) break;
       wait_all_then_barrier();
       if (k0 + 256 < P.K) issue(st1, k0 + 256);
       compute(st0);
     }
 
-    const int mbase = m0 + wm * TM * 16, nbase = n0 + wn * TN * 16;
-    const bool interior = (m0 + BM <= P.M) && (n0 + BN <= P.N);
-    const int jn = j + per;
-    const bool more = jn < jend;
-    int m0n = 0, n0n = 0;
-    if (more) { int l2 = xcd * chunk + jn; m0n = (l2 / nt) * BM; n0n = (l2 % nt) * BN; }
-    EpiPre<TM, TN> En = E;
-
-    if (plain && interior) {
-      // everything the stores need is fetched first, then the next slab is requested, then exactly
-      // TM * TN stores are issued by every wave
-      float4 bias[TN];
-#pragma unroll
-      for (int jj = 0; jj < TN; jj++)
-        bias[jj] = P.bias ? gload4(P.bias + nbase + jj * 16 + lg * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-      if (more) epi_prefetch<TM, TN>(En, P, m0n + wm * TM * 16, n0n + wn * TN * 16, li, lg);
-      wait_all_then_barrier();                   // scales and bias are here; every wave is done with both stages
+    if (!early) {
+      wg_barrier();                                  // every wave is done with both stages
       if (more) { set_src(m0n, n0n); issue(st0, 0); }
-#pragma unroll
-      for (int i = 0; i < TM; i++) {
-        float* crow = P.C + E.inst[i] * P.c_is + (long long)E.row[i] * P.ldc + nbase + lg * 4;
-#pragma unroll
-        for (int jj = 0; jj < TN; jj++) {
-          float s2 = E.sa[i] * E.sw[jj];
-          float4 v = make_float4(acc[i][jj][0] * s2, acc[i][jj][1] * s2, acc[i][jj][2] * s2, acc[i][jj][3] * s2);
-          if (P.bias) { v.x += bias[jj].x; v.y += bias[jj].y; v.z += bias[jj].z; v.w += bias[jj].w; }
-          if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
-          gstore4(crow + jj * 16, v);
-        }
-      }
-      stores_in_flight = true;
-    } else {
-      wg_barrier();
-      if (more) { set_src(m0n, n0n); issue(st0, 0); epi_prefetch<TM, TN>(En, P, m0n + wm * TM * 16, n0n + wn * TN * 16, li, lg); }
-      epi_store<TM, TN>(E, P, acc, mbase, nbase, li, lg);
-      stores_in_flight = false;
     }
+    // scales, bias and this wave's part of the next slab 0: requested at least a slab ago when
+    // `early`; after this wait nothing the wave has to wait for precedes the stores
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    epi_store<TM, TN>(E, P, acc, mbase, nbase, li, lg);
     if (!more) break;
-    E = En; j = jn; m0 = m0n; n0 = n0n;
+    slab0_here = true;       // the barrier at the top publishes slab 0
+    j = jn; m0 = m0n; n0 = n0n;
   }
 }
 
