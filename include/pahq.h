@@ -215,6 +215,12 @@ typedef struct {
 } pahq_kernel_stat;
 enum { PAHQ_N_KERNEL_CLASSES = 10 };
 int pahq_set_profiling(pahq_model*, int32_t on);
+/* Restricts what pahq_set_profiling(model, 1) records: only kernel classes whose bit is set in
+ * class_mask, and only in every every_nth_pass-th pass of the executor (1 = every pass).  Two event
+ * records per launch cost a few microseconds each; a benchmark that wants its throughput
+ * undisturbed samples the dominant class only.  Defaults: all classes, every pass.
+ * PAHQ_EINVAL for a null model, an empty mask or every_nth_pass < 1. */
+int pahq_set_profiling_sample(pahq_model*, uint32_t class_mask, int32_t every_nth_pass);
 int pahq_get_profile(pahq_model*, pahq_kernel_stat out[PAHQ_N_KERNEL_CLASSES]);
 
 const char* pahq_strerror(int code);

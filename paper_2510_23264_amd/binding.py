@@ -85,6 +85,7 @@ def lib():
             "pahq_get_sender_output": [C.c_void_p, C.c_int32, C.c_int32, f32p],
             "pahq_get_counters": [C.c_void_p, i64p],
             "pahq_set_profiling": [C.c_void_p, C.c_int32],
+            "pahq_set_profiling_sample": [C.c_void_p, C.c_uint32, C.c_int32],
             "pahq_get_profile": [C.c_void_p, C.POINTER(KernelStat)],
         }
         for name, args in sig.items():
@@ -244,6 +245,11 @@ class Model:
 
     def set_profiling(self, on):
         _chk(lib().pahq_set_profiling(self.h, 1 if on else 0), "pahq_set_profiling")
+
+    def set_profiling_sample(self, classes=None, every_nth_pass=1):
+        """Record only the named kernel classes (None = all), in every n-th pass."""
+        mask = 0xFFFFFFFF if classes is None else sum(1 << KERNEL_CLASSES.index(c) for c in classes)
+        _chk(lib().pahq_set_profiling_sample(self.h, mask, every_nth_pass), "pahq_set_profiling_sample")
 
     def get_profile(self):
         """dict: kernel class -> (launches, ms, algorithmic flops, algorithmic bytes)."""

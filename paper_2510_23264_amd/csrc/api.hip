@@ -57,6 +57,7 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
   M->Kd = pad128(M->d); M->Kh = pad128(M->dh); M->Km = pad128(M->m > 0 ? M->m : 1);
   M->Vp = (M->V + 31) / 32 * 32;      // logits rows start on 128-byte boundaries
   M->nmax = c->max_batch_edges; M->G = 3 * M->H + 1;
+  M->ncap = std::max(M->nmax, 1024);
   M->tile = (long long)M->T * M->d;
 }
 
@@ -97,7 +98,7 @@ size_t layout(pahq_model* M, char* base) {
   M->out_codes = mlp ? b.take<uint8_t>(L * d * Km) : nullptr; M->out_scale = mlp ? b.take<float>(L) : nullptr;
   M->u_codes = b.take<uint8_t>(V * Kd); M->u_scale = b.take<float>(1);
   M->amax_tmp = b.take<unsigned>((L * H + 4 + 3) / 4 * 4); M->flag_tmp = b.take<int>(4);
-  M->tok_clean = b.take<int>(T); M->tok_corrupt = b.take<int>(T); M->send_dev = b.take<int>(n);
+  M->tok_clean = b.take<int>(T); M->tok_corrupt = b.take<int>(T); M->send_dev = b.take<int>(M->ncap);
   M->clean = b.take<float>(Ns * tile); M->corrupt = b.take<float>(Ns * tile); M->delta = b.take<float>((Ns + 1) * tile);   // tile Ns stays zero
   M->rc = b.take<float>((2 * L + 1) * tile); M->rx = b.take<float>((2 * L + 1) * tile);
   M->logits_clean = b.take<float>(B * Vp); M->logits_corrupt = b.take<float>(B * Vp); M->logz_clean = b.take<double>(B);
@@ -117,7 +118,7 @@ size_t layout(pahq_model* M, char* base) {
   M->lastcodes = b.take<uint8_t>(n * B * Kd); M->lastscale = b.take<float>(n * B); M->logits = b.take<float>(n * B * Vp);
   M->pool_tiles = (long long)std::max<size_t>(2 * Ns, 4 * n);
   M->slots = b.take<float>((size_t)M->pool_tiles * tile);
-  M->row_kl = b.take<double>(n * B); M->kl_dev = b.take<double>(n);
+  M->row_kl = b.take<double>(n * B); M->kl_dev = b.take<double>(M->ncap);
   M->arena.slot_bytes = arena_slot_bytes(M);
   for (int i = 0; i < Arena::SLOTS; i++) M->arena.dev[i] = b.take<char>(M->arena.slot_bytes);
   return (b.off + 255) / 256 * 256;
@@ -309,8 +310,8 @@ int pahq_init_model(const pahq_config* c, const pahq_weights* w, int32_t B, int3
   M->arena.next = 0;
   int rc = PAHQ_OK;
   auto fail = [&](int code) { pahq_free(M); return code; };
-  if (hipHostMalloc((void**)&M->kl_host, sizeof(double) * M->nmax, hipHostMallocDefault) != hipSuccess) return fail(PAHQ_EHIP);
-  if (hipHostMalloc((void**)&M->send_host, sizeof(int) * M->nmax, hipHostMallocDefault) != hipSuccess) return fail(PAHQ_EHIP);
+  if (hipHostMalloc((void**)&M->kl_host, sizeof(double) * M->ncap, hipHostMallocDefault) != hipSuccess) return fail(PAHQ_EHIP);
+  if (hipHostMalloc((void**)&M->send_host, sizeof(int) * M->ncap, hipHostMallocDefault) != hipSuccess) return fail(PAHQ_EHIP);
   for (int i = 0; i < Arena::SLOTS; i++) {
     if (hipHostMalloc((void**)&M->arena.host[i], M->arena.slot_bytes, hipHostMallocDefault) != hipSuccess) return fail(PAHQ_EHIP);
     if (hipEventCreateWithFlags(&M->arena.ev[i], hipEventDisableTiming) != hipSuccess) return fail(PAHQ_EHIP);
@@ -419,16 +420,29 @@ int pahq_eval_edges(pahq_model* M, int32_t receiver, const int32_t* sender_ids, 
   if (n == 0) return PAHQ_OK;
   RecvCtx ctx;
   PCHK(setup_receiver(M, receiver, ctx));
+  // Candidates are independent, so the device batches of a call are queued back to back and the
+  // host waits once per ncap candidates: batch b reads its senders from send_dev + off and writes
+  // its results to kl_dev + off.
   for (int pos = 0; pos < n;) {
-    int nb = std::min(ctx.n_eff, n - pos);
-    // an edge that is already removed adds nothing: such a candidate patches with the all-zero tile
-    for (int i = 0; i < nb; i++) {
-      int u = sender_ids[pos + i];
-      M->send_host[i] = M->removed[edge_index(M, u, receiver)] ? M->g.Ns : u;
+    const int chunk = std::min(M->ncap, n - pos);
+    for (int off = 0; off < chunk;) {
+      int nb = std::min(ctx.n_eff, chunk - off);
+      // an edge that is already removed adds nothing: such a candidate patches with the all-zero tile
+      for (int i = 0; i < nb; i++) {
+        int u = sender_ids[pos + off + i];
+        M->send_host[off + i] = M->removed[edge_index(M, u, receiver)] ? M->g.Ns : u;
+      }
+      HIPCHK(hipMemcpyAsync(M->send_dev + off, M->send_host + off, (size_t)nb * sizeof(int), hipMemcpyHostToDevice, M->stream));
+      PassArgs a; a.kind = CAND; a.p0 = ctx.p0; a.n = nb; a.pl = ctx.pl; a.ph = ctx.ph; a.v = ctx.v; a.patch_mode = 1;
+      a.io_off = off;
+      PCHK(run_pass(M, a, &M->plan));
+      M->counters[0] += nb; M->counters[1] += 1;
+      off += nb;
     }
-    PCHK(eval_batch(M, ctx, nb, 1));
-    for (int i = 0; i < nb; i++) kl_out[pos + i] = (float)M->kl_host[i];
-    pos += nb;
+    HIPCHK(hipMemcpyAsync(M->kl_host, M->kl_dev, (size_t)chunk * sizeof(double), hipMemcpyDeviceToHost, M->stream));
+    HIPCHK(hipStreamSynchronize(M->stream));
+    for (int i = 0; i < chunk; i++) kl_out[pos + i] = (float)M->kl_host[i];
+    pos += chunk;
   }
   return PAHQ_OK;
 }
@@ -609,6 +623,12 @@ int pahq_set_profiling(pahq_model* M, int32_t on) {
   if (M->prof_on) PCHK(prof_harvest(M));
   if (on) memset(M->prof, 0, sizeof(M->prof));
   M->prof_on = on != 0;
+  return PAHQ_OK;
+}
+int pahq_set_profiling_sample(pahq_model* M, uint32_t class_mask, int32_t every_nth_pass) {
+  if (!M || every_nth_pass < 1 || (class_mask & ((1u << PAHQ_N_KERNEL_CLASSES) - 1)) == 0) return PAHQ_EINVAL;
+  if (M->prof_on) PCHK(prof_harvest(M));
+  M->prof_mask = class_mask; M->prof_every = every_nth_pass; M->prof_pass = 0;
   return PAHQ_OK;
 }
 int pahq_get_profile(pahq_model* M, pahq_kernel_stat out[PAHQ_N_KERNEL_CLASSES]) {

@@ -34,6 +34,7 @@ struct PassArgs {
   int pl, ph;          // fp32 head (layer, head) or -1
   int v;               // patched receiver (CAND) or -1
   int patch_mode;      // 1 independent, 2 cumulative
+  int io_off = 0;      // first element of send_dev / kl_dev this pass reads / writes
 };
 
 struct Arena {          // descriptor staging: pinned host mirror + device copy, a small ring
@@ -83,6 +84,7 @@ struct pahq_model {
   double *row_kl, *kl_dev;
   double* kl_host;                        // pinned
   int* send_host;                         // pinned
+  int ncap;                               // candidates one host round trip can carry (size of the send / kl arrays)
   pahq::Arena arena;
 
   // host state
@@ -98,6 +100,9 @@ struct pahq_model {
   std::vector<hipEvent_t> prof_ev;        // pairs (start, stop)
   std::vector<int> prof_cls;              // class of each recorded pair
   int prof_used;                          // pairs recorded since the last harvest
+  unsigned prof_mask = 0xFFFFFFFFu;       // kernel classes that are recorded
+  int prof_every = 1;                     // ... in every prof_every-th pass
+  long long prof_pass = 0;                // passes seen while profiling
   pahq_kernel_stat prof[PAHQ_N_KERNEL_CLASSES];
 };
 

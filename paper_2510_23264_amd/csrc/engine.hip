@@ -513,9 +513,10 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
   const int n = a.n, T = M->T, B = M->B, S = M->S, d = M->d;
   hipStream_t st = M->stream;
   static const int cls_of[] = {0, 2, 3, 4, 5, 6, 7, 8, 1, 9};   // OpType -> kernel class
+  const bool prof_pass = M->prof_on && (M->prof_pass++ % M->prof_every) == 0;
   for (const Op& o : b.ops) {
     int pair = -1;
-    if (M->prof_on) {
+    if (prof_pass && ((M->prof_mask >> cls_of[o.t]) & 1u)) {
       if (M->prof_used * 2 + 2 > (int)M->prof_ev.size()) { int r = prof_harvest(M); if (r != PAHQ_OK) return r; }
       pair = M->prof_used++;
       int cls = cls_of[o.t];
@@ -540,7 +541,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         break;
       }
       case OP_PATCH:
-        HIPCHK(launch_patch_build(d_groups + o.i0, M->xv, M->delta, M->tile, M->send_dev, n, a.patch_mode, T, B, S, d,
+        HIPCHK(launch_patch_build(d_groups + o.i0, M->xv, M->delta, M->tile, M->send_dev + a.io_off, n, a.patch_mode, T, B, S, d,
                                   M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
         break;
       case OP_GEMM8:
@@ -569,7 +570,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         break;
       case OP_LOGZ: HIPCHK(launch_logz((const float*)o.p0, B, M->V, M->Vp, (double*)o.p1, st)); break;
       case OP_KL:
-        HIPCHK(launch_kl(M->logits, (long long)B * M->Vp, (const float*)o.p0, (const double*)o.p1, M->row_kl, M->kl_dev,
+        HIPCHK(launch_kl(M->logits, (long long)B * M->Vp, (const float*)o.p0, (const double*)o.p1, M->row_kl, M->kl_dev + a.io_off,
                          n, B, M->V, M->Vp, st));
         break;
     }
