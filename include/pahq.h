@@ -211,7 +211,7 @@ typedef struct {
   int64_t launches;
   double ms;        /* sum of event-to-event times                                   */
   double flops;     /* algorithmic flops (classes 2, 3, 9), else 0                      */
-  double bytes;     /* algorithmic bytes read + written (classes 0, 1, 5, 6, 7, 8)   */
+  double bytes;     /* algorithmic bytes read + written (all classes but 4 and 9)     */
 } pahq_kernel_stat;
 enum { PAHQ_N_KERNEL_CLASSES = 10 };
 int pahq_set_profiling(pahq_model*, int32_t on);

@@ -143,9 +143,19 @@ struct Builder {
   }
   // algorithmic work of the op just added (all instances)
   void work_gemm(int pb) {
-    double f = 0;
-    for (size_t i = pb; i < probs.size(); i++) f += 2.0 * probs[i].M * probs[i].N * (double)probs[i].k_real;
+    // flops of the contraction; bytes that must move: operand codes once (A: M x K, W: N x K; for
+    // the fp32 GEMM four bytes per element), row scales, the fp32 result, and the residual /
+    // second-output tiles when the problem has them
+    double f = 0, by = 0;
+    for (size_t i = pb; i < probs.size(); i++) {
+      const GemmProb& q = probs[i];
+      const double M_ = q.M, N_ = q.N, K_ = q.k_real, eb = q.ascale ? 1.0 : 4.0;
+      f += 2.0 * M_ * N_ * K_;
+      by += eb * (M_ * K_ + N_ * K_) + 4.0 * M_ * N_ + (q.ascale ? 4.0 * M_ : 0.0) + (q.add ? 4.0 * M_ * N_ : 0.0) +
+            (q.aux ? 4.0 * M_ * N_ : 0.0) + (q.aux_sub ? 4.0 * (double)q.rpi * N_ : 0.0);
+    }
     ops.back().flops = f;
+    ops.back().bytes = by;
   }
   void work_build(int g0, int n_groups, int skip = -1) {
     double by = 0;
