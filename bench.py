@@ -31,6 +31,15 @@ PEAKS = {"gemm_fp8": ("mfma", 2500.0, "TFLOP/s"), "oproj_fused": ("mfma", 2500.0
          "gemm_f32": ("mfma", 157.3, "TFLOP/s")}
 HBM_PEAK = 8000.0  # GB/s
 
+# HBM bytes per launch (read, write) from the two rocprofv3 --pmc runs summarised in
+# profiles/hbm_traffic_per_kernel_cfg3_all_edges_pmc.txt (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000, the factors a
+# plain streaming kernel of known size gives in the same runs).  Counters cannot be read from inside this
+# process, so the figures are the committed ones and apply to the default workload only (config 3, batch 64,
+# exact sums); any other invocation reports null.
+PMC_TRAFFIC_MB = {"gemm_fp8": (168.4, 151.3), "hidden_quant": (226.8, 56.8), "attention": (125.0, 12.6),
+                  "kl": (985.1, 0.1), "gather_norm_quant": (48.4, 12.3), "oproj_fused": (104.5, 51.5),
+                  "gemm_f32": (54.5, 32.1), "edge_patch": (100.0, 94.6)}
+
 
 def all_edges_pass(gm, P, cfg, n_recv, stride=1):
     n = 0
@@ -143,6 +152,7 @@ def main():
         if s["bytes"] > 0:
             e["GB/s"] = round(s["bytes"] / (s["ms"] * 1e-3) / 1e9, 1)
         kernels[k] = e
+    default_workload = (args.config == "cfg3" and args.batch == 64 and args.mma == 1 and args.recv_stride == 1)
     s = timed            # the dominant class, measured inside the timed steps (sampled launches)
     if dom in PEAKS:
         bound, peak, unit = PEAKS[dom]
@@ -153,7 +163,10 @@ def main():
         bound, peak, unit = "hbm", HBM_PEAK, "GB/s"
         ach = s["bytes"] / (s["ms"] * 1e-3) / 1e9
     roofline = {"kernel": dom, "bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit,
-                "frac": round(ach / peak, 4), "traffic": None,
+                "frac": round(ach / peak, 4),
+                "traffic": (round(sum(PMC_TRAFFIC_MB[dom]) * 1e6) if default_workload and dom in PMC_TRAFFIC_MB else None),
+                "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated; profiles/)",
+                "algorithmic_bytes_per_launch": (round(s["bytes"] / s["launches"]) if s["bytes"] > 0 else None),
                 "avg_launch_us": round(1e3 * s["ms"] / s["launches"], 2), "launches_measured": s["launches"],
                 "measured": "HIP events on the library's stream around every launch of this class in every third "
                             "executor pass of the timed steps",
