@@ -397,13 +397,13 @@ struct Builder {
     int pb = (int)probs.size();
     probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
                           M->in_codes + (long long)l * m * Kd, Kd, M->in_scale + l, m, M->b_in + (long long)l * m, M->hid,
-                          (long long)T * m, m, M->cfg.act == PAHQ_ACT_GELU ? 1 : 0, T, m, Kd, d));
+                          (long long)T * m, m, 0, T, m, Kd, d));       // the activation is applied by the hidden quantiser
     if (swiglu)
       probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
                             M->gate_codes + (long long)l * m * Kd, Kd, M->gate_scale + l, m, nullptr, M->hid2,
                             (long long)T * m, m, 0, T, m, Kd, d));
     add_op(OP_GEMM8, pb, swiglu ? 2 : 1, T * a.n, m); work_gemm(pb);
-    add_op(OP_HIDQ, swiglu ? 1 : 0);
+    add_op(OP_HIDQ, swiglu ? 2 : (M->cfg.act == PAHQ_ACT_GELU ? 1 : 0));
     ops.back().bytes = (double)a.n * T * m * ((swiglu ? 8.0 : 4.0) + 1.0);
     // output projection fused with the stream update: next = run + b_out + out; the sender's own
     // output (cache passes) or its difference to the corrupted run (a slot some receiver reads)
@@ -575,7 +575,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         HIPCHK(launch_oproj_fused(d_odesc, o.i0, d_haux, o.i1, o.i2, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
         break;
       case OP_HIDQ:
-        HIPCHK(launch_hidden_quant(M->hid, o.i0 ? M->hid2 : nullptr, (long long)T * M->m, M->hcodes, (long long)T * M->Km,
+        HIPCHK(launch_hidden_quant(M->hid, o.i0 == 2 ? M->hid2 : nullptr, (long long)T * M->m, M->hcodes, (long long)T * M->Km,
                                    M->hscale, T, n, T, M->m, M->Km, o.i0, st));
         break;
       case OP_LOGZ: HIPCHK(launch_logz((const float*)o.p0, B, M->V, M->Vp, (double*)o.p1, st)); break;

@@ -141,9 +141,9 @@ hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is
 hipError_t launch_combine(const CombineDesc* descs, int desc_index, const CombineSrc* srcs, int n_inst,
                           long long n_elem, int d, hipStream_t s);
 
-// hidden rows [inst][T][m]: h = up (act 0/1: already activated) or silu(gate) * up (act 2); row-quantise.
+// hidden rows [inst][T][m]: h = up (act 0), tanh-GELU(up) (act 1) or silu(gate) * up (act 2); row-quantise.
 hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_is, uint8_t* codes, long long c_is,
-                               float* scale, long long s_is, int n_inst, int T, int m, int ldq, int swiglu,
+                               float* scale, long long s_is, int n_inst, int T, int m, int ldq, int act,
                                hipStream_t s);
 
 // logz[b] = log(sum_v exp(logits[b][v]))  (double)

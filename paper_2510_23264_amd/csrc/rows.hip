@@ -412,22 +412,25 @@ hipError_t launch_combine(const CombineDesc* descs, int desc_index, const Combin
 }
 
 // ------------------------------------------------------------------ generic row quantiser (one block per row)
-__device__ __forceinline__ float hidden_value(const float* up, const float* gate, long long i, int swiglu) {
-  float u = up[i];
-  if (!swiglu) return u;
-  float g = gate[i];
-  return g / (1.0f + expf(-g)) * u;
+// act: 0 the value as it is, 1 tanh-GELU of it, 2 SwiGLU (silu(gate) * value)
+__device__ __forceinline__ float hidden_act(float u, float g, int act) {
+  if (act == 1) return gelu_tanh(u);
+  if (act == 2) return g / (1.0f + expf(-g)) * u;
+  return u;
+}
+__device__ __forceinline__ float hidden_value(const float* up, const float* gate, long long i, int act) {
+  return hidden_act(up[i], act == 2 ? gate[i] : 0.f, act);
 }
 
 __global__ __launch_bounds__(256) void hidden_quant_k(const float* up, const float* gate, long long h_is,
                                                       uint8_t* codes, long long c_is, float* scale, long long s_is,
-                                                      int T, int m, int ldq, int swiglu) {
+                                                      int T, int m, int ldq, int act) {
   __shared__ float red[4];
   int inst = blockIdx.y, row = blockIdx.x;
   const float* pu = up + inst * h_is + (long long)row * m;
   const float* pg = gate ? gate + inst * h_is + (long long)row * m : nullptr;
   float am = 0.f;
-  for (int i = threadIdx.x; i < m; i += 256) am = fmaxf(am, fabsf(hidden_value(pu, pg, i, swiglu)));
+  for (int i = threadIdx.x; i < m; i += 256) am = fmaxf(am, fabsf(hidden_value(pu, pg, i, act)));
   am = wave_max(am);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = am;
   __syncthreads();
@@ -435,7 +438,7 @@ __global__ __launch_bounds__(256) void hidden_quant_k(const float* up, const flo
   float sc = (am == 0.f) ? 1.0f : am / 448.0f;
   float inv = 1.0f / sc;
   uint8_t* o = codes + inst * c_is + (long long)row * ldq;
-  for (int i = threadIdx.x; i < m; i += 256) o[i] = (uint8_t)e4m3_encode(hidden_value(pu, pg, i, swiglu) * inv);
+  for (int i = threadIdx.x; i < m; i += 256) o[i] = (uint8_t)e4m3_encode(hidden_value(pu, pg, i, act) * inv);
   if (threadIdx.x == 0) scale[inst * s_is + row] = sc;
 }
 // The same quantiser for rows of 4-float multiples: TPR threads own a row (a wavefront, or the
@@ -444,7 +447,7 @@ __global__ __launch_bounds__(256) void hidden_quant_k(const float* up, const flo
 template <int TPR, int NV>
 __global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const float* gate, long long h_is,
                                                           uint8_t* codes, long long c_is, float* scale,
-                                                          long long s_is, int T, int m, int ldq, int swiglu) {
+                                                          long long s_is, int T, int m, int ldq, int act) {
   constexpr int RPB = 256 / TPR;
   __shared__ float red[4];
   const int inst = blockIdx.y;
@@ -461,12 +464,13 @@ __global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const
     v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (live && e < m) {
       v[j] = *(const float4*)(pu + e);
-      if (swiglu) {
-        float4 g = *(const float4*)(pg + e);
-        v[j].x = g.x / (1.0f + expf(-g.x)) * v[j].x;
-        v[j].y = g.y / (1.0f + expf(-g.y)) * v[j].y;
-        v[j].z = g.z / (1.0f + expf(-g.z)) * v[j].z;
-        v[j].w = g.w / (1.0f + expf(-g.w)) * v[j].w;
+      if (act) {
+        float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (act == 2) g = *(const float4*)(pg + e);
+        v[j].x = hidden_act(v[j].x, g.x, act);
+        v[j].y = hidden_act(v[j].y, g.y, act);
+        v[j].z = hidden_act(v[j].z, g.z, act);
+        v[j].w = hidden_act(v[j].w, g.w, act);
       }
     }
     am = fmaxf(fmaxf(am, fmaxf(fabsf(v[j].x), fabsf(v[j].y))), fmaxf(fabsf(v[j].z), fabsf(v[j].w)));
@@ -494,13 +498,13 @@ __global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const
 }
 
 hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_is, uint8_t* codes, long long c_is,
-                               float* scale, long long s_is, int n_inst, int T, int m, int ldq, int swiglu,
+                               float* scale, long long s_is, int n_inst, int T, int m, int ldq, int act,
                                hipStream_t s) {
   const bool vec = (m % 4 == 0) && (ldq % 4 == 0) && (h_is % 4 == 0) && (c_is % 4 == 0) &&
                    ((((uintptr_t)up) | ((uintptr_t)gate)) % 16 == 0) && (((uintptr_t)codes) % 4 == 0);
 #define HQV(TPR_, NV_)                                                                                              \
   hipLaunchKernelGGL((hidden_quant_vec_k<TPR_, NV_>), dim3((T + 256 / TPR_ - 1) / (256 / TPR_), n_inst), dim3(256), \
-                     0, s, up, gate, h_is, codes, c_is, scale, s_is, T, m, ldq, swiglu)
+                     0, s, up, gate, h_is, codes, c_is, scale, s_is, T, m, ldq, act)
   if (vec && m <= 64 * 4 * 8) HQV(64, 8);
   else if (vec && m <= 64 * 4 * 12) HQV(64, 12);
   else if (vec && m <= 64 * 4 * 16) HQV(64, 16);
@@ -508,7 +512,7 @@ hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_i
   else if (vec && m <= 256 * 4 * 12) HQV(256, 12);
   else
     hipLaunchKernelGGL(hidden_quant_k, dim3(T, n_inst), dim3(256), 0, s, up, gate, h_is, codes, c_is, scale, s_is,
-                       T, m, ldq, swiglu);
+                       T, m, ldq, act);
 #undef HQV
   return hipGetLastError();
 }
