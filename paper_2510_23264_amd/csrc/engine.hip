@@ -572,7 +572,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         break;
       case OP_COMBINE: HIPCHK(launch_combine(d_cdesc, o.i0, d_csrc, n, M->tile, d, st)); break;
       case OP_OPROJ:
-        HIPCHK(launch_oproj_fused(d_odesc, o.i0, d_haux, o.i1, o.i2, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
+        HIPCHK(launch_oproj_fused(d_odesc, o.i0, d_haux, o.i1, o.i2, M->H, M->dh, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
         break;
       case OP_HIDQ:
         HIPCHK(launch_hidden_quant(M->hid, o.i0 == 2 ? M->hid2 : nullptr, (long long)T * M->m, M->hcodes, (long long)T * M->Km,

@@ -28,47 +28,11 @@
 //   fp32 multiply-accumulate) for the investigated head.
 #include "kernels.h"
 #include "device_util.h"
+#include "mma_util.h"
 
 namespace pahq {
 
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef _Float16 v8h __attribute__((ext_vector_type(8)));
-typedef _Float16 v2h __attribute__((ext_vector_type(2)));
-
-// Eight e4m3 codes (two 32-bit words) -> eight fp16 values with the hardware
-// converter (V_CVT_SCALEF32_PK_F16_FP8, scale 1): exact for every finite code,
-// subnormals and signed zero included (checked over all 254 codes on gfx950).
-__device__ __forceinline__ v8h decode8(uint32_t w0, uint32_t w1) {
-  union { v8h h; v2h p[4]; } r;
-  r.p[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w0, 1.0f, false);
-  r.p[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w0, 1.0f, true);
-  r.p[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w1, 1.0f, false);
-  r.p[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w1, 1.0f, true);
-  return r.h;
-}
-
 #define LDS_ROW 144   // gemm_fp8_k: 128 data bytes + 16 pad
-
-// Pointers that arrive inside GemmProb are generic to the compiler; every one of them points to
-// global memory.  Saying so turns FLAT accesses (which may touch LDS and therefore wait for the
-// slab loads in flight) into GLOBAL ones.
-#define GCF(p) ((const __attribute__((address_space(1))) float*)(p))
-#define GF(p) ((__attribute__((address_space(1))) float*)(p))
-__device__ __forceinline__ float4 gload4(const float* p) {
-  v4f v = *(const __attribute__((address_space(1))) v4f*)p;
-  return make_float4(v[0], v[1], v[2], v[3]);
-}
-__device__ __forceinline__ void gstore4(float* p, float4 v) {
-  *(__attribute__((address_space(1))) v4f*)p = (v4f){v.x, v.y, v.z, v.w};
-}
-
-// XCD-aware tile order: workgroup id w runs on XCD w % 8; that XCD gets the
-// contiguous range [x * chunk, (x+1) * chunk) of the linear tile index.
-__device__ __forceinline__ int xcd_tile(int wg, int total) {
-  int chunk = (total + 7) >> 3;
-  return (wg & 7) * chunk + (wg >> 3);
-}
 
 // One result element (the slow path: ragged column tail or unaligned rows).
 __device__ __forceinline__ void epilogue_store(const GemmProb& P, int n, float acc, float sa, float sw, int inst,
@@ -162,32 +126,6 @@ __device__ __forceinline__ void epi_store(const EpiPre<TM, TN>& E, const GemmPro
 // round-robin, so that the first slab of the next tile, its scales and its bias can be requested
 // while the last slab of this tile is multiplied, and the next K loop starts while the stores of
 // this tile are still in flight.
-//
-// The slab loads, the waits for them and the workgroup barriers are written as volatile assembly
-// with a memory clobber.  The compiler's own wait insertion treats a load into LDS as something
-// every later LDS read may depend on wherever control flow merges, and waits for all of them
-// (and for the stores in flight) at exactly the points where this kernel wants them outstanding;
-// __syncthreads() adds a fence that waits for every global store.  What must be ordered is spelled
-// out instead: a wave waits for its own slab loads (s_waitcnt vmcnt) before the barrier that
-// publishes a stage, and has consumed its operand reads (their values fed MFMAs) before the
-// barrier that frees it.  Waits the compiler adds for ordinary loads count fewer operations than
-// are in flight, which only makes them stricter.
-__device__ __forceinline__ void slab_load16(const uint8_t* g, uint32_t lds_addr) {
-  // M0 = wave-uniform LDS base; lane l writes bytes [16 l, 16 l + 16) behind it
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
-}
-__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
-// "Everything has arrived" is said with the builtin, so that the compiler also knows that its own
-// loads (scales, bias) are complete and does not wait for them again in the middle of a slab.
-// 0x0F70: vmcnt(0), expcnt and lgkmcnt left at their maxima.
-__device__ __forceinline__ void wait_all_then_barrier() {
-  asm volatile("" ::: "memory");       // no load may be moved below the wait
-  __builtin_amdgcn_s_waitcnt(0x0F70);
-  wg_barrier();
-}
-__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
-  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
-}
 
 template <int WAVES_M, int WAVES_N, int TM, int TN>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmProb* probs) {

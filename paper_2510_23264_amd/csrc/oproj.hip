@@ -10,25 +10,9 @@
 // the fp8 GEMM (144-byte rows), next head prefetched into registers.
 #include "kernels.h"
 #include "device_util.h"
+#include "mma_util.h"
 
 namespace pahq {
-
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef _Float16 v8h __attribute__((ext_vector_type(8)));
-typedef _Float16 v2h __attribute__((ext_vector_type(2)));
-
-// Eight e4m3 codes (two 32-bit words) -> eight fp16 values with the hardware
-// converter (V_CVT_SCALEF32_PK_F16_FP8, scale 1): exact for every finite code,
-// subnormals and signed zero included (checked over all 254 codes on gfx950).
-__device__ __forceinline__ v8h decode8_o(uint32_t w0, uint32_t w1) {
-  union { v8h h; v2h p[4]; } r;
-  r.p[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w0, 1.0f, false);
-  r.p[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w0, 1.0f, true);
-  r.p[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w1, 1.0f, false);
-  r.p[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w1, 1.0f, true);
-  return r.h;
-}
 
 #define LDS_ROW 144
 
@@ -116,12 +100,12 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
 #pragma unroll
         for (int i = 0; i < TM; i++) {
           uint2 w = *(const uint2*)(sA + (wave * 32 + i * 16 + li) * LDS_ROW + kk * 32 + lg * 8);
-          ha[i] = decode8_o(w.x, w.y);
+          ha[i] = decode8(w.x, w.y);
         }
 #pragma unroll
         for (int j = 0; j < TN; j++) {
           uint2 w = *(const uint2*)(sB + (j * 16 + li) * LDS_ROW + kk * 32 + lg * 8);
-          v8h hb = decode8_o(w.x, w.y);
+          v8h hb = decode8(w.x, w.y);
 #pragma unroll
           for (int i = 0; i < TM; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb, ha[i], acc[i][j], 0, 0, 0);
         }
@@ -190,12 +174,178 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
   }
 }
 
-hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const HeadAux* auxs, int M, int N, int exact,
-                              hipStream_t s) {
+// ------------------------------------------------------------------ exact sums, d_head 64 or 128
+// The same projection with the slab pipeline of the exact GEMM: slabs of 128 code bytes (one head
+// of 128, or two heads of 64: only the real codes are fetched, the padding of the stored rows is
+// skipped) go straight into swizzled LDS, two stages, one barrier per slab.  128 x 64 tile, four
+// wavefronts of 32 x 64.  A head's partial result is complete after one (d_head 64) or two
+// (d_head 128) 64-byte halves of a slab; it is scaled by z-scale[row][head] * w-scale[head] and
+// added to the running total in registers.  The fp32 head (skip_head) takes part with scale 0.
+template <int DH>
+__global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int di, const HeadAux* auxs) {
+  constexpr int BM = 128, BN = 64, TM = 2, TN = 4, NI = 6, STAGE = (BM + BN) * 128;
+  constexpr int HPS = 128 / DH;            // heads per slab
+  constexpr int CPH = 8 / HPS;             // 16-byte chunks per head
+  __shared__ __attribute__((aligned(1024))) uint8_t st0[STAGE];
+  __shared__ __attribute__((aligned(1024))) uint8_t st1[STAGE];
+  const OprojDesc D = descs[di];
+  const int mt = (D.M + BM - 1) / BM, nt = (D.N + BN - 1) / BN;
+  const int lin = xcd_tile(blockIdx.x, mt * nt);
+  if (lin >= mt * nt) return;
+  const int m0 = (lin / nt) * BM, n0 = (lin % nt) * BN;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15, lg = lane >> 4;
+  const int nslab = D.H / HPS;
+
+  // lane l of a load instruction fills LDS row l >> 3, chunk position l & 7, i.e. logical chunk
+  // c = (l & 7) ^ (l >> 3) of the slab: head c / CPH of the slab, bytes 16 (c % CPH) of that head
+  const int c = (lane & 7) ^ (lane >> 3);
+  const uint8_t* src[NI];
+  long long stride[NI];                    // bytes from one slab to the next: activation or weight rows
+#pragma unroll
+  for (int t = 0; t < NI; t++) {
+    int r = 8 * (wave * NI + t) + (lane >> 3);
+    if (r < BM) {
+      int m = min(m0 + r, D.M - 1);
+      src[t] = D.zc + (long long)(m / D.rpi) * D.zc_is + (long long)(m % D.rpi) * D.H * D.Kh +
+               (long long)(c / CPH) * D.Kh + (c % CPH) * 16;
+      stride[t] = (long long)HPS * D.Kh;
+    } else {
+      int n = min(n0 + r - BM, D.N - 1);
+      src[t] = D.W + (long long)n * D.Kh + (long long)(c / CPH) * D.N * D.Kh + (c % CPH) * 16;
+      stride[t] = (long long)HPS * D.N * D.Kh;
+    }
+  }
+  auto issue = [&](const uint8_t* st) {      // fetches the next slab and advances
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_addr_of(st) + wave * NI * 1024);
+#pragma unroll
+    for (int t = 0; t < NI; t++) { slab_load16(src[t], base + t * 1024); src[t] += stride[t]; }
+  };
+  issue(st0);
+
+  const int mbase = m0 + wave * 32, nbase = n0;
+  const float* zs_p[TM];
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    int m = min(mbase + i * 16 + li, D.M - 1);
+    zs_p[i] = D.zs + (long long)(m / D.rpi) * D.zs_is + (long long)(m % D.rpi) * D.H;
+  }
+
+  const int offA = (wave * 32 + li) * 128, offB = (BM + li) * 128;
+  const int sw0 = (lg ^ (li & 7)) * 16, sw1 = ((4 + lg) ^ (li & 7)) * 16;
+  v4f tot[TM][TN], acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++) tot[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+  // adds head h's finished partial result to the total and hands it out if some receiver needs it
+  auto fold = [&](int h, const float (&zsc)[TM]) {
+    const bool skip = h == D.skip_head;      // its codes and scales are whatever an earlier pass left
+    const float sw = skip ? 0.f : GCF(D.ws)[h];
+    HeadAux ax; ax.dst = nullptr; ax.dst_is = 0; ax.sub = nullptr;
+    if (D.aux_begin >= 0 && !skip) ax = auxs[D.aux_begin + h];
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+      const float sc = skip ? 0.f : zsc[i] * sw;
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        float4 val = make_float4(acc[i][j][0] * sc, acc[i][j][1] * sc, acc[i][j][2] * sc, acc[i][j][3] * sc);
+        if (skip) val = make_float4(0.f, 0.f, 0.f, 0.f);
+        tot[i][j][0] += val.x; tot[i][j][1] += val.y; tot[i][j][2] += val.z; tot[i][j][3] += val.w;
+        if (ax.dst) {
+          int m = mbase + i * 16 + li, nb = nbase + j * 16 + lg * 4;
+          if (m < D.M && nb < D.N) {
+            long long off = (long long)(m % D.rpi) * D.N + nb;
+            if (ax.sub) { float4 u = gload4(ax.sub + off); val.x -= u.x; val.y -= u.y; val.z -= u.z; val.w -= u.w; }
+            gstore4(ax.dst + (long long)(m / D.rpi) * ax.dst_is + off, val);
+          }
+        }
+      }
+    }
+  };
+  auto compute = [&](const uint8_t* st, int s) {
+    const uint8_t* sA = st + offA;
+    const uint8_t* sB = st + offB;
+    float zsc[HPS][TM];                      // requested now, used after the MFMAs of the half
+#pragma unroll
+    for (int q = 0; q < HPS; q++)
+#pragma unroll
+      for (int i = 0; i < TM; i++) zsc[q][i] = GCF(zs_p[i])[s * HPS + q];
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      if (HPS == 2 || q == 0) {
+#pragma unroll
+        for (int i = 0; i < TM; i++)
+#pragma unroll
+          for (int j = 0; j < TN; j++) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+      }
+      const int sw = q ? sw1 : sw0;
+      v8h ha[TM][2];
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        uint4 w = *(const uint4*)(sA + i * 2048 + sw);
+        ha[i][0] = decode8(w.x, w.y);
+        ha[i][1] = decode8(w.z, w.w);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        uint4 w = *(const uint4*)(sB + j * 2048 + sw);
+        v8h hb0 = decode8(w.x, w.y), hb1 = decode8(w.z, w.w);
+#pragma unroll
+        for (int i = 0; i < TM; i++) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb0, ha[i][0], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb1, ha[i][1], acc[i][j], 0, 0, 0);
+        }
+      }
+      if (HPS == 2) fold(2 * s + q, zsc[q]);
+      else if (q == 1) fold(s, zsc[0]);
+    }
+  };
+
+  wait_all_then_barrier();
+  if (1 < nslab) issue(st1);
+  compute(st0, 0);
+  for (int s = 1; s < nslab; s += 2) {
+    wait_all_then_barrier();
+    if (s + 1 < nslab) issue(st0);
+    compute(st1, s);
+    if (s + 1 >= nslab) break;
+    wait_all_then_barrier();
+    if (s + 2 < nslab) issue(st1);
+    compute(st0, s + 1);
+  }
+
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    const int m = mbase + i * 16 + li;
+    if (m >= D.M) continue;
+    const int inst_i = m / D.rpi;
+    const long long roff = (long long)(m - inst_i * D.rpi) * D.N;
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      int nb = nbase + j * 16 + lg * 4;
+      if (nb >= D.N) continue;
+      float4 v = gload4(D.run_in + inst_i * D.run_in_is + roff + nb);
+      if (D.bias) { float4 b = gload4(D.bias + nb); v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w; }
+      v.x += tot[i][j][0]; v.y += tot[i][j][1]; v.z += tot[i][j][2]; v.w += tot[i][j][3];
+      // the fp32 head goes in last, as in oproj_fused_k
+      if (D.extra) { float4 e = gload4(D.extra + inst_i * D.extra_is + roff + nb); v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w; }
+      gstore4(D.run_out + inst_i * D.run_out_is + roff + nb, v);
+    }
+  }
+}
+
+hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const HeadAux* auxs, int M, int N, int H, int dh,
+                              int exact, hipStream_t s) {
   if (M == 0) return hipSuccess;
   int tiles = ((M + 127) / 128) * ((N + 63) / 64);
   dim3 grid((tiles + 7) / 8 * 8);
-  if (exact) hipLaunchKernelGGL(oproj_fused_k<true>, grid, dim3(256), 0, s, descs, desc_index, auxs);
+  if (exact && (dh == 64 || dh == 128) && N % 4 == 0 && H % (128 / dh) == 0) {
+    if (dh == 64) hipLaunchKernelGGL(oproj_x_k<64>, grid, dim3(256), 0, s, descs, desc_index, auxs);
+    else hipLaunchKernelGGL(oproj_x_k<128>, grid, dim3(256), 0, s, descs, desc_index, auxs);
+  } else if (exact) hipLaunchKernelGGL(oproj_fused_k<true>, grid, dim3(256), 0, s, descs, desc_index, auxs);
   else hipLaunchKernelGGL(oproj_fused_k<false>, grid, dim3(256), 0, s, descs, desc_index, auxs);
   return hipGetLastError();
 }
