@@ -23,7 +23,7 @@ typedef float v4f_a __attribute__((ext_vector_type(4)));
 // q, k and v each come with their own base pointer, instance stride and row
 // stride (AttnSrc), so one head can take a per-candidate query, key or value
 // while the other two are shared by all instances.
-template <int ST, int DH>
+template <int ST, int DH, bool ROPE>
 __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zcodes,
                                                          long long zc_is, float* zscale, long long zs_is, float* zf32,
                                                          long long zf_is, int f32_head, int n_pairs, int B, int S, int H,
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
       k[a][c] = vk.x; k[a][c + 1] = vk.y; k[a][c + 2] = vk.z; k[a][c + 3] = vk.w;
     }
   }
-  if (rope) {
+  if (ROPE) {
 #pragma unroll
     for (int a = 0; a < ST; a++) {
       int pos = 16 * a + i;
@@ -180,8 +180,9 @@ hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is
   if (S > 32) return hipErrorInvalidValue;
   int n_pairs = n_inst * B * src.n_heads;
   dim3 grid((n_pairs + 3) / 4);
-#define ATT(ST_, DH_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_>), grid, dim3(256), 0, s, src, zcodes, zc_is, \
-                                         zscale, zs_is, zf32, zf_is, f32_head, n_pairs, B, S, H, ldz, rope, rope_theta)
+#define ATT1(ST_, DH_, R_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_, R_>), grid, dim3(256), 0, s, src, zcodes, \
+                                              zc_is, zscale, zs_is, zf32, zf_is, f32_head, n_pairs, B, S, H, ldz, rope, rope_theta)
+#define ATT(ST_, DH_) do { if (rope) ATT1(ST_, DH_, true); else ATT1(ST_, DH_, false); } while (0)
   if (S <= 16) {
     if (dh == 16) ATT(1, 16); else if (dh == 32) ATT(1, 32); else if (dh == 64) ATT(1, 64);
     else if (dh == 128) ATT(1, 128); else return hipErrorInvalidValue;
@@ -190,6 +191,7 @@ hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is
     else if (dh == 128) ATT(2, 128); else return hipErrorInvalidValue;
   }
 #undef ATT
+#undef ATT1
   return hipGetLastError();
 }
 
