@@ -264,33 +264,38 @@ __global__ __launch_bounds__(256) void kl_rows_k(const float* logits, long long 
   int b = blockIdx.x, inst = blockIdx.y;
   const float* x = logits + inst * l_is + (long long)b * ldv;
   const float* xr = ref_logits + (long long)b * ldv;
-  double lz = row_logz(x, V, redf, redd);
-  double lzr = ref_logz[b];
-  float lzr_f = (float)lzr;
+  const double lzr = ref_logz[b];
+  const float lzr_f = (float)lzr;
+  // one sweep over the candidate's row: the running (max, rescaled sum) of its log-sum-exp and the
+  // two KL sums advance together, so the row is read once
+  float mx = -3.0e38f, se = 0.f;
   double a = 0.0, psum = 0.0;
+  auto step = [&](float r, float c) {
+    if (c > mx) { se *= expf(mx - c); mx = c; }
+    se += expf(c - mx);
+    double p = (double)expf(r - lzr_f);
+    a += p * (double)(r - c);
+    psum += p;
+  };
   if (((((uintptr_t)x) | ((uintptr_t)xr)) & 15) == 0) {
     int i = threadIdx.x * 4;
     for (; i + 3 < V; i += 1024) {
       float4 r = *(const float4*)(xr + i), c = *(const float4*)(x + i);
+      float m4 = fmaxf(fmaxf(c.x, c.y), fmaxf(c.z, c.w));
+      if (m4 > mx) { se *= expf(mx - m4); mx = m4; }
+      se += expf(c.x - mx) + expf(c.y - mx) + expf(c.z - mx) + expf(c.w - mx);
       float p0 = expf(r.x - lzr_f), p1 = expf(r.y - lzr_f), p2 = expf(r.z - lzr_f), p3 = expf(r.w - lzr_f);
       a += (double)p0 * (double)(r.x - c.x) + (double)p1 * (double)(r.y - c.y) + (double)p2 * (double)(r.z - c.z) +
            (double)p3 * (double)(r.w - c.w);
       psum += (double)p0 + (double)p1 + (double)p2 + (double)p3;
     }
-    for (int e = i; e < V && e < i + 4; e++) {
-      float r = xr[e];
-      double p = (double)expf(r - lzr_f);
-      a += p * (double)(r - x[e]);
-      psum += p;
-    }
+    for (int e = i; e < V && e < i + 4; e++) step(xr[e], x[e]);
   } else {
-    for (int i = threadIdx.x; i < V; i += 256) {
-      float r = xr[i];
-      double p = (double)expf(r - lzr_f);
-      a += p * (double)(r - x[i]);
-      psum += p;
-    }
+    for (int i = threadIdx.x; i < V; i += 256) step(xr[i], x[i]);
   }
+  float gm = block_max_f(mx, redf);
+  double sd = block_sum_d((double)se * (double)expf(mx - gm), redd);
+  const double lz = (double)gm + log(sd);
   a = block_sum_d(a, redd);
   psum = block_sum_d(psum, redd);
   if (threadIdx.x == 0) row_kl[inst * B + b] = a - (lzr - lz) * psum;
