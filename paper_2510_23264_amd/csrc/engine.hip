@@ -134,6 +134,8 @@ struct Builder {
     p.A = A; p.a_is = a_is; p.lda = lda; p.ascale = as; p.as_is = as_is; p.as_stride = as_stride;
     p.W = W; p.ldw = ldw; p.wscale = ws; p.wscale_block = ws_block; p.bias = bias;
     p.C = C; p.c_is = c_is; p.ldc = ldc; p.act = act; p.rpi = Mr; p.M = Mr * a.n; p.N = N; p.K = K; p.k_real = k_real;
+    p.ws_shift = -1;
+    if (ws_block > 0 && (ws_block & (ws_block - 1)) == 0) { p.ws_shift = 0; while ((1 << p.ws_shift) < ws_block) p.ws_shift++; }
     return p;
   }
 

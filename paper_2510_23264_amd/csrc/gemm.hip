@@ -60,20 +60,30 @@ struct EpiPre {
   float sw[TN];      // column scale of columns nbase + 16 j + 4 lg .. + 3 (they share one weight slice)
   float4 bias[TN];   // bias of those columns (zero without a bias)
 };
+// Row m0 + r of a problem whose instances have rpi rows each: (instance, row in the instance), from the
+// split (i0, r0) of m0.  One wrap covers tiles that are not taller than an instance; shorter
+// instances take the loop.
+__device__ __forceinline__ void split_row(int i0, int r0, int r, int rpi, int& inst, int& row) {
+  inst = i0; row = r0 + r;
+  while (row >= rpi) { row -= rpi; inst++; }
+}
+__device__ __forceinline__ int wscale_index(const GemmProb& P, int n) {
+  if (P.wscale_block >= P.N) return 0;
+  return P.ws_shift >= 0 ? (n >> P.ws_shift) : n / P.wscale_block;
+}
 template <int TM, int TN>
-__device__ __forceinline__ void epi_prefetch(EpiPre<TM, TN>& E, const GemmProb& P, int mbase, int nbase, int li,
-                                             int lg) {
+__device__ __forceinline__ void epi_prefetch(EpiPre<TM, TN>& E, const GemmProb& P, int m0, int i0, int r0, int mbase,
+                                             int nbase, int li, int lg) {
 #pragma unroll
   for (int i = 0; i < TM; i++) {
     int m = min(mbase + i * 16 + li, P.M - 1);
-    E.inst[i] = m / P.rpi;
-    E.row[i] = m - E.inst[i] * P.rpi;
+    split_row(i0, r0, m - m0, P.rpi, E.inst[i], E.row[i]);
     E.sa[i] = GCF(P.ascale)[E.inst[i] * P.as_is + (long long)E.row[i] * P.as_stride];
   }
 #pragma unroll
   for (int j = 0; j < TN; j++) {
     int nb = nbase + j * 16 + lg * 4;
-    E.sw[j] = GCF(P.wscale)[min(nb, P.N - 1) / P.wscale_block];
+    E.sw[j] = GCF(P.wscale)[wscale_index(P, min(nb, P.N - 1))];
     // one 16-byte load, no divergence: a group past the last one re-reads the last one (its results are
     // never stored), and the last group may read up to three floats behind bias[N - 1] (the bias
     // arrays of this library are followed by padding; the values land in the padding of the C row)
@@ -152,12 +162,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
   const uint8_t* src[NI];
   const int cg = ((lane & 7) ^ (lane >> 3)) * 16;
   auto set_src = [&](int m0, int n0) {
+    const int i0 = m0 / P.rpi, r0 = m0 - i0 * P.rpi;
 #pragma unroll
     for (int t = 0; t < NI; t++) {
       int r = 8 * (wave * NI + t) + (lane >> 3);
       if (r < BM) {
-        int m = min(m0 + r, P.M - 1);
-        src[t] = (const uint8_t*)P.A + (long long)(m / P.rpi) * P.a_is + (long long)(m % P.rpi) * P.lda + cg;
+        int m = min(m0 + r, P.M - 1), inst, row;
+        split_row(i0, r0, m - m0, P.rpi, inst, row);
+        src[t] = (const uint8_t*)P.A + (long long)inst * P.a_is + (long long)row * P.lda + cg;
       } else {
         int n = min(n0 + r - BM, P.N - 1);
         src[t] = (const uint8_t*)P.W + (long long)n * P.ldw + cg;
@@ -229,7 +241,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
     else wait_all_then_barrier();
     if (128 < P.K) issue(st1, 128);
     EpiPre<TM, TN> E;
-    epi_prefetch<TM, TN>(E, P, mbase, nbase, li, lg);
+    { const int i0 = m0 / P.rpi; epi_prefetch<TM, TN>(E, P, m0, i0, m0 - i0 * P.rpi, mbase, nbase, li, lg); }
     compute(st0);
     for (int k0 = 128; k0 < P.K; k0 += 256) {        // slabs k0 (in st1) and k0 + 128 (in st0)
       wait_all_then_barrier();                       // the slab has landed for everyone, the other stage is free
@@ -327,7 +339,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_k(const GemmPr
   load_slab(0);
   const int mbase = m0 + wm * WM, nbase = n0 + wn * WN;
   EpiPre<TM, TN> E;
-  epi_prefetch<TM, TN>(E, P, mbase, nbase, li, lg);
+  { const int i0 = m0 / P.rpi; epi_prefetch<TM, TN>(E, P, m0, i0, m0 - i0 * P.rpi, mbase, nbase, li, lg); }
   for (int k0 = 0; k0 < P.K; k0 += 128) {
     __syncthreads();                 // previous slab fully consumed
     store_slab();

@@ -46,7 +46,8 @@ struct GemmProb {
   const float* add;    long long add_is;                     // row stride ldc; may be null
   float* aux;          long long aux_is;                     // row stride ldc; may be null
   const float* aux_sub;                                      // instance-independent, row stride ldc; may be null
-  int M, N, K, pad_;
+  int M, N, K;
+  int ws_shift;        // log2(wscale_block) when it is a power of two, else -1 (the kernels then divide)
 };
 // What the fp8 GEMM kernels assume of a problem (checked on the host before a launch): 16-byte
 // aligned operands and outputs, K a multiple of 128, groups of four columns that share one weight
