@@ -41,13 +41,31 @@ PMC_TRAFFIC_MB = {"gemm_fp8": (168.4, 151.3), "hidden_quant": (226.8, 56.8), "at
                   "gemm_f32": (54.5, 32.1), "edge_patch": (100.0, 94.6)}
 
 
-def all_edges_pass(gm, P, cfg, n_recv, stride=1):
+def all_edges_pass(gm, P, cfg, receivers, stride=1):
+    """Every in-edge of the given receivers (descending, as the sweep visits them), once."""
     n = 0
-    for r in range(n_recv - 1, -1, -stride):
-        senders = np.arange(P.n_upstream(cfg, r), dtype=np.int32)
-        gm.eval_edges(r, senders)
+    for r in receivers[::-1][::stride]:
+        senders = np.arange(P.n_upstream(cfg, int(r)), dtype=np.int32)
+        gm.eval_edges(int(r), senders)
         n += senders.size
     return n
+
+
+def gather_regime(gm, P, cfg, receivers, torch):
+    """Secondary figure: the same candidates against a seeded removed set with 90 % of all edges
+    removed, where receivers no longer share their inputs and every one gathers its own sum of
+    sender tiles.  A sample of receivers keeps it to a few seconds."""
+    rng = np.random.default_rng(12345)
+    gm.set_removed((rng.random(gm.n_edges) < 0.9).astype(np.uint8))
+    sample = receivers[:: max(1, len(receivers) // 24)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n = all_edges_pass(gm, P, cfg, sample)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    gm.set_removed(np.zeros(gm.n_edges, np.uint8))
+    return {"edges_per_s": round(n / dt, 1), "edges": int(n), "receivers": int(len(sample)),
+            "removed_fraction": 0.9, "seed": 12345}
 
 
 def cpu_baseline(name, shape, w, clean, corrupt):
@@ -110,11 +128,12 @@ def main():
     shape, w, clean, corrupt, spec = synth.make_workload(args.config)
     gm = P.Model(shape, w, spec["B"], spec["S"], precision=P.PAHQ, max_batch_edges=args.batch, mma=args.mma)
     cfg = gm.cfg
-    n_recv = P.n_receivers(cfg)
+    # configs that name a receiver sample (4 and 5) run the in-edges of that seeded sample
+    receivers = synth.make_receiver_sample(P.n_receivers(cfg), spec["n_recv"], spec["seed"])
     gm.clean_cache(clean, corrupt)
 
     for _ in range(args.warmup):
-        all_edges_pass(gm, P, cfg, n_recv, args.recv_stride)
+        all_edges_pass(gm, P, cfg, receivers, args.recv_stride)
     torch.cuda.synchronize()
 
     # Untimed: one pass with HIP events around every launch, for the per-kernel breakdown and to
@@ -123,7 +142,7 @@ def main():
     # pass of the executor.
     gm.set_profiling_sample(None, 1)
     gm.set_profiling(True)
-    all_edges_pass(gm, P, cfg, n_recv, args.recv_stride)
+    all_edges_pass(gm, P, cfg, receivers, args.recv_stride)
     torch.cuda.synchronize()
     prof = gm.get_profile()
     gm.set_profiling(False)
@@ -135,7 +154,7 @@ def main():
     t0 = time.perf_counter()
     n_evals = 0
     for _ in range(args.steps):
-        n_evals += all_edges_pass(gm, P, cfg, n_recv, args.recv_stride)
+        n_evals += all_edges_pass(gm, P, cfg, receivers, args.recv_stride)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     timed = gm.get_profile()[dom]
@@ -172,13 +191,15 @@ def main():
                             "executor pass of the timed steps",
                 "share_of_kernel_time": round(prof[dom]["ms"] / sum(v["ms"] for v in prof.values()), 3)}
 
+    gather = None if args.no_sweep else gather_regime(gm, P, cfg, receivers, torch)
+
     sweeps = {}
     if not args.no_sweep:
         for tau in spec["taus"]:
             gm.clean_cache(clean, corrupt)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
-            kept, ne, _ = gm.acdc_sweep(tau, trace_cap=0)
+            kept, ne, _ = gm.acdc_sweep(tau, receivers=(receivers if spec["n_recv"] else None), trace_cap=0)
             ts = time.perf_counter() - t1
             sweeps[str(tau)] = {"s": round(ts, 4), "evals": int(ne), "kept_edges": int(kept.sum()),
                                 "edges_decided_per_s": round(gm.n_edges / ts, 1)}
@@ -189,13 +210,15 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8_e4m3 (FP8 matrix cores)" if args.mma == 0 else "fp8_e4m3 operands, fp16 matrix cores, fp32 accumulate",
         "data": "synthetic",
-        "config": {"workload": f"{args.config}: every edge of the split-QKV graph ({gm.n_edges} edges) evaluated once "
-                               f"at the empty removed set, PAHQ precision (fp32 investigated head)",
+        "config": {"workload": (f"{args.config}: every edge of the split-QKV graph ({gm.n_edges} edges) evaluated once "
+                                if not spec["n_recv"] else
+                                f"{args.config}: every in-edge of the {len(receivers)} seeded receivers evaluated once ")
+                               + "at the empty removed set, PAHQ precision (fp32 investigated head)",
                    "B": spec["B"], "S": spec["S"], "batch_edges": args.batch, "recv_stride": args.recv_stride, "edges_per_step": n_evals // args.steps,
                    "seed": spec["seed"]},
         "roofline": roofline, "kernels": kernels,
         "kernels_note": "per-class HIP-event times of one untimed pass with events around every launch",
-        "sweep": sweeps,
+        "sweep": sweeps, "gather_regime": gather,
     }
     if not args.no_cpu_baseline:
         gm.close()

@@ -116,7 +116,13 @@ size_t layout(pahq_model* M, char* base) {
   M->hid = mlp ? b.take<float>(n * T * m) : nullptr; M->hid2 = (mlp && swi) ? b.take<float>(n * T * m) : nullptr;
   M->hcodes = mlp ? b.take<uint8_t>(n * T * Km) : nullptr; M->hscale = mlp ? b.take<float>(n * T) : nullptr;
   M->lastcodes = b.take<uint8_t>(n * B * Kd); M->lastscale = b.take<float>(n * B); M->logits = b.take<float>(n * B * Vp);
-  M->pool_tiles = (long long)std::max<size_t>(2 * Ns, 4 * n);
+  // Per-instance copies of recomputed sender outputs that some receiver reads individually: in the
+  // worst case (most edges removed) every sender but the embedding needs one per candidate.  Room
+  // for a full batch of those, capped at 64 GiB; a smaller pool only shrinks the batches.
+  {
+    const size_t want = n * (Ns - 1), cap = ((size_t)64 << 30) / (tile * sizeof(float));
+    M->pool_tiles = (long long)std::max<size_t>(std::max<size_t>(2 * Ns, 4 * n), std::min(want, cap));
+  }
   M->slots = b.take<float>((size_t)M->pool_tiles * tile);
   M->row_kl = b.take<double>(n * B); M->kl_dev = b.take<double>(M->ncap);
   M->arena.slot_bytes = arena_slot_bytes(M);
