@@ -241,6 +241,29 @@ def test_batch_invariance_and_determinism(mid):
     mid.gm.set_removed(np.zeros(g.n_edges(), np.uint8))
 
 
+def test_long_sender_lists_and_sampled_profiling(cfg1):
+    """A call with more candidates than one host round trip carries (1024) is split into queued
+    chunks; results equal the short call's, candidate by candidate.  The sampled profiling
+    entry point records only the classes it is given."""
+    g, gm = cfg1.g, cfg1.gm
+    r = g.OUT
+    base = np.arange(g.n_upstream(r), dtype=np.int32)
+    short = gm.eval_edges(r, base)
+    long_ids = np.tile(base, 2500 // base.size + 1)[:2500]
+    gm.set_profiling_sample(["kl"], 1)
+    gm.set_profiling(True)
+    long = gm.eval_edges(r, long_ids)
+    prof = gm.get_profile()
+    gm.set_profiling(False)
+    gm.set_profiling_sample(None, 1)
+    assert (long.view(np.uint32) == short[long_ids].view(np.uint32)).all()
+    assert prof["kl"]["launches"] > 0 and prof["kl"]["ms"] > 0
+    assert all(v["launches"] == 0 for k, v in prof.items() if k != "kl")
+    import paper_2510_23264_amd as p
+    with pytest.raises(p.PahqError):
+        gm.set_profiling_sample(["kl"], 0)
+
+
 # ------------------------------------------------------------------ sweep
 def compare_sweep(pr, tau, receivers=None):
     """Full sweep on both sides; on a decision that differs the two KL increments must both lie
