@@ -270,6 +270,232 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
   }
 }
 
+// ------------------------------------------------------------------ exact sums, three-stage pipeline
+// The large problems.  What bounds gemm_x_k is the distance between requesting a slab and needing
+// it: one slab of MFMAs, less than the latency of the loads under load.  Here one workgroup of
+// eight wavefronts (4 x 2, 64 x 64 each) owns a 256 x 128 tile per compute unit, LDS holds three
+// stages of 48 KB, and a slab is requested two slabs before it is multiplied.  The slabs of all
+// tiles a workgroup walks form one stream: the request side runs two slabs ahead of the compute
+// side across tile boundaries, so a tile's stores drain while the next tile is multiplied.
+// Everything that is loaded goes through LDS, also the scales and the bias of a tile (one
+// GLOBAL_LOAD_LDS_DWORD per wave when the tile's first slab is multiplied; read back by the
+// epilogue), so that the only vector-memory operations the compiler knows of are stores and the
+// residual loads of the epilogue, and the waits can be counted: a wave waits for slab c with
+// "at most (6 if slab c+1 is requested) + (stores issued since) operations outstanding".
+template <int UNUSED>
+__global__ __launch_bounds__(512, 1) void gemm_p_k(const GemmProb* probs) {
+  constexpr int BM = 256, BN = 128, TM = 4, TN = 4, NW = 8;
+  constexpr int ROWS = BM + BN, NI = ROWS / 8 / NW, STAGE = ROWS * 128, NS = 3;
+  static_assert(NI == 6, "six slab loads per wave: the wait counts below assume it");
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+  float* const e_rs = (float*)(smem + NS * STAGE);      // row scales of the tile [BM]
+  float* const e_cs = e_rs + BM;                        // column scales [BN]
+  float* const e_bi = e_cs + BN;                        // bias [BN]
+
+  const GemmProb P = probs[blockIdx.y];
+  const int mt = (P.M + BM - 1) / BM, nt = (P.N + BN - 1) / BN, total = mt * nt;
+  const int chunk = (total + 7) >> 3, xcd = blockIdx.x & 7, per = gridDim.x >> 3;
+  const int jend = min(chunk, total - xcd * chunk);
+  int j = blockIdx.x >> 3;
+  if (j >= jend) return;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int li = lane & 15, lg = lane >> 4;
+  const int nslab = P.K >> 7;
+  const uint32_t lds0 = lds_addr_of(smem);
+
+  // ---- request side
+  const uint8_t* src[NI];
+  const int cg = ((lane & 7) ^ (lane >> 3)) * 16;
+  auto set_src = [&](int m0, int n0) {
+    const int i0 = m0 / P.rpi, r0 = m0 - i0 * P.rpi;
+#pragma unroll
+    for (int t = 0; t < NI; t++) {
+      int r = 8 * (wave * NI + t) + (lane >> 3);
+      if (r < BM) {
+        int m = min(m0 + r, P.M - 1), inst, row;
+        split_row(i0, r0, m - m0, P.rpi, inst, row);
+        src[t] = (const uint8_t*)P.A + (long long)inst * P.a_is + (long long)row * P.lda + cg;
+      } else {
+        int n = min(n0 + r - BM, P.N - 1);
+        src[t] = (const uint8_t*)P.W + (long long)n * P.ldw + cg;
+      }
+    }
+  };
+  auto tile_origin = [&](int jj, int& m0, int& n0) {
+    int lin = xcd * chunk + jj;
+    m0 = (lin / nt) * BM; n0 = (lin % nt) * BN;
+  };
+  int ji = j, ki = 0, si = 0;          // tile, slab and stage of the next request
+  bool requesting = true;
+  auto request = [&]() -> bool {
+    if (!requesting) return false;
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds0 + si * STAGE + wave * NI * 1024);
+#pragma unroll
+    for (int t = 0; t < NI; t++) slab_load16(src[t] + ki * 128, base + t * 1024);
+    si = (si == NS - 1) ? 0 : si + 1;
+    if (++ki == nslab) {
+      ki = 0; ji += per;
+      if (ji < jend) { int a, b; tile_origin(ji, a, b); set_src(a, b); }
+      else requesting = false;
+    }
+    return true;
+  };
+  // scales and bias of a tile: one dword per lane and wave
+  auto request_scales = [&](int m0, int n0) {
+    const float* g;
+    float* dst;
+    if (wave < 4) {
+      const int i0 = m0 / P.rpi;
+      int m = min(m0 + wave * 64 + lane, P.M - 1), inst, row;
+      split_row(i0, m0 - i0 * P.rpi, m - m0, P.rpi, inst, row);
+      g = P.ascale + inst * P.as_is + (long long)row * P.as_stride;
+      dst = e_rs + wave * 64;
+    } else {
+      int n = min(n0 + (wave & 1) * 64 + lane, P.N - 1);
+      if (wave >= 6 && P.bias) { g = P.bias + n; dst = e_bi + (wave & 1) * 64; }
+      else { g = P.wscale + wscale_index(P, n); dst = ((wave >= 6) ? e_bi : e_cs) + (wave & 1) * 64; }
+    }
+    lds_load4(g, __builtin_amdgcn_readfirstlane(lds_addr_of(dst)));
+  };
+
+  // ---- compute side
+  const int offA = (wm * 64 + li) * 128, offB = (BM + wn * 64 + li) * 128;
+  const int sw0 = (lg ^ (li & 7)) * 16, sw1 = ((4 + lg) ^ (li & 7)) * 16;
+  v4f acc[TM][TN];
+  auto compute = [&](const uint8_t* st) {
+    const uint8_t* sA = st + offA;
+    const uint8_t* sB = st + offB;
+    // all operand reads of the slab are issued before the first convert, so that the reads of the
+    // second half are in flight while the first half is multiplied
+    uint4 ra[2][TM], rb[2][TN];
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      const int sw = q ? sw1 : sw0;
+#pragma unroll
+      for (int i = 0; i < TM; i++) ra[q][i] = *(const uint4*)(sA + i * 2048 + sw);
+#pragma unroll
+      for (int jj = 0; jj < TN; jj++) rb[q][jj] = *(const uint4*)(sB + jj * 2048 + sw);
+    }
+    __builtin_amdgcn_sched_barrier(0);       // keep the scheduler from sinking the reads to their uses
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      v8h ha[TM][2];
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        ha[i][0] = decode8(ra[q][i].x, ra[q][i].y);
+        ha[i][1] = decode8(ra[q][i].z, ra[q][i].w);
+      }
+#pragma unroll
+      for (int jj = 0; jj < TN; jj++) {
+        v8h hb0 = decode8(rb[q][jj].x, rb[q][jj].y), hb1 = decode8(rb[q][jj].z, rb[q][jj].w);
+#pragma unroll
+        for (int i = 0; i < TM; i++) {
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb0, ha[i][0], acc[i][jj], 0, 0, 0);
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb1, ha[i][1], acc[i][jj], 0, 0, 0);
+        }
+      }
+    }
+  };
+
+  int m0, n0;
+  tile_origin(j, m0, n0);
+  set_src(m0, n0);
+  request();
+  bool next_requested = request();      // is the slab after the one about to be multiplied on its way?
+  int stores = 0;                       // stores this wave issued since that slab was requested (0, 16 or 32)
+  int sc = 0;                           // stage of the slab about to be multiplied
+
+  for (;;) {
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int jj = 0; jj < TN; jj++) acc[i][jj] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    for (int k = 0; k < nslab; k++) {
+      // this wave's part of the slab has landed: everything but what was issued after it is complete
+      if (next_requested) {
+        if (stores == 0) wait_vm<6>(); else if (stores == 16) wait_vm<22>(); else wait_vm<38>();
+      } else {
+        if (stores == 0) wait_vm<0>(); else if (stores == 16) wait_vm<16>(); else wait_vm<32>();
+      }
+      stores = 0;
+      wg_barrier();                     // everyone's part has; the stage of the previous slab is free
+      if (k == 0) request_scales(m0, n0);
+      next_requested = request();       // two slabs ahead, into the stage just freed
+      compute(smem + sc * STAGE);
+      sc = (sc == NS - 1) ? 0 : sc + 1;
+    }
+    if (nslab == 1) { wait_vm<0>(); wg_barrier(); }     // the scales were requested in this very slab
+
+    // ---- epilogue: scales and bias from LDS, 16-byte stores
+    const int mbase = m0 + wm * 64, nbase = n0 + wn * 64;
+    const bool interior = (m0 + BM <= P.M) && (n0 + BN <= P.N);
+    const int i0 = m0 / P.rpi, r0 = m0 - i0 * P.rpi;
+    float4 bias[TN];
+    float cs[TN];
+#pragma unroll
+    for (int jj = 0; jj < TN; jj++) {
+      cs[jj] = e_cs[wn * 64 + jj * 16 + lg * 4];
+      bias[jj] = *(const float4*)(e_bi + wn * 64 + jj * 16 + lg * 4);
+    }
+    int inst[TM];
+    long long roff[TM];
+    bool live[TM];
+    float sa[TM];
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+      const int m = mbase + i * 16 + li;
+      live[i] = interior || m < P.M;
+      int row;
+      split_row(i0, r0, min(m, P.M - 1) - m0, P.rpi, inst[i], row);
+      sa[i] = e_rs[wm * 64 + i * 16 + li];
+      roff[i] = (long long)row * P.ldc + nbase + lg * 4;
+    }
+    // the residual tile first, all of it, so that its loads are in flight together
+    float4 addv[TM][TN];
+    if (P.add) {
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int jj = 0; jj < TN; jj++) {
+          const bool on = live[i] && (interior || nbase + jj * 16 + lg * 4 < P.N);
+          addv[i][jj] = on ? gload4(P.add + inst[i] * P.add_is + roff[i] + jj * 16) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+      if (!live[i]) continue;
+#pragma unroll
+      for (int jj = 0; jj < TN; jj++) {
+        if (!interior && nbase + jj * 16 + lg * 4 >= P.N) continue;
+        float s2 = sa[i] * cs[jj];
+        float4 val = make_float4(acc[i][jj][0] * s2, acc[i][jj][1] * s2, acc[i][jj][2] * s2, acc[i][jj][3] * s2);
+        float4 v = val;
+        if (P.bias) { v.x += bias[jj].x; v.y += bias[jj].y; v.z += bias[jj].z; v.w += bias[jj].w; }
+        if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
+        const long long off = roff[i] + jj * 16;
+        if (P.add) { v.x += addv[i][jj].x; v.y += addv[i][jj].y; v.z += addv[i][jj].z; v.w += addv[i][jj].w; }
+        gstore4(P.C + inst[i] * P.c_is + off, v);
+        if (P.aux) {
+          if (P.aux_sub) { float4 u = gload4(P.aux_sub + off); val.x -= u.x; val.y -= u.y; val.z -= u.z; val.w -= u.w; }
+          gstore4(P.aux + inst[i] * P.aux_is + off, val);
+        }
+      }
+    }
+    if (interior) stores = P.aux ? 32 : 16;     // every wave issued exactly that many
+    else {                                      // ragged tile: the count is not uniform, so drain
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      stores = 0;
+    }
+    j += per;
+    if (j >= jend) break;
+    tile_origin(j, m0, n0);
+  }
+}
+
 // ------------------------------------------------------------------ FP8 matrix-core instruction
 // Lane layout of the instruction (lane = 16*g + i): the operand of lane (i, g) is row i, bytes
 // [32g, 32g+32) of the slab.  WAVES_M x WAVES_N wavefronts; each owns a (BM / WAVES_M) x
@@ -371,6 +597,21 @@ hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int ma
   if (exact) {
     // persistent: at most two workgroups per compute unit (64 KB of LDS each), 256 compute units
     const bool wide = max_N > 64;
+    if (wide && max_M >= 8192 && max_N >= 128) {
+      // one 512-thread workgroup per compute unit, three 48 KB stages + 2 KB of scales
+      static bool attr_set = false;
+      const int lds_bytes = 3 * 384 * 128 + 2048;
+      if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_p_k<0>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+      }
+      int tiles = ((max_M + 255) / 256) * ((max_N + 127) / 128);
+      int gx = (tiles + 7) / 8 * 8;
+      if (gx > 256) gx = 256;
+      hipLaunchKernelGGL((gemm_p_k<0>), dim3(gx, n_probs), dim3(512), lds_bytes, s, probs);
+      return hipGetLastError();
+    }
     int tiles = ((max_M + 127) / 128) * (wide ? (max_N + 127) / 128 : (max_N + 63) / 64);
     int gx = (tiles + 7) / 8 * 8;
     if (gx > 512) gx = 512;

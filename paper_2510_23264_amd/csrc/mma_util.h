@@ -57,6 +57,15 @@ __device__ __forceinline__ void slab_load16(const uint8_t* g, uint32_t lds_addr)
   // M0 = wave-uniform LDS base; lane l writes bytes [16 l, 16 l + 16) behind it
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
 }
+// one dword per lane: lane l writes LDS bytes [4 l, 4 l + 4) behind the base
+__device__ __forceinline__ void lds_load4(const void* g, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(lds_addr) : "memory");
+}
+// at most N vector-memory operations of this wave still outstanding (they retire in issue order)
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 // "Everything has arrived" is said with the builtin, so that the compiler also knows that its own
 // loads (scales, bias) are complete and does not wait for them again in the middle of a slab.
