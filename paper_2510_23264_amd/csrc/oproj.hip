@@ -273,6 +273,17 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
     for (int q = 0; q < HPS; q++)
 #pragma unroll
       for (int i = 0; i < TM; i++) zsc[q][i] = GCF(zs_p[i])[s * HPS + q];
+    // all operand reads of the slab first (the scheduler would otherwise sink them to their uses)
+    uint4 ra[2][TM], rb[2][TN];
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      const int sw = q ? sw1 : sw0;
+#pragma unroll
+      for (int i = 0; i < TM; i++) ra[q][i] = *(const uint4*)(sA + i * 2048 + sw);
+#pragma unroll
+      for (int j = 0; j < TN; j++) rb[q][j] = *(const uint4*)(sB + j * 2048 + sw);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int q = 0; q < 2; q++) {
       if (HPS == 2 || q == 0) {
@@ -281,18 +292,15 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
 #pragma unroll
           for (int j = 0; j < TN; j++) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
       }
-      const int sw = q ? sw1 : sw0;
       v8h ha[TM][2];
 #pragma unroll
       for (int i = 0; i < TM; i++) {
-        uint4 w = *(const uint4*)(sA + i * 2048 + sw);
-        ha[i][0] = decode8(w.x, w.y);
-        ha[i][1] = decode8(w.z, w.w);
+        ha[i][0] = decode8(ra[q][i].x, ra[q][i].y);
+        ha[i][1] = decode8(ra[q][i].z, ra[q][i].w);
       }
 #pragma unroll
       for (int j = 0; j < TN; j++) {
-        uint4 w = *(const uint4*)(sB + j * 2048 + sw);
-        v8h hb0 = decode8(w.x, w.y), hb1 = decode8(w.z, w.w);
+        v8h hb0 = decode8(rb[q][j].x, rb[q][j].y), hb1 = decode8(rb[q][j].z, rb[q][j].w);
 #pragma unroll
         for (int i = 0; i < TM; i++) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb0, ha[i][0], acc[i][j], 0, 0, 0);
