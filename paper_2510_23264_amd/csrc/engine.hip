@@ -179,7 +179,17 @@ struct Builder {
                               (gd.out_codes ? rows * (d + 4.0) : 0));
   }
   void add_build(int g0, int n_groups, int patch_group) {
-    if (n_groups - (patch_group >= 0 ? 1 : 0) > 0) { add_op(OP_BUILD, g0, n_groups, patch_group); work_build(g0, n_groups, patch_group); }
+    if (n_groups - (patch_group >= 0 ? 1 : 0) > 0) {
+      int shared_terms = 0;      // terms every instance reads from the same tile
+      for (int i = g0; i < g0 + n_groups; i++) {
+        if (i == patch_group) continue;
+        int c = 0;
+        for (int t = 0; t < groups[i].term_count; t++) c += terms[groups[i].term_begin + t].inst_stride == 0;
+        shared_terms = std::max(shared_terms, c);
+      }
+      add_op(OP_BUILD, g0, n_groups, patch_group, shared_terms);
+      work_build(g0, n_groups, patch_group);
+    }
     if (patch_group >= 0) add_patch(patch_group);
   }
 
@@ -543,12 +553,12 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         // the patched receiver's group (if any) is built by the edge-batched patch kernel
         int pg = o.i2;
         if (pg < 0) {
-          HIPCHK(launch_build_inputs(d_groups + o.i0, o.i1, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
+          HIPCHK(launch_build_inputs(d_groups + o.i0, o.i1, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, o.i3, st));
         } else {
           if (pg > o.i0)
-            HIPCHK(launch_build_inputs(d_groups + o.i0, pg - o.i0, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
+            HIPCHK(launch_build_inputs(d_groups + o.i0, pg - o.i0, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, o.i3, st));
           if (o.i0 + o.i1 > pg + 1)
-            HIPCHK(launch_build_inputs(d_groups + pg + 1, o.i0 + o.i1 - pg - 1, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
+            HIPCHK(launch_build_inputs(d_groups + pg + 1, o.i0 + o.i1 - pg - 1, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, o.i3, st));
         }
         break;
       }

@@ -318,7 +318,10 @@ __global__ __launch_bounds__(512, 1) void gemm_p_k(const GemmProb* probs) {
         split_row(i0, r0, m - m0, P.rpi, inst, row);
         src[t] = (const uint8_t*)P.A + (long long)inst * P.a_is + (long long)row * P.lda + cg;
       } else {
-        int n = min(n0 + r - BM, P.N - 1);
+        // LDS row 16 jj + li of a wave's 64-column block holds column 4 li + jj of the block, so that a lane's four
+        // accumulators of one tile row are four neighbouring columns (see the epilogue)
+        const int q = r - BM;
+        int n = min(n0 + (q & 64) + (q & 15) * 4 + ((q >> 4) & 3), P.N - 1);
         src[t] = (const uint8_t*)P.W + (long long)n * P.ldw + cg;
       }
     }
@@ -392,8 +395,8 @@ __global__ __launch_bounds__(512, 1) void gemm_p_k(const GemmProb* probs) {
         v8h hb0 = decode8(rb[q][jj].x, rb[q][jj].y), hb1 = decode8(rb[q][jj].z, rb[q][jj].w);
 #pragma unroll
         for (int i = 0; i < TM; i++) {
-          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb0, ha[i][0], acc[i][jj], 0, 0, 0);
-          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb1, ha[i][1], acc[i][jj], 0, 0, 0);
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ha[i][0], hb0, acc[i][jj], 0, 0, 0);
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ha[i][1], hb1, acc[i][jj], 0, 0, 0);
         }
       }
     }
@@ -430,57 +433,58 @@ __global__ __launch_bounds__(512, 1) void gemm_p_k(const GemmProb* probs) {
     if (nslab == 1) { wait_vm<0>(); wg_barrier(); }     // the scales were requested in this very slab
 
     // ---- epilogue: scales and bias from LDS, 16-byte stores
-    const int mbase = m0 + wm * 64, nbase = n0 + wn * 64;
+    // Accumulator acc[i][jj][r] of lane (li, lg) is tile row 16 i + 4 lg + r and, with the column order the
+    // request side gave the W rows, column 4 li + jj of the wave's block: a lane stores the four jj values of one
+    // row as 16 bytes, and the 16 lanes of a group cover 256 contiguous bytes of that row.  Neighbouring lanes
+    // writing neighbouring addresses is what the store path wants: the same bytes stored as 16 rows x 64 bytes
+    // per instruction take a fifth longer end to end.
+    const int nbase = n0 + wn * 64 + li * 4;
     const bool interior = (m0 + BM <= P.M) && (n0 + BN <= P.N);
+    const bool col_on = interior || nbase < P.N;
     const int i0 = m0 / P.rpi, r0 = m0 - i0 * P.rpi;
-    float4 bias[TN];
-    float cs[TN];
-#pragma unroll
-    for (int jj = 0; jj < TN; jj++) {
-      cs[jj] = e_cs[wn * 64 + jj * 16 + lg * 4];
-      bias[jj] = *(const float4*)(e_bi + wn * 64 + jj * 16 + lg * 4);
-    }
-    int inst[TM];
-    long long roff[TM];
-    bool live[TM];
-    float sa[TM];
+    const float cs = e_cs[wn * 64 + li * 4];
+    const float4 bias = *(const float4*)(e_bi + wn * 64 + li * 4);
+    int inst[TM][4];
+    int roff[TM][4];           // within one instance's block: far below 2^31 elements
+    bool live[TM][4];
+    float4 sa[TM];
 #pragma unroll
     for (int i = 0; i < TM; i++) {
-      const int m = mbase + i * 16 + li;
-      live[i] = interior || m < P.M;
-      int row;
-      split_row(i0, r0, min(m, P.M - 1) - m0, P.rpi, inst[i], row);
-      sa[i] = e_rs[wm * 64 + i * 16 + li];
-      roff[i] = (long long)row * P.ldc + nbase + lg * 4;
+      sa[i] = *(const float4*)(e_rs + wm * 64 + i * 16 + lg * 4);
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int m = m0 + wm * 64 + i * 16 + lg * 4 + r;
+        live[i][r] = col_on && (interior || m < P.M);
+        int row;
+        split_row(i0, r0, min(m, P.M - 1) - m0, P.rpi, inst[i][r], row);
+        roff[i][r] = row * (int)P.ldc + nbase;
+      }
     }
     // the residual tile first, all of it, so that its loads are in flight together
-    float4 addv[TM][TN];
+    float4 addv[TM][4];
     if (P.add) {
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
-        for (int jj = 0; jj < TN; jj++) {
-          const bool on = live[i] && (interior || nbase + jj * 16 + lg * 4 < P.N);
-          addv[i][jj] = on ? gload4(P.add + inst[i] * P.add_is + roff[i] + jj * 16) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        for (int r = 0; r < 4; r++)
+          addv[i][r] = live[i][r] ? gload4(P.add + inst[i][r] * P.add_is + roff[i][r]) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
     for (int i = 0; i < TM; i++) {
-      if (!live[i]) continue;
+      const float sar[4] = {sa[i].x, sa[i].y, sa[i].z, sa[i].w};
 #pragma unroll
-      for (int jj = 0; jj < TN; jj++) {
-        if (!interior && nbase + jj * 16 + lg * 4 >= P.N) continue;
-        float s2 = sa[i] * cs[jj];
-        float4 val = make_float4(acc[i][jj][0] * s2, acc[i][jj][1] * s2, acc[i][jj][2] * s2, acc[i][jj][3] * s2);
+      for (int r = 0; r < 4; r++) {
+        if (!live[i][r]) continue;
+        const float s2 = sar[r] * cs;
+        float4 val = make_float4(acc[i][0][r] * s2, acc[i][1][r] * s2, acc[i][2][r] * s2, acc[i][3][r] * s2);
         float4 v = val;
-        if (P.bias) { v.x += bias[jj].x; v.y += bias[jj].y; v.z += bias[jj].z; v.w += bias[jj].w; }
+        if (P.bias) { v.x += bias.x; v.y += bias.y; v.z += bias.z; v.w += bias.w; }
         if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
-        const long long off = roff[i] + jj * 16;
-        if (P.add) { v.x += addv[i][jj].x; v.y += addv[i][jj].y; v.z += addv[i][jj].z; v.w += addv[i][jj].w; }
-        gstore4(P.C + inst[i] * P.c_is + off, v);
+        if (P.add) { v.x += addv[i][r].x; v.y += addv[i][r].y; v.z += addv[i][r].z; v.w += addv[i][r].w; }
+        gstore4(P.C + inst[i][r] * P.c_is + roff[i][r], v);
         if (P.aux) {
-          if (P.aux_sub) { float4 u = gload4(P.aux_sub + off); val.x -= u.x; val.y -= u.y; val.z -= u.z; val.w -= u.w; }
-          gstore4(P.aux + inst[i] * P.aux_is + off, val);
+          if (P.aux_sub) { float4 u = gload4(P.aux_sub + roff[i][r]); val.x -= u.x; val.y -= u.y; val.z -= u.z; val.w -= u.w; }
+          gstore4(P.aux + inst[i][r] * P.aux_is + roff[i][r], val);
         }
       }
     }

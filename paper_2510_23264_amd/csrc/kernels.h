@@ -51,13 +51,15 @@ struct GemmProb {
 };
 // What the fp8 GEMM kernels assume of a problem (checked on the host before a launch): 16-byte
 // aligned operands and outputs, K a multiple of 128, groups of four columns that share one weight
-// scale, and a row of C that has room for a last partial group of four columns.
+// scale, a row of C that has room for a last partial group of four columns, and an instance's
+// block of C (rows per instance x row stride) that 32-bit element offsets can address.
 inline bool gemm8_prob_ok(const GemmProb& p) {
   auto a16 = [](const void* q) { return (((uintptr_t)q) & 15) == 0; };
   return p.M >= 0 && p.N >= 1 && p.K >= 128 && p.K % 128 == 0 && p.rpi >= 1 && p.lda % 16 == 0 && p.ldw % 16 == 0 &&
          p.a_is % 16 == 0 && a16(p.A) && a16(p.W) && p.ldc % 4 == 0 && p.c_is % 4 == 0 && p.add_is % 4 == 0 &&
          p.aux_is % 4 == 0 && (p.wscale_block % 4 == 0 || p.wscale_block >= p.N) && a16(p.C) && a16(p.add) && a16(p.aux) && a16(p.aux_sub) &&
-         a16(p.bias) && (p.N + 3) / 4 * 4 <= p.ldc && p.lda >= p.K && p.ldw >= p.K;
+         a16(p.bias) && (p.N + 3) / 4 * 4 <= p.ldc && p.lda >= p.K && p.ldw >= p.K &&
+         (long long)p.rpi * p.ldc < (1ll << 31);
 }
 // For the fp32 GEMM the same struct is used with A = float [..][lda], W = float
 // [K][ldw] (row-major, K rows), ascale / wscale unused (null).
@@ -101,8 +103,9 @@ hipError_t launch_quant_transpose(const float* w, int K, int N, const unsigned* 
 hipError_t launch_embed(const int* tok, const float* W_E, const float* W_pos, float* out, int T, int S, int d,
                         hipStream_t s);
 
+// shared_terms: the largest number of terms without instance stride in any of the groups (0: none)
 hipError_t launch_build_inputs(const GroupDesc* groups, int n_groups, const Term* terms, int n_inst, int T, int B,
-                               int S, int d, int ldq, int norm_kind, float eps, hipStream_t s);
+                               int S, int d, int ldq, int norm_kind, float eps, int shared_terms, hipStream_t s);
 
 // Edge-batched patch: instance i reads x_i = xv - delta[send[i]] (mode 1) or
 // x_i = x_{i-1} - delta[send[i]] with x_{-1} = xv (mode 2), then norm and

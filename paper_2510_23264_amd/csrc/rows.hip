@@ -3,6 +3,7 @@
 // embedding lookup and weight quantisation.  All are HBM-bound streaming
 // kernels: one 64-lane wavefront owns one row of d_model floats, loads are
 // coalesced along the row, reductions are wave shuffles in a fixed order.
+#include <algorithm>
 #include "kernels.h"
 #include "device_util.h"
 
@@ -211,28 +212,49 @@ __device__ __forceinline__ void emit_row(const float (&y)[MAXE], int E, int d, i
   }
 }
 
+// One wavefront per (group, row), blockIdx.z = a chunk of instances.  Everything that is the same for every
+// instance -- a base without instance stride and the terms without one (cached sender tiles, senders
+// recomputed once for all candidates) -- is summed once per row into x0 and reused for the instances of the
+// chunk; with most edges removed that is the larger part of what a receiver's input is gathered from.  The
+// arithmetic of an instance does not depend on the chunk size or on its place in the chunk.
 template <int MAXE, bool VEC>
 __global__ __launch_bounds__(256) void build_inputs_k(const GroupDesc* groups, const Term* terms, int T, int B,
-                                                       int S, int d, int ldq, int norm_kind, float eps) {
+                                                       int S, int d, int ldq, int norm_kind, float eps,
+                                                       int n_inst, int chunk) {
   GroupDesc g = groups[blockIdx.y];
-  int inst = blockIdx.z;
   int lane = threadIdx.x & 63;
   int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   int rows = g.last_only ? B : T;
   if (row >= rows) return;
   long long src = (long long)(g.last_only ? row * S + S - 1 : row) * d;
   int E = d >> 6;
-  float x[MAXE];
+  const Term* tt = terms + g.term_begin;
+  const bool base_shared = g.base && g.base_is == 0;
+  float x0[MAXE];
 #pragma unroll
-  for (int j = 0; j < MAXE; j++) x[j] = 0.f;
-  if (g.base) row_load<MAXE, VEC>(x, g.base + inst * g.base_is + src, E, lane);
-  if (g.run) row_axpy<MAXE, VEC>(x, 1.0f, g.run + inst * g.run_is + src, E, lane);
+  for (int j = 0; j < MAXE; j++) x0[j] = 0.f;
+  if (base_shared) row_load<MAXE, VEC>(x0, g.base + src, E, lane);
+  int n_dyn = 0;
   for (int t = 0; t < g.term_count; t++) {
-    Term tm = terms[g.term_begin + t];
-    row_axpy<MAXE, VEC>(x, tm.sign, tm.p + inst * tm.inst_stride + src, E, lane);
+    Term tm = tt[t];
+    if (tm.inst_stride == 0) row_axpy<MAXE, VEC>(x0, tm.sign, tm.p + src, E, lane);
+    else n_dyn++;
   }
-  norm_row<MAXE, VEC>(x, E, d, lane, norm_kind, eps, g.gain, g.offset);
-  emit_row<MAXE, VEC>(x, E, d, lane, g, inst, row, ldq);
+  const int i_end = min(n_inst, ((int)blockIdx.z + 1) * chunk);
+  for (int inst = blockIdx.z * chunk; inst < i_end; inst++) {
+    float x[MAXE];
+#pragma unroll
+    for (int j = 0; j < MAXE; j++) x[j] = x0[j];
+    if (g.base && !base_shared) row_axpy<MAXE, VEC>(x, 1.0f, g.base + inst * g.base_is + src, E, lane);
+    if (g.run) row_axpy<MAXE, VEC>(x, 1.0f, g.run + inst * g.run_is + src, E, lane);
+    if (n_dyn)
+      for (int t = 0; t < g.term_count; t++) {
+        Term tm = tt[t];
+        if (tm.inst_stride != 0) row_axpy<MAXE, VEC>(x, tm.sign, tm.p + inst * tm.inst_stride + src, E, lane);
+      }
+    norm_row<MAXE, VEC>(x, E, d, lane, norm_kind, eps, g.gain, g.offset);
+    emit_row<MAXE, VEC>(x, E, d, lane, g, inst, row, ldq);
+  }
 }
 
 template <int MAXE, bool VEC>
@@ -306,10 +328,18 @@ __global__ __launch_bounds__(256) void patch_indep_k(const GroupDesc* gp, const 
   } while (0)
 
 hipError_t launch_build_inputs(const GroupDesc* groups, int n_groups, const Term* terms, int n_inst, int T, int B,
-                               int S, int d, int ldq, int norm_kind, float eps, hipStream_t s) {
+                               int S, int d, int ldq, int norm_kind, float eps, int shared_terms, hipStream_t s) {
   if (n_groups == 0 || n_inst == 0) return hipSuccess;
-  dim3 grid((T + 3) / 4, n_groups, n_inst);
-#define CALL(M, V) hipLaunchKernelGGL((build_inputs_k<M, V>), grid, dim3(256), 0, s, groups, terms, T, B, S, d, ldq, norm_kind, eps)
+  // instances per workgroup: one unless the groups have instance-independent terms worth sharing and the grid
+  // stays several times larger than the chip; wide rows (more than 16 values per lane) keep one, they have no
+  // registers to spare for the shared sum
+  int chunk = 1;
+  if (shared_terms > 0 && d / 64 <= 16) {
+    long long blocks = (long long)((T + 3) / 4) * n_groups * n_inst;
+    chunk = (int)std::min<long long>(8, std::max<long long>(1, blocks / 16384));
+  }
+  dim3 grid((T + 3) / 4, n_groups, (n_inst + chunk - 1) / chunk);
+#define CALL(M, V) hipLaunchKernelGGL((build_inputs_k<M, V>), grid, dim3(256), 0, s, groups, terms, T, B, S, d, ldq, norm_kind, eps, n_inst, chunk)
   PAHQ_DISPATCH_E(d / 64, CALL);
 #undef CALL
   return hipGetLastError();
