@@ -219,8 +219,50 @@ __device__ __forceinline__ void emit_row(const float (&y)[MAXE], int E, int d, i
 // arithmetic of an instance does not depend on the chunk size or on its place in the chunk.
 template <int MAXE, bool VEC>
 __global__ __launch_bounds__(256) void build_inputs_k(const GroupDesc* groups, const Term* terms, int T, int B,
-                                                       int S, int d, int ldq, int norm_kind, float eps,
-                                                       int n_inst, int chunk) {
+                                                       int S, int d, int ldq, int norm_kind, float eps) {
+  GroupDesc g = groups[blockIdx.y];
+  int inst = blockIdx.z;
+  int lane = threadIdx.x & 63;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int rows = g.last_only ? B : T;
+  if (row >= rows) return;
+  long long src = (long long)(g.last_only ? row * S + S - 1 : row) * d;
+  int E = d >> 6;
+  float x[MAXE];
+#pragma unroll
+  for (int j = 0; j < MAXE; j++) x[j] = 0.f;
+  // order of the sum: what every instance shares (a base without instance stride, terms without one), then the
+  // instance's own base / stream, then its own terms -- the order build_inputs_shared_k takes, so that a group
+  // gets the same bits from either kernel
+  const Term* tt = terms + g.term_begin;
+  const bool base_shared = g.base && g.base_is == 0;
+  if (base_shared) row_load<MAXE, VEC>(x, g.base + src, E, lane);
+  int n_dyn = 0;
+  for (int t = 0; t < g.term_count; t++) {
+    Term tm = tt[t];
+    if (tm.inst_stride == 0) row_axpy<MAXE, VEC>(x, tm.sign, tm.p + src, E, lane);
+    else n_dyn++;
+  }
+  if (g.base && !base_shared) row_axpy<MAXE, VEC>(x, 1.0f, g.base + inst * g.base_is + src, E, lane);
+  if (g.run) row_axpy<MAXE, VEC>(x, 1.0f, g.run + inst * g.run_is + src, E, lane);
+  if (n_dyn)
+    for (int t = 0; t < g.term_count; t++) {
+      Term tm = tt[t];
+      if (tm.inst_stride != 0) row_axpy<MAXE, VEC>(x, tm.sign, tm.p + inst * tm.inst_stride + src, E, lane);
+    }
+  norm_row<MAXE, VEC>(x, E, d, lane, norm_kind, eps, g.gain, g.offset);
+  emit_row<MAXE, VEC>(x, E, d, lane, g, inst, row, ldq);
+}
+
+// The same for groups that have terms every instance reads from the same tile (cached sender outputs, senders
+// recomputed once for all candidates), blockIdx.z = a chunk of instances: those terms and a base without
+// instance stride are summed once per row into x0 and reused for the instances of the chunk.  With most edges
+// removed that is the larger part of what a receiver's input is gathered from.  The arithmetic of an instance
+// does not depend on the chunk size or on its place in the chunk, and is that of the kernel above.
+template <int MAXE, bool VEC>
+__global__ __launch_bounds__(256) void build_inputs_shared_k(const GroupDesc* groups, const Term* terms, int T, int B,
+                                                              int S, int d, int ldq, int norm_kind, float eps,
+                                                              int n_inst, int chunk) {
   GroupDesc g = groups[blockIdx.y];
   int lane = threadIdx.x & 63;
   int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -330,16 +372,20 @@ __global__ __launch_bounds__(256) void patch_indep_k(const GroupDesc* gp, const 
 hipError_t launch_build_inputs(const GroupDesc* groups, int n_groups, const Term* terms, int n_inst, int T, int B,
                                int S, int d, int ldq, int norm_kind, float eps, int shared_terms, hipStream_t s) {
   if (n_groups == 0 || n_inst == 0) return hipSuccess;
-  // instances per workgroup: one unless the groups have instance-independent terms worth sharing and the grid
-  // stays several times larger than the chip; wide rows (more than 16 values per lane) keep one, they have no
-  // registers to spare for the shared sum
-  int chunk = 1;
+  // Groups with instance-independent terms go to the kernel that sums those once per chunk of instances (wide
+  // rows, more than 16 values per lane, have no registers to spare for the shared sum and stay with the plain
+  // kernel).  Both kernels give a group the same bits.
   if (shared_terms > 0 && d / 64 <= 16) {
     long long blocks = (long long)((T + 3) / 4) * n_groups * n_inst;
-    chunk = (int)std::min<long long>(8, std::max<long long>(1, blocks / 16384));
+    int chunk = (int)std::min<long long>(8, std::max<long long>(1, blocks / 16384));
+    dim3 grid((T + 3) / 4, n_groups, (n_inst + chunk - 1) / chunk);
+#define CALL(M, V) hipLaunchKernelGGL((build_inputs_shared_k<M, V>), grid, dim3(256), 0, s, groups, terms, T, B, S, d, ldq, norm_kind, eps, n_inst, chunk)
+    PAHQ_DISPATCH_E(d / 64, CALL);
+#undef CALL
+    return hipGetLastError();
   }
-  dim3 grid((T + 3) / 4, n_groups, (n_inst + chunk - 1) / chunk);
-#define CALL(M, V) hipLaunchKernelGGL((build_inputs_k<M, V>), grid, dim3(256), 0, s, groups, terms, T, B, S, d, ldq, norm_kind, eps, n_inst, chunk)
+  dim3 grid((T + 3) / 4, n_groups, n_inst);
+#define CALL(M, V) hipLaunchKernelGGL((build_inputs_k<M, V>), grid, dim3(256), 0, s, groups, terms, T, B, S, d, ldq, norm_kind, eps)
   PAHQ_DISPATCH_E(d / 64, CALL);
 #undef CALL
   return hipGetLastError();
