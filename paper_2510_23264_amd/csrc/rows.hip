@@ -520,35 +520,41 @@ __global__ __launch_bounds__(256) void hidden_quant_k(const float* up, const flo
 // The same quantiser for rows of 4-float multiples: TPR threads own a row (a wavefront, or the
 // whole block for long rows), the row is read once with 16-byte loads and stays in registers
 // between the abs-max and the encode, and four codes leave as one 32-bit store.
-template <int TPR, int NV>
+// The activation is a template parameter: as a run-time argument it costs a scalar branch per value.
+template <int TPR, int NV, int ACT>
 __global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const float* gate, long long h_is,
                                                           uint8_t* codes, long long c_is, float* scale,
-                                                          long long s_is, int T, int m, int ldq, int act) {
+                                                          long long s_is, int T, int m, int ldq) {
+  constexpr int act = ACT;
   constexpr int RPB = 256 / TPR;
   __shared__ float red[4];
   const int inst = blockIdx.y;
   const int row = blockIdx.x * RPB + (TPR == 64 ? (int)(threadIdx.x >> 6) : 0);
   const int t = (TPR == 64) ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
   const bool live = row < T;
-  const float* pu = up + inst * h_is + (long long)row * m;
-  const float* pg = gate ? gate + inst * h_is + (long long)row * m : nullptr;
-  float4 v[NV];
+  // loads are unconditional so that all of a row's loads are in flight together: a row past the end re-reads
+  // the last row, a group of four past the end of the row re-reads the last group; neither is stored
+  const long long ro = (long long)min(row, T - 1) * m;
+  const float* pu = up + inst * h_is + ro;
+  const float* pg = (act == 2) ? gate + inst * h_is + ro : nullptr;
+  float4 v[NV], g[NV];
+#pragma unroll
+  for (int j = 0; j < NV; j++) {
+    const int e = min((j * TPR + t) * 4, m - 4);
+    v[j] = *(const float4*)(pu + e);
+    if (act == 2) g[j] = *(const float4*)(pg + e);
+  }
   float am = 0.f;
 #pragma unroll
   for (int j = 0; j < NV; j++) {
-    int e = (j * TPR + t) * 4;
-    v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (live && e < m) {
-      v[j] = *(const float4*)(pu + e);
-      if (act) {
-        float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (act == 2) g = *(const float4*)(pg + e);
-        v[j].x = hidden_act(v[j].x, g.x, act);
-        v[j].y = hidden_act(v[j].y, g.y, act);
-        v[j].z = hidden_act(v[j].z, g.z, act);
-        v[j].w = hidden_act(v[j].w, g.w, act);
-      }
+    if (act) {
+      const float4 gg = (act == 2) ? g[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+      v[j].x = hidden_act(v[j].x, gg.x, act);
+      v[j].y = hidden_act(v[j].y, gg.y, act);
+      v[j].z = hidden_act(v[j].z, gg.z, act);
+      v[j].w = hidden_act(v[j].w, gg.w, act);
     }
+    if ((j * TPR + t) * 4 >= m) v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     am = fmaxf(fmaxf(am, fmaxf(fabsf(v[j].x), fabsf(v[j].y))), fmaxf(fabsf(v[j].z), fabsf(v[j].w)));
   }
   am = wave_max(am);
@@ -578,9 +584,13 @@ hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_i
                                hipStream_t s) {
   const bool vec = (m % 4 == 0) && (ldq % 4 == 0) && (h_is % 4 == 0) && (c_is % 4 == 0) &&
                    ((((uintptr_t)up) | ((uintptr_t)gate)) % 16 == 0) && (((uintptr_t)codes) % 4 == 0);
-#define HQV(TPR_, NV_)                                                                                              \
-  hipLaunchKernelGGL((hidden_quant_vec_k<TPR_, NV_>), dim3((T + 256 / TPR_ - 1) / (256 / TPR_), n_inst), dim3(256), \
-                     0, s, up, gate, h_is, codes, c_is, scale, s_is, T, m, ldq, act)
+#define HQV_(TPR_, NV_, ACT_)                                                                                    \
+  hipLaunchKernelGGL((hidden_quant_vec_k<TPR_, NV_, ACT_>), dim3((T + 256 / TPR_ - 1) / (256 / TPR_), n_inst),   \
+                     dim3(256), 0, s, up, gate, h_is, codes, c_is, scale, s_is, T, m, ldq)
+#define HQV(TPR_, NV_)                                                                                           \
+  do {                                                                                                           \
+    if (act == 1) HQV_(TPR_, NV_, 1); else if (act == 2) HQV_(TPR_, NV_, 2); else HQV_(TPR_, NV_, 0);            \
+  } while (0)
   if (vec && m <= 64 * 4 * 8) HQV(64, 8);
   else if (vec && m <= 64 * 4 * 12) HQV(64, 12);
   else if (vec && m <= 64 * 4 * 16) HQV(64, 16);
@@ -590,6 +600,7 @@ hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_i
     hipLaunchKernelGGL(hidden_quant_k, dim3(T, n_inst), dim3(256), 0, s, up, gate, h_is, codes, c_is, scale, s_is,
                        T, m, ldq, act);
 #undef HQV
+#undef HQV_
   return hipGetLastError();
 }
 
