@@ -206,7 +206,9 @@ int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
   }
   void* dterms = nullptr;
   if (!terms.empty()) PCHK(upload_table(M, terms.data(), terms.size() * sizeof(Term), &dterms));
-  HIPCHK(launch_tile_lincomb(M->xv, base, (const Term*)dterms, (int)terms.size(), M->tile, M->stream));
+  // the stream goes in after the removed senders' terms (form 1), a corrupted-run base before the kept ones
+  // (form 2): the order in which the row kernels add the same sum when they build this input for the current state
+  HIPCHK(launch_tile_lincomb(M->xv, base, (const Term*)dterms, (int)terms.size(), M->tile, sp.form == 1 ? 1 : 0, M->stream));
   if (M->plan.split_first) {
     // everything in v's layer that does not depend on the candidate: the other heads, and the
     // investigated head's two unpatched inputs

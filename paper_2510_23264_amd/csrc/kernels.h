@@ -118,7 +118,7 @@ hipError_t launch_xv_advance(float* xv, const float* delta0, long long delta_str
                              long long n_elem, hipStream_t s);
 // out = base + sum(terms) over n_elem elements (instance 0 of every term)
 hipError_t launch_tile_lincomb(float* out, const float* base, const Term* terms, int n_terms, long long n_elem,
-                               hipStream_t s);
+                               int base_last, hipStream_t s);
 hipError_t launch_tile_sub(float* out, const float* a, const float* b, long long n_elem, hipStream_t s);
 
 // exact = 0: FP8 matrix-core instruction; exact = 1: codes decoded to fp16, fp16 matrix cores (exact

@@ -426,17 +426,22 @@ hipError_t launch_xv_advance(float* xv, const float* delta0, long long delta_str
   return hipGetLastError();
 }
 
-__global__ void tile_lincomb_k(float* out, const float* base, const Term* terms, int n_terms, long long n) {
+// out = base + sum of terms, or (sum of terms) + base when base_last: the two orders in which build_inputs_k
+// adds a group's shared base (first) and an instance's stream (after the shared terms), so that a receiver's
+// input built here has the bits the row kernels give the same sum.
+__global__ void tile_lincomb_k(float* out, const float* base, const Term* terms, int n_terms, long long n,
+                               int base_last) {
   long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
-  float x = base ? base[i] : 0.f;
+  float x = (base && !base_last) ? base[i] : 0.f;
   for (int t = 0; t < n_terms; t++) x += terms[t].sign * terms[t].p[i];
+  if (base && base_last) x += base[i];
   out[i] = x;
 }
 hipError_t launch_tile_lincomb(float* out, const float* base, const Term* terms, int n_terms, long long n_elem,
-                               hipStream_t s) {
+                               int base_last, hipStream_t s) {
   hipLaunchKernelGGL(tile_lincomb_k, dim3((unsigned)((n_elem + 255) / 256)), dim3(256), 0, s, out, base, terms,
-                     n_terms, n_elem);
+                     n_terms, n_elem, base_last);
   return hipGetLastError();
 }
 

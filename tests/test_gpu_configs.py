@@ -66,6 +66,34 @@ def test_cfg3_sampled_edges():
     run_config("cfg3", 64)
 
 
+def test_cfg3_gather_with_most_edges_removed_is_batch_invariant():
+    """With 90 % of the edges removed a receiver's input is gathered from many terms, most of them tiles every
+    candidate shares; a full batch takes the kernel that sums those once for a chunk of instances, a batch of one
+    does not chunk.  The KL of a candidate has the same bits either way, also against the current state when the
+    candidate's edge is already removed."""
+    import paper_2510_23264_amd as P
+    shape, w, clean, corrupt, spec = synth.make_workload("cfg3")
+    gm = P.Model(shape, w, spec["B"], spec["S"], precision=P.PAHQ, max_batch_edges=64)
+    try:
+        gm.clean_cache(clean, corrupt)
+        n_recv = P.n_receivers(gm.cfg)
+        removed = removed_flat(gm.cfg, P, 0.9, 77, 0)
+        gm.set_removed(removed)
+        r = n_recv // 2                       # a receiver in the middle of the model: six layers are recomputed
+        n_up = P.n_upstream(gm.cfg, r)
+        senders = np.arange(n_up, dtype=np.int32)[:64]
+        batch = gm.eval_edges(r, senders)
+        ones = np.array([gm.eval_edges(r, senders[i:i + 1])[0] for i in range(0, senders.size, 9)], np.float32)
+        assert (ones.view(np.uint32) == batch[::9].view(np.uint32)).all()
+        off = int(sum(P.n_upstream(gm.cfg, q) for q in range(r)))
+        gone = [int(u) for u in senders if removed[off + int(u)]]
+        assert gone
+        cur = np.float32(gm.eval_current(r))
+        assert all(np.float32(batch[u]).view(np.uint32) == cur.view(np.uint32) for u in gone)
+    finally:
+        gm.close()
+
+
 def test_cfg3_sampled_edges_fp8_matrix_core_adder():
     run_config("cfg3", 64, mma=0, rtol=2.5e-2)
 
