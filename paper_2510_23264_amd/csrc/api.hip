@@ -125,6 +125,8 @@ size_t layout(pahq_model* M, char* base) {
   }
   M->slots = b.take<float>((size_t)M->pool_tiles * tile);
   M->row_kl = b.take<double>(n * B); M->kl_dev = b.take<double>(M->ncap);
+  M->psum_clean = b.take<double>(B); M->psum_ref = b.take<double>(B);
+  M->kl_npart = kl_parts_per_row((int)V); M->kl_part = b.take<float>(n * B * (size_t)M->kl_npart * 4);
   M->arena.slot_bytes = arena_slot_bytes(M);
   for (int i = 0; i < Arena::SLOTS; i++) M->arena.dev[i] = b.take<char>(M->arena.slot_bytes);
   return (b.off + 255) / 256 * 256;

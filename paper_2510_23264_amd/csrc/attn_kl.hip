@@ -315,4 +315,56 @@ hipError_t launch_kl(const float* logits, long long l_is, const float* ref_logit
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ KL from the parts the unembedding left
+// One wavefront per row.  The row's log-sum-exp from its (max, sum) parts: global maximum first, then
+// the rescaled sums in fp64, lanes striding over the parts and a butterfly at the end -- an order
+// that depends on nothing but the number of parts, so the reference row and a candidate row with the
+// same logits get the same bits and their difference is an exact zero.
+__global__ __launch_bounds__(64) void kl_reduce_k(const float* part, int npart, int B, const double* ref_logz,
+                                                  const double* ref_psum, double* logz, double* row_kl) {
+  const int row = blockIdx.x, lane = threadIdx.x;
+  const float4* p = (const float4*)part + (long long)row * npart;
+  float mx = -3.0e38f;
+  for (int t = lane; t < npart; t += 64) mx = fmaxf(mx, p[t].x);
+  mx = wave_max(mx);
+  double se = 0.0, a = 0.0;
+  for (int t = lane; t < npart; t += 64) {
+    const float4 q = p[t];
+    se += (double)q.y * (double)expf(q.x - mx);
+    a += (double)q.z;
+  }
+  se = wave_sum_d(se);
+  a = wave_sum_d(a);
+  const double lz = (double)mx + log(se);
+  if (lane == 0) {
+    if (logz) logz[row] = lz;
+    if (row_kl) { const int b = row % B; row_kl[row] = a - (ref_logz[b] - lz) * ref_psum[b]; }
+  }
+}
+hipError_t launch_kl_reduce(const float* kl_part, int npart, int rows, int B, const double* ref_logz,
+                            const double* ref_psum, double* logz, double* row_kl, double* kl, hipStream_t s) {
+  if (rows == 0) return hipSuccess;
+  hipLaunchKernelGGL(kl_reduce_k, dim3(rows), dim3(64), 0, s, kl_part, npart, B, ref_logz, ref_psum, logz, row_kl);
+  if (kl) hipLaunchKernelGGL(kl_mean_k, dim3((rows / B + 63) / 64), dim3(64), 0, s, row_kl, kl, rows / B, B);
+  return hipGetLastError();
+}
+
+// Sum of a reference row's probabilities (1 up to rounding; the KL uses the sum it gets).
+__global__ __launch_bounds__(256) void ref_probs_k(const float* logits, const double* logz, double* psum, int V,
+                                                   int ldv) {
+  __shared__ double redd[4];
+  const int b = blockIdx.x;
+  const float* x = logits + (long long)b * ldv;
+  const float lz = (float)logz[b];
+  double s = 0.0;
+  for (int v = threadIdx.x; v < V; v += 256) s += (double)expf(x[v] - lz);
+  s = block_sum_d(s, redd);
+  if (threadIdx.x == 0) psum[b] = s;
+}
+hipError_t launch_ref_probs(const float* logits, const double* logz, double* psum, int B, int V, int ldv,
+                            hipStream_t s) {
+  hipLaunchKernelGGL(ref_probs_k, dim3(B), dim3(256), 0, s, logits, logz, psum, V, ldv);
+  return hipGetLastError();
+}
+
 }  // namespace pahq

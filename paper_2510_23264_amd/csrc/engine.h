@@ -82,6 +82,8 @@ struct pahq_model {
   uint8_t* lastcodes; float* lastscale; float* logits;
   float* slots; long long pool_tiles;
   double *row_kl, *kl_dev;
+  double *psum_clean, *psum_ref;          // [B] sums of the reference rows' probabilities
+  float* kl_part; int kl_npart;           // [nmax * B][kl_npart][4]: what the unembedding leaves of a scored pass
   double* kl_host;                        // pinned
   int* send_host;                         // pinned
   int ncap;                               // candidates one host round trip can carry (size of the send / kl arrays)

@@ -65,7 +65,7 @@ void make_plan(pahq_model* M, int p0, int v, RecvPlan& out) {
 
 namespace {
 
-enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH, OP_OPROJ };
+enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH, OP_OPROJ, OP_KLRED, OP_PREF };
 struct Op { OpType t; int i0, i1, i2, i3; void* p0; void* p1; double flops, bytes; };
 
 struct Stream { float* p; long long is; };
@@ -153,7 +153,8 @@ struct Builder {
       const GemmProb& q = probs[i];
       const double M_ = q.M, N_ = q.N, K_ = q.k_real, eb = q.ascale ? 1.0 : 4.0;
       f += 2.0 * M_ * N_ * K_;
-      by += eb * (M_ * K_ + N_ * K_) + 4.0 * M_ * N_ + (q.ascale ? 4.0 * M_ : 0.0) + (q.add ? 4.0 * M_ * N_ : 0.0) +
+      by += eb * (M_ * K_ + N_ * K_) + (q.C ? 4.0 * M_ * N_ : 0.0) + (q.kl_ref ? 4.0 * (double)q.rpi * N_ : 0.0) +
+            (q.ascale ? 4.0 * M_ : 0.0) + (q.add ? 4.0 * M_ * N_ : 0.0) +
             (q.aux ? 4.0 * M_ * N_ : 0.0) + (q.aux_sub ? 4.0 * (double)q.rpi * N_ : 0.0);
     }
     ops.back().flops = f;
@@ -462,6 +463,35 @@ struct Builder {
     int pb = (int)probs.size();
     probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1, M->u_codes, Kd,
                           M->u_scale, V, M->b_U, lg, lg_is, Vp, 0, B, V, Kd, d));
+    // With exact sums the unembedding itself reduces its rows to the parts of a log-sum-exp and of the KL
+    // against the reference (one row of parts instead of one row of logits per candidate and sequence); the
+    // reference passes also keep their logits and get their log-sum-exp from the same parts, so that a candidate
+    // with the reference's logits scores exactly 0.  The FP8 matrix-core mode keeps the two-kernel path.
+    const bool fused = M->cfg.mma == PAHQ_MMA_F16_EXACT;
+    const bool ref_pass = a.kind == BASE_CLEAN || a.kind == PI_REF;
+    if (fused && (ref_pass || general)) {
+      GemmProb& q = probs.back();
+      q.kl_part = M->kl_part; q.kl_npart = M->kl_npart;
+      if (general) {
+        q.C = nullptr;
+        q.kl_ref = has_pi ? M->ref_logits : M->logits_clean;
+        q.kl_ref_logz = has_pi ? M->ref_logz : M->logz_clean;
+      }
+      add_op(OP_GEMM8, pb, 1, B * a.n, V, (void*)1); work_gemm(pb);
+      const double part_bytes = (double)a.n * B * M->kl_npart * 16.0;
+      ops.back().bytes += part_bytes;
+      if (ref_pass) {
+        const bool cl = a.kind == BASE_CLEAN;
+        add_op(OP_KLRED, 0, 0, 0, 0, cl ? M->logz_clean : M->ref_logz, nullptr);
+        ops.back().bytes = part_bytes;
+        add_op(OP_PREF, 0, 0, 0, 0, cl ? (void*)M->logits_clean : (void*)M->ref_logits, nullptr);
+        ops.back().bytes = (double)B * V * 4.0;
+      } else {
+        add_op(OP_KLRED, 1, 0, 0, 0, has_pi ? M->ref_logz : M->logz_clean, has_pi ? M->psum_ref : M->psum_clean);
+        ops.back().bytes = part_bytes;
+      }
+      return;
+    }
     add_op(OP_GEMM8, pb, 1, B * a.n, V); work_gemm(pb);
     if (a.kind == BASE_CLEAN) add_op(OP_LOGZ, 0, 0, 0, 0, M->logits_clean, M->logz_clean);
     else if (a.kind == PI_REF) add_op(OP_LOGZ, 0, 0, 0, 0, M->ref_logits, M->ref_logz);
@@ -534,7 +564,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
   // ---- launch
   const int n = a.n, T = M->T, B = M->B, S = M->S, d = M->d;
   hipStream_t st = M->stream;
-  static const int cls_of[] = {0, 2, 3, 4, 5, 6, 7, 8, 1, 9};   // OpType -> kernel class
+  static const int cls_of[] = {0, 2, 3, 4, 5, 6, 7, 8, 1, 9, 8, 7};   // OpType -> kernel class
   const bool prof_pass = M->prof_on && (M->prof_pass++ % M->prof_every) == 0;
   for (const Op& o : b.ops) {
     int pair = -1;
@@ -574,8 +604,23 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
                     p.M, p.N, p.K, p.lda, p.ldw, p.ldc, p.a_is, p.c_is, p.add_is, p.aux_is, p.wscale_block, p.A, p.W, (void*)p.C, (void*)p.add, (void*)p.aux, (void*)p.aux_sub, (void*)p.bias);
             return PAHQ_EINVAL;
           }
-        HIPCHK(launch_gemm_fp8(d_probs + o.i0, o.i1, o.i2, o.i3, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
+        if (o.p0) HIPCHK(launch_gemm_fp8_kl(d_probs + o.i0, o.i1, o.i2, o.i3, st));      // log-softmax / KL epilogue
+        else {
+          for (int q = 0; q < o.i1; q++) if (b.probs[o.i0 + q].kl_part || !b.probs[o.i0 + q].C) return PAHQ_EINVAL;
+          HIPCHK(launch_gemm_fp8(d_probs + o.i0, o.i1, o.i2, o.i3, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
+        }
         break;
+      case OP_KLRED:
+        if (o.i0 == 0) HIPCHK(launch_kl_reduce(M->kl_part, M->kl_npart, B, B, nullptr, nullptr, (double*)o.p0, nullptr, nullptr, st));
+        else HIPCHK(launch_kl_reduce(M->kl_part, M->kl_npart, n * B, B, (const double*)o.p0, (const double*)o.p1, nullptr,
+                                     M->row_kl, M->kl_dev + a.io_off, st));
+        break;
+      case OP_PREF: {
+        const bool cl = o.p0 == (void*)M->logits_clean;
+        HIPCHK(launch_ref_probs((const float*)o.p0, cl ? M->logz_clean : M->ref_logz, cl ? M->psum_clean : M->psum_ref, B,
+                                M->V, M->Vp, st));
+        break;
+      }
       case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, o.i2, o.i3, st)); break;
       case OP_ATTN:
         HIPCHK(launch_attention(b.asrcs[o.i0], M->zcodes, (long long)T * M->H * M->Kh,

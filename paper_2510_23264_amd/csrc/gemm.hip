@@ -123,6 +123,59 @@ __device__ __forceinline__ void epi_store(const EpiPre<TM, TN>& E, const GemmPro
   }
 }
 
+// The log-softmax / KL epilogue (the unembedding of a scored pass): nothing of a row has to reach
+// memory but, per 64-column part of it, the running maximum, the sum of exponentials against it and
+// the part's share of sum_v p_ref[v] (ref[v] - x[v]), p_ref[v] = exp(ref[v] - logz_ref).  A lane holds 16 values of a row (four groups
+// of four columns); the four lanes that share the row combine through two shuffles.  Columns past N
+// count as -3e38 (their exponentials vanish) and have p_ref = 0.  The order of every sum is fixed by the lane layout alone, so equal
+// logits give equal parts whatever the problem's number of rows.
+template <int TM, int TN>
+__device__ __forceinline__ void epi_kl(const EpiPre<TM, TN>& E, const GemmProb& P, const v4f (&acc)[TM][TN],
+                                       int mbase, int nbase, int li, int lg, int part) {
+  const float NEG = -3.0e38f;
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    const int m = mbase + i * 16 + li;
+    const bool row_on = m < P.M;
+    const int inst = E.inst[i], row = E.row[i];
+    float c[TN][4];
+    float mx = NEG;
+    const float lzr = P.kl_ref ? (float)P.kl_ref_logz[row] : 0.f;
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int nb = nbase + j * 16 + lg * 4;
+      const float s2 = E.sa[i] * E.sw[j];
+      float4 v = make_float4(acc[i][j][0] * s2, acc[i][j][1] * s2, acc[i][j][2] * s2, acc[i][j][3] * s2);
+      if (P.bias) { v.x += E.bias[j].x; v.y += E.bias[j].y; v.z += E.bias[j].z; v.w += E.bias[j].w; }
+      if (P.C && row_on && nb < P.N) gstore4(P.C + inst * P.c_is + (long long)row * P.ldc + nb, v);
+      c[j][0] = nb + 0 < P.N ? v.x : NEG; c[j][1] = nb + 1 < P.N ? v.y : NEG;
+      c[j][2] = nb + 2 < P.N ? v.z : NEG; c[j][3] = nb + 3 < P.N ? v.w : NEG;
+      mx = fmaxf(fmaxf(mx, fmaxf(c[j][0], c[j][1])), fmaxf(c[j][2], c[j][3]));
+    }
+    float se = 0.f, a = 0.f;
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int nb = nbase + j * 16 + lg * 4;
+#pragma unroll
+      for (int r = 0; r < 4; r++) se += (c[j][r] > -1.0e38f) ? __expf(c[j][r] - mx) : 0.f;
+      if (P.kl_ref && row_on && nb < P.N) {
+        // reference probabilities from the reference logits (one fast exponential each, relative error 1e-6,
+        // instead of a second load); a column past N has p = 0 exactly through the select
+        const float4 rr = gload4(P.kl_ref + (long long)row * P.ldc + nb);
+        const float p0 = __expf(rr.x - lzr), p1 = nb + 1 < P.N ? __expf(rr.y - lzr) : 0.f,
+                    p2 = nb + 2 < P.N ? __expf(rr.z - lzr) : 0.f, p3 = nb + 3 < P.N ? __expf(rr.w - lzr) : 0.f;
+        a += p0 * (rr.x - c[j][0]) + p1 * (rr.y - c[j][1]) + p2 * (rr.z - c[j][2]) + p3 * (rr.w - c[j][3]);
+      }
+    }
+    float ma = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    ma = fmaxf(ma, __shfl_xor(ma, 32, 64));
+    se *= __expf(mx - ma);                 // 0 * exp(0) for a lane whose columns are all past N
+    se += __shfl_xor(se, 16, 64); se += __shfl_xor(se, 32, 64);
+    a += __shfl_xor(a, 16, 64); a += __shfl_xor(a, 32, 64);
+    if (lg == 0 && row_on) gstore4(P.kl_part + ((long long)m * P.kl_npart + part) * 4, make_float4(ma, se, a, 0.f));
+  }
+}
+
 // ------------------------------------------------------------------ exact sums (fp16 matrix cores)
 // LDS rows are 128 bytes without padding; the 16-byte chunk c of row r sits at chunk position
 // c ^ (r & 7), so the 16-byte operand reads of 8 consecutive rows cover all 32 banks.  A load
@@ -263,7 +316,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
     // `early`; after this wait nothing the wave has to wait for precedes the stores
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(0x0F70);
-    epi_store<TM, TN>(E, P, acc, mbase, nbase, li, lg);
+    if (P.kl_part) epi_kl<TM, TN>(E, P, acc, mbase, nbase, li, lg, (n0 / BN) * WAVES_N + wn);
+    else epi_store<TM, TN>(E, P, acc, mbase, nbase, li, lg);
     if (!more) break;
     slab0_here = true;       // the barrier at the top publishes slab 0
     j = jn; m0 = m0n; n0 = n0n;
@@ -594,6 +648,17 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_k(const GemmPr
     }
   }
   epi_store<TM, TN>(E, P, acc, mbase, nbase, li, lg);
+}
+
+// Problems with the log-softmax / KL epilogue: always the 128 x 128 kernel, whose column tiling the number
+// of parts per row (kl_parts_per_row) is derived from.
+hipError_t launch_gemm_fp8_kl(const GemmProb* probs, int n_probs, int max_M, int max_N, hipStream_t s) {
+  if (n_probs == 0 || max_M == 0 || max_N == 0) return hipSuccess;
+  int tiles = ((max_M + 127) / 128) * ((max_N + 127) / 128);
+  int gx = (tiles + 7) / 8 * 8;
+  if (gx > 512) gx = 512;
+  hipLaunchKernelGGL((gemm_x_k<2, 2, 4, 4>), dim3(gx, n_probs), dim3(256), 0, s, probs);
+  return hipGetLastError();
 }
 
 hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, hipStream_t s) {

@@ -48,7 +48,14 @@ struct GemmProb {
   const float* aux_sub;                                      // instance-independent, row stride ldc; may be null
   int M, N, K;
   int ws_shift;        // log2(wscale_block) when it is a power of two, else -1 (the kernels then divide)
+  // Log-softmax / KL epilogue (launch_gemm_fp8_kl only; kl_part == null: none).  Instead of, or next to, the
+  // result rows the kernel leaves, per row and per 64-column part p of the row, (max, sum exp(x - max),
+  // sum p_ref * (kl_ref - x), 0) in kl_part[row][p] with p_ref = exp(kl_ref - kl_ref_logz); kl_ref is [rpi][ldc]
+  // (reference logits), kl_ref_logz [rpi]; both may be null (then the third value is 0).  C may be null.
+  const float* kl_ref; const double* kl_ref_logz; float* kl_part; int kl_npart; int pad_;
 };
+// Parts per row of the log-softmax / KL epilogue (128-column tiles, two wavefronts across).
+inline int kl_parts_per_row(int N) { return (N + 127) / 128 * 2; }
 // What the fp8 GEMM kernels assume of a problem (checked on the host before a launch): 16-byte
 // aligned operands and outputs, K a multiple of 128, groups of four columns that share one weight
 // scale, a row of C that has room for a last partial group of four columns, and an instance's
@@ -59,7 +66,9 @@ inline bool gemm8_prob_ok(const GemmProb& p) {
          p.a_is % 16 == 0 && a16(p.A) && a16(p.W) && p.ldc % 4 == 0 && p.c_is % 4 == 0 && p.add_is % 4 == 0 &&
          p.aux_is % 4 == 0 && (p.wscale_block % 4 == 0 || p.wscale_block >= p.N) && a16(p.C) && a16(p.add) && a16(p.aux) && a16(p.aux_sub) &&
          a16(p.bias) && (p.N + 3) / 4 * 4 <= p.ldc && p.lda >= p.K && p.ldw >= p.K &&
-         (long long)p.rpi * p.ldc < (1ll << 31);
+         (long long)p.rpi * p.ldc < (1ll << 31) && (p.C || p.kl_part) &&
+         (!p.kl_part || (p.kl_npart == kl_parts_per_row(p.N) && a16(p.kl_part) && a16(p.kl_ref) &&
+                         (!p.kl_ref == !p.kl_ref_logz) && !p.add && !p.aux && p.act == 0));
 }
 // For the fp32 GEMM the same struct is used with A = float [..][lda], W = float
 // [K][ldw] (row-major, K rows), ascale / wscale unused (null).
@@ -117,6 +126,15 @@ hipError_t launch_patch_build(const GroupDesc* g, const float* xv, const float* 
 hipError_t launch_xv_advance(float* xv, const float* delta0, long long delta_stride, const int* send, int k,
                              long long n_elem, hipStream_t s);
 // out = base + sum(terms) over n_elem elements (instance 0 of every term)
+hipError_t launch_gemm_fp8_kl(const GemmProb* probs, int n_probs, int max_M, int max_N, hipStream_t s);
+// One wavefront per row of kl_part: logz[row] = log sum exp of the row from its parts (if logz != null);
+// row_kl[row] = a - (ref_logz[row % B] - logz) * ref_psum[row % B] with a = the sum of the parts' third values
+// (if row_kl != null); then kl[i] = mean over the B rows of instance i (if kl != null).
+hipError_t launch_kl_reduce(const float* kl_part, int npart, int rows, int B, const double* ref_logz,
+                            const double* ref_psum, double* logz, double* row_kl, double* kl, hipStream_t s);
+// psum[b] = sum over v < V of exp(logits[b][v] - logz[b])
+hipError_t launch_ref_probs(const float* logits, const double* logz, double* psum, int B, int V, int ldv,
+                            hipStream_t s);
 hipError_t launch_tile_lincomb(float* out, const float* base, const Term* terms, int n_terms, long long n_elem,
                                int base_last, hipStream_t s);
 hipError_t launch_tile_sub(float* out, const float* a, const float* b, long long n_elem, hipStream_t s);
