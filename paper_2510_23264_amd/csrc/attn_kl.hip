@@ -23,7 +23,7 @@ typedef float v4f_a __attribute__((ext_vector_type(4)));
 // q, k and v each come with their own base pointer, instance stride and row
 // stride (AttnSrc), so one head can take a per-candidate query, key or value
 // while the other two are shared by all instances.
-template <int ST, int DH, bool ROPE>
+template <int ST, int DH, bool ROPE, bool STG>
 __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zcodes,
                                                          long long zc_is, float* zscale, long long zs_is, float* zf32,
                                                          long long zf_is, int f32_head, int n_pairs, int B, int S, int H,
@@ -41,6 +41,45 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
   const float* vb = src.v + inst * src.v_is + (long long)b * S * src.v_ld + hl * src.head_cols;
 
   float q[ST][CH], k[ST][CH];
+  // STG (one 16-position tile, d_head 64): the three 16 x 64 blocks go from global memory straight into this
+  // wave's 8 KB of LDS (q and k first; v takes q's place once q is in registers), four rows of 256 contiguous bytes per load instruction (lane l writes bytes [16 l, 16 l +
+  // 16) behind the base: row l >> 4, chunk position l & 15), and are read back in the operand layouts.  Position p
+  // of row r holds chunk p ^ r of the row, so that the 16 rows a 16-byte operand read touches lie in 16 different
+  // bank groups.  Loading each lane's operand directly costs the same bytes as 16-byte pieces of 16 different rows.
+  __shared__ __attribute__((aligned(1024))) float stage[STG ? 4 * 2 * 1024 : 4];
+  float* const sq = stage + (STG ? (threadIdx.x >> 6) * 2048 : 0);
+  if (STG) {
+    const float* mats[2] = {qb, kb};
+    const int lds_[2] = {src.q_ld, src.k_ld};
+#pragma unroll
+    for (int mtx = 0; mtx < 2; mtx++)
+#pragma unroll
+      for (int t = 0; t < 4; t++) {
+        const int r = 4 * t + (lane >> 4);
+        const float* gp = mats[mtx] + (long long)min(r, S - 1) * lds_[mtx] + (((lane & 15) ^ r) * 4);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
+                                         (__attribute__((address_space(3))) void*)(sq + mtx * 1024 + t * 256), 16, 0, 0);
+      }
+    __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): this wave's blocks are in LDS
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int cc = 0; cc < 4; cc++) {
+      const int pos4 = ((4 * g + cc) ^ i) * 4;
+      const float4 vq = *(const float4*)(sq + i * 64 + pos4), vk = *(const float4*)(sq + 1024 + i * 64 + pos4);
+      const bool on = i < S;
+      q[0][4 * cc] = on ? vq.x : 0.f; q[0][4 * cc + 1] = on ? vq.y : 0.f; q[0][4 * cc + 2] = on ? vq.z : 0.f; q[0][4 * cc + 3] = on ? vq.w : 0.f;
+      k[0][4 * cc] = on ? vk.x : 0.f; k[0][4 * cc + 1] = on ? vk.y : 0.f; k[0][4 * cc + 2] = on ? vk.z : 0.f; k[0][4 * cc + 3] = on ? vk.w : 0.f;
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): q and k are in registers
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int t = 0; t < 4; t++) {             // v into q's place; waited for after the softmax
+      const int r = 4 * t + (lane >> 4);
+      const float* gp = vb + (long long)min(r, S - 1) * src.v_ld + (((lane & 15) ^ r) * 4);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
+                                       (__attribute__((address_space(3))) void*)(sq + t * 256), 16, 0, 0);
+    }
+  } else {
 #pragma unroll
   for (int a = 0; a < ST; a++) {
     int pos = 16 * a + i;
@@ -53,6 +92,7 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
       q[a][c] = vq.x; q[a][c + 1] = vq.y; q[a][c + 2] = vq.z; q[a][c + 3] = vq.w;
       k[a][c] = vk.x; k[a][c + 1] = vk.y; k[a][c + 2] = vk.z; k[a][c + 3] = vk.w;
     }
+  }
   }
   if (ROPE) {
 #pragma unroll
@@ -120,14 +160,22 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
 
   // values: vv[bk][r][t] = V[key 16bk + 4g + r][16t + i]
   float vv[ST][4][NT];
+  if (STG) { __builtin_amdgcn_s_waitcnt(0x0F70); __builtin_amdgcn_wave_barrier(); }
 #pragma unroll
   for (int bk = 0; bk < ST; bk++)
 #pragma unroll
     for (int r = 0; r < 4; r++) {
       int kpos = 16 * bk + 4 * g + r;
-      const float* row = vb + (long long)kpos * src.v_ld + i;
+      if (STG) {
+        // V[kpos][16 t + i]: chunk 4 t + (i >> 2) of row kpos, word i & 3 of it
 #pragma unroll
-      for (int t = 0; t < NT; t++) vv[bk][r][t] = (kpos < S) ? row[16 * t] : 0.f;
+        for (int t = 0; t < NT; t++)
+          vv[bk][r][t] = (kpos < S) ? sq[kpos * 64 + (((4 * t + (i >> 2)) ^ kpos) * 4) + (i & 3)] : 0.f;
+      } else {
+        const float* row = vb + (long long)kpos * src.v_ld + i;
+#pragma unroll
+        for (int t = 0; t < NT; t++) vv[bk][r][t] = (kpos < S) ? row[16 * t] : 0.f;
+      }
     }
 
   const bool f32 = (h == f32_head);
@@ -162,13 +210,29 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
         for (int o = 8; o > 0; o >>= 1) am = fmaxf(am, __shfl_xor(am, o, 64));
         float scale = (am == 0.f) ? 1.0f : am / 448.0f;
         float inv = 1.0f / scale;
-        if (pos < S) {
+        if (STG) {
+          // codes of the 16 x 64 block are collected in this wave's LDS (the k block is no longer needed) and
+          // leave as one 16-byte store per lane below, instead of one byte per lane and column tile here
+          uint8_t* zb = (uint8_t*)(sq + 1024) + pos * 64 + i;
+#pragma unroll
+          for (int t = 0; t < NT; t++) zb[16 * t] = (uint8_t)e4m3_encode(z[t][rr] * inv);
+          if (pos < S && i == 0) zscale[inst * zs_is + tok * H + h] = scale;
+        } else if (pos < S) {
           uint8_t* o = zcodes + inst * zc_is + (tok * H + h) * ldz + i;
 #pragma unroll
           for (int t = 0; t < NT; t++) o[16 * t] = (uint8_t)e4m3_encode(z[t][rr] * inv);
           if (i == 0) zscale[inst * zs_is + tok * H + h] = scale;
         }
       }
+    }
+  }
+  if (STG && !f32) {
+    __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): the byte writes above
+    __builtin_amdgcn_wave_barrier();
+    const int pos = lane >> 2;                // token of the block, 16-byte piece lane & 3 of its 64 codes
+    if (pos < S) {
+      const uint4 w = *(const uint4*)((const uint8_t*)(sq + 1024) + lane * 16);
+      *(uint4*)(zcodes + inst * zc_is + (((long long)b * S + pos) * H + h) * ldz + (lane & 3) * 16) = w;
     }
   }
 }
@@ -180,7 +244,7 @@ hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is
   if (S > 32) return hipErrorInvalidValue;
   int n_pairs = n_inst * B * src.n_heads;
   dim3 grid((n_pairs + 3) / 4);
-#define ATT1(ST_, DH_, R_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_, R_>), grid, dim3(256), 0, s, src, zcodes, \
+#define ATT1(ST_, DH_, R_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_, R_, (ST_ == 1 && DH_ == 64 && !R_)>), grid, dim3(256), 0, s, src, zcodes, \
                                               zc_is, zscale, zs_is, zf32, zf_is, f32_head, n_pairs, B, S, H, ldz, rope, rope_theta)
 #define ATT(ST_, DH_) do { if (rope) ATT1(ST_, DH_, true); else ATT1(ST_, DH_, false); } while (0)
   if (S <= 16) {
