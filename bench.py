@@ -36,9 +36,9 @@ HBM_PEAK = 8000.0  # GB/s
 # plain streaming kernel of known size gives in the same runs).  Counters cannot be read from inside this
 # process, so the figures are the committed ones and apply to the default workload only (config 3, batch 64,
 # exact sums); any other invocation reports null.
-PMC_TRAFFIC_MB = {"gemm_fp8": (156.4, 151.7), "hidden_quant": (226.8, 56.8), "attention": (136.2, 12.8),
-                  "kl": (570.6, 0.1), "gather_norm_quant": (48.5, 12.3), "oproj_fused": (89.7, 51.6),
-                  "gemm_f32": (54.5, 32.1), "edge_patch": (100.0, 94.6)}
+PMC_TRAFFIC_MB = {"gemm_fp8": (163.1, 135.9), "hidden_quant": (226.8, 56.8), "attention": (125.0, 12.6),
+                  "kl": (34.0, 0.1), "gather_norm_quant": (48.5, 12.3), "oproj_fused": (89.5, 51.6),
+                  "gemm_f32": (54.5, 32.1), "edge_patch": (100.1, 94.6)}
 
 
 def all_edges_pass(gm, P, cfg, receivers, stride=1):
