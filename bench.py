@@ -60,12 +60,17 @@ def gather_regime(gm, P, cfg, receivers, torch):
     removed, where receivers no longer share their inputs and every one gathers its own sum of
     sender tiles.  A sample of receivers keeps it to a few seconds."""
     rng = np.random.default_rng(12345)
-    gm.set_removed((rng.random(gm.n_edges) < 0.9).astype(np.uint8))
+    removed = (rng.random(gm.n_edges) < 0.9).astype(np.uint8)
+    first_edge = np.concatenate([[0], np.cumsum([P.n_upstream(cfg, q) for q in range(P.n_receivers(cfg))])])
     sample = receivers[:: max(1, len(receivers) // 24)][::-1]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     n = done = 0
     for r in sample:                       # descending; at most about 15 s (the large configs stop early)
+        # the state a sweep is in when it reaches r: edges into earlier receivers are all still there
+        state = removed.copy()
+        state[: first_edge[int(r)]] = 0
+        gm.set_removed(state)
         senders = np.arange(P.n_upstream(cfg, int(r)), dtype=np.int32)
         gm.eval_edges(int(r), senders)
         n += senders.size

@@ -56,7 +56,8 @@ extern "C" {
 enum {
   PAHQ_OK = 0,
   PAHQ_EINVAL = -1,   /* bad argument (null pointer, id out of range, shape mismatch)   */
-  PAHQ_ESTATE = -2,   /* call out of order (e.g. eval before clean_cache)               */
+  PAHQ_ESTATE = -2,   /* call out of order (e.g. eval before clean_cache), or a removed  */
+                      /* set with edges into receivers upstream of the one evaluated    */
   PAHQ_ENOMEM = -3,   /* workspace too small                                            */
   PAHQ_EHIP = -4,     /* a HIP runtime call failed / no device                          */
   PAHQ_ENAN = -5,     /* non-finite weight                                              */
@@ -160,7 +161,13 @@ int pahq_clean_cache(pahq_model*, const int32_t* clean_tok, const int32_t* corru
  * precision set of `receiver` (third inference of the paper's algorithm; Eq.
  * Delta L).  Does not modify the removed set.  kl_out: host, n floats.  Any n
  * >= 0; batches of max_batch_edges are formed internally.  Results do not
- * depend on n, on the other candidates or on earlier calls. */
+ * depend on n, on the other candidates or on earlier calls.
+ * The removed set may only hold edges into receivers at or after `receiver`'s
+ * position in the forward pass (its own layer's inputs and everything
+ * downstream): what lies upstream is taken from the caches of the unmodified
+ * runs.  Every state of the sweep (receivers in descending order) is of this
+ * kind; any other removed set gives PAHQ_ESTATE, here and in
+ * pahq_eval_current. */
 int pahq_eval_edges(pahq_model*, int32_t receiver, const int32_t* sender_ids, int32_t n, float* kl_out);
 
 /* KL of the current removed set itself under the precision set of `receiver`. */

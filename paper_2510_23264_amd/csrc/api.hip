@@ -186,6 +186,13 @@ int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
   int kind, l, h, c;
   g.receiver_info(v, kind, l, h, c);
   ctx.v = v; ctx.p0 = g.pos_of_receiver(v);
+  // Everything upstream of v comes from the caches, which hold the runs with no edge removed: the removed set may
+  // only touch receivers at or after v's position (every state of the sweep is of this kind).
+  for (int w = 0; w < g.Nr; w++) {
+    if (g.pos_of_receiver(w) >= ctx.p0) continue;
+    const uint8_t* row = M->removed.data() + M->edge_off[w];
+    for (int s = 0, n_up = g.n_upstream(w); s < n_up; s++) if (row[s]) return PAHQ_ESTATE;
+  }
   ctx.pl = ctx.ph = -1;
   if (M->cfg.precision == PAHQ_PAHQ && kind == 0) { ctx.pl = l; ctx.ph = h; }
   if (ctx.pl >= 0 && (M->pi_l != ctx.pl || M->pi_h != ctx.ph)) {
@@ -652,7 +659,7 @@ const char* pahq_strerror(int code) {
   switch (code) {
     case PAHQ_OK: return "ok";
     case PAHQ_EINVAL: return "invalid argument";
-    case PAHQ_ESTATE: return "call out of order (run pahq_clean_cache first)";
+    case PAHQ_ESTATE: return "call out of order (run pahq_clean_cache first), or removed edges into receivers upstream of the one evaluated";
     case PAHQ_ENOMEM: return "workspace too small";
     case PAHQ_EHIP: return "HIP runtime error or no device";
     case PAHQ_ENAN: return "non-finite weight";

@@ -77,9 +77,9 @@ def test_cfg3_gather_with_most_edges_removed_is_batch_invariant():
     try:
         gm.clean_cache(clean, corrupt)
         n_recv = P.n_receivers(gm.cfg)
-        removed = removed_flat(gm.cfg, P, 0.9, 77, 0)
-        gm.set_removed(removed)
         r = n_recv // 2                       # a receiver in the middle of the model: six layers are recomputed
+        removed = removed_flat(gm.cfg, P, 0.9, 77, r)
+        gm.set_removed(removed)
         n_up = P.n_upstream(gm.cfg, r)
         senders = np.arange(n_up, dtype=np.int32)[:64]
         batch = gm.eval_edges(r, senders)

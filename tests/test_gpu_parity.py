@@ -183,6 +183,25 @@ def test_mid_llama_every_edge_kl(mid_llama):
     all_edges_parity(mid_llama)
 
 
+def test_short_sequence_d_head_64_every_edge_kl():
+    """d_head 64 without rotary positions takes the attention path that stages q, k, v through LDS; a sequence
+    shorter than the 16-position tile exercises its row clamping and masks (also with removed edges)."""
+    shape = ModelShape(n_layers=2, n_heads=2, d_head=64, d_model=128, d_mlp=256, vocab=300, n_ctx=10)
+    pr = make_mid(shape, 21, B=5)
+    try:
+        all_edges_parity(pr)
+        g = pr.g
+        for r in (g.OUT, g.n_receivers // 2, 2):
+            R = random_removed(g, 0.5, 40 + r, from_receiver=r)
+            pr.gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
+            got = pr.gm.eval_edges(r, np.arange(g.n_upstream(r), dtype=np.int32))
+            for u in range(g.n_upstream(r)):
+                want = pr.oa.kl_edge(r, u, removed=R)
+                assert kl_close(got[u], want), (r, u, got[u], want)
+    finally:
+        pr.close()
+
+
 def random_removed(g, frac, seed, from_receiver=0):
     rng = np.random.default_rng(seed)
     R = g.empty_removed()
@@ -214,9 +233,9 @@ def test_clean_patch_is_exactly_zero():
     pr = Pair(shape, w, clean, clean.copy())
     try:
         g = pr.g
-        R = random_removed(g, 0.5, 3)
-        pr.gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
         for r in (g.OUT, g.headin(1, 2, 1), g.headin(0, 0, 0)):
+            R = random_removed(g, 0.5, 3, from_receiver=r)
+            pr.gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
             got = pr.gm.eval_edges(r, np.arange(g.n_upstream(r), dtype=np.int32))
             assert (got == 0.0).all()
             assert pr.gm.eval_current(r) == 0.0
@@ -360,6 +379,17 @@ def test_error_codes(cfg1):
         gm.eval_edges(0, [1])              # sender 1 is not upstream of a layer-0 head input
     assert e.value.code == -1
     assert gm.eval_edges(0, []).size == 0
+    # a removed edge into a receiver upstream of the one evaluated is not a state the caches cover
+    g = cfg1.g
+    R = g.empty_removed()
+    R[0, 0] = True
+    gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
+    for call in (lambda: gm.eval_edges(g.OUT, [0]), lambda: gm.eval_current(g.OUT)):
+        with pytest.raises(p.PahqError) as e:
+            call()
+        assert e.value.code == -2
+    assert gm.eval_edges(0, [0]).size == 1       # the receiver itself and everything downstream may have removed edges
+    gm.set_removed(np.zeros(g.n_edges(), np.uint8))
     bad = cfg1.clean.copy(); bad[0, 0] = cfg1.shape.vocab
     with pytest.raises(p.PahqError) as e:
         gm.clean_cache(bad, cfg1.corrupt)
