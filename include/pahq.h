@@ -187,7 +187,8 @@ int pahq_eval_current(pahq_model*, int32_t receiver, float* kl_out);
 int pahq_acdc_sweep(pahq_model*, float tau, const int32_t* receivers, int32_t n_receivers,
                     uint8_t* kept, int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap);
 
-/* Removed set, canonical edge order, one byte per edge (1 = removed). */
+/* Removed set, canonical edge order, one byte per edge (1 = removed, 0 = kept).  Any set is stored; which
+ * sets an evaluation accepts is said at pahq_eval_edges. */
 int pahq_set_removed(pahq_model*, const uint8_t* removed);
 int pahq_get_removed(pahq_model*, uint8_t* removed);
 
@@ -211,9 +212,13 @@ int pahq_get_counters(pahq_model*, int64_t out[3]);
  * per kernel class, the number of launches, the summed event time and the
  * algorithmic work (floating-point operations of the contraction for the
  * matrix-core kernels; bytes that must be read and written for the streaming
- * kernels).  Classes: 0 gather+norm+quantise, 1 edge patch, 2 fp8 GEMM,
- * 3 fp32 GEMM, 4 attention, 5 stream update, 6 hidden quantise, 7 log-sum-exp,
- * 8 KL, 9 fused output projection + stream update (fp8 matrix cores).  Turning profiling on resets the counters. */
+ * kernels).  Classes: 0 gather+norm+quantise, 1 edge patch, 2 fp8 GEMM (with
+ * exact sums the unembedding's log-softmax / KL epilogue is part of it),
+ * 3 fp32 GEMM, 4 attention, 5 stream update, 6 hidden quantise, 7 log-sum-exp
+ * and reference probabilities, 8 KL (the reduction of the epilogue's parts, or
+ * the whole log-softmax + KL over stored logits in the FP8 matrix-core mode),
+ * 9 fused output projection + stream update (fp8 matrix cores).  Turning
+ * profiling on resets the counters. */
 typedef struct {
   int64_t launches;
   double ms;        /* sum of event-to-event times                                   */
