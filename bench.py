@@ -236,6 +236,11 @@ def main():
         "kernels_note": "per-class HIP-event times of one untimed pass with events around every launch",
         "sweep": sweeps, "gather_regime": gather,
     }
+    # what this device does on a pure matrix-core issue loop and on a streaming copy, measured now, next to the
+    # published peaks the roofline divides by
+    tf, gb = P.measure_ceilings()
+    out["ceilings"] = {"mfma_f16_issue_loop_TFLOPs": round(tf, 1), "stream_copy_GBps": round(gb, 1),
+                       "note": "micro-kernels of the library (pahq_measure_ceilings), all compute units busy"}
     if not args.no_cpu_baseline:
         gm.close()
         out["cpu_baseline"] = cpu_baseline(args.config, shape, w, clean, corrupt)

@@ -235,6 +235,14 @@ int pahq_set_profiling(pahq_model*, int32_t on);
 int pahq_set_profiling_sample(pahq_model*, uint32_t class_mask, int32_t every_nth_pass);
 int pahq_get_profile(pahq_model*, pahq_kernel_stat out[PAHQ_N_KERNEL_CLASSES]);
 
+/* Measured ceilings of the device, for reading the roofline fractions next to the published peaks (no model
+ * needed): the rate of a pure issue loop of the fp16 matrix-core instruction the exact GEMM multiplies with, all
+ * compute units busy for a few tens of milliseconds, and the rate (bytes read + written) of a streaming copy of
+ * half of `scratch` to its other half.  hip_stream: a hipStream_t or NULL; scratch: device memory, 256-byte
+ * aligned, at least 64 MiB (the caller's; its contents are overwritten).  Synchronises the stream. */
+int pahq_measure_ceilings(void* hip_stream, void* scratch, size_t scratch_bytes, double* mfma_f16_tflops,
+                          double* copy_gbs);
+
 const char* pahq_strerror(int code);
 void pahq_free(pahq_model*);            /* frees host state only; the workspace stays the caller's */
 

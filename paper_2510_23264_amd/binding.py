@@ -87,6 +87,7 @@ def lib():
             "pahq_set_profiling": [C.c_void_p, C.c_int32],
             "pahq_set_profiling_sample": [C.c_void_p, C.c_uint32, C.c_int32],
             "pahq_get_profile": [C.c_void_p, C.POINTER(KernelStat)],
+            "pahq_measure_ceilings": [C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double)],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -119,6 +120,16 @@ def edge_count(cfg): return _scalar(lib().pahq_edge_count, C.c_int64, cfg)
 def edge_id(cfg, s, r): return _scalar(lib().pahq_edge_id, C.c_int64, cfg, s, r)
 def node_of_receiver(cfg, r): return _scalar(lib().pahq_node_of_receiver, C.c_int32, cfg, r)
 def workspace_bytes(cfg, B, S): return _scalar(lib().pahq_workspace_bytes, C.c_size_t, cfg, B, S)
+
+
+def measure_ceilings(scratch_mib=1024):
+    """(fp16 matrix-core issue-loop TFLOP/s, streaming-copy GB/s read + written) of cuda:0, measured now."""
+    import torch
+    buf = torch.empty(int(scratch_mib) << 20, dtype=torch.uint8, device="cuda:0")
+    tf, gb = C.c_double(), C.c_double()
+    _chk(lib().pahq_measure_ceilings(C.c_void_p(torch.cuda.current_stream().cuda_stream), C.c_void_p(buf.data_ptr()),
+                                     C.c_size_t(buf.numel()), C.byref(tf), C.byref(gb)), "pahq_measure_ceilings")
+    return tf.value, gb.value
 
 
 class Model:

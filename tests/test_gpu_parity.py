@@ -369,6 +369,16 @@ def test_all_fp8_mode(mid):
         pr.close()
 
 
+def test_measured_ceilings_are_plausible():
+    p = P()
+    tf, gb = p.measure_ceilings(scratch_mib=256)
+    assert 200.0 < tf < 2600.0, tf          # between a tenth of and just above the published fp16 dense peak
+    assert 500.0 < gb < 16000.0, gb         # read + written: at most twice the published HBM rate
+    with pytest.raises(p.PahqError) as e:
+        p.measure_ceilings(scratch_mib=1)   # scratch below the stated minimum
+    assert e.value.code == -1
+
+
 def test_error_codes(cfg1):
     p = P()
     gm = cfg1.gm
