@@ -202,6 +202,33 @@ def test_short_sequence_d_head_64_every_edge_kl():
         pr.close()
 
 
+ODD = dict(n_layers=2, n_heads=2, d_head=64, d_model=128, d_mlp=256, vocab=300, n_ctx=10)
+
+
+@pytest.mark.parametrize("name,change,B", [
+    ("two ragged position tiles", {"n_ctx": 17}, 3), ("longest sequence", {"n_ctx": 32}, 2),
+    ("one head, one 64-wide row chunk", {"n_heads": 1, "d_model": 64}, 4), ("vocabulary below one column tile", {"vocab": 64}, 4),
+    ("one sequence", {}, 1), ("d_head 128", {"n_heads": 1, "d_head": 128}, 3), ("d_head 16", {"n_heads": 8, "d_head": 16}, 3),
+    ("rotary, RMSNorm, SwiGLU over two tiles", {"n_ctx": 17, "pos": 1, "norm": 1, "act": 2, "norm_eps": 1e-6}, 3),
+    ("attention only", {"d_mlp": 0}, 4), ("one layer", {"n_layers": 1}, 4)])
+def test_odd_shapes_every_edge_kl(name, change, B):
+    """Shapes at the edges of what the kernels tile for: every edge at the empty removed set and one sweep state."""
+    cfg = dict(ODD); cfg.update(change)
+    pr = make_mid(ModelShape(**cfg), 21, B=B)
+    try:
+        all_edges_parity(pr)
+        g = pr.g
+        r = g.n_receivers // 2
+        R = random_removed(g, 0.6, 5, from_receiver=r)
+        pr.gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
+        got = pr.gm.eval_edges(r, np.arange(g.n_upstream(r), dtype=np.int32))
+        for u in range(g.n_upstream(r)):
+            want = pr.oa.kl_edge(r, u, removed=R)
+            assert kl_close(got[u], want), (name, r, u, got[u], want)
+    finally:
+        pr.close()
+
+
 def random_removed(g, frac, seed, from_receiver=0):
     rng = np.random.default_rng(seed)
     R = g.empty_removed()
