@@ -143,9 +143,16 @@ __device__ __forceinline__ void row_sub(float (&y)[MAXE], const float (&a)[MAXE]
   }
 }
 
+// gain and offset of a norm, in the element map of the rows (offset only for LayerNorm)
+template <int MAXE, bool VEC>
+__device__ __forceinline__ void norm_params_load(float (&gn)[MAXE], float (&of)[MAXE], int E, int lane, int norm_kind,
+                                                 const float* gain, const float* offset) {
+  row_load<MAXE, VEC>(gn, gain, E, lane);
+  if (norm_kind == 0) row_load<MAXE, VEC>(of, offset, E, lane);
+}
 template <int MAXE, bool VEC>
 __device__ __forceinline__ void norm_row(float (&x)[MAXE], int E, int d, int lane, int norm_kind, float eps,
-                                         const float* gain, const float* offset) {
+                                         const float (&gn)[MAXE], const float (&of)[MAXE]) {
   float inv_d = 1.0f / (float)d;
   float rstd;
   if (norm_kind == 0) {
@@ -163,16 +170,20 @@ __device__ __forceinline__ void norm_row(float (&x)[MAXE], int E, int d, int lan
     for (int j = 0; j < MAXE; j++) if (j < E) v += x[j] * x[j];
     rstd = 1.0f / sqrtf(wave_sum(v) * inv_d + eps);
   }
-  float gn[MAXE], of[MAXE];
-  row_load<MAXE, VEC>(gn, gain, E, lane);
   if (norm_kind == 0) {
-    row_load<MAXE, VEC>(of, offset, E, lane);
 #pragma unroll
     for (int j = 0; j < MAXE; j++) if (j < E) x[j] = x[j] * rstd * gn[j] + of[j];
   } else {
 #pragma unroll
     for (int j = 0; j < MAXE; j++) if (j < E) x[j] = x[j] * rstd * gn[j];
   }
+}
+template <int MAXE, bool VEC>
+__device__ __forceinline__ void norm_row(float (&x)[MAXE], int E, int d, int lane, int norm_kind, float eps,
+                                         const float* gain, const float* offset) {
+  float gn[MAXE], of[MAXE];
+  norm_params_load<MAXE, VEC>(gn, of, E, lane, norm_kind, gain, offset);
+  norm_row<MAXE, VEC>(x, E, d, lane, norm_kind, eps, gn, of);
 }
 
 template <int MAXE, bool VEC>
@@ -262,10 +273,14 @@ __global__ __launch_bounds__(256) void build_inputs_k(const GroupDesc* groups, c
 template <int MAXE, bool VEC>
 __global__ __launch_bounds__(256) void build_inputs_shared_k(const GroupDesc* groups, const Term* terms, int T, int B,
                                                               int S, int d, int ldq, int norm_kind, float eps,
-                                                              int n_inst, int chunk) {
-  GroupDesc g = groups[blockIdx.y];
+                                                              int n_inst, int chunk, int n_groups) {
+  // Workgroup -> (row quad, group): all groups of a row quad run back to back on one XCD (workgroup id mod 8), so
+  // that a sender row several receivers of the layer gather is fetched into that XCD's L2 once.
+  const int xcd = blockIdx.x & 7, t_ = blockIdx.x >> 3;
+  const int gi = t_ % n_groups, rq = (t_ / n_groups) * 8 + xcd;
+  GroupDesc g = groups[gi];
   int lane = threadIdx.x & 63;
-  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  int row = rq * 4 + (threadIdx.x >> 6);
   int rows = g.last_only ? B : T;
   if (row >= rows) return;
   long long src = (long long)(g.last_only ? row * S + S - 1 : row) * d;
@@ -282,6 +297,8 @@ __global__ __launch_bounds__(256) void build_inputs_shared_k(const GroupDesc* gr
     if (tm.inst_stride == 0) row_axpy<MAXE, VEC>(x0, tm.sign, tm.p + src, E, lane);
     else n_dyn++;
   }
+  float gn[MAXE], of[MAXE];               // read once for the chunk, not once per instance
+  norm_params_load<MAXE, VEC>(gn, of, E, lane, norm_kind, g.gain, g.offset);
   const int i_end = min(n_inst, ((int)blockIdx.z + 1) * chunk);
   for (int inst = blockIdx.z * chunk; inst < i_end; inst++) {
     float x[MAXE];
@@ -294,7 +311,7 @@ __global__ __launch_bounds__(256) void build_inputs_shared_k(const GroupDesc* gr
         Term tm = tt[t];
         if (tm.inst_stride != 0) row_axpy<MAXE, VEC>(x, tm.sign, tm.p + inst * tm.inst_stride + src, E, lane);
       }
-    norm_row<MAXE, VEC>(x, E, d, lane, norm_kind, eps, g.gain, g.offset);
+    norm_row<MAXE, VEC>(x, E, d, lane, norm_kind, eps, gn, of);
     emit_row<MAXE, VEC>(x, E, d, lane, g, inst, row, ldq);
   }
 }
@@ -378,8 +395,9 @@ hipError_t launch_build_inputs(const GroupDesc* groups, int n_groups, const Term
   if (shared_terms > 0 && d / 64 <= 16) {
     long long blocks = (long long)((T + 3) / 4) * n_groups * n_inst;
     int chunk = (int)std::min<long long>(8, std::max<long long>(1, blocks / 16384));
-    dim3 grid((T + 3) / 4, n_groups, (n_inst + chunk - 1) / chunk);
-#define CALL(M, V) hipLaunchKernelGGL((build_inputs_shared_k<M, V>), grid, dim3(256), 0, s, groups, terms, T, B, S, d, ldq, norm_kind, eps, n_inst, chunk)
+    const int rq8 = ((T + 3) / 4 + 7) / 8 * 8;        // row quads, padded to the 8 XCDs (the padding exits at once)
+    dim3 grid(rq8 * n_groups, 1, (n_inst + chunk - 1) / chunk);
+#define CALL(M, V) hipLaunchKernelGGL((build_inputs_shared_k<M, V>), grid, dim3(256), 0, s, groups, terms, T, B, S, d, ldq, norm_kind, eps, n_inst, chunk, n_groups)
     PAHQ_DISPATCH_E(d / 64, CALL);
 #undef CALL
     return hipGetLastError();
