@@ -131,7 +131,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(candidates are independent and would be sharded across GPUs, see DESIGN.md)", file=sys.stderr)
+              "(candidates are independent: on several GPUs each would take a share of every batch)", file=sys.stderr)
         sys.exit(2)
 
     import torch
