@@ -56,7 +56,7 @@ extern "C" int pahq_measure_ceilings(void* hip_stream, void* scratch, size_t scr
   int rc = PAHQ_OK;
   float ms = 0.f;
   // ---- matrix cores: 256 workgroups x 8 waves x iters x 32 MFMAs of 16 x 16 x 32 (2 * 16 * 16 * 32 flops each)
-  const int grid = 256, iters = 20000;
+  const int grid = 256, iters = 80000;
   float* out = (float*)scratch;                       // 256 * 512 floats
   hipLaunchKernelGGL(mfma_issue_k, dim3(grid), dim3(512), 0, st, out, 200);
   hipEventRecord(e0, st);
