@@ -27,7 +27,7 @@ template <int ST, int DH, bool ROPE, bool STG>
 __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zcodes,
                                                          long long zc_is, float* zscale, long long zs_is, float* zf32,
                                                          long long zf_is, int f32_head, int n_pairs, int B, int S, int H,
-                                                         int ldz, int rope, float rope_theta) {
+                                                         int ldz, int rope, const float2* rope_tab) {
   constexpr int CH = DH / 4;        // columns of q / k per lane
   constexpr int NT = DH / 16;       // output column tiles
   const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -101,8 +101,9 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
 #pragma unroll
       for (int c = 0; c < CH; c++) {
         int col = (CH * g + c) % (DH / 2);
-        double ang = (double)pos * pow((double)rope_theta, -2.0 * (double)col / (double)DH);
-        float sn = (float)sin(ang), cs = (float)cos(ang);
+        // (cos, sin) of pos * theta^(-2 col / d_head), from the table rope_table_k filled once
+        const float2 t2 = rope_tab[pos * (DH / 2) + col];
+        float sn = t2.y, cs = t2.x;
         float pq = __shfl_xor(q[a][c], 32, 64), pk = __shfl_xor(k[a][c], 32, 64);
         // first half: x cos - y sin ; second half: x cos + y sin (y = the partner column)
         float sg = (g < 2) ? -sn : sn;
@@ -237,15 +238,31 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
   }
 }
 
+// tab[pos][col] = (cos, sin) of pos * theta^(-2 col / d_head) for col < d_head / 2: the angle in fp64, rounded
+// once, as the attention kernel used to compute it per element
+__global__ void rope_table_k(float2* tab, int n_pos, int dh, float theta) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_pos * (dh / 2)) return;
+  int pos = i / (dh / 2), col = i % (dh / 2);
+  double ang = (double)pos * pow((double)theta, -2.0 * (double)col / (double)dh);
+  tab[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+hipError_t launch_rope_table(float* tab, int n_pos, int dh, float theta, hipStream_t s) {
+  int n = n_pos * (dh / 2);
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(rope_table_k, dim3((n + 255) / 256), dim3(256), 0, s, (float2*)tab, n_pos, dh, theta);
+  return hipGetLastError();
+}
+
 hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is, float* zscale,
                             long long zs_is, float* zf32, long long zf_is, int f32_head, int n_inst, int B, int S,
-                            int H, int dh, int ldz, int rope, float rope_theta, hipStream_t s) {
+                            int H, int dh, int ldz, int rope, const float* rope_tab, hipStream_t s) {
   if (n_inst == 0) return hipSuccess;
   if (S > 32) return hipErrorInvalidValue;
   int n_pairs = n_inst * B * src.n_heads;
   dim3 grid((n_pairs + 3) / 4);
 #define ATT1(ST_, DH_, R_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_, R_, (ST_ == 1 && DH_ == 64 && !R_)>), grid, dim3(256), 0, s, src, zcodes, \
-                                              zc_is, zscale, zs_is, zf32, zf_is, f32_head, n_pairs, B, S, H, ldz, rope, rope_theta)
+                                              zc_is, zscale, zs_is, zf32, zf_is, f32_head, n_pairs, B, S, H, ldz, rope, (const float2*)rope_tab)
 #define ATT(ST_, DH_) do { if (rope) ATT1(ST_, DH_, true); else ATT1(ST_, DH_, false); } while (0)
   if (S <= 16) {
     if (dh == 16) ATT(1, 16); else if (dh == 32) ATT(1, 32); else if (dh == 64) ATT(1, 64);

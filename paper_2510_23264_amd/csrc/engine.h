@@ -63,6 +63,7 @@ struct pahq_model {
   float *W_E, *W_pos, *W_Q, *W_K, *W_V, *W_O, *b_Q, *b_K, *b_V, *b_O;
   float *ln1_g, *ln1_b, *ln2_g, *ln2_b, *W_in, *b_in, *W_gate, *W_out, *b_out, *lnf_g, *lnf_b, *W_U, *b_U;
   float* zeros_d;                         // [max(d, 64)] zeros (norm offset for RMSNorm)
+  float* rope_tab;                        // [32][dh / 2] (cos, sin) pairs of the rotary positions (null without them)
   float* bqkv;                            // [L][3][H][dh] fused projection bias
   uint8_t *qkv_codes, *o_codes, *in_codes, *gate_codes, *out_codes, *u_codes;
   float *qkv_scale, *o_scale, *in_scale, *gate_scale, *out_scale, *u_scale;

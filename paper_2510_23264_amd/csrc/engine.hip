@@ -625,7 +625,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
       case OP_ATTN:
         HIPCHK(launch_attention(b.asrcs[o.i0], M->zcodes, (long long)T * M->H * M->Kh,
                                 M->zscale, (long long)T * M->H, M->zf32, (long long)T * M->dh, o.i1, n, B, S, M->H,
-                                M->dh, M->Kh, M->cfg.pos == PAHQ_POS_ROPE, M->cfg.rope_theta, st));
+                                M->dh, M->Kh, M->cfg.pos == PAHQ_POS_ROPE, M->rope_tab, st));
         break;
       case OP_COMBINE: HIPCHK(launch_combine(d_cdesc, o.i0, d_csrc, n, M->tile, d, st)); break;
       case OP_OPROJ:

@@ -158,7 +158,9 @@ struct AttnSrc {
 };
 hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is, float* zscale,
                             long long zs_is, float* zf32, long long zf_is, int f32_head, int n_inst, int B, int S,
-                            int H, int dh, int ldz, int rope, float rope_theta, hipStream_t s);
+                            int H, int dh, int ldz, int rope, const float* rope_tab, hipStream_t s);
+// rope_tab: [n_pos][dh / 2] pairs (cos, sin), filled by launch_rope_table; read only when rope != 0, n_pos >= S
+hipError_t launch_rope_table(float* tab, int n_pos, int dh, float theta, hipStream_t s);
 
 hipError_t launch_combine(const CombineDesc* descs, int desc_index, const CombineSrc* srcs, int n_inst,
                           long long n_elem, int d, hipStream_t s);
