@@ -117,21 +117,17 @@ class Model:
             self._dec_cache[key] = a
         return a
 
-    def _quant_act(self, x, memo):
-        """Row-quantise an activation; `memo` (keyed by array identity) avoids
-        repeating the identical computation when several receivers share one input."""
-        if memo is not None and id(x) in memo:
-            return memo[id(x)][1:]
+    def _quant_act(self, x):
+        """Row-quantise an activation: decoded grid values and one scale per row."""
         ca, sa = e4m3.quantize_rows(x)
-        da = e4m3.decode(ca)
-        if memo is not None:
-            memo[id(x)] = (x, da, sa)          # holding x keeps id(x) unique
-        return da, sa
+        return e4m3.decode(ca), sa
 
-    def _linear(self, x, nm, idx, quantised, bias=None, memo=None):
-        """x @ W[nm][idx] (+ bias): fp8 GEMM when `quantised`, else fp32 masters in fp64."""
+    def _linear(self, x, nm, idx, quantised, bias=None, qa=None):
+        """x @ W[nm][idx] (+ bias): fp8 GEMM when `quantised`, else fp32 masters in fp64.
+        qa: the result of _quant_act(x) when the caller already has it (several
+        projections read the same quantised rows)."""
         if quantised:
-            da, sa = self._quant_act(x, memo)
+            da, sa = self._quant_act(x) if qa is None else qa
             acc = da @ self._wdec(nm, *idx)                        # exact products, fp64 sum
             y = acc * sa.astype(np.float64)[:, None] * np.float64(self.qs[nm][idx] if idx else self.qs[nm])
         else:
@@ -188,39 +184,25 @@ class Model:
         """x_w = sum over upstream senders s of (edge s->w removed ? C[s] : outs[s]) + bias prefix.
 
         outs, C: [n_senders][T*d] (rows of senders not yet computed are never
-        read: only the first n_upstream(w) rows enter).  Returns [len(recv_ids)][T][d].
-        The selection is written as a 0/1 matrix product over the sender axis.
+        read: only the first n_upstream(w) rows enter).  Receivers with the same
+        upstream senders and the same removed edges read the same sum; it is
+        formed once.  Returns (inputs, which): inputs is a list of distinct
+        [T][d] arrays, which[i] the index of recv_ids[i]'s input in it.
         """
         g, T = self.g, outs.shape[1] // self.d
-        res = []
-        memo = {}
+        inputs, which, seen = [], [], {}
         for r in recv_ids:
             n_up = g.n_upstream(r)
-            row = None if removed is None else removed[r, :n_up]
-            key = (n_up, None if row is None or not row.any() else row.tobytes())
-            if key not in memo:
-                ones = np.ones((1, n_up))
-                if key[1] is None:
-                    x = ones @ outs[:n_up]
-                else:
-                    # literal selection: put C[s] in place of outs[s] for removed edges, sum, restore.
-                    # The sum is the same operation whatever the mask, so identical operands give
-                    # identical results and a replaced output never enters the sum.
-                    idx = np.nonzero(row)[0]
-                    saved = outs[idx].copy()
-                    outs[idx] = C[idx]
-                    x = ones @ outs[:n_up]
-                    outs[idx] = saved
-                memo[key] = x.reshape(T, self.d)
-            res.append(memo[key])
-        bias = {}
-        out = []
-        for r, x in zip(recv_ids, res):                # receivers of one layer share the bias prefix
-            kb = (id(x), self.g.receiver_info(r)[0], self.g.receiver_info(r)[1])
-            if kb not in bias:
-                bias[kb] = x + self.bias_prefix(r)
-            out.append(bias[kb])
-        return out
+            mask = np.zeros(n_up, dtype=bool) if removed is None else removed[r, :n_up]
+            kind, l, _, _ = g.receiver_info(r)
+            key = (kind, l, mask.tobytes())
+            if key not in seen:
+                src = np.where(mask[:, None], C[:n_up], outs[:n_up]) if mask.any() else outs[:n_up]
+                x = src.sum(axis=0).reshape(T, self.d) + self.bias_prefix(r)
+                seen[key] = len(inputs)
+                inputs.append(x)
+            which.append(seen[key])
+        return inputs, which
 
     # ------------------------------------------------------------------ forward
     def forward(self, tokens, pi=NONE, removed=None, C=None, base=None, start_layer=0):
@@ -249,36 +231,38 @@ class Model:
 
         for l in range(start_layer, L):
             rids = [g.headin(l, h, c) for h in range(H) for c in range(3)]
-            xs = self.receiver_inputs(rids, outs, removed, C)
-            normed, qmemo = {}, {}
+            xs, which = self.receiver_inputs(rids, outs, removed, C)
+            normed = [self.norm(x, "ln1", l) for x in xs]
+            quant = {}                                             # distinct input -> its quantised rows
             for h in range(H):
                 hq = quant_all and (l, h) not in pis
                 a = []
                 for c, nm in enumerate(("Q", "K", "V")):
-                    xin = xs[3 * h + c]
-                    if id(xin) not in normed:                      # receivers sharing one input
-                        normed[id(xin)] = (xin, self.norm(xin, "ln1", l))
-                    xn = normed[id(xin)][1]
-                    y = self._linear(xn, "W_" + nm, (l, h), hq, self.w["b_" + nm][l, h], memo=qmemo)
+                    k = which[3 * h + c]
+                    if hq and k not in quant:
+                        quant[k] = self._quant_act(normed[k])
+                    y = self._linear(normed[k], "W_" + nm, (l, h), hq, self.w["b_" + nm][l, h],
+                                     qa=quant[k] if hq else None)
                     if self.s.pos == POS_ROPE and c < 2:
                         y = self._rope(y, B, S)
                     a.append(y)
                 z = self.attention(a[0], a[1], a[2], B, S)
                 outs[g.head(l, h)] = self._linear(z, "W_O", (l, h), hq).reshape(-1)
             if self.m > 0:
-                x = self.receiver_inputs([g.mlpin(l)], outs, removed, C)[0]
-                xn = self.norm(x, "ln2", l)
-                up = self._linear(xn, "W_in", (l,), quant_all, self.w["b_in"][l])
+                xs, _ = self.receiver_inputs([g.mlpin(l)], outs, removed, C)
+                xn = self.norm(xs[0], "ln2", l)
+                qa = self._quant_act(xn) if quant_all else None
+                up = self._linear(xn, "W_in", (l,), quant_all, self.w["b_in"][l], qa=qa)
                 if self.s.act == ACT_SWIGLU:
-                    hid = silu(self._linear(xn, "W_gate", (l,), quant_all)) * up
+                    hid = silu(self._linear(xn, "W_gate", (l,), quant_all, qa=qa)) * up
                 elif self.s.act == ACT_GELU:
                     hid = gelu_tanh(up)
                 else:
                     hid = up
                 outs[g.mlp(l)] = self._linear(hid, "W_out", (l,), quant_all).reshape(-1)
 
-        x = self.receiver_inputs([g.OUT], outs, removed, C)[0]
-        last = x.reshape(B, S, d)[:, S - 1, :]
+        xs, _ = self.receiver_inputs([g.OUT], outs, removed, C)
+        last = xs[0].reshape(B, S, d)[:, S - 1, :]
         xn = self.norm(last, "lnf")
         logits = self._linear(xn, "W_U", (), quant_all, self.w["b_U"])
         return outs, logits

@@ -294,3 +294,93 @@ def test_pahq_keeps_what_rtn_loses():
     klq = Acdc(m, clean, corrupt, MODE_ALL_FP8).kl_edge(v, 0)
     assert kl32 > 0 and klp > 0
     assert klp != klq
+
+
+# ---------------------------------------------------------------- pins by an independent loop forward
+from loop_forward import loop_forward, SITES
+
+
+def _names(g):
+    """id -> tuple name of every sender and receiver (the id formulas are pinned by test_edge_counts)."""
+    snd = {}
+    for s in range(g.n_senders):
+        kind, l, h = g.sender_info(s)
+        snd[s] = ("embed",) if kind == "embed" else (("head", l, h) if kind == "head" else ("mlp", l))
+    rcv = {}
+    for r in range(g.n_receivers):
+        kind, l, h, c = g.receiver_info(r)
+        rcv[r] = ("out",) if kind == "out" else (("mlpin", l) if kind == "mlpin" else ("qkv"[c], l, h))
+    return snd, rcv
+
+
+def _rel(a, b):
+    return np.abs(a - b).max() / max(1.0, np.abs(b).max())
+
+
+@pytest.mark.parametrize("shape", [TINY_GELU, TINY_LLAMA, TINY_ATTN])
+def test_quantiser_placement_against_loop_forward(shape):
+    """Every operand the method quantises, and no other, is quantised: the oracle's forward under
+    several precision sets equals a forward written out with explicit loops; leaving out any single
+    quantiser in that forward is seen (so a quantiser missing from, or added to, the oracle would be)."""
+    m, w, clean, _ = tiny(shape, B=2)
+    snd, _ = _names(m.g)
+    sets = [frozenset(), frozenset([(1, 0)]), frozenset([(0, 1)]), frozenset([(0, 0), (1, 1)])]
+    for pi in sets:
+        outs, lg = m.forward(clean, pi)
+        l_out, l_lg = loop_forward(shape, w, clean, pi=pi)
+        assert _rel(lg, l_lg) < 1e-12, sorted(pi)
+        for s, nm in snd.items():
+            assert _rel(outs[s].reshape(l_out[nm].shape), l_out[nm]) < 1e-12, (sorted(pi), nm)
+    outs, lg = m.forward(clean, ALL)
+    _, l_lg = loop_forward(shape, w, clean, quantise=False)
+    assert _rel(lg, l_lg) < 1e-12
+    # sensitivity: one quantiser left out of the loop forward is a visible difference
+    pi = frozenset([(1, 0)])
+    _, lg = m.forward(clean, pi)
+    for site in SITES:
+        if shape.d_mlp == 0 and site in ("act:in", "w:in", "w:gate", "act:out", "w:out"):
+            continue
+        if shape.act != 2 and site == "w:gate":
+            continue
+        _, l_lg = loop_forward(shape, w, clean, pi=pi, drop=site)
+        assert _rel(lg, l_lg) > 1e-7, site
+    # ... and so is a head of the precision set that is quantised after all, or one too many in fp32
+    _, l_lg = loop_forward(shape, w, clean, pi=frozenset())
+    assert _rel(lg, l_lg) > 1e-7
+    _, l_lg = loop_forward(shape, w, clean, pi=frozenset([(1, 0), (1, 1)]))
+    assert _rel(lg, l_lg) > 1e-7
+
+
+@pytest.mark.parametrize("shape", [TINY_GELU, TINY_LLAMA, TINY_ATTN])
+def test_patch_routing_against_loop_forward(shape):
+    """A removed edge replaces one sender's output at one receiver -- one channel of one head, one MLP
+    input, or the unembedding input -- and nowhere else: random removed sets, explicit per-receiver sums."""
+    m, w, clean, corrupt = tiny(shape, B=2)
+    g = m.g
+    snd, rcv = _names(g)
+    rng = np.random.default_rng(11)
+    for pi in (frozenset(), frozenset([(1, 1)])):
+        C, _ = m.forward(corrupt, pi)
+        other = {snd[s]: C[s].reshape(clean.size, shape.d_model) for s in snd}
+        for frac in (0.15, 0.6):
+            R = g.flat_to_removed(rng.random(g.n_edges()) < frac)
+            rem = {(snd[s], rcv[r]) for r in range(g.n_receivers) for s in range(g.n_upstream(r)) if R[r, s]}
+            outs, lg = m.forward(clean, pi, removed=R, C=C)
+            l_out, l_lg = loop_forward(shape, w, clean, pi=pi, removed=rem, other=other)
+            assert _rel(lg, l_lg) < 1e-12
+            for s, nm in snd.items():
+                assert _rel(outs[s].reshape(l_out[nm].shape), l_out[nm]) < 1e-12, nm
+            # sensitivity: the same edges routed into another channel of the same head give something else
+            swap = {"q": "k", "k": "v", "v": "q"}
+            rem2 = {(s_, (swap[r_[0]],) + r_[1:] if r_[0] in swap else r_) for s_, r_ in rem}
+            if rem2 != rem:
+                _, l_lg2 = loop_forward(shape, w, clean, pi=pi, removed=rem2, other=other)
+                assert _rel(lg, l_lg2) > 1e-7
+    # one edge at a time: the patched run differs from the clean run only downstream of the receiver's node
+    C, _ = m.forward(corrupt, frozenset())
+    base, _ = m.forward(clean, frozenset())
+    v = g.headin(1, 0, 2)
+    R = g.empty_removed(); R[v, g.head(0, 1)] = True
+    outs, _ = m.forward(clean, frozenset(), removed=R, C=C)
+    changed = [s for s in range(g.n_senders) if not (outs[s] == base[s]).all()]
+    assert changed and changed[0] == g.head(1, 0) and g.head(1, 1) not in changed
