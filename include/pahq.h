@@ -61,7 +61,8 @@ enum {
   PAHQ_ENOMEM = -3,   /* workspace too small                                            */
   PAHQ_EHIP = -4,     /* a HIP runtime call failed / no device                          */
   PAHQ_ENAN = -5,     /* non-finite weight                                              */
-  PAHQ_EUNSUPPORTED = -6 /* valid request that this build does not implement           */
+  PAHQ_EUNSUPPORTED = -6, /* valid request that this build does not implement          */
+  PAHQ_ETOOBIG = -7    /* input larger than the fixed capacity of an allocation-free call  */
 };
 
 enum { PAHQ_NORM_LAYER = 0, PAHQ_NORM_RMS = 1 };
@@ -242,6 +243,25 @@ int pahq_get_profile(pahq_model*, pahq_kernel_stat out[PAHQ_N_KERNEL_CLASSES]);
  * aligned, at least 64 MiB (the caller's; its contents are overwritten).  Synchronises the stream. */
 int pahq_measure_ceilings(void* hip_stream, void* scratch, size_t scratch_bytes, double* mfma_f16_tflops,
                           double* copy_gbs);
+
+/* ---- for callers that cannot allocate -----------------------------------------
+ * pahq_quantize_rows for code that may not allocate device or pinned memory and has no model
+ * or workspace at hand: kernels recorded into a HIP graph, serving loops, harnesses that forbid
+ * hipMalloc.  Same arithmetic, bit for bit (scale = amax / 448, 1 if amax = 0; inv = 1 / scale;
+ * code = rne_e4m3(x * inv)), for rows of ANY length: a row is split over workgroups, and the per-row
+ * maxima they combine live in a static device array of PAHQ_NOALLOC_MAX_ROWS words (128 KiB) that
+ * every GPU the library runs on holds until the process ends.
+ *   hip_stream  hipStream_t (NULL = default stream); the work is enqueued there, nothing is waited for
+ *   x           DEVICE, rows x cols floats, row-major          (caller-owned, read)
+ *   codes       DEVICE, rows x cols bytes                      (caller-owned, written)
+ *   scales      DEVICE, rows floats                            (caller-owned, written)
+ * The device that owns the pointers and the stream must be the current one.  rows = 0 does nothing;
+ * rows > PAHQ_NOALLOC_MAX_ROWS gives PAHQ_ETOOBIG (split the call), rows < 0, cols < 1 or a null
+ * pointer PAHQ_EINVAL.  No allocation, no memset node, no synchronisation.  All calls on one GPU
+ * share that GPU's array: calls that overlap there (different streams or host threads) race. */
+enum { PAHQ_NOALLOC_MAX_ROWS = 32768 };
+int pahq_quantize_rows_noalloc(void* hip_stream, const float* x, int32_t rows, int32_t cols, uint8_t* codes,
+                               float* scales);
 
 const char* pahq_strerror(int code);
 void pahq_free(pahq_model*);            /* frees host state only; the workspace stays the caller's */

@@ -87,6 +87,7 @@ def lib():
             "pahq_set_profiling": [C.c_void_p, C.c_int32],
             "pahq_set_profiling_sample": [C.c_void_p, C.c_uint32, C.c_int32],
             "pahq_get_profile": [C.c_void_p, C.POINTER(KernelStat)],
+            "pahq_quantize_rows_noalloc": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
             "pahq_measure_ceilings": [C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double)],
         }
         for name, args in sig.items():
@@ -130,6 +131,21 @@ def measure_ceilings(scratch_mib=1024):
     _chk(lib().pahq_measure_ceilings(C.c_void_p(torch.cuda.current_stream().cuda_stream), C.c_void_p(buf.data_ptr()),
                                      C.c_size_t(buf.numel()), C.byref(tf), C.byref(gb)), "pahq_measure_ceilings")
     return tf.value, gb.value
+
+
+def quantize_rows_noalloc(x, codes, scales, stream=None):
+    """pahq_quantize_rows_noalloc on device tensors the caller owns: x float32 [rows][cols], codes uint8
+    [rows][cols], scales float32 [rows], all contiguous on the current device.  Enqueues; does not wait."""
+    import torch
+    rows, cols = x.shape
+    if not (x.is_cuda and codes.is_cuda and scales.is_cuda and x.is_contiguous() and codes.is_contiguous()
+            and scales.is_contiguous() and x.dtype == torch.float32 and codes.dtype == torch.uint8
+            and scales.dtype == torch.float32 and codes.shape == x.shape and scales.numel() == rows):
+        raise ValueError("x float32 [rows][cols], codes uint8 [rows][cols], scales float32 [rows], contiguous, on the device")
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    _chk(lib().pahq_quantize_rows_noalloc(C.c_void_p(st), C.c_void_p(x.data_ptr()), rows, cols,
+                                          C.c_void_p(codes.data_ptr()), C.c_void_p(scales.data_ptr())),
+         "pahq_quantize_rows_noalloc")
 
 
 class Model:

@@ -6,7 +6,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpahq.so")
-SOURCES = ["rows.hip", "gemm.hip", "oproj.hip", "attn_kl.hip", "engine.hip", "api.hip", "ceilings.hip"]
+SOURCES = ["rows.hip", "gemm.hip", "oproj.hip", "attn_kl.hip", "engine.hip", "api.hip", "ceilings.hip", "noalloc.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -666,6 +666,7 @@ const char* pahq_strerror(int code) {
     case PAHQ_EHIP: return "HIP runtime error or no device";
     case PAHQ_ENAN: return "non-finite weight";
     case PAHQ_EUNSUPPORTED: return "not supported by this build";
+    case PAHQ_ETOOBIG: return "input exceeds the fixed capacity of the allocation-free call";
     default: return "unknown error";
   }
 }
