@@ -35,7 +35,7 @@
  *   receivers ascending, then senders ascending.
  *
  * Conventions.  Every function returns 0 or a negative PAHQ_E* code; nothing is
- * printed, nothing throws, and a failed call leaves the model state unchanged.
+ * printed, nothing throws, and a failed call leaves the removed set unchanged.
  * Pointers are HOST pointers unless the comment says "device".  All device work
  * is enqueued on the stream given to pahq_init_model; calls that return host
  * values synchronise that stream.  The library performs no device allocation:
@@ -69,7 +69,7 @@ enum { PAHQ_NORM_LAYER = 0, PAHQ_NORM_RMS = 1 };
 enum { PAHQ_ACT_NONE = 0, PAHQ_ACT_GELU = 1, PAHQ_ACT_SWIGLU = 2 };
 enum { PAHQ_POS_LEARNED = 0, PAHQ_POS_ROPE = 1 };
 enum { PAHQ_ALL_FP32 = 0, PAHQ_ALL_FP8 = 1, PAHQ_PAHQ = 2 };
-enum { PAHQ_LOGITS_CLEAN = 0, PAHQ_LOGITS_CORRUPT = 1 };
+enum { PAHQ_LOGITS_CLEAN = 0, PAHQ_LOGITS_CORRUPT = 1, PAHQ_LOGITS_REF = 2 };
 enum { PAHQ_MMA_FP8 = 0, PAHQ_MMA_F16_EXACT = 1 };
 enum { PAHQ_W_Q = 0, PAHQ_W_K = 1, PAHQ_W_V = 2, PAHQ_W_O = 3, PAHQ_W_IN = 4, PAHQ_W_GATE = 5,
        PAHQ_W_OUT = 6, PAHQ_W_U = 7 };
@@ -88,7 +88,8 @@ typedef struct {
   int32_t split_qkv;        /* must be 1: query, key and value inputs are separate receivers      */
   int32_t precision;        /* PAHQ_PAHQ: fp32 investigated head (the head a candidate edge feeds);
                                PAHQ_ALL_FP8: no fp32 head (all-8-bit RTN baseline);
-                               PAHQ_ALL_FP32: not implemented -> PAHQ_EUNSUPPORTED               */
+                               PAHQ_ALL_FP32: no quantiser anywhere, every matrix product on the fp32
+                               masters (the unaccelerated ACDC of the paper's runtime table)        */
   int32_t max_batch_edges;  /* most candidates evaluated in one device batch (>= 1)               */
   int32_t mma;              /* how the E4M3 x E4M3 products are summed:
                                PAHQ_MMA_F16_EXACT (recommended): the codes are converted to fp16 in
@@ -188,6 +189,21 @@ int pahq_eval_current(pahq_model*, int32_t receiver, float* kl_out);
 int pahq_acdc_sweep(pahq_model*, float tau, const int32_t* receivers, int32_t n_receivers,
                     uint8_t* kept, int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap);
 
+/* Inference on a pruned graph with a SET of fp32 heads (Appendix "Integration with ACDC", last block of the
+ * algorithm: forward on G_sparse with the heads H_high of every layer in high precision): the clean run in
+ * which every edge that is not kept carries the corrupted run's activation, the flagged heads' query / key /
+ * value and output projections on the fp32 masters and unquantised activations, everything else on E4M3
+ * operands.  kl_out: batch-mean KL at the last position to the clean run with no edge removed under the
+ * same set of fp32 heads (the corrupted activations come from a corrupted run under that set as well).
+ *   kept        host, pahq_edge_count bytes, canonical order, 1 = kept; NULL = the model's current removed set
+ *   f32_heads   host, [n_layers][n_heads] bytes, 1 = head in fp32; NULL = every head that still has a kept
+ *               edge in and a kept edge out.  Ignored unless the model's precision is PAHQ_PAHQ (ALL_FP8: no
+ *               fp32 head; ALL_FP32: everything is fp32 anyway)
+ *   logits_out  host, [B][vocab] logits of the pruned run, or NULL
+ * Any removed set is accepted (the pass starts at the embedding).  The model's removed set is not changed;
+ * the state of the head investigated last is dropped (the next evaluation rebuilds it). */
+int pahq_eval_circuit(pahq_model*, const uint8_t* kept, const uint8_t* f32_heads, float* kl_out, float* logits_out);
+
 /* Removed set, canonical edge order, one byte per edge (1 = removed, 0 = kept).  Any set is stored; which
  * sets an evaluation accepts is said at pahq_eval_edges. */
 int pahq_set_removed(pahq_model*, const uint8_t* removed);
@@ -200,7 +216,9 @@ int pahq_get_weight_q(pahq_model*, int32_t which, int32_t layer, int32_t head, u
 /* The activation quantiser as a function: host x [rows][cols] -> codes, one scale per row.
  * cols <= 16384. */
 int pahq_quantize_rows(pahq_model*, const float* x, int32_t rows, int32_t cols, uint8_t* codes, float* scales);
-/* Last-position logits [B][vocab] of the cached clean / corrupted run. */
+/* Last-position logits [B][vocab]: PAHQ_LOGITS_CLEAN / PAHQ_LOGITS_CORRUPT of the cached runs;
+ * PAHQ_LOGITS_REF of the clean run under the precision set of the head investigated last (the reference
+ * distribution its candidates were scored against; PAHQ_ESTATE when no head's state is current). */
 int pahq_get_logits(pahq_model*, int32_t which, float* out);
 /* Cached output [B*S][d_model] of one sender in the clean (which=0) or corrupted (1) run. */
 int pahq_get_sender_output(pahq_model*, int32_t which, int32_t sender, float* out);

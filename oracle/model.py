@@ -197,8 +197,10 @@ class Model:
             kind, l, _, _ = g.receiver_info(r)
             key = (kind, l, mask.tobytes())
             if key not in seen:
-                src = np.where(mask[:, None], C[:n_up], outs[:n_up]) if mask.any() else outs[:n_up]
-                x = src.sum(axis=0).reshape(T, self.d) + self.bias_prefix(r)
+                x = np.zeros(T * self.d)
+                for s in range(n_up):                              # senders in ascending id
+                    x += C[s] if mask[s] else outs[s]
+                x = x.reshape(T, self.d) + self.bias_prefix(r)
                 seen[key] = len(inputs)
                 inputs.append(x)
             which.append(seen[key])

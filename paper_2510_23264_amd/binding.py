@@ -78,6 +78,7 @@ def lib():
             "pahq_eval_edges": [C.c_void_p, C.c_int32, i32p, C.c_int32, f32p],
             "pahq_eval_current": [C.c_void_p, C.c_int32, f32p],
             "pahq_acdc_sweep": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
+            "pahq_eval_circuit": [C.c_void_p, u8p, u8p, f32p, f32p],
             "pahq_set_removed": [C.c_void_p, u8p], "pahq_get_removed": [C.c_void_p, u8p],
             "pahq_get_weight_q": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, u8p, f32p],
             "pahq_quantize_rows": [C.c_void_p, f32p, C.c_int32, C.c_int32, u8p, f32p],
@@ -232,6 +233,26 @@ class Model:
         n = min(n_evals.value, cap)
         tr = np.ctypeslib.as_array(trace)[:n].copy() if n else np.zeros(0, dtype=np.dtype(TraceRec))
         return kept, n_evals.value, tr
+
+    def eval_circuit(self, kept=None, f32_heads=None, want_logits=False):
+        """KL of the pruned graph under a set of fp32 heads (and its logits when asked for)."""
+        kp = hp = lp = None
+        if kept is not None:
+            k = np.ascontiguousarray(kept, dtype=np.uint8)
+            if k.size != self.n_edges:
+                raise ValueError("kept must have one byte per edge")
+            kp = _ptr(k, C.c_uint8)
+        if f32_heads is not None:
+            h = np.ascontiguousarray(f32_heads, dtype=np.uint8)
+            if h.shape != (self.cfg.n_layers, self.cfg.n_heads):
+                raise ValueError("f32_heads must be [n_layers][n_heads]")
+            hp = _ptr(h, C.c_uint8)
+        logits = np.empty((self.B, self.cfg.vocab), dtype=np.float32) if want_logits else None
+        if want_logits:
+            lp = _ptr(logits, C.c_float)
+        out = C.c_float()
+        _chk(lib().pahq_eval_circuit(self.h, kp, hp, C.byref(out), lp), "pahq_eval_circuit")
+        return (out.value, logits) if want_logits else out.value
 
     def set_removed(self, removed):
         r = np.ascontiguousarray(removed, dtype=np.uint8)

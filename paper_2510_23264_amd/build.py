@@ -7,7 +7,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpahq.so")
 SOURCES = ["rows.hip", "gemm.hip", "oproj.hip", "attn_kl.hip", "engine.hip", "api.hip", "ceilings.hip", "noalloc.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+# -ffp-contract=off: a product and a sum are rounded separately unless the source says fmaf.  The same
+# expression (a norm's x * rstd * gain + offset, a GEMM epilogue's acc * scale + bias) is compiled into
+# several kernels -- cache passes and candidate passes take different ones -- and results that must agree
+# bit for bit between them (a clean patch scores exactly 0) may not depend on where the compiler chose to fuse.
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

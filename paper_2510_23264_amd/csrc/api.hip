@@ -27,8 +27,9 @@ int check_config(const pahq_config* c) {
 // what this build of the kernels supports
 int check_supported(const pahq_config* c, int B, int S) {
   if (c->split_qkv != 1) return PAHQ_EUNSUPPORTED;
-  if (c->precision == PAHQ_ALL_FP32) return PAHQ_EUNSUPPORTED;
+  if (c->n_heads > 64) return PAHQ_EUNSUPPORTED;                      // sets of heads are 64-bit masks
   if (c->d_model % 64 != 0 || c->d_model > 4096) return PAHQ_EUNSUPPORTED;
+  if (c->d_mlp % 4 != 0) return PAHQ_EUNSUPPORTED;                    // 16-byte rows of the hidden activations
   if (c->d_head != 16 && c->d_head != 32 && c->d_head != 64 && c->d_head != 128) return PAHQ_EUNSUPPORTED;
   if (c->pos == PAHQ_POS_ROPE && (c->d_head & 1)) return PAHQ_EUNSUPPORTED;
   if (c->d_mlp > 0 && c->act == PAHQ_ACT_NONE) return PAHQ_EUNSUPPORTED;
@@ -57,6 +58,9 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
   M->Kd = pad128(M->d); M->Kh = pad128(M->dh); M->Km = pad128(M->m > 0 ? M->m : 1);
   M->Vp = (M->V + 31) / 32 * 32;      // logits rows start on 128-byte boundaries
   M->nmax = c->max_batch_edges; M->G = 3 * M->H + 1;
+  M->all_f32 = c->precision == PAHQ_ALL_FP32;
+  M->f32_groups = M->all_f32 ? 3 * M->H : 3;
+  M->f32_heads_max = M->all_f32 ? M->H : 1;
   M->ncap = std::max(M->nmax, 1024);
   M->tile = (long long)M->T * M->d;
 }
@@ -109,9 +113,9 @@ size_t layout(pahq_model* M, char* base) {
   M->qkv_sh = b.take<float>(T * 3 * H * dh); M->oth = b.take<float>(tile); M->sh_slots = b.take<float>(H * tile);
   M->qv = b.take<float>(n * T * dh);
   M->run_a = b.take<float>(n * tile); M->run_b = b.take<float>(n * tile);
-  M->xcodes = b.take<uint8_t>(n * G * T * Kd); M->xscale = b.take<float>(n * G * T); M->xf32 = b.take<float>(n * 3 * tile);
+  M->xcodes = b.take<uint8_t>(n * G * T * Kd); M->xscale = b.take<float>(n * G * T); M->xf32 = b.take<float>(std::max<size_t>(n * (size_t)M->f32_groups, 3 * H) * tile);
   M->qkv = b.take<float>(n * T * 3 * H * dh);
-  M->zcodes = b.take<uint8_t>(n * T * H * Kh); M->zscale = b.take<float>(n * T * H); M->zf32 = b.take<float>(n * T * dh);
+  M->zcodes = b.take<uint8_t>(n * T * H * Kh); M->zscale = b.take<float>(n * T * H); M->zf32 = b.take<float>(std::max<size_t>(n * (size_t)M->f32_heads_max, H) * T * dh);
   M->headout = b.take<float>(n * H * tile);
   M->mlpout = mlp ? b.take<float>(n * tile) : nullptr;
   M->hid = mlp ? b.take<float>(n * T * m) : nullptr; M->hid2 = (mlp && swi) ? b.take<float>(n * T * m) : nullptr;
@@ -477,8 +481,20 @@ int pahq_eval_current(pahq_model* M, int32_t receiver, float* kl_out) {
   return PAHQ_OK;
 }
 
+static int sweep_impl(pahq_model* M, float tau, const int32_t* receivers, int32_t n_receivers, uint8_t* kept,
+                      int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap);
+
 int pahq_acdc_sweep(pahq_model* M, float tau, const int32_t* receivers, int32_t n_receivers, uint8_t* kept,
                     int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap) {
+  if (!M) return PAHQ_EINVAL;
+  const std::vector<uint8_t> before = M->removed;       // a failed sweep leaves the removed set as it found it
+  int rc = sweep_impl(M, tau, receivers, n_receivers, kept, n_evals, trace, trace_cap);
+  if (rc != PAHQ_OK) M->removed = before;
+  return rc;
+}
+
+static int sweep_impl(pahq_model* M, float tau, const int32_t* receivers, int32_t n_receivers, uint8_t* kept,
+                      int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap) {
   if (!M || n_receivers < 0 || (n_receivers > 0 && !receivers) || trace_cap < 0 || (trace_cap > 0 && !trace)) return PAHQ_EINVAL;
   if (tau != tau) return PAHQ_EINVAL;
   if (!M->has_cache) return PAHQ_ESTATE;
@@ -540,6 +556,66 @@ int pahq_acdc_sweep(pahq_model* M, float tau, const int32_t* receivers, int32_t 
   if (kept) for (size_t i = 0; i < M->removed.size(); i++) kept[i] = M->removed[i] ? 0 : 1;
   if (n_evals) *n_evals = evals;
   HIPCHK(hipStreamSynchronize(M->stream));
+  return PAHQ_OK;
+}
+
+int pahq_eval_circuit(pahq_model* M, const uint8_t* kept, const uint8_t* f32_heads, float* kl_out, float* logits_out) {
+  if (!M || !kl_out) return PAHQ_EINVAL;
+  if (!M->has_cache) return PAHQ_ESTATE;
+  const GraphDims& g = M->g;
+  const int L = M->L, H = M->H;
+  if (kept) for (size_t i = 0; i < M->removed.size(); i++) if (kept[i] > 1) return PAHQ_EINVAL;
+  if (f32_heads) for (int i = 0; i < L * H; i++) if (f32_heads[i] > 1) return PAHQ_EINVAL;
+  std::vector<uint8_t> saved;
+  if (kept) {
+    saved = M->removed;
+    for (size_t i = 0; i < M->removed.size(); i++) M->removed[i] = kept[i] ? 0 : 1;
+  }
+  // fp32 heads: the caller's, or every head that is still part of the graph (a kept edge in and a kept edge out)
+  std::vector<unsigned long long> masks(L, 0ull);
+  bool any = false;
+  if (M->cfg.precision == PAHQ_PAHQ) {
+    for (int l = 0; l < L; l++)
+      for (int h = 0; h < H; h++) {
+        bool on;
+        if (f32_heads) on = f32_heads[l * H + h] != 0;
+        else {
+          bool in_kept = false;
+          for (int c = 0; c < 3 && !in_kept; c++) {
+            const int r = g.headin(l, h, c);
+            const uint8_t* row = M->removed.data() + M->edge_off[r];
+            for (int s = 0, n_up = g.n_upstream(r); s < n_up; s++) if (!row[s]) { in_kept = true; break; }
+          }
+          on = in_kept && node_is_live(M, g.headin(l, h, 0));
+        }
+        if (on) { masks[l] |= 1ull << h; any = true; }
+      }
+  }
+  int rc = PAHQ_OK;
+  double kl = 0.0;
+  do {
+    PassArgs a; a.n = 1; a.p0 = 0; a.pl = a.ph = -1; a.v = -1; a.patch_mode = 0;
+    a.heads = any ? masks.data() : nullptr;
+    if (any) {
+      // corrupted run and reference distribution under this precision set (they replace the state of the
+      // last investigated head)
+      M->pi_l = M->pi_h = -2;
+      a.kind = PI_CORRUPT; if ((rc = run_pass(M, a, nullptr)) != PAHQ_OK) break;
+      a.kind = PI_REF; if ((rc = run_pass(M, a, nullptr)) != PAHQ_OK) break;
+    }
+    make_plan(M, 0, g.out(), M->plan);
+    if (M->plan.n_slots > M->pool_tiles) { rc = PAHQ_ENOMEM; break; }
+    a.kind = STATE; a.keep_logits = logits_out != nullptr;
+    if ((rc = run_pass(M, a, &M->plan)) != PAHQ_OK) break;
+    if (hipMemcpyAsync(M->kl_host, M->kl_dev, sizeof(double), hipMemcpyDeviceToHost, M->stream) != hipSuccess) { rc = PAHQ_EHIP; break; }
+    if (logits_out && hipMemcpy2DAsync(logits_out, (size_t)M->V * sizeof(float), M->logits, (size_t)M->Vp * sizeof(float),
+                                       (size_t)M->V * sizeof(float), M->B, hipMemcpyDeviceToHost, M->stream) != hipSuccess) { rc = PAHQ_EHIP; break; }
+    if (hipStreamSynchronize(M->stream) != hipSuccess) { rc = PAHQ_EHIP; break; }
+    kl = M->kl_host[0];
+  } while (0);
+  if (kept) M->removed.swap(saved);
+  if (rc != PAHQ_OK) return rc;
+  *kl_out = (float)kl;
   return PAHQ_OK;
 }
 
@@ -607,9 +683,10 @@ int pahq_quantize_rows(pahq_model* M, const float* x, int32_t rows, int32_t cols
 }
 
 int pahq_get_logits(pahq_model* M, int32_t which, float* out) {
-  if (!M || !out || (which != PAHQ_LOGITS_CLEAN && which != PAHQ_LOGITS_CORRUPT)) return PAHQ_EINVAL;
+  if (!M || !out || (which != PAHQ_LOGITS_CLEAN && which != PAHQ_LOGITS_CORRUPT && which != PAHQ_LOGITS_REF)) return PAHQ_EINVAL;
   if (!M->has_cache) return PAHQ_ESTATE;
-  const float* src = which == PAHQ_LOGITS_CLEAN ? M->logits_clean : M->logits_corrupt;
+  if (which == PAHQ_LOGITS_REF && M->pi_l < 0) return PAHQ_ESTATE;      // no fp32 head's state is current
+  const float* src = which == PAHQ_LOGITS_CLEAN ? M->logits_clean : (which == PAHQ_LOGITS_CORRUPT ? M->logits_corrupt : M->ref_logits);
   HIPCHK(hipMemcpy2DAsync(out, (size_t)M->V * sizeof(float), src, (size_t)M->Vp * sizeof(float), (size_t)M->V * sizeof(float),
                           M->B, hipMemcpyDeviceToHost, M->stream));
   HIPCHK(hipStreamSynchronize(M->stream));

@@ -26,7 +26,7 @@ typedef float v4f_a __attribute__((ext_vector_type(4)));
 template <int ST, int DH, bool ROPE, bool STG>
 __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zcodes,
                                                          long long zc_is, float* zscale, long long zs_is, float* zf32,
-                                                         long long zf_is, int f32_head, int n_pairs, int B, int S, int H,
+                                                         long long zf_is, unsigned long long f32_mask, int n_pairs, int B, int S, int H,
                                                          int ldz, int rope, const float2* rope_tab) {
   constexpr int CH = DH / 4;        // columns of q / k per lane
   constexpr int NT = DH / 16;       // output column tiles
@@ -179,7 +179,9 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
       }
     }
 
-  const bool f32 = (h == f32_head);
+  const bool f32 = (f32_mask >> h) & 1ull;
+  // place of this head among the fp32 heads, and their number
+  const int f32_slot = __popcll(f32_mask & ((1ull << h) - 1ull)), f32_n = __popcll(f32_mask);
 #pragma unroll
   for (int a = 0; a < ST; a++) {
     v4f_a z[NT];
@@ -199,7 +201,7 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
       long long tok = (long long)b * S + pos;
       if (f32) {
         if (pos < S) {
-          float* o = zf32 + inst * zf_is + tok * DH + i;
+          float* o = zf32 + inst * zf_is + (tok * f32_n + f32_slot) * DH + i;
 #pragma unroll
           for (int t = 0; t < NT; t++) o[16 * t] = z[t][rr];
         }
@@ -255,14 +257,14 @@ hipError_t launch_rope_table(float* tab, int n_pos, int dh, float theta, hipStre
 }
 
 hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is, float* zscale,
-                            long long zs_is, float* zf32, long long zf_is, int f32_head, int n_inst, int B, int S,
+                            long long zs_is, float* zf32, long long zf_is, unsigned long long f32_mask, int n_inst, int B, int S,
                             int H, int dh, int ldz, int rope, const float* rope_tab, hipStream_t s) {
   if (n_inst == 0) return hipSuccess;
   if (S > 32) return hipErrorInvalidValue;
   int n_pairs = n_inst * B * src.n_heads;
   dim3 grid((n_pairs + 3) / 4);
 #define ATT1(ST_, DH_, R_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_, R_, (ST_ == 1 && DH_ == 64 && !R_)>), grid, dim3(256), 0, s, src, zcodes, \
-                                              zc_is, zscale, zs_is, zf32, zf_is, f32_head, n_pairs, B, S, H, ldz, rope, (const float2*)rope_tab)
+                                              zc_is, zscale, zs_is, zf32, zf_is, f32_mask, n_pairs, B, S, H, ldz, rope, (const float2*)rope_tab)
 #define ATT(ST_, DH_) do { if (rope) ATT1(ST_, DH_, true); else ATT1(ST_, DH_, false); } while (0)
   if (S <= 16) {
     if (dh == 16) ATT(1, 16); else if (dh == 32) ATT(1, 32); else if (dh == 64) ATT(1, 64);

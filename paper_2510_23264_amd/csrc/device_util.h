@@ -43,13 +43,16 @@ __device__ __forceinline__ uint32_t e4m3_encode(float y) {
 }
 
 // tanh-form GELU, 0.5 x (1 + tanh(u)) with u = sqrt(2/pi) (x + 0.044715 x^3), written as
-// x / (1 + exp(-2u)): one hardware exponential and one hardware reciprocal (1 ulp), no branches.
-// exp(-2u) overflows to +inf for very negative x, which gives the correct limit -0.  Relative error
-// about 1e-6 (the fast exponential), against 1e-7 for the libm tanhf it replaces.
+// x / (1 + exp(-2u)): relative accuracy is kept for negative x, where 1 + tanh(u) cancels.  The
+// exponential and the division are the correctly rounded-to-an-ulp library forms, not the hardware
+// approximations: the result feeds the row quantiser, where a relative error e moves about e / 2^-4
+// of the elements across a rounding boundary, and the approximations' 1e-6 was the largest single
+// contribution to such moves on GELU models.  exp(-2u) overflows to +inf for very negative x, which
+// gives the correct limit -0.
 __device__ __forceinline__ float gelu_tanh(float x) {
   const float k2 = -2.0f * 0.7978845608028654f;   // -2 sqrt(2/pi)
   float u = k2 * (x + 0.044715f * x * x * x);
-  return x * __builtin_amdgcn_rcpf(1.0f + __expf(u));
+  return x / (1.0f + expf(u));
 }
 
 }  // namespace pahq

@@ -35,6 +35,8 @@ struct PassArgs {
   int v;               // patched receiver (CAND) or -1
   int patch_mode;      // 1 independent, 2 cumulative
   int io_off = 0;      // first element of send_dev / kl_dev this pass reads / writes
+  const unsigned long long* heads = nullptr;   // per layer: bit h set = head h in fp32 (a set of fp32 heads instead of (pl, ph))
+  bool keep_logits = false;                    // a scored pass also stores its logits (M->logits)
 };
 
 struct Arena {          // descriptor staging: pinned host mirror + device copy, a small ring
@@ -74,6 +76,9 @@ struct pahq_model {
   float *logits_clean, *logits_corrupt;   // [B][V]
   double* logz_clean;                     // [B]
   float *cpi, *rxpi, *ref_logits; double* ref_logz;   // state of the current fp32 head
+  bool all_f32;                           // PAHQ_ALL_FP32: every matrix product on the fp32 masters, no quantiser
+  int f32_groups;                         // receiver-input groups of a layer that may need fp32 rows (per instance)
+  int f32_heads_max;                      // heads whose attention output may be needed unquantised (per instance)
   float* xv;                              // current input of the receiver under evaluation
   float *qkv_sh, *oth, *sh_slots, *qv;    // first-layer state shared by all candidates of a receiver
   float *run_a, *run_b;                   // [nmax] tiles each

@@ -14,7 +14,6 @@
 // position comes from the cache (clean - corrupt); for recomputed senders it is
 // written by the kernel that adds the sender's output to the stream.
 #include "engine.h"
-#include <stdio.h>
 #include <map>
 #include <string.h>
 
@@ -65,8 +64,8 @@ void make_plan(pahq_model* M, int p0, int v, RecvPlan& out) {
 
 namespace {
 
-enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH, OP_OPROJ, OP_KLRED, OP_PREF };
-struct Op { OpType t; int i0, i1, i2, i3; void* p0; void* p1; double flops, bytes; };
+enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH, OP_OPROJ, OP_KLRED, OP_PREF, OP_SWIGLU32 };
+struct Op { OpType t; int i0, i1, i2, i3; void* p0; void* p1; double flops, bytes; unsigned long long u64; };
 
 struct Stream { float* p; long long is; };
 
@@ -83,15 +82,26 @@ struct Builder {
   std::vector<HeadAux> haux;
   std::vector<AttnSrc> asrcs;
   std::vector<Op> ops;
-  bool general, has_pi;
+  bool general, has_pi, f32_rest;
   int nstat;
 
   Builder(pahq_model* M_, const PassArgs& a_, const RecvPlan* p_) : M(M_), a(a_), plan(p_) {
     general = (a.kind == STATE || a.kind == CAND || a.kind == PREFIX);
-    has_pi = a.pl >= 0;
+    f32_rest = M->all_f32;
+    has_pi = false;
+    if (!M->all_f32) {
+      if (a.heads) { for (int l = 0; l < M->L; l++) if (a.heads[l]) has_pi = true; }
+      else has_pi = a.pl >= 0;
+    }
     nstat = M->g.n_static(a.p0);
   }
 
+  // heads of layer l whose projections run on the fp32 masters
+  unsigned long long mask_of(int l) const {
+    if (M->all_f32) return M->H >= 64 ? ~0ull : ((1ull << M->H) - 1ull);
+    if (a.heads) return a.heads[l];
+    return (a.pl == l && a.ph >= 0) ? (1ull << a.ph) : 0ull;
+  }
   float* corrupt_prefix_pi(int p) {
     if (has_pi && p > a.p0) return M->rxpi + (long long)canon(M, p) * M->tile;
     return corrupt_prefix(M, p);
@@ -140,7 +150,7 @@ struct Builder {
   }
 
   void add_op(OpType t, int i0 = 0, int i1 = 0, int i2 = 0, int i3 = 0, void* p0 = nullptr, void* p1 = nullptr) {
-    Op o; o.t = t; o.i0 = i0; o.i1 = i1; o.i2 = i2; o.i3 = i3; o.p0 = p0; o.p1 = p1; o.flops = 0; o.bytes = 0;
+    Op o; o.t = t; o.i0 = i0; o.i1 = i1; o.i2 = i2; o.i3 = i3; o.p0 = p0; o.p1 = p1; o.flops = 0; o.bytes = 0; o.u64 = 0;
     ops.push_back(o);
   }
   // algorithmic work of the op just added (all instances)
@@ -222,9 +232,10 @@ struct Builder {
     gd.offset = (M->cfg.norm == PAHQ_NORM_RMS || !offset) ? M->zeros_d : offset;
   }
 
-  void add_attention(const AttnSrc& src, int f32_head) {
+  void add_attention(const AttnSrc& src, unsigned long long f32_mask) {
     asrcs.push_back(src);
-    add_op(OP_ATTN, (int)asrcs.size() - 1, f32_head);
+    add_op(OP_ATTN, (int)asrcs.size() - 1);
+    ops.back().u64 = f32_mask;
   }
 
   // First layer of a candidate pass into a head input (fp32 investigated head): the PREFIX pass
@@ -256,7 +267,7 @@ struct Builder {
     src.k = cv == 1 ? M->qv : shared0 + H * dh;      src.k_is = cv == 1 ? (long long)T * dh : 0; src.k_ld = cv == 1 ? dh : ld_sh;
     src.v = cv == 2 ? M->qv : shared0 + 2 * H * dh;  src.v_is = cv == 2 ? (long long)T * dh : 0; src.v_ld = cv == 2 ? dh : ld_sh;
     src.n_heads = 1; src.h0 = hv; src.head_cols = 0;
-    add_attention(src, hv);
+    add_attention(src, 1ull << hv);
     Stream nxt = next_run(2 * l + 1, run.p == M->run_a ? M->run_b : M->run_a);
     int s = g.head(l, hv);
     pf = (int)probs.size();
@@ -272,7 +283,9 @@ struct Builder {
   void attention_block(int l, Stream& run) {
     const GraphDims& g = M->g;
     const int H = M->H, dh = M->dh, d = M->d, T = M->T, Kd = M->Kd, Kh = M->Kh;
-    const bool pi_layer = has_pi && l == a.pl;
+    const unsigned long long fmask = mask_of(l);               // heads of this layer computed in fp32
+    const unsigned long long all_heads = H >= 64 ? ~0ull : ((1ull << H) - 1ull);
+    const int nf = __builtin_popcountll(fmask);
     const bool prefix = a.kind == PREFIX;
     float* const qkv_buf = prefix ? M->qkv_sh : M->qkv;
     // ---- groups
@@ -282,7 +295,7 @@ struct Builder {
     for (int h = 0; h < H; h++)
       for (int c = 0; c < 3; c++) {
         int w = g.headin(l, h, c);
-        const bool is_pi = pi_layer && h == a.ph;
+        const bool is_pi = (fmask >> h) & 1ull;
         int gi;
         if (a.kind == CAND && w == a.v) {
           GroupDesc gd; memset(&gd, 0, sizeof(gd));
@@ -303,7 +316,8 @@ struct Builder {
         GroupDesc& gd = groups[gi];
         int local = gi - g_begin;
         if (is_pi) {
-          if (!gd.out_f32) { gd.out_f32 = M->xf32 + (long long)n_f32 * M->nmax * M->tile; gd.out_f32_is = M->tile; n_f32++; }
+          // fp32 rows of a group: a.n instances back to back, one block per group that needs them
+          if (!gd.out_f32) { gd.out_f32 = M->xf32 + (long long)n_f32 * a.n * M->tile; gd.out_f32_is = M->tile; n_f32++; }
         } else if (!gd.out_codes) {
           gd.out_codes = M->xcodes + (long long)local * M->nmax * T * Kd; gd.out_codes_is = (long long)T * Kd;
           gd.out_scale = M->xscale + (long long)local * M->nmax * T; gd.out_scale_is = T;
@@ -311,14 +325,14 @@ struct Builder {
       }
     int n_groups = (int)groups.size() - g_begin;
     add_build(g_begin, n_groups, patch_group);
-    // ---- fp8 projections: runs of consecutive column blocks that read the same quantised group
+    // ---- fp8 projections: runs of consecutive column blocks of quantised heads that read the same group
     int pb = (int)probs.size(), maxN = 0;
     const long long qkv_ld = 3LL * H * dh;
     for (int nb = 0; nb < 3 * H;) {
       int gi = grp_of[nb];
-      if (!groups[gi].out_codes) { nb++; continue; }
+      if ((fmask >> (nb % H)) & 1ull) { nb++; continue; }
       int e = nb + 1;
-      while (e < 3 * H && grp_of[e] == gi) e++;
+      while (e < 3 * H && grp_of[e] == gi && !((fmask >> (e % H)) & 1ull)) e++;
       const GroupDesc& gd = groups[gi];
       probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
                             M->qkv_codes + ((long long)l * 3 * H * dh + (long long)nb * dh) * Kd, Kd,
@@ -328,19 +342,22 @@ struct Builder {
       nb = e;
     }
     if ((int)probs.size() > pb) { add_op(OP_GEMM8, pb, (int)probs.size() - pb, T * a.n, maxN); work_gemm(pb); }
-    // ---- fp32 projections of the investigated head
-    if (pi_layer) {
+    // ---- fp32 projections of the heads in the precision set
+    if (nf) {
       int pf = (int)probs.size();
       const float* Wc[3] = {M->W_Q, M->W_K, M->W_V};
       const float* bc[3] = {M->b_Q, M->b_K, M->b_V};
-      for (int c = 0; c < 3; c++) {
-        const GroupDesc& gd = groups[grp_of[c * H + a.ph]];
-        long long hoff = (long long)l * H + a.ph;
-        probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1,
-                              bc[c] + hoff * dh, qkv_buf + ((long long)c * H + a.ph) * dh, (long long)T * qkv_ld,
-                              (int)qkv_ld, 0, T, dh, d, d));
+      for (int h = 0; h < H; h++) {
+        if (!((fmask >> h) & 1ull)) continue;
+        for (int c = 0; c < 3; c++) {
+          const GroupDesc& gd = groups[grp_of[c * H + h]];
+          long long hoff = (long long)l * H + h;
+          probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1,
+                                bc[c] + hoff * dh, qkv_buf + ((long long)c * H + h) * dh, (long long)T * qkv_ld,
+                                (int)qkv_ld, 0, T, dh, d, d));
+        }
       }
-      add_op(OP_GEMM32, pf, 3, T * a.n, dh); work_gemm(pf);
+      add_op(OP_GEMM32, pf, 3 * nf, T * a.n, dh); work_gemm(pf);
     }
     {
       AttnSrc src; memset(&src, 0, sizeof(src));
@@ -348,7 +365,7 @@ struct Builder {
       src.q_is = src.k_is = src.v_is = (long long)T * qkv_ld;
       src.q_ld = src.k_ld = src.v_ld = (int)qkv_ld;
       src.n_heads = H; src.h0 = 0; src.head_cols = dh;
-      add_attention(src, pi_layer ? a.ph : -1);
+      add_attention(src, fmask);
     }
     // ---- output projections of all heads fused with the stream update.  Only heads whose
     // individual output is needed (cache passes; a downstream receiver that treats the head's
@@ -361,7 +378,7 @@ struct Builder {
     od.W = M->o_codes + (long long)l * H * d * Kh; od.ws = M->o_scale + (long long)l * H;
     od.run_in = run.p; od.run_in_is = run.is; od.run_out = nxt.p; od.run_out_is = nxt.is;
     od.bias = M->b_O + (long long)l * d;
-    od.H = H; od.Kh = Kh; od.skip_head = pi_layer ? a.ph : -1; od.rpi = T; od.M = T * a.n; od.N = d;
+    od.H = H; od.Kh = Kh; od.skip_mask = fmask; od.rpi = T; od.M = T * a.n; od.N = d;
     od.aux_begin = -1; od.dh = M->dh;
     bool any_aux = false;
     std::vector<HeadAux> hx(H);
@@ -373,23 +390,43 @@ struct Builder {
         hx[h].dst = slot_ptr(s); hx[h].dst_is = slot_is(s);
         hx[h].sub = corrupt_ref_tile(s);
       }
-      if (hx[h].dst) any_aux = true;
+      if (hx[h].dst && !((fmask >> h) & 1ull)) any_aux = true;
     }
-    if (pi_layer && !prefix) {
-      // the investigated head's projection in fp32; its output goes to scratch (added by the fused
-      // kernel) and, where needed, to its cache tile / slot through the second output
-      int pf = (int)probs.size();
-      GemmProb pp = prob8(M->zf32, (long long)T * dh, dh, nullptr, 0, 0, M->W_O + ((long long)l * H + a.ph) * dh * d, d,
-                          nullptr, 1, nullptr, M->headout, M->tile, d, 0, T, d, dh, dh);
-      pp.aux = hx[a.ph].dst; pp.aux_is = hx[a.ph].dst_is; pp.aux_sub = hx[a.ph].sub;
-      probs.push_back(pp);
-      add_op(OP_GEMM32, pf, 1, T * a.n, d); work_gemm(pf);
+    if (nf && !prefix) {
+      // the fp32 heads' projections, one fp32 GEMM each, summed in ascending head order into one tile (the
+      // fused kernel, or the plain stream update when every head is fp32, adds it); a head's own output goes,
+      // where needed, to its cache tile / slot through the second output
+      int k = 0;
+      for (int h = 0; h < H; h++) {
+        if (!((fmask >> h) & 1ull)) continue;
+        int pf = (int)probs.size();
+        GemmProb pp = prob8(M->zf32 + (long long)k * dh, (long long)T * nf * dh, nf * dh, nullptr, 0, 0,
+                            M->W_O + ((long long)l * H + h) * dh * d, d, nullptr, 1, nullptr, M->headout, M->tile, d, 0, T, d, dh, dh);
+        if (k > 0) { pp.add = M->headout; pp.add_is = M->tile; }
+        pp.aux = hx[h].dst; pp.aux_is = hx[h].dst_is; pp.aux_sub = hx[h].sub;
+        probs.push_back(pp);
+        add_op(OP_GEMM32, pf, 1, T * a.n, d); work_gemm(pf);
+        k++;
+      }
       od.extra = M->headout; od.extra_is = M->tile;
     }
-    if (any_aux) { od.aux_begin = (int)haux.size(); haux.insert(haux.end(), hx.begin(), hx.end()); }
-    odescs.push_back(od);
-    add_op(OP_OPROJ, (int)odescs.size() - 1, T * a.n, d);
-    ops.back().flops = 2.0 * T * a.n * d * dh * (H - (pi_layer ? 1 : 0));
+    if (fmask == all_heads && !prefix) {
+      // nothing is quantised in this layer: next = run + b_O + (sum of the fp32 heads)
+      CombineDesc cd; memset(&cd, 0, sizeof(cd));
+      cd.run_in = run.p; cd.run_in_is = run.is; cd.run_out = nxt.p; cd.run_out_is = nxt.is;
+      cd.bias = M->b_O + (long long)l * d; cd.src_begin = (int)csrcs.size(); cd.n_src = 1;
+      CombineSrc cs; memset(&cs, 0, sizeof(cs));
+      cs.src = M->headout; cs.src_is = M->tile;
+      csrcs.push_back(cs);
+      cdescs.push_back(cd);
+      add_op(OP_COMBINE, (int)cdescs.size() - 1);
+      ops.back().bytes = 3.0 * a.n * (double)M->tile * 4.0;
+    } else {
+      if (any_aux) { od.aux_begin = (int)haux.size(); haux.insert(haux.end(), hx.begin(), hx.end()); }
+      odescs.push_back(od);
+      add_op(OP_OPROJ, (int)odescs.size() - 1, T * a.n, d);
+      ops.back().flops = 2.0 * T * a.n * d * dh * (H - nf);
+    }
     run = nxt;
   }
 
@@ -402,11 +439,43 @@ struct Builder {
     if (a.kind == CAND && w == a.v) patch_group = gi;
     else fill_input(gd, general ? &plan->spec[w] : nullptr, 2 * l + 1, run);
     norm_params(gd, M->ln2_g + (long long)l * d, M->ln2_b + (long long)l * d);
-    gd.out_codes = M->xcodes; gd.out_codes_is = (long long)T * Kd;
-    gd.out_scale = M->xscale; gd.out_scale_is = T;
+    if (f32_rest) { gd.out_f32 = M->xf32; gd.out_f32_is = M->tile; }
+    else {
+      gd.out_codes = M->xcodes; gd.out_codes_is = (long long)T * Kd;
+      gd.out_scale = M->xscale; gd.out_scale_is = T;
+    }
     groups.push_back(gd);
     add_build(gi, 1, patch_group);
     const bool swiglu = M->cfg.act == PAHQ_ACT_SWIGLU;
+    Stream nxt = next_run(2 * l + 2, run.p == M->run_a ? M->run_b : M->run_a);
+    const bool store_raw = a.kind == BASE_CLEAN || a.kind == BASE_CORRUPT || a.kind == PI_CORRUPT;
+    auto second_output = [&](GemmProb& po) {
+      // the sender's own output (cache passes) or its difference to the corrupted run (a slot some receiver
+      // reads) leaves through the second output
+      if (store_raw) { Stream dest = sender_dest(s, nullptr, 0); po.aux = dest.p; po.aux_is = dest.is; }
+      else if (general && plan->slot_of[s] >= 0) { po.aux = slot_ptr(s); po.aux_is = slot_is(s); po.aux_sub = corrupt_ref_tile(s); }
+    };
+    if (f32_rest) {
+      // all-fp32 mode: both matrix products on the fp32 masters; GELU in the first one's epilogue, SwiGLU by an
+      // elementwise kernel over the two results
+      int pb = (int)probs.size();
+      probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, M->W_in + (long long)l * d * m, m, nullptr, 1,
+                            M->b_in + (long long)l * m, M->hid, (long long)T * m, m, M->cfg.act == PAHQ_ACT_GELU ? 1 : 0, T, m, d, d));
+      if (swiglu)
+        probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, M->W_gate + (long long)l * d * m, m, nullptr, 1,
+                              nullptr, M->hid2, (long long)T * m, m, 0, T, m, d, d));
+      add_op(OP_GEMM32, pb, swiglu ? 2 : 1, T * a.n, m); work_gemm(pb);
+      if (swiglu) { add_op(OP_SWIGLU32); ops.back().bytes = 3.0 * a.n * T * (double)m * 4.0; }
+      pb = (int)probs.size();
+      GemmProb po = prob8(M->hid, (long long)T * m, m, nullptr, 0, 0, M->W_out + (long long)l * m * d, d, nullptr, 1,
+                          M->b_out + (long long)l * d, nxt.p, nxt.is, d, 0, T, d, m, m);
+      po.add = run.p; po.add_is = run.is;
+      second_output(po);
+      probs.push_back(po);
+      add_op(OP_GEMM32, pb, 1, T * a.n, d); work_gemm(pb);
+      run = nxt;
+      return;
+    }
     int pb = (int)probs.size();
     probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
                           M->in_codes + (long long)l * m * Kd, Kd, M->in_scale + l, m, M->b_in + (long long)l * m, M->hid,
@@ -418,21 +487,12 @@ struct Builder {
     add_op(OP_GEMM8, pb, swiglu ? 2 : 1, T * a.n, m); work_gemm(pb);
     add_op(OP_HIDQ, swiglu ? 2 : (M->cfg.act == PAHQ_ACT_GELU ? 1 : 0));
     ops.back().bytes = (double)a.n * T * m * ((swiglu ? 8.0 : 4.0) + 1.0);
-    // output projection fused with the stream update: next = run + b_out + out; the sender's own
-    // output (cache passes) or its difference to the corrupted run (a slot some receiver reads)
-    // leaves through the second output
-    Stream nxt = next_run(2 * l + 2, run.p == M->run_a ? M->run_b : M->run_a);
+    // output projection fused with the stream update: next = run + b_out + out
     pb = (int)probs.size();
     GemmProb po = prob8(M->hcodes, (long long)T * Km, Km, M->hscale, T, 1, M->out_codes + (long long)l * d * Km, Km,
                         M->out_scale + l, d, M->b_out + (long long)l * d, nxt.p, nxt.is, d, 0, T, d, Km, m);
     po.add = run.p; po.add_is = run.is;
-    if (a.kind == BASE_CLEAN || a.kind == BASE_CORRUPT || a.kind == PI_CORRUPT) {
-      Stream dest = sender_dest(s, nullptr, 0);
-      po.aux = dest.p; po.aux_is = dest.is;
-    } else if (general && plan->slot_of[s] >= 0) {
-      po.aux = slot_ptr(s); po.aux_is = slot_is(s);
-      po.aux_sub = corrupt_ref_tile(s);
-    }
+    second_output(po);
     probs.push_back(po);
     add_op(OP_GEMM8, pb, 1, T * a.n, d); work_gemm(pb);
     run = nxt;
@@ -449,8 +509,11 @@ struct Builder {
     else fill_input(gd, general ? &plan->spec[w] : nullptr, 2 * M->L, run);
     norm_params(gd, M->lnf_g, M->lnf_b);
     gd.last_only = 1;
-    gd.out_codes = M->lastcodes; gd.out_codes_is = (long long)B * Kd;
-    gd.out_scale = M->lastscale; gd.out_scale_is = B;
+    if (f32_rest) { gd.out_f32 = M->xf32; gd.out_f32_is = (long long)B * d; }
+    else {
+      gd.out_codes = M->lastcodes; gd.out_codes_is = (long long)B * Kd;
+      gd.out_scale = M->lastscale; gd.out_scale_is = B;
+    }
     groups.push_back(gd);
     add_build(gi, 1, patch_group);
     float* lg; long long lg_is = 0;
@@ -461,6 +524,18 @@ struct Builder {
       default: lg = M->logits; lg_is = (long long)B * Vp; break;
     }
     int pb = (int)probs.size();
+    if (f32_rest) {
+      // all-fp32 mode: the unembedding on the fp32 master, logits in memory, log-softmax + KL over them
+      probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, M->W_U, V, nullptr, 1, M->b_U, lg, lg_is, Vp, 0,
+                            B, V, d, d));
+      add_op(OP_GEMM32, pb, 1, B * a.n, V); work_gemm(pb);
+      if (a.kind == BASE_CLEAN) { add_op(OP_LOGZ, 0, 0, 0, 0, M->logits_clean, M->logz_clean); ops.back().bytes = (double)B * V * 4.0; }
+      else if (general) {
+        add_op(OP_KL, 0, 0, 0, 0, (void*)M->logits_clean, (void*)M->logz_clean);
+        ops.back().bytes = (double)a.n * B * V * 4.0 * (1.0 + 1.0 / a.n);
+      }
+      return;
+    }
     probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1, M->u_codes, Kd,
                           M->u_scale, V, M->b_U, lg, lg_is, Vp, 0, B, V, Kd, d));
     // With exact sums the unembedding itself reduces its rows to the parts of a log-sum-exp and of the KL
@@ -473,7 +548,7 @@ struct Builder {
       GemmProb& q = probs.back();
       q.kl_part = M->kl_part; q.kl_npart = M->kl_npart;
       if (general) {
-        q.C = nullptr;
+        if (!a.keep_logits) q.C = nullptr;
         q.kl_ref = has_pi ? M->ref_logits : M->logits_clean;
         q.kl_ref_logz = has_pi ? M->ref_logz : M->logz_clean;
       }
@@ -564,7 +639,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
   // ---- launch
   const int n = a.n, T = M->T, B = M->B, S = M->S, d = M->d;
   hipStream_t st = M->stream;
-  static const int cls_of[] = {0, 2, 3, 4, 5, 6, 7, 8, 1, 9, 8, 7};   // OpType -> kernel class
+  static const int cls_of[] = {0, 2, 3, 4, 5, 6, 7, 8, 1, 9, 8, 7, 6};   // OpType -> kernel class
   const bool prof_pass = M->prof_on && (M->prof_pass++ % M->prof_every) == 0;
   for (const Op& o : b.ops) {
     int pair = -1;
@@ -598,12 +673,8 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         break;
       case OP_GEMM8:
         for (int q = 0; q < o.i1; q++)
-          if (!gemm8_prob_ok(b.probs[o.i0 + q])) {
-            const GemmProb& p = b.probs[o.i0 + q];
-            fprintf(stderr, "pahq: fp8 GEMM problem rejected: M %d N %d K %d lda %d ldw %d ldc %d a_is %lld c_is %lld add_is %lld aux_is %lld wsb %d A %p W %p C %p add %p aux %p sub %p bias %p\n",
-                    p.M, p.N, p.K, p.lda, p.ldw, p.ldc, p.a_is, p.c_is, p.add_is, p.aux_is, p.wscale_block, p.A, p.W, (void*)p.C, (void*)p.add, (void*)p.aux, (void*)p.aux_sub, (void*)p.bias);
+          if (!gemm8_prob_ok(b.probs[o.i0 + q]))      // the problem does not meet what the kernels assume
             return PAHQ_EINVAL;
-          }
         if (o.p0) HIPCHK(launch_gemm_fp8_kl(d_probs + o.i0, o.i1, o.i2, o.i3, st));      // log-softmax / KL epilogue
         else {
           for (int q = 0; q < o.i1; q++) if (b.probs[o.i0 + q].kl_part || !b.probs[o.i0 + q].C) return PAHQ_EINVAL;
@@ -624,7 +695,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
       case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, o.i2, o.i3, st)); break;
       case OP_ATTN:
         HIPCHK(launch_attention(b.asrcs[o.i0], M->zcodes, (long long)T * M->H * M->Kh,
-                                M->zscale, (long long)T * M->H, M->zf32, (long long)T * M->dh, o.i1, n, B, S, M->H,
+                                M->zscale, (long long)T * M->H, M->zf32, (long long)T * M->dh * __builtin_popcountll(o.u64), o.u64, n, B, S, M->H,
                                 M->dh, M->Kh, M->cfg.pos == PAHQ_POS_ROPE, M->rope_tab, st));
         break;
       case OP_COMBINE: HIPCHK(launch_combine(d_cdesc, o.i0, d_csrc, n, M->tile, d, st)); break;
@@ -635,6 +706,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         HIPCHK(launch_hidden_quant(M->hid, o.i0 == 2 ? M->hid2 : nullptr, (long long)T * M->m, M->hcodes, (long long)T * M->Km,
                                    M->hscale, T, n, T, M->m, M->Km, o.i0, st));
         break;
+      case OP_SWIGLU32: HIPCHK(launch_swiglu_f32(M->hid, M->hid2, (long long)n * T * M->m, st)); break;
       case OP_LOGZ: HIPCHK(launch_logz((const float*)o.p0, B, M->V, M->Vp, (double*)o.p1, st)); break;
       case OP_KL:
         HIPCHK(launch_kl(M->logits, (long long)B * M->Vp, (const float*)o.p0, (const double*)o.p1, M->row_kl, M->kl_dev + a.io_off,

@@ -96,8 +96,9 @@ struct OprojDesc {
   const float* run_in; long long run_in_is;
   float* run_out;      long long run_out_is;
   const float* bias;                        // [N] or null
-  int H, Kh, skip_head, rpi;                // skip_head: the fp32 head (or -1)
+  int H, Kh, rpi, pad_;
   int M, N, aux_begin, dh;                  // M = rows over all instances; aux_begin: first of H HeadAux, or -1; dh = d_head (Kh = dh padded to 128)
+  unsigned long long skip_mask;             // bit h set: head h is computed in fp32 elsewhere (it arrives in `extra`)
 };
 
 // ---- launchers ---------------------------------------------------------------
@@ -148,8 +149,9 @@ hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const Head
 
 // Causal attention per (instance, sequence, head).  q, k, v: fp32 rows [inst][T][..]; head hl of the
 // launch reads columns hl * head_cols .. + dh of each and writes output head h0 + hl (of H).
-// Heads other than f32_head: z rows quantised per head -> zcodes [inst][T][H][ldz], zscale [inst][T][H].
-// f32_head (or -1): z written unquantised to zf32 [inst][T][dh].
+// Heads whose bit is clear in f32_mask: z rows quantised per head -> zcodes [inst][T][H][ldz], zscale [inst][T][H].
+// Heads whose bit is set: z written unquantised to zf32 [inst][T][nf][dh], nf = number of set bits, a head's place
+// = number of set bits below its own.
 struct AttnSrc {
   const float* q; long long q_is; int q_ld; int pad0_;
   const float* k; long long k_is; int k_ld; int pad1_;
@@ -157,7 +159,7 @@ struct AttnSrc {
   int n_heads, h0, head_cols, pad3_;
 };
 hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is, float* zscale,
-                            long long zs_is, float* zf32, long long zf_is, int f32_head, int n_inst, int B, int S,
+                            long long zs_is, float* zf32, long long zf_is, unsigned long long f32_mask, int n_inst, int B, int S,
                             int H, int dh, int ldz, int rope, const float* rope_tab, hipStream_t s);
 // rope_tab: [n_pos][dh / 2] pairs (cos, sin), filled by launch_rope_table; read only when rope != 0, n_pos >= S
 hipError_t launch_rope_table(float* tab, int n_pos, int dh, float theta, hipStream_t s);
@@ -175,6 +177,9 @@ hipError_t launch_logz(const float* logits, int rows, int V, int ldv, double* lo
 // kl[inst] = mean_b sum_v p_ref (log p_ref - log p_inst)
 hipError_t launch_kl(const float* logits, long long l_is, const float* ref_logits, const double* ref_logz,
                      double* row_kl, double* kl, int n_inst, int B, int V, int ldv, hipStream_t s);
+
+// fp32 hidden rows in place: up = silu(gate) * up (the all-fp32 mode's SwiGLU; GELU is the fp32 GEMM's epilogue)
+hipError_t launch_swiglu_f32(float* up, const float* gate, long long n_elem, hipStream_t s);
 
 hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales,
                                    hipStream_t s);

@@ -56,7 +56,8 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
     for (int c = 0; c < 2; c++)
       rb[c] = (pb[c] && real_chunk) ? *(const uint4*)(pb[c] + (long long)h * D.N * D.Kh) : make_uint4(0, 0, 0, 0);
   };
-  auto next_head = [&](int h) { h++; if (h == D.skip_head) h++; return h; };
+  auto skipped = [&](int h) { return ((D.skip_mask >> h) & 1ull) != 0; };
+  auto next_head = [&](int h) { h++; while (h < D.H && skipped(h)) h++; return h; };
 
   // W is the first MFMA operand, so lane (i, g) owns row i of a 16-row tile and columns 4g .. 4g+3
   int row_m[TM];
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
 #pragma unroll
     for (int j = 0; j < TN; j++) tot[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-  int h = (D.skip_head == 0) ? 1 : 0;
+  int h = next_head(-1);
   if (h < D.H) load_head(h);
   for (; h < D.H; h = next_head(h)) {
     __syncthreads();
@@ -242,7 +243,7 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
 
   // adds head h's finished partial result to the total and hands it out if some receiver needs it
   auto fold = [&](int h, const float (&zsc)[TM]) {
-    const bool skip = h == D.skip_head;      // its codes and scales are whatever an earlier pass left
+    const bool skip = ((D.skip_mask >> h) & 1ull) != 0;      // its codes and scales are whatever an earlier pass left
     const float sw = skip ? 0.f : GCF(D.ws)[h];
     HeadAux ax; ax.dst = nullptr; ax.dst_is = 0; ax.sub = nullptr;
     if (D.aux_begin >= 0 && !skip) ax = auxs[D.aux_begin + h];

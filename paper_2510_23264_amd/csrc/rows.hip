@@ -627,6 +627,18 @@ hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_i
   return hipGetLastError();
 }
 
+__global__ void swiglu_f32_k(float* up, const float* gate, long long n) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float g = gate[i];
+  up[i] = g / (1.0f + expf(-g)) * up[i];
+}
+hipError_t launch_swiglu_f32(float* up, const float* gate, long long n_elem, hipStream_t s) {
+  if (n_elem == 0) return hipSuccess;
+  hipLaunchKernelGGL(swiglu_f32_k, dim3((unsigned)((n_elem + 255) / 256)), dim3(256), 0, s, up, gate, n_elem);
+  return hipGetLastError();
+}
+
 hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales,
                                    hipStream_t s) {
   return launch_hidden_quant(x, nullptr, 0LL, codes, 0LL, scales, 0LL, 1, rows, cols, cols, 0, s);

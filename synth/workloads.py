@@ -70,6 +70,10 @@ CONFIGS = {
     "cfg5_L2": dict(shape=dict(n_layers=2, n_heads=32, d_head=128, d_model=4096, d_mlp=11008, vocab=32000,
                                n_ctx=32, norm=NORM_RMS, act=ACT_SWIGLU, pos=POS_ROPE, norm_eps=1e-6),
                     B=16, S=32, law="zipf", k=4, shared_pos=True, taus=(0.01,), n_recv=0, seed=506),
+    # the same at depth 8: the deepest stack of cfg5 layers the CPU check handles in about an hour
+    "cfg5_L8": dict(shape=dict(n_layers=8, n_heads=32, d_head=128, d_model=4096, d_mlp=11008, vocab=32000,
+                               n_ctx=32, norm=NORM_RMS, act=ACT_SWIGLU, pos=POS_ROPE, norm_eps=1e-6),
+                    B=16, S=32, law="zipf", k=4, shared_pos=True, taus=(0.01,), n_recv=0, seed=508),
 }
 
 

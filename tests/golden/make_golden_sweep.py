@@ -1,11 +1,19 @@
 #!/usr/bin/env python3
-"""Writes tests/golden/sweep_<config>.json: the CPU oracle's ACDC pass restricted
-to a few receivers of one named config (full size), with its evaluation trace.
+"""Writes tests/golden/sweep_<name>.json: the CPU oracle's literal one-by-one ACDC pass on one named
+config (full size), whole or restricted to a few receivers, with its evaluation trace and the removed set
+it ends with.  Only oracle/ and synth/ are used.  The GPU test runs pahq_acdc_sweep with the same
+receivers and thresholds and compares step by step.
 
-Only oracle/ and synth/ are used.  The GPU test runs pahq_acdc_sweep on the
-same receivers with the same threshold and compares the trace step by step.
+  cfg2        restricted to six late receivers, a threshold that keeps edges
+  cfg3        the three thresholds the config names, whole graph (on random-initialised weights each of
+              them exceeds every increment: the pass removes the 157 in-edges of the output node and finds
+              every other node dead)
+  cfg3_keep   a threshold a hundred times lower, restricted to the output node and three receivers of the
+              top layer: a circuit with kept edges
+  cfg4        the top MLP input of the config's seeded receiver sample (and the sample's top head input at
+              the config's own threshold)
 
-usage: python tests/golden/make_golden_sweep.py cfg2 5e-4
+usage: python tests/golden/make_golden_sweep.py cfg2|cfg3|cfg3_keep|cfg4
 """
 import json
 import os
@@ -20,29 +28,42 @@ from oracle.model import Model                 # noqa: E402
 from oracle.acdc import Acdc                   # noqa: E402
 
 
-def receivers_for(name, g, L):
+def runs_for(name, g, L, spec):
     top = L - 1
     if name == "cfg2":
-        return [g.OUT, g.mlpin(top), g.headin(top, 7, 2), g.headin(top, 7, 1), g.headin(top, 2, 0), g.headin(top - 1, 4, 2)]
-    raise SystemExit("no receiver sample defined for " + name)
+        return "cfg2", [(5e-4, [g.OUT, g.mlpin(top), g.headin(top, 7, 2), g.headin(top, 7, 1), g.headin(top, 2, 0), g.headin(top - 1, 4, 2)])]
+    if name == "cfg3":
+        return "cfg3", [(tau, None) for tau in spec["taus"]]
+    if name == "cfg3_keep":
+        return "cfg3", [(1e-4, [g.OUT, g.mlpin(top), g.headin(top, 3, 1), g.headin(top, 7, 2)])]
+    if name == "cfg4":
+        sample = [int(r) for r in synth.make_receiver_sample(g.n_receivers, spec["n_recv"], spec["seed"])]
+        assert g.mlpin(top) in sample
+        heads = [r for r in sample if g.receiver_info(r)[0] == "headin" and g.receiver_info(r)[1] == top]
+        return "cfg4", [(1e-4, [g.mlpin(top)]), (spec["taus"][0], [g.mlpin(top), max(heads)])]
+    raise SystemExit("no sweep defined for " + name)
 
 
 def main():
-    name, tau = sys.argv[1], float(sys.argv[2])
+    name = sys.argv[1]
     t0 = time.time()
-    shape, w, clean, corrupt, spec = synth.make_workload(name)
+    cfg = "cfg3" if name.startswith("cfg3") else name
+    shape, w, clean, corrupt, spec = synth.make_workload(cfg)
     oa = Acdc(Model(shape, w), clean, corrupt)
-    recv = receivers_for(name, oa.g, shape.n_layers)
-    removed, trace = oa.sweep(tau, receivers=recv,
-                              progress=lambda v, n, r: print("receiver", v, "evals", n, "removed", r,
-                                                             "t=%.0fs" % (time.time() - t0), flush=True))
-    out = {"config": name, "seed": spec["seed"], "tau": tau, "receivers": [int(r) for r in recv],
-           "trace": [[int(v), int(u), kn, kc, bool(rm)] for v, u, kn, kc, rm in trace],
-           "removed": [int(x) for x in oa.g.removed_to_flat(removed).nonzero()[0]]}
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "sweep_%s.json" % name)
-    with open(path, "w") as f:
-        json.dump(out, f)
-    print("wrote", path, "evals", len(trace), "removed", len(out["removed"]), "in %.0f s" % (time.time() - t0))
+    cfg, runs = runs_for(name, oa.g, shape.n_layers, spec)
+    out = {"config": cfg, "seed": spec["seed"], "runs": []}
+    for tau, recv in runs:
+        removed, trace = oa.sweep(tau, receivers=recv,
+                                  progress=lambda v, n, r: print(name, "tau", tau, "receiver", v, "evals", n, "removed", r,
+                                                                 "t=%.0fs" % (time.time() - t0), flush=True))
+        out["runs"].append({"tau": tau, "receivers": None if recv is None else [int(r) for r in recv],
+                            "trace": [[int(v), int(u), kn, kc, bool(rm)] for v, u, kn, kc, rm in trace],
+                            "removed": [int(x) for x in oa.g.removed_to_flat(removed).nonzero()[0]]})
+        print(name, "tau", tau, "evals", len(trace), "removed", len(out["runs"][-1]["removed"]), "t=%.0fs" % (time.time() - t0), flush=True)
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "sweep_%s.json" % name)
+        with open(path, "w") as f:
+            json.dump(out, f)
+    print("wrote", path, "in %.0f s" % (time.time() - t0))
 
 
 if __name__ == "__main__":

@@ -59,11 +59,17 @@ def test_argument_validation_without_a_device():
     bad = p.Config.from_shape(s); bad.n_layers = 0
     with pytest.raises(p.PahqError):
         p.edge_count(bad)
-    unsup = p.Config.from_shape(s, precision=p.ALL_FP32)
+    unsup = p.Config.from_shape(s); unsup.split_qkv = 0          # the unsplit graph is not built
     with pytest.raises(p.PahqError) as e:
         p.workspace_bytes(unsup, 8, 16)
     assert e.value.code == -6
+    odd = p.Config.from_shape(synth.make_shape("cfg2")); odd.d_mlp = 2050      # hidden rows must be 16-byte multiples
+    with pytest.raises(p.PahqError) as e:
+        p.workspace_bytes(odd, 8, 16)
+    assert e.value.code == -6
     assert p.workspace_bytes(cfg, 8, 16) > 0
+    # the all-fp32 mode needs room for unquantised rows of every receiver group
+    assert p.workspace_bytes(p.Config.from_shape(s, precision=p.ALL_FP32), 8, 16) > p.workspace_bytes(cfg, 8, 16)
     assert p.lib().pahq_strerror(-3) == b"workspace too small"
     # null handles are rejected, not dereferenced
     assert p.lib().pahq_clean_cache(None, None, None) == -1
