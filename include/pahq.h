@@ -156,6 +156,18 @@ int pahq_init_model(const pahq_config*, const pahq_weights*, int32_t B, int32_t 
  * 0 <= id < vocab.  Resets the removed set to empty. */
 int pahq_clean_cache(pahq_model*, const int32_t* clean_tok, const int32_t* corrupt_tok);
 
+/* Which loss every evaluation returns and the sweep decides on (Appendix "Metrics", "Task Metrics"):
+ *   PAHQ_METRIC_KL          batch-mean KL(P_ref || P) at the last position (the default)
+ *   PAHQ_METRIC_LOGIT_DIFF  the task metric: batch mean of how far logit[answer] - logit[distractor] at the
+ *                           last position has dropped below its value in the reference run (0 for the unpruned
+ *                           graph, like the KL; larger = worse); answer_ids, distractor_ids: host int32 [B],
+ *                           0 <= id < vocab, different per sequence (ignored for PAHQ_METRIC_KL, may be NULL).
+ *                           Only the two logits are computed for a candidate, not the unembedding.
+ * Wherever this header says KL, the chosen loss is meant.  Call before pahq_clean_cache: the cache pass takes the
+ * reference values of the loss, so a change of metric drops the caches (PAHQ_ESTATE until they are rebuilt). */
+enum { PAHQ_METRIC_KL = 0, PAHQ_METRIC_LOGIT_DIFF = 1 };
+int pahq_set_metric(pahq_model*, int32_t metric, const int32_t* answer_ids, const int32_t* distractor_ids);
+
 /* Evaluates n candidate edges (sender_ids[i] -> receiver) INDEPENDENTLY: the
  * i-th result is the batch-mean KL(P_ref || P_i) at the last position, where
  * P_i is the clean run with the current removed set plus that one edge
@@ -216,6 +228,22 @@ int pahq_get_weight_q(pahq_model*, int32_t which, int32_t layer, int32_t head, u
 /* The activation quantiser as a function: host x [rows][cols] -> codes, one scale per row.
  * cols <= 16384. */
 int pahq_quantize_rows(pahq_model*, const float* x, int32_t rows, int32_t cols, uint8_t* codes, float* scales);
+/* The same function as the path's three quantisers implement it, each through the code of its own kernel:
+ *   PAHQ_QSITE_HIDDEN  rows of hidden activations (what pahq_quantize_rows runs; cols <= 16384)
+ *   PAHQ_QSITE_NORM    the quantiser at the end of the gather / patch / norm kernels (cols a multiple of 64, <= 4096)
+ *   PAHQ_QSITE_ATTN    the per-head quantiser at the end of the attention kernel (cols = d_head: 16, 32, 64 or 128);
+ *                      the rows are run through the kernel as the values of one-position sequences, whose
+ *                      attention output is the value row itself
+ * All three must give the codes and scales of the definition bit for bit. */
+enum { PAHQ_QSITE_HIDDEN = 0, PAHQ_QSITE_NORM = 1, PAHQ_QSITE_ATTN = 2 };
+int pahq_quantize_rows_site(pahq_model*, int32_t site, const float* x, int32_t rows, int32_t cols, uint8_t* codes,
+                            float* scales);
+/* The E4M3 x E4M3 matrix product of the path as a function (Eq. for A_{comp,8}: low-precision projection, sums in
+ * fp32): out[i][j] = sum_k dec(a[i][k]) * dec(w[j][k]) with unit scales, through the GEMM kernels the model's `mma`
+ * setting selects and the tile shapes its launcher picks for (m, n).  a: host codes [m][k], w: host codes [n][k]
+ * (k contiguous, a multiple of 128), out: host [m][n].  PAHQ_ENOMEM when the model's batch buffers cannot stage
+ * the problem, PAHQ_ESTATE in the all-fp32 mode. */
+int pahq_gemm_codes(pahq_model*, const uint8_t* a, const uint8_t* w, int32_t m, int32_t n, int32_t k, float* out);
 /* Last-position logits [B][vocab]: PAHQ_LOGITS_CLEAN / PAHQ_LOGITS_CORRUPT of the cached runs;
  * PAHQ_LOGITS_REF of the clean run under the precision set of the head investigated last (the reference
  * distribution its candidates were scored against; PAHQ_ESTATE when no head's state is current). */

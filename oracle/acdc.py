@@ -35,11 +35,30 @@ import numpy as np
 from .model import Model, ALL, NONE, log_softmax, kl_to_reference
 
 MODE_ALL_FP32, MODE_ALL_FP8, MODE_PAHQ = 0, 1, 2
+METRIC_KL, METRIC_LOGIT_DIFF = 0, 1
+
+
+def logit_diff_drop(ref_logits, logits, answer, distractor):
+    """Batch mean of how far the logit difference (answer minus distractor) of `logits` has dropped below
+    that of the reference logits.  Paper, Appendix "Task Metrics": the task metric is the difference in
+    logit values between the correct answer and a distractor; taken relative to the clean reference, and
+    with the sign of a loss (larger = worse), it is 0 for the unpruned graph, like the KL."""
+    b = np.arange(len(answer))
+    ref = ref_logits[b, answer] - ref_logits[b, distractor]
+    cur = logits[b, answer] - logits[b, distractor]
+    return float((ref - cur).mean())
 
 
 class Acdc:
-    def __init__(self, model: Model, clean_tokens, corrupt_tokens, mode=MODE_PAHQ):
+    def __init__(self, model: Model, clean_tokens, corrupt_tokens, mode=MODE_PAHQ, metric=METRIC_KL, answer=None,
+                 distractor=None):
+        """metric: METRIC_KL (KL to the clean reference) or METRIC_LOGIT_DIFF (needs one answer and one
+        distractor token id per sequence)."""
         self.m, self.g, self.mode = model, model.g, mode
+        self.metric = metric
+        if metric == METRIC_LOGIT_DIFF:
+            self.answer, self.distractor = np.asarray(answer), np.asarray(distractor)
+            assert self.answer.shape == self.distractor.shape == (len(clean_tokens),)
         self.clean = np.asarray(clean_tokens)
         self.corrupt = np.asarray(corrupt_tokens)
         self.base_pi = ALL if mode == MODE_ALL_FP32 else NONE
@@ -67,7 +86,13 @@ class Acdc:
         _, ref = self.m.forward(self.clean, pi)
         _, lg = self.m.forward(self.clean, pi, removed=removed, C=C)
         self.n_forwards += 3
-        return kl_to_reference(log_softmax(ref), lg)
+        return self.score(ref, lg)
+
+    def score(self, ref_logits, logits):
+        """The loss of a pruned run against the reference run's logits (0 when they are equal)."""
+        if self.metric == METRIC_LOGIT_DIFF:
+            return logit_diff_drop(ref_logits, logits, self.answer, self.distractor)
+        return kl_to_reference(log_softmax(ref_logits), logits)
 
     # cached fast path ------------------------------------------------------------
     def base(self):
@@ -84,7 +109,7 @@ class Acdc:
             oc, ox, _, _ = self.base()
             C, _ = self.m.forward(self.corrupt, pi, base=ox, start_layer=l0)
             _, ref = self.m.forward(self.clean, pi, base=oc, start_layer=l0)
-            self._pi_cache = {key: (C, log_softmax(ref))}      # keep one entry: they are large
+            self._pi_cache = {key: (C, ref)}      # keep one entry: they are large
         return self._pi_cache[key]
 
     def logits_fast(self, receiver, removed):
@@ -96,8 +121,8 @@ class Acdc:
         return lg
 
     def kl_fast(self, receiver, removed):
-        _, logp_ref = self._pi_state(receiver)
-        return kl_to_reference(logp_ref, self.logits_fast(receiver, removed))
+        _, ref = self._pi_state(receiver)
+        return self.score(ref, self.logits_fast(receiver, removed))
 
     def kl_edge(self, receiver, sender, removed=None, brute=False):
         """kl_new of the candidate (sender -> receiver) on top of the removed set."""

@@ -12,6 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libpahq.so")
 
 ALL_FP32, ALL_FP8, PAHQ = 0, 1, 2
 MMA_FP8, MMA_F16_EXACT = 0, 1
+METRIC_KL, METRIC_LOGIT_DIFF = 0, 1
 W_Q, W_K, W_V, W_O, W_IN, W_GATE, W_OUT, W_U = range(8)
 
 
@@ -79,9 +80,12 @@ def lib():
             "pahq_eval_current": [C.c_void_p, C.c_int32, f32p],
             "pahq_acdc_sweep": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
             "pahq_eval_circuit": [C.c_void_p, u8p, u8p, f32p, f32p],
+            "pahq_set_metric": [C.c_void_p, C.c_int32, i32p, i32p],
             "pahq_set_removed": [C.c_void_p, u8p], "pahq_get_removed": [C.c_void_p, u8p],
             "pahq_get_weight_q": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, u8p, f32p],
             "pahq_quantize_rows": [C.c_void_p, f32p, C.c_int32, C.c_int32, u8p, f32p],
+            "pahq_quantize_rows_site": [C.c_void_p, C.c_int32, f32p, C.c_int32, C.c_int32, u8p, f32p],
+            "pahq_gemm_codes": [C.c_void_p, u8p, u8p, C.c_int32, C.c_int32, C.c_int32, f32p],
             "pahq_get_logits": [C.c_void_p, C.c_int32, f32p],
             "pahq_get_sender_output": [C.c_void_p, C.c_int32, C.c_int32, f32p],
             "pahq_get_counters": [C.c_void_p, i64p],
@@ -153,7 +157,8 @@ class Model:
     """pahq_init_model + the calls on the handle.  `weights`: dict of float32 numpy arrays
     (layouts as in include/pahq.h)."""
 
-    def __init__(self, shape, weights, B, S, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, device="cuda:0"):
+    def __init__(self, shape, weights, B, S, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, device="cuda:0",
+                 workspace_bytes_override=None):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no HIP device: libpahq has no CPU path")
@@ -161,6 +166,8 @@ class Model:
         self.B, self.S, self.T = B, S, B * S
         self.n_edges = edge_count(self.cfg)
         nbytes = workspace_bytes(self.cfg, B, S)
+        if workspace_bytes_override is not None:       # hand the library a workspace of another size (its size check)
+            nbytes = int(workspace_bytes_override)
         self._torch = torch
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
@@ -204,6 +211,18 @@ class Model:
         if a.shape != (self.B, self.S) or b.shape != (self.B, self.S):
             raise ValueError("token arrays must be [B][S]")
         _chk(lib().pahq_clean_cache(self.h, _ptr(a, C.c_int32), _ptr(b, C.c_int32)), "pahq_clean_cache")
+
+    def set_metric(self, metric, answer_ids=None, distractor_ids=None):
+        """METRIC_KL or METRIC_LOGIT_DIFF (then with one answer and one distractor token id per sequence);
+        call before clean_cache."""
+        a = d = None
+        if answer_ids is not None:
+            a = np.ascontiguousarray(answer_ids, dtype=np.int32)
+            d = np.ascontiguousarray(distractor_ids, dtype=np.int32)
+            if a.shape != (self.B,) or d.shape != (self.B,):
+                raise ValueError("one answer and one distractor id per sequence")
+        _chk(lib().pahq_set_metric(self.h, int(metric), None if a is None else _ptr(a, C.c_int32),
+                                   None if d is None else _ptr(d, C.c_int32)), "pahq_set_metric")
 
     def eval_edges(self, receiver, sender_ids):
         s = np.ascontiguousarray(sender_ids, dtype=np.int32)
@@ -272,14 +291,32 @@ class Model:
              "pahq_get_weight_q")
         return codes, np.float32(scale.value)
 
-    def quantize_rows(self, x):
+    def quantize_rows(self, x, site=None):
+        """site None: pahq_quantize_rows; 0 / 1 / 2: pahq_quantize_rows_site (hidden, norm, attention quantiser)."""
         x = np.ascontiguousarray(x, dtype=np.float32)
         rows, cols = x.shape
         codes = np.empty((rows, cols), dtype=np.uint8)
         scales = np.empty(rows, dtype=np.float32)
-        _chk(lib().pahq_quantize_rows(self.h, _ptr(x, C.c_float), rows, cols, _ptr(codes, C.c_uint8),
-                                      _ptr(scales, C.c_float)), "pahq_quantize_rows")
+        if site is None:
+            _chk(lib().pahq_quantize_rows(self.h, _ptr(x, C.c_float), rows, cols, _ptr(codes, C.c_uint8),
+                                          _ptr(scales, C.c_float)), "pahq_quantize_rows")
+        else:
+            _chk(lib().pahq_quantize_rows_site(self.h, int(site), _ptr(x, C.c_float), rows, cols, _ptr(codes, C.c_uint8),
+                                               _ptr(scales, C.c_float)), "pahq_quantize_rows_site")
         return codes, scales
+
+    def gemm_codes(self, a, w):
+        """a uint8 [m][k], w uint8 [n][k] -> float32 [m][n] = sum_k dec(a) dec(w)."""
+        a = np.ascontiguousarray(a, dtype=np.uint8)
+        w = np.ascontiguousarray(w, dtype=np.uint8)
+        m, k = a.shape
+        n, k2 = w.shape
+        if k != k2:
+            raise ValueError("a and w must share k")
+        out = np.empty((m, n), dtype=np.float32)
+        _chk(lib().pahq_gemm_codes(self.h, _ptr(a, C.c_uint8), _ptr(w, C.c_uint8), m, n, k, _ptr(out, C.c_float)),
+             "pahq_gemm_codes")
+        return out
 
     def get_logits(self, which):
         out = np.empty((self.B, self.cfg.vocab), dtype=np.float32)

@@ -131,6 +131,7 @@ size_t layout(pahq_model* M, char* base) {
   M->slots = b.take<float>((size_t)M->pool_tiles * tile);
   M->row_kl = b.take<double>(n * B); M->kl_dev = b.take<double>(M->ncap);
   M->psum_clean = b.take<double>(B); M->psum_ref = b.take<double>(B);
+  M->ans_dev = b.take<int>(B); M->dis_dev = b.take<int>(B); M->ld_clean = b.take<double>(B); M->ld_ref = b.take<double>(B);
   M->kl_npart = kl_parts_per_row((int)V); M->kl_part = b.take<float>(n * B * (size_t)M->kl_npart * 4);
   M->arena.slot_bytes = arena_slot_bytes(M);
   for (int i = 0; i < Arena::SLOTS; i++) M->arena.dev[i] = b.take<char>(M->arena.slot_bytes);
@@ -398,6 +399,7 @@ int pahq_init_model(const pahq_config* c, const pahq_weights* w, int32_t B, int3
   for (int r = 0; r < M->g.Nr; r++) M->edge_off[r + 1] = M->edge_off[r] + M->g.n_upstream(r);
   M->removed.assign((size_t)M->edge_off[M->g.Nr], 0);
   M->has_cache = false; M->pi_l = M->pi_h = -2; M->pi_p0 = -1;
+  M->metric = PAHQ_METRIC_KL;
   M->counters[0] = M->counters[1] = M->counters[2] = 0;
   M->prof_on = false; M->prof_used = 0; memset(M->prof, 0, sizeof(M->prof));
   *out = M;
@@ -431,6 +433,23 @@ int pahq_clean_cache(pahq_model* M, const int32_t* clean_tok, const int32_t* cor
   HIPCHK(hipStreamSynchronize(M->stream));
   std::fill(M->removed.begin(), M->removed.end(), 0);
   M->has_cache = true; M->pi_l = M->pi_h = -2;
+  return PAHQ_OK;
+}
+
+int pahq_set_metric(pahq_model* M, int32_t metric, const int32_t* answer_ids, const int32_t* distractor_ids) {
+  if (!M || (metric != PAHQ_METRIC_KL && metric != PAHQ_METRIC_LOGIT_DIFF)) return PAHQ_EINVAL;
+  if (metric == PAHQ_METRIC_LOGIT_DIFF) {
+    if (!answer_ids || !distractor_ids) return PAHQ_EINVAL;
+    for (int b = 0; b < M->B; b++)
+      if (answer_ids[b] < 0 || answer_ids[b] >= M->V || distractor_ids[b] < 0 || distractor_ids[b] >= M->V ||
+          answer_ids[b] == distractor_ids[b]) return PAHQ_EINVAL;
+    HIPCHK(hipMemcpyAsync(M->ans_dev, answer_ids, M->B * sizeof(int), hipMemcpyHostToDevice, M->stream));
+    HIPCHK(hipMemcpyAsync(M->dis_dev, distractor_ids, M->B * sizeof(int), hipMemcpyHostToDevice, M->stream));
+    HIPCHK(hipStreamSynchronize(M->stream));
+  }
+  M->metric = metric;
+  M->has_cache = false;          // the reference values of the metric are taken by the cache pass
+  M->pi_l = M->pi_h = -2;
   return PAHQ_OK;
 }
 
@@ -660,24 +679,72 @@ int pahq_get_weight_q(pahq_model* M, int32_t which, int32_t layer, int32_t head,
   return PAHQ_OK;
 }
 
-int pahq_quantize_rows(pahq_model* M, const float* x, int32_t rows, int32_t cols, uint8_t* codes, float* scales) {
+int pahq_quantize_rows_site(pahq_model* M, int32_t site, const float* x, int32_t rows, int32_t cols, uint8_t* codes,
+                            float* scales) {
   if (!M || !x || !codes || !scales || rows < 0 || cols < 1 || cols > 16384) return PAHQ_EINVAL;
+  if (site == PAHQ_QSITE_NORM && (cols % 64 != 0 || cols > 4096)) return PAHQ_EINVAL;
+  if (site == PAHQ_QSITE_ATTN && cols != 16 && cols != 32 && cols != 64 && cols != 128) return PAHQ_EINVAL;
+  if (site < PAHQ_QSITE_HIDDEN || site > PAHQ_QSITE_ATTN) return PAHQ_EINVAL;
   if (rows == 0) return PAHQ_OK;
   // staged through the candidate buffers: fp32 rows in `logits`, codes in `xcodes`, scales in `xscale`
+  const size_t ldc = site == PAHQ_QSITE_ATTN ? 128 : (size_t)cols;        // the attention kernel writes rows padded to 128 codes
   size_t cap_f = (size_t)M->nmax * M->B * M->Vp, cap_c = (size_t)M->nmax * M->G * M->T * M->Kd, cap_s = (size_t)M->nmax * M->G * M->T;
-  size_t chunk = std::min(std::min(cap_f / cols, cap_c / cols), cap_s);
+  size_t chunk = std::min(std::min(cap_f / cols, cap_c / ldc), cap_s);
   if (chunk < 1) return PAHQ_ENOMEM;
   for (size_t r0 = 0; r0 < (size_t)rows; r0 += chunk) {
     size_t nr = std::min(chunk, (size_t)rows - r0);
     HIPCHK(hipMemcpyAsync(M->logits, x + r0 * cols, nr * cols * sizeof(float), hipMemcpyHostToDevice, M->stream));
-    HIPCHK(launch_quant_rows_plain(M->logits, (int)nr, cols, M->xcodes, M->xscale, M->stream));
-    HIPCHK(hipMemcpyAsync(codes + r0 * cols, M->xcodes, nr * cols, hipMemcpyDeviceToHost, M->stream));
+    if (site == PAHQ_QSITE_HIDDEN) HIPCHK(launch_quant_rows_plain(M->logits, (int)nr, cols, M->xcodes, M->xscale, M->stream));
+    else if (site == PAHQ_QSITE_NORM) HIPCHK(launch_emit_rows(M->logits, (int)nr, cols, M->xcodes, M->xscale, M->stream));
+    else {
+      // nr sequences of one position and one head whose value row is the given row: the softmax over a single
+      // key is 1, so the attention output IS the value row, and what leaves the kernel is its quantisation
+      AttnSrc src; memset(&src, 0, sizeof(src));
+      src.q = src.k = src.v = M->logits; src.q_ld = src.k_ld = src.v_ld = cols;
+      src.n_heads = 1; src.h0 = 0; src.head_cols = 0;
+      HIPCHK(launch_attention(src, M->xcodes, 0, M->xscale, 0, nullptr, 0, 0ull, 1, (int)nr, 1, 1, cols, (int)ldc, 0, nullptr, M->stream));
+    }
+    HIPCHK(hipMemcpy2DAsync(codes + r0 * cols, (size_t)cols, M->xcodes, ldc, (size_t)cols, nr, hipMemcpyDeviceToHost, M->stream));
     HIPCHK(hipMemcpyAsync(scales + r0, M->xscale, nr * sizeof(float), hipMemcpyDeviceToHost, M->stream));
     HIPCHK(hipStreamSynchronize(M->stream));
   }
   // the staging area doubles as zero-padded code storage: restore the zeros
-  size_t used = std::min((size_t)rows, chunk) * cols;
+  size_t used = std::min((size_t)rows, chunk) * ldc;
   HIPCHK(launch_fill_zero(M->xcodes, std::min(cap_c, (used + 15) / 16 * 16), M->stream));
+  HIPCHK(hipStreamSynchronize(M->stream));
+  return PAHQ_OK;
+}
+
+int pahq_quantize_rows(pahq_model* M, const float* x, int32_t rows, int32_t cols, uint8_t* codes, float* scales) {
+  return pahq_quantize_rows_site(M, PAHQ_QSITE_HIDDEN, x, rows, cols, codes, scales);
+}
+
+int pahq_gemm_codes(pahq_model* M, const uint8_t* a, const uint8_t* w, int32_t m, int32_t n, int32_t k, float* out) {
+  if (!M || !a || !w || !out || m < 1 || n < 1 || k < 128 || k % 128 != 0) return PAHQ_EINVAL;
+  if (M->all_f32) return PAHQ_ESTATE;                     // no E4M3 product in that mode
+  const size_t ldc = ((size_t)n + 3) / 4 * 4;
+  const size_t cap_f = (size_t)M->nmax * M->B * M->Vp, cap_c = (size_t)M->nmax * M->G * M->T * M->Kd, cap_s = (size_t)M->nmax * M->G * M->T;
+  const size_t a_bytes = ((size_t)m * k + 255) / 256 * 256;
+  if ((size_t)m * ldc > cap_f || a_bytes + (size_t)n * k > cap_c || (size_t)m + 16 > cap_s) return PAHQ_ENOMEM;
+  uint8_t* da = M->xcodes;
+  uint8_t* dw = M->xcodes + a_bytes;
+  HIPCHK(hipMemcpyAsync(da, a, (size_t)m * k, hipMemcpyHostToDevice, M->stream));
+  HIPCHK(hipMemcpyAsync(dw, w, (size_t)n * k, hipMemcpyHostToDevice, M->stream));
+  std::vector<float> ones((size_t)m + 16, 1.0f);
+  HIPCHK(hipMemcpyAsync(M->xscale, ones.data(), ones.size() * sizeof(float), hipMemcpyHostToDevice, M->stream));
+  GemmProb p; memset(&p, 0, sizeof(p));
+  p.A = da; p.a_is = 0; p.lda = k; p.rpi = m; p.ascale = M->xscale; p.as_is = 0; p.as_stride = 1; p.k_real = k;
+  p.W = dw; p.ldw = k; p.wscale_block = n; p.ws_shift = -1;
+  p.wscale = M->xscale + m;                                // one more 1.0: the whole matrix is one weight slice
+  p.C = M->logits; p.c_is = 0; p.ldc = (int)ldc; p.M = m; p.N = n; p.K = k;
+  if (!gemm8_prob_ok(p)) return PAHQ_EINVAL;
+  void* dp = nullptr;
+  PCHK(upload_table(M, &p, sizeof(p), &dp));
+  HIPCHK(launch_gemm_fp8((const GemmProb*)dp, 1, m, n, M->cfg.mma == PAHQ_MMA_F16_EXACT, M->stream));
+  HIPCHK(hipMemcpy2DAsync(out, (size_t)n * sizeof(float), M->logits, ldc * sizeof(float), (size_t)n * sizeof(float), m,
+                          hipMemcpyDeviceToHost, M->stream));
+  HIPCHK(hipStreamSynchronize(M->stream));
+  HIPCHK(launch_fill_zero(M->xcodes, std::min(cap_c, (a_bytes + (size_t)n * k + 15) / 16 * 16), M->stream));
   HIPCHK(hipStreamSynchronize(M->stream));
   return PAHQ_OK;
 }

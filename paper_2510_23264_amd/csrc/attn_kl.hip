@@ -2,6 +2,7 @@
 // matrix cores) and the fused log-softmax + KL reduction.
 #include "kernels.h"
 #include "device_util.h"
+#include "mma_util.h"
 
 namespace pahq {
 
@@ -429,6 +430,77 @@ hipError_t launch_kl_reduce(const float* kl_part, int npart, int rows, int B, co
   if (rows == 0) return hipSuccess;
   hipLaunchKernelGGL(kl_reduce_k, dim3(rows), dim3(64), 0, s, kl_part, npart, B, ref_logz, ref_psum, logz, row_kl);
   if (kl) hipLaunchKernelGGL(kl_mean_k, dim3((rows / B + 63) / 64), dim3(64), 0, s, row_kl, kl, rows / B, B);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ logit-difference task metric
+// One wavefront per (instance, sequence): the two logits the metric needs -- the answer's and the
+// distractor's -- each the product of the row's e4m3 codes with one column of the unembedding codes
+// (exact products, fp32 sum in an order fixed by the lane layout), scaled and biased like the GEMM's
+// result.  The unembedding itself is not computed for this metric.
+__global__ __launch_bounds__(64) void logit_pair_k(const uint8_t* codes, long long c_is, const float* scale, long long s_is,
+                                                   int ldq, int K, const uint8_t* wcodes, int ldw, const float* wscale,
+                                                   const float* bias, const int* ans, const int* dis, int B, double* ld) {
+  const int row = blockIdx.x, inst = row / B, b = row % B, lane = threadIdx.x;
+  const uint8_t* a = codes + inst * c_is + (long long)b * ldq;
+  const float s2 = scale[inst * s_is + b] * wscale[0];
+  float out[2];
+#pragma unroll
+  for (int which = 0; which < 2; which++) {
+    const int col = which ? dis[b] : ans[b];
+    const uint8_t* wv = wcodes + (long long)col * ldw;
+    float acc = 0.f;
+    for (int k = lane * 8; k < K; k += 512) {
+      const uint2 av = *(const uint2*)(a + k), bv = *(const uint2*)(wv + k);
+      const v8h ha = decode8(av.x, av.y), hb = decode8(bv.x, bv.y);
+#pragma unroll
+      for (int e = 0; e < 8; e++) acc += (float)ha[e] * (float)hb[e];
+    }
+    acc = wave_sum(acc);
+    out[which] = acc * s2 + bias[col];
+  }
+  if (lane == 0) ld[row] = (double)out[0] - (double)out[1];
+}
+// The same from unquantised rows and the fp32 unembedding (all-fp32 mode): x [inst][B][d], W [d][ldw].
+__global__ __launch_bounds__(64) void logit_pair_f32_k(const float* x, long long x_is, int d, const float* W, int ldw,
+                                                       const float* bias, const int* ans, const int* dis, int B, double* ld) {
+  const int row = blockIdx.x, inst = row / B, b = row % B, lane = threadIdx.x;
+  const float* a = x + inst * x_is + (long long)b * d;
+  float out[2];
+#pragma unroll
+  for (int which = 0; which < 2; which++) {
+    const int col = which ? dis[b] : ans[b];
+    float acc = 0.f;
+    for (int k = lane; k < d; k += 64) acc += a[k] * W[(long long)k * ldw + col];
+    out[which] = wave_sum(acc) + bias[col];
+  }
+  if (lane == 0) ld[row] = (double)out[0] - (double)out[1];
+}
+// score[i] = mean over the B sequences of (ref_ld[b] - ld[i][b]): how far the logit difference dropped
+__global__ void metric_mean_k(const double* ld, const double* ref_ld, double* score, int n_inst, int B) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_inst) return;
+  double s = 0.0;
+  for (int b = 0; b < B; b++) s += ref_ld[b] - ld[i * B + b];
+  score[i] = s / (double)B;
+}
+hipError_t launch_logit_pair(const uint8_t* codes, long long c_is, const float* scale, long long s_is, int ldq, int K,
+                             const uint8_t* wcodes, int ldw, const float* wscale, const float* bias, const int* ans,
+                             const int* dis, int n_inst, int B, double* ld, hipStream_t s) {
+  if (n_inst == 0) return hipSuccess;
+  hipLaunchKernelGGL(logit_pair_k, dim3(n_inst * B), dim3(64), 0, s, codes, c_is, scale, s_is, ldq, K, wcodes, ldw, wscale, bias,
+                     ans, dis, B, ld);
+  return hipGetLastError();
+}
+hipError_t launch_logit_pair_f32(const float* x, long long x_is, int d, const float* W, int ldw, const float* bias,
+                                 const int* ans, const int* dis, int n_inst, int B, double* ld, hipStream_t s) {
+  if (n_inst == 0) return hipSuccess;
+  hipLaunchKernelGGL(logit_pair_f32_k, dim3(n_inst * B), dim3(64), 0, s, x, x_is, d, W, ldw, bias, ans, dis, B, ld);
+  return hipGetLastError();
+}
+hipError_t launch_metric_mean(const double* ld, const double* ref_ld, double* score, int n_inst, int B, hipStream_t s) {
+  if (n_inst == 0) return hipSuccess;
+  hipLaunchKernelGGL(metric_mean_k, dim3((n_inst + 63) / 64), dim3(64), 0, s, ld, ref_ld, score, n_inst, B);
   return hipGetLastError();
 }
 

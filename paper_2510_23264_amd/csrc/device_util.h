@@ -43,16 +43,24 @@ __device__ __forceinline__ uint32_t e4m3_encode(float y) {
 }
 
 // tanh-form GELU, 0.5 x (1 + tanh(u)) with u = sqrt(2/pi) (x + 0.044715 x^3), written as
-// x / (1 + exp(-2u)): relative accuracy is kept for negative x, where 1 + tanh(u) cancels.  The
-// exponential and the division are the correctly rounded-to-an-ulp library forms, not the hardware
-// approximations: the result feeds the row quantiser, where a relative error e moves about e / 2^-4
-// of the elements across a rounding boundary, and the approximations' 1e-6 was the largest single
-// contribution to such moves on GELU models.  exp(-2u) overflows to +inf for very negative x, which
-// gives the correct limit -0.
+// x / (1 + exp(-2u)): relative accuracy is kept for negative x, where 1 + tanh(u) cancels.  The result
+// feeds the row quantiser, where a relative error e moves about e / 2^-4 of the elements across a rounding
+// boundary, so both the exponential and the reciprocal are carried to an ulp or two instead of the 1e-6 of
+// the bare hardware forms: exp(v) = exp2(t) * (1 + r ln 2) with t = fl(v log2 e) and r what that product
+// and the rounding of log2 e lost (one FMA recovers it), and one Newton step on the hardware reciprocal.
+// The exponent is clamped at 126: beyond it the result is below 2^-125 |x| and quantises to zero either way.
 __device__ __forceinline__ float gelu_tanh(float x) {
   const float k2 = -2.0f * 0.7978845608028654f;   // -2 sqrt(2/pi)
-  float u = k2 * (x + 0.044715f * x * x * x);
-  return x / (1.0f + expf(u));
+  const float l2e_hi = 1.44269502162933349609375f, l2e_lo = 1.925963033500011e-8f, ln2 = 0.6931471805599453f;
+  const float v = k2 * (x + 0.044715f * x * x * x);
+  const float t = fminf(v * l2e_hi, 126.0f);
+  const float r = (t < 126.0f) ? __fmaf_rn(v, l2e_hi, -t) + v * l2e_lo : 0.0f;
+  float e = __builtin_amdgcn_exp2f(t);
+  e = __fmaf_rn(e, r * ln2, e);
+  const float den = 1.0f + e;
+  float q = __builtin_amdgcn_rcpf(den);
+  q = __fmaf_rn(__fmaf_rn(-den, q, 1.0f), q, q);
+  return x * q;
 }
 
 }  // namespace pahq

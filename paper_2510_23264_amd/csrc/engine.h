@@ -89,6 +89,9 @@ struct pahq_model {
   float* slots; long long pool_tiles;
   double *row_kl, *kl_dev;
   double *psum_clean, *psum_ref;          // [B] sums of the reference rows' probabilities
+  int metric;                             // PAHQ_METRIC_*
+  int *ans_dev, *dis_dev;                 // [B] answer / distractor token of each sequence (logit-difference metric)
+  double *ld_clean, *ld_ref;              // [B] logit difference of the cached clean run / of the current fp32 head's reference run
   float* kl_part; int kl_npart;           // [nmax * B][kl_npart][4]: what the unembedding leaves of a scored pass
   double* kl_host;                        // pinned
   int* send_host;                         // pinned

@@ -64,7 +64,7 @@ void make_plan(pahq_model* M, int p0, int v, RecvPlan& out) {
 
 namespace {
 
-enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH, OP_OPROJ, OP_KLRED, OP_PREF, OP_SWIGLU32 };
+enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH, OP_OPROJ, OP_KLRED, OP_PREF, OP_SWIGLU32, OP_LD };
 struct Op { OpType t; int i0, i1, i2, i3; void* p0; void* p1; double flops, bytes; unsigned long long u64; };
 
 struct Stream { float* p; long long is; };
@@ -498,7 +498,24 @@ struct Builder {
     run = nxt;
   }
 
+  // The logit-difference metric of the rows the final group just produced: for a reference pass into that
+  // run's reference values, for a scored pass into one score per instance.
+  void add_logit_diff() {
+    const bool ref_pass = a.kind == BASE_CLEAN || a.kind == PI_REF;
+    if (ref_pass) add_op(OP_LD, 0, 0, 0, 0, a.kind == BASE_CLEAN ? M->ld_clean : M->ld_ref);
+    else if (general) add_op(OP_LD, 1, 0, 0, 0, has_pi ? M->ld_ref : M->ld_clean);
+    else return;
+    ops.back().bytes = (double)a.n * M->B * (3.0 * M->d + 16.0);
+  }
+
   void final_block(Stream run) {
+    const bool ld = M->metric == PAHQ_METRIC_LOGIT_DIFF;
+    // with that metric a scored pass needs two logits per sequence, not the unembedding (unless its logits are asked for)
+    final_block_kl(run, ld && general && !a.keep_logits);
+    if (ld && a.kind != PI_CORRUPT && a.kind != BASE_CORRUPT) add_logit_diff();
+  }
+
+  void final_block_kl(Stream run, bool group_only) {
     const GraphDims& g = M->g;
     const int d = M->d, B = M->B, Kd = M->Kd, V = M->V, Vp = M->Vp;
     if (a.kind == PI_CORRUPT) return;           // only the sender outputs are needed
@@ -516,6 +533,7 @@ struct Builder {
     }
     groups.push_back(gd);
     add_build(gi, 1, patch_group);
+    if (group_only) return;
     float* lg; long long lg_is = 0;
     switch (a.kind) {
       case BASE_CLEAN: lg = M->logits_clean; break;
@@ -639,7 +657,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
   // ---- launch
   const int n = a.n, T = M->T, B = M->B, S = M->S, d = M->d;
   hipStream_t st = M->stream;
-  static const int cls_of[] = {0, 2, 3, 4, 5, 6, 7, 8, 1, 9, 8, 7, 6};   // OpType -> kernel class
+  static const int cls_of[] = {0, 2, 3, 4, 5, 6, 7, 8, 1, 9, 8, 7, 6, 8};   // OpType -> kernel class
   const bool prof_pass = M->prof_on && (M->prof_pass++ % M->prof_every) == 0;
   for (const Op& o : b.ops) {
     int pair = -1;
@@ -707,6 +725,14 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
                                    M->hscale, T, n, T, M->m, M->Km, o.i0, st));
         break;
       case OP_SWIGLU32: HIPCHK(launch_swiglu_f32(M->hid, M->hid2, (long long)n * T * M->m, st)); break;
+      case OP_LD: {
+        double* ld = o.i0 ? M->row_kl : (double*)o.p0;
+        if (M->all_f32) HIPCHK(launch_logit_pair_f32(M->xf32, (long long)B * d, d, M->W_U, M->V, M->b_U, M->ans_dev, M->dis_dev, n, B, ld, st));
+        else HIPCHK(launch_logit_pair(M->lastcodes, (long long)B * M->Kd, M->lastscale, B, M->Kd, M->Kd, M->u_codes, M->Kd, M->u_scale,
+                                      M->b_U, M->ans_dev, M->dis_dev, n, B, ld, st));
+        if (o.i0) HIPCHK(launch_metric_mean(M->row_kl, (const double*)o.p0, M->kl_dev + a.io_off, n, B, st));
+        break;
+      }
       case OP_LOGZ: HIPCHK(launch_logz((const float*)o.p0, B, M->V, M->Vp, (double*)o.p1, st)); break;
       case OP_KL:
         HIPCHK(launch_kl(M->logits, (long long)B * M->Vp, (const float*)o.p0, (const double*)o.p1, M->row_kl, M->kl_dev + a.io_off,

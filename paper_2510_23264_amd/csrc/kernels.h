@@ -181,7 +181,19 @@ hipError_t launch_kl(const float* logits, long long l_is, const float* ref_logit
 // fp32 hidden rows in place: up = silu(gate) * up (the all-fp32 mode's SwiGLU; GELU is the fp32 GEMM's epilogue)
 hipError_t launch_swiglu_f32(float* up, const float* gate, long long n_elem, hipStream_t s);
 
+// the gather / patch kernels' output quantiser on given rows (cols a multiple of 64, at most 4096; codes row stride cols)
+hipError_t launch_emit_rows(const float* x, int rows, int cols, uint8_t* codes, float* scales, hipStream_t s);
 hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales,
                                    hipStream_t s);
+
+// Logit-difference task metric.  ld[inst * B + b] = logit[answer[b]] - logit[distractor[b]] of row (inst, b), from the
+// row's e4m3 codes and scale and the unembedding's codes [vocab][ldw] (or, fp32 variant, from unquantised rows and
+// the fp32 unembedding [d][ldw]); score[inst] = mean_b (ref_ld[b] - ld[inst * B + b]).
+hipError_t launch_logit_pair(const uint8_t* codes, long long c_is, const float* scale, long long s_is, int ldq, int K,
+                             const uint8_t* wcodes, int ldw, const float* wscale, const float* bias, const int* ans,
+                             const int* dis, int n_inst, int B, double* ld, hipStream_t s);
+hipError_t launch_logit_pair_f32(const float* x, long long x_is, int d, const float* W, int ldw, const float* bias,
+                                 const int* ans, const int* dis, int n_inst, int B, double* ld, hipStream_t s);
+hipError_t launch_metric_mean(const double* ld, const double* ref_ld, double* score, int n_inst, int B, hipStream_t s);
 
 }  // namespace pahq

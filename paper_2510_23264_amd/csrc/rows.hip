@@ -639,6 +639,32 @@ hipError_t launch_swiglu_f32(float* up, const float* gate, long long n_elem, hip
   return hipGetLastError();
 }
 
+// The quantiser at the end of the gather / patch kernels (emit_row) on given rows: one wavefront per row, the
+// row in the element map those kernels use.  cols a multiple of 64, at most 4096.
+template <int MAXE, bool VEC>
+__global__ __launch_bounds__(256) void emit_rows_k(const float* x, int rows, int d, uint8_t* codes, float* scales) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int E = d >> 6;
+  float y[MAXE];
+#pragma unroll
+  for (int j = 0; j < MAXE; j++) y[j] = 0.f;
+  row_load<MAXE, VEC>(y, x + (long long)row * d, E, lane);
+  GroupDesc g;
+  g.out_f32 = nullptr; g.out_codes = codes; g.out_codes_is = 0; g.out_scale = scales; g.out_scale_is = 0;
+  emit_row<MAXE, VEC>(y, E, d, lane, g, 0, row, d);
+}
+hipError_t launch_emit_rows(const float* x, int rows, int cols, uint8_t* codes, float* scales, hipStream_t s) {
+  if (rows == 0) return hipSuccess;
+  if (cols % 64 != 0 || cols > 4096) return hipErrorInvalidValue;
+  dim3 grid((rows + 3) / 4);
+#define CALL(M, V) hipLaunchKernelGGL((emit_rows_k<M, V>), grid, dim3(256), 0, s, x, rows, cols, codes, scales)
+  PAHQ_DISPATCH_E(cols / 64, CALL);
+#undef CALL
+  return hipGetLastError();
+}
+
 hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales,
                                    hipStream_t s) {
   return launch_hidden_quant(x, nullptr, 0LL, codes, 0LL, scales, 0LL, 1, rows, cols, cols, 0, s);

@@ -173,6 +173,18 @@ def make_tokens(vocab: int, B: int, S: int, law: str, k: int, shared_pos: bool, 
     return clean, corrupt
 
 
+def make_answers(vocab: int, B: int, law: str, seed: int):
+    """One answer and one distractor token id per sequence (different from each other), for the
+    logit-difference task metric: stand-ins for the correct and the wrong name of a templated prompt."""
+    rng = np.random.default_rng(seed + 15485863)
+    ans = _draw_tokens(rng, law, vocab, (B,))
+    dis = ans.copy()
+    for b in range(B):
+        while dis[b] == ans[b]:
+            dis[b] = _draw_tokens(rng, law, vocab, ())
+    return ans.astype(np.int32), dis.astype(np.int32)
+
+
 def make_receiver_sample(n_receivers: int, count: int, seed: int):
     """Receiver ids drawn without replacement (all of them when count = 0)."""
     if count <= 0 or count >= n_receivers:

@@ -45,12 +45,13 @@ class SpreadModel(Model):
         return super()._quant_act(x)
 
 
-def kl_with_spread(model, clean, corrupt, mode, cases, seeds=4, eps=EPS, progress=None):
+def kl_with_spread(model, clean, corrupt, mode, cases, seeds=4, eps=EPS, progress=None, **acdc_args):
     """cases: list of (receiver, removed matrix, [senders]).  Returns per case a dict with the oracle's
     kl_current, kl_new[], and the rms deviations sigma_current, sigma_new[], sigma_inc[] (of kl_new -
-    kl_current) over `seeds` perturbed re-evaluations.  `model` must be a SpreadModel."""
+    kl_current) over `seeds` perturbed re-evaluations.  `model` must be a SpreadModel; acdc_args go to
+    oracle.acdc.Acdc (the metric and its token ids)."""
     def run():
-        oa = Acdc(model, clean, corrupt, mode)          # fresh caches under the current perturbation
+        oa = Acdc(model, clean, corrupt, mode, **acdc_args)          # fresh caches under the current perturbation
         out = []
         for r, R, senders in cases:
             cur = oa.kl_fast(r, R)

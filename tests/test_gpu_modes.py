@@ -159,3 +159,85 @@ def test_eval_circuit_with_sets_of_fp32_heads(name):
         check_kl_cases(x, [oa.kl_edge(r, u) for u in range(g.n_upstream(r))], np.zeros(len(x)) + max(sigma), what=name + " after")
     finally:
         gm.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1_hi", "mid_hi", "midllama_hi"])
+def test_logit_difference_metric(name):
+    """The task metric of the paper's Appendix "Task Metrics" (logit of the answer minus logit of a distractor, as
+    a drop below the clean reference) in place of the KL: per-edge values and states under PAHQ precision against
+    the oracle (binding bound), exactly 0 for identical prompts, and in the all-fp32 mode to rounding, with sweeps
+    that decide on it equal to the oracle's decision by decision."""
+    import paper_2510_23264_amd as P
+    import synth
+    from oracle.acdc import METRIC_LOGIT_DIFF
+    from fp32_spread import kl_with_spread
+    shape, w, clean, corrupt = workloads.make(name)
+    B, S = clean.shape
+    ans, dis = synth.make_answers(shape.vocab, B, "uniform", 77)
+    om = SpreadModel(shape, w)
+    g = om.g
+    margs = dict(metric=METRIC_LOGIT_DIFF, answer=ans, distractor=dis)
+    # ---- PAHQ precision
+    gm = P.Model(shape, w, B, S, precision=P.PAHQ, max_batch_edges=16)
+    try:
+        gm.set_metric(P.METRIC_LOGIT_DIFF, ans, dis)
+        with pytest.raises(P.PahqError) as e:
+            gm.eval_current(g.OUT)                           # the caches were dropped with the metric
+        assert e.value.code == -2
+        gm.clean_cache(clean, corrupt)
+        cases = []
+        for frac in (0.0, 0.5):
+            for r in range(g.n_receivers - 1, -1, -max(1, g.n_receivers // 8)):
+                R = rnd_removed(g, frac, 100 + r, r) if frac else g.empty_removed()
+                cases.append((r, R, list(range(g.n_upstream(r)))))
+        res = kl_with_spread(om, clean, corrupt, MODE_PAHQ, cases, seeds=6, **margs)
+        got, want, sigma = [], [], []
+        for (r, R, senders), o in zip(cases, res):
+            gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
+            vals = gm.eval_edges(r, np.array(senders, np.int32))
+            got += [gm.eval_current(r)] + list(vals)
+            want += [o["kl_current"]] + o["kl_new"]
+            sigma += [o["sigma_current"]] + o["sigma_new"]
+        worst = check_kl_cases(got, want, sigma, what=name + " logit difference")
+        assert np.median(np.abs(want)) > 1e-3                # the values are large enough for the bound to bind
+        print(name, "logit difference: median |value| %.3g, worst |d| / bound %.3f" % (np.median(np.abs(want)), worst))
+        # its value for a pruned graph equals the one assembled from the oracle's logits
+        kept = (~g.removed_to_flat(rnd_removed(g, 0.5, 5))).astype(np.uint8)
+        gm.set_removed(np.zeros(g.n_edges(), np.uint8))
+        v, lg = gm.eval_circuit(kept=kept, f32_heads=np.zeros((shape.n_layers, shape.n_heads), np.uint8), want_logits=True)
+        ref = gm.get_logits(0)
+        b = np.arange(B)
+        assert abs(v - np.mean((ref[b, ans] - ref[b, dis]) - (lg[b, ans] - lg[b, dis]))) < 1e-5
+        # identical prompts: exactly 0
+        gm.clean_cache(clean, clean.copy())
+        gm.set_removed(g.removed_to_flat(rnd_removed(g, 0.5, 3, g.mlpin(0) if shape.d_mlp else 3)).astype(np.uint8))
+        r0 = g.mlpin(0) if shape.d_mlp else 3
+        assert (gm.eval_edges(r0, np.arange(g.n_upstream(r0), dtype=np.int32)) == 0.0).all() and gm.eval_current(r0) == 0.0
+        # back to the KL: again a change of metric, again the caches go
+        gm.set_metric(P.METRIC_KL)
+        gm.clean_cache(clean, corrupt)
+        gm.set_removed(np.zeros(g.n_edges(), np.uint8))
+        oa_kl = Acdc(om, clean, corrupt, MODE_PAHQ)
+        x = gm.eval_edges(g.OUT, np.arange(g.n_senders, dtype=np.int32))
+        check_kl_cases(x, [oa_kl.kl_edge(g.OUT, u) for u in range(g.n_senders)], np.zeros(g.n_senders) + max(sigma), what="kl again")
+    finally:
+        gm.close()
+    # ---- all-fp32: rounding-level agreement and equal sweeps
+    gm = P.Model(shape, w, B, S, precision=P.ALL_FP32, max_batch_edges=16)
+    try:
+        gm.set_metric(P.METRIC_LOGIT_DIFF, ans, dis)
+        gm.clean_cache(clean, corrupt)
+        oa = Acdc(om, clean, corrupt, MODE_ALL_FP32, **margs)
+        for r in (g.OUT, g.n_receivers // 2, 1):
+            vals = gm.eval_edges(r, np.arange(g.n_upstream(r), dtype=np.int32))
+            for u in range(g.n_upstream(r)):
+                wv = oa.kl_edge(r, u)
+                assert abs(vals[u] - wv) <= F32_ATOL + F32_RTOL * abs(wv), (name, r, u, vals[u], wv)
+        for tau in (1e-2, 1e-1):
+            kept, n_evals, tr = gm.acdc_sweep(tau)
+            o_removed, o_tr = oa.sweep(tau)
+            assert n_evals == len(o_tr) and all(bool(t["removed"]) == o[4] for t, o in zip(tr, o_tr)), (name, tau)
+            assert (kept == (~g.removed_to_flat(o_removed)).astype(np.uint8)).all()
+            print(name, "logit-difference sweep, all-fp32, tau", tau, "equal; kept", int(kept.sum()))
+    finally:
+        gm.close()

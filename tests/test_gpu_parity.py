@@ -524,7 +524,27 @@ def test_error_codes(cfg1):
         p.Model(cfg1.shape, w, 8, 16)
     assert e.value.code == -5
     fresh = p.Model(cfg1.shape, cfg1.w, 8, 16)
-    with pytest.raises(p.PahqError) as e:
-        fresh.eval_edges(0, [0])
-    assert e.value.code == -2
+    for call in (lambda: fresh.eval_edges(0, [0]), lambda: fresh.eval_circuit(), lambda: fresh.acdc_sweep(0.1)):
+        with pytest.raises(p.PahqError) as e:
+            call()
+        assert e.value.code == -2                       # nothing cached yet
     fresh.close()
+    # a workspace one byte short of what pahq_workspace_bytes asks for is refused, the exact size is accepted
+    need = p.workspace_bytes(p.Config.from_shape(cfg1.shape), 8, 16)
+    with pytest.raises(p.PahqError) as e:
+        p.Model(cfg1.shape, cfg1.w, 8, 16, workspace_bytes_override=need - 1)
+    assert e.value.code == -3
+    p.Model(cfg1.shape, cfg1.w, 8, 16, workspace_bytes_override=need).close()
+    # a sweep that fails leaves the removed set as it found it
+    before = np.zeros(g.n_edges(), np.uint8); before[-3:] = 1
+    gm.set_removed(before)
+    with pytest.raises(p.PahqError):
+        gm.acdc_sweep(0.1, receivers=[10 ** 6])
+    assert (gm.get_removed() == before).all()
+    gm.set_removed(np.zeros(g.n_edges(), np.uint8))
+    # the reference logits exist once a head has been investigated
+    gm.eval_edges(g.headin(1, 0, 0), [0])
+    assert gm.get_logits(2).shape == (8, cfg1.shape.vocab)
+    with pytest.raises(p.PahqError) as e:
+        gm.get_logits(3)
+    assert e.value.code == -1

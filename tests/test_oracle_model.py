@@ -384,3 +384,45 @@ def test_patch_routing_against_loop_forward(shape):
     outs, _ = m.forward(clean, frozenset(), removed=R, C=C)
     changed = [s for s in range(g.n_senders) if not (outs[s] == base[s]).all()]
     assert changed and changed[0] == g.head(1, 0) and g.head(1, 1) not in changed
+
+
+# ---------------------------------------------------------------- logit-difference task metric
+from oracle.acdc import METRIC_LOGIT_DIFF, logit_diff_drop
+
+
+def test_logit_difference_metric():
+    """Paper, Appendix "Task Metrics": the logit of the correct answer minus that of a distractor.  As a
+    loss relative to the clean reference it is 0 for the unpruned graph, the drop ld(clean) - ld(corrupt) for
+    the fully ablated one, unchanged by a per-sequence shift of the logits, and written out per sequence it is
+    what the function returns."""
+    m, w, clean, corrupt = tiny(TINY_GELU, B=4)
+    g = m.g
+    ans, dis = synth.make_answers(TINY_GELU.vocab, 4, "uniform", 9)
+    assert (ans != dis).all()
+    rng = np.random.default_rng(1)
+    ref, lg = rng.standard_normal((4, 40)), rng.standard_normal((4, 40))
+    by_hand = np.mean([(ref[b, ans[b]] - ref[b, dis[b]]) - (lg[b, ans[b]] - lg[b, dis[b]]) for b in range(4)])
+    assert abs(logit_diff_drop(ref, lg, ans, dis) - by_hand) < 1e-15
+    assert logit_diff_drop(ref, ref, ans, dis) == 0.0
+    assert abs(logit_diff_drop(ref, lg + rng.standard_normal((4, 1)), ans, dis) - by_hand) < 1e-14
+    a = Acdc(m, clean, corrupt, MODE_PAHQ, metric=METRIC_LOGIT_DIFF, answer=ans, distractor=dis)
+    v = g.headin(1, 0, 1)
+    assert a.kl_fast(v, g.empty_removed()) == 0.0
+    full = g.flat_to_removed(np.ones(g.n_edges(), bool))
+    pi = a.pi_of(v)
+    _, lc = m.forward(clean, pi)
+    _, lx = m.forward(corrupt, pi)
+    b = np.arange(4)
+    drop = ((lc[b, ans] - lc[b, dis]) - (lx[b, ans] - lx[b, dis])).mean()
+    assert abs(a.kl_brute(v, full) - drop) < 1e-12
+    # brute force (three forwards) = cached fast path, and a clean patch scores exactly 0
+    R = g.flat_to_removed(rng.random(g.n_edges()) < 0.4)
+    for r in (g.OUT, g.mlpin(1), v):
+        Rr = R.copy(); Rr[:r] = False
+        for u in (0, g.n_upstream(r) - 1):
+            assert abs(a.kl_edge(r, u, removed=Rr) - a.kl_edge(r, u, removed=Rr, brute=True)) < 1e-13
+    a0 = Acdc(m, clean, clean, MODE_PAHQ, metric=METRIC_LOGIT_DIFF, answer=ans, distractor=dis)
+    assert a0.kl_fast(v, R * 0 + (np.arange(g.n_receivers)[:, None] >= v) * R) == 0.0
+    # the sweep runs on it with the same rule
+    removed, trace = a.sweep(1e-3)
+    assert all(rm == ((kn - kc) < 1e-3) for _, _, kn, kc, rm in trace)
