@@ -201,6 +201,14 @@ int pahq_eval_current(pahq_model*, int32_t receiver, float* kl_out);
 int pahq_acdc_sweep(pahq_model*, float tau, const int32_t* receivers, int32_t n_receivers,
                     uint8_t* kept, int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap);
 
+/* The same pass for a grid of thresholds (the paper's Experiments section scans 21 log-spaced values of tau in
+ * [0.001, 3.16] to trace a ROC curve): every sweep starts from the empty removed set and all of them share the
+ * clean / corrupted caches of one pahq_clean_cache call, which is the only part of a sweep that does not depend
+ * on tau.  taus: host, n_taus values; kept: host, n_taus x pahq_edge_count bytes (row i = result at taus[i]);
+ * n_evals: host, n_taus counts (may be NULL).  The removed set is left at the last threshold's result. */
+int pahq_acdc_sweep_grid(pahq_model*, const float* taus, int32_t n_taus, const int32_t* receivers, int32_t n_receivers,
+                         uint8_t* kept, int64_t* n_evals);
+
 /* Inference on a pruned graph with a SET of fp32 heads (Appendix "Integration with ACDC", last block of the
  * algorithm: forward on G_sparse with the heads H_high of every layer in high precision): the clean run in
  * which every edge that is not kept carries the corrupted run's activation, the flagged heads' query / key /

@@ -79,6 +79,7 @@ def lib():
             "pahq_eval_edges": [C.c_void_p, C.c_int32, i32p, C.c_int32, f32p],
             "pahq_eval_current": [C.c_void_p, C.c_int32, f32p],
             "pahq_acdc_sweep": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
+            "pahq_acdc_sweep_grid": [C.c_void_p, f32p, C.c_int32, i32p, C.c_int32, u8p, i64p],
             "pahq_eval_circuit": [C.c_void_p, u8p, u8p, f32p, f32p],
             "pahq_set_metric": [C.c_void_p, C.c_int32, i32p, i32p],
             "pahq_set_removed": [C.c_void_p, u8p], "pahq_get_removed": [C.c_void_p, u8p],
@@ -136,6 +137,11 @@ def measure_ceilings(scratch_mib=1024):
     _chk(lib().pahq_measure_ceilings(C.c_void_p(torch.cuda.current_stream().cuda_stream), C.c_void_p(buf.data_ptr()),
                                      C.c_size_t(buf.numel()), C.byref(tf), C.byref(gb)), "pahq_measure_ceilings")
     return tf.value, gb.value
+
+
+def tau_grid(n=21, lo=1e-3, hi=10 ** 0.5):
+    """The threshold grid of the paper's ROC scans: n log-spaced values from lo to hi (21 values in [0.001, 3.16])."""
+    return np.exp(np.linspace(np.log(lo), np.log(hi), n)).astype(np.float32)
 
 
 def quantize_rows_noalloc(x, codes, scales, stream=None):
@@ -252,6 +258,20 @@ class Model:
         n = min(n_evals.value, cap)
         tr = np.ctypeslib.as_array(trace)[:n].copy() if n else np.zeros(0, dtype=np.dtype(TraceRec))
         return kept, n_evals.value, tr
+
+    def acdc_sweep_grid(self, taus, receivers=None):
+        """Sweeps at every threshold of `taus` on one set of caches.  Returns (kept uint8[n_taus][n_edges], n_evals[n_taus])."""
+        t = np.ascontiguousarray(taus, dtype=np.float32)
+        kept = np.empty((t.size, self.n_edges), dtype=np.uint8)
+        n_evals = np.zeros(t.size, dtype=np.int64)
+        if receivers is None:
+            rp, rn = None, 0
+        else:
+            r = np.ascontiguousarray(receivers, dtype=np.int32)
+            rp, rn = _ptr(r, C.c_int32), r.size
+        _chk(lib().pahq_acdc_sweep_grid(self.h, _ptr(t, C.c_float), t.size, rp, rn, _ptr(kept, C.c_uint8),
+                                        _ptr(n_evals, C.c_int64)), "pahq_acdc_sweep_grid")
+        return kept, n_evals
 
     def eval_circuit(self, kept=None, f32_heads=None, want_logits=False):
         """KL of the pruned graph under a set of fp32 heads (and its logits when asked for)."""

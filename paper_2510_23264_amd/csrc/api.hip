@@ -512,6 +512,21 @@ int pahq_acdc_sweep(pahq_model* M, float tau, const int32_t* receivers, int32_t 
   return rc;
 }
 
+int pahq_acdc_sweep_grid(pahq_model* M, const float* taus, int32_t n_taus, const int32_t* receivers, int32_t n_receivers,
+                         uint8_t* kept, int64_t* n_evals) {
+  if (!M || !taus || n_taus < 1 || !kept) return PAHQ_EINVAL;
+  for (int i = 0; i < n_taus; i++) if (taus[i] != taus[i]) return PAHQ_EINVAL;
+  const std::vector<uint8_t> before = M->removed;
+  const size_t ne = M->removed.size();
+  for (int i = 0; i < n_taus; i++) {
+    int64_t evals = 0;
+    int rc = sweep_impl(M, taus[i], receivers, n_receivers, kept + (size_t)i * ne, &evals, nullptr, 0);
+    if (rc != PAHQ_OK) { M->removed = before; return rc; }
+    if (n_evals) n_evals[i] = evals;
+  }
+  return PAHQ_OK;
+}
+
 static int sweep_impl(pahq_model* M, float tau, const int32_t* receivers, int32_t n_receivers, uint8_t* kept,
                       int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap) {
   if (!M || n_receivers < 0 || (n_receivers > 0 && !receivers) || trace_cap < 0 || (trace_cap > 0 && !trace)) return PAHQ_EINVAL;

@@ -103,6 +103,8 @@ def test_cfg5_full_size_properties():
 def pooled_increment_spread(name):
     """rms over the stored cases of a workload of the spread binary32 arithmetic leaves in an increment."""
     gold = json.load(open(os.path.join(GOLDEN, "kl_%s.json" % name)))
+    if "spread_eps" not in gold:
+        pytest.skip("stored values of %s carry no binary32 spread" % name)
     return pooled([v for c in gold["cases"] for v in c["sigma_inc"]])
 
 

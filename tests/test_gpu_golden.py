@@ -73,7 +73,10 @@ def test_stored_oracle_values(name):
     worst = {}
     for what, a in (("kl_new", new), ("kl_current", cur), ("increment", inc)):
         worst[what] = check_kl_cases(a[:, 0], a[:, 1], a[:, 2], what="%s %s" % (name, what), kl_scale=a[:, 3])
-    print(name, "median KL %.3g, worst |d| / bound:" % np.median(new[:, 1]), {k: round(v, 3) for k, v in worst.items()})
+    from tolerance import tight, pooled
+    med = float(np.median(np.abs(new[:, 0] - new[:, 1]) / (tight(new[:, 3]) + np.maximum(new[:, 2], pooled(new[:, 2])))))
+    print(name, "median KL %.3g, worst |d| / bound:" % np.median(new[:, 1]), {k: round(v, 3) for k, v in worst.items()},
+          "median |d| / (tight + sigma) %.3f, pooled sigma / median KL %.2g" % (med, pooled(new[:, 2]) / np.median(new[:, 1])))
     if task_tol:
         for a in (new, cur):
             d = np.abs(a[:, 0] - a[:, 1])

@@ -241,3 +241,34 @@ def test_logit_difference_metric(name):
             print(name, "logit-difference sweep, all-fp32, tau", tau, "equal; kept", int(kept.sum()))
     finally:
         gm.close()
+
+
+def test_threshold_grid_on_one_set_of_caches():
+    """pahq_acdc_sweep_grid over the paper's 21-value threshold grid (scaled to the workload's KL range): every
+    row equals the single sweep at that threshold, no cache pass is repeated, and in the all-fp32 mode every
+    row equals the oracle's sweep (kept sets shrink as the threshold grows)."""
+    import paper_2510_23264_amd as P
+    shape, w, clean, corrupt = workloads.make("cfg1_hi")
+    B, S = clean.shape
+    grid = P.tau_grid()
+    assert grid.size == 21 and abs(grid[0] - 1e-3) < 1e-9 and abs(grid[-1] - 3.1623) < 1e-3
+    om = OModel(shape, w)
+    g = om.g
+    for precision, mode in ((P.ALL_FP32, MODE_ALL_FP32), (P.PAHQ, MODE_PAHQ)):
+        gm = P.Model(shape, w, B, S, precision=precision, max_batch_edges=16)
+        try:
+            gm.clean_cache(clean, corrupt)
+            passes0 = gm.counters()[2]
+            kept, n_evals = gm.acdc_sweep_grid(grid)
+            sizes = kept.sum(axis=1)
+            assert (np.diff(sizes.astype(int)) <= 0).all() and sizes[0] > sizes[-1]
+            for i in (0, 7, 14, 20):
+                k1, n1, _ = gm.acdc_sweep(float(grid[i]))
+                assert n1 == n_evals[i] and (k1 == kept[i]).all()
+            if precision == P.ALL_FP32:
+                oa = Acdc(om, clean, corrupt, mode)
+                for i in range(0, 21, 2):
+                    o_removed, o_tr = oa.sweep(float(grid[i]))
+                    assert len(o_tr) == n_evals[i] and (kept[i] == (~g.removed_to_flat(o_removed)).astype(np.uint8)).all(), i
+        finally:
+            gm.close()
