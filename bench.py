@@ -228,8 +228,11 @@ def main():
                     help="all_fp32: the unaccelerated ACDC of the paper's runtime table (no quantiser anywhere)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
-    ap.add_argument("--only", default=None, choices=(None, "all_edges", "gather_regime", "sweep"),
-                    help="run one regime only (short runs under a profiler)")
+    ap.add_argument("--only", default=None, choices=(None, "all_edges", "gather_regime", "sweep", "policies"),
+                    help="run one regime only (short runs under a profiler); 'policies' (never part of the default run) "
+                         "sweeps once under each precision policy -- fp32 for the head an edge feeds (the default) and "
+                         "fp32 for the edge's source head as Eq. P_t prints it -- and reports where they differ")
+    ap.add_argument("--tau", type=float, default=None, help="threshold of the 'policies' comparison")
     ap.add_argument("--recv-stride", type=int, default=1,
                     help="evaluate only every k-th receiver (short runs under a profiler; the headline uses 1)")
     args = ap.parse_args()
@@ -335,6 +338,29 @@ def main():
                 e["kernels"] = kernel_table(sp)
             sweeps[str(tau)] = e
         out["sweep"] = sweeps
+
+    if args.only == "policies":
+        tau = args.tau if args.tau is not None else 1e-4
+        recv = receivers if spec["n_recv"] else None
+        res = {}
+        for label, sp in (("receiver_side", False), ("sender_side", True)):
+            gm.clean_cache(clean, corrupt)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            kept, ne, tr = gm.acdc_sweep(tau, receivers=recv, sender_policy=sp)
+            res[label] = (kept.copy(), int(ne), time.perf_counter() - t1, tr)
+        ka, kb = res["receiver_side"][0], res["sender_side"][0]
+        ta, tb = res["receiver_side"][3], res["sender_side"][3]
+        same_prefix = 0
+        for x, y in zip(ta, tb):
+            if (x["receiver"], x["sender"], x["removed"]) != (y["receiver"], y["sender"], y["removed"]):
+                break
+            same_prefix += 1
+        out["policies"] = {"tau": tau, "edges": int(gm.n_edges),
+                           "receiver_side": {"decisions": res["receiver_side"][1], "kept": int(ka.sum()), "s": round(res["receiver_side"][2], 3)},
+                           "sender_side": {"decisions": res["sender_side"][1], "kept": int(kb.sum()), "s": round(res["sender_side"][2], 3)},
+                           "kept_by_both": int((ka & kb).sum()), "kept_by_one_only": int((ka ^ kb).sum()),
+                           "identical_decisions_before_the_first_difference": same_prefix}
 
     # what this device does on a pure matrix-core issue loop and on a streaming copy, measured now, next to the
     # published peaks the roofline divides by

@@ -209,6 +209,19 @@ int pahq_acdc_sweep(pahq_model*, float tau, const int32_t* receivers, int32_t n_
 int pahq_acdc_sweep_grid(pahq_model*, const float* taus, int32_t n_taus, const int32_t* receivers, int32_t n_receivers,
                          uint8_t* kept, int64_t* n_evals);
 
+/* The precision policy exactly as Eq. P_t prints it: FP32 for the SOURCE node of the evaluated edge (when it is a
+ * head), FP8 for everything else.  Under it the precision set changes with every candidate, so nothing can be shared
+ * between the candidates of a receiver: each one costs a corrupted run and a reference run under its set from the
+ * sender's layer on, the current graph and the graph without the edge -- the three inferences per edge of the
+ * appendix algorithm plus the current state.  kl_new_out[i] / kl_cur_out[i]: loss with / without the i-th edge
+ * removed on top of the current removed set, both under the set of sender_ids[i]; the sweep decides on their
+ * difference, in the same order and by the same rule as pahq_acdc_sweep.  Meant for comparing the two policies
+ * (the default, receiver side, is what pahq_eval_edges and pahq_acdc_sweep implement); one candidate at a time. */
+int pahq_eval_edges_sender_policy(pahq_model*, int32_t receiver, const int32_t* sender_ids, int32_t n, float* kl_new_out,
+                                  float* kl_cur_out);
+int pahq_acdc_sweep_sender_policy(pahq_model*, float tau, const int32_t* receivers, int32_t n_receivers, uint8_t* kept,
+                                  int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap);
+
 /* Inference on a pruned graph with a SET of fp32 heads (Appendix "Integration with ACDC", last block of the
  * algorithm: forward on G_sparse with the heads H_high of every layer in high precision): the clean run in
  * which every edge that is not kept carries the corrupted run's activation, the flagged heads' query / key /

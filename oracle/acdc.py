@@ -10,7 +10,9 @@ evaluation only the investigated head is kept in fp32.
 
 Readings (the paper defers the procedure to ACDC and is silent on them):
 * the fp32 head is the head the candidate edge feeds (receiver side); edges
-  into an MLP or into the unembedding have no fp32 head;
+  into an MLP or into the unembedding have no fp32 head.  The policy as Eq. P_t
+  prints it (fp32 for the edge's SOURCE) is available next to it
+  (pair_sender_policy, sweep_sender_policy) for comparison;
 * the reference distribution is computed under the same precision set as the
   patched run, so that patching with clean activations gives KL = 0;
 * one pass over receivers in descending id (output first), senders in
@@ -130,6 +132,51 @@ class Acdc:
         assert sender < self.g.n_upstream(receiver)
         rem[receiver, sender] = True
         return self.kl_brute(receiver, rem) if brute else self.kl_fast(receiver, rem)
+
+    # the paper-literal precision policy -------------------------------------------
+    def pi_of_sender(self, sender):
+        """Eq. P_t as printed: FP32 for the SOURCE node of the evaluated edge (a head; an MLP or the embedding
+        has no attention weights to keep in fp32), FP8 for everything else."""
+        kind, l, h = self.g.sender_info(sender)
+        if self.mode == MODE_ALL_FP32:
+            return ALL
+        return frozenset([(l, h)]) if (self.mode == MODE_PAHQ and kind == "head") else NONE
+
+    def pair_sender_policy(self, receiver, sender, removed):
+        """(loss of the current graph, loss with the edge sender -> receiver removed as well), both under the
+        precision set of the SENDER: corrupted run, reference run and the two pruned runs are recomputed from
+        the sender's layer on (below it nothing depends on that set)."""
+        pi = self.pi_of_sender(sender)
+        kind, l_s, _ = self.g.sender_info(sender)
+        l0 = min(l_s, self.start_layer_of(receiver)) if kind == "head" else self.start_layer_of(receiver)
+        oc, ox, _, _ = self.base()
+        C, _ = self.m.forward(self.corrupt, pi, base=ox, start_layer=l0)
+        _, ref = self.m.forward(self.clean, pi, base=oc, start_layer=l0)
+        _, cur = self.m.forward(self.clean, pi, removed=removed, C=C, base=oc, start_layer=l0)
+        cand = removed.copy()
+        cand[receiver, sender] = True
+        _, new = self.m.forward(self.clean, pi, removed=cand, C=C, base=oc, start_layer=l0)
+        self.n_forwards += 4
+        return self.score(ref, cur), self.score(ref, new)
+
+    def sweep_sender_policy(self, tau, receivers=None):
+        """The same pass as sweep(), every candidate judged under the precision set of its own sender."""
+        g = self.g
+        removed = g.empty_removed()
+        trace = []
+        order = range(g.n_receivers - 1, -1, -1) if receivers is None else sorted(receivers, reverse=True)
+        for v in order:
+            n_up = g.n_upstream(v)
+            if not self.node_is_live(v, removed):
+                removed[v, :n_up] = True
+                continue
+            for u in range(n_up - 1, -1, -1):
+                kl_cur, kl_new = self.pair_sender_policy(v, u, removed)
+                rm = (kl_new - kl_cur) < tau
+                trace.append((v, u, kl_new, kl_cur, bool(rm)))
+                if rm:
+                    removed[v, u] = True
+        return removed, trace
 
     # the sweep -------------------------------------------------------------------
     def node_is_live(self, receiver, removed):

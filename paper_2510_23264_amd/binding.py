@@ -79,6 +79,8 @@ def lib():
             "pahq_eval_edges": [C.c_void_p, C.c_int32, i32p, C.c_int32, f32p],
             "pahq_eval_current": [C.c_void_p, C.c_int32, f32p],
             "pahq_acdc_sweep": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
+            "pahq_eval_edges_sender_policy": [C.c_void_p, C.c_int32, i32p, C.c_int32, f32p, f32p],
+            "pahq_acdc_sweep_sender_policy": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
             "pahq_acdc_sweep_grid": [C.c_void_p, f32p, C.c_int32, i32p, C.c_int32, u8p, i64p],
             "pahq_eval_circuit": [C.c_void_p, u8p, u8p, f32p, f32p],
             "pahq_set_metric": [C.c_void_p, C.c_int32, i32p, i32p],
@@ -242,7 +244,16 @@ class Model:
         _chk(lib().pahq_eval_current(self.h, int(receiver), C.byref(out)), "pahq_eval_current")
         return out.value
 
-    def acdc_sweep(self, tau, receivers=None, trace_cap=None):
+    def eval_edges_sender_policy(self, receiver, sender_ids):
+        """(kl_new, kl_cur) per candidate, each under the precision set of its own sender."""
+        s = np.ascontiguousarray(sender_ids, dtype=np.int32)
+        new = np.empty(s.size, dtype=np.float32)
+        cur = np.empty(s.size, dtype=np.float32)
+        _chk(lib().pahq_eval_edges_sender_policy(self.h, int(receiver), _ptr(s, C.c_int32), s.size, _ptr(new, C.c_float),
+                                                 _ptr(cur, C.c_float)), "pahq_eval_edges_sender_policy")
+        return new, cur
+
+    def acdc_sweep(self, tau, receivers=None, trace_cap=None, sender_policy=False):
         """Returns (kept uint8[n_edges], n_evals, trace structured array)."""
         kept = np.empty(self.n_edges, dtype=np.uint8)
         n_evals = C.c_int64()
@@ -253,8 +264,8 @@ class Model:
         else:
             r = np.ascontiguousarray(receivers, dtype=np.int32)
             rp, rn = _ptr(r, C.c_int32), r.size
-        _chk(lib().pahq_acdc_sweep(self.h, C.c_float(tau), rp, rn, _ptr(kept, C.c_uint8), C.byref(n_evals), trace,
-                                   cap), "pahq_acdc_sweep")
+        fn = lib().pahq_acdc_sweep_sender_policy if sender_policy else lib().pahq_acdc_sweep
+        _chk(fn(self.h, C.c_float(tau), rp, rn, _ptr(kept, C.c_uint8), C.byref(n_evals), trace, cap), "pahq_acdc_sweep")
         n = min(n_evals.value, cap)
         tr = np.ctypeslib.as_array(trace)[:n].copy() if n else np.zeros(0, dtype=np.dtype(TraceRec))
         return kept, n_evals.value, tr

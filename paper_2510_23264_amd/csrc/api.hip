@@ -653,6 +653,104 @@ int pahq_eval_circuit(pahq_model* M, const uint8_t* kept, const uint8_t* f32_hea
   return PAHQ_OK;
 }
 
+namespace {
+// One candidate under the precision set of its SENDER (Eq. P_t as printed): corrupted run and reference under that
+// set from the sender's layer on, then the current graph and the graph without the edge.  Four passes of one
+// instance each: the cost of a policy under which nothing can be shared between the candidates of a receiver.
+int eval_pair_sender(pahq_model* M, int v, int u, double* kl_cur, double* kl_new) {
+  const GraphDims& g = M->g;
+  const int L = M->L, H = M->H;
+  int p0 = g.pos_of_receiver(v);
+  std::vector<unsigned long long> masks(L, 0ull);
+  bool any = false;
+  if (M->cfg.precision == PAHQ_PAHQ && u > 0) {
+    const int l = (u - 1) / (H + g.mu), r = (u - 1) % (H + g.mu);
+    if (r < H) { masks[l] = 1ull << r; any = true; p0 = std::min(p0, 2 * l); }
+  }
+  for (int w = 0; w < g.Nr; w++) {                 // what lies upstream of the first recomputed position comes from the caches
+    if (g.pos_of_receiver(w) >= p0) continue;
+    const uint8_t* row = M->removed.data() + M->edge_off[w];
+    for (int s = 0, n_up = g.n_upstream(w); s < n_up; s++) if (row[s]) return PAHQ_ESTATE;
+  }
+  PassArgs a; a.n = 1; a.p0 = p0; a.pl = a.ph = -1; a.v = -1; a.patch_mode = 0;
+  a.heads = any ? masks.data() : nullptr;
+  if (any) {
+    M->pi_l = M->pi_h = -2;
+    a.kind = PI_CORRUPT; PCHK(run_pass(M, a, nullptr));
+    a.kind = PI_REF; PCHK(run_pass(M, a, nullptr));
+  }
+  uint8_t& flag = M->removed[edge_index(M, u, v)];
+  const uint8_t was = flag;
+  int rc = PAHQ_OK;
+  a.kind = STATE;
+  for (int step = 0; step < 2 && rc == PAHQ_OK; step++) {
+    if (step == 1) flag = 1;
+    make_plan(M, p0, g.out(), M->plan);
+    if (M->plan.n_slots > M->pool_tiles) { rc = PAHQ_ENOMEM; break; }
+    rc = run_pass(M, a, &M->plan);
+    if (rc == PAHQ_OK && hipMemcpyAsync(M->kl_host + step, M->kl_dev, sizeof(double), hipMemcpyDeviceToHost, M->stream) != hipSuccess) rc = PAHQ_EHIP;
+    if (rc == PAHQ_OK && hipStreamSynchronize(M->stream) != hipSuccess) rc = PAHQ_EHIP;
+  }
+  flag = was;
+  if (rc != PAHQ_OK) return rc;
+  *kl_cur = M->kl_host[0]; *kl_new = M->kl_host[1];
+  M->counters[0] += 1; M->counters[1] += 1;
+  return PAHQ_OK;
+}
+}  // namespace
+
+int pahq_eval_edges_sender_policy(pahq_model* M, int32_t receiver, const int32_t* sender_ids, int32_t n, float* kl_new_out,
+                                  float* kl_cur_out) {
+  if (!M || n < 0 || (n > 0 && (!sender_ids || !kl_new_out || !kl_cur_out))) return PAHQ_EINVAL;
+  if (receiver < 0 || receiver >= M->g.Nr) return PAHQ_EINVAL;
+  if (!M->has_cache) return PAHQ_ESTATE;
+  const int n_up = M->g.n_upstream(receiver);
+  for (int i = 0; i < n; i++) if (sender_ids[i] < 0 || sender_ids[i] >= n_up) return PAHQ_EINVAL;
+  for (int i = 0; i < n; i++) {
+    double c, k;
+    PCHK(eval_pair_sender(M, receiver, sender_ids[i], &c, &k));
+    kl_cur_out[i] = (float)c; kl_new_out[i] = (float)k;
+  }
+  return PAHQ_OK;
+}
+
+int pahq_acdc_sweep_sender_policy(pahq_model* M, float tau, const int32_t* receivers, int32_t n_receivers, uint8_t* kept,
+                                  int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap) {
+  if (!M || n_receivers < 0 || (n_receivers > 0 && !receivers) || trace_cap < 0 || (trace_cap > 0 && !trace) || tau != tau) return PAHQ_EINVAL;
+  if (!M->has_cache) return PAHQ_ESTATE;
+  const GraphDims& g = M->g;
+  std::vector<int> order;
+  if (n_receivers == 0) { for (int r = g.Nr - 1; r >= 0; r--) order.push_back(r); }
+  else {
+    for (int i = 0; i < n_receivers; i++) { if (receivers[i] < 0 || receivers[i] >= g.Nr) return PAHQ_EINVAL; order.push_back(receivers[i]); }
+    std::sort(order.begin(), order.end(), [](int x, int y) { return x > y; });
+    order.erase(std::unique(order.begin(), order.end()), order.end());
+  }
+  const std::vector<uint8_t> before = M->removed;
+  std::fill(M->removed.begin(), M->removed.end(), 0);
+  int64_t evals = 0;
+  for (int v : order) {
+    const int n_up = g.n_upstream(v);
+    uint8_t* row = M->removed.data() + M->edge_off[v];
+    if (!node_is_live(M, v)) { memset(row, 1, n_up); continue; }
+    for (int u = n_up - 1; u >= 0; u--) {
+      double kc, kn;
+      int rc = eval_pair_sender(M, v, u, &kc, &kn);
+      if (rc != PAHQ_OK) { M->removed = before; return rc; }
+      const bool rm = (kn - kc) < (double)tau;
+      if (evals < trace_cap) {
+        pahq_trace_rec& t = trace[evals];
+        t.receiver = v; t.sender = u; t.kl_new = (float)kn; t.kl_cur = (float)kc; t.removed = rm ? 1 : 0;
+      }
+      evals++;
+      if (rm) row[u] = 1;
+    }
+  }
+  if (kept) for (size_t i = 0; i < M->removed.size(); i++) kept[i] = M->removed[i] ? 0 : 1;
+  if (n_evals) *n_evals = evals;
+  return PAHQ_OK;
+}
+
 int pahq_set_removed(pahq_model* M, const uint8_t* removed) {
   if (!M || !removed) return PAHQ_EINVAL;
   for (size_t i = 0; i < M->removed.size(); i++) if (removed[i] > 1) return PAHQ_EINVAL;

@@ -272,3 +272,66 @@ def test_threshold_grid_on_one_set_of_caches():
                     assert len(o_tr) == n_evals[i] and (kept[i] == (~g.removed_to_flat(o_removed)).astype(np.uint8)).all(), i
         finally:
             gm.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1_hi", "mid_hi"])
+def test_sender_side_precision_policy(name):
+    """Eq. P_t as printed (fp32 for the source head of the evaluated edge) on the device against the oracle's
+    pair_sender_policy / sweep_sender_policy: per-candidate (current, new) pairs under sweep-like states, and a
+    whole sweep; and the two policies do give different numbers for the same edge."""
+    import paper_2510_23264_amd as P
+    shape, w, clean, corrupt = workloads.make(name)
+    B, S = clean.shape
+    om = SpreadModel(shape, w)
+    g = om.g
+    gm = P.Model(shape, w, B, S, precision=P.PAHQ, max_batch_edges=8)
+    try:
+        gm.clean_cache(clean, corrupt)
+        got, want, sigma = [], [], []
+        for r, frac in ((g.OUT, 0.0), (g.n_receivers - 3, 0.5), (g.n_receivers // 2, 0.3)):
+            R = rnd_removed(g, frac, 50 + r, r) if frac else g.empty_removed()
+            gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
+            senders = list(range(g.n_upstream(r)))[:: max(1, g.n_upstream(r) // 6)]
+            new, cur = gm.eval_edges_sender_policy(r, senders)
+            base, devs = [], []
+            for seed in range(5):                                  # the oracle's pairs and their binary32 spread
+                om.set_spread(0.0 if seed == 0 else 2.0 ** -22, 1000 + seed)
+                oa = Acdc(om, clean, corrupt, MODE_PAHQ)
+                vals = [oa.pair_sender_policy(r, u, R) for u in senders]
+                if seed == 0:
+                    base = vals
+                else:
+                    devs.append([(c - b[0], n - b[1]) for (c, n), b in zip(vals, base)])
+            om.set_spread(0.0, 0)
+            sg = np.sqrt(np.mean(np.square(np.array(devs)), axis=0))          # [sender][cur|new]
+            for k in range(len(senders)):
+                got += [cur[k], new[k]]; want += [base[k][0], base[k][1]]; sigma += [sg[k][0], sg[k][1]]
+        check_kl_cases(got, want, sigma, what=name + " sender policy")
+        gm.set_removed(np.zeros(g.n_edges(), np.uint8))
+        # the other policy gives other numbers for an edge out of a head
+        r = g.headin(shape.n_layers - 1, 0, 1)
+        u = g.head(0, 1)
+        assert gm.eval_edges_sender_policy(r, [u])[0][0] != gm.eval_edges(r, [u])[0]
+        # a sweep under it, decision by decision (a differing decision only inside the bound, as elsewhere)
+        oa = Acdc(om, clean, corrupt, MODE_PAHQ)
+        recv = [g.OUT, g.n_receivers - 2, g.n_receivers - 5]
+        tau = 0.03
+        kept, n_evals, tr = gm.acdc_sweep(tau, receivers=recv, sender_policy=True)
+        o_removed, o_tr = oa.sweep_sender_policy(tau, receivers=recv)
+        equal = True
+        for i in range(min(n_evals, len(o_tr))):
+            ov, ou, okn, okc, orm = o_tr[i]
+            t = tr[i]
+            assert (t["receiver"], t["sender"]) == (ov, ou)
+            if bool(t["removed"]) != orm:
+                from tolerance import bound, pooled
+                assert abs((okn - okc) - tau) <= bound(max(abs(okn), abs(okc)), pooled(sigma)), (name, i)
+                equal = False
+                break
+        if equal:
+            assert n_evals == len(o_tr)
+            rows = np.concatenate([np.arange(g.edge_offsets()[r], g.edge_offsets()[r + 1]) for r in recv])
+            assert (kept[rows] == (~g.removed_to_flat(o_removed))[rows].astype(np.uint8)).all()
+        print(name, "sender-policy sweep:", "equal" if equal else "diverged inside the bound", "evals", n_evals)
+    finally:
+        gm.close()

@@ -426,3 +426,32 @@ def test_logit_difference_metric():
     # the sweep runs on it with the same rule
     removed, trace = a.sweep(1e-3)
     assert all(rm == ((kn - kc) < 1e-3) for _, _, kn, kc, rm in trace)
+
+
+def test_sender_side_precision_policy():
+    """Eq. P_t as printed (fp32 for the source of the evaluated edge): the cached evaluation from the sender's layer
+    equals three-plus-one full forwards under that set; a clean patch scores 0; with everything in fp32 the two
+    policies are the same procedure; under mixed precision they are different numbers."""
+    m, w, clean, corrupt = tiny(TINY_GELU, B=3)
+    g = m.g
+    a = Acdc(m, clean, corrupt, MODE_PAHQ)
+    rng = np.random.default_rng(4)
+    v = g.headin(1, 1, 2)
+    R = g.empty_removed(); R[v:, :] = g.flat_to_removed(rng.random(g.n_edges()) < 0.4)[v:, :]
+    for u in (g.head(0, 1), g.mlp(0), 0):
+        cur, new = a.pair_sender_policy(v, u, R)
+        pi = a.pi_of_sender(u)
+        assert pi == (frozenset([(0, 1)]) if u == g.head(0, 1) else frozenset())
+        C, _ = m.forward(corrupt, pi)
+        _, ref = m.forward(clean, pi)
+        _, lc = m.forward(clean, pi, removed=R, C=C)
+        R2 = R.copy(); R2[v, u] = True
+        _, ln = m.forward(clean, pi, removed=R2, C=C)
+        assert abs(cur - a.score(ref, lc)) < 1e-13 and abs(new - a.score(ref, ln)) < 1e-13
+    assert Acdc(m, clean, clean, MODE_PAHQ).pair_sender_policy(v, g.head(0, 0), R) == (0.0, 0.0)
+    a32 = Acdc(m, clean, corrupt, MODE_ALL_FP32)
+    r1, t1 = a32.sweep(1e-3)
+    r2, t2 = a32.sweep_sender_policy(1e-3)
+    assert (r1 == r2).all() and all(abs(x[2] - y[2]) < 1e-12 and x[4] == y[4] for x, y in zip(t1, t2))
+    cur_s, new_s = a.pair_sender_policy(v, g.head(0, 1), g.empty_removed())
+    assert cur_s == 0.0 and new_s > 0 and new_s != a.kl_edge(v, g.head(0, 1))
