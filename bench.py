@@ -16,8 +16,9 @@ roofline blocks, because the empty removed set is the best case of this design
                   the edges removed: every receiver gathers its own sum of
                   sender tiles (what a sweep looks like once it has removed
                   most of the graph);
-  sweep           pahq_acdc_sweep at a threshold that leaves a circuit (1e-4)
-                  and at the thresholds the config names (on random-initialised
+  sweep           pahq_acdc_sweep at thresholds that leave a circuit (1e-4: about
+                  80 edges after 1 700 decisions; 3e-5: about 800 edges, every one
+                  of the 32 491 edges decided) and at the thresholds the config names (on random-initialised
                   weights each of those exceeds every increment: 157 evaluations
                   and an empty circuit).
 
@@ -313,7 +314,7 @@ def main():
 
     if do("sweep") and not args.no_sweep:
         sweeps = {}
-        taus = ((1e-4,) if args.config == "cfg3" else ()) + tuple(spec["taus"])
+        taus = ((1e-4, 3e-5) if args.config == "cfg3" else ()) + tuple(spec["taus"])
         for tau in taus:
             gm.clean_cache(clean, corrupt)
             profiled = tau == taus[0]
