@@ -468,7 +468,10 @@ int pahq_eval_edges(pahq_model* M, int32_t receiver, const int32_t* sender_ids, 
   for (int pos = 0; pos < n;) {
     const int chunk = std::min(M->ncap, n - pos);
     for (int off = 0; off < chunk;) {
-      int nb = std::min(ctx.n_eff, chunk - off);
+      // batches of equal size: 131 candidates run as 66 + 65, not as 128 + 3 (a batch of three pays a full
+      // batch's launches and leaves most compute units idle)
+      const int left = chunk - off, parts = (left + ctx.n_eff - 1) / ctx.n_eff;
+      int nb = (left + parts - 1) / parts;
       // an edge that is already removed adds nothing: such a candidate patches with the all-zero tile
       for (int i = 0; i < nb; i++) {
         int u = sender_ids[pos + off + i];
