@@ -159,13 +159,7 @@ int quantise_class(pahq_model* M, const float* w, int n_slices, int K, int N, ui
 
 inline int64_t edge_index(const pahq_model* M, int s, int r) { return M->edge_off[r] + s; }
 
-bool node_is_live(const pahq_model* M, int v) {
-  int s = M->g.node_of_receiver(v);
-  if (s < 0) return true;
-  for (int r = 0; r < M->g.Nr; r++)
-    if (s < M->g.n_upstream(r) && !M->removed[edge_index(M, s, r)]) return true;
-  return false;
-}
+bool node_is_live(const pahq_model* M, int v) { return node_is_live(M->g, M->removed.data(), M->edge_off.data(), v); }
 
 // copies a small host table to the device through the descriptor ring
 int upload_table(pahq_model* M, const void* src, size_t bytes, void** dev_out) {
@@ -537,15 +531,9 @@ static int sweep_impl(pahq_model* M, float tau, const int32_t* receivers, int32_
   if (!M->has_cache) return PAHQ_ESTATE;
   const GraphDims& g = M->g;
   std::vector<int> order;
-  if (n_receivers == 0) { for (int r = g.Nr - 1; r >= 0; r--) order.push_back(r); }
-  else {
-    for (int i = 0; i < n_receivers; i++) { if (receivers[i] < 0 || receivers[i] >= g.Nr) return PAHQ_EINVAL; order.push_back(receivers[i]); }
-    std::sort(order.begin(), order.end(), [](int x, int y) { return x > y; });
-    order.erase(std::unique(order.begin(), order.end()), order.end());
-  }
+  if (!sweep_order(g, receivers, n_receivers, order)) return PAHQ_EINVAL;
   std::fill(M->removed.begin(), M->removed.end(), 0);
   int64_t evals = 0;
-  const double tau_d = (double)tau;
   for (int v : order) {
     const int n_up = g.n_upstream(v);
     uint8_t* row = M->removed.data() + M->edge_off[v];
@@ -554,41 +542,22 @@ static int sweep_impl(pahq_model* M, float tau, const int32_t* receivers, int32_
     PCHK(setup_receiver(M, v, ctx));
     double kl_cur;
     PCHK(eval_state(M, ctx, &kl_cur));
-    int pos = 0;                      // candidates are senders n_up-1-pos, descending
-    int bs = ctx.n_eff;
-    int recent_rm = 1, recent_n = 1;  // decision history of this receiver (start optimistic: most edges go)
-    while (pos < n_up) {
-      int nb = std::min(std::min(bs, ctx.n_eff), n_up - pos);
-      // cumulative candidates pay off when removals dominate, independent ones when keeps do
-      int mode = (2 * recent_rm >= recent_n) ? 2 : 1;
-      for (int i = 0; i < nb; i++) M->send_host[i] = n_up - 1 - (pos + i);
-      PCHK(eval_batch(M, ctx, nb, mode));
-      int used = 0, n_rm = 0;
-      for (int i = 0; i < nb; i++) {
-        double kn = M->kl_host[i];
-        bool rm = (kn - kl_cur) < tau_d;
-        int u = M->send_host[i];
-        if (evals < trace_cap) {
-          pahq_trace_rec& t = trace[evals];
-          t.receiver = v; t.sender = u; t.kl_new = (float)kn; t.kl_cur = (float)kl_cur; t.removed = rm ? 1 : 0;
-        }
-        evals++; used++; recent_n++;
-        if (rm) { row[u] = 1; kl_cur = kn; n_rm++; recent_rm++; }
-        // cumulative: later candidates assumed this edge gone -> stop at the first kept edge;
-        // independent: later candidates assumed this edge present -> stop at the first removed edge
-        if ((mode == 2 && !rm) || (mode == 1 && rm)) break;
-      }
-      if (n_rm > 0) {
-        // removed edges of this batch: in cumulative mode the first n_rm candidates, in independent mode the last used
-        if (mode == 2) {
-          HIPCHK(launch_xv_advance(M->xv, M->delta, M->tile, M->send_dev, n_rm, M->tile, M->stream));
-        } else {
-          HIPCHK(launch_xv_advance(M->xv, M->delta, M->tile, M->send_dev + (used - 1), 1, M->tile, M->stream));
-        }
-      }
-      pos += used;
-      bs = (used == nb) ? std::min(ctx.n_eff, std::max(2 * bs, 2)) : std::max(1, std::min(ctx.n_eff, 2 * used));
-    }
+    // the accept scan (controller.h) drives the device batches; send_host / kl_host are its work arrays
+    PCHK(scan_receiver(
+        n_up, ctx.n_eff, (double)tau, kl_cur, row, M->send_host, M->kl_host,
+        [&](const int*, int nb, int mode, double*) -> int { return eval_batch(M, ctx, nb, mode); },
+        [&](int first, int count) -> int {
+          // same subtraction order as the patch kernel used for these candidates
+          HIPCHK(launch_xv_advance(M->xv, M->delta, M->tile, M->send_dev + first, count, M->tile, M->stream));
+          return PAHQ_OK;
+        },
+        [&](int u, double kn, double kc, bool rm) {
+          if (evals < trace_cap) {
+            pahq_trace_rec& t = trace[evals];
+            t.receiver = v; t.sender = u; t.kl_new = (float)kn; t.kl_cur = (float)kc; t.removed = rm ? 1 : 0;
+          }
+          evals++;
+        }));
   }
   if (kept) for (size_t i = 0; i < M->removed.size(); i++) kept[i] = M->removed[i] ? 0 : 1;
   if (n_evals) *n_evals = evals;
@@ -723,12 +692,7 @@ int pahq_acdc_sweep_sender_policy(pahq_model* M, float tau, const int32_t* recei
   if (!M->has_cache) return PAHQ_ESTATE;
   const GraphDims& g = M->g;
   std::vector<int> order;
-  if (n_receivers == 0) { for (int r = g.Nr - 1; r >= 0; r--) order.push_back(r); }
-  else {
-    for (int i = 0; i < n_receivers; i++) { if (receivers[i] < 0 || receivers[i] >= g.Nr) return PAHQ_EINVAL; order.push_back(receivers[i]); }
-    std::sort(order.begin(), order.end(), [](int x, int y) { return x > y; });
-    order.erase(std::unique(order.begin(), order.end()), order.end());
-  }
+  if (!sweep_order(g, receivers, n_receivers, order)) return PAHQ_EINVAL;
   const std::vector<uint8_t> before = M->removed;
   std::fill(M->removed.begin(), M->removed.end(), 0);
   int64_t evals = 0;

@@ -5,27 +5,12 @@
 #include <vector>
 #include "../../include/pahq.h"
 #include "graph.h"
+#include "controller.h"
 #include "kernels.h"
 
 namespace pahq {
 
 enum PassKind { BASE_CLEAN = 0, BASE_CORRUPT, PI_CORRUPT, PI_REF, STATE, CAND, PREFIX };
-
-// How one recomputed receiver forms its input from the residual streams.
-struct RecvSpec {
-  int form;                    // 0 dense (running stream only), 1 removed form, 2 kept form
-  std::vector<int> senders;    // removed senders (form 1) or kept senders (form 2), ascending
-};
-
-struct RecvPlan {
-  int p0 = -1;
-  std::vector<RecvSpec> spec;  // indexed by receiver id (only receivers at positions >= p0 are filled)
-  std::vector<int> slot_of;    // per sender: slot index or -1
-  std::vector<char> shared;    // per sender: its slot is the same for every instance (see split_first)
-  int n_slots = 0;             // per-instance slots
-  int n_shared = 0;            // instance-independent slots
-  bool split_first = false;    // candidates recompute only the investigated head in their first layer
-};
 
 struct PassArgs {
   PassKind kind;

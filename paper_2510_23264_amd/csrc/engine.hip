@@ -24,42 +24,7 @@ namespace pahq {
 static inline int canon(const pahq_model* M, int p) { return canon_pos(M, p); }
 
 void make_plan(pahq_model* M, int p0, int v, RecvPlan& out) {
-  const GraphDims& g = M->g;
-  out.p0 = p0;
-  out.spec.assign(g.Nr, RecvSpec());
-  out.slot_of.assign(g.Ns, -1);
-  out.shared.assign(g.Ns, 0);
-  out.n_slots = 0;
-  out.n_shared = 0;
-  // With an fp32 investigated head, a candidate into a head input changes, inside its own layer,
-  // only that head: the other heads of the layer are the same for every candidate.
-  int vk, vl, vh, vc;
-  g.receiver_info(v, vk, vl, vh, vc);
-  out.split_first = (vk == 0 && M->cfg.precision == PAHQ_PAHQ);
-  const int v_node = g.node_of_receiver(v);
-  const int nstat = g.n_static(p0);
-  for (int w = 0; w < g.Nr; w++) {
-    if (g.pos_of_receiver(w) < p0) continue;
-    const int n_up = g.n_upstream(w);
-    const uint8_t* row = M->removed.data() + M->edge_off[w];
-    int n_rem = 0;
-    for (int s = 0; s < n_up; s++) n_rem += row[s];
-    RecvSpec& sp = out.spec[w];
-    if (n_rem == 0) { sp.form = 0; continue; }
-    if (n_rem <= n_up - n_rem) {
-      sp.form = 1;
-      for (int s = 0; s < n_up; s++) if (row[s]) sp.senders.push_back(s);
-    } else {
-      sp.form = 2;
-      for (int s = 0; s < n_up; s++) if (!row[s]) sp.senders.push_back(s);
-    }
-    for (int s : sp.senders)
-      if (s >= nstat && out.slot_of[s] < 0) {
-        bool sh = out.split_first && s != v_node && g.pos_after_sender(s) == p0 + 1;   // another head of v's layer
-        out.shared[s] = sh ? 1 : 0;
-        out.slot_of[s] = sh ? out.n_shared++ : out.n_slots++;
-      }
-  }
+  plan_receivers(M->g, M->removed.data(), M->edge_off.data(), M->cfg.precision == PAHQ_PAHQ, p0, v, out);
 }
 
 namespace {

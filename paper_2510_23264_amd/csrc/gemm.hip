@@ -26,6 +26,7 @@
 //
 // gemm_f32: plain fp32 C = A * W (+ bias) with V_MFMA_F32_16X16X4_F32 (true
 //   fp32 multiply-accumulate) for the investigated head.
+#include <atomic>
 #include "kernels.h"
 #include "device_util.h"
 #include "mma_util.h"
@@ -668,12 +669,16 @@ hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int ma
     const bool wide = max_N > 64;
     if (wide && max_M >= 8192 && max_N >= 128) {
       // one 512-thread workgroup per compute unit, three 48 KB stages + 2 KB of scales
-      static bool attr_set = false;
       const int lds_bytes = 3 * 384 * 128 + 2048;
-      if (!attr_set) {
+      // the attribute belongs to the kernel's code object on one device: set once per device (atomically, so that
+      // models on several streams or host threads may launch concurrently)
+      static std::atomic<bool> attr_set[64];
+      int dev = 0;
+      if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+      if (!attr_set[dev].load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)gemm_p_k<0>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set[dev].store(true, std::memory_order_release);
       }
       int tiles = ((max_M + 255) / 256) * ((max_N + 127) / 128);
       int gx = (tiles + 7) / 8 * 8;

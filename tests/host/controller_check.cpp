@@ -1,0 +1,179 @@
+// CPU check of the sweep's host logic (csrc/controller.h, csrc/graph.h), built with the address and
+// undefined-behaviour sanitizers by tests/test_host_controller.py.  No GPU code is involved: the device
+// batches are played by a synthetic metric that is a fixed function of the removed set, so the decisions
+// the accept scan reaches through speculative batches can be compared, one by one, with the sequential
+// procedure of the paper's Appendix "Preliminaries" (remove an edge iff it raises the metric by less
+// than tau, edges in descending order, each judged with all earlier decisions applied).
+#include <stdio.h>
+#include <stdlib.h>
+#include <stdint.h>
+#include <vector>
+#include <set>
+#include "controller.h"
+
+using namespace pahq;
+
+static int failures = 0;
+#define CHECK(cond, ...) do { if (!(cond)) { failures++; printf("FAIL %s:%d: ", __FILE__, __LINE__); printf(__VA_ARGS__); printf("\n"); if (failures > 20) exit(1); } } while (0)
+
+static uint64_t mix(uint64_t x) { x += 0x9E3779B97F4A7C15ull; x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull; x = (x ^ (x >> 27)) * 0x94D049BB133111EBull; return x ^ (x >> 31); }
+static double unit(uint64_t x) { return (double)(mix(x) >> 11) * (1.0 / 9007199254740992.0); }
+
+// A metric that depends on the whole removed set (not a sum over edges): every edge has a weight, most of
+// them tiny, and a set-dependent term couples them, so that cumulative and independent candidates differ.
+struct Metric {
+  uint64_t seed; int n;
+  double weight(int s) const { double u = unit(seed * 1315423911ull + s); return u < 0.6 ? 1e-6 * u : 1e-3 * u; }
+  double operator()(const std::vector<uint8_t>& R) const {
+    double f = 0.01; uint64_t h = seed;
+    for (int s = 0; s < n; s++) if (R[s]) { f += weight(s); h = mix(h ^ (uint64_t)(s + 1)); }
+    return f + 2e-4 * unit(h);
+  }
+};
+
+struct Decision { int u; double kn, kc; bool rm; };
+static bool same(const Decision& a, const Decision& b) { return a.u == b.u && a.kn == b.kn && a.kc == b.kc && a.rm == b.rm; }
+
+static void sequential(const Metric& F, double tau, std::vector<uint8_t>& R, std::vector<Decision>& out) {
+  double cur = F(R);
+  for (int u = F.n - 1; u >= 0; u--) {
+    R[u] = 1; double kn = F(R);
+    bool rm = (kn - cur) < tau;
+    out.push_back({u, kn, cur, rm});
+    if (rm) cur = kn; else R[u] = 0;
+  }
+}
+
+static void check_scan(uint64_t seed, int n_up, int max_batch, double tau, int fail_at) {
+  Metric F{seed, n_up};
+  std::vector<uint8_t> Rseq(n_up, 0), row(n_up, 0), Rdev(n_up, 0);
+  std::vector<Decision> want, got;
+  sequential(F, tau, Rseq, want);
+  std::vector<int> senders(std::max(max_batch, 1));
+  std::vector<double> kl(std::max(max_batch, 1));
+  std::vector<int> last; int calls = 0, max_nb = 0;
+  double kl_cur = F(Rdev);
+  int rc = scan_receiver(
+      n_up, max_batch, tau, kl_cur, row.data(), senders.data(), kl.data(),
+      [&](const int* s, int nb, int mode, double* out) -> int {
+        if (calls++ == fail_at) return -4;
+        CHECK(nb >= 1 && nb <= max_batch, "batch of %d with a limit of %d", nb, max_batch);
+        CHECK(Rdev == row, "the evaluator's input lags behind the decisions (seed %llu)", (unsigned long long)seed);
+        max_nb = std::max(max_nb, nb);
+        last.assign(s, s + nb);
+        std::vector<uint8_t> R = Rdev;
+        for (int i = 0; i < nb; i++) {
+          CHECK(s[i] >= 0 && s[i] < n_up && !Rdev[s[i]], "candidate %d out of range or already removed", s[i]);
+          if (mode == 2) { R[s[i]] = 1; out[i] = F(R); }
+          else { std::vector<uint8_t> Q = Rdev; Q[s[i]] = 1; out[i] = F(Q); }
+        }
+        return 0;
+      },
+      [&](int first, int count) -> int {
+        CHECK(first >= 0 && count >= 1 && first + count <= (int)last.size(), "advance(%d, %d) outside the last batch of %zu", first, count, last.size());
+        for (int i = first; i < first + count && i < (int)last.size(); i++) Rdev[last[i]] = 1;
+        return 0;
+      },
+      [&](int u, double kn, double kc, bool rm) { got.push_back({u, kn, kc, rm}); });
+  if (fail_at >= 0 && fail_at < calls) {
+    CHECK(rc == -4, "an evaluator error must come back (got %d)", rc);
+    CHECK(got.size() <= want.size(), "more decisions than edges");
+    for (size_t i = 0; i < got.size(); i++) CHECK(same(got[i], want[i]), "decision %zu before the error differs", i);
+    return;
+  }
+  CHECK(rc == 0, "scan returned %d", rc);
+  CHECK(got.size() == want.size(), "seed %llu n_up %d batch %d: %zu decisions, want %zu", (unsigned long long)seed, n_up, max_batch, got.size(), want.size());
+  for (size_t i = 0; i < got.size() && i < want.size(); i++)
+    if (!same(got[i], want[i])) { CHECK(false, "seed %llu n_up %d batch %d tau %g: decision %zu differs (sender %d/%d removed %d/%d)", (unsigned long long)seed, n_up, max_batch, tau, i, got[i].u, want[i].u, got[i].rm, want[i].rm); break; }
+  CHECK(row == Rseq, "removed row differs from the sequential procedure's");
+  CHECK(Rdev == row, "the evaluator's input does not hold the final decisions");
+  CHECK(kl_cur == F(Rseq), "kl_cur is not the metric of the final state");
+  if (n_up > 0) CHECK(calls <= n_up, "%d device batches for %d edges", calls, n_up);
+}
+
+static void check_graph_and_plan(uint64_t seed, int L, int H, bool mlp) {
+  GraphDims g(L, H, mlp);
+  // ids: receivers enumerate (layer, head, channel) / MLP inputs / the output once each, in stream order
+  std::set<int> seen; int prev_pos = -1;
+  for (int r = 0; r < g.Nr; r++) {
+    int k, l, h, c; g.receiver_info(r, k, l, h, c);
+    int id = k == 0 ? g.headin(l, h, c) : (k == 1 ? g.mlpin(l) : g.out());
+    CHECK(id == r, "receiver %d does not map back to itself", r);
+    CHECK(g.pos_of_receiver(r) >= prev_pos, "receiver ids do not follow the stream"); prev_pos = g.pos_of_receiver(r);
+    int n = 0; for (int s = 0; s < g.Ns; s++) n += g.pos_after_sender(s) <= g.pos_of_receiver(r);
+    CHECK(n == g.n_upstream(r), "receiver %d: %d senders upstream by position, n_upstream says %d", r, n, g.n_upstream(r));
+    seen.insert(id);
+  }
+  CHECK((int)seen.size() == g.Nr, "receiver ids not unique");
+  std::vector<int64_t> off(g.Nr + 1, 0);
+  for (int r = 0; r < g.Nr; r++) off[r + 1] = off[r] + g.n_upstream(r);
+  // random removed sets restricted to receivers at or after a random position; plans must describe them exactly
+  for (int rep = 0; rep < 8; rep++) {
+    std::vector<uint8_t> removed(off[g.Nr], 0);
+    const int v = (int)(mix(seed + rep) % g.Nr), p0 = g.pos_of_receiver(v);
+    const double dens = unit(seed * 7 + rep);
+    for (int r = 0; r < g.Nr; r++) if (g.pos_of_receiver(r) >= p0)
+      for (int s = 0; s < g.n_upstream(r); s++) removed[off[r] + s] = unit(seed * 31 + rep * 1000003ull + off[r] + s) < dens;
+    for (int pahq = 0; pahq < 2; pahq++) {
+      RecvPlan plan; plan_receivers(g, removed.data(), off.data(), pahq, p0, v, plan);
+      const int nstat = g.n_static(p0);
+      std::vector<char> needed(g.Ns, 0);
+      for (int r = 0; r < g.Nr; r++) {
+        if (g.pos_of_receiver(r) < p0) continue;
+        const RecvSpec& sp = plan.spec[r];
+        std::vector<uint8_t> row(g.n_upstream(r), sp.form == 2 ? 1 : 0);
+        for (int s : sp.senders) { CHECK(s >= 0 && s < g.n_upstream(r), "sender %d not upstream of %d", s, r); if (s >= 0 && s < g.n_upstream(r)) row[s] = sp.form == 2 ? 0 : 1; if (s >= nstat) needed[s] = 1; }
+        if (sp.form == 0) CHECK(sp.senders.empty(), "dense form with terms");
+        for (int s = 0; s < g.n_upstream(r); s++) CHECK(row[s] == removed[off[r] + s], "plan of receiver %d misdescribes edge from %d", r, s);
+        int n_rem = 0; for (int s = 0; s < g.n_upstream(r); s++) n_rem += removed[off[r] + s];
+        CHECK((int)sp.senders.size() == std::min(n_rem, g.n_upstream(r) - n_rem), "receiver %d does not take the cheaper form", r);
+      }
+      std::set<int> own, shared;
+      int vk, vl, vh, vc; g.receiver_info(v, vk, vl, vh, vc);
+      for (int s = 0; s < g.Ns; s++) {
+        CHECK((plan.slot_of[s] >= 0) == (bool)needed[s], "sender %d: slot %d, needed %d", s, plan.slot_of[s], (int)needed[s]);
+        if (plan.slot_of[s] < 0) continue;
+        if (plan.shared[s]) {
+          CHECK(pahq && vk == 0 && s != g.node_of_receiver(v) && s >= g.head(vl, 0) && s < g.head(vl, 0) + H, "sender %d shared without being another head of the receiver's layer", s);
+          shared.insert(plan.slot_of[s]);
+        } else {
+          CHECK(!(pahq && vk == 0 && s != g.node_of_receiver(v) && s >= g.head(vl, 0) && s < g.head(vl, 0) + H), "another head of the receiver's layer has a per-candidate slot");
+          own.insert(plan.slot_of[s]);
+        }
+      }
+      CHECK((int)own.size() == plan.n_slots && (int)shared.size() == plan.n_shared, "slot numbers not a bijection");
+      if (!own.empty()) CHECK(*own.rbegin() == plan.n_slots - 1, "slot numbers not dense");
+    }
+    // liveness: a node is live iff one of its outgoing edges is kept
+    for (int r = 0; r < g.Nr; r++) {
+      const int s = g.node_of_receiver(r);
+      bool live = s < 0;
+      for (int w = 0; w < g.Nr && !live; w++) if (g.pos_after_sender(s) <= g.pos_of_receiver(w) && !removed[off[w] + s]) live = true;
+      CHECK(live == node_is_live(g, removed.data(), off.data(), r), "liveness of receiver %d", r);
+    }
+  }
+  // order of the sweep
+  std::vector<int> order;
+  CHECK(sweep_order(g, nullptr, 0, order) && (int)order.size() == g.Nr && order.front() == g.Nr - 1 && order.back() == 0, "full order");
+  int32_t some[5] = {0, g.Nr - 1, 0, g.Nr / 2, g.Nr - 1};
+  CHECK(sweep_order(g, some, 5, order), "subset order");
+  for (size_t i = 1; i < order.size(); i++) CHECK(order[i] < order[i - 1], "subset order not strictly descending");
+  int32_t bad[2] = {0, g.Nr};
+  CHECK(!sweep_order(g, bad, 2, order), "an id out of range must be refused");
+  int32_t neg[1] = {-1};
+  CHECK(!sweep_order(g, neg, 1, order), "a negative id must be refused");
+}
+
+int main() {
+  int cases = 0;
+  const double taus[] = {-1.0, 0.0, 5e-7, 2e-5, 1.5e-4, 6e-4, 1.0};
+  const int sizes[] = {0, 1, 2, 3, 7, 16, 33, 100, 157, 301};
+  const int batches[] = {1, 2, 3, 8, 64, 128, 512};
+  for (int n_up : sizes) for (int mb : batches) for (double tau : taus)
+    for (uint64_t seed = 1; seed <= 6; seed++) { check_scan(seed * 1000 + n_up, n_up, mb, tau, -1); cases++; }
+  for (int fail_at = 0; fail_at < 6; fail_at++) for (uint64_t seed = 1; seed <= 4; seed++) { check_scan(seed, 100, 8, 2e-5, fail_at); cases++; }
+  const int shapes[][3] = {{1, 1, 0}, {1, 1, 1}, {2, 2, 0}, {2, 3, 1}, {3, 4, 1}, {4, 2, 1}, {12, 12, 1}};
+  for (auto& sh : shapes) for (uint64_t seed = 1; seed <= 3; seed++) { check_graph_and_plan(seed * 77 + sh[0], sh[0], sh[1], sh[2]); cases++; }
+  printf("%d cases, %d failures\n", cases, failures);
+  return failures ? 1 : 0;
+}
