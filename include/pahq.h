@@ -237,6 +237,15 @@ int pahq_acdc_sweep_sender_policy(pahq_model*, float tau, const int32_t* receive
  * the state of the head investigated last is dropped (the next evaluation rebuilds it). */
 int pahq_eval_circuit(pahq_model*, const uint8_t* kept, const uint8_t* f32_heads, float* kl_out, float* logits_out);
 
+/* Dead nodes.  Once every edge out of a node is removed (or leads only to such nodes), each of its receivers reads
+ * the corrupted run's cached activation from it whatever the node computes (Appendix "Preliminaries": a removed
+ * edge carries the corrupted activation), and ACDC drops its incoming edges unevaluated (Appendix "Integration with
+ * ACDC").  With on = 1 (the default) passes over a pruned graph -- current state, candidates, circuit evaluation,
+ * sweeps -- do not compute such nodes: the stream takes their cached corrupted outputs in their place.  In exact
+ * arithmetic nothing changes; in binary32 the order of a few additions does.  on = 0 computes every node (for
+ * comparison and timing).  Takes effect from the next evaluation. */
+int pahq_set_dead_node_skipping(pahq_model*, int32_t on);
+
 /* Removed set, canonical edge order, one byte per edge (1 = removed, 0 = kept).  Any set is stored; which
  * sets an evaluation accepts is said at pahq_eval_edges. */
 int pahq_set_removed(pahq_model*, const uint8_t* removed);

@@ -85,6 +85,7 @@ def lib():
             "pahq_eval_circuit": [C.c_void_p, u8p, u8p, f32p, f32p],
             "pahq_set_metric": [C.c_void_p, C.c_int32, i32p, i32p],
             "pahq_set_removed": [C.c_void_p, u8p], "pahq_get_removed": [C.c_void_p, u8p],
+            "pahq_set_dead_node_skipping": [C.c_void_p, C.c_int32],
             "pahq_get_weight_q": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, u8p, f32p],
             "pahq_quantize_rows": [C.c_void_p, f32p, C.c_int32, C.c_int32, u8p, f32p],
             "pahq_quantize_rows_site": [C.c_void_p, C.c_int32, f32p, C.c_int32, C.c_int32, u8p, f32p],
@@ -303,6 +304,9 @@ class Model:
         out = C.c_float()
         _chk(lib().pahq_eval_circuit(self.h, kp, hp, C.byref(out), lp), "pahq_eval_circuit")
         return (out.value, logits) if want_logits else out.value
+
+    def set_dead_node_skipping(self, on):
+        _chk(lib().pahq_set_dead_node_skipping(self.h, 1 if on else 0), "pahq_set_dead_node_skipping")
 
     def set_removed(self, removed):
         r = np.ascontiguousarray(removed, dtype=np.uint8)

@@ -59,6 +59,7 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
   M->Vp = (M->V + 31) / 32 * 32;      // logits rows start on 128-byte boundaries
   M->nmax = c->max_batch_edges; M->G = 3 * M->H + 1;
   M->all_f32 = c->precision == PAHQ_ALL_FP32;
+  M->skip_dead = true;
   M->f32_groups = M->all_f32 ? 3 * M->H : 3;
   M->f32_heads_max = M->all_f32 ? M->H : 1;
   M->ncap = std::max(M->nmax, 1024);
@@ -68,7 +69,7 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
 size_t arena_slot_bytes(const pahq_model* M) {
   size_t Nr = M->g.Nr, Ns = M->g.Ns, L = M->L, H = M->H;
   size_t b = Nr * sizeof(GroupDesc) + Nr * (Ns / 2 + 2) * sizeof(Term) + L * (5 * H + 8) * sizeof(GemmProb) +
-             2 * L * sizeof(CombineDesc) + L * (H + 1) * sizeof(CombineSrc) + L * sizeof(OprojDesc) +
+             4 * L * sizeof(CombineDesc) + L * (H + 3) * sizeof(CombineSrc) + L * sizeof(OprojDesc) +
              L * H * sizeof(HeadAux) + 65536;
   return (b + 4095) / 4096 * 4096;
 }
@@ -110,7 +111,7 @@ size_t layout(pahq_model* M, char* base) {
   M->cpi = b.take<float>(Ns * tile); M->rxpi = b.take<float>((2 * L + 1) * tile);
   M->ref_logits = b.take<float>(B * Vp); M->ref_logz = b.take<double>(B);
   M->xv = b.take<float>(tile);
-  M->qkv_sh = b.take<float>(T * 3 * H * dh); M->oth = b.take<float>(tile); M->sh_slots = b.take<float>(H * tile);
+  M->qkv_sh = b.take<float>(T * 3 * H * dh); M->oth = b.take<float>(tile); M->deadsum = b.take<float>(tile); M->sh_slots = b.take<float>(H * tile);
   M->qv = b.take<float>(n * T * dh);
   M->run_a = b.take<float>(n * tile); M->run_b = b.take<float>(n * tile);
   M->xcodes = b.take<uint8_t>(n * G * T * Kd); M->xscale = b.take<float>(n * G * T); M->xf32 = b.take<float>(std::max<size_t>(n * (size_t)M->f32_groups, 3 * H) * tile);
@@ -718,6 +719,12 @@ int pahq_acdc_sweep_sender_policy(pahq_model* M, float tau, const int32_t* recei
   return PAHQ_OK;
 }
 
+int pahq_set_dead_node_skipping(pahq_model* M, int32_t on) {
+  if (!M || (on != 0 && on != 1)) return PAHQ_EINVAL;
+  M->skip_dead = on != 0;
+  return PAHQ_OK;
+}
+
 int pahq_set_removed(pahq_model* M, const uint8_t* removed) {
   if (!M || !removed) return PAHQ_EINVAL;
   for (size_t i = 0; i < M->removed.size(); i++) if (removed[i] > 1) return PAHQ_EINVAL;
@@ -782,7 +789,7 @@ int pahq_quantize_rows_site(pahq_model* M, int32_t site, const float* x, int32_t
       AttnSrc src; memset(&src, 0, sizeof(src));
       src.q = src.k = src.v = M->logits; src.q_ld = src.k_ld = src.v_ld = cols;
       src.n_heads = 1; src.h0 = 0; src.head_cols = 0;
-      HIPCHK(launch_attention(src, M->xcodes, 0, M->xscale, 0, nullptr, 0, 0ull, 1, (int)nr, 1, 1, cols, (int)ldc, 0, nullptr, M->stream));
+      HIPCHK(launch_attention(src, M->xcodes, 0, M->xscale, 0, nullptr, 0, 0ull, 0ull, 1, (int)nr, 1, 1, cols, (int)ldc, 0, nullptr, M->stream));
     }
     HIPCHK(hipMemcpy2DAsync(codes + r0 * cols, (size_t)cols, M->xcodes, ldc, (size_t)cols, nr, hipMemcpyDeviceToHost, M->stream));
     HIPCHK(hipMemcpyAsync(scales + r0, M->xscale, nr * sizeof(float), hipMemcpyDeviceToHost, M->stream));

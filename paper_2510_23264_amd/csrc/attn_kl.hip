@@ -27,7 +27,8 @@ typedef float v4f_a __attribute__((ext_vector_type(4)));
 template <int ST, int DH, bool ROPE, bool STG>
 __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zcodes,
                                                          long long zc_is, float* zscale, long long zs_is, float* zf32,
-                                                         long long zf_is, unsigned long long f32_mask, int n_pairs, int B, int S, int H,
+                                                         long long zf_is, unsigned long long f32_mask, unsigned long long dead_mask,
+                                                         int n_pairs, int B, int S, int H,
                                                          int ldz, int rope, const float2* rope_tab) {
   constexpr int CH = DH / 4;        // columns of q / k per lane
   constexpr int NT = DH / 16;       // output column tiles
@@ -35,6 +36,7 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
   if (pair >= n_pairs) return;
   const int hl = pair % src.n_heads, sb = pair / src.n_heads;          // sb = inst * B + b
   const int h = src.h0 + hl;                                           // head index in the outputs
+  if ((dead_mask >> h) & 1ull) return;                                 // this head is not computed (a wave owns a pair: no barrier follows)
   const int inst = sb / B, b = sb % B;
   const int lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
   const float* qb = src.q + inst * src.q_is + (long long)b * S * src.q_ld + hl * src.head_cols;
@@ -258,14 +260,14 @@ hipError_t launch_rope_table(float* tab, int n_pos, int dh, float theta, hipStre
 }
 
 hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is, float* zscale,
-                            long long zs_is, float* zf32, long long zf_is, unsigned long long f32_mask, int n_inst, int B, int S,
+                            long long zs_is, float* zf32, long long zf_is, unsigned long long f32_mask, unsigned long long dead_mask, int n_inst, int B, int S,
                             int H, int dh, int ldz, int rope, const float* rope_tab, hipStream_t s) {
   if (n_inst == 0) return hipSuccess;
   if (S > 32) return hipErrorInvalidValue;
   int n_pairs = n_inst * B * src.n_heads;
   dim3 grid((n_pairs + 3) / 4);
 #define ATT1(ST_, DH_, R_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_, R_, (ST_ == 1 && DH_ == 64 && !R_)>), grid, dim3(256), 0, s, src, zcodes, \
-                                              zc_is, zscale, zs_is, zf32, zf_is, f32_mask, n_pairs, B, S, H, ldz, rope, (const float2*)rope_tab)
+                                              zc_is, zscale, zs_is, zf32, zf_is, f32_mask, dead_mask, n_pairs, B, S, H, ldz, rope, (const float2*)rope_tab)
 #define ATT(ST_, DH_) do { if (rope) ATT1(ST_, DH_, true); else ATT1(ST_, DH_, false); } while (0)
   if (S <= 16) {
     if (dh == 16) ATT(1, 16); else if (dh == 32) ATT(1, 32); else if (dh == 64) ATT(1, 64);

@@ -18,7 +18,7 @@ namespace pahq {
 
 // How one recomputed receiver forms its input from the residual streams.
 struct RecvSpec {
-  int form;                    // 0 dense (running stream only), 1 removed form, 2 kept form
+  int form;                    // 0 dense (running stream only), 1 removed form, 2 kept form, -1 not computed (dead node)
   std::vector<int> senders;    // removed senders (form 1) or kept senders (form 2), ascending
 };
 
@@ -27,8 +27,10 @@ struct RecvPlan {
   std::vector<RecvSpec> spec;  // indexed by receiver id (only receivers at positions >= p0 are filled)
   std::vector<int> slot_of;    // per sender: slot index or -1
   std::vector<char> shared;    // per sender: its slot is the same for every instance (see split_first)
+  std::vector<char> live;      // per sender: 0 = recomputed sender whose output no kept path carries to the output
   int n_slots = 0;             // per-instance slots
   int n_shared = 0;            // instance-independent slots
+  int n_dead = 0;              // recomputed senders with live == 0
   bool split_first = false;    // candidates recompute only the investigated head in their first layer
 };
 
@@ -57,34 +59,61 @@ inline bool node_is_live(const GraphDims& g, const uint8_t* removed, const int64
 }
 
 // Plan of a pass that recomputes everything from position p0 on, for candidates into receiver v
-// (v < 0: no candidates).  Per receiver the cheaper of the two forms of its input; every recomputed
-// sender that some receiver needs separately gets a slot for its (output - corrupted output).
+// (v < 0: no candidates).
+//
+// Dead nodes.  A recomputed sender is live if one of its kept edges leads to the output node or to a
+// receiver of a live node (v's own node always counts as live).  Every edge out of a dead sender is
+// removed, so every receiver takes the corrupted run's output from it whatever it computes: it is not
+// computed at all, the running stream takes its cached corrupted output in its place (its difference
+// D_s to the corrupted run is then zero and drops out of every removed-form sum), and its receivers
+// get form -1.  The outputs are those of the full computation; a sparse graph costs only its live part.
+//
+// Per live receiver the cheaper of the two forms of its input; every recomputed sender that some
+// receiver needs separately gets a slot for its (output - corrupted output).
 // split: the receiver's own layer is shared between candidates except for the investigated head, so
 // the other heads of that layer need one slot for all instances instead of one per instance.
 inline void plan_receivers(const GraphDims& g, const uint8_t* removed, const int64_t* edge_off, bool pahq_precision,
-                           int p0, int v, RecvPlan& out) {
+                           int p0, int v, RecvPlan& out, bool skip_dead = true) {
   out.p0 = p0;
   out.spec.assign(g.Nr, RecvSpec());
   out.slot_of.assign(g.Ns, -1);
   out.shared.assign(g.Ns, 0);
+  out.live.assign(g.Ns, 1);
   out.n_slots = 0;
   out.n_shared = 0;
+  out.n_dead = 0;
   int vk = -1, vl, vh, vc;
   if (v >= 0) g.receiver_info(v, vk, vl, vh, vc);
   out.split_first = (vk == 0 && pahq_precision);
   const int v_node = v >= 0 ? g.node_of_receiver(v) : -1;
   const int nstat = g.n_static(p0);
+  // liveness, from the last sender backwards: the receivers a sender feeds belong to later senders (or are the output)
+  if (skip_dead)
+    for (int s = g.Ns - 1; s >= nstat; s--) {
+      bool lv = (s == v_node);
+      const int pa = g.pos_after_sender(s);
+      for (int w = g.Nr - 1; w >= 0 && !lv; w--) {
+        if (g.pos_of_receiver(w) < pa) break;                 // receiver ids follow the stream
+        if (removed[edge_off[w] + s]) continue;
+        const int nw = g.node_of_receiver(w);
+        lv = nw < 0 || out.live[nw];
+      }
+      out.live[s] = lv ? 1 : 0;
+      out.n_dead += lv ? 0 : 1;
+    }
   for (int w = 0; w < g.Nr; w++) {
     if (g.pos_of_receiver(w) < p0) continue;
+    RecvSpec& sp = out.spec[w];
+    const int nw = g.node_of_receiver(w);
+    if (nw >= 0 && !out.live[nw]) { sp.form = -1; continue; }
     const int n_up = g.n_upstream(w);
     const uint8_t* row = removed + edge_off[w];
-    int n_rem = 0;
-    for (int s = 0; s < n_up; s++) n_rem += row[s];
-    RecvSpec& sp = out.spec[w];
+    int n_rem = 0, n_kept = 0;       // removed edges from live senders; kept edges (dead senders have none)
+    for (int s = 0; s < n_up; s++) { n_rem += row[s] && out.live[s]; n_kept += !row[s]; }
     if (n_rem == 0) { sp.form = 0; continue; }
-    if (n_rem <= n_up - n_rem) {
+    if (n_rem <= n_kept) {
       sp.form = 1;
-      for (int s = 0; s < n_up; s++) if (row[s]) sp.senders.push_back(s);
+      for (int s = 0; s < n_up; s++) if (row[s] && out.live[s]) sp.senders.push_back(s);
     } else {
       sp.form = 2;
       for (int s = 0; s < n_up; s++) if (!row[s]) sp.senders.push_back(s);

@@ -61,11 +61,12 @@ struct pahq_model {
   float *logits_clean, *logits_corrupt;   // [B][V]
   double* logz_clean;                     // [B]
   float *cpi, *rxpi, *ref_logits; double* ref_logz;   // state of the current fp32 head
+  bool skip_dead;                         // passes over a pruned graph leave out nodes no kept path connects to the output
   bool all_f32;                           // PAHQ_ALL_FP32: every matrix product on the fp32 masters, no quantiser
   int f32_groups;                         // receiver-input groups of a layer that may need fp32 rows (per instance)
   int f32_heads_max;                      // heads whose attention output may be needed unquantised (per instance)
   float* xv;                              // current input of the receiver under evaluation
-  float *qkv_sh, *oth, *sh_slots, *qv;    // first-layer state shared by all candidates of a receiver
+  float *qkv_sh, *oth, *deadsum, *sh_slots, *qv;    // first-layer state shared by all candidates of a receiver
   float *run_a, *run_b;                   // [nmax] tiles each
   uint8_t* xcodes; float* xscale; float* xf32;
   float* qkv; uint8_t* zcodes; float* zscale; float* zf32;

@@ -24,13 +24,13 @@ namespace pahq {
 static inline int canon(const pahq_model* M, int p) { return canon_pos(M, p); }
 
 void make_plan(pahq_model* M, int p0, int v, RecvPlan& out) {
-  plan_receivers(M->g, M->removed.data(), M->edge_off.data(), M->cfg.precision == PAHQ_PAHQ, p0, v, out);
+  plan_receivers(M->g, M->removed.data(), M->edge_off.data(), M->cfg.precision == PAHQ_PAHQ, p0, v, out, M->skip_dead);
 }
 
 namespace {
 
 enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH, OP_OPROJ, OP_KLRED, OP_PREF, OP_SWIGLU32, OP_LD };
-struct Op { OpType t; int i0, i1, i2, i3; void* p0; void* p1; double flops, bytes; unsigned long long u64; };
+struct Op { OpType t; int i0, i1, i2, i3; void* p0; void* p1; double flops, bytes; unsigned long long u64, u64b; };
 
 struct Stream { float* p; long long is; };
 
@@ -49,6 +49,8 @@ struct Builder {
   std::vector<Op> ops;
   bool general, has_pi, f32_rest;
   int nstat;
+  // stand-ins of dead blocks the stream has not taken yet: cached corrupted outputs (tiles) and block biases (rows)
+  std::vector<const float*> pend_tiles, pend_rows;
 
   Builder(pahq_model* M_, const PassArgs& a_, const RecvPlan* p_) : M(M_), a(a_), plan(p_) {
     general = (a.kind == STATE || a.kind == CAND || a.kind == PREFIX);
@@ -115,7 +117,7 @@ struct Builder {
   }
 
   void add_op(OpType t, int i0 = 0, int i1 = 0, int i2 = 0, int i3 = 0, void* p0 = nullptr, void* p1 = nullptr) {
-    Op o; o.t = t; o.i0 = i0; o.i1 = i1; o.i2 = i2; o.i3 = i3; o.p0 = p0; o.p1 = p1; o.flops = 0; o.bytes = 0; o.u64 = 0;
+    Op o; o.t = t; o.i0 = i0; o.i1 = i1; o.i2 = i2; o.i3 = i3; o.p0 = p0; o.p1 = p1; o.flops = 0; o.bytes = 0; o.u64 = 0; o.u64b = 0;
     ops.push_back(o);
   }
   // algorithmic work of the op just added (all instances)
@@ -197,10 +199,55 @@ struct Builder {
     gd.offset = (M->cfg.norm == PAHQ_NORM_RMS || !offset) ? M->zeros_d : offset;
   }
 
-  void add_attention(const AttnSrc& src, unsigned long long f32_mask) {
+  void add_attention(const AttnSrc& src, unsigned long long f32_mask, unsigned long long dead_mask = 0) {
     asrcs.push_back(src);
     add_op(OP_ATTN, (int)asrcs.size() - 1);
     ops.back().u64 = f32_mask;
+    ops.back().u64b = dead_mask;
+  }
+
+  // heads of layer l that are not computed: no kept path carries their output to the output node
+  unsigned long long dead_heads(int l) const {
+    unsigned long long m = 0;
+    if (general && plan)
+      for (int h = 0; h < M->H; h++) if (!plan->live[M->g.head(l, h)]) m |= 1ull << h;
+    return m;
+  }
+  // A dead block leaves its stand-ins here; the stream takes all that have gathered in one pass over its tiles
+  // when the next live block (or the final norm) reads it.
+  void defer_standins(const float* bias, const std::vector<int>& senders) {
+    for (int s : senders) pend_tiles.push_back(corrupt_ref_tile(s));
+    if (bias) pend_rows.push_back(bias);
+  }
+  void take_standins(Stream& run) {
+    if (pend_tiles.empty() && pend_rows.empty()) return;
+    Stream nx; nx.p = run.p == M->run_a ? M->run_b : M->run_a; nx.is = M->tile;
+    CombineDesc cd; memset(&cd, 0, sizeof(cd));
+    cd.run_in = run.p; cd.run_in_is = run.is; cd.run_out = nx.p; cd.run_out_is = nx.is;
+    cd.bias = nullptr; cd.src_begin = (int)csrcs.size(); cd.n_src = (int)(pend_tiles.size() + pend_rows.size());
+    for (const float* t : pend_tiles) { CombineSrc cs; memset(&cs, 0, sizeof(cs)); cs.src = t; csrcs.push_back(cs); }
+    for (const float* r : pend_rows) { CombineSrc cs; memset(&cs, 0, sizeof(cs)); cs.src = r; cs.bcast = 1; csrcs.push_back(cs); }
+    cdescs.push_back(cd);
+    add_op(OP_COMBINE, (int)cdescs.size() - 1, 0);
+    ops.back().bytes = (double)a.n * M->tile * 8.0 + (double)pend_tiles.size() * M->tile * 4.0;
+    pend_tiles.clear(); pend_rows.clear();
+    run = nx;
+  }
+  // out = in + bias + the corrupted-run outputs of the given senders (what dead senders contribute to every
+  // receiver); one_inst: a single instance-independent tile instead of one per instance
+  void add_standins(const float* in, long long in_is, float* out, long long out_is, const float* bias,
+                    const std::vector<int>& senders, bool one_inst) {
+    CombineDesc cd; memset(&cd, 0, sizeof(cd));
+    cd.run_in = in; cd.run_in_is = in_is; cd.run_out = out; cd.run_out_is = out_is;
+    cd.bias = bias; cd.src_begin = (int)csrcs.size(); cd.n_src = (int)senders.size();
+    for (int s : senders) {
+      CombineSrc cs; memset(&cs, 0, sizeof(cs));
+      cs.src = corrupt_ref_tile(s); cs.src_is = 0;
+      csrcs.push_back(cs);
+    }
+    cdescs.push_back(cd);
+    add_op(OP_COMBINE, (int)cdescs.size() - 1, one_inst ? 1 : 0);
+    ops.back().bytes = (one_inst ? 1.0 : (double)a.n) * (double)M->tile * 4.0 * 2.0 + (double)senders.size() * M->tile * 4.0;
   }
 
   // First layer of a candidate pass into a head input (fp32 investigated head): the PREFIX pass
@@ -248,17 +295,35 @@ struct Builder {
   void attention_block(int l, Stream& run) {
     const GraphDims& g = M->g;
     const int H = M->H, dh = M->dh, d = M->d, T = M->T, Kd = M->Kd, Kh = M->Kh;
-    const unsigned long long fmask = mask_of(l);               // heads of this layer computed in fp32
     const unsigned long long all_heads = H >= 64 ? ~0ull : ((1ull << H) - 1ull);
+    const unsigned long long dead = dead_heads(l);             // heads of this layer that are not computed at all
+    const unsigned long long fmask = mask_of(l) & ~dead;       // live heads of this layer computed in fp32
+    const unsigned long long off8 = fmask | dead;              // heads that take no part in the quantised kernels
     const int nf = __builtin_popcountll(fmask);
     const bool prefix = a.kind == PREFIX;
     float* const qkv_buf = prefix ? M->qkv_sh : M->qkv;
+    std::vector<int> dead_list;
+    for (int h = 0; h < H; h++) if ((dead >> h) & 1ull) dead_list.push_back(g.head(l, h));
+    if (dead == all_heads) {
+      // nothing of this layer reaches the output: the stream moves on with the corrupted run's head outputs
+      defer_standins(M->b_O + (long long)l * d, dead_list);
+      return;
+    }
+    take_standins(run);
+    // sum of the dead heads' stand-ins, the same for every instance
+    const float* deadsum = nullptr;
+    if (!dead_list.empty()) {
+      std::vector<int> rest(dead_list.begin() + 1, dead_list.end());
+      add_standins(corrupt_ref_tile(dead_list[0]), 0, M->deadsum, 0, nullptr, rest, true);
+      deadsum = M->deadsum;
+    }
     // ---- groups
     std::map<std::pair<int, std::vector<int>>, int> seen;
     std::vector<int> grp_of(3 * H, -1);          // index into `groups` per (h, c) block
     int g_begin = (int)groups.size(), n_f32 = 0, patch_group = -1;
     for (int h = 0; h < H; h++)
       for (int c = 0; c < 3; c++) {
+        if ((dead >> h) & 1ull) continue;
         int w = g.headin(l, h, c);
         const bool is_pi = (fmask >> h) & 1ull;
         int gi;
@@ -295,9 +360,9 @@ struct Builder {
     const long long qkv_ld = 3LL * H * dh;
     for (int nb = 0; nb < 3 * H;) {
       int gi = grp_of[nb];
-      if ((fmask >> (nb % H)) & 1ull) { nb++; continue; }
+      if ((off8 >> (nb % H)) & 1ull) { nb++; continue; }
       int e = nb + 1;
-      while (e < 3 * H && grp_of[e] == gi && !((fmask >> (e % H)) & 1ull)) e++;
+      while (e < 3 * H && grp_of[e] == gi && !((off8 >> (e % H)) & 1ull)) e++;
       const GroupDesc& gd = groups[gi];
       probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
                             M->qkv_codes + ((long long)l * 3 * H * dh + (long long)nb * dh) * Kd, Kd,
@@ -324,13 +389,20 @@ struct Builder {
       }
       add_op(OP_GEMM32, pf, 3 * nf, T * a.n, dh); work_gemm(pf);
     }
+    if (prefix && off8 == all_heads) {
+      // only the investigated head of this layer is live: what every candidate shares is the stream, the bias and
+      // the dead heads' stand-ins
+      add_standins(run.p, run.is, M->oth, 0, M->b_O + (long long)l * d, dead_list, false);
+      run.p = M->oth; run.is = 0;
+      return;
+    }
     {
       AttnSrc src; memset(&src, 0, sizeof(src));
       src.q = qkv_buf; src.k = qkv_buf + H * dh; src.v = qkv_buf + 2 * H * dh;
       src.q_is = src.k_is = src.v_is = (long long)T * qkv_ld;
       src.q_ld = src.k_ld = src.v_ld = (int)qkv_ld;
       src.n_heads = H; src.h0 = 0; src.head_cols = dh;
-      add_attention(src, fmask);
+      add_attention(src, fmask, dead);
     }
     // ---- output projections of all heads fused with the stream update.  Only heads whose
     // individual output is needed (cache passes; a downstream receiver that treats the head's
@@ -343,8 +415,9 @@ struct Builder {
     od.W = M->o_codes + (long long)l * H * d * Kh; od.ws = M->o_scale + (long long)l * H;
     od.run_in = run.p; od.run_in_is = run.is; od.run_out = nxt.p; od.run_out_is = nxt.is;
     od.bias = M->b_O + (long long)l * d;
-    od.H = H; od.Kh = Kh; od.skip_mask = fmask; od.rpi = T; od.M = T * a.n; od.N = d;
+    od.H = H; od.Kh = Kh; od.skip_mask = off8; od.rpi = T; od.M = T * a.n; od.N = d;
     od.aux_begin = -1; od.dh = M->dh;
+    od.extra = deadsum; od.extra_is = 0;              // replaced below when fp32 heads are chained in front of it
     bool any_aux = false;
     std::vector<HeadAux> hx(H);
     for (int h = 0; h < H; h++) {
@@ -368,6 +441,7 @@ struct Builder {
         GemmProb pp = prob8(M->zf32 + (long long)k * dh, (long long)T * nf * dh, nf * dh, nullptr, 0, 0,
                             M->W_O + ((long long)l * H + h) * dh * d, d, nullptr, 1, nullptr, M->headout, M->tile, d, 0, T, d, dh, dh);
         if (k > 0) { pp.add = M->headout; pp.add_is = M->tile; }
+        else if (deadsum) { pp.add = deadsum; pp.add_is = 0; }          // the chain starts from the dead heads' stand-ins
         pp.aux = hx[h].dst; pp.aux_is = hx[h].dst_is; pp.aux_sub = hx[h].sub;
         probs.push_back(pp);
         add_op(OP_GEMM32, pf, 1, T * a.n, d); work_gemm(pf);
@@ -375,7 +449,7 @@ struct Builder {
       }
       od.extra = M->headout; od.extra_is = M->tile;
     }
-    if (fmask == all_heads && !prefix) {
+    if (off8 == all_heads && nf && !prefix) {
       // nothing is quantised in this layer: next = run + b_O + (sum of the fp32 heads)
       CombineDesc cd; memset(&cd, 0, sizeof(cd));
       cd.run_in = run.p; cd.run_in_is = run.is; cd.run_out = nxt.p; cd.run_out_is = nxt.is;
@@ -390,7 +464,7 @@ struct Builder {
       if (any_aux) { od.aux_begin = (int)haux.size(); haux.insert(haux.end(), hx.begin(), hx.end()); }
       odescs.push_back(od);
       add_op(OP_OPROJ, (int)odescs.size() - 1, T * a.n, d);
-      ops.back().flops = 2.0 * T * a.n * d * dh * (H - nf);
+      ops.back().flops = 2.0 * T * a.n * d * dh * (H - __builtin_popcountll(off8));
     }
     run = nxt;
   }
@@ -399,6 +473,12 @@ struct Builder {
     const GraphDims& g = M->g;
     const int d = M->d, T = M->T, Kd = M->Kd, Km = M->Km, m = M->m;
     int w = g.mlpin(l), s = g.mlp(l);
+    if (general && plan && !plan->live[s]) {
+      // a dead MLP: the stream moves on with the corrupted run's output in its place
+      defer_standins(M->b_out + (long long)l * d, std::vector<int>(1, s));
+      return;
+    }
+    take_standins(run);
     GroupDesc gd; memset(&gd, 0, sizeof(gd));
     int patch_group = -1, gi = (int)groups.size();
     if (a.kind == CAND && w == a.v) patch_group = gi;
@@ -474,6 +554,7 @@ struct Builder {
   }
 
   void final_block(Stream run) {
+    take_standins(run);
     const bool ld = M->metric == PAHQ_METRIC_LOGIT_DIFF;
     // with that metric a scored pass needs two logits per sequence, not the unembedding (unless its logits are asked for)
     final_block_kl(run, ld && general && !a.keep_logits);
@@ -678,10 +759,10 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
       case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, o.i2, o.i3, st)); break;
       case OP_ATTN:
         HIPCHK(launch_attention(b.asrcs[o.i0], M->zcodes, (long long)T * M->H * M->Kh,
-                                M->zscale, (long long)T * M->H, M->zf32, (long long)T * M->dh * __builtin_popcountll(o.u64), o.u64, n, B, S, M->H,
+                                M->zscale, (long long)T * M->H, M->zf32, (long long)T * M->dh * __builtin_popcountll(o.u64), o.u64, o.u64b, n, B, S, M->H,
                                 M->dh, M->Kh, M->cfg.pos == PAHQ_POS_ROPE, M->rope_tab, st));
         break;
-      case OP_COMBINE: HIPCHK(launch_combine(d_cdesc, o.i0, d_csrc, n, M->tile, d, st)); break;
+      case OP_COMBINE: HIPCHK(launch_combine(d_cdesc, o.i0, d_csrc, o.i1 ? 1 : n, M->tile, d, st)); break;
       case OP_OPROJ:
         HIPCHK(launch_oproj_fused(d_odesc, o.i0, d_haux, o.i1, o.i2, M->H, M->dh, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
         break;

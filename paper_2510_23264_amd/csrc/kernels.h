@@ -77,6 +77,7 @@ struct CombineSrc {
   const float* src;  long long src_is;
   float* slot;       long long slot_is;   // optional: slot = src - sub
   const float* sub;                       // instance-independent tile (may be null -> slot = src)
+  long long bcast;                        // nonzero: src is one row of d values added to every row (a bias)
 };
 // run_out = run_in + bias + sum(src), element-wise over T*d
 struct CombineDesc {
@@ -159,7 +160,7 @@ struct AttnSrc {
   int n_heads, h0, head_cols, pad3_;
 };
 hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is, float* zscale,
-                            long long zs_is, float* zf32, long long zf_is, unsigned long long f32_mask, int n_inst, int B, int S,
+                            long long zs_is, float* zf32, long long zf_is, unsigned long long f32_mask, unsigned long long dead_mask, int n_inst, int B, int S,
                             int H, int dh, int ldz, int rope, const float* rope_tab, hipStream_t s);
 // rope_tab: [n_pos][dh / 2] pairs (cos, sin), filled by launch_rope_table; read only when rope != 0, n_pos >= S
 hipError_t launch_rope_table(float* tab, int n_pos, int dh, float theta, hipStream_t s);

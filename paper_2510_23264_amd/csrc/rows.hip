@@ -490,7 +490,7 @@ __global__ void combine_k(const CombineDesc* descs, int di, const CombineSrc* sr
   }
   for (int k = 0; k < D.n_src; k++) {
     CombineSrc s = srcs[D.src_begin + k];
-    float4 v = *(const float4*)(s.src + inst * s.src_is + e);
+    float4 v = s.bcast ? *(const float4*)(s.src + (e % d)) : *(const float4*)(s.src + inst * s.src_is + e);
     acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     if (s.slot) {
       if (s.sub) {

@@ -14,6 +14,7 @@
 using namespace pahq;
 
 static int failures = 0;
+static long plans_with_dead = 0, dead_total = 0;
 #define CHECK(cond, ...) do { if (!(cond)) { failures++; printf("FAIL %s:%d: ", __FILE__, __LINE__); printf(__VA_ARGS__); printf("\n"); if (failures > 20) exit(1); } } while (0)
 
 static uint64_t mix(uint64_t x) { x += 0x9E3779B97F4A7C15ull; x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull; x = (x ^ (x >> 27)) * 0x94D049BB133111EBull; return x ^ (x >> 31); }
@@ -113,23 +114,57 @@ static void check_graph_and_plan(uint64_t seed, int L, int H, bool mlp) {
     const int v = (int)(mix(seed + rep) % g.Nr), p0 = g.pos_of_receiver(v);
     const double dens = unit(seed * 7 + rep);
     for (int r = 0; r < g.Nr; r++) if (g.pos_of_receiver(r) >= p0)
-      for (int s = 0; s < g.n_upstream(r); s++) removed[off[r] + s] = unit(seed * 31 + rep * 1000003ull + off[r] + s) < dens;
-    for (int pahq = 0; pahq < 2; pahq++) {
-      RecvPlan plan; plan_receivers(g, removed.data(), off.data(), pahq, p0, v, plan);
+      for (int s = 0; s < g.n_upstream(r); s++) {
+        const bool sender_off = unit(seed * 131 + rep * 7919ull + s) < 0.4;       // all edges out of some senders go
+        removed[off[r] + s] = sender_off || unit(seed * 31 + rep * 1000003ull + off[r] + s) < dens;
+      }
+    for (int variant = 0; variant < 4; variant++) {
+      const int pahq = variant & 1; const bool skip = (variant & 2) != 0;
+      RecvPlan plan; plan_receivers(g, removed.data(), off.data(), pahq, p0, v, plan, skip);
       const int nstat = g.n_static(p0);
+      int vk, vl, vh, vc; g.receiver_info(v, vk, vl, vh, vc);
+      // liveness by its definition, as a fixed point over all (sender, receiver) pairs in no particular order:
+      // a recomputed sender is live if it is the candidates' own node or a kept edge leads to the output or to a live node
+      std::vector<char> live(g.Ns, 1);
+      if (skip) {
+        for (int s = nstat; s < g.Ns; s++) live[s] = (s == g.node_of_receiver(v));
+        for (bool changed = true; changed;) {
+          changed = false;
+          for (int s = nstat; s < g.Ns; s++) for (int w = 0; w < g.Nr && !live[s]; w++) {
+            if (g.pos_after_sender(s) > g.pos_of_receiver(w) || removed[off[w] + s]) continue;
+            const int nw = g.node_of_receiver(w);
+            if (nw < 0 || live[nw]) { live[s] = 1; changed = true; }
+          }
+        }
+      }
+      int n_dead = 0;
+      for (int s = 0; s < g.Ns; s++) { CHECK(plan.live[s] == live[s], "liveness of sender %d: plan %d, definition %d", s, (int)plan.live[s], (int)live[s]); n_dead += !live[s]; }
+      CHECK(plan.n_dead == n_dead, "n_dead %d, counted %d", plan.n_dead, n_dead);
+      plans_with_dead += n_dead > 0; dead_total += n_dead;
       std::vector<char> needed(g.Ns, 0);
       for (int r = 0; r < g.Nr; r++) {
         if (g.pos_of_receiver(r) < p0) continue;
         const RecvSpec& sp = plan.spec[r];
+        const int nr = g.node_of_receiver(r);
+        if (nr >= 0 && !live[nr]) { CHECK(sp.form == -1 && sp.senders.empty(), "receiver %d of a dead node has form %d", r, sp.form); continue; }
+        CHECK(sp.form >= 0 && sp.form <= 2, "receiver %d: form %d", r, sp.form);
+        // the edges the plan describes: form 2 lists the kept ones; forms 0 and 1 list the removed ones from live
+        // senders, and every edge from a dead sender is removed without being listed
         std::vector<uint8_t> row(g.n_upstream(r), sp.form == 2 ? 1 : 0);
-        for (int s : sp.senders) { CHECK(s >= 0 && s < g.n_upstream(r), "sender %d not upstream of %d", s, r); if (s >= 0 && s < g.n_upstream(r)) row[s] = sp.form == 2 ? 0 : 1; if (s >= nstat) needed[s] = 1; }
+        if (sp.form != 2) for (int s = 0; s < g.n_upstream(r); s++) if (!live[s]) row[s] = 1;
+        for (int s : sp.senders) {
+          CHECK(s >= 0 && s < g.n_upstream(r), "sender %d not upstream of %d", s, r);
+          if (s < 0 || s >= g.n_upstream(r)) continue;
+          CHECK(live[s], "dead sender %d listed for receiver %d", s, r);
+          row[s] = sp.form == 2 ? 0 : 1;
+          if (s >= nstat) needed[s] = 1;
+        }
         if (sp.form == 0) CHECK(sp.senders.empty(), "dense form with terms");
         for (int s = 0; s < g.n_upstream(r); s++) CHECK(row[s] == removed[off[r] + s], "plan of receiver %d misdescribes edge from %d", r, s);
-        int n_rem = 0; for (int s = 0; s < g.n_upstream(r); s++) n_rem += removed[off[r] + s];
-        CHECK((int)sp.senders.size() == std::min(n_rem, g.n_upstream(r) - n_rem), "receiver %d does not take the cheaper form", r);
+        int n_rem = 0, n_kept = 0; for (int s = 0; s < g.n_upstream(r); s++) { n_rem += removed[off[r] + s] && live[s]; n_kept += !removed[off[r] + s]; }
+        CHECK((int)sp.senders.size() == std::min(n_rem, n_kept), "receiver %d does not take the cheaper form", r);
       }
       std::set<int> own, shared;
-      int vk, vl, vh, vc; g.receiver_info(v, vk, vl, vh, vc);
       for (int s = 0; s < g.Ns; s++) {
         CHECK((plan.slot_of[s] >= 0) == (bool)needed[s], "sender %d: slot %d, needed %d", s, plan.slot_of[s], (int)needed[s]);
         if (plan.slot_of[s] < 0) continue;
@@ -174,6 +209,7 @@ int main() {
   for (int fail_at = 0; fail_at < 6; fail_at++) for (uint64_t seed = 1; seed <= 4; seed++) { check_scan(seed, 100, 8, 2e-5, fail_at); cases++; }
   const int shapes[][3] = {{1, 1, 0}, {1, 1, 1}, {2, 2, 0}, {2, 3, 1}, {3, 4, 1}, {4, 2, 1}, {12, 12, 1}};
   for (auto& sh : shapes) for (uint64_t seed = 1; seed <= 3; seed++) { check_graph_and_plan(seed * 77 + sh[0], sh[0], sh[1], sh[2]); cases++; }
-  printf("%d cases, %d failures\n", cases, failures);
+  CHECK(plans_with_dead > 50, "the removed sets of this check hardly ever leave a node dead (%ld plans)", plans_with_dead);
+  printf("%d cases (%ld plans with dead nodes, %ld dead nodes), %d failures\n", cases, plans_with_dead, dead_total, failures);
   return failures ? 1 : 0;
 }

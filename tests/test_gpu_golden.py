@@ -99,10 +99,12 @@ def test_cfg5_layer_shape_at_the_task_tolerance(name):
 
 def test_fp8_matrix_core_adder_is_biased_low():
     """The record behind the default arithmetic: with the FP8 matrix-core instruction (PAHQ_MMA_FP8) the
-    same candidates come out systematically LOW -- its adder truncates products below a window under
-    the largest one -- by 0.5 % to 3 % on KLs that are large enough to tell, which the median rule of
-    the binding bound rejects; the exact path (codes decoded to fp16, fp32 sums) passes it above."""
-    new, _, _ = run_workload("cfg3_hi", 64, mma=0)
+    candidates of config 3 as it is specified come out systematically LOW -- its adder truncates products
+    below a window under the largest one -- by 0.5 % to 3 % on the KLs large enough to tell (above 1e-3),
+    which the median rule of the binding bound rejects; the exact path (codes decoded to fp16, fp32 sums)
+    passes it above.  (With weights scaled up until KLs are of order 0.1 the same adder loses 0.1 % in the
+    median: the loss is an absolute amount per sum, and config 3's KLs are small differences of such sums.)"""
+    new, _, _ = run_workload("cfg3", 64, mma=0)
     big = new[:, 1] > 1e-3
     rel = (new[big, 0] - new[big, 1]) / new[big, 1]
     print("FP8 matrix-core adder: relative KL error median %.4f min %.4f max %.4f" % (np.median(rel), rel.min(), rel.max()))
@@ -110,4 +112,4 @@ def test_fp8_matrix_core_adder_is_biased_low():
     assert -0.03 < np.median(rel) < -0.005
     assert (rel < 0).mean() >= 0.9
     with pytest.raises(AssertionError):
-        check_kl_cases(new[:, 0], new[:, 1], new[:, 2], what="fp8 adder")
+        check_kl_cases(new[big, 0], new[big, 1], new[big, 2], what="fp8 adder")

@@ -269,6 +269,12 @@ def test_every_edge_kl_under_removed_sets(cfg1, mid, frac):
         pr.gm.set_removed(np.zeros(g.n_edges(), np.uint8))
 
 
+# Identical prompts with nodes left out as dead: the stream takes a dead node's cached output at another place
+# of its sums than the kernel that computes the node adds it, so the pruned run's logits equal the clean run's
+# to rounding (and, where a rounding moves an e4m3 code, to that code's step) instead of bit for bit.
+ZERO_WITH_DEAD_NODES = 1e-6
+
+
 def test_clean_patch_is_exactly_zero():
     shape, w, clean, _, _ = synth.make_workload("cfg1")
     pr = Pair(shape, w, clean, clean.copy())
@@ -277,9 +283,11 @@ def test_clean_patch_is_exactly_zero():
         for r in (g.OUT, g.headin(1, 2, 1), g.headin(0, 0, 0)):
             R = random_removed(g, 0.5, 3, from_receiver=r)
             pr.gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
-            got = pr.gm.eval_edges(r, np.arange(g.n_upstream(r), dtype=np.int32))
-            assert (got == 0.0).all()
-            assert pr.gm.eval_current(r) == 0.0
+            for skipping, limit in ((False, 0.0), (True, ZERO_WITH_DEAD_NODES)):
+                pr.gm.set_dead_node_skipping(skipping)
+                got = pr.gm.eval_edges(r, np.arange(g.n_upstream(r), dtype=np.int32))
+                assert (np.abs(got) <= limit).all(), (skipping, got)
+                assert abs(pr.gm.eval_current(r)) <= limit, skipping
     finally:
         pr.close()
 
@@ -300,13 +308,21 @@ def test_clean_patch_is_exactly_zero_with_mlps_and_any_removed_set(shape):
             ref = gm.get_logits(0)
             for r in (g.OUT, g.mlpin(1), g.headin(2, 1, 0), g.headin(0, 0, 2)):
                 gm.set_removed(g.removed_to_flat(random_removed(g, 0.5, 3, from_receiver=r)).astype(np.uint8))
-                assert (gm.eval_edges(r, np.arange(g.n_upstream(r), dtype=np.int32)) == 0.0).all()
-                assert gm.eval_current(r) == 0.0
+                for skipping, limit in ((False, 0.0), (True, ZERO_WITH_DEAD_NODES)):
+                    gm.set_dead_node_skipping(skipping)
+                    assert (np.abs(gm.eval_edges(r, np.arange(g.n_upstream(r), dtype=np.int32))) <= limit).all(), (precision, r, skipping)
+                    assert abs(gm.eval_current(r)) <= limit, (precision, r, skipping)
             gm.set_removed(np.zeros(g.n_edges(), np.uint8))
             for frac, seed in ((0.5, 1), (0.9, 2)):
                 kept = (~g.removed_to_flat(random_removed(g, frac, seed))).astype(np.uint8)
-                kl, lg = gm.eval_circuit(kept=kept, f32_heads=np.zeros((shape.n_layers, shape.n_heads), np.uint8), want_logits=True)
+                flags = np.zeros((shape.n_layers, shape.n_heads), np.uint8)
+                gm.set_dead_node_skipping(False)
+                kl, lg = gm.eval_circuit(kept=kept, f32_heads=flags, want_logits=True)
                 assert kl == 0.0 and np.array_equal(lg.view(np.uint32), ref.view(np.uint32)), (precision, frac)
+                gm.set_dead_node_skipping(True)
+                kl, lg = gm.eval_circuit(kept=kept, f32_heads=flags, want_logits=True)
+                assert abs(kl) <= ZERO_WITH_DEAD_NODES and np.abs(lg - ref).max() <= 1e-3 * np.abs(ref).max(), (precision, frac)
+            gm.set_dead_node_skipping(False)        # (removing the top MLP's only edge would leave it dead)
             for r in range(0, g.n_receivers, 3):
                 for s in (0, g.n_upstream(r) - 1):
                     R = g.empty_removed(); R[r, s] = True
