@@ -60,6 +60,7 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
   M->nmax = c->max_batch_edges; M->G = 3 * M->H + 1;
   M->all_f32 = c->precision == PAHQ_ALL_FP32;
   M->skip_dead = true;
+  M->deadsum_tag.assign(M->L, -1);
   M->f32_groups = M->all_f32 ? 3 * M->H : 3;
   M->f32_heads_max = M->all_f32 ? M->H : 1;
   M->ncap = std::max(M->nmax, 1024);
@@ -111,7 +112,7 @@ size_t layout(pahq_model* M, char* base) {
   M->cpi = b.take<float>(Ns * tile); M->rxpi = b.take<float>((2 * L + 1) * tile);
   M->ref_logits = b.take<float>(B * Vp); M->ref_logz = b.take<double>(B);
   M->xv = b.take<float>(tile);
-  M->qkv_sh = b.take<float>(T * 3 * H * dh); M->oth = b.take<float>(tile); M->deadsum = b.take<float>(tile); M->sh_slots = b.take<float>(H * tile);
+  M->qkv_sh = b.take<float>(T * 3 * H * dh); M->oth = b.take<float>(tile); M->deadsum = b.take<float>(L * tile); M->sh_slots = b.take<float>(H * tile);
   M->qv = b.take<float>(n * T * dh);
   M->run_a = b.take<float>(n * tile); M->run_b = b.take<float>(n * tile);
   M->xcodes = b.take<uint8_t>(n * G * T * Kd); M->xscale = b.take<float>(n * G * T); M->xf32 = b.take<float>(std::max<size_t>(n * (size_t)M->f32_groups, 3 * H) * tile);

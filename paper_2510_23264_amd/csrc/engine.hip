@@ -24,6 +24,7 @@ namespace pahq {
 static inline int canon(const pahq_model* M, int p) { return canon_pos(M, p); }
 
 void make_plan(pahq_model* M, int p0, int v, RecvPlan& out) {
+  M->plan_serial++;
   plan_receivers(M->g, M->removed.data(), M->edge_off.data(), M->cfg.precision == PAHQ_PAHQ, p0, v, out, M->skip_dead);
 }
 
@@ -51,6 +52,7 @@ struct Builder {
   int nstat;
   // stand-ins of dead blocks the stream has not taken yet: cached corrupted outputs (tiles) and block biases (rows)
   std::vector<const float*> pend_tiles, pend_rows;
+  std::vector<std::pair<int, long long>> new_tags;     // (layer, tag) of the dead-head sums this pass makes
 
   Builder(pahq_model* M_, const PassArgs& a_, const RecvPlan* p_) : M(M_), a(a_), plan(p_) {
     general = (a.kind == STATE || a.kind == CAND || a.kind == PREFIX);
@@ -310,12 +312,18 @@ struct Builder {
       return;
     }
     take_standins(run);
-    // sum of the dead heads' stand-ins, the same for every instance
+    // sum of the dead heads' stand-ins: the same for every instance and for every pass under this plan (the state
+    // pass and all candidate batches of a receiver), so it is made by the first pass that needs it
     const float* deadsum = nullptr;
     if (!dead_list.empty()) {
-      std::vector<int> rest(dead_list.begin() + 1, dead_list.end());
-      add_standins(corrupt_ref_tile(dead_list[0]), 0, M->deadsum, 0, nullptr, rest, true);
-      deadsum = M->deadsum;
+      float* ds = M->deadsum + (long long)l * M->tile;
+      const long long tag = 2 * M->plan_serial + (has_pi ? 1 : 0);
+      if (M->deadsum_tag[l] != tag) {
+        std::vector<int> rest(dead_list.begin() + 1, dead_list.end());
+        add_standins(corrupt_ref_tile(dead_list[0]), 0, ds, 0, nullptr, rest, true);
+        new_tags.push_back(std::make_pair(l, tag));
+      }
+      deadsum = ds;
     }
     // ---- groups
     std::map<std::pair<int, std::vector<int>>, int> seen;
@@ -787,6 +795,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
     }
     if (pair >= 0) HIPCHK(hipEventRecord(M->prof_ev[2 * pair + 1], st));
   }
+  for (const auto& t : b.new_tags) M->deadsum_tag[t.first] = t.second;      // every launch of the pass is queued
   M->counters[2]++;
   return PAHQ_OK;
 }
