@@ -101,6 +101,16 @@ typedef struct {
                                sum|a*w| per sum, truncating toward zero), which makes every KL come out
                                about 1.3 % low.  About 6 % faster end to end.
                                Codes and scales are identical in both modes.                        */
+  int32_t low_bits;         /* grid of the low-precision operands (weights per slice, activation rows):
+                               8 (or 0): FP8 E4M3, the paper's setting.
+                               4: the 4-bit point of the paper's bit-width ablation (Sec. "Ablation
+                               Studies", Different Quantization Precisions), Eq. RTN-Q with N = 4 as
+                               printed: step = max|x| / 2^(N-1), values round to the nearest multiple
+                               (ties to even), |multiple| <= 8.  The multiples are stored as the E4M3
+                               codes of those integers (exact), so pahq_get_weight_q and the quantiser
+                               hooks return, at 4 bits, E4M3 codes of integers and the step as scale;
+                               the matrix products are the same exact kernels.  The 16-bit point of
+                               that table is not built.                                             */
 } pahq_config;
 
 /* fp32 master weights, row-major.  All pointers host memory (on_device = 0) or

@@ -34,6 +34,7 @@ from __future__ import annotations
 import numpy as np
 
 from . import e4m3
+from .rtn import Rtn
 from .graph import Graph
 
 NORM_LAYER, NORM_RMS = 0, 1
@@ -76,8 +77,13 @@ def kl_to_reference(logp_ref, logits):
 
 
 class Model:
-    def __init__(self, shape, weights, cache_decoded_bytes=6 << 30):
-        """shape: any object with the ModelShape attributes; weights: dict of float32 arrays."""
+    def __init__(self, shape, weights, cache_decoded_bytes=6 << 30, low_bits=8):
+        """shape: any object with the ModelShape attributes; weights: dict of float32 arrays.
+        low_bits: the grid of the quantised operands -- 8: e4m3 (the paper's setting); 4: Eq. RTN-Q with
+        N = 4 (the 4-bit point of the bit-width ablation, rtn.py)."""
+        if low_bits not in (4, 8):
+            raise ValueError("low_bits")
+        self.q = e4m3 if low_bits == 8 else Rtn(low_bits)
         self.s = shape
         self.L, self.H, self.dh, self.d = shape.n_layers, shape.n_heads, shape.d_head, shape.d_model
         self.m, self.V = shape.d_mlp, shape.vocab
@@ -96,14 +102,14 @@ class Model:
         self.qc, self.qs = {}, {}
         for nm in ("W_Q", "W_K", "W_V", "W_O"):
             flat = w[nm].reshape(L * H, -1)
-            c, s = e4m3.quantize_groups(flat, axis=-1)
+            c, s = self.q.quantize_groups(flat, axis=-1)
             self.qc[nm], self.qs[nm] = c.reshape(w[nm].shape), s.reshape(L, H)
         for nm in ("W_in", "W_gate", "W_out"):
             if nm in w:
                 flat = w[nm].reshape(L, -1)
-                c, s = e4m3.quantize_groups(flat, axis=-1)
+                c, s = self.q.quantize_groups(flat, axis=-1)
                 self.qc[nm], self.qs[nm] = c.reshape(w[nm].shape), s.reshape(L)
-        c, s = e4m3.quantize_groups(w["W_U"], axis=None)
+        c, s = self.q.quantize_groups(w["W_U"], axis=None)
         self.qc["W_U"], self.qs["W_U"] = c, np.float32(s)
 
     def _wdec(self, nm, *idx):
@@ -111,7 +117,7 @@ class Model:
         key = (nm,) + idx
         if key in self._dec_cache:
             return self._dec_cache[key]
-        a = e4m3.decode(self.qc[nm][idx])
+        a = self.q.decode(self.qc[nm][idx])
         if self._dec_budget >= a.nbytes:
             self._dec_budget -= a.nbytes
             self._dec_cache[key] = a
@@ -119,8 +125,8 @@ class Model:
 
     def _quant_act(self, x):
         """Row-quantise an activation: decoded grid values and one scale per row."""
-        ca, sa = e4m3.quantize_rows(x)
-        return e4m3.decode(ca), sa
+        ca, sa = self.q.quantize_rows(x)
+        return self.q.decode(ca), sa
 
     def _linear(self, x, nm, idx, quantised, bias=None, qa=None):
         """x @ W[nm][idx] (+ bias): fp8 GEMM when `quantised`, else fp32 masters in fp64.

@@ -26,14 +26,14 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "n_heads", "d_head", "d_model", "d_mlp", "vocab", "n_ctx",
                                          "norm", "act", "pos")] + \
                [("norm_eps", C.c_float), ("rope_theta", C.c_float)] + \
-               [(n, C.c_int32) for n in ("split_qkv", "precision", "max_batch_edges", "mma")]
+               [(n, C.c_int32) for n in ("split_qkv", "precision", "max_batch_edges", "mma", "low_bits")]
 
     @classmethod
-    def from_shape(cls, shape, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT):
+    def from_shape(cls, shape, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, low_bits=8):
         return cls(n_layers=shape.n_layers, n_heads=shape.n_heads, d_head=shape.d_head, d_model=shape.d_model,
                    d_mlp=shape.d_mlp, vocab=shape.vocab, n_ctx=shape.n_ctx, norm=shape.norm, act=shape.act,
                    pos=shape.pos, norm_eps=shape.norm_eps, rope_theta=shape.rope_theta, split_qkv=1,
-                   precision=precision, max_batch_edges=max_batch_edges, mma=mma)
+                   precision=precision, max_batch_edges=max_batch_edges, mma=mma, low_bits=low_bits)
 
 
 _W_NAMES = ("W_E", "W_pos", "W_Q", "W_K", "W_V", "W_O", "b_Q", "b_K", "b_V", "b_O", "ln1_g", "ln1_b", "ln2_g",
@@ -167,11 +167,11 @@ class Model:
     (layouts as in include/pahq.h)."""
 
     def __init__(self, shape, weights, B, S, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, device="cuda:0",
-                 workspace_bytes_override=None):
+                 workspace_bytes_override=None, low_bits=8):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no HIP device: libpahq has no CPU path")
-        self.cfg = Config.from_shape(shape, precision, max_batch_edges, mma)
+        self.cfg = Config.from_shape(shape, precision, max_batch_edges, mma, low_bits)
         self.B, self.S, self.T = B, S, B * S
         self.n_edges = edge_count(self.cfg)
         nbytes = workspace_bytes(self.cfg, B, S)

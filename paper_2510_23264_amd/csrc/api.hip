@@ -22,6 +22,7 @@ int check_config(const pahq_config* c) {
   if (c->precision < PAHQ_ALL_FP32 || c->precision > PAHQ_PAHQ) return PAHQ_EINVAL;
   if (!(c->norm_eps >= 0.f)) return PAHQ_EINVAL;
   if (c->mma != PAHQ_MMA_FP8 && c->mma != PAHQ_MMA_F16_EXACT) return PAHQ_EINVAL;
+  if (c->low_bits != 0 && c->low_bits != 4 && c->low_bits != 8) return PAHQ_EINVAL;
   return PAHQ_OK;
 }
 // what this build of the kernels supports
@@ -60,6 +61,7 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
   M->nmax = c->max_batch_edges; M->G = 3 * M->H + 1;
   M->all_f32 = c->precision == PAHQ_ALL_FP32;
   M->skip_dead = true;
+  M->qbits = c->low_bits == 4 ? 4 : 8;
   M->deadsum_tag.assign(M->L, -1);
   M->f32_groups = M->all_f32 ? 3 * M->H : 3;
   M->f32_heads_max = M->all_f32 ? M->H : 1;
@@ -154,7 +156,7 @@ int quantise_class(pahq_model* M, const float* w, int n_slices, int K, int N, ui
   HIPCHK(launch_slice_absmax(w, (long long)K * N, n_slices, M->amax_tmp, M->flag_tmp, M->stream));
   for (int i = 0; i < n_slices; i++)
     HIPCHK(launch_quant_transpose(w + (long long)i * K * N, K, N, M->amax_tmp + i, scale0 + (long long)i * scale_stride,
-                                  codes0 + i * codes_stride, ldq, M->stream));
+                                  codes0 + i * codes_stride, ldq, M->qbits, M->stream));
   HIPCHK(hipStreamSynchronize(M->stream));       // amax_tmp is reused by the next class
   return PAHQ_OK;
 }
@@ -782,14 +784,14 @@ int pahq_quantize_rows_site(pahq_model* M, int32_t site, const float* x, int32_t
   for (size_t r0 = 0; r0 < (size_t)rows; r0 += chunk) {
     size_t nr = std::min(chunk, (size_t)rows - r0);
     HIPCHK(hipMemcpyAsync(M->logits, x + r0 * cols, nr * cols * sizeof(float), hipMemcpyHostToDevice, M->stream));
-    if (site == PAHQ_QSITE_HIDDEN) HIPCHK(launch_quant_rows_plain(M->logits, (int)nr, cols, M->xcodes, M->xscale, M->stream));
-    else if (site == PAHQ_QSITE_NORM) HIPCHK(launch_emit_rows(M->logits, (int)nr, cols, M->xcodes, M->xscale, M->stream));
+    if (site == PAHQ_QSITE_HIDDEN) HIPCHK(launch_quant_rows_plain(M->logits, (int)nr, cols, M->xcodes, M->xscale, M->qbits, M->stream));
+    else if (site == PAHQ_QSITE_NORM) HIPCHK(launch_emit_rows(M->logits, (int)nr, cols, M->xcodes, M->xscale, M->qbits, M->stream));
     else {
       // nr sequences of one position and one head whose value row is the given row: the softmax over a single
       // key is 1, so the attention output IS the value row, and what leaves the kernel is its quantisation
       AttnSrc src; memset(&src, 0, sizeof(src));
       src.q = src.k = src.v = M->logits; src.q_ld = src.k_ld = src.v_ld = cols;
-      src.n_heads = 1; src.h0 = 0; src.head_cols = 0;
+      src.n_heads = 1; src.h0 = 0; src.head_cols = 0; src.qbits = M->qbits;
       HIPCHK(launch_attention(src, M->xcodes, 0, M->xscale, 0, nullptr, 0, 0ull, 0ull, 1, (int)nr, 1, 1, cols, (int)ldc, 0, nullptr, M->stream));
     }
     HIPCHK(hipMemcpy2DAsync(codes + r0 * cols, (size_t)cols, M->xcodes, ldc, (size_t)cols, nr, hipMemcpyDeviceToHost, M->stream));

@@ -214,19 +214,19 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
         for (int t = 0; t < NT; t++) am = fmaxf(am, fabsf(z[t][rr]));
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) am = fmaxf(am, __shfl_xor(am, o, 64));
-        float scale = (am == 0.f) ? 1.0f : am / 448.0f;
+        float scale = (am == 0.f) ? 1.0f : am / q_top(src.qbits);
         float inv = 1.0f / scale;
         if (STG) {
           // codes of the 16 x 64 block are collected in this wave's LDS (the k block is no longer needed) and
           // leave as one 16-byte store per lane below, instead of one byte per lane and column tile here
           uint8_t* zb = (uint8_t*)(sq + 1024) + pos * 64 + i;
 #pragma unroll
-          for (int t = 0; t < NT; t++) zb[16 * t] = (uint8_t)e4m3_encode(z[t][rr] * inv);
+          for (int t = 0; t < NT; t++) zb[16 * t] = (uint8_t)q_encode(z[t][rr] * inv, src.qbits);
           if (pos < S && i == 0) zscale[inst * zs_is + tok * H + h] = scale;
         } else if (pos < S) {
           uint8_t* o = zcodes + inst * zc_is + (tok * H + h) * ldz + i;
 #pragma unroll
-          for (int t = 0; t < NT; t++) o[16 * t] = (uint8_t)e4m3_encode(z[t][rr] * inv);
+          for (int t = 0; t < NT; t++) o[16 * t] = (uint8_t)q_encode(z[t][rr] * inv, src.qbits);
           if (i == 0) zscale[inst * zs_is + tok * H + h] = scale;
         }
       }

@@ -42,6 +42,13 @@ __device__ __forceinline__ uint32_t e4m3_encode(float y) {
   return code | sign;
 }
 
+// The grid a quantiser rounds to.  bits == 4: the paper's Eq. RTN-Q with N = 4 as printed -- step = max|x| / 2^(N-1),
+// integer multiples of it, round to nearest (ties to even) -- with the multiple k (|k| <= 8) stored as the E4M3
+// code of the integer k, which is exact, so the matrix products downstream are the same exact machinery.
+// Any other value: E4M3 itself (step = max|x| / 448 at the top of the grid).
+__device__ __forceinline__ float q_top(int bits) { return bits == 4 ? 8.0f : 448.0f; }
+__device__ __forceinline__ uint32_t q_encode(float y, int bits) { return e4m3_encode(bits == 4 ? rintf(y) : y); }
+
 // tanh-form GELU, 0.5 x (1 + tanh(u)) with u = sqrt(2/pi) (x + 0.044715 x^3), written as
 // x / (1 + exp(-2u)): relative accuracy is kept for negative x, where 1 + tanh(u) cancels.  The result
 // feeds the row quantiser, where a relative error e moves about e / 2^-4 of the elements across a rounding

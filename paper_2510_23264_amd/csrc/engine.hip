@@ -676,6 +676,8 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
     b.final_block(run);
   }
 
+  for (GroupDesc& gd : b.groups) gd.qbits = M->qbits;
+  for (AttnSrc& as : b.asrcs) as.qbits = M->qbits;
   // ---- upload the descriptor tables
   Arena& A = M->arena;
   int slot = A.next;
@@ -776,7 +778,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         break;
       case OP_HIDQ:
         HIPCHK(launch_hidden_quant(M->hid, o.i0 == 2 ? M->hid2 : nullptr, (long long)T * M->m, M->hcodes, (long long)T * M->Km,
-                                   M->hscale, T, n, T, M->m, M->Km, o.i0, st));
+                                   M->hscale, T, n, T, M->m, M->Km, o.i0, M->qbits, st));
         break;
       case OP_SWIGLU32: HIPCHK(launch_swiglu_f32(M->hid, M->hid2, (long long)n * T * M->m, st)); break;
       case OP_LD: {

@@ -26,7 +26,7 @@ struct GroupDesc {
   uint8_t* out_codes; long long out_codes_is;   // e4m3 codes, row stride ldq (may be null)
   float* out_scale;   long long out_scale_is;   // one scale per row
   int last_only;      // 1: only the last position of each sequence (B rows per instance)
-  int pad_;
+  int qbits;          // grid of the codes: 4 = 4-bit round-to-nearest, anything else E4M3 (device_util.h, q_encode)
 };
 
 // One GEMM problem.  Rows are numbered 0 .. M-1 over all instances: row m belongs
@@ -109,7 +109,7 @@ hipError_t launch_slice_absmax(const float* w, long long slice_elems, int n_slic
                                int* nonfinite_flag, hipStream_t s);
 // codes_out[(n_off + n) * ldq + k] = e4m3(W[slice][k][n] / scale[slice]),  W slice is [K][N] row-major
 hipError_t launch_quant_transpose(const float* w, int K, int N, const unsigned* amax_bits, float* scale_out,
-                                  uint8_t* codes_out, int ldq, hipStream_t s);
+                                  uint8_t* codes_out, int ldq, int qbits, hipStream_t s);
 
 hipError_t launch_embed(const int* tok, const float* W_E, const float* W_pos, float* out, int T, int S, int d,
                         hipStream_t s);
@@ -157,7 +157,7 @@ struct AttnSrc {
   const float* q; long long q_is; int q_ld; int pad0_;
   const float* k; long long k_is; int k_ld; int pad1_;
   const float* v; long long v_is; int v_ld; int pad2_;
-  int n_heads, h0, head_cols, pad3_;
+  int n_heads, h0, head_cols, qbits;    // qbits: grid of the output codes (device_util.h, q_encode)
 };
 hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is, float* zscale,
                             long long zs_is, float* zf32, long long zf_is, unsigned long long f32_mask, unsigned long long dead_mask, int n_inst, int B, int S,
@@ -170,7 +170,7 @@ hipError_t launch_combine(const CombineDesc* descs, int desc_index, const Combin
 
 // hidden rows [inst][T][m]: h = up (act 0), tanh-GELU(up) (act 1) or silu(gate) * up (act 2); row-quantise.
 hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_is, uint8_t* codes, long long c_is,
-                               float* scale, long long s_is, int n_inst, int T, int m, int ldq, int act,
+                               float* scale, long long s_is, int n_inst, int T, int m, int ldq, int act, int qbits,
                                hipStream_t s);
 
 // logz[b] = log(sum_v exp(logits[b][v]))  (double)
@@ -183,8 +183,8 @@ hipError_t launch_kl(const float* logits, long long l_is, const float* ref_logit
 hipError_t launch_swiglu_f32(float* up, const float* gate, long long n_elem, hipStream_t s);
 
 // the gather / patch kernels' output quantiser on given rows (cols a multiple of 64, at most 4096; codes row stride cols)
-hipError_t launch_emit_rows(const float* x, int rows, int cols, uint8_t* codes, float* scales, hipStream_t s);
-hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales,
+hipError_t launch_emit_rows(const float* x, int rows, int cols, uint8_t* codes, float* scales, int qbits, hipStream_t s);
+hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales, int qbits,
                                    hipStream_t s);
 
 // Logit-difference task metric.  ld[inst * B + b] = logit[answer[b]] - logit[distractor[b]] of row (inst, b), from the

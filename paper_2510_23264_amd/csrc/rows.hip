@@ -53,10 +53,10 @@ hipError_t launch_slice_absmax(const float* w, long long slice_elems, int n_slic
 
 // W slice [K][N] row-major -> codes [N][ldq] (K contiguous), through a 32x32 LDS transpose.
 __global__ void quant_transpose_k(const float* w, int K, int N, const unsigned* amax_bits, float* scale_out,
-                                  uint8_t* codes, int ldq) {
+                                  uint8_t* codes, int ldq, int qbits) {
   __shared__ float tile[32][33];
   float amax = __uint_as_float(*amax_bits);
-  float scale = (amax == 0.f) ? 1.0f : amax / 448.0f;
+  float scale = (amax == 0.f) ? 1.0f : amax / q_top(qbits);
   float inv = 1.0f / scale;
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && threadIdx.y == 0) *scale_out = scale;
   int k0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
@@ -67,13 +67,13 @@ __global__ void quant_transpose_k(const float* w, int K, int N, const unsigned* 
   __syncthreads();
   for (int r = threadIdx.y; r < 32; r += 8) {
     int n = n0 + r, k = k0 + threadIdx.x;
-    if (n < N && k < K) codes[(long long)n * ldq + k] = (uint8_t)e4m3_encode(tile[threadIdx.x][r] * inv);
+    if (n < N && k < K) codes[(long long)n * ldq + k] = (uint8_t)q_encode(tile[threadIdx.x][r] * inv, qbits);
   }
 }
 hipError_t launch_quant_transpose(const float* w, int K, int N, const unsigned* amax_bits, float* scale_out,
-                                  uint8_t* codes_out, int ldq, hipStream_t s) {
+                                  uint8_t* codes_out, int ldq, int qbits, hipStream_t s) {
   hipLaunchKernelGGL(quant_transpose_k, dim3((N + 31) / 32, (K + 31) / 32), dim3(32, 8), 0, s, w, K, N,
-                     amax_bits, scale_out, codes_out, ldq);
+                     amax_bits, scale_out, codes_out, ldq, qbits);
   return hipGetLastError();
 }
 
@@ -205,19 +205,20 @@ __device__ __forceinline__ void emit_row(const float (&y)[MAXE], int E, int d, i
 #pragma unroll
     for (int j = 0; j < MAXE; j++) if (j < E) am = fmaxf(am, fabsf(y[j]));
     am = wave_max(am);
-    float scale = (am == 0.f) ? 1.0f : am / 448.0f;
+    const int qb = g.qbits;
+    float scale = (am == 0.f) ? 1.0f : am / q_top(qb);
     float inv = 1.0f / scale;
     uint8_t* o = g.out_codes + inst * g.out_codes_is + (long long)row * ldq;
     if (VEC) {
 #pragma unroll
       for (int q = 0; q < MAXE / 4; q++) if (4 * q < E) {
-        uint32_t w = e4m3_encode(y[4 * q] * inv) | (e4m3_encode(y[4 * q + 1] * inv) << 8) |
-                     (e4m3_encode(y[4 * q + 2] * inv) << 16) | (e4m3_encode(y[4 * q + 3] * inv) << 24);
+        uint32_t w = q_encode(y[4 * q] * inv, qb) | (q_encode(y[4 * q + 1] * inv, qb) << 8) |
+                     (q_encode(y[4 * q + 2] * inv, qb) << 16) | (q_encode(y[4 * q + 3] * inv, qb) << 24);
         *(uint32_t*)(o + (q * 64 + lane) * 4) = w;
       }
     } else {
 #pragma unroll
-      for (int j = 0; j < MAXE; j++) if (j < E) o[lane + 64 * j] = (uint8_t)e4m3_encode(y[j] * inv);
+      for (int j = 0; j < MAXE; j++) if (j < E) o[lane + 64 * j] = (uint8_t)q_encode(y[j] * inv, qb);
     }
     if (lane == 0) g.out_scale[inst * g.out_scale_is + row] = scale;
   }
@@ -523,7 +524,7 @@ __device__ __forceinline__ float hidden_value(const float* up, const float* gate
 
 __global__ __launch_bounds__(256) void hidden_quant_k(const float* up, const float* gate, long long h_is,
                                                       uint8_t* codes, long long c_is, float* scale, long long s_is,
-                                                      int T, int m, int ldq, int act) {
+                                                      int T, int m, int ldq, int act, int qbits) {
   __shared__ float red[4];
   int inst = blockIdx.y, row = blockIdx.x;
   const float* pu = up + inst * h_is + (long long)row * m;
@@ -534,10 +535,10 @@ __global__ __launch_bounds__(256) void hidden_quant_k(const float* up, const flo
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = am;
   __syncthreads();
   am = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  float sc = (am == 0.f) ? 1.0f : am / 448.0f;
+  float sc = (am == 0.f) ? 1.0f : am / q_top(qbits);
   float inv = 1.0f / sc;
   uint8_t* o = codes + inst * c_is + (long long)row * ldq;
-  for (int i = threadIdx.x; i < m; i += 256) o[i] = (uint8_t)e4m3_encode(hidden_value(pu, pg, i, act) * inv);
+  for (int i = threadIdx.x; i < m; i += 256) o[i] = (uint8_t)q_encode(hidden_value(pu, pg, i, act) * inv, qbits);
   if (threadIdx.x == 0) scale[inst * s_is + row] = sc;
 }
 // The same quantiser for rows of 4-float multiples: TPR threads own a row (a wavefront, or the
@@ -547,7 +548,7 @@ __global__ __launch_bounds__(256) void hidden_quant_k(const float* up, const flo
 template <int TPR, int NV, int ACT>
 __global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const float* gate, long long h_is,
                                                           uint8_t* codes, long long c_is, float* scale,
-                                                          long long s_is, int T, int m, int ldq) {
+                                                          long long s_is, int T, int m, int ldq, int qbits) {
   constexpr int act = ACT;
   constexpr int RPB = 256 / TPR;
   __shared__ float red[4];
@@ -587,15 +588,15 @@ __global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const
     am = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   }
   if (!live) return;
-  const float sc = (am == 0.f) ? 1.0f : am / 448.0f;
+  const float sc = (am == 0.f) ? 1.0f : am / q_top(qbits);
   const float inv = 1.0f / sc;
   uint8_t* o = codes + inst * c_is + (long long)row * ldq;
 #pragma unroll
   for (int j = 0; j < NV; j++) {
     int e = (j * TPR + t) * 4;
     if (e < m) {
-      uint32_t w = e4m3_encode(v[j].x * inv) | (e4m3_encode(v[j].y * inv) << 8) | (e4m3_encode(v[j].z * inv) << 16) |
-                   (e4m3_encode(v[j].w * inv) << 24);
+      uint32_t w = q_encode(v[j].x * inv, qbits) | (q_encode(v[j].y * inv, qbits) << 8) | (q_encode(v[j].z * inv, qbits) << 16) |
+                   (q_encode(v[j].w * inv, qbits) << 24);
       *(uint32_t*)(o + e) = w;
     }
   }
@@ -603,13 +604,13 @@ __global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const
 }
 
 hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_is, uint8_t* codes, long long c_is,
-                               float* scale, long long s_is, int n_inst, int T, int m, int ldq, int act,
+                               float* scale, long long s_is, int n_inst, int T, int m, int ldq, int act, int qbits,
                                hipStream_t s) {
   const bool vec = (m % 4 == 0) && (ldq % 4 == 0) && (h_is % 4 == 0) && (c_is % 4 == 0) &&
                    ((((uintptr_t)up) | ((uintptr_t)gate)) % 16 == 0) && (((uintptr_t)codes) % 4 == 0);
 #define HQV_(TPR_, NV_, ACT_)                                                                                    \
   hipLaunchKernelGGL((hidden_quant_vec_k<TPR_, NV_, ACT_>), dim3((T + 256 / TPR_ - 1) / (256 / TPR_), n_inst),   \
-                     dim3(256), 0, s, up, gate, h_is, codes, c_is, scale, s_is, T, m, ldq)
+                     dim3(256), 0, s, up, gate, h_is, codes, c_is, scale, s_is, T, m, ldq, qbits)
 #define HQV(TPR_, NV_)                                                                                           \
   do {                                                                                                           \
     if (act == 1) HQV_(TPR_, NV_, 1); else if (act == 2) HQV_(TPR_, NV_, 2); else HQV_(TPR_, NV_, 0);            \
@@ -621,7 +622,7 @@ hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_i
   else if (vec && m <= 256 * 4 * 12) HQV(256, 12);
   else
     hipLaunchKernelGGL(hidden_quant_k, dim3(T, n_inst), dim3(256), 0, s, up, gate, h_is, codes, c_is, scale, s_is,
-                       T, m, ldq, act);
+                       T, m, ldq, act, qbits);
 #undef HQV
 #undef HQV_
   return hipGetLastError();
@@ -642,7 +643,7 @@ hipError_t launch_swiglu_f32(float* up, const float* gate, long long n_elem, hip
 // The quantiser at the end of the gather / patch kernels (emit_row) on given rows: one wavefront per row, the
 // row in the element map those kernels use.  cols a multiple of 64, at most 4096.
 template <int MAXE, bool VEC>
-__global__ __launch_bounds__(256) void emit_rows_k(const float* x, int rows, int d, uint8_t* codes, float* scales) {
+__global__ __launch_bounds__(256) void emit_rows_k(const float* x, int rows, int d, uint8_t* codes, float* scales, int qbits) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -652,22 +653,22 @@ __global__ __launch_bounds__(256) void emit_rows_k(const float* x, int rows, int
   for (int j = 0; j < MAXE; j++) y[j] = 0.f;
   row_load<MAXE, VEC>(y, x + (long long)row * d, E, lane);
   GroupDesc g;
-  g.out_f32 = nullptr; g.out_codes = codes; g.out_codes_is = 0; g.out_scale = scales; g.out_scale_is = 0;
+  g.out_f32 = nullptr; g.out_codes = codes; g.out_codes_is = 0; g.out_scale = scales; g.out_scale_is = 0; g.qbits = qbits;
   emit_row<MAXE, VEC>(y, E, d, lane, g, 0, row, d);
 }
-hipError_t launch_emit_rows(const float* x, int rows, int cols, uint8_t* codes, float* scales, hipStream_t s) {
+hipError_t launch_emit_rows(const float* x, int rows, int cols, uint8_t* codes, float* scales, int qbits, hipStream_t s) {
   if (rows == 0) return hipSuccess;
   if (cols % 64 != 0 || cols > 4096) return hipErrorInvalidValue;
   dim3 grid((rows + 3) / 4);
-#define CALL(M, V) hipLaunchKernelGGL((emit_rows_k<M, V>), grid, dim3(256), 0, s, x, rows, cols, codes, scales)
+#define CALL(M, V) hipLaunchKernelGGL((emit_rows_k<M, V>), grid, dim3(256), 0, s, x, rows, cols, codes, scales, qbits)
   PAHQ_DISPATCH_E(cols / 64, CALL);
 #undef CALL
   return hipGetLastError();
 }
 
-hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales,
+hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* codes, float* scales, int qbits,
                                    hipStream_t s) {
-  return launch_hidden_quant(x, nullptr, 0LL, codes, 0LL, scales, 0LL, 1, rows, cols, cols, 0, s);
+  return launch_hidden_quant(x, nullptr, 0LL, codes, 0LL, scales, 0LL, 1, rows, cols, cols, 0, qbits, s);
 }
 
 }  // namespace pahq

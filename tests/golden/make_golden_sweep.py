@@ -10,10 +10,13 @@ receivers and thresholds and compares step by step.
               every other node dead)
   cfg3_keep   a threshold of 3e-4 (in a wide gap of the increments into the output node), restricted to the output node and three receivers of the
               top layer: a circuit with kept edges
-  cfg4        the top MLP input of the config's seeded receiver sample (and the sample's top head input at
-              the config's own threshold)
+  cfg4        the top MLP input of the config's seeded receiver sample at two thresholds: 1e-4 (above every
+              increment: all 408 in-edges go, one by one, into an ever larger removed set) and 4e-5 (in the
+              widest gap of those increments: edges are kept)
 
-usage: python tests/golden/make_golden_sweep.py cfg2|cfg3|cfg3_keep|cfg4
+usage: python tests/golden/make_golden_sweep.py cfg2|cfg3|cfg3_keep|cfg4 [--resume]
+  --resume    keep the runs an existing output file already holds for the same (threshold, receivers)
+              (a run of config 4 takes more than an hour)
 """
 import json
 import os
@@ -39,8 +42,7 @@ def runs_for(name, g, L, spec):
     if name == "cfg4":
         sample = [int(r) for r in synth.make_receiver_sample(g.n_receivers, spec["n_recv"], spec["seed"])]
         assert g.mlpin(top) in sample
-        heads = [r for r in sample if g.receiver_info(r)[0] == "headin" and g.receiver_info(r)[1] == top]
-        return "cfg4", [(1e-4, [g.mlpin(top)]), (spec["taus"][0], [g.mlpin(top), max(heads)])]
+        return "cfg4", [(1e-4, [g.mlpin(top)]), (4e-5, [g.mlpin(top)])]
     raise SystemExit("no sweep defined for " + name)
 
 
@@ -52,7 +54,19 @@ def main():
     oa = Acdc(Model(shape, w), clean, corrupt)
     cfg, runs = runs_for(name, oa.g, shape.n_layers, spec)
     out = {"config": cfg, "seed": spec["seed"], "runs": []}
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "sweep_%s.json" % name)
+    have = {}
+    if "--resume" in sys.argv[2:] and os.path.exists(path):
+        with open(path) as f:
+            old = json.load(f)
+        if old.get("config") == cfg and old.get("seed") == spec["seed"]:
+            have = {(r["tau"], None if r["receivers"] is None else tuple(r["receivers"])): r for r in old["runs"]}
     for tau, recv in runs:
+        key = (tau, None if recv is None else tuple(int(r) for r in recv))
+        if key in have:
+            out["runs"].append(have[key])
+            print(name, "tau", tau, "kept from the existing file", flush=True)
+            continue
         removed, trace = oa.sweep(tau, receivers=recv,
                                   progress=lambda v, n, r: print(name, "tau", tau, "receiver", v, "evals", n, "removed", r,
                                                                  "t=%.0fs" % (time.time() - t0), flush=True))
@@ -60,7 +74,6 @@ def main():
                             "trace": [[int(v), int(u), kn, kc, bool(rm)] for v, u, kn, kc, rm in trace],
                             "removed": [int(x) for x in oa.g.removed_to_flat(removed).nonzero()[0]]})
         print(name, "tau", tau, "evals", len(trace), "removed", len(out["runs"][-1]["removed"]), "t=%.0fs" % (time.time() - t0), flush=True)
-        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "sweep_%s.json" % name)
         with open(path, "w") as f:
             json.dump(out, f)
     print("wrote", path, "in %.0f s" % (time.time() - t0))

@@ -34,16 +34,19 @@ SITES = ("act:q", "act:k", "act:v", "w:q", "w:k", "w:v", "act:o", "w:o",
          "act:in", "w:in", "w:gate", "act:out", "w:out", "act:u", "w:u")
 
 
+_CODEC = [e4m3]      # the grid of the quantised operands (loop_forward's `codec` argument)
+
+
 def _qrows(x):
-    """Dequantised rows: e4m3 codes x one scale per row."""
-    codes, scale = e4m3.quantize_rows(np.asarray(x, dtype=np.float32))
-    return e4m3.decode(codes) * scale.astype(np.float64)[:, None]
+    """Dequantised rows: grid points x one scale per row."""
+    codes, scale = _CODEC[0].quantize_rows(np.asarray(x, dtype=np.float32))
+    return _CODEC[0].decode(codes) * scale.astype(np.float64)[:, None]
 
 
 def _qall(w):
-    """Dequantised matrix: e4m3 codes x one scale for the whole slice."""
-    codes, scale = e4m3.quantize_groups(np.asarray(w, dtype=np.float32), axis=None)
-    return e4m3.decode(codes) * np.float64(scale)
+    """Dequantised matrix: grid points x one scale for the whole slice."""
+    codes, scale = _CODEC[0].quantize_groups(np.asarray(w, dtype=np.float32), axis=None)
+    return _CODEC[0].decode(codes) * np.float64(scale)
 
 
 def _matmul(x, w, low, drop, act_site, w_site):
@@ -65,8 +68,10 @@ def _is_upstream(sender, receiver):
     return ls < receiver[1] or (ls == receiver[1] and sender[0] == "head")      # MLP input
 
 
-def loop_forward(shape, w, tokens, pi=frozenset(), quantise=True, removed=frozenset(), other=None, drop=None):
-    """Returns (outputs: dict sender -> [T][d], logits [B][vocab] at the last position)."""
+def loop_forward(shape, w, tokens, pi=frozenset(), quantise=True, removed=frozenset(), other=None, drop=None, codec=None):
+    """Returns (outputs: dict sender -> [T][d], logits [B][vocab] at the last position).
+    codec: the quantiser (quantize_rows / quantize_groups / decode); default the separately pinned e4m3 codec."""
+    _CODEC[0] = e4m3 if codec is None else codec
     L, H, dh, d, m = shape.n_layers, shape.n_heads, shape.d_head, shape.d_model, shape.d_mlp
     B, S = tokens.shape
     T = B * S
