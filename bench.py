@@ -3,7 +3,7 @@
 
 Workload (config 3, GPT-2-small shape, seeded synthetic weights and tokens):
 one step = one pass over the whole split-QKV graph, every one of its 32 491
-edges evaluated once by pahq_eval_edges against the empty removed set under
+edges evaluated once by pahq_eval_edge_list against the empty removed set under
 PAHQ precision (fp32 investigated head, everything else FP8 E4M3 operands).
 That is one patched forward + KL per edge: the paper's per-edge cost
 (Appendix "Integration with ACDC", third inference; Eq. Delta L), with the
@@ -79,15 +79,23 @@ def traffic_from_profile(regime, kernel_class, workload_key):
 
 
 def all_edges_pass(gm, P, cfg, receivers, stride=1):
-    """Every in-edge of the given receivers (descending, as the sweep visits them), once."""
+    """Every in-edge of the given receivers, once, layer by layer from the top (as the sweep visits them), through
+    pahq_eval_edge_list: within a layer the query, key and value inputs of a head follow each other in that
+    order, so that their candidates share device batches."""
     n, t_last = 0, time.perf_counter()
-    todo = receivers[::-1][::stride]
-    for i, r in enumerate(todo):
-        senders = np.arange(P.n_upstream(cfg, int(r)), dtype=np.int32)
-        gm.eval_edges(int(r), senders)
-        n += senders.size
+    todo = [int(r) for r in receivers[::-1][::stride]]
+    per_layer = 3 * cfg.n_heads + (1 if cfg.d_mlp > 0 else 0)
+    chunks = {}
+    for r in todo:
+        chunks.setdefault(r // per_layer, []).append(r)
+    for i, layer in enumerate(sorted(chunks, reverse=True)):
+        rs = sorted(chunks[layer], key=lambda r: (-((r % per_layer) // 3), (r % per_layer) % 3))     # heads descending, q k v ascending
+        recv = np.concatenate([np.full(P.n_upstream(cfg, r), r, np.int32) for r in rs])
+        send = np.concatenate([np.arange(P.n_upstream(cfg, r), dtype=np.int32) for r in rs])
+        gm.eval_edge_list(recv, send)
+        n += send.size
         if time.perf_counter() - t_last > 30.0:          # long passes (the large configs) say where they are
-            print(f"bench.py: receiver {i + 1} of {len(todo)}, {n} edges", file=sys.stderr, flush=True)
+            print(f"bench.py: layer {layer} ({i + 1} of {len(chunks)}), {n} edges", file=sys.stderr, flush=True)
             t_last = time.perf_counter()
     return n
 

@@ -194,6 +194,18 @@ int pahq_set_metric(pahq_model*, int32_t metric, const int32_t* answer_ids, cons
  * pahq_eval_current. */
 int pahq_eval_edges(pahq_model*, int32_t receiver, const int32_t* sender_ids, int32_t n, float* kl_out);
 
+/* The same evaluation for a list of candidate edges into any receivers: kl_out[i] is, bit for bit, what
+ * pahq_eval_edges returns for the edge (sender_ids[i] -> receivers[i]) -- each candidate judged on its own, on top
+ * of the current removed set, under the precision set of ITS receiver (Eq. Delta L; third inference of the
+ * paper's algorithm) -- and the removed set is not modified.  receivers, sender_ids: host, n entries; kl_out: host,
+ * n floats.  The list is taken in the order given: neighbouring entries with the same receiver form one run, and
+ * with PAHQ_PAHQ up to three neighbouring runs that are the query, key and value inputs of one head, in that order,
+ * share device batches (their candidates have the same fp32 head, the same reference and the same layer state and
+ * differ in which of the head's three projections reads the patched input), which fills the batches of the early
+ * layers, where a single receiver has few senders.  The condition on the removed set is that of pahq_eval_edges, for
+ * every receiver of the list; a receiver that violates it gives PAHQ_ESTATE (results before it are written). */
+int pahq_eval_edge_list(pahq_model*, int64_t n, const int32_t* receivers, const int32_t* sender_ids, float* kl_out);
+
 /* KL of the current removed set itself under the precision set of `receiver`. */
 int pahq_eval_current(pahq_model*, int32_t receiver, float* kl_out);
 

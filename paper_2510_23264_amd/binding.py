@@ -77,6 +77,7 @@ def lib():
                                 C.POINTER(C.c_void_p)],
             "pahq_clean_cache": [C.c_void_p, i32p, i32p],
             "pahq_eval_edges": [C.c_void_p, C.c_int32, i32p, C.c_int32, f32p],
+            "pahq_eval_edge_list": [C.c_void_p, C.c_int64, i32p, i32p, f32p],
             "pahq_eval_current": [C.c_void_p, C.c_int32, f32p],
             "pahq_acdc_sweep": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
             "pahq_eval_edges_sender_policy": [C.c_void_p, C.c_int32, i32p, C.c_int32, f32p, f32p],
@@ -238,6 +239,16 @@ class Model:
         out = np.empty(s.size, dtype=np.float32)
         _chk(lib().pahq_eval_edges(self.h, int(receiver), _ptr(s, C.c_int32), s.size, _ptr(out, C.c_float)),
              "pahq_eval_edges")
+        return out
+
+    def eval_edge_list(self, receivers, sender_ids):
+        r = np.ascontiguousarray(receivers, dtype=np.int32)
+        s = np.ascontiguousarray(sender_ids, dtype=np.int32)
+        if r.shape != s.shape or r.ndim != 1:
+            raise ValueError("receivers and sender_ids: one entry per edge")
+        out = np.empty(s.size, dtype=np.float32)
+        _chk(lib().pahq_eval_edge_list(self.h, s.size, _ptr(r, C.c_int32), _ptr(s, C.c_int32), _ptr(out, C.c_float)),
+             "pahq_eval_edge_list")
         return out
 
     def eval_current(self, receiver):

@@ -114,7 +114,7 @@ size_t layout(pahq_model* M, char* base) {
   M->cpi = b.take<float>(Ns * tile); M->rxpi = b.take<float>((2 * L + 1) * tile);
   M->ref_logits = b.take<float>(B * Vp); M->ref_logz = b.take<double>(B);
   M->xv = b.take<float>(tile);
-  M->qkv_sh = b.take<float>(T * 3 * H * dh); M->oth = b.take<float>(tile); M->deadsum = b.take<float>(L * tile); M->sh_slots = b.take<float>(H * tile);
+  M->qkv_sh = b.take<float>(T * 3 * H * dh); M->oth = b.take<float>(tile); M->xvc = b.take<float>(3 * tile); M->deadsum = b.take<float>(L * tile); M->sh_slots = b.take<float>(H * tile);
   M->qv = b.take<float>(n * T * dh);
   M->run_a = b.take<float>(n * tile); M->run_b = b.take<float>(n * tile);
   M->xcodes = b.take<uint8_t>(n * G * T * Kd); M->xscale = b.take<float>(n * G * T); M->xf32 = b.take<float>(std::max<size_t>(n * (size_t)M->f32_groups, 3 * H) * tile);
@@ -181,6 +181,24 @@ int upload_table(pahq_model* M, const void* src, size_t bytes, void** dev_out) {
 
 struct RecvCtx { int v, p0, pl, ph, n_eff; };
 
+// dst = receiver w's input under the current removed set, from the cached streams and sender tiles (every sender
+// upstream of w is cached); the plan must hold w's spec
+int build_receiver_input(pahq_model* M, int w, int p0, float* dst) {
+  const RecvSpec& sp = M->plan.spec[w];
+  float* base = sp.form == 2 ? corrupt_prefix(M, p0) : clean_prefix(M, p0);
+  std::vector<Term> terms;
+  for (int s : sp.senders) {
+    Term t; t.p = M->delta + (long long)s * M->tile; t.inst_stride = 0; t.sign = sp.form == 1 ? -1.f : 1.f; t.pad_ = 0;
+    terms.push_back(t);
+  }
+  void* dterms = nullptr;
+  if (!terms.empty()) PCHK(upload_table(M, terms.data(), terms.size() * sizeof(Term), &dterms));
+  // the stream goes in after the removed senders' terms (form 1), a corrupted-run base before the kept ones
+  // (form 2): the order in which the row kernels add the same sum when they build this input for the current state
+  HIPCHK(launch_tile_lincomb(dst, base, (const Term*)dterms, (int)terms.size(), M->tile, sp.form == 1 ? 1 : 0, M->stream));
+  return PAHQ_OK;
+}
+
 // Brings the model into the state needed to evaluate edges into receiver v:
 // the state of v's fp32 head (corrupted run + reference distribution under that
 // precision set), the receiver plan for the current removed set, and v's
@@ -209,19 +227,7 @@ int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
   ctx.n_eff = M->nmax;
   if (M->plan.n_slots > 0) ctx.n_eff = (int)std::min<long long>(M->nmax, M->pool_tiles / M->plan.n_slots);
   if (ctx.n_eff < 1) return PAHQ_ENOMEM;
-  // xv = v's input under the current removed set (every sender upstream of v is cached)
-  const RecvSpec& sp = M->plan.spec[v];
-  float* base = sp.form == 2 ? corrupt_prefix(M, ctx.p0) : clean_prefix(M, ctx.p0);
-  std::vector<Term> terms;
-  for (int s : sp.senders) {
-    Term t; t.p = M->delta + (long long)s * M->tile; t.inst_stride = 0; t.sign = sp.form == 1 ? -1.f : 1.f; t.pad_ = 0;
-    terms.push_back(t);
-  }
-  void* dterms = nullptr;
-  if (!terms.empty()) PCHK(upload_table(M, terms.data(), terms.size() * sizeof(Term), &dterms));
-  // the stream goes in after the removed senders' terms (form 1), a corrupted-run base before the kept ones
-  // (form 2): the order in which the row kernels add the same sum when they build this input for the current state
-  HIPCHK(launch_tile_lincomb(M->xv, base, (const Term*)dterms, (int)terms.size(), M->tile, sp.form == 1 ? 1 : 0, M->stream));
+  PCHK(build_receiver_input(M, v, ctx.p0, M->xv));
   if (M->plan.split_first) {
     // everything in v's layer that does not depend on the candidate: the other heads, and the
     // investigated head's two unpatched inputs
@@ -451,6 +457,42 @@ int pahq_set_metric(pahq_model* M, int32_t metric, const int32_t* answer_ids, co
   return PAHQ_OK;
 }
 
+// Independent candidates (sender_ids[i] -> receiver) for one receiver, or -- recv3 -- for the query, key and value
+// inputs of one head side by side: cnt[c] candidates of channel c, senders and results in channel order.  The device
+// batches of a call are queued back to back and the host waits once per ncap candidates: batch b reads its senders
+// from send_dev + off and writes its results to kl_dev + off.
+static int eval_candidates(pahq_model* M, const RecvCtx& ctx, const int* recv3, const int* cnt3, const int32_t* sender_ids, int n,
+                           float* kl_out) {
+  // receiver of candidate i
+  auto recv_of = [&](int i) { if (!recv3) return ctx.v; int c = 0; while (i >= cnt3[c]) { i -= cnt3[c]; c++; } return recv3[c]; };
+  for (int pos = 0; pos < n;) {
+    const int chunk = std::min(M->ncap, n - pos);
+    for (int off = 0; off < chunk;) {
+      // batches of equal size: 131 candidates run as 66 + 65, not as 128 + 3 (a batch of three pays a full
+      // batch's launches and leaves most compute units idle)
+      const int left = chunk - off, parts = (left + ctx.n_eff - 1) / ctx.n_eff;
+      int nb = (left + parts - 1) / parts;
+      PassArgs a; a.kind = CAND; a.p0 = ctx.p0; a.n = nb; a.pl = ctx.pl; a.ph = ctx.ph; a.v = ctx.v; a.patch_mode = 1;
+      a.io_off = off;
+      // an edge that is already removed adds nothing: such a candidate patches with the all-zero tile
+      for (int i = 0; i < nb; i++) {
+        const int u = sender_ids[pos + off + i], w = recv_of(pos + off + i);
+        M->send_host[off + i] = M->removed[edge_index(M, u, w)] ? M->g.Ns : u;
+        if (recv3) { int k, l, h, c; M->g.receiver_info(w, k, l, h, c); a.chan_count[c]++; }
+      }
+      HIPCHK(hipMemcpyAsync(M->send_dev + off, M->send_host + off, (size_t)nb * sizeof(int), hipMemcpyHostToDevice, M->stream));
+      PCHK(run_pass(M, a, &M->plan));
+      M->counters[0] += nb; M->counters[1] += 1;
+      off += nb;
+    }
+    HIPCHK(hipMemcpyAsync(M->kl_host, M->kl_dev, (size_t)chunk * sizeof(double), hipMemcpyDeviceToHost, M->stream));
+    HIPCHK(hipStreamSynchronize(M->stream));
+    for (int i = 0; i < chunk; i++) kl_out[pos + i] = (float)M->kl_host[i];
+    pos += chunk;
+  }
+  return PAHQ_OK;
+}
+
 int pahq_eval_edges(pahq_model* M, int32_t receiver, const int32_t* sender_ids, int32_t n, float* kl_out) {
   if (!M || n < 0 || (n > 0 && (!sender_ids || !kl_out))) return PAHQ_EINVAL;
   if (receiver < 0 || receiver >= M->g.Nr) return PAHQ_EINVAL;
@@ -460,32 +502,50 @@ int pahq_eval_edges(pahq_model* M, int32_t receiver, const int32_t* sender_ids, 
   if (n == 0) return PAHQ_OK;
   RecvCtx ctx;
   PCHK(setup_receiver(M, receiver, ctx));
-  // Candidates are independent, so the device batches of a call are queued back to back and the
-  // host waits once per ncap candidates: batch b reads its senders from send_dev + off and writes
-  // its results to kl_dev + off.
-  for (int pos = 0; pos < n;) {
-    const int chunk = std::min(M->ncap, n - pos);
-    for (int off = 0; off < chunk;) {
-      // batches of equal size: 131 candidates run as 66 + 65, not as 128 + 3 (a batch of three pays a full
-      // batch's launches and leaves most compute units idle)
-      const int left = chunk - off, parts = (left + ctx.n_eff - 1) / ctx.n_eff;
-      int nb = (left + parts - 1) / parts;
-      // an edge that is already removed adds nothing: such a candidate patches with the all-zero tile
-      for (int i = 0; i < nb; i++) {
-        int u = sender_ids[pos + off + i];
-        M->send_host[off + i] = M->removed[edge_index(M, u, receiver)] ? M->g.Ns : u;
-      }
-      HIPCHK(hipMemcpyAsync(M->send_dev + off, M->send_host + off, (size_t)nb * sizeof(int), hipMemcpyHostToDevice, M->stream));
-      PassArgs a; a.kind = CAND; a.p0 = ctx.p0; a.n = nb; a.pl = ctx.pl; a.ph = ctx.ph; a.v = ctx.v; a.patch_mode = 1;
-      a.io_off = off;
-      PCHK(run_pass(M, a, &M->plan));
-      M->counters[0] += nb; M->counters[1] += 1;
-      off += nb;
+  return eval_candidates(M, ctx, nullptr, nullptr, sender_ids, n, kl_out);
+}
+
+int pahq_eval_edge_list(pahq_model* M, int64_t n, const int32_t* receivers, const int32_t* sender_ids, float* kl_out) {
+  if (!M || n < 0 || (n > 0 && (!receivers || !sender_ids || !kl_out))) return PAHQ_EINVAL;
+  if (!M->has_cache) return PAHQ_ESTATE;
+  const GraphDims& g = M->g;
+  for (int64_t i = 0; i < n; i++) {
+    if (receivers[i] < 0 || receivers[i] >= g.Nr) return PAHQ_EINVAL;
+    if (sender_ids[i] < 0 || sender_ids[i] >= g.n_upstream(receivers[i])) return PAHQ_EINVAL;
+  }
+  // runs of one receiver; up to three neighbouring runs that are the query, key and value inputs of one head
+  // (each at most once, in channel order) go to the device side by side when that head is the fp32 head of all three
+  for (int64_t i = 0; i < n;) {
+    int recv3[3] = {-1, -1, -1}, cnt3[3] = {0, 0, 0};
+    int k0, l0, h0, c0;
+    g.receiver_info(receivers[i], k0, l0, h0, c0);
+    int runs = 0, last_c = -1;
+    int64_t j = i;
+    while (j < n && runs < 3) {
+      int k, l, h, c;
+      g.receiver_info(receivers[j], k, l, h, c);
+      const bool joins = runs == 0 || (M->cfg.precision == PAHQ_PAHQ && k0 == 0 && k == 0 && l == l0 && h == h0 && c > last_c);
+      if (!joins) break;
+      int64_t r = j;
+      while (r < n && receivers[r] == receivers[j]) r++;
+      if (r - i > 0x7fffffff) return PAHQ_ETOOBIG;
+      if (k == 0) { recv3[c] = receivers[j]; cnt3[c] = (int)(r - j); }
+      last_c = k == 0 ? c : 3;
+      runs++;
+      j = r;
+      if (k != 0) break;
     }
-    HIPCHK(hipMemcpyAsync(M->kl_host, M->kl_dev, (size_t)chunk * sizeof(double), hipMemcpyDeviceToHost, M->stream));
-    HIPCHK(hipStreamSynchronize(M->stream));
-    for (int i = 0; i < chunk; i++) kl_out[pos + i] = (float)M->kl_host[i];
-    pos += chunk;
+    RecvCtx ctx;
+    PCHK(setup_receiver(M, receivers[i], ctx));
+    if (runs == 1) {
+      PCHK(eval_candidates(M, ctx, nullptr, nullptr, sender_ids + i, (int)(j - i), kl_out + i));
+    } else {
+      // the three inputs share the head's state, the plan and the layer's shared part; each has its own current input
+      for (int c = 0; c < 3; c++)
+        if (recv3[c] >= 0) PCHK(build_receiver_input(M, recv3[c], ctx.p0, M->xvc + (long long)c * M->tile));
+      PCHK(eval_candidates(M, ctx, recv3, cnt3, sender_ids + i, (int)(j - i), kl_out + i));
+    }
+    i = j;
   }
   return PAHQ_OK;
 }

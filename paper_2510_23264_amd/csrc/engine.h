@@ -22,6 +22,9 @@ struct PassArgs {
   int io_off = 0;      // first element of send_dev / kl_dev this pass reads / writes
   const unsigned long long* heads = nullptr;   // per layer: bit h set = head h in fp32 (a set of fp32 heads instead of (pl, ph))
   bool keep_logits = false;                    // a scored pass also stores its logits (M->logits)
+  int chan_count[3] = {0, 0, 0};               // CAND into a head input with an fp32 head: when not all zero, the first
+                                               // chan_count[0] instances patch the head's query input, the next its key
+                                               // input, the rest its value input (their current inputs in M->xvc)
 };
 
 struct Arena {          // descriptor staging: pinned host mirror + device copy, a small ring
@@ -69,7 +72,7 @@ struct pahq_model {
   int f32_groups;                         // receiver-input groups of a layer that may need fp32 rows (per instance)
   int f32_heads_max;                      // heads whose attention output may be needed unquantised (per instance)
   float* xv;                              // current input of the receiver under evaluation
-  float *qkv_sh, *oth, *deadsum, *sh_slots, *qv;    // first-layer state shared by all candidates of a receiver
+  float *qkv_sh, *oth, *deadsum, *sh_slots, *qv, *xvc;    // xvc: three tiles, the current inputs of a head's query / key / value receivers    // first-layer state shared by all candidates of a receiver
   float *run_a, *run_b;                   // [nmax] tiles each
   uint8_t* xcodes; float* xscale; float* xf32;
   float* qkv; uint8_t* zcodes; float* zscale; float* zf32;

@@ -151,12 +151,13 @@ struct Builder {
     ops.back().bytes = by * a.n;
   }
   // the edge-batched patch of group gi: per instance one delta tile (+ the shared current input once)
-  void add_patch(int gi) {
-    add_op(OP_PATCH, gi);
+  void add_patch(int gi, int inst0 = 0, int count = 0, float* xv = nullptr) {
+    const int n = count ? count : a.n;        // instances inst0 .. inst0 + n - 1 (the group's outputs start at inst0)
+    add_op(OP_PATCH, gi, inst0, n, 0, xv ? xv : M->xv);
     const GroupDesc& gd = groups[gi];
     double rows = gd.last_only ? M->B : M->T, d = M->d;
-    ops.back().bytes = a.n * (rows * d * 4.0 * (1.0 + 1.0 / a.n) + (gd.out_f32 ? rows * d * 4.0 : 0) +
-                              (gd.out_codes ? rows * (d + 4.0) : 0));
+    ops.back().bytes = n * (rows * d * 4.0 * (1.0 + 1.0 / n) + (gd.out_f32 ? rows * d * 4.0 : 0) +
+                            (gd.out_codes ? rows * (d + 4.0) : 0));
   }
   void add_build(int g0, int n_groups, int patch_group) {
     if (n_groups - (patch_group >= 0 ? 1 : 0) > 0) {
@@ -261,27 +262,47 @@ struct Builder {
     const int H = M->H, dh = M->dh, d = M->d, T = M->T;
     int vk, vl, hv, cv;
     g.receiver_info(a.v, vk, vl, hv, cv);
-    GroupDesc gd; memset(&gd, 0, sizeof(gd));
-    norm_params(gd, M->ln1_g + (long long)l * d, M->ln1_b + (long long)l * d);
-    gd.out_f32 = M->xf32; gd.out_f32_is = M->tile;
-    int gi = (int)groups.size();
-    groups.push_back(gd);
-    add_patch(gi);
+    // instances [off, off + cnt[c]) patch input c (query, key, value) of the investigated head: one receiver's
+    // candidates, or the candidates of all three inputs of the head side by side (they share everything else)
+    int cnt[3] = {0, 0, 0};
+    const bool multi = a.chan_count[0] + a.chan_count[1] + a.chan_count[2] > 0;
+    if (multi) { for (int c = 0; c < 3; c++) cnt[c] = a.chan_count[c]; } else cnt[cv] = a.n;
     const float* Wc[3] = {M->W_Q, M->W_K, M->W_V};
     const float* bc[3] = {M->b_Q, M->b_K, M->b_V};
     const long long hoff = (long long)l * H + hv;
-    int pf = (int)probs.size();
-    probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, Wc[cv] + hoff * d * dh, dh, nullptr, 1,
-                          bc[cv] + hoff * dh, M->qv, (long long)T * dh, dh, 0, T, dh, d, d));
-    add_op(OP_GEMM32, pf, 1, T * a.n, dh); work_gemm(pf);
-    AttnSrc src; memset(&src, 0, sizeof(src));
     const float* shared0 = M->qkv_sh + (long long)hv * dh;
     const int ld_sh = 3 * H * dh;
-    src.q = cv == 0 ? M->qv : shared0;               src.q_is = cv == 0 ? (long long)T * dh : 0; src.q_ld = cv == 0 ? dh : ld_sh;
-    src.k = cv == 1 ? M->qv : shared0 + H * dh;      src.k_is = cv == 1 ? (long long)T * dh : 0; src.k_ld = cv == 1 ? dh : ld_sh;
-    src.v = cv == 2 ? M->qv : shared0 + 2 * H * dh;  src.v_is = cv == 2 ? (long long)T * dh : 0; src.v_ld = cv == 2 ? dh : ld_sh;
-    src.n_heads = 1; src.h0 = hv; src.head_cols = 0;
-    add_attention(src, 1ull << hv);
+    // patched rows of every range, then their projections in one launch, then the head's attention per range
+    int gi[3] = {-1, -1, -1};
+    for (int c = 0, off = 0; c < 3; off += cnt[c], c++) {
+      if (!cnt[c]) continue;
+      GroupDesc gd; memset(&gd, 0, sizeof(gd));
+      norm_params(gd, M->ln1_g + (long long)l * d, M->ln1_b + (long long)l * d);
+      gd.out_f32 = M->xf32 + (long long)off * M->tile; gd.out_f32_is = M->tile;
+      gi[c] = (int)groups.size();
+      groups.push_back(gd);
+      add_patch(gi[c], off, cnt[c], multi ? M->xvc + (long long)c * M->tile : M->xv);
+    }
+    int pf = (int)probs.size(), np = 0;
+    for (int c = 0, off = 0; c < 3; off += cnt[c], c++) {
+      if (!cnt[c]) continue;
+      GemmProb pq = prob8(M->xf32 + (long long)off * M->tile, M->tile, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1,
+                          bc[c] + hoff * dh, M->qv + (long long)off * T * dh, (long long)T * dh, dh, 0, T, dh, d, d);
+      pq.M = T * cnt[c];
+      probs.push_back(pq); np++;
+    }
+    add_op(OP_GEMM32, pf, np, T * a.n, dh); work_gemm(pf);
+    for (int c = 0, off = 0; c < 3; off += cnt[c], c++) {
+      if (!cnt[c]) continue;
+      const float* own = M->qv + (long long)off * T * dh;
+      AttnSrc src; memset(&src, 0, sizeof(src));
+      src.q = c == 0 ? own : shared0;               src.q_is = c == 0 ? (long long)T * dh : 0; src.q_ld = c == 0 ? dh : ld_sh;
+      src.k = c == 1 ? own : shared0 + H * dh;      src.k_is = c == 1 ? (long long)T * dh : 0; src.k_ld = c == 1 ? dh : ld_sh;
+      src.v = c == 2 ? own : shared0 + 2 * H * dh;  src.v_is = c == 2 ? (long long)T * dh : 0; src.v_ld = c == 2 ? dh : ld_sh;
+      src.n_heads = 1; src.h0 = hv; src.head_cols = 0;
+      add_attention(src, 1ull << hv);
+      ops.back().i1 = off; ops.back().i2 = cnt[c];
+    }
     Stream nxt = next_run(2 * l + 1, run.p == M->run_a ? M->run_b : M->run_a);
     int s = g.head(l, hv);
     pf = (int)probs.size();
@@ -742,8 +763,8 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         break;
       }
       case OP_PATCH:
-        HIPCHK(launch_patch_build(d_groups + o.i0, M->xv, M->delta, M->tile, M->send_dev + a.io_off, n, a.patch_mode, T, B, S, d,
-                                  M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
+        HIPCHK(launch_patch_build(d_groups + o.i0, (const float*)o.p0, M->delta, M->tile, M->send_dev + a.io_off + o.i1, o.i2, a.patch_mode,
+                                  T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, st));
         break;
       case OP_GEMM8:
         for (int q = 0; q < o.i1; q++)
@@ -767,11 +788,15 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         break;
       }
       case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, o.i2, o.i3, st)); break;
-      case OP_ATTN:
-        HIPCHK(launch_attention(b.asrcs[o.i0], M->zcodes, (long long)T * M->H * M->Kh,
-                                M->zscale, (long long)T * M->H, M->zf32, (long long)T * M->dh * __builtin_popcountll(o.u64), o.u64, o.u64b, n, B, S, M->H,
+      case OP_ATTN: {
+        // o.i2 instances starting at o.i1 (0: all of the pass); the sources of such a range are already offset
+        const long long zc_is = (long long)T * M->H * M->Kh, zs_is = (long long)T * M->H,
+                        zf_is = (long long)T * M->dh * __builtin_popcountll(o.u64);
+        HIPCHK(launch_attention(b.asrcs[o.i0], M->zcodes + o.i1 * zc_is, zc_is, M->zscale + o.i1 * zs_is, zs_is,
+                                M->zf32 + o.i1 * zf_is, zf_is, o.u64, o.u64b, o.i2 ? o.i2 : n, B, S, M->H,
                                 M->dh, M->Kh, M->cfg.pos == PAHQ_POS_ROPE, M->rope_tab, st));
         break;
+      }
       case OP_COMBINE: HIPCHK(launch_combine(d_cdesc, o.i0, d_csrc, o.i1 ? 1 : n, M->tile, d, st)); break;
       case OP_OPROJ:
         HIPCHK(launch_oproj_fused(d_odesc, o.i0, d_haux, o.i1, o.i2, M->H, M->dh, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
