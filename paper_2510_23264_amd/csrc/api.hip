@@ -217,13 +217,24 @@ int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
   }
   ctx.pl = ctx.ph = -1;
   if (M->cfg.precision == PAHQ_PAHQ && kind == 0) { ctx.pl = l; ctx.ph = h; }
-  if (ctx.pl >= 0 && (M->pi_l != ctx.pl || M->pi_h != ctx.ph)) {
-    PassArgs a; a.n = 1; a.p0 = ctx.p0; a.pl = ctx.pl; a.ph = ctx.ph; a.v = -1; a.patch_mode = 0;
-    a.kind = PI_CORRUPT; PCHK(run_pass(M, a, nullptr));
-    a.kind = PI_REF; PCHK(run_pass(M, a, nullptr));
-    M->pi_l = ctx.pl; M->pi_h = ctx.ph;
-  }
   make_plan(M, ctx.p0, v, M->plan);
+  if (ctx.pl >= 0) {
+    PassArgs a; a.n = 1; a.p0 = ctx.p0; a.pl = ctx.pl; a.ph = ctx.ph; a.v = -1; a.patch_mode = 0;
+    if (M->pi_l != ctx.pl || M->pi_h != ctx.ph) {
+      M->pi_l = M->pi_h = -2; M->pi_corrupt = false;
+      a.kind = PI_REF; PCHK(run_pass(M, a, nullptr));          // the reference distribution under this head's precision set
+      M->pi_l = ctx.pl; M->pi_h = ctx.ph;
+    }
+    // The corrupted run under the same precision set is read only where the plan has a receiver in kept form
+    // downstream, a recomputed sender whose difference to it some receiver needs, or a dead node standing in with
+    // it: not at all while nothing downstream is removed (every receiver then reads the running stream alone).
+    bool need = M->plan.n_slots + M->plan.n_shared + M->plan.n_dead > 0;
+    for (int w = 0; w < g.Nr && !need; w++) need = g.pos_of_receiver(w) > ctx.p0 && M->plan.spec[w].form == 2;
+    if (need && !M->pi_corrupt) {
+      a.kind = PI_CORRUPT; PCHK(run_pass(M, a, nullptr));
+      M->pi_corrupt = true;
+    }
+  }
   ctx.n_eff = M->nmax;
   if (M->plan.n_slots > 0) ctx.n_eff = (int)std::min<long long>(M->nmax, M->pool_tiles / M->plan.n_slots);
   if (ctx.n_eff < 1) return PAHQ_ENOMEM;

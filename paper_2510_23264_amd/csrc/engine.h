@@ -94,6 +94,7 @@ struct pahq_model {
   std::vector<uint8_t> removed;           // canonical edge order
   std::vector<int64_t> edge_off;          // [Nr + 1]
   bool has_cache;
+  bool pi_corrupt = false;                // the corrupted run under that head's precision set (cpi, rxpi) is current too
   int pi_l, pi_h, pi_p0;                  // fp32 head whose state (cpi, rxpi, ref_*) is current; -2 = none
   pahq::RecvPlan plan;
   int64_t counters[3];
