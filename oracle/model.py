@@ -33,7 +33,7 @@ projection bias, logits at the last position only.
 from __future__ import annotations
 import numpy as np
 
-from . import e4m3
+from . import e4m3, bf16
 from .rtn import Rtn
 from .graph import Graph
 
@@ -77,13 +77,17 @@ def kl_to_reference(logp_ref, logits):
 
 
 class Model:
-    def __init__(self, shape, weights, cache_decoded_bytes=6 << 30, low_bits=8):
+    def __init__(self, shape, weights, cache_decoded_bytes=6 << 30, low_bits=8, nonattn_bf16=False):
         """shape: any object with the ModelShape attributes; weights: dict of float32 arrays.
         low_bits: the grid of the quantised operands -- 8: e4m3 (the paper's setting); 4: Eq. RTN-Q with
-        N = 4 (the 4-bit point of the bit-width ablation, rtn.py)."""
+        N = 4 (the 4-bit point of the bit-width ablation, rtn.py).
+        nonattn_bf16: the MLP matrices and the unembedding multiply bfloat16-rounded operands instead (paper, Sec.
+        "Selective Precision Allocation Strategy": bfloat16 for the components that are not attention heads)."""
         if low_bits not in (4, 8):
             raise ValueError("low_bits")
         self.q = e4m3 if low_bits == 8 else Rtn(low_bits)
+        # the quantiser of the matrix products that are not attention heads: the MLP matrices and the unembedding
+        self.q_other = bf16 if nonattn_bf16 else self.q
         self.s = shape
         self.L, self.H, self.dh, self.d = shape.n_layers, shape.n_heads, shape.d_head, shape.d_model
         self.m, self.V = shape.d_mlp, shape.vocab
@@ -107,9 +111,9 @@ class Model:
         for nm in ("W_in", "W_gate", "W_out"):
             if nm in w:
                 flat = w[nm].reshape(L, -1)
-                c, s = self.q.quantize_groups(flat, axis=-1)
+                c, s = self.q_other.quantize_groups(flat, axis=-1)
                 self.qc[nm], self.qs[nm] = c.reshape(w[nm].shape), s.reshape(L)
-        c, s = self.q.quantize_groups(w["W_U"], axis=None)
+        c, s = self.q_other.quantize_groups(w["W_U"], axis=None)
         self.qc["W_U"], self.qs["W_U"] = c, np.float32(s)
 
     def _wdec(self, nm, *idx):
@@ -117,23 +121,27 @@ class Model:
         key = (nm,) + idx
         if key in self._dec_cache:
             return self._dec_cache[key]
-        a = self.q.decode(self.qc[nm][idx])
+        a = self._q_of(nm).decode(self.qc[nm][idx])
         if self._dec_budget >= a.nbytes:
             self._dec_budget -= a.nbytes
             self._dec_cache[key] = a
         return a
 
-    def _quant_act(self, x):
-        """Row-quantise an activation: decoded grid values and one scale per row."""
-        ca, sa = self.q.quantize_rows(x)
-        return self.q.decode(ca), sa
+    def _q_of(self, nm):
+        return self.q if nm in ("W_Q", "W_K", "W_V", "W_O") else self.q_other
+
+    def _quant_act(self, x, nm="W_Q"):
+        """Row-quantise an activation that multiplies W[nm]: decoded grid values and one scale per row."""
+        q = self._q_of(nm)
+        ca, sa = q.quantize_rows(x)
+        return q.decode(ca), sa
 
     def _linear(self, x, nm, idx, quantised, bias=None, qa=None):
         """x @ W[nm][idx] (+ bias): fp8 GEMM when `quantised`, else fp32 masters in fp64.
         qa: the result of _quant_act(x) when the caller already has it (several
         projections read the same quantised rows)."""
         if quantised:
-            da, sa = self._quant_act(x) if qa is None else qa
+            da, sa = self._quant_act(x, nm) if qa is None else qa
             acc = da @ self._wdec(nm, *idx)                        # exact products, fp64 sum
             y = acc * sa.astype(np.float64)[:, None] * np.float64(self.qs[nm][idx] if idx else self.qs[nm])
         else:
@@ -259,7 +267,7 @@ class Model:
             if self.m > 0:
                 xs, _ = self.receiver_inputs([g.mlpin(l)], outs, removed, C)
                 xn = self.norm(xs[0], "ln2", l)
-                qa = self._quant_act(xn) if quant_all else None
+                qa = self._quant_act(xn, "W_in") if quant_all else None
                 up = self._linear(xn, "W_in", (l,), quant_all, self.w["b_in"][l], qa=qa)
                 if self.s.act == ACT_SWIGLU:
                     hid = silu(self._linear(xn, "W_gate", (l,), quant_all, qa=qa)) * up

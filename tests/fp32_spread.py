@@ -30,7 +30,7 @@ class SpreadModel(Model):
     def set_spread(self, eps, seed):
         self.eps, self.seed = float(eps), int(seed)
 
-    def _quant_act(self, x):
+    def _quant_act(self, x, nm="W_Q"):
         if self.eps:
             bits = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
             idx = np.arange(x.size, dtype=np.uint64).reshape(x.shape)
@@ -42,7 +42,7 @@ class SpreadModel(Model):
                 h ^= h >> np.uint64(31)
             xi = ((h >> np.uint64(11)).astype(np.float64) / 2.0 ** 53 - 0.5) * np.sqrt(12.0)
             x = x * (1.0 + self.eps * xi)
-        return super()._quant_act(x)
+        return super()._quant_act(x, nm)
 
 
 def kl_with_spread(model, clean, corrupt, mode, cases, seeds=4, eps=EPS, progress=None, **acdc_args):

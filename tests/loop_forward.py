@@ -34,24 +34,25 @@ SITES = ("act:q", "act:k", "act:v", "w:q", "w:k", "w:v", "act:o", "w:o",
          "act:in", "w:in", "w:gate", "act:out", "w:out", "act:u", "w:u")
 
 
-_CODEC = [e4m3]      # the grid of the quantised operands (loop_forward's `codec` argument)
+_CODEC = [e4m3, e4m3]      # the quantisers of the attention heads' products and of the other products (loop_forward's arguments)
 
 
-def _qrows(x):
+def _qrows(x, q):
     """Dequantised rows: grid points x one scale per row."""
-    codes, scale = _CODEC[0].quantize_rows(np.asarray(x, dtype=np.float32))
-    return _CODEC[0].decode(codes) * scale.astype(np.float64)[:, None]
+    codes, scale = q.quantize_rows(np.asarray(x, dtype=np.float32))
+    return q.decode(codes) * scale.astype(np.float64)[:, None]
 
 
-def _qall(w):
+def _qall(w, q):
     """Dequantised matrix: grid points x one scale for the whole slice."""
-    codes, scale = _CODEC[0].quantize_groups(np.asarray(w, dtype=np.float32), axis=None)
-    return _CODEC[0].decode(codes) * np.float64(scale)
+    codes, scale = q.quantize_groups(np.asarray(w, dtype=np.float32), axis=None)
+    return q.decode(codes) * np.float64(scale)
 
 
 def _matmul(x, w, low, drop, act_site, w_site):
-    a = _qrows(x) if (low and drop != act_site) else np.asarray(x, dtype=np.float64)
-    b = _qall(w) if (low and drop != w_site) else np.asarray(w, dtype=np.float64)
+    q = _CODEC[0] if w_site in ("w:q", "w:k", "w:v", "w:o") else _CODEC[1]
+    a = _qrows(x, q) if (low and drop != act_site) else np.asarray(x, dtype=np.float64)
+    b = _qall(w, q) if (low and drop != w_site) else np.asarray(w, dtype=np.float64)
     out = np.zeros((a.shape[0], b.shape[1]))
     for t in range(a.shape[0]):
         for j in range(b.shape[1]):
@@ -68,10 +69,13 @@ def _is_upstream(sender, receiver):
     return ls < receiver[1] or (ls == receiver[1] and sender[0] == "head")      # MLP input
 
 
-def loop_forward(shape, w, tokens, pi=frozenset(), quantise=True, removed=frozenset(), other=None, drop=None, codec=None):
+def loop_forward(shape, w, tokens, pi=frozenset(), quantise=True, removed=frozenset(), other=None, drop=None, codec=None,
+                 codec_other=None):
     """Returns (outputs: dict sender -> [T][d], logits [B][vocab] at the last position).
-    codec: the quantiser (quantize_rows / quantize_groups / decode); default the separately pinned e4m3 codec."""
+    codec: the quantiser (quantize_rows / quantize_groups / decode) of the attention heads' products, default the
+    separately pinned e4m3 codec; codec_other: that of the MLP matrices and the unembedding, default `codec`."""
     _CODEC[0] = e4m3 if codec is None else codec
+    _CODEC[1] = _CODEC[0] if codec_other is None else codec_other
     L, H, dh, d, m = shape.n_layers, shape.n_heads, shape.d_head, shape.d_model, shape.d_mlp
     B, S = tokens.shape
     T = B * S
