@@ -235,6 +235,9 @@ def main():
                          "0: the FP8 matrix-core instruction (faster, but its adder truncates: KL about 1.3% low)")
     ap.add_argument("--precision", default="pahq", choices=("pahq", "all_fp8", "all_fp32"),
                     help="all_fp32: the unaccelerated ACDC of the paper's runtime table (no quantiser anywhere)")
+    ap.add_argument("--nonattn-bf16", action="store_true",
+                    help="bfloat16 operands for the MLP matrices and the unembedding (the heads stay on the e4m3 grid)")
+    ap.add_argument("--low-bits", type=int, default=8, choices=(4, 8), help="grid of the low-precision operands")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--only", default=None, choices=(None, "all_edges", "gather_regime", "sweep", "policies"),
@@ -259,19 +262,23 @@ def main():
         sys.exit(1)
     precision = {"pahq": P.PAHQ, "all_fp8": P.ALL_FP8, "all_fp32": P.ALL_FP32}[args.precision]
     shape, w, clean, corrupt, spec = synth.make_workload(args.config)
-    gm = P.Model(shape, w, spec["B"], spec["S"], precision=precision, max_batch_edges=args.batch, mma=args.mma)
+    gm = P.Model(shape, w, spec["B"], spec["S"], precision=precision, max_batch_edges=args.batch, mma=args.mma,
+                 low_bits=args.low_bits, nonattn_bf16=args.nonattn_bf16)
     cfg = gm.cfg
     # configs that name a receiver sample (4 and 5) run the in-edges of that seeded sample
     receivers = synth.make_receiver_sample(P.n_receivers(cfg), spec["n_recv"], spec["seed"])
     gm.clean_cache(clean, corrupt)
-    workload_key = f"{args.config} batch={args.batch} mma={args.mma} precision={args.precision}"
+    workload_key = f"{args.config} batch={args.batch} mma={args.mma} precision={args.precision}" + \
+        (" nonattn_bf16" if args.nonattn_bf16 else "") + (f" low_bits={args.low_bits}" if args.low_bits != 8 else "")
     do = lambda what: args.only in (None, what)
 
     out = {"metric": "patched edge evals/sec (GPT-2-small shape)", "value": None, "unit": "edges/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": None,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": ("f32" if args.precision == "all_fp32" else
-                     "fp8_e4m3 (FP8 matrix cores)" if args.mma == 0 else "fp8_e4m3 operands, fp16 matrix cores, fp32 accumulate"),
+                     "fp8_e4m3 (FP8 matrix cores)" if args.mma == 0 else
+                     "fp8_e4m3 operands for the heads, bf16 for MLPs and unembedding, fp32 accumulate" if args.nonattn_bf16 else
+                     "fp8_e4m3 operands, fp16 matrix cores, fp32 accumulate"),
            "data": "synthetic"}
 
     if do("all_edges"):

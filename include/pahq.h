@@ -111,6 +111,13 @@ typedef struct {
                                hooks return, at 4 bits, E4M3 codes of integers and the step as scale;
                                the matrix products are the same exact kernels.  The 16-bit point of
                                that table is not built.                                             */
+  int32_t nonattn_bf16;     /* 1: the components that are not attention heads -- the MLP matrices and the
+                               unembedding -- multiply bfloat16 operands (activations and weights rounded
+                               to bfloat16, nearest-even, no scale) instead of low_bits ones; the heads
+                               keep low_bits (Sec. "Selective Precision Allocation Strategy": bfloat16 for
+                               non-attention components).  Products are exact on the bf16 matrix cores,
+                               sums fp32.  Needs PAHQ_MMA_F16_EXACT; ignored with PAHQ_ALL_FP32.
+                               0 (default): every quantised product uses low_bits.                   */
 } pahq_config;
 
 /* fp32 master weights, row-major.  All pointers host memory (on_device = 0) or
@@ -280,6 +287,14 @@ int pahq_get_weight_q(pahq_model*, int32_t which, int32_t layer, int32_t head, u
 /* The activation quantiser as a function: host x [rows][cols] -> codes, one scale per row.
  * cols <= 16384. */
 int pahq_quantize_rows(pahq_model*, const float* x, int32_t rows, int32_t cols, uint8_t* codes, float* scales);
+/* Test hooks of the bfloat16 mode (nonattn_bf16 = 1; PAHQ_ESTATE otherwise for the first).
+ * pahq_get_weight_bf16: the bfloat16 patterns of W_in / W_gate / W_out (which = PAHQ_W_*, layer) or of W_U, as the
+ * model holds them, in the master's layout [K][N]; out: host.  pahq_get_weight_q refuses those four in this mode.
+ * pahq_round_rows_bf16: host rows through the row kernel of site PAHQ_QSITE_HIDDEN or PAHQ_QSITE_NORM (their
+ * column constraints as in pahq_quantize_rows_site) in its bfloat16 form; out: host [rows][cols] patterns. */
+int pahq_get_weight_bf16(pahq_model*, int32_t which, int32_t layer, uint16_t* out);
+int pahq_round_rows_bf16(pahq_model*, int32_t site, const float* x, int32_t rows, int32_t cols, uint16_t* out);
+
 /* The same function as the path's three quantisers implement it, each through the code of its own kernel:
  *   PAHQ_QSITE_HIDDEN  rows of hidden activations (what pahq_quantize_rows runs; cols <= 16384)
  *   PAHQ_QSITE_NORM    the quantiser at the end of the gather / patch / norm kernels (cols a multiple of 64, <= 4096)

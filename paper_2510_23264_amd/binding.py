@@ -26,14 +26,15 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "n_heads", "d_head", "d_model", "d_mlp", "vocab", "n_ctx",
                                          "norm", "act", "pos")] + \
                [("norm_eps", C.c_float), ("rope_theta", C.c_float)] + \
-               [(n, C.c_int32) for n in ("split_qkv", "precision", "max_batch_edges", "mma", "low_bits")]
+               [(n, C.c_int32) for n in ("split_qkv", "precision", "max_batch_edges", "mma", "low_bits", "nonattn_bf16")]
 
     @classmethod
-    def from_shape(cls, shape, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, low_bits=8):
+    def from_shape(cls, shape, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, low_bits=8, nonattn_bf16=False):
         return cls(n_layers=shape.n_layers, n_heads=shape.n_heads, d_head=shape.d_head, d_model=shape.d_model,
                    d_mlp=shape.d_mlp, vocab=shape.vocab, n_ctx=shape.n_ctx, norm=shape.norm, act=shape.act,
                    pos=shape.pos, norm_eps=shape.norm_eps, rope_theta=shape.rope_theta, split_qkv=1,
-                   precision=precision, max_batch_edges=max_batch_edges, mma=mma, low_bits=low_bits)
+                   precision=precision, max_batch_edges=max_batch_edges, mma=mma, low_bits=low_bits,
+                   nonattn_bf16=1 if nonattn_bf16 else 0)
 
 
 _W_NAMES = ("W_E", "W_pos", "W_Q", "W_K", "W_V", "W_O", "b_Q", "b_K", "b_V", "b_O", "ln1_g", "ln1_b", "ln2_g",
@@ -78,6 +79,8 @@ def lib():
             "pahq_clean_cache": [C.c_void_p, i32p, i32p],
             "pahq_eval_edges": [C.c_void_p, C.c_int32, i32p, C.c_int32, f32p],
             "pahq_eval_edge_list": [C.c_void_p, C.c_int64, i32p, i32p, f32p],
+            "pahq_get_weight_bf16": [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_uint16)],
+            "pahq_round_rows_bf16": [C.c_void_p, C.c_int32, f32p, C.c_int32, C.c_int32, C.POINTER(C.c_uint16)],
             "pahq_eval_current": [C.c_void_p, C.c_int32, f32p],
             "pahq_acdc_sweep": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
             "pahq_eval_edges_sender_policy": [C.c_void_p, C.c_int32, i32p, C.c_int32, f32p, f32p],
@@ -168,11 +171,11 @@ class Model:
     (layouts as in include/pahq.h)."""
 
     def __init__(self, shape, weights, B, S, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, device="cuda:0",
-                 workspace_bytes_override=None, low_bits=8):
+                 workspace_bytes_override=None, low_bits=8, nonattn_bf16=False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no HIP device: libpahq has no CPU path")
-        self.cfg = Config.from_shape(shape, precision, max_batch_edges, mma, low_bits)
+        self.cfg = Config.from_shape(shape, precision, max_batch_edges, mma, low_bits, nonattn_bf16)
         self.B, self.S, self.T = B, S, B * S
         self.n_edges = edge_count(self.cfg)
         nbytes = workspace_bytes(self.cfg, B, S)
@@ -350,6 +353,19 @@ class Model:
             _chk(lib().pahq_quantize_rows_site(self.h, int(site), _ptr(x, C.c_float), rows, cols, _ptr(codes, C.c_uint8),
                                                _ptr(scales, C.c_float)), "pahq_quantize_rows_site")
         return codes, scales
+
+    def get_weight_bf16(self, which, layer, shape):
+        """bfloat16 patterns uint16 [K][N] of an MLP matrix or the unembedding (nonattn_bf16 models)."""
+        out = np.empty(shape, dtype=np.uint16)
+        _chk(lib().pahq_get_weight_bf16(self.h, int(which), int(layer), _ptr(out, C.c_uint16)), "pahq_get_weight_bf16")
+        return out
+
+    def round_rows_bf16(self, x, site):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        out = np.empty(x.shape, dtype=np.uint16)
+        _chk(lib().pahq_round_rows_bf16(self.h, int(site), _ptr(x, C.c_float), x.shape[0], x.shape[1], _ptr(out, C.c_uint16)),
+             "pahq_round_rows_bf16")
+        return out
 
     def gemm_codes(self, a, w):
         """a uint8 [m][k], w uint8 [n][k] -> float32 [m][n] = sum_k dec(a) dec(w)."""

@@ -23,12 +23,14 @@ int check_config(const pahq_config* c) {
   if (!(c->norm_eps >= 0.f)) return PAHQ_EINVAL;
   if (c->mma != PAHQ_MMA_FP8 && c->mma != PAHQ_MMA_F16_EXACT) return PAHQ_EINVAL;
   if (c->low_bits != 0 && c->low_bits != 4 && c->low_bits != 8) return PAHQ_EINVAL;
+  if (c->nonattn_bf16 != 0 && c->nonattn_bf16 != 1) return PAHQ_EINVAL;
   return PAHQ_OK;
 }
 // what this build of the kernels supports
 int check_supported(const pahq_config* c, int B, int S) {
   if (c->split_qkv != 1) return PAHQ_EUNSUPPORTED;
   if (c->n_heads > 64) return PAHQ_EUNSUPPORTED;                      // sets of heads are 64-bit masks
+  if (c->nonattn_bf16 && c->mma != PAHQ_MMA_F16_EXACT && c->precision != PAHQ_ALL_FP32) return PAHQ_EUNSUPPORTED;   // bfloat16 products have no FP8-instruction form
   if (c->d_model % 64 != 0 || c->d_model > 4096) return PAHQ_EUNSUPPORTED;
   if (c->d_mlp % 4 != 0) return PAHQ_EUNSUPPORTED;                    // 16-byte rows of the hidden activations
   if (c->d_head != 16 && c->d_head != 32 && c->d_head != 64 && c->d_head != 128) return PAHQ_EUNSUPPORTED;
@@ -62,6 +64,9 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
   M->all_f32 = c->precision == PAHQ_ALL_FP32;
   M->skip_dead = true;
   M->qbits = c->low_bits == 4 ? 4 : 8;
+  M->nb16 = c->nonattn_bf16 != 0 && !M->all_f32;
+  M->Kd_o = M->nb16 ? pad128(2 * M->d) : M->Kd;
+  M->Km_o = M->nb16 ? pad128(2 * (M->m > 0 ? M->m : 1)) : M->Km;
   M->deadsum_tag.assign(M->L, -1);
   M->f32_groups = M->all_f32 ? 3 * M->H : 3;
   M->f32_heads_max = M->all_f32 ? M->H : 1;
@@ -81,6 +86,7 @@ size_t arena_slot_bytes(const pahq_model* M) {
 size_t layout(pahq_model* M, char* base) {
   Bump b{base, 0};
   const size_t L = M->L, H = M->H, dh = M->dh, d = M->d, m = M->m, V = M->V, T = M->T, B = M->B;
+  const size_t Kdo = M->Kd_o, Kmo = M->Km_o;
   const size_t Kd = M->Kd, Kh = M->Kh, Km = M->Km, n = M->nmax, G = M->G, Ns = M->g.Ns, tile = M->tile, Vp = M->Vp;
   const bool mlp = m > 0, swi = M->cfg.act == PAHQ_ACT_SWIGLU, learned = M->cfg.pos == PAHQ_POS_LEARNED;
   M->W_E = b.take<float>(V * d);
@@ -101,11 +107,11 @@ size_t layout(pahq_model* M, char* base) {
   M->bqkv = b.take<float>(L * 3 * H * dh);
   M->qkv_codes = b.take<uint8_t>(L * 3 * H * dh * Kd); M->qkv_scale = b.take<float>(L * 3 * H);
   M->o_codes = b.take<uint8_t>(L * H * d * Kh); M->o_scale = b.take<float>(L * H);
-  M->in_codes = mlp ? b.take<uint8_t>(L * m * Kd) : nullptr; M->in_scale = mlp ? b.take<float>(L) : nullptr;
-  M->gate_codes = (mlp && swi) ? b.take<uint8_t>(L * m * Kd) : nullptr;
+  M->in_codes = mlp ? b.take<uint8_t>(L * m * Kdo) : nullptr; M->in_scale = mlp ? b.take<float>(L) : nullptr;
+  M->gate_codes = (mlp && swi) ? b.take<uint8_t>(L * m * Kdo) : nullptr;
   M->gate_scale = (mlp && swi) ? b.take<float>(L) : nullptr;
-  M->out_codes = mlp ? b.take<uint8_t>(L * d * Km) : nullptr; M->out_scale = mlp ? b.take<float>(L) : nullptr;
-  M->u_codes = b.take<uint8_t>(V * Kd); M->u_scale = b.take<float>(1);
+  M->out_codes = mlp ? b.take<uint8_t>(L * d * Kmo) : nullptr; M->out_scale = mlp ? b.take<float>(L) : nullptr;
+  M->u_codes = b.take<uint8_t>(V * Kdo); M->u_scale = b.take<float>(1);
   M->amax_tmp = b.take<unsigned>((L * H + 4 + 3) / 4 * 4); M->flag_tmp = b.take<int>(4);
   M->tok_clean = b.take<int>(T); M->tok_corrupt = b.take<int>(T); M->send_dev = b.take<int>(M->ncap);
   M->clean = b.take<float>(Ns * tile); M->corrupt = b.take<float>(Ns * tile); M->delta = b.take<float>((Ns + 1) * tile);   // tile Ns stays zero
@@ -123,8 +129,8 @@ size_t layout(pahq_model* M, char* base) {
   M->headout = b.take<float>(n * H * tile);
   M->mlpout = mlp ? b.take<float>(n * tile) : nullptr;
   M->hid = mlp ? b.take<float>(n * T * m) : nullptr; M->hid2 = (mlp && swi) ? b.take<float>(n * T * m) : nullptr;
-  M->hcodes = mlp ? b.take<uint8_t>(n * T * Km) : nullptr; M->hscale = mlp ? b.take<float>(n * T) : nullptr;
-  M->lastcodes = b.take<uint8_t>(n * B * Kd); M->lastscale = b.take<float>(n * B); M->logits = b.take<float>(n * B * Vp);
+  M->hcodes = mlp ? b.take<uint8_t>(n * T * Kmo) : nullptr; M->hscale = mlp ? b.take<float>(n * T) : nullptr;
+  M->lastcodes = b.take<uint8_t>(n * B * Kdo); M->lastscale = b.take<float>(n * B); M->logits = b.take<float>(n * B * Vp);
   // Per-instance copies of recomputed sender outputs that some receiver reads individually: in the
   // worst case (most edges removed) every sender but the embedding needs one per candidate.  Room
   // for a full batch of those, capped at 64 GiB; a smaller pool only shrinks the batches.
@@ -151,12 +157,12 @@ int copy_in(pahq_model* M, float* dst, const float* src, size_t n, int on_device
 
 // quantise n_slices contiguous slices of shape [K][N]; slice i goes to codes0 + i*codes_stride, scale0 + i*scale_stride
 int quantise_class(pahq_model* M, const float* w, int n_slices, int K, int N, uint8_t* codes0, long long codes_stride,
-                   int ldq, float* scale0, int scale_stride) {
+                   int ldq, float* scale0, int scale_stride, int qbits) {
   HIPCHK(launch_fill_zero(M->amax_tmp, ((size_t)n_slices * 4 + 15) / 16 * 16, M->stream));
   HIPCHK(launch_slice_absmax(w, (long long)K * N, n_slices, M->amax_tmp, M->flag_tmp, M->stream));
   for (int i = 0; i < n_slices; i++)
     HIPCHK(launch_quant_transpose(w + (long long)i * K * N, K, N, M->amax_tmp + i, scale0 + (long long)i * scale_stride,
-                                  codes0 + i * codes_stride, ldq, M->qbits, M->stream));
+                                  codes0 + i * codes_stride, ldq, qbits, M->stream));
   HIPCHK(hipStreamSynchronize(M->stream));       // amax_tmp is reused by the next class
   return PAHQ_OK;
 }
@@ -385,16 +391,17 @@ int pahq_init_model(const pahq_config* c, const pahq_weights* w, int32_t B, int3
   if (M->rope_tab && launch_rope_table(M->rope_tab, 32, (int)dh, c->rope_theta, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
   // e4m3 codes + scales of every weight slice
   const float* wc[3] = {M->W_Q, M->W_K, M->W_V};
+  const int qo = M->nb16 ? 16 : M->qbits;      // the grid of the components that are not attention heads
   for (size_t l = 0; l < L && rc == PAHQ_OK; l++)
     for (int cc = 0; cc < 3 && rc == PAHQ_OK; cc++)
       rc = quantise_class(M, wc[cc] + l * H * d * dh, (int)H, (int)d, (int)dh,
                           M->qkv_codes + (l * 3 * H * dh + (size_t)cc * H * dh) * M->Kd, (long long)dh * M->Kd, M->Kd,
-                          M->qkv_scale + l * 3 * H + (size_t)cc * H, 1);
-  if (rc == PAHQ_OK) rc = quantise_class(M, M->W_O, (int)(L * H), (int)dh, (int)d, M->o_codes, (long long)d * M->Kh, M->Kh, M->o_scale, 1);
-  if (mlp && rc == PAHQ_OK) rc = quantise_class(M, M->W_in, (int)L, (int)d, (int)m, M->in_codes, (long long)m * M->Kd, M->Kd, M->in_scale, 1);
-  if (mlp && swi && rc == PAHQ_OK) rc = quantise_class(M, M->W_gate, (int)L, (int)d, (int)m, M->gate_codes, (long long)m * M->Kd, M->Kd, M->gate_scale, 1);
-  if (mlp && rc == PAHQ_OK) rc = quantise_class(M, M->W_out, (int)L, (int)m, (int)d, M->out_codes, (long long)d * M->Km, M->Km, M->out_scale, 1);
-  if (rc == PAHQ_OK) rc = quantise_class(M, M->W_U, 1, (int)d, (int)V, M->u_codes, 0, M->Kd, M->u_scale, 1);
+                          M->qkv_scale + l * 3 * H + (size_t)cc * H, 1, M->qbits);
+  if (rc == PAHQ_OK) rc = quantise_class(M, M->W_O, (int)(L * H), (int)dh, (int)d, M->o_codes, (long long)d * M->Kh, M->Kh, M->o_scale, 1, M->qbits);
+  if (mlp && rc == PAHQ_OK) rc = quantise_class(M, M->W_in, (int)L, (int)d, (int)m, M->in_codes, (long long)m * M->Kd_o, M->Kd_o, M->in_scale, 1, qo);
+  if (mlp && swi && rc == PAHQ_OK) rc = quantise_class(M, M->W_gate, (int)L, (int)d, (int)m, M->gate_codes, (long long)m * M->Kd_o, M->Kd_o, M->gate_scale, 1, qo);
+  if (mlp && rc == PAHQ_OK) rc = quantise_class(M, M->W_out, (int)L, (int)m, (int)d, M->out_codes, (long long)d * M->Km_o, M->Km_o, M->out_scale, 1, qo);
+  if (rc == PAHQ_OK) rc = quantise_class(M, M->W_U, 1, (int)d, (int)V, M->u_codes, 0, M->Kd_o, M->u_scale, 1, qo);
   if (rc != PAHQ_OK) return fail(rc);
   // embeddings, biases and norm parameters are used unquantised: check them too
   {
@@ -817,6 +824,7 @@ int pahq_get_weight_q(pahq_model* M, int32_t which, int32_t layer, int32_t head,
   const int L = M->L, H = M->H, dh = M->dh, d = M->d, m = M->m, V = M->V;
   if (which >= PAHQ_W_Q && which <= PAHQ_W_O) { if (layer < 0 || layer >= L || head < 0 || head >= H) return PAHQ_EINVAL; }
   else if (which >= PAHQ_W_IN && which <= PAHQ_W_OUT) { if (layer < 0 || layer >= L || m == 0) return PAHQ_EINVAL; }
+  if (M->nb16 && which >= PAHQ_W_IN) return PAHQ_EUNSUPPORTED;      // those are bfloat16 patterns: pahq_get_weight_bf16
   switch (which) {
     case PAHQ_W_Q: case PAHQ_W_K: case PAHQ_W_V: {
       int cc = which - PAHQ_W_Q;
@@ -837,6 +845,50 @@ int pahq_get_weight_q(pahq_model* M, int32_t which, int32_t layer, int32_t head,
   HIPCHK(hipStreamSynchronize(M->stream));
   for (int k = 0; k < K; k++)
     for (int n = 0; n < N; n++) codes[(size_t)k * N + n] = tmp[(size_t)n * ldq + k];
+  return PAHQ_OK;
+}
+
+int pahq_get_weight_bf16(pahq_model* M, int32_t which, int32_t layer, uint16_t* out) {
+  if (!M || !out) return PAHQ_EINVAL;
+  if (!M->nb16) return PAHQ_ESTATE;
+  const int L = M->L, d = M->d, m = M->m, V = M->V;
+  const uint8_t* src; int K, N, ldq;
+  if (which >= PAHQ_W_IN && which <= PAHQ_W_OUT) { if (layer < 0 || layer >= L || m == 0) return PAHQ_EINVAL; }
+  switch (which) {
+    case PAHQ_W_IN: K = d; N = m; ldq = M->Kd_o; src = M->in_codes + (long long)layer * m * ldq; break;
+    case PAHQ_W_GATE: if (!M->gate_codes) return PAHQ_EINVAL;
+      K = d; N = m; ldq = M->Kd_o; src = M->gate_codes + (long long)layer * m * ldq; break;
+    case PAHQ_W_OUT: K = m; N = d; ldq = M->Km_o; src = M->out_codes + (long long)layer * d * ldq; break;
+    case PAHQ_W_U: K = d; N = V; ldq = M->Kd_o; src = M->u_codes; break;
+    default: return PAHQ_EINVAL;
+  }
+  std::vector<uint8_t> tmp((size_t)N * ldq);
+  HIPCHK(hipMemcpyAsync(tmp.data(), src, tmp.size(), hipMemcpyDeviceToHost, M->stream));
+  HIPCHK(hipStreamSynchronize(M->stream));
+  for (int k = 0; k < K; k++)
+    for (int n = 0; n < N; n++) out[(size_t)k * N + n] = *(const uint16_t*)(tmp.data() + (size_t)n * ldq + 2 * (size_t)k);
+  return PAHQ_OK;
+}
+
+int pahq_round_rows_bf16(pahq_model* M, int32_t site, const float* x, int32_t rows, int32_t cols, uint16_t* out) {
+  if (!M || rows < 0 || cols < 1 || (rows > 0 && (!x || !out))) return PAHQ_EINVAL;
+  if (site != PAHQ_QSITE_HIDDEN && site != PAHQ_QSITE_NORM) return PAHQ_EINVAL;
+  if (site == PAHQ_QSITE_NORM && (cols % 64 != 0 || cols > 4096)) return PAHQ_EINVAL;
+  if (site == PAHQ_QSITE_HIDDEN && cols % 4 != 0) return PAHQ_EINVAL;
+  if (rows == 0) return PAHQ_OK;
+  // staged through the candidate buffers: fp32 rows in `logits`, patterns in `xcodes`, the (unit) scales in `xscale`
+  size_t cap_f = (size_t)M->nmax * M->B * M->Vp, cap_c = (size_t)M->nmax * M->G * M->T * M->Kd, cap_s = (size_t)M->nmax * M->G * M->T;
+  size_t chunk = std::min(std::min(cap_f / cols, cap_c / (2 * (size_t)cols)), cap_s);
+  if (chunk < 1) return PAHQ_ENOMEM;
+  for (size_t r0 = 0; r0 < (size_t)rows; r0 += chunk) {
+    size_t nr = std::min(chunk, (size_t)rows - r0);
+    HIPCHK(hipMemcpyAsync(M->logits, x + r0 * cols, nr * cols * sizeof(float), hipMemcpyHostToDevice, M->stream));
+    if (site == PAHQ_QSITE_HIDDEN)
+      HIPCHK(launch_hidden_quant(M->logits, nullptr, 0LL, M->xcodes, 0LL, M->xscale, 0LL, 1, (int)nr, cols, 2 * cols, 0, 16, M->stream));
+    else HIPCHK(launch_emit_rows(M->logits, (int)nr, cols, M->xcodes, M->xscale, 16, M->stream));
+    HIPCHK(hipMemcpyAsync(out + r0 * cols, M->xcodes, nr * cols * 2, hipMemcpyDeviceToHost, M->stream));
+    HIPCHK(hipStreamSynchronize(M->stream));
+  }
   return PAHQ_OK;
 }
 
@@ -901,7 +953,7 @@ int pahq_gemm_codes(pahq_model* M, const uint8_t* a, const uint8_t* w, int32_t m
   if (!gemm8_prob_ok(p)) return PAHQ_EINVAL;
   void* dp = nullptr;
   PCHK(upload_table(M, &p, sizeof(p), &dp));
-  HIPCHK(launch_gemm_fp8((const GemmProb*)dp, 1, m, n, M->cfg.mma == PAHQ_MMA_F16_EXACT, M->stream));
+  HIPCHK(launch_gemm_fp8((const GemmProb*)dp, 1, m, n, M->cfg.mma == PAHQ_MMA_F16_EXACT, 0, M->stream));
   HIPCHK(hipMemcpy2DAsync(out, (size_t)n * sizeof(float), M->logits, ldc * sizeof(float), (size_t)n * sizeof(float), m,
                           hipMemcpyDeviceToHost, M->stream));
   HIPCHK(hipStreamSynchronize(M->stream));

@@ -442,7 +442,7 @@ hipError_t launch_kl_reduce(const float* kl_part, int npart, int rows, int B, co
 // result.  The unembedding itself is not computed for this metric.
 __global__ __launch_bounds__(64) void logit_pair_k(const uint8_t* codes, long long c_is, const float* scale, long long s_is,
                                                    int ldq, int K, const uint8_t* wcodes, int ldw, const float* wscale,
-                                                   const float* bias, const int* ans, const int* dis, int B, double* ld) {
+                                                   const float* bias, const int* ans, const int* dis, int B, double* ld, int b16) {
   const int row = blockIdx.x, inst = row / B, b = row % B, lane = threadIdx.x;
   const uint8_t* a = codes + inst * c_is + (long long)b * ldq;
   const float s2 = scale[inst * s_is + b] * wscale[0];
@@ -452,6 +452,16 @@ __global__ __launch_bounds__(64) void logit_pair_k(const uint8_t* codes, long lo
     const int col = which ? dis[b] : ans[b];
     const uint8_t* wv = wcodes + (long long)col * ldw;
     float acc = 0.f;
+    if (b16) {
+      // bfloat16 patterns (K in bytes): a pattern shifted into the upper half of a word is the binary32 value
+      for (int k = lane * 8; k < K; k += 512) {
+        const uint2 av = *(const uint2*)(a + k), bv = *(const uint2*)(wv + k);
+        acc += __uint_as_float(av.x << 16) * __uint_as_float(bv.x << 16);
+        acc += __uint_as_float(av.x & 0xFFFF0000u) * __uint_as_float(bv.x & 0xFFFF0000u);
+        acc += __uint_as_float(av.y << 16) * __uint_as_float(bv.y << 16);
+        acc += __uint_as_float(av.y & 0xFFFF0000u) * __uint_as_float(bv.y & 0xFFFF0000u);
+      }
+    } else
     for (int k = lane * 8; k < K; k += 512) {
       const uint2 av = *(const uint2*)(a + k), bv = *(const uint2*)(wv + k);
       const v8h ha = decode8(av.x, av.y), hb = decode8(bv.x, bv.y);
@@ -488,10 +498,10 @@ __global__ void metric_mean_k(const double* ld, const double* ref_ld, double* sc
 }
 hipError_t launch_logit_pair(const uint8_t* codes, long long c_is, const float* scale, long long s_is, int ldq, int K,
                              const uint8_t* wcodes, int ldw, const float* wscale, const float* bias, const int* ans,
-                             const int* dis, int n_inst, int B, double* ld, hipStream_t s) {
+                             const int* dis, int n_inst, int B, double* ld, int b16, hipStream_t s) {
   if (n_inst == 0) return hipSuccess;
   hipLaunchKernelGGL(logit_pair_k, dim3(n_inst * B), dim3(64), 0, s, codes, c_is, scale, s_is, ldq, K, wcodes, ldw, wscale, bias,
-                     ans, dis, B, ld);
+                     ans, dis, B, ld, b16);
   return hipGetLastError();
 }
 hipError_t launch_logit_pair_f32(const float* x, long long x_is, int d, const float* W, int ldw, const float* bias,

@@ -49,6 +49,13 @@ __device__ __forceinline__ uint32_t e4m3_encode(float y) {
 __device__ __forceinline__ float q_top(int bits) { return bits == 4 ? 8.0f : 448.0f; }
 __device__ __forceinline__ uint32_t q_encode(float y, int bits) { return e4m3_encode(bits == 4 ? rintf(y) : y); }
 
+// binary32 -> bfloat16 bit pattern, round to nearest, ties to even (finite input): the 16 dropped mantissa bits
+// round the kept ones up when they exceed half a unit, or equal it and the kept pattern is odd.
+__device__ __forceinline__ uint32_t bf16_rne(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
 // tanh-form GELU, 0.5 x (1 + tanh(u)) with u = sqrt(2/pi) (x + 0.044715 x^3), written as
 // x / (1 + exp(-2u)): relative accuracy is kept for negative x, where 1 + tanh(u) cancels.  The result
 // feeds the row quantiser, where a relative error e moves about e / 2^-4 of the elements across a rounding

@@ -67,6 +67,8 @@ struct pahq_model {
   long long plan_serial = 0;              // counts make_plan calls: the per-layer sums of dead heads' stand-ins are kept per plan
   std::vector<long long> deadsum_tag;     // per layer: 2 * plan_serial + (precision-set pass) the layer's tile was made for, or -1
   int qbits;                              // grid of the low-precision operands: 8 = E4M3, 4 = 4-bit round-to-nearest
+  bool nb16;                              // the MLP matrices and the unembedding multiply bfloat16 operands instead
+  int Kd_o, Km_o;                         // bytes of a d_model / d_mlp row of those operands (= Kd, Km unless nb16)
   bool skip_dead;                         // passes over a pruned graph leave out nodes no kept path connects to the output
   bool all_f32;                           // PAHQ_ALL_FP32: every matrix product on the fp32 masters, no quantiser
   int f32_groups;                         // receiver-input groups of a layer that may need fp32 rows (per instance)

@@ -130,7 +130,7 @@ struct Builder {
     double f = 0, by = 0;
     for (size_t i = pb; i < probs.size(); i++) {
       const GemmProb& q = probs[i];
-      const double M_ = q.M, N_ = q.N, K_ = q.k_real, eb = q.ascale ? 1.0 : 4.0;
+      const double M_ = q.M, N_ = q.N, K_ = q.k_real, eb = q.ascale ? (q.b16 ? 2.0 : 1.0) : 4.0;
       f += 2.0 * M_ * N_ * K_;
       by += eb * (M_ * K_ + N_ * K_) + (q.C ? 4.0 * M_ * N_ : 0.0) + (q.kl_ref ? 4.0 * (double)q.rpi * N_ : 0.0) +
             (q.ascale ? 4.0 * M_ : 0.0) + (q.add ? 4.0 * M_ * N_ : 0.0) +
@@ -513,10 +513,12 @@ struct Builder {
     if (a.kind == CAND && w == a.v) patch_group = gi;
     else fill_input(gd, general ? &plan->spec[w] : nullptr, 2 * l + 1, run);
     norm_params(gd, M->ln2_g + (long long)l * d, M->ln2_b + (long long)l * d);
+    const int Ko = M->Kd_o, Kmo = M->Km_o, b16 = M->nb16 ? 1 : 0;      // row bytes of this block's operands (bfloat16: two per element)
     if (f32_rest) { gd.out_f32 = M->xf32; gd.out_f32_is = M->tile; }
     else {
-      gd.out_codes = M->xcodes; gd.out_codes_is = (long long)T * Kd;
+      gd.out_codes = M->xcodes; gd.out_codes_is = (long long)T * Ko;
       gd.out_scale = M->xscale; gd.out_scale_is = T;
+      if (b16) gd.qbits = 16;
     }
     groups.push_back(gd);
     add_build(gi, 1, patch_group);
@@ -551,20 +553,24 @@ struct Builder {
       return;
     }
     int pb = (int)probs.size();
-    probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
-                          M->in_codes + (long long)l * m * Kd, Kd, M->in_scale + l, m, M->b_in + (long long)l * m, M->hid,
-                          (long long)T * m, m, 0, T, m, Kd, d));       // the activation is applied by the hidden quantiser
-    if (swiglu)
-      probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
-                            M->gate_codes + (long long)l * m * Kd, Kd, M->gate_scale + l, m, nullptr, M->hid2,
-                            (long long)T * m, m, 0, T, m, Kd, d));
+    probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Ko, gd.out_scale, gd.out_scale_is, 1,
+                          M->in_codes + (long long)l * m * Ko, Ko, M->in_scale + l, m, M->b_in + (long long)l * m, M->hid,
+                          (long long)T * m, m, 0, T, m, Ko, d));       // the activation is applied by the hidden quantiser
+    probs.back().b16 = b16;
+    if (swiglu) {
+      probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Ko, gd.out_scale, gd.out_scale_is, 1,
+                            M->gate_codes + (long long)l * m * Ko, Ko, M->gate_scale + l, m, nullptr, M->hid2,
+                            (long long)T * m, m, 0, T, m, Ko, d));
+      probs.back().b16 = b16;
+    }
     add_op(OP_GEMM8, pb, swiglu ? 2 : 1, T * a.n, m); work_gemm(pb);
     add_op(OP_HIDQ, swiglu ? 2 : (M->cfg.act == PAHQ_ACT_GELU ? 1 : 0));
-    ops.back().bytes = (double)a.n * T * m * ((swiglu ? 8.0 : 4.0) + 1.0);
+    ops.back().bytes = (double)a.n * T * m * ((swiglu ? 8.0 : 4.0) + (b16 ? 2.0 : 1.0));
     // output projection fused with the stream update: next = run + b_out + out
     pb = (int)probs.size();
-    GemmProb po = prob8(M->hcodes, (long long)T * Km, Km, M->hscale, T, 1, M->out_codes + (long long)l * d * Km, Km,
-                        M->out_scale + l, d, M->b_out + (long long)l * d, nxt.p, nxt.is, d, 0, T, d, Km, m);
+    GemmProb po = prob8(M->hcodes, (long long)T * Kmo, Kmo, M->hscale, T, 1, M->out_codes + (long long)l * d * Kmo, Kmo,
+                        M->out_scale + l, d, M->b_out + (long long)l * d, nxt.p, nxt.is, d, 0, T, d, Kmo, m);
+    po.b16 = b16;
     po.add = run.p; po.add_is = run.is;
     second_output(po);
     probs.push_back(po);
@@ -603,8 +609,9 @@ struct Builder {
     gd.last_only = 1;
     if (f32_rest) { gd.out_f32 = M->xf32; gd.out_f32_is = (long long)B * d; }
     else {
-      gd.out_codes = M->lastcodes; gd.out_codes_is = (long long)B * Kd;
+      gd.out_codes = M->lastcodes; gd.out_codes_is = (long long)B * M->Kd_o;
       gd.out_scale = M->lastscale; gd.out_scale_is = B;
+      if (M->nb16) gd.qbits = 16;
     }
     groups.push_back(gd);
     add_build(gi, 1, patch_group);
@@ -629,8 +636,9 @@ struct Builder {
       }
       return;
     }
-    probs.push_back(prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1, M->u_codes, Kd,
-                          M->u_scale, V, M->b_U, lg, lg_is, Vp, 0, B, V, Kd, d));
+    probs.push_back(prob8(gd.out_codes, gd.out_codes_is, M->Kd_o, gd.out_scale, gd.out_scale_is, 1, M->u_codes, M->Kd_o,
+                          M->u_scale, V, M->b_U, lg, lg_is, Vp, 0, B, V, M->Kd_o, d));
+    probs.back().b16 = M->nb16 ? 1 : 0;
     // With exact sums the unembedding itself reduces its rows to the parts of a log-sum-exp and of the KL
     // against the reference (one row of parts instead of one row of logits per candidate and sequence); the
     // reference passes also keep their logits and get their log-sum-exp from the same parts, so that a candidate
@@ -697,7 +705,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
     b.final_block(run);
   }
 
-  for (GroupDesc& gd : b.groups) gd.qbits = M->qbits;
+  for (GroupDesc& gd : b.groups) if (!gd.qbits) gd.qbits = M->qbits;      // groups of bfloat16 blocks have said 16
   for (AttnSrc& as : b.asrcs) as.qbits = M->qbits;
   // ---- upload the descriptor tables
   Arena& A = M->arena;
@@ -770,10 +778,10 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         for (int q = 0; q < o.i1; q++)
           if (!gemm8_prob_ok(b.probs[o.i0 + q]))      // the problem does not meet what the kernels assume
             return PAHQ_EINVAL;
-        if (o.p0) HIPCHK(launch_gemm_fp8_kl(d_probs + o.i0, o.i1, o.i2, o.i3, st));      // log-softmax / KL epilogue
+        if (o.p0) HIPCHK(launch_gemm_fp8_kl(d_probs + o.i0, o.i1, o.i2, o.i3, b.probs[o.i0].b16, st));      // log-softmax / KL epilogue
         else {
           for (int q = 0; q < o.i1; q++) if (b.probs[o.i0 + q].kl_part || !b.probs[o.i0 + q].C) return PAHQ_EINVAL;
-          HIPCHK(launch_gemm_fp8(d_probs + o.i0, o.i1, o.i2, o.i3, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
+          HIPCHK(launch_gemm_fp8(d_probs + o.i0, o.i1, o.i2, o.i3, M->cfg.mma == PAHQ_MMA_F16_EXACT, b.probs[o.i0].b16, st));
         }
         break;
       case OP_KLRED:
@@ -802,15 +810,15 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         HIPCHK(launch_oproj_fused(d_odesc, o.i0, d_haux, o.i1, o.i2, M->H, M->dh, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
         break;
       case OP_HIDQ:
-        HIPCHK(launch_hidden_quant(M->hid, o.i0 == 2 ? M->hid2 : nullptr, (long long)T * M->m, M->hcodes, (long long)T * M->Km,
-                                   M->hscale, T, n, T, M->m, M->Km, o.i0, M->qbits, st));
+        HIPCHK(launch_hidden_quant(M->hid, o.i0 == 2 ? M->hid2 : nullptr, (long long)T * M->m, M->hcodes, (long long)T * M->Km_o,
+                                   M->hscale, T, n, T, M->m, M->Km_o, o.i0, M->nb16 ? 16 : M->qbits, st));
         break;
       case OP_SWIGLU32: HIPCHK(launch_swiglu_f32(M->hid, M->hid2, (long long)n * T * M->m, st)); break;
       case OP_LD: {
         double* ld = o.i0 ? M->row_kl : (double*)o.p0;
         if (M->all_f32) HIPCHK(launch_logit_pair_f32(M->xf32, (long long)B * d, d, M->W_U, M->V, M->b_U, M->ans_dev, M->dis_dev, n, B, ld, st));
-        else HIPCHK(launch_logit_pair(M->lastcodes, (long long)B * M->Kd, M->lastscale, B, M->Kd, M->Kd, M->u_codes, M->Kd, M->u_scale,
-                                      M->b_U, M->ans_dev, M->dis_dev, n, B, ld, st));
+        else HIPCHK(launch_logit_pair(M->lastcodes, (long long)B * M->Kd_o, M->lastscale, B, M->Kd_o, M->Kd_o, M->u_codes, M->Kd_o, M->u_scale,
+                                      M->b_U, M->ans_dev, M->dis_dev, n, B, ld, M->nb16 ? 1 : 0, st));
         if (o.i0) HIPCHK(launch_metric_mean(M->row_kl, (const double*)o.p0, M->kl_dev + a.io_off, n, B, st));
         break;
       }

@@ -191,7 +191,10 @@ __device__ __forceinline__ void epi_kl(const EpiPre<TM, TN>& E, const GemmProb& 
 // while the last slab of this tile is multiplied, and the next K loop starts while the stores of
 // this tile are still in flight.
 
-template <int WAVES_M, int WAVES_N, int TM, int TN>
+// B16: the rows hold bfloat16 patterns instead of e4m3 codes.  Nothing changes on the way into LDS (rows of 128
+// bytes, K counted in bytes); a 16-byte operand read is then eight elements, one step of V_MFMA_F32_16X16X32_BF16,
+// with no conversion (products of two bfloat16 numbers are exact in binary32, as those of two e4m3 codes are).
+template <int WAVES_M, int WAVES_N, int TM, int TN, bool B16 = false>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmProb* probs) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int BM = WAVES_M * TM * 16, BN = WAVES_N * TN * 16, ROWS = BM + BN;
@@ -242,6 +245,23 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
   auto compute = [&](const uint8_t* st) {
     const uint8_t* sA = st + offA;
     const uint8_t* sB = st + offB;
+    if constexpr (B16) {
+#pragma unroll
+      for (int q = 0; q < 2; q++) {
+        const int sw = q ? sw1 : sw0;
+        union U { uint4 u; v8bf h; };
+        U ha[TM];
+#pragma unroll
+        for (int i = 0; i < TM; i++) ha[i].u = *(const uint4*)(sA + i * 2048 + sw);
+#pragma unroll
+        for (int jj = 0; jj < TN; jj++) {
+          U hb; hb.u = *(const uint4*)(sB + jj * 2048 + sw);
+#pragma unroll
+          for (int i = 0; i < TM; i++) acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hb.h, ha[i].h, acc[i][jj], 0, 0, 0);
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int q = 0; q < 2; q++) {
       const int sw = q ? sw1 : sw0;
@@ -653,17 +673,30 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_k(const GemmPr
 
 // Problems with the log-softmax / KL epilogue: always the 128 x 128 kernel, whose column tiling the number
 // of parts per row (kl_parts_per_row) is derived from.
-hipError_t launch_gemm_fp8_kl(const GemmProb* probs, int n_probs, int max_M, int max_N, hipStream_t s) {
+hipError_t launch_gemm_fp8_kl(const GemmProb* probs, int n_probs, int max_M, int max_N, int b16, hipStream_t s) {
   if (n_probs == 0 || max_M == 0 || max_N == 0) return hipSuccess;
   int tiles = ((max_M + 127) / 128) * ((max_N + 127) / 128);
   int gx = (tiles + 7) / 8 * 8;
   if (gx > 512) gx = 512;
-  hipLaunchKernelGGL((gemm_x_k<2, 2, 4, 4>), dim3(gx, n_probs), dim3(256), 0, s, probs);
+  if (b16) hipLaunchKernelGGL((gemm_x_k<2, 2, 4, 4, true>), dim3(gx, n_probs), dim3(256), 0, s, probs);
+  else hipLaunchKernelGGL((gemm_x_k<2, 2, 4, 4>), dim3(gx, n_probs), dim3(256), 0, s, probs);
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, hipStream_t s) {
+hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, int b16, hipStream_t s) {
   if (n_probs == 0 || max_M == 0 || max_N == 0) return hipSuccess;
+  if (b16) {
+    // bfloat16 operands: the two-stage kernel at every size (the three-stage kernel has no such form)
+    if (!exact) return hipErrorInvalidValue;
+    const bool wide = max_N > 64;
+    int tiles = ((max_M + 127) / 128) * (wide ? (max_N + 127) / 128 : (max_N + 63) / 64);
+    int gx = (tiles + 7) / 8 * 8;
+    if (gx > 512) gx = 512;
+    dim3 grid(gx, n_probs);
+    if (wide) hipLaunchKernelGGL((gemm_x_k<2, 2, 4, 4, true>), grid, dim3(256), 0, s, probs);
+    else hipLaunchKernelGGL((gemm_x_k<4, 1, 2, 4, true>), grid, dim3(256), 0, s, probs);
+    return hipGetLastError();
+  }
   if (exact) {
     // persistent: at most two workgroups per compute unit (64 KB of LDS each), 256 compute units
     const bool wide = max_N > 64;

@@ -52,7 +52,8 @@ struct GemmProb {
   // result rows the kernel leaves, per row and per 64-column part p of the row, (max, sum exp(x - max),
   // sum p_ref * (kl_ref - x), 0) in kl_part[row][p] with p_ref = exp(kl_ref - kl_ref_logz); kl_ref is [rpi][ldc]
   // (reference logits), kl_ref_logz [rpi]; both may be null (then the third value is 0).  C may be null.
-  const float* kl_ref; const double* kl_ref_logz; float* kl_part; int kl_npart; int pad_;
+  const float* kl_ref; const double* kl_ref_logz; float* kl_part; int kl_npart;
+  int b16;             // operands are bfloat16 patterns, two bytes per element (lda, ldw, K stay in bytes), not e4m3 codes
 };
 // Parts per row of the log-softmax / KL epilogue (128-column tiles, two wavefronts across).
 inline int kl_parts_per_row(int N) { return (N + 127) / 128 * 2; }
@@ -128,7 +129,7 @@ hipError_t launch_patch_build(const GroupDesc* g, const float* xv, const float* 
 hipError_t launch_xv_advance(float* xv, const float* delta0, long long delta_stride, const int* send, int k,
                              long long n_elem, hipStream_t s);
 // out = base + sum(terms) over n_elem elements (instance 0 of every term)
-hipError_t launch_gemm_fp8_kl(const GemmProb* probs, int n_probs, int max_M, int max_N, hipStream_t s);
+hipError_t launch_gemm_fp8_kl(const GemmProb* probs, int n_probs, int max_M, int max_N, int b16, hipStream_t s);
 // One wavefront per row of kl_part: logz[row] = log sum exp of the row from its parts (if logz != null);
 // row_kl[row] = a - (ref_logz[row % B] - logz) * ref_psum[row % B] with a = the sum of the parts' third values
 // (if row_kl != null); then kl[i] = mean over the B rows of instance i (if kl != null).
@@ -143,7 +144,8 @@ hipError_t launch_tile_sub(float* out, const float* a, const float* b, long long
 
 // exact = 0: FP8 matrix-core instruction; exact = 1: codes decoded to fp16, fp16 matrix cores (exact
 // products, fp32 sums).
-hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, hipStream_t s);
+// b16: the problems' operands are bfloat16 patterns (exact products on the bf16 matrix cores, fp32 sums)
+hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, int b16, hipStream_t s);
 hipError_t launch_gemm_f32(const GemmProb* probs, int n_probs, int max_M, int max_N, hipStream_t s);
 hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const HeadAux* auxs, int M, int N, int H, int dh,
                               int exact, hipStream_t s);
@@ -192,7 +194,7 @@ hipError_t launch_quant_rows_plain(const float* x, int rows, int cols, uint8_t* 
 // the fp32 unembedding [d][ldw]); score[inst] = mean_b (ref_ld[b] - ld[inst * B + b]).
 hipError_t launch_logit_pair(const uint8_t* codes, long long c_is, const float* scale, long long s_is, int ldq, int K,
                              const uint8_t* wcodes, int ldw, const float* wscale, const float* bias, const int* ans,
-                             const int* dis, int n_inst, int B, double* ld, hipStream_t s);
+                             const int* dis, int n_inst, int B, double* ld, int b16, hipStream_t s);
 hipError_t launch_logit_pair_f32(const float* x, long long x_is, int d, const float* W, int ldw, const float* bias,
                                  const int* ans, const int* dis, int n_inst, int B, double* ld, hipStream_t s);
 hipError_t launch_metric_mean(const double* ld, const double* ref_ld, double* score, int n_inst, int B, hipStream_t s);

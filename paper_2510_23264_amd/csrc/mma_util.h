@@ -10,6 +10,7 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 // Eight e4m3 codes (two 32-bit words) -> eight fp16 values with the hardware
 // converter (V_CVT_SCALEF32_PK_F16_FP8, scale 1): exact for every finite code,

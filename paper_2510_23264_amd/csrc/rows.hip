@@ -56,7 +56,7 @@ __global__ void quant_transpose_k(const float* w, int K, int N, const unsigned* 
                                   uint8_t* codes, int ldq, int qbits) {
   __shared__ float tile[32][33];
   float amax = __uint_as_float(*amax_bits);
-  float scale = (amax == 0.f) ? 1.0f : amax / q_top(qbits);
+  float scale = (amax == 0.f || qbits == 16) ? 1.0f : amax / q_top(qbits);      // bfloat16 has no scale
   float inv = 1.0f / scale;
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && threadIdx.y == 0) *scale_out = scale;
   int k0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
@@ -67,7 +67,10 @@ __global__ void quant_transpose_k(const float* w, int K, int N, const unsigned* 
   __syncthreads();
   for (int r = threadIdx.y; r < 32; r += 8) {
     int n = n0 + r, k = k0 + threadIdx.x;
-    if (n < N && k < K) codes[(long long)n * ldq + k] = (uint8_t)q_encode(tile[threadIdx.x][r] * inv, qbits);
+    if (n < N && k < K) {
+      if (qbits == 16) *(uint16_t*)(codes + (long long)n * ldq + 2 * k) = (uint16_t)bf16_rne(tile[threadIdx.x][r]);     // ldq in bytes
+      else codes[(long long)n * ldq + k] = (uint8_t)q_encode(tile[threadIdx.x][r] * inv, qbits);
+    }
   }
 }
 hipError_t launch_quant_transpose(const float* w, int K, int N, const unsigned* amax_bits, float* scale_out,
@@ -200,7 +203,24 @@ __device__ __forceinline__ void emit_row(const float (&y)[MAXE], int E, int d, i
       for (int j = 0; j < MAXE; j++) if (j < E) o[lane + 64 * j] = y[j];
     }
   }
-  if (g.out_codes) {
+  if (g.out_codes && g.qbits == 16) {
+    // bfloat16 rows: two bytes per element, rows of exactly 2 d bytes (d is a multiple of 64: no padding; ldq is the
+    // launch's stride for one-byte codes), no scale (the scale array gets 1 so that the product's epilogue is the same)
+    uint8_t* o = g.out_codes + inst * g.out_codes_is + (long long)row * (2 * d);
+    if (VEC) {
+#pragma unroll
+      for (int q = 0; q < MAXE / 4; q++) if (4 * q < E) {
+        uint2 w;
+        w.x = bf16_rne(y[4 * q]) | (bf16_rne(y[4 * q + 1]) << 16);
+        w.y = bf16_rne(y[4 * q + 2]) | (bf16_rne(y[4 * q + 3]) << 16);
+        *(uint2*)(o + (q * 64 + lane) * 8) = w;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < MAXE; j++) if (j < E) *(uint16_t*)(o + (lane + 64 * j) * 2) = (uint16_t)bf16_rne(y[j]);
+    }
+    if (lane == 0) g.out_scale[inst * g.out_scale_is + row] = 1.0f;
+  } else if (g.out_codes) {
     float am = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXE; j++) if (j < E) am = fmaxf(am, fabsf(y[j]));
@@ -535,9 +555,11 @@ __global__ __launch_bounds__(256) void hidden_quant_k(const float* up, const flo
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = am;
   __syncthreads();
   am = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  float sc = (am == 0.f) ? 1.0f : am / q_top(qbits);
+  float sc = (am == 0.f || qbits == 16) ? 1.0f : am / q_top(qbits);
   float inv = 1.0f / sc;
   uint8_t* o = codes + inst * c_is + (long long)row * ldq;
+  if (qbits == 16) { for (int i = threadIdx.x; i < m; i += 256) *(uint16_t*)(o + 2 * i) = (uint16_t)bf16_rne(hidden_value(pu, pg, i, act)); }
+  else
   for (int i = threadIdx.x; i < m; i += 256) o[i] = (uint8_t)q_encode(hidden_value(pu, pg, i, act) * inv, qbits);
   if (threadIdx.x == 0) scale[inst * s_is + row] = sc;
 }
@@ -588,9 +610,23 @@ __global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const
     am = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   }
   if (!live) return;
-  const float sc = (am == 0.f) ? 1.0f : am / q_top(qbits);
+  const float sc = (am == 0.f || qbits == 16) ? 1.0f : am / q_top(qbits);
   const float inv = 1.0f / sc;
   uint8_t* o = codes + inst * c_is + (long long)row * ldq;
+  if (qbits == 16) {
+#pragma unroll
+    for (int j = 0; j < NV; j++) {
+      int e = (j * TPR + t) * 4;
+      if (e < m) {
+        uint2 w;
+        w.x = bf16_rne(v[j].x) | (bf16_rne(v[j].y) << 16);
+        w.y = bf16_rne(v[j].z) | (bf16_rne(v[j].w) << 16);
+        *(uint2*)(o + 2 * e) = w;
+      }
+    }
+    if (t == 0) scale[inst * s_is + row] = 1.0f;
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < NV; j++) {
     int e = (j * TPR + t) * 4;
@@ -606,8 +642,9 @@ __global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const
 hipError_t launch_hidden_quant(const float* up, const float* gate, long long h_is, uint8_t* codes, long long c_is,
                                float* scale, long long s_is, int n_inst, int T, int m, int ldq, int act, int qbits,
                                hipStream_t s) {
-  const bool vec = (m % 4 == 0) && (ldq % 4 == 0) && (h_is % 4 == 0) && (c_is % 4 == 0) &&
-                   ((((uintptr_t)up) | ((uintptr_t)gate)) % 16 == 0) && (((uintptr_t)codes) % 4 == 0);
+  const int ca = qbits == 16 ? 8 : 4;       // bytes four codes take
+  const bool vec = (m % 4 == 0) && (ldq % ca == 0) && (h_is % 4 == 0) && (c_is % ca == 0) &&
+                   ((((uintptr_t)up) | ((uintptr_t)gate)) % 16 == 0) && (((uintptr_t)codes) % ca == 0);
 #define HQV_(TPR_, NV_, ACT_)                                                                                    \
   hipLaunchKernelGGL((hidden_quant_vec_k<TPR_, NV_, ACT_>), dim3((T + 256 / TPR_ - 1) / (256 / TPR_), n_inst),   \
                      dim3(256), 0, s, up, gate, h_is, codes, c_is, scale, s_is, T, m, ldq, qbits)
