@@ -77,7 +77,7 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
 size_t arena_slot_bytes(const pahq_model* M) {
   size_t Nr = M->g.Nr, Ns = M->g.Ns, L = M->L, H = M->H;
   size_t b = Nr * sizeof(GroupDesc) + Nr * (Ns / 2 + 2) * sizeof(Term) + L * (5 * H + 8) * sizeof(GemmProb) +
-             4 * L * sizeof(CombineDesc) + L * (H + 3) * sizeof(CombineSrc) + L * sizeof(OprojDesc) +
+             4 * L * sizeof(CombineDesc) + L * (H + 3) * sizeof(CombineSrc) + (L + H) * sizeof(OprojDesc) +
              L * H * sizeof(HeadAux) + 65536;
   return (b + 4095) / 4096 * 4096;
 }
@@ -118,7 +118,8 @@ size_t layout(pahq_model* M, char* base) {
   M->rc = b.take<float>((2 * L + 1) * tile); M->rx = b.take<float>((2 * L + 1) * tile);
   M->logits_clean = b.take<float>(B * Vp); M->logits_corrupt = b.take<float>(B * Vp); M->logz_clean = b.take<double>(B);
   M->cpi = b.take<float>(Ns * tile); M->rxpi = b.take<float>((2 * L + 1) * tile);
-  M->ref_logits = b.take<float>(B * Vp); M->ref_logz = b.take<double>(B);
+  M->ref_logits_all = b.take<float>(H * B * Vp); M->ref_logz_all = b.take<double>(H * B);
+  M->ref_logits = M->ref_logits_all; M->ref_logz = M->ref_logz_all;
   M->xv = b.take<float>(tile);
   M->qkv_sh = b.take<float>(T * 3 * H * dh); M->oth = b.take<float>(tile); M->xvc = b.take<float>(3 * tile); M->deadsum = b.take<float>(L * tile); M->sh_slots = b.take<float>(H * tile);
   M->qv = b.take<float>(n * T * dh);
@@ -140,8 +141,8 @@ size_t layout(pahq_model* M, char* base) {
   }
   M->slots = b.take<float>((size_t)M->pool_tiles * tile);
   M->row_kl = b.take<double>(n * B); M->kl_dev = b.take<double>(M->ncap);
-  M->psum_clean = b.take<double>(B); M->psum_ref = b.take<double>(B);
-  M->ans_dev = b.take<int>(B); M->dis_dev = b.take<int>(B); M->ld_clean = b.take<double>(B); M->ld_ref = b.take<double>(B);
+  M->psum_clean = b.take<double>(B); M->psum_ref_all = b.take<double>(H * B); M->psum_ref = M->psum_ref_all;
+  M->ans_dev = b.take<int>(B); M->dis_dev = b.take<int>(B); M->ld_clean = b.take<double>(B); M->ld_ref_all = b.take<double>(H * B); M->ld_ref = M->ld_ref_all;
   M->kl_npart = kl_parts_per_row((int)V); M->kl_part = b.take<float>(n * B * (size_t)M->kl_npart * 4);
   M->arena.slot_bytes = arena_slot_bytes(M);
   for (int i = 0; i < Arena::SLOTS; i++) M->arena.dev[i] = b.take<char>(M->arena.slot_bytes);
@@ -228,7 +229,22 @@ int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
     PassArgs a; a.n = 1; a.p0 = ctx.p0; a.pl = ctx.pl; a.ph = ctx.ph; a.v = -1; a.patch_mode = 0;
     if (M->pi_l != ctx.pl || M->pi_h != ctx.ph) {
       M->pi_l = M->pi_h = -2; M->pi_corrupt = false;
-      a.kind = PI_REF; PCHK(run_pass(M, a, nullptr));          // the reference distribution under this head's precision set
+      // The reference distribution under this head's precision set.  The reference runs of all H heads of a layer go
+      // as one pass of H instances where the model has room for them (they differ only in which head of that layer is
+      // in fp32); the state of head h is then copy h of the arrays that pass fills.
+      const bool layerwise = M->H > 1 && M->H <= M->nmax && M->cfg.mma == PAHQ_MMA_F16_EXACT;
+      const int copy = layerwise ? ctx.ph : 0;
+      M->ref_logits = M->ref_logits_all + (long long)copy * M->B * M->Vp;
+      M->ref_logz = M->ref_logz_all + (long long)copy * M->B;
+      M->psum_ref = M->psum_ref_all + (long long)copy * M->B;
+      M->ld_ref = M->ld_ref_all + (long long)copy * M->B;
+      if (!layerwise) { M->ref_layer = -1; a.kind = PI_REF; PCHK(run_pass(M, a, nullptr)); }
+      else if (M->ref_layer != ctx.pl) {
+        M->ref_layer = -1;
+        PassArgs r = a; r.kind = PI_REF_LAYER; r.n = M->H; r.ph = -1;
+        PCHK(run_pass(M, r, nullptr));
+        M->ref_layer = ctx.pl;
+      }
       M->pi_l = ctx.pl; M->pi_h = ctx.ph;
     }
     // The corrupted run under the same precision set is read only where the plan has a receiver in kept form
@@ -420,7 +436,7 @@ int pahq_init_model(const pahq_config* c, const pahq_weights* w, int32_t B, int3
   M->edge_off.assign(M->g.Nr + 1, 0);
   for (int r = 0; r < M->g.Nr; r++) M->edge_off[r + 1] = M->edge_off[r] + M->g.n_upstream(r);
   M->removed.assign((size_t)M->edge_off[M->g.Nr], 0);
-  M->has_cache = false; M->pi_l = M->pi_h = -2; M->pi_p0 = -1;
+  M->has_cache = false; M->pi_l = M->pi_h = -2; M->pi_p0 = -1; M->ref_layer = -1;
   M->metric = PAHQ_METRIC_KL;
   M->counters[0] = M->counters[1] = M->counters[2] = 0;
   M->prof_on = false; M->prof_used = 0; memset(M->prof, 0, sizeof(M->prof));
@@ -454,7 +470,7 @@ int pahq_clean_cache(pahq_model* M, const int32_t* clean_tok, const int32_t* cor
   HIPCHK(launch_tile_sub(M->delta, M->clean, M->corrupt, (long long)M->g.Ns * M->tile, M->stream));
   HIPCHK(hipStreamSynchronize(M->stream));
   std::fill(M->removed.begin(), M->removed.end(), 0);
-  M->has_cache = true; M->pi_l = M->pi_h = -2;
+  M->has_cache = true; M->pi_l = M->pi_h = -2; M->ref_layer = -1;
   return PAHQ_OK;
 }
 
@@ -471,7 +487,7 @@ int pahq_set_metric(pahq_model* M, int32_t metric, const int32_t* answer_ids, co
   }
   M->metric = metric;
   M->has_cache = false;          // the reference values of the metric are taken by the cache pass
-  M->pi_l = M->pi_h = -2;
+  M->pi_l = M->pi_h = -2; M->ref_layer = -1;
   return PAHQ_OK;
 }
 
@@ -687,7 +703,7 @@ int pahq_eval_circuit(pahq_model* M, const uint8_t* kept, const uint8_t* f32_hea
     if (any) {
       // corrupted run and reference distribution under this precision set (they replace the state of the
       // last investigated head)
-      M->pi_l = M->pi_h = -2;
+      M->pi_l = M->pi_h = -2; M->ref_layer = -1;
       a.kind = PI_CORRUPT; if ((rc = run_pass(M, a, nullptr)) != PAHQ_OK) break;
       a.kind = PI_REF; if ((rc = run_pass(M, a, nullptr)) != PAHQ_OK) break;
     }
@@ -729,7 +745,7 @@ int eval_pair_sender(pahq_model* M, int v, int u, double* kl_cur, double* kl_new
   PassArgs a; a.n = 1; a.p0 = p0; a.pl = a.ph = -1; a.v = -1; a.patch_mode = 0;
   a.heads = any ? masks.data() : nullptr;
   if (any) {
-    M->pi_l = M->pi_h = -2;
+    M->pi_l = M->pi_h = -2; M->ref_layer = -1;
     a.kind = PI_CORRUPT; PCHK(run_pass(M, a, nullptr));
     a.kind = PI_REF; PCHK(run_pass(M, a, nullptr));
   }

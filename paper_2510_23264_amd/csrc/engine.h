@@ -10,7 +10,7 @@
 
 namespace pahq {
 
-enum PassKind { BASE_CLEAN = 0, BASE_CORRUPT, PI_CORRUPT, PI_REF, STATE, CAND, PREFIX };
+enum PassKind { BASE_CLEAN = 0, BASE_CORRUPT, PI_CORRUPT, PI_REF, STATE, CAND, PREFIX, PI_REF_LAYER };
 
 struct PassArgs {
   PassKind kind;
@@ -63,7 +63,9 @@ struct pahq_model {
   float *rc, *rx;                         // [2L+1] residual prefixes (entry 0 unused: it is sender 0's tile)
   float *logits_clean, *logits_corrupt;   // [B][V]
   double* logz_clean;                     // [B]
-  float *cpi, *rxpi, *ref_logits; double* ref_logz;   // state of the current fp32 head
+  float *cpi, *rxpi, *ref_logits; double* ref_logz;   // state of the current fp32 head (the ref_* point into the *_all arrays)
+  float* ref_logits_all; double *ref_logz_all, *psum_ref_all, *ld_ref_all;   // [H] copies: the reference runs of all heads of layer ref_layer
+  int ref_layer = -1;                     // layer whose H reference runs the *_all arrays hold (one H-instance pass), or -1
   long long plan_serial = 0;              // counts make_plan calls: the per-layer sums of dead heads' stand-ins are kept per plan
   std::vector<long long> deadsum_tag;     // per layer: 2 * plan_serial + (precision-set pass) the layer's tile was made for, or -1
   int qbits;                              // grid of the low-precision operands: 8 = E4M3, 4 = 4-bit round-to-nearest

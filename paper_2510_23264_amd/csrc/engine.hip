@@ -315,6 +315,81 @@ struct Builder {
     run = nxt;
   }
 
+  // First layer of the reference runs of all H heads of layer l as one pass of H instances (PI_REF_LAYER): instance i is
+  // the run with head (l, i) in fp32 and nothing removed.  The instances share the layer's input, so everything is
+  // computed once -- the quantised projections and attention of every head, the fp32 projections and attention of every
+  // head -- and instance i's stream is the fused output projection with head i left out plus head i's fp32 output:
+  // launch for launch what the single-head reference pass (attention_block with that one head in fp32) does, with the
+  // same kernels on the same operands, so the two give the same bits.
+  void ref_layer_block(int l, Stream& run) {
+    const int H = M->H, dh = M->dh, d = M->d, T = M->T, Kd = M->Kd, Kh = M->Kh;
+    const unsigned long long all_heads = H >= 64 ? ~0ull : ((1ull << H) - 1ull);
+    const long long qkv_ld = 3LL * H * dh;
+    GroupDesc gd; memset(&gd, 0, sizeof(gd));
+    fill_input(gd, nullptr, 2 * l, run);
+    norm_params(gd, M->ln1_g + (long long)l * d, M->ln1_b + (long long)l * d);
+    gd.out_f32 = M->xf32; gd.out_f32_is = M->tile;
+    gd.out_codes = M->xcodes; gd.out_codes_is = (long long)T * Kd;
+    gd.out_scale = M->xscale; gd.out_scale_is = T;
+    int gi = (int)groups.size();
+    groups.push_back(gd);
+    add_op(OP_BUILD, gi, 1, -1, 0); ops.back().u64 = 1;            // one instance
+    work_build(gi, 1); ops.back().bytes /= a.n;
+    // quantised projections of all heads -> qkv_sh; fp32 projections of all heads -> qkv
+    int pb = (int)probs.size();
+    GemmProb p8 = prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
+                        M->qkv_codes + (long long)l * 3 * H * dh * Kd, Kd, M->qkv_scale + (long long)l * 3 * H, dh,
+                        M->bqkv + (long long)l * 3 * H * dh, M->qkv_sh, (long long)T * qkv_ld, (int)qkv_ld, 0, T, 3 * H * dh, Kd, d);
+    p8.M = T;
+    probs.push_back(p8);
+    add_op(OP_GEMM8, pb, 1, T, 3 * H * dh); work_gemm(pb);
+    int pf = (int)probs.size();
+    const float* Wc[3] = {M->W_Q, M->W_K, M->W_V};
+    const float* bc[3] = {M->b_Q, M->b_K, M->b_V};
+    for (int h = 0; h < H; h++)
+      for (int c = 0; c < 3; c++) {
+        const long long hoff = (long long)l * H + h;
+        GemmProb pq = prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1, bc[c] + hoff * dh,
+                            M->qkv + ((long long)c * H + h) * dh, (long long)T * qkv_ld, (int)qkv_ld, 0, T, dh, d, d);
+        pq.M = T;
+        probs.push_back(pq);
+      }
+    add_op(OP_GEMM32, pf, 3 * H, T, dh); work_gemm(pf);
+    for (int f32 = 0; f32 < 2; f32++) {
+      const float* buf = f32 ? M->qkv : M->qkv_sh;
+      AttnSrc src; memset(&src, 0, sizeof(src));
+      src.q = buf; src.k = buf + H * dh; src.v = buf + 2 * H * dh;
+      src.q_ld = src.k_ld = src.v_ld = (int)qkv_ld;
+      src.n_heads = H; src.h0 = 0; src.head_cols = dh;
+      add_attention(src, f32 ? all_heads : 0ull);
+      ops.back().i1 = 0; ops.back().i2 = 1;                          // one instance
+    }
+    // every head's fp32 output (H problems, one launch), then per instance the fused projection of the other heads
+    pf = (int)probs.size();
+    for (int h = 0; h < H; h++) {
+      GemmProb pp = prob8(M->zf32 + (long long)h * dh, (long long)T * H * dh, H * dh, nullptr, 0, 0,
+                          M->W_O + ((long long)l * H + h) * dh * d, d, nullptr, 1, nullptr, M->headout + (long long)h * M->tile, M->tile, d, 0, T, d, dh, dh);
+      pp.M = T;
+      probs.push_back(pp);
+    }
+    add_op(OP_GEMM32, pf, H, T, d); work_gemm(pf);
+    Stream nxt = next_run(2 * l + 1, run.p == M->run_a ? M->run_b : M->run_a);
+    for (int h = 0; h < H; h++) {
+      OprojDesc od; memset(&od, 0, sizeof(od));
+      od.zc = M->zcodes; od.zc_is = (long long)T * H * Kh; od.zs = M->zscale; od.zs_is = (long long)T * H;
+      od.W = M->o_codes + (long long)l * H * d * Kh; od.ws = M->o_scale + (long long)l * H;
+      od.run_in = run.p; od.run_in_is = run.is; od.run_out = nxt.p + (long long)h * nxt.is; od.run_out_is = nxt.is;
+      od.bias = M->b_O + (long long)l * d;
+      od.H = H; od.Kh = Kh; od.skip_mask = 1ull << h; od.rpi = T; od.M = T; od.N = d;
+      od.aux_begin = -1; od.dh = M->dh;
+      od.extra = M->headout + (long long)h * M->tile; od.extra_is = M->tile;
+      odescs.push_back(od);
+      add_op(OP_OPROJ, (int)odescs.size() - 1, T, d);
+      ops.back().flops = 2.0 * T * d * dh * (H - 1);
+    }
+    run = nxt;
+  }
+
   void attention_block(int l, Stream& run) {
     const GraphDims& g = M->g;
     const int H = M->H, dh = M->dh, d = M->d, T = M->T, Kd = M->Kd, Kh = M->Kh;
@@ -581,8 +656,8 @@ struct Builder {
   // The logit-difference metric of the rows the final group just produced: for a reference pass into that
   // run's reference values, for a scored pass into one score per instance.
   void add_logit_diff() {
-    const bool ref_pass = a.kind == BASE_CLEAN || a.kind == PI_REF;
-    if (ref_pass) add_op(OP_LD, 0, 0, 0, 0, a.kind == BASE_CLEAN ? M->ld_clean : M->ld_ref);
+    const bool ref_pass = a.kind == BASE_CLEAN || a.kind == PI_REF || a.kind == PI_REF_LAYER;
+    if (ref_pass) add_op(OP_LD, 0, 0, 0, 0, a.kind == BASE_CLEAN ? M->ld_clean : (a.kind == PI_REF_LAYER ? M->ld_ref_all : M->ld_ref));
     else if (general) add_op(OP_LD, 1, 0, 0, 0, has_pi ? M->ld_ref : M->ld_clean);
     else return;
     ops.back().bytes = (double)a.n * M->B * (3.0 * M->d + 16.0);
@@ -621,6 +696,7 @@ struct Builder {
       case BASE_CLEAN: lg = M->logits_clean; break;
       case BASE_CORRUPT: lg = M->logits_corrupt; break;
       case PI_REF: lg = M->ref_logits; break;
+      case PI_REF_LAYER: lg = M->ref_logits_all; lg_is = (long long)B * Vp; break;
       default: lg = M->logits; lg_is = (long long)B * Vp; break;
     }
     int pb = (int)probs.size();
@@ -644,7 +720,7 @@ struct Builder {
     // reference passes also keep their logits and get their log-sum-exp from the same parts, so that a candidate
     // with the reference's logits scores exactly 0.  The FP8 matrix-core mode keeps the two-kernel path.
     const bool fused = M->cfg.mma == PAHQ_MMA_F16_EXACT;
-    const bool ref_pass = a.kind == BASE_CLEAN || a.kind == PI_REF;
+    const bool ref_pass = a.kind == BASE_CLEAN || a.kind == PI_REF || a.kind == PI_REF_LAYER;
     if (fused && (ref_pass || general)) {
       GemmProb& q = probs.back();
       q.kl_part = M->kl_part; q.kl_npart = M->kl_npart;
@@ -657,11 +733,13 @@ struct Builder {
       const double part_bytes = (double)a.n * B * M->kl_npart * 16.0;
       ops.back().bytes += part_bytes;
       if (ref_pass) {
-        const bool cl = a.kind == BASE_CLEAN;
-        add_op(OP_KLRED, 0, 0, 0, 0, cl ? M->logz_clean : M->ref_logz, nullptr);
+        const bool cl = a.kind == BASE_CLEAN, lay = a.kind == PI_REF_LAYER;      // lay: a.n reference runs side by side
+        add_op(OP_KLRED, 0, 0, 0, 0, cl ? M->logz_clean : (lay ? M->ref_logz_all : M->ref_logz), nullptr);
         ops.back().bytes = part_bytes;
-        add_op(OP_PREF, 0, 0, 0, 0, cl ? (void*)M->logits_clean : (void*)M->ref_logits, nullptr);
-        ops.back().bytes = (double)B * V * 4.0;
+        add_op(OP_PREF, 0, 0, 0, 0, cl ? (void*)M->logits_clean : (lay ? (void*)M->ref_logits_all : (void*)M->ref_logits),
+               cl ? (void*)M->psum_clean : (lay ? (void*)M->psum_ref_all : (void*)M->psum_ref));
+        ops.back().u64 = (unsigned long long)(uintptr_t)(cl ? M->logz_clean : (lay ? M->ref_logz_all : M->ref_logz));
+        ops.back().bytes = (double)a.n * B * V * 4.0;
       } else {
         add_op(OP_KLRED, 1, 0, 0, 0, has_pi ? M->ref_logz : M->logz_clean, has_pi ? M->psum_ref : M->psum_clean);
         ops.back().bytes = part_bytes;
@@ -698,6 +776,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
     for (int l = a.p0 / 2; l < L; l++) {
       if (a.p0 <= 2 * l) {
         if (a.kind == CAND && plan->split_first && 2 * l == a.p0) b.first_block_split(l, run);
+        else if (a.kind == PI_REF_LAYER && 2 * l == a.p0) b.ref_layer_block(l, run);
         else b.attention_block(l, run);
       }
       if (M->g.mu && a.p0 <= 2 * l + 1) b.mlp_block(l, run);
@@ -761,7 +840,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         // the patched receiver's group (if any) is built by the edge-batched patch kernel
         int pg = o.i2;
         if (pg < 0) {
-          HIPCHK(launch_build_inputs(d_groups + o.i0, o.i1, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, o.i3, st));
+          HIPCHK(launch_build_inputs(d_groups + o.i0, o.i1, d_terms, o.u64 ? 1 : n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, o.i3, st));
         } else {
           if (pg > o.i0)
             HIPCHK(launch_build_inputs(d_groups + o.i0, pg - o.i0, d_terms, n, T, B, S, d, M->Kd, M->cfg.norm, M->cfg.norm_eps, o.i3, st));
@@ -785,14 +864,13 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         }
         break;
       case OP_KLRED:
-        if (o.i0 == 0) HIPCHK(launch_kl_reduce(M->kl_part, M->kl_npart, B, B, nullptr, nullptr, (double*)o.p0, nullptr, nullptr, st));
+        if (o.i0 == 0) HIPCHK(launch_kl_reduce(M->kl_part, M->kl_npart, n * B, B, nullptr, nullptr, (double*)o.p0, nullptr, nullptr, st));
         else HIPCHK(launch_kl_reduce(M->kl_part, M->kl_npart, n * B, B, (const double*)o.p0, (const double*)o.p1, nullptr,
                                      M->row_kl, M->kl_dev + a.io_off, st));
         break;
       case OP_PREF: {
-        const bool cl = o.p0 == (void*)M->logits_clean;
-        HIPCHK(launch_ref_probs((const float*)o.p0, cl ? M->logz_clean : M->ref_logz, cl ? M->psum_clean : M->psum_ref, B,
-                                M->V, M->Vp, st));
+        // n reference runs side by side (their logits, log-sum-exps and sums are contiguous copies)
+        HIPCHK(launch_ref_probs((const float*)o.p0, (const double*)(uintptr_t)o.u64, (double*)o.p1, n * B, M->V, M->Vp, st));
         break;
       }
       case OP_GEMM32: HIPCHK(launch_gemm_f32(d_probs + o.i0, o.i1, o.i2, o.i3, st)); break;
