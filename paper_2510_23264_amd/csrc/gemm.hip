@@ -286,7 +286,15 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
   };
 
   int lin = xcd * chunk + j;
-  int m0 = (lin / nt) * BM, n0 = (lin % nt) * BN;
+  // Order of an XCD's tiles: neighbours share the larger operand.  With more weight rows than activation rows (the
+  // unembedding: 50 257 columns against a few thousand rows) consecutive tiles walk down the rows of one column tile, so
+  // that the weights cross HBM once and the small activation block is what the L2 re-serves; otherwise row tile first.
+  const bool col_first = P.N > P.M;
+  auto origin = [&](int t, int& mo, int& no) {
+    if (col_first) { mo = (t % mt) * BM; no = (t / mt) * BN; } else { mo = (t / nt) * BM; no = (t % nt) * BN; }
+  };
+  int m0, n0;
+  origin(lin, m0, n0);
   set_src(m0, n0);
   issue(st0, 0);
   // With an even number of slabs the last slab of a tile sits in st1 while st0 is idle: the first
@@ -307,7 +315,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 2) void gemm_x_k(const GemmP
     const int jn = j + per;
     const bool more = jn < jend;
     int m0n = 0, n0n = 0;
-    if (more) { int l2 = xcd * chunk + jn; m0n = (l2 / nt) * BM; n0n = (l2 % nt) * BN; }
+    if (more) origin(xcd * chunk + jn, m0n, n0n);
     const bool early = even && more;
 
     // slab 0 has landed for every wave; st1 is free

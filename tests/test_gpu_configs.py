@@ -101,10 +101,11 @@ def test_cfg5_full_size_properties():
 
 
 def pooled_increment_spread(name):
-    """rms over the stored cases of a workload of the spread binary32 arithmetic leaves in an increment."""
+    """rms over the stored cases of a workload of the spread binary32 arithmetic leaves in an increment
+    (0 where the stored values carry none: the bound is then the tight one)."""
     gold = json.load(open(os.path.join(GOLDEN, "kl_%s.json" % name)))
     if "spread_eps" not in gold:
-        pytest.skip("stored values of %s carry no binary32 spread" % name)
+        return 0.0
     return pooled([v for c in gold["cases"] for v in c["sigma_inc"]])
 
 
