@@ -69,3 +69,34 @@ def test_edge_list_equals_per_receiver_calls(name, mode):
             gm.eval_edge_list(np.array([g.n_receivers - 1], np.int32), np.array([0], np.int32))
     finally:
         gm.close()
+
+
+@pytest.mark.parametrize("name", ["mid_hi", "midllama_hi", "cfg1_hi"])
+def test_layerwise_reference_runs_equal_single_head_runs(name):
+    """The reference runs of all heads of a layer as one pass (models with room for H instances) against one pass
+    per head (a model whose batch limit is below H): the same reference logits bit for bit, for every head, and the
+    same per-edge values -- under both metrics."""
+    import paper_2510_23264_amd as P
+    import synth
+    shape, w, clean, corrupt = workloads.make(name)
+    B, S = clean.shape
+    H, L = shape.n_heads, shape.n_layers
+    g = Graph(L, H, shape.d_mlp > 0)
+    ans, dis = synth.make_answers(shape.vocab, B, "uniform", 5)
+    one = P.Model(shape, w, B, S, precision=P.PAHQ, max_batch_edges=H - 1)       # no room: one reference pass per head
+    many = P.Model(shape, w, B, S, precision=P.PAHQ, max_batch_edges=max(H, 8))
+    try:
+        for metric in (P.METRIC_KL, P.METRIC_LOGIT_DIFF):
+            for gm in (one, many):
+                gm.set_metric(metric, ans, dis)
+                gm.clean_cache(clean, corrupt)
+            for l in range(L - 1, -1, -1):
+                for h in range(H):
+                    r = g.headin(l, h, (l + h) % 3)
+                    senders = np.arange(g.n_upstream(r), dtype=np.int32)
+                    a, b = one.eval_edges(r, senders), many.eval_edges(r, senders)
+                    assert np.array_equal(bits(a), bits(b)), (name, metric, l, h)
+                    assert np.array_equal(bits(one.get_logits(2)), bits(many.get_logits(2))), (name, metric, l, h)
+                    assert one.eval_current(r) == many.eval_current(r)
+    finally:
+        one.close(); many.close()
