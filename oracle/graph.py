@@ -7,10 +7,14 @@ predecessors.  The appendix on the edge-cutting process reports about 35 000
 starting edges for GPT-2 small, which only the graph with separate query, key
 and value inputs per head reaches (32 491 edges), so head inputs are split.
 
+The coarser graph, in which a head has a single input that its query, key and
+value projections all read (11 611 edges for GPT-2 small), is available with
+split_qkv=False: C = 1 input per head instead of C = 3.
+
 Ids
   senders    0 = EMBED;  HEAD(l,h) = 1 + l*(H+mu) + h;  MLP(l) = 1 + l*(H+mu) + H
-  receivers  HEADIN(l,h,c) = l*(3H+mu) + 3h + c  (c: Q=0, K=1, V=2)
-             MLPIN(l) = l*(3H+mu) + 3H;  OUT = L*(3H+mu)
+  receivers  HEADIN(l,h,c) = l*(C*H+mu) + C*h + c  (C = 3, c: Q=0, K=1, V=2; or C = 1, c ignored)
+             MLPIN(l) = l*(C*H+mu) + C*H;  OUT = L*(C*H+mu)
   with mu = 1 when the model has MLPs, else 0.  Receiver ids ascend in
   topological order.  Canonical edge order: receivers ascending, then senders
   ascending.
@@ -22,10 +26,12 @@ Q, K, V = 0, 1, 2
 
 
 class Graph:
-    def __init__(self, n_layers: int, n_heads: int, has_mlp: bool):
+    def __init__(self, n_layers: int, n_heads: int, has_mlp: bool, split_qkv: bool = True):
         self.L, self.H, self.mu = n_layers, n_heads, 1 if has_mlp else 0
+        self.split = bool(split_qkv)
+        self.C = 3 if self.split else 1              # inputs per head
         self.n_senders = 1 + self.L * (self.H + self.mu)
-        self.n_receivers = self.L * (3 * self.H + self.mu) + 1
+        self.n_receivers = self.L * (self.C * self.H + self.mu) + 1
         self.OUT = self.n_receivers - 1
 
     # ---- senders
@@ -44,20 +50,20 @@ class Graph:
         return ("head", l, r) if r < self.H else ("mlp", l, -1)
 
     # ---- receivers
-    def headin(self, l, h, c):
-        return l * (3 * self.H + self.mu) + 3 * h + c
+    def headin(self, l, h, c=0):
+        return l * (self.C * self.H + self.mu) + self.C * h + (c if self.split else 0)
 
     def mlpin(self, l):
         assert self.mu
-        return l * (3 * self.H + self.mu) + 3 * self.H
+        return l * (self.C * self.H + self.mu) + self.C * self.H
 
     def receiver_info(self, r):
-        """('headin',l,h,c) | ('mlpin',l,-1,-1) | ('out',L,-1,-1)"""
+        """('headin',l,h,c) | ('mlpin',l,-1,-1) | ('out',L,-1,-1); c = -1 for the single input of an unsplit head"""
         if r == self.OUT:
             return ("out", self.L, -1, -1)
-        l, q = divmod(r, 3 * self.H + self.mu)
-        if q < 3 * self.H:
-            return ("headin", l, q // 3, q % 3)
+        l, q = divmod(r, self.C * self.H + self.mu)
+        if q < self.C * self.H:
+            return ("headin", l, q // self.C, q % self.C if self.split else -1)
         return ("mlpin", l, -1, -1)
 
     def n_upstream(self, r):

@@ -77,12 +77,13 @@ def kl_to_reference(logp_ref, logits):
 
 
 class Model:
-    def __init__(self, shape, weights, cache_decoded_bytes=6 << 30, low_bits=8, nonattn_bf16=False):
+    def __init__(self, shape, weights, cache_decoded_bytes=6 << 30, low_bits=8, nonattn_bf16=False, split_qkv=True):
         """shape: any object with the ModelShape attributes; weights: dict of float32 arrays.
         low_bits: the grid of the quantised operands -- 8: e4m3 (the paper's setting); 4: Eq. RTN-Q with
         N = 4 (the 4-bit point of the bit-width ablation, rtn.py).
         nonattn_bf16: the MLP matrices and the unembedding multiply bfloat16-rounded operands instead (paper, Sec.
-        "Selective Precision Allocation Strategy": bfloat16 for the components that are not attention heads)."""
+        "Selective Precision Allocation Strategy": bfloat16 for the components that are not attention heads).
+        split_qkv: False = the coarser graph in which a head's query, key and value projections read one input."""
         if low_bits not in (4, 8):
             raise ValueError("low_bits")
         self.q = e4m3 if low_bits == 8 else Rtn(low_bits)
@@ -91,7 +92,7 @@ class Model:
         self.s = shape
         self.L, self.H, self.dh, self.d = shape.n_layers, shape.n_heads, shape.d_head, shape.d_model
         self.m, self.V = shape.d_mlp, shape.vocab
-        self.g = Graph(self.L, self.H, self.m > 0)
+        self.g = Graph(self.L, self.H, self.m > 0, split_qkv)
         self.w = {k: np.asarray(v, dtype=np.float32) for k, v in weights.items()}
         for k, v in self.w.items():
             if not np.isfinite(v).all():
