@@ -85,7 +85,9 @@ typedef struct {
   int32_t act;              /* PAHQ_ACT_*: GELU is the tanh form; SWIGLU = silu(x W_gate)*(x W_in) */
   int32_t pos;              /* PAHQ_POS_*: ROPE rotates pairs (i, i + d_head/2) of q and k        */
   float norm_eps, rope_theta;
-  int32_t split_qkv;        /* must be 1: query, key and value inputs are separate receivers      */
+  int32_t split_qkv;        /* 1: the query, key and value inputs of a head are separate receivers (the
+                               graph the paper's edge counts fit: 32 491 edges for GPT-2 small);
+                               0: a head has one receiver that all three projections read (11 611)  */
   int32_t precision;        /* PAHQ_PAHQ: fp32 investigated head (the head a candidate edge feeds);
                                PAHQ_ALL_FP8: no fp32 head (all-8-bit RTN baseline);
                                PAHQ_ALL_FP32: no quantiser anywhere, every matrix product on the fp32

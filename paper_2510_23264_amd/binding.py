@@ -29,10 +29,11 @@ class Config(C.Structure):
                [(n, C.c_int32) for n in ("split_qkv", "precision", "max_batch_edges", "mma", "low_bits", "nonattn_bf16")]
 
     @classmethod
-    def from_shape(cls, shape, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, low_bits=8, nonattn_bf16=False):
+    def from_shape(cls, shape, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, low_bits=8, nonattn_bf16=False,
+                   split_qkv=True):
         return cls(n_layers=shape.n_layers, n_heads=shape.n_heads, d_head=shape.d_head, d_model=shape.d_model,
                    d_mlp=shape.d_mlp, vocab=shape.vocab, n_ctx=shape.n_ctx, norm=shape.norm, act=shape.act,
-                   pos=shape.pos, norm_eps=shape.norm_eps, rope_theta=shape.rope_theta, split_qkv=1,
+                   pos=shape.pos, norm_eps=shape.norm_eps, rope_theta=shape.rope_theta, split_qkv=1 if split_qkv else 0,
                    precision=precision, max_batch_edges=max_batch_edges, mma=mma, low_bits=low_bits,
                    nonattn_bf16=1 if nonattn_bf16 else 0)
 
@@ -171,11 +172,11 @@ class Model:
     (layouts as in include/pahq.h)."""
 
     def __init__(self, shape, weights, B, S, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, device="cuda:0",
-                 workspace_bytes_override=None, low_bits=8, nonattn_bf16=False):
+                 workspace_bytes_override=None, low_bits=8, nonattn_bf16=False, split_qkv=True):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no HIP device: libpahq has no CPU path")
-        self.cfg = Config.from_shape(shape, precision, max_batch_edges, mma, low_bits, nonattn_bf16)
+        self.cfg = Config.from_shape(shape, precision, max_batch_edges, mma, low_bits, nonattn_bf16, split_qkv)
         self.B, self.S, self.T = B, S, B * S
         self.n_edges = edge_count(self.cfg)
         nbytes = workspace_bytes(self.cfg, B, S)

@@ -22,13 +22,13 @@ int check_config(const pahq_config* c) {
   if (c->precision < PAHQ_ALL_FP32 || c->precision > PAHQ_PAHQ) return PAHQ_EINVAL;
   if (!(c->norm_eps >= 0.f)) return PAHQ_EINVAL;
   if (c->mma != PAHQ_MMA_FP8 && c->mma != PAHQ_MMA_F16_EXACT) return PAHQ_EINVAL;
+  if (c->split_qkv != 0 && c->split_qkv != 1) return PAHQ_EINVAL;
   if (c->low_bits != 0 && c->low_bits != 4 && c->low_bits != 8) return PAHQ_EINVAL;
   if (c->nonattn_bf16 != 0 && c->nonattn_bf16 != 1) return PAHQ_EINVAL;
   return PAHQ_OK;
 }
 // what this build of the kernels supports
 int check_supported(const pahq_config* c, int B, int S) {
-  if (c->split_qkv != 1) return PAHQ_EUNSUPPORTED;
   if (c->n_heads > 64) return PAHQ_EUNSUPPORTED;                      // sets of heads are 64-bit masks
   if (c->nonattn_bf16 && c->mma != PAHQ_MMA_F16_EXACT && c->precision != PAHQ_ALL_FP32) return PAHQ_EUNSUPPORTED;   // bfloat16 products have no FP8-instruction form
   if (c->d_model % 64 != 0 || c->d_model > 4096) return PAHQ_EUNSUPPORTED;
@@ -55,7 +55,7 @@ struct Bump {
 
 void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
   M->cfg = *c;
-  M->g = GraphDims(c->n_layers, c->n_heads, c->d_mlp > 0);
+  M->g = GraphDims(c->n_layers, c->n_heads, c->d_mlp > 0, c->split_qkv != 0);
   M->B = B; M->S = S; M->T = B * S; M->L = c->n_layers; M->H = c->n_heads; M->dh = c->d_head;
   M->d = c->d_model; M->m = c->d_mlp; M->V = c->vocab;
   M->Kd = pad128(M->d); M->Kh = pad128(M->dh); M->Km = pad128(M->m > 0 ? M->m : 1);
@@ -122,7 +122,7 @@ size_t layout(pahq_model* M, char* base) {
   M->ref_logits = M->ref_logits_all; M->ref_logz = M->ref_logz_all;
   M->xv = b.take<float>(tile);
   M->qkv_sh = b.take<float>(T * 3 * H * dh); M->oth = b.take<float>(tile); M->xvc = b.take<float>(3 * tile); M->deadsum = b.take<float>(L * tile); M->sh_slots = b.take<float>(H * tile);
-  M->qv = b.take<float>(n * T * dh);
+  M->qv = b.take<float>(3 * n * T * dh);
   M->run_a = b.take<float>(n * tile); M->run_b = b.take<float>(n * tile);
   M->xcodes = b.take<uint8_t>(n * G * T * Kd); M->xscale = b.take<float>(n * G * T); M->xf32 = b.take<float>(std::max<size_t>(n * (size_t)M->f32_groups, 3 * H) * tile);
   M->qkv = b.take<float>(n * T * 3 * H * dh);
@@ -296,28 +296,28 @@ extern "C" {
 
 int pahq_n_senders(const pahq_config* c, int32_t* out) {
   if (check_config(c) || !out) return PAHQ_EINVAL;
-  *out = GraphDims(c->n_layers, c->n_heads, c->d_mlp > 0).Ns; return PAHQ_OK;
+  *out = GraphDims(c->n_layers, c->n_heads, c->d_mlp > 0, c->split_qkv != 0).Ns; return PAHQ_OK;
 }
 int pahq_n_receivers(const pahq_config* c, int32_t* out) {
   if (check_config(c) || !out) return PAHQ_EINVAL;
-  *out = GraphDims(c->n_layers, c->n_heads, c->d_mlp > 0).Nr; return PAHQ_OK;
+  *out = GraphDims(c->n_layers, c->n_heads, c->d_mlp > 0, c->split_qkv != 0).Nr; return PAHQ_OK;
 }
 int pahq_n_upstream(const pahq_config* c, int32_t r, int32_t* out) {
   if (check_config(c) || !out) return PAHQ_EINVAL;
-  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0);
+  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0, c->split_qkv != 0);
   if (r < 0 || r >= g.Nr) return PAHQ_EINVAL;
   *out = g.n_upstream(r); return PAHQ_OK;
 }
 int pahq_edge_count(const pahq_config* c, int64_t* out) {
   if (check_config(c) || !out) return PAHQ_EINVAL;
-  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0);
+  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0, c->split_qkv != 0);
   int64_t n = 0;
   for (int r = 0; r < g.Nr; r++) n += g.n_upstream(r);
   *out = n; return PAHQ_OK;
 }
 int pahq_edge_id(const pahq_config* c, int32_t s, int32_t r, int64_t* out) {
   if (check_config(c) || !out) return PAHQ_EINVAL;
-  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0);
+  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0, c->split_qkv != 0);
   if (r < 0 || r >= g.Nr || s < 0 || s >= g.n_upstream(r)) return PAHQ_EINVAL;
   int64_t n = 0;
   for (int q = 0; q < r; q++) n += g.n_upstream(q);
@@ -325,7 +325,7 @@ int pahq_edge_id(const pahq_config* c, int32_t s, int32_t r, int64_t* out) {
 }
 int pahq_node_of_receiver(const pahq_config* c, int32_t r, int32_t* out) {
   if (check_config(c) || !out) return PAHQ_EINVAL;
-  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0);
+  GraphDims g(c->n_layers, c->n_heads, c->d_mlp > 0, c->split_qkv != 0);
   if (r < 0 || r >= g.Nr) return PAHQ_EINVAL;
   *out = g.node_of_receiver(r); return PAHQ_OK;
 }
@@ -558,13 +558,13 @@ int pahq_eval_edge_list(pahq_model* M, int64_t n, const int32_t* receivers, cons
     while (j < n && runs < 3) {
       int k, l, h, c;
       g.receiver_info(receivers[j], k, l, h, c);
-      const bool joins = runs == 0 || (M->cfg.precision == PAHQ_PAHQ && k0 == 0 && k == 0 && l == l0 && h == h0 && c > last_c);
+      const bool joins = runs == 0 || (M->cfg.precision == PAHQ_PAHQ && g.C == 3 && k0 == 0 && k == 0 && l == l0 && h == h0 && c > last_c);
       if (!joins) break;
       int64_t r = j;
       while (r < n && receivers[r] == receivers[j]) r++;
       if (r - i > 0x7fffffff) return PAHQ_ETOOBIG;
-      if (k == 0) { recv3[c] = receivers[j]; cnt3[c] = (int)(r - j); }
-      last_c = k == 0 ? c : 3;
+      if (k == 0 && c >= 0) { recv3[c] = receivers[j]; cnt3[c] = (int)(r - j); }
+      last_c = (k == 0 && c >= 0) ? c : 3;
       runs++;
       j = r;
       if (k != 0) break;

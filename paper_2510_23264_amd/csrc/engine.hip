@@ -266,12 +266,33 @@ struct Builder {
     // candidates, or the candidates of all three inputs of the head side by side (they share everything else)
     int cnt[3] = {0, 0, 0};
     const bool multi = a.chan_count[0] + a.chan_count[1] + a.chan_count[2] > 0;
-    if (multi) { for (int c = 0; c < 3; c++) cnt[c] = a.chan_count[c]; } else cnt[cv] = a.n;
     const float* Wc[3] = {M->W_Q, M->W_K, M->W_V};
     const float* bc[3] = {M->b_Q, M->b_K, M->b_V};
     const long long hoff = (long long)l * H + hv;
     const float* shared0 = M->qkv_sh + (long long)hv * dh;
     const int ld_sh = 3 * H * dh;
+    if (cv < 0) {
+      // a head with a single input: every instance patches it, and all three projections read the patched rows
+      GroupDesc gd; memset(&gd, 0, sizeof(gd));
+      norm_params(gd, M->ln1_g + (long long)l * d, M->ln1_b + (long long)l * d);
+      gd.out_f32 = M->xf32; gd.out_f32_is = M->tile;
+      int g1 = (int)groups.size();
+      groups.push_back(gd);
+      add_patch(g1);
+      const long long blk = (long long)a.n * T * dh;              // q, k, v of all instances one after the other
+      int pq = (int)probs.size();
+      for (int c = 0; c < 3; c++)
+        probs.push_back(prob8(M->xf32, M->tile, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1, bc[c] + hoff * dh,
+                              M->qv + c * blk, (long long)T * dh, dh, 0, T, dh, d, d));
+      add_op(OP_GEMM32, pq, 3, T * a.n, dh); work_gemm(pq);
+      AttnSrc src; memset(&src, 0, sizeof(src));
+      src.q = M->qv; src.k = M->qv + blk; src.v = M->qv + 2 * blk;
+      src.q_is = src.k_is = src.v_is = (long long)T * dh;
+      src.q_ld = src.k_ld = src.v_ld = dh;
+      src.n_heads = 1; src.h0 = hv; src.head_cols = 0;
+      add_attention(src, 1ull << hv);
+    } else {
+    if (multi) { for (int c = 0; c < 3; c++) cnt[c] = a.chan_count[c]; } else cnt[cv] = a.n;
     // patched rows of every range, then their projections in one launch, then the head's attention per range
     int gi[3] = {-1, -1, -1};
     for (int c = 0, off = 0; c < 3; off += cnt[c], c++) {
@@ -283,7 +304,7 @@ struct Builder {
       groups.push_back(gd);
       add_patch(gi[c], off, cnt[c], multi ? M->xvc + (long long)c * M->tile : M->xv);
     }
-    int pf = (int)probs.size(), np = 0;
+    int pq0 = (int)probs.size(), np = 0;
     for (int c = 0, off = 0; c < 3; off += cnt[c], c++) {
       if (!cnt[c]) continue;
       GemmProb pq = prob8(M->xf32 + (long long)off * M->tile, M->tile, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1,
@@ -291,7 +312,7 @@ struct Builder {
       pq.M = T * cnt[c];
       probs.push_back(pq); np++;
     }
-    add_op(OP_GEMM32, pf, np, T * a.n, dh); work_gemm(pf);
+    add_op(OP_GEMM32, pq0, np, T * a.n, dh); work_gemm(pq0);
     for (int c = 0, off = 0; c < 3; off += cnt[c], c++) {
       if (!cnt[c]) continue;
       const float* own = M->qv + (long long)off * T * dh;
@@ -303,9 +324,10 @@ struct Builder {
       add_attention(src, 1ull << hv);
       ops.back().i1 = off; ops.back().i2 = cnt[c];
     }
+    }
     Stream nxt = next_run(2 * l + 1, run.p == M->run_a ? M->run_b : M->run_a);
     int s = g.head(l, hv);
-    pf = (int)probs.size();
+    const int pf = (int)probs.size();
     GemmProb pp = prob8(M->zf32, (long long)T * dh, dh, nullptr, 0, 0, M->W_O + hoff * dh * d, d, nullptr, 1, nullptr,
                         nxt.p, nxt.is, d, 0, T, d, dh, dh);
     pp.add = M->oth; pp.add_is = 0;
@@ -432,9 +454,12 @@ struct Builder {
         const bool is_pi = (fmask >> h) & 1ull;
         int gi;
         if (a.kind == CAND && w == a.v) {
-          GroupDesc gd; memset(&gd, 0, sizeof(gd));
-          norm_params(gd, M->ln1_g + (long long)l * d, M->ln1_b + (long long)l * d);
-          gi = (int)groups.size(); groups.push_back(gd); patch_group = gi;
+          if (patch_group < 0) {           // (a head with a single input meets it three times: one group)
+            GroupDesc gd; memset(&gd, 0, sizeof(gd));
+            norm_params(gd, M->ln1_g + (long long)l * d, M->ln1_b + (long long)l * d);
+            patch_group = (int)groups.size(); groups.push_back(gd);
+          }
+          gi = patch_group;
         } else {
           const RecvSpec* sp = general ? &plan->spec[w] : nullptr;
           std::pair<int, std::vector<int>> key(sp ? sp->form : 0, sp ? sp->senders : std::vector<int>());

@@ -9,22 +9,23 @@ namespace pahq {
 
 struct GraphDims {
   int L, H, mu, Ns, Nr;
-  GraphDims() : L(0), H(0), mu(0), Ns(0), Nr(0) {}
-  GraphDims(int L_, int H_, bool mlp) : L(L_), H(H_), mu(mlp ? 1 : 0) {
+  int C;      // inputs per head: 3 (separate query, key and value receivers) or 1 (one receiver all three projections read)
+  GraphDims() : L(0), H(0), mu(0), Ns(0), Nr(0), C(3) {}
+  GraphDims(int L_, int H_, bool mlp, bool split_qkv = true) : L(L_), H(H_), mu(mlp ? 1 : 0), C(split_qkv ? 3 : 1) {
     Ns = 1 + L * (H + mu);
-    Nr = L * (3 * H + mu) + 1;
+    Nr = L * (C * H + mu) + 1;
   }
   int head(int l, int h) const { return 1 + l * (H + mu) + h; }
   int mlp(int l) const { return 1 + l * (H + mu) + H; }
-  int headin(int l, int h, int c) const { return l * (3 * H + mu) + 3 * h + c; }
-  int mlpin(int l) const { return l * (3 * H + mu) + 3 * H; }
+  int headin(int l, int h, int c) const { return l * (C * H + mu) + C * h + (C == 3 ? c : 0); }
+  int mlpin(int l) const { return l * (C * H + mu) + C * H; }
   int out() const { return Nr - 1; }
-  // kind: 0 headin, 1 mlpin, 2 out
+  // kind: 0 headin, 1 mlpin, 2 out; c = -1 for the single input of an unsplit head
   void receiver_info(int r, int& kind, int& l, int& h, int& c) const {
     if (r == Nr - 1) { kind = 2; l = L; h = c = -1; return; }
-    l = r / (3 * H + mu);
-    int q = r % (3 * H + mu);
-    if (q < 3 * H) { kind = 0; h = q / 3; c = q % 3; } else { kind = 1; h = c = -1; }
+    l = r / (C * H + mu);
+    int q = r % (C * H + mu);
+    if (q < C * H) { kind = 0; h = q / C; c = C == 3 ? q % 3 : -1; } else { kind = 1; h = c = -1; }
   }
   // position on the residual stream: 2l before attention of layer l, 2l+1 before its MLP, 2L at the end
   int pos_of_receiver(int r) const {

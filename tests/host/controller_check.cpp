@@ -92,13 +92,15 @@ static void check_scan(uint64_t seed, int n_up, int max_batch, double tau, int f
   if (n_up > 0) CHECK(calls <= n_up, "%d device batches for %d edges", calls, n_up);
 }
 
-static void check_graph_and_plan(uint64_t seed, int L, int H, bool mlp) {
-  GraphDims g(L, H, mlp);
+static void check_graph_and_plan(uint64_t seed, int L, int H, bool mlp, bool split) {
+  GraphDims g(L, H, mlp, split);
+  CHECK(g.Nr == L * ((split ? 3 : 1) * H + (mlp ? 1 : 0)) + 1, "receiver count");
   // ids: receivers enumerate (layer, head, channel) / MLP inputs / the output once each, in stream order
   std::set<int> seen; int prev_pos = -1;
   for (int r = 0; r < g.Nr; r++) {
     int k, l, h, c; g.receiver_info(r, k, l, h, c);
-    int id = k == 0 ? g.headin(l, h, c) : (k == 1 ? g.mlpin(l) : g.out());
+    int id = k == 0 ? g.headin(l, h, split ? c : 2) : (k == 1 ? g.mlpin(l) : g.out());
+    CHECK(k != 0 || (split ? (c >= 0 && c < 3) : c == -1), "channel of receiver %d", r);
     CHECK(id == r, "receiver %d does not map back to itself", r);
     CHECK(g.pos_of_receiver(r) >= prev_pos, "receiver ids do not follow the stream"); prev_pos = g.pos_of_receiver(r);
     int n = 0; for (int s = 0; s < g.Ns; s++) n += g.pos_after_sender(s) <= g.pos_of_receiver(r);
@@ -208,7 +210,7 @@ int main() {
     for (uint64_t seed = 1; seed <= 6; seed++) { check_scan(seed * 1000 + n_up, n_up, mb, tau, -1); cases++; }
   for (int fail_at = 0; fail_at < 6; fail_at++) for (uint64_t seed = 1; seed <= 4; seed++) { check_scan(seed, 100, 8, 2e-5, fail_at); cases++; }
   const int shapes[][3] = {{1, 1, 0}, {1, 1, 1}, {2, 2, 0}, {2, 3, 1}, {3, 4, 1}, {4, 2, 1}, {12, 12, 1}};
-  for (auto& sh : shapes) for (uint64_t seed = 1; seed <= 3; seed++) { check_graph_and_plan(seed * 77 + sh[0], sh[0], sh[1], sh[2]); cases++; }
+  for (auto& sh : shapes) for (int split = 0; split < 2; split++) for (uint64_t seed = 1; seed <= 3; seed++) { check_graph_and_plan(seed * 77 + sh[0], sh[0], sh[1], sh[2], split); cases++; }
   CHECK(plans_with_dead > 50, "the removed sets of this check hardly ever leave a node dead (%ld plans)", plans_with_dead);
   printf("%d cases (%ld plans with dead nodes, %ld dead nodes), %d failures\n", cases, plans_with_dead, dead_total, failures);
   return failures ? 1 : 0;

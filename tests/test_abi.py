@@ -59,7 +59,10 @@ def test_argument_validation_without_a_device():
     bad = p.Config.from_shape(s); bad.n_layers = 0
     with pytest.raises(p.PahqError):
         p.edge_count(bad)
-    unsup = p.Config.from_shape(s); unsup.split_qkv = 0          # the unsplit graph is not built
+    coarse = p.Config.from_shape(s, split_qkv=False)             # one input per head: a third of the head receivers
+    assert p.n_receivers(coarse) == s.n_layers * (s.n_heads + (1 if s.d_mlp else 0)) + 1 and p.workspace_bytes(coarse, 8, 16) > 0
+    assert p.edge_count(p.Config.from_shape(synth.make_shape("cfg3"), split_qkv=False)) == 11611
+    unsup = p.Config.from_shape(s); unsup.n_heads = 65           # sets of heads are 64-bit masks
     with pytest.raises(p.PahqError) as e:
         p.workspace_bytes(unsup, 8, 16)
     assert e.value.code == -6

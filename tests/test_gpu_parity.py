@@ -28,18 +28,19 @@ def kl_close(got, want):
 class Pair:
     """An oracle model and a device model built from the same seeded workload."""
 
-    def __init__(self, shape, w, clean, corrupt, precision=2, max_batch=16, mma=1, low_bits=8, nonattn_bf16=False):
+    def __init__(self, shape, w, clean, corrupt, precision=2, max_batch=16, mma=1, low_bits=8, nonattn_bf16=False,
+                 split_qkv=True):
         """mma=1: e4m3 products summed in fp32 (exact products), the arithmetic the oracle
         defines; mma=0: the FP8 matrix-core instruction with its own, narrower adder.
         low_bits: the grid of the quantised operands on both sides (8: e4m3, 4: Eq. RTN-Q with N = 4)."""
         p = P()
         self.shape, self.w, self.clean, self.corrupt = shape, w, clean, corrupt
-        self.om = SpreadModel(shape, w, low_bits=low_bits, nonattn_bf16=nonattn_bf16)      # the oracle model; its perturbed re-evaluations are off unless asked for
+        self.om = SpreadModel(shape, w, low_bits=low_bits, nonattn_bf16=nonattn_bf16, split_qkv=split_qkv)      # the oracle model; its perturbed re-evaluations are off unless asked for
         self.mode = MODE_PAHQ if precision == 2 else MODE_ALL_FP8
         self.oa = Acdc(self.om, clean, corrupt, self.mode)
         B, S = clean.shape
         self.gm = p.Model(shape, w, B, S, precision=precision, max_batch_edges=max_batch, mma=mma, low_bits=low_bits,
-                          nonattn_bf16=nonattn_bf16)
+                          nonattn_bf16=nonattn_bf16, split_qkv=split_qkv)
         self.gm.clean_cache(clean, corrupt)
         self.g = self.om.g
 
