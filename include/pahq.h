@@ -6,7 +6,8 @@
  *   - A transformer is a graph whose nodes are attention heads and MLP layers
  *     (plus the embedding and the unembedding); a node's input is the sum of
  *     the outputs of its predecessors (Appendix "Preliminaries", Circuit
- *     Discovery).  Head inputs are split into query, key and value inputs.
+ *     Discovery).  Head inputs are split into query, key and value inputs
+ *     (split_qkv = 1, the default) or are one input per head (split_qkv = 0).
  *   - Removing an edge replaces the sender's activation at that receiver by the
  *     activation of a run on the corrupted prompt (activation patching, same
  *     appendix); ACDC removes an edge when the loss change stays below a
@@ -30,6 +31,7 @@
  *   senders    0 = EMBED; HEAD(l,h) = 1 + l*(H+mu) + h; MLP(l) = 1 + l*(H+mu) + H
  *   receivers  HEADIN(l,h,c) = l*(3H+mu) + 3h + c (c: 0 query, 1 key, 2 value);
  *              MLPIN(l) = l*(3H+mu) + 3H; OUT = L*(3H+mu)
+ *              (split_qkv = 0: HEADIN(l,h) = l*(H+mu) + h; MLPIN(l) = l*(H+mu) + H; OUT = L*(H+mu))
  *   An edge (s -> r) exists iff s is strictly upstream of r; for every receiver
  *   these are the senders 0 .. pahq_n_upstream(r)-1.  Canonical edge order:
  *   receivers ascending, then senders ascending.
