@@ -160,7 +160,9 @@ int pahq_node_of_receiver(const pahq_config*, int32_t receiver, int32_t* sender_
 /* Bytes of device workspace pahq_init_model needs for batches of B sequences
  * of S tokens (paper, Appendix "Integration with ACDC": all low-precision
  * weights resident on the device; here the fp32 masters and every activation
- * cache are resident too). */
+ * cache are resident too).  S <= 64 (S <= 32 for d_head = 128), d_head one of
+ * 16, 32, 64, 128, d_model a multiple of 64 up to 4096, at most 64 heads, d_mlp a
+ * multiple of 4: PAHQ_EUNSUPPORTED otherwise. */
 int pahq_workspace_bytes(const pahq_config*, int32_t B, int32_t S, size_t* out);
 
 /* Copies the fp32 masters into `workspace` (DEVICE memory, 256-byte aligned,

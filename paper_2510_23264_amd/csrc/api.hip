@@ -36,7 +36,7 @@ int check_supported(const pahq_config* c, int B, int S) {
   if (c->d_head != 16 && c->d_head != 32 && c->d_head != 64 && c->d_head != 128) return PAHQ_EUNSUPPORTED;
   if (c->pos == PAHQ_POS_ROPE && (c->d_head & 1)) return PAHQ_EUNSUPPORTED;
   if (c->d_mlp > 0 && c->act == PAHQ_ACT_NONE) return PAHQ_EUNSUPPORTED;
-  if (B < 1 || S < 1 || S > 32) return PAHQ_EUNSUPPORTED;
+  if (B < 1 || S < 1 || S > 64 || (S > 32 && c->d_head == 128)) return PAHQ_EUNSUPPORTED;      // the attention kernel's tiles of positions
   if (c->pos == PAHQ_POS_LEARNED && S > c->n_ctx) return PAHQ_EINVAL;
   return PAHQ_OK;
 }
@@ -103,7 +103,7 @@ size_t layout(pahq_model* M, char* base) {
   M->lnf_g = b.take<float>(d); M->lnf_b = b.take<float>(d);
   M->W_U = b.take<float>(d * V); M->b_U = b.take<float>(V + 4);     // the GEMM epilogue reads bias in groups of four
   M->zeros_d = b.take<float>(d);
-  M->rope_tab = M->cfg.pos == PAHQ_POS_ROPE ? b.take<float>((size_t)32 * dh) : nullptr;    // the attention kernel's two 16-position tiles
+  M->rope_tab = M->cfg.pos == PAHQ_POS_ROPE ? b.take<float>((size_t)64 * dh) : nullptr;    // the attention kernel's (up to four) 16-position tiles
   M->bqkv = b.take<float>(L * 3 * H * dh);
   M->qkv_codes = b.take<uint8_t>(L * 3 * H * dh * Kd); M->qkv_scale = b.take<float>(L * 3 * H);
   M->o_codes = b.take<uint8_t>(L * H * d * Kh); M->o_scale = b.take<float>(L * H);
@@ -404,7 +404,7 @@ int pahq_init_model(const pahq_config* c, const pahq_weights* w, int32_t B, int3
     for (int cc = 0; cc < 3; cc++)
       if (hipMemcpyAsync(M->bqkv + (l * 3 + cc) * H * dh, bsrc[cc] + l * H * dh, H * dh * sizeof(float),
                          hipMemcpyDeviceToDevice, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
-  if (M->rope_tab && launch_rope_table(M->rope_tab, 32, (int)dh, c->rope_theta, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
+  if (M->rope_tab && launch_rope_table(M->rope_tab, 64, (int)dh, c->rope_theta, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
   // e4m3 codes + scales of every weight slice
   const float* wc[3] = {M->W_Q, M->W_K, M->W_V};
   const int qo = M->nb16 ? 16 : M->qbits;      // the grid of the components that are not attention heads

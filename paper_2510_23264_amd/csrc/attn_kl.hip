@@ -7,7 +7,7 @@
 namespace pahq {
 
 // Causal attention on the fp32 matrix cores, one wavefront per (instance,
-// sequence, head), no LDS.  S <= 32 is covered by ST = 1 or 2 tiles of 16
+// sequence, head), no LDS.  S <= 64 is covered by ST = 1 .. 4 tiles of 16
 // positions; lane = 16*g + i.
 //   scores  S^T = K Q^T with V_MFMA_F32_16X16X4_F32: lane (i, g) feeds row i of a
 //           K tile and of a Q tile (its own d_head/4 consecutive columns, the
@@ -263,7 +263,7 @@ hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is
                             long long zs_is, float* zf32, long long zf_is, unsigned long long f32_mask, unsigned long long dead_mask, int n_inst, int B, int S,
                             int H, int dh, int ldz, int rope, const float* rope_tab, hipStream_t s) {
   if (n_inst == 0) return hipSuccess;
-  if (S > 32) return hipErrorInvalidValue;
+  if (S > 64 || (S > 32 && dh == 128)) return hipErrorInvalidValue;
   int n_pairs = n_inst * B * src.n_heads;
   dim3 grid((n_pairs + 3) / 4);
 #define ATT1(ST_, DH_, R_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_, R_, (ST_ == 1 && DH_ == 64 && !R_)>), grid, dim3(256), 0, s, src, zcodes, \
@@ -272,9 +272,15 @@ hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is
   if (S <= 16) {
     if (dh == 16) ATT(1, 16); else if (dh == 32) ATT(1, 32); else if (dh == 64) ATT(1, 64);
     else if (dh == 128) ATT(1, 128); else return hipErrorInvalidValue;
-  } else {
+  } else if (S <= 32) {
     if (dh == 16) ATT(2, 16); else if (dh == 32) ATT(2, 32); else if (dh == 64) ATT(2, 64);
     else if (dh == 128) ATT(2, 128); else return hipErrorInvalidValue;
+  } else if (S <= 48) {
+    // three and four tiles of positions: the same kernel with more of a sequence's scores and values in registers
+    // (d_head up to 64: with 128 they no longer fit)
+    if (dh == 16) ATT(3, 16); else if (dh == 32) ATT(3, 32); else if (dh == 64) ATT(3, 64); else return hipErrorInvalidValue;
+  } else {
+    if (dh == 16) ATT(4, 16); else if (dh == 32) ATT(4, 32); else if (dh == 64) ATT(4, 64); else return hipErrorInvalidValue;
   }
 #undef ATT
 #undef ATT1
