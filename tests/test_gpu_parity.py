@@ -9,7 +9,7 @@ import synth
 from synth import ModelShape
 from oracle import e4m3
 from oracle.model import Model as OModel, NONE, log_softmax, kl_to_reference
-from oracle.acdc import Acdc, MODE_ALL_FP8, MODE_PAHQ
+from oracle.acdc import Acdc, MODE_ALL_FP32, MODE_ALL_FP8, MODE_PAHQ
 from fp32_spread import SpreadModel, kl_with_spread
 from tolerance import KL_ATOL, KL_RTOL, bound, tight, check_median
 
@@ -36,7 +36,7 @@ class Pair:
         p = P()
         self.shape, self.w, self.clean, self.corrupt = shape, w, clean, corrupt
         self.om = SpreadModel(shape, w, low_bits=low_bits, nonattn_bf16=nonattn_bf16, split_qkv=split_qkv)      # the oracle model; its perturbed re-evaluations are off unless asked for
-        self.mode = MODE_PAHQ if precision == 2 else MODE_ALL_FP8
+        self.mode = {2: MODE_PAHQ, 1: MODE_ALL_FP8, 0: MODE_ALL_FP32}[precision]
         self.oa = Acdc(self.om, clean, corrupt, self.mode)
         B, S = clean.shape
         self.gm = p.Model(shape, w, B, S, precision=precision, max_batch_edges=max_batch, mma=mma, low_bits=low_bits,

@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("name", ["cfg1_hi", "mid_hi", "midllama_hi"])
-@pytest.mark.parametrize("precision", [2, 1])
+@pytest.mark.parametrize("precision", [2, 1, 0])
 def test_coarser_graph(name, precision):
     import paper_2510_23264_amd as P
     shape, w, clean, corrupt = workloads.make(name)
@@ -72,3 +72,31 @@ def test_coarser_graph(name, precision):
             assert (gm.eval_edges(r, np.arange(g.n_upstream(r), dtype=np.int32)) == 0.0).all() and gm.eval_current(r) == 0.0
     finally:
         gm.close()
+
+
+def test_options_compose():
+    """The coarser graph, the 4-bit grid for the heads and bfloat16 for everything else, in one model, on a pruned
+    state with dead nodes: against the oracle with the same three options."""
+    shape, w, clean, corrupt = workloads.make("mid_hi")
+    pr = Pair(shape, w, clean, corrupt, split_qkv=False, low_bits=4, nonattn_bf16=True, max_batch=8)
+    try:
+        g, gm = pr.g, pr.gm
+        L, H = shape.n_layers, shape.n_heads
+        cases, got = [], []
+        for i, r in enumerate((g.OUT, g.headin(L - 1, 1), g.mlpin(0), g.headin(0, 0))):
+            R = random_removed(g, 0.5, 61 + i, from_receiver=r)
+            for s in (g.head(L - 1, 0), g.mlp(L - 1)):                   # two dead nodes
+                for t in g.receivers_downstream_of(s):
+                    if t >= r:
+                        R[t, s] = True
+            senders = np.arange(g.n_upstream(r), dtype=np.int32)
+            gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
+            got.append(np.concatenate([[gm.eval_current(r)], gm.eval_edges(r, senders)]))
+            cases.append((r, R, senders))
+        res = kl_with_spread(pr.om, clean, corrupt, pr.mode, cases, seeds=3)
+        want = np.concatenate([[r["kl_current"]] + list(r["kl_new"]) for r in res])
+        sigma = np.concatenate([[r["sigma_current"]] + list(r["sigma_new"]) for r in res])
+        check_kl_cases(np.concatenate(got), want, sigma, what="options together")
+        assert np.median(want) > 1e-3
+    finally:
+        pr.close()
