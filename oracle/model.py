@@ -80,13 +80,14 @@ class Model:
     def __init__(self, shape, weights, cache_decoded_bytes=6 << 30, low_bits=8, nonattn_bf16=False, split_qkv=True):
         """shape: any object with the ModelShape attributes; weights: dict of float32 arrays.
         low_bits: the grid of the quantised operands -- 8: e4m3 (the paper's setting); 4: Eq. RTN-Q with
-        N = 4 (the 4-bit point of the bit-width ablation, rtn.py).
+        N = 4 (the 4-bit point of the bit-width ablation, rtn.py); 16: bfloat16 rounding (its 16-bit point,
+        bf16.py: the 16-bit format the paper itself uses).
         nonattn_bf16: the MLP matrices and the unembedding multiply bfloat16-rounded operands instead (paper, Sec.
         "Selective Precision Allocation Strategy": bfloat16 for the components that are not attention heads).
         split_qkv: False = the coarser graph in which a head's query, key and value projections read one input."""
-        if low_bits not in (4, 8):
+        if low_bits not in (4, 8, 16):
             raise ValueError("low_bits")
-        self.q = e4m3 if low_bits == 8 else Rtn(low_bits)
+        self.q = e4m3 if low_bits == 8 else (bf16 if low_bits == 16 else Rtn(low_bits))
         # the quantiser of the matrix products that are not attention heads: the MLP matrices and the unembedding
         self.q_other = bf16 if nonattn_bf16 else self.q
         self.s = shape

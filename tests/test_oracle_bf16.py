@@ -101,3 +101,24 @@ def test_forward_with_bfloat16_non_attention_components(shape):
     _, a = mb.forward(clean, heads)
     _, b = m8.forward(clean, heads)
     assert np.abs(a - full).max() < 0.5 * np.abs(b - full).max()
+
+
+@pytest.mark.parametrize("shape", [TINY_GELU, TINY_LLAMA])
+def test_forward_at_sixteen_bits(shape):
+    """low_bits = 16 (the 16-bit point of the paper's bit-width table): every quantised operand, the heads' included,
+    is rounded to bfloat16 -- equal to the loop forward handed that one quantiser for everything, and closer to the
+    unquantised run than the 8-bit forward (8 significand bits against 4)."""
+    m8, w, clean, _ = tiny(shape, B=2)
+    m16 = Model(shape, w, low_bits=16)
+    snd, _ = _names(m16.g)
+    for pi in (frozenset(), frozenset([(0, 1)])):
+        outs, lg = m16.forward(clean, pi)
+        l_out, l_lg = loop_forward(shape, w, clean, pi=pi, codec=bf16, codec_other=bf16)
+        assert _rel(lg, l_lg) < 1e-12, sorted(pi)
+        for s, nm in snd.items():
+            assert _rel(outs[s].reshape(l_out[nm].shape), l_out[nm]) < 1e-12, (sorted(pi), nm)
+    _, full = m16.forward(clean, ALL)
+    _, lg16 = m16.forward(clean, frozenset())
+    _, lg8 = m8.forward(clean, frozenset())
+    assert np.abs(lg16 - full).max() < 0.25 * np.abs(lg8 - full).max()
+    assert np.array_equal(m16.forward(clean, frozenset())[1], Model(shape, w, low_bits=16, nonattn_bf16=True).forward(clean, frozenset())[1])

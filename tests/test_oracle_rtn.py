@@ -97,4 +97,4 @@ def test_forward_on_the_four_bit_grid(shape):
     _, lg8 = m8.forward(clean, frozenset())
     assert np.abs(lg4 - full8).max() > 3 * np.abs(lg8 - full8).max()
     with pytest.raises(ValueError):
-        Model(shape, w, low_bits=16)
+        Model(shape, w, low_bits=12)
