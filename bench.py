@@ -237,7 +237,7 @@ def main():
                     help="all_fp32: the unaccelerated ACDC of the paper's runtime table (no quantiser anywhere)")
     ap.add_argument("--nonattn-bf16", action="store_true",
                     help="bfloat16 operands for the MLP matrices and the unembedding (the heads stay on the e4m3 grid)")
-    ap.add_argument("--low-bits", type=int, default=8, choices=(4, 8), help="grid of the low-precision operands")
+    ap.add_argument("--low-bits", type=int, default=8, choices=(4, 8, 16), help="grid of the low-precision operands")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--only", default=None, choices=(None, "all_edges", "gather_regime", "sweep", "policies"),

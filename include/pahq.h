@@ -113,8 +113,13 @@ typedef struct {
                                (ties to even), |multiple| <= 8.  The multiples are stored as the E4M3
                                codes of those integers (exact), so pahq_get_weight_q and the quantiser
                                hooks return, at 4 bits, E4M3 codes of integers and the step as scale;
-                               the matrix products are the same exact kernels.  The 16-bit point of
-                               that table is not built.                                             */
+                               the matrix products are the same exact kernels.
+                               16: the 16-bit point of that table: every quantised operand, the
+                               heads' included, is rounded to bfloat16 (nearest-even, no scale;
+                               this implies nonattn_bf16).  d_head 32 or 64; needs
+                               PAHQ_MMA_F16_EXACT.  Weights and rows are then two-byte patterns:
+                               pahq_get_weight_bf16 / pahq_round_rows_bf16 instead of the E4M3
+                               hooks.                                                             */
   int32_t nonattn_bf16;     /* 1: the components that are not attention heads -- the MLP matrices and the
                                unembedding -- multiply bfloat16 operands (activations and weights rounded
                                to bfloat16, nearest-even, no scale) instead of low_bits ones; the heads
@@ -294,11 +299,13 @@ int pahq_get_weight_q(pahq_model*, int32_t which, int32_t layer, int32_t head, u
  * cols <= 16384. */
 int pahq_quantize_rows(pahq_model*, const float* x, int32_t rows, int32_t cols, uint8_t* codes, float* scales);
 /* Test hooks of the bfloat16 mode (nonattn_bf16 = 1; PAHQ_ESTATE otherwise for the first).
- * pahq_get_weight_bf16: the bfloat16 patterns of W_in / W_gate / W_out (which = PAHQ_W_*, layer) or of W_U, as the
- * model holds them, in the master's layout [K][N]; out: host.  pahq_get_weight_q refuses those four in this mode.
- * pahq_round_rows_bf16: host rows through the row kernel of site PAHQ_QSITE_HIDDEN or PAHQ_QSITE_NORM (their
- * column constraints as in pahq_quantize_rows_site) in its bfloat16 form; out: host [rows][cols] patterns. */
-int pahq_get_weight_bf16(pahq_model*, int32_t which, int32_t layer, uint16_t* out);
+ * pahq_get_weight_bf16: the bfloat16 patterns of W_in / W_gate / W_out (which = PAHQ_W_*, layer; head ignored) or of
+ * W_U, and with low_bits = 16 also of a head's W_Q / W_K / W_V / W_O (layer, head), as the model holds them, in the
+ * master's layout [K][N]; out: host.  pahq_get_weight_q refuses whatever is held as patterns.
+ * pahq_round_rows_bf16: host rows through the row kernel of site PAHQ_QSITE_HIDDEN, PAHQ_QSITE_NORM or
+ * PAHQ_QSITE_ATTN (their column constraints as in pahq_quantize_rows_site) in its bfloat16 form; out: host
+ * [rows][cols] patterns. */
+int pahq_get_weight_bf16(pahq_model*, int32_t which, int32_t layer, int32_t head, uint16_t* out);
 int pahq_round_rows_bf16(pahq_model*, int32_t site, const float* x, int32_t rows, int32_t cols, uint16_t* out);
 
 /* The same function as the path's three quantisers implement it, each through the code of its own kernel:

@@ -80,7 +80,7 @@ def lib():
             "pahq_clean_cache": [C.c_void_p, i32p, i32p],
             "pahq_eval_edges": [C.c_void_p, C.c_int32, i32p, C.c_int32, f32p],
             "pahq_eval_edge_list": [C.c_void_p, C.c_int64, i32p, i32p, f32p],
-            "pahq_get_weight_bf16": [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_uint16)],
+            "pahq_get_weight_bf16": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_uint16)],
             "pahq_round_rows_bf16": [C.c_void_p, C.c_int32, f32p, C.c_int32, C.c_int32, C.POINTER(C.c_uint16)],
             "pahq_eval_current": [C.c_void_p, C.c_int32, f32p],
             "pahq_acdc_sweep": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
@@ -355,10 +355,11 @@ class Model:
                                                _ptr(scales, C.c_float)), "pahq_quantize_rows_site")
         return codes, scales
 
-    def get_weight_bf16(self, which, layer, shape):
-        """bfloat16 patterns uint16 [K][N] of an MLP matrix or the unembedding (nonattn_bf16 models)."""
+    def get_weight_bf16(self, which, layer, shape, head=0):
+        """bfloat16 patterns uint16 [K][N] of an MLP matrix or the unembedding (nonattn_bf16 models), or of a head's
+        projection (low_bits = 16)."""
         out = np.empty(shape, dtype=np.uint16)
-        _chk(lib().pahq_get_weight_bf16(self.h, int(which), int(layer), _ptr(out, C.c_uint16)), "pahq_get_weight_bf16")
+        _chk(lib().pahq_get_weight_bf16(self.h, int(which), int(layer), int(head), _ptr(out, C.c_uint16)), "pahq_get_weight_bf16")
         return out
 
     def round_rows_bf16(self, x, site):

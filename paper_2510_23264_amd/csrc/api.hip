@@ -23,14 +23,16 @@ int check_config(const pahq_config* c) {
   if (!(c->norm_eps >= 0.f)) return PAHQ_EINVAL;
   if (c->mma != PAHQ_MMA_FP8 && c->mma != PAHQ_MMA_F16_EXACT) return PAHQ_EINVAL;
   if (c->split_qkv != 0 && c->split_qkv != 1) return PAHQ_EINVAL;
-  if (c->low_bits != 0 && c->low_bits != 4 && c->low_bits != 8) return PAHQ_EINVAL;
+  if (c->low_bits != 0 && c->low_bits != 4 && c->low_bits != 8 && c->low_bits != 16) return PAHQ_EINVAL;
   if (c->nonattn_bf16 != 0 && c->nonattn_bf16 != 1) return PAHQ_EINVAL;
   return PAHQ_OK;
 }
 // what this build of the kernels supports
 int check_supported(const pahq_config* c, int B, int S) {
   if (c->n_heads > 64) return PAHQ_EUNSUPPORTED;                      // sets of heads are 64-bit masks
-  if (c->nonattn_bf16 && c->mma != PAHQ_MMA_F16_EXACT && c->precision != PAHQ_ALL_FP32) return PAHQ_EUNSUPPORTED;   // bfloat16 products have no FP8-instruction form
+  if ((c->nonattn_bf16 || c->low_bits == 16) && c->mma != PAHQ_MMA_F16_EXACT && c->precision != PAHQ_ALL_FP32) return PAHQ_EUNSUPPORTED;   // bfloat16 products have no FP8-instruction form
+  if (c->low_bits == 16 && c->precision != PAHQ_ALL_FP32 && ((c->d_head != 32 && c->d_head != 64) || c->n_heads % (64 / c->d_head) != 0))
+    return PAHQ_EUNSUPPORTED;                                         // the bfloat16 form of the fused output projection
   if (c->d_model % 64 != 0 || c->d_model > 4096) return PAHQ_EUNSUPPORTED;
   if (c->d_mlp % 4 != 0) return PAHQ_EUNSUPPORTED;                    // 16-byte rows of the hidden activations
   if (c->d_head != 16 && c->d_head != 32 && c->d_head != 64 && c->d_head != 128) return PAHQ_EUNSUPPORTED;
@@ -63,8 +65,11 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
   M->nmax = c->max_batch_edges; M->G = 3 * M->H + 1;
   M->all_f32 = c->precision == PAHQ_ALL_FP32;
   M->skip_dead = true;
-  M->qbits = c->low_bits == 4 ? 4 : 8;
-  M->nb16 = c->nonattn_bf16 != 0 && !M->all_f32;
+  M->qbits = c->low_bits == 4 ? 4 : (c->low_bits == 16 ? 16 : 8);
+  M->nb16 = (c->nonattn_bf16 != 0 || M->qbits == 16) && !M->all_f32;
+  if (M->qbits == 16) {        // bfloat16 operands for the heads too: their rows take two bytes per element
+    M->Kd = pad128(2 * M->d); M->Kh = pad128(2 * M->dh);
+  }
   M->Kd_o = M->nb16 ? pad128(2 * M->d) : M->Kd;
   M->Km_o = M->nb16 ? pad128(2 * (M->m > 0 ? M->m : 1)) : M->Km;
   M->deadsum_tag.assign(M->L, -1);
@@ -840,7 +845,7 @@ int pahq_get_weight_q(pahq_model* M, int32_t which, int32_t layer, int32_t head,
   const int L = M->L, H = M->H, dh = M->dh, d = M->d, m = M->m, V = M->V;
   if (which >= PAHQ_W_Q && which <= PAHQ_W_O) { if (layer < 0 || layer >= L || head < 0 || head >= H) return PAHQ_EINVAL; }
   else if (which >= PAHQ_W_IN && which <= PAHQ_W_OUT) { if (layer < 0 || layer >= L || m == 0) return PAHQ_EINVAL; }
-  if (M->nb16 && which >= PAHQ_W_IN) return PAHQ_EUNSUPPORTED;      // those are bfloat16 patterns: pahq_get_weight_bf16
+  if ((M->nb16 && which >= PAHQ_W_IN) || M->qbits == 16) return PAHQ_EUNSUPPORTED;      // those are bfloat16 patterns: pahq_get_weight_bf16
   switch (which) {
     case PAHQ_W_Q: case PAHQ_W_K: case PAHQ_W_V: {
       int cc = which - PAHQ_W_Q;
@@ -864,13 +869,22 @@ int pahq_get_weight_q(pahq_model* M, int32_t which, int32_t layer, int32_t head,
   return PAHQ_OK;
 }
 
-int pahq_get_weight_bf16(pahq_model* M, int32_t which, int32_t layer, uint16_t* out) {
+int pahq_get_weight_bf16(pahq_model* M, int32_t which, int32_t layer, int32_t head, uint16_t* out) {
   if (!M || !out) return PAHQ_EINVAL;
   if (!M->nb16) return PAHQ_ESTATE;
-  const int L = M->L, d = M->d, m = M->m, V = M->V;
+  const int L = M->L, H = M->H, dh = M->dh, d = M->d, m = M->m, V = M->V;
   const uint8_t* src; int K, N, ldq;
   if (which >= PAHQ_W_IN && which <= PAHQ_W_OUT) { if (layer < 0 || layer >= L || m == 0) return PAHQ_EINVAL; }
+  if (which >= PAHQ_W_Q && which <= PAHQ_W_O) {
+    if (M->qbits != 16) return PAHQ_ESTATE;              // the heads' weights are patterns only at 16 bits
+    if (layer < 0 || layer >= L || head < 0 || head >= H) return PAHQ_EINVAL;
+  }
   switch (which) {
+    case PAHQ_W_Q: case PAHQ_W_K: case PAHQ_W_V: {
+      const int cc = which - PAHQ_W_Q;
+      K = d; N = dh; ldq = M->Kd;
+      src = M->qkv_codes + ((long long)layer * 3 * H * dh + ((long long)cc * H + head) * dh) * M->Kd; break; }
+    case PAHQ_W_O: K = dh; N = d; ldq = M->Kh; src = M->o_codes + ((long long)layer * H + head) * d * M->Kh; break;
     case PAHQ_W_IN: K = d; N = m; ldq = M->Kd_o; src = M->in_codes + (long long)layer * m * ldq; break;
     case PAHQ_W_GATE: if (!M->gate_codes) return PAHQ_EINVAL;
       K = d; N = m; ldq = M->Kd_o; src = M->gate_codes + (long long)layer * m * ldq; break;
@@ -888,7 +902,8 @@ int pahq_get_weight_bf16(pahq_model* M, int32_t which, int32_t layer, uint16_t* 
 
 int pahq_round_rows_bf16(pahq_model* M, int32_t site, const float* x, int32_t rows, int32_t cols, uint16_t* out) {
   if (!M || rows < 0 || cols < 1 || (rows > 0 && (!x || !out))) return PAHQ_EINVAL;
-  if (site != PAHQ_QSITE_HIDDEN && site != PAHQ_QSITE_NORM) return PAHQ_EINVAL;
+  if (site < PAHQ_QSITE_HIDDEN || site > PAHQ_QSITE_ATTN) return PAHQ_EINVAL;
+  if (site == PAHQ_QSITE_ATTN && cols != 16 && cols != 32 && cols != 64 && cols != 128) return PAHQ_EINVAL;
   if (site == PAHQ_QSITE_NORM && (cols % 64 != 0 || cols > 4096)) return PAHQ_EINVAL;
   if (site == PAHQ_QSITE_HIDDEN && cols % 4 != 0) return PAHQ_EINVAL;
   if (rows == 0) return PAHQ_OK;
@@ -901,7 +916,14 @@ int pahq_round_rows_bf16(pahq_model* M, int32_t site, const float* x, int32_t ro
     HIPCHK(hipMemcpyAsync(M->logits, x + r0 * cols, nr * cols * sizeof(float), hipMemcpyHostToDevice, M->stream));
     if (site == PAHQ_QSITE_HIDDEN)
       HIPCHK(launch_hidden_quant(M->logits, nullptr, 0LL, M->xcodes, 0LL, M->xscale, 0LL, 1, (int)nr, cols, 2 * cols, 0, 16, M->stream));
-    else HIPCHK(launch_emit_rows(M->logits, (int)nr, cols, M->xcodes, M->xscale, 16, M->stream));
+    else if (site == PAHQ_QSITE_NORM) HIPCHK(launch_emit_rows(M->logits, (int)nr, cols, M->xcodes, M->xscale, 16, M->stream));
+    else {
+      // one position, one head whose value row is the given row: the attention output is that row (see pahq_quantize_rows_site)
+      AttnSrc src; memset(&src, 0, sizeof(src));
+      src.q = src.k = src.v = M->logits; src.q_ld = src.k_ld = src.v_ld = cols;
+      src.n_heads = 1; src.h0 = 0; src.head_cols = 0; src.qbits = 16;
+      HIPCHK(launch_attention(src, M->xcodes, 0, M->xscale, 0, nullptr, 0, 0ull, 0ull, 1, (int)nr, 1, 1, cols, 2 * cols, 0, nullptr, M->stream));
+    }
     HIPCHK(hipMemcpyAsync(out + r0 * cols, M->xcodes, nr * cols * 2, hipMemcpyDeviceToHost, M->stream));
     HIPCHK(hipStreamSynchronize(M->stream));
   }
@@ -911,6 +933,7 @@ int pahq_round_rows_bf16(pahq_model* M, int32_t site, const float* x, int32_t ro
 int pahq_quantize_rows_site(pahq_model* M, int32_t site, const float* x, int32_t rows, int32_t cols, uint8_t* codes,
                             float* scales) {
   if (!M || !x || !codes || !scales || rows < 0 || cols < 1 || cols > 16384) return PAHQ_EINVAL;
+  if (M->qbits == 16) return PAHQ_EUNSUPPORTED;          // two-byte patterns: pahq_round_rows_bf16
   if (site == PAHQ_QSITE_NORM && (cols % 64 != 0 || cols > 4096)) return PAHQ_EINVAL;
   if (site == PAHQ_QSITE_ATTN && cols != 16 && cols != 32 && cols != 64 && cols != 128) return PAHQ_EINVAL;
   if (site < PAHQ_QSITE_HIDDEN || site > PAHQ_QSITE_ATTN) return PAHQ_EINVAL;

@@ -214,9 +214,17 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
         for (int t = 0; t < NT; t++) am = fmaxf(am, fabsf(z[t][rr]));
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) am = fmaxf(am, __shfl_xor(am, o, 64));
-        float scale = (am == 0.f) ? 1.0f : am / q_top(src.qbits);
+        float scale = (am == 0.f || src.qbits == 16) ? 1.0f : am / q_top(src.qbits);
         float inv = 1.0f / scale;
-        if (STG) {
+        if (!STG && src.qbits == 16) {
+          // bfloat16 patterns, two bytes per value, no scale
+          if (pos < S) {
+            uint8_t* o = zcodes + inst * zc_is + (tok * H + h) * ldz + 2 * i;
+#pragma unroll
+            for (int t = 0; t < NT; t++) *(uint16_t*)(o + 32 * t) = (uint16_t)bf16_rne(z[t][rr]);
+            if (i == 0) zscale[inst * zs_is + tok * H + h] = 1.0f;
+          }
+        } else if (STG) {
           // codes of the 16 x 64 block are collected in this wave's LDS (the k block is no longer needed) and
           // leave as one 16-byte store per lane below, instead of one byte per lane and column tile here
           uint8_t* zb = (uint8_t*)(sq + 1024) + pos * 64 + i;
@@ -266,8 +274,11 @@ hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is
   if (S > 64 || (S > 32 && dh == 128)) return hipErrorInvalidValue;
   int n_pairs = n_inst * B * src.n_heads;
   dim3 grid((n_pairs + 3) / 4);
-#define ATT1(ST_, DH_, R_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_, R_, (ST_ == 1 && DH_ == 64 && !R_)>), grid, dim3(256), 0, s, src, zcodes, \
+  // the staged form (one tile, d_head 64, no rotation) collects one-byte codes in LDS: bfloat16 outputs take the plain form
+#define ATT0(ST_, DH_, R_, G_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_, R_, G_>), grid, dim3(256), 0, s, src, zcodes, \
                                               zc_is, zscale, zs_is, zf32, zf_is, f32_mask, dead_mask, n_pairs, B, S, H, ldz, rope, (const float2*)rope_tab)
+#define ATT1(ST_, DH_, R_) do { if ((ST_ == 1 && DH_ == 64 && !R_) && src.qbits != 16) ATT0(ST_, DH_, R_, (ST_ == 1 && DH_ == 64 && !R_)); \
+                                else ATT0(ST_, DH_, R_, false); } while (0)
 #define ATT(ST_, DH_) do { if (rope) ATT1(ST_, DH_, true); else ATT1(ST_, DH_, false); } while (0)
   if (S <= 16) {
     if (dh == 16) ATT(1, 16); else if (dh == 32) ATT(1, 32); else if (dh == 64) ATT(1, 64);
@@ -284,6 +295,7 @@ hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is
   }
 #undef ATT
 #undef ATT1
+#undef ATT0
   return hipGetLastError();
 }
 

@@ -362,7 +362,7 @@ struct Builder {
     GemmProb p8 = prob8(gd.out_codes, gd.out_codes_is, Kd, gd.out_scale, gd.out_scale_is, 1,
                         M->qkv_codes + (long long)l * 3 * H * dh * Kd, Kd, M->qkv_scale + (long long)l * 3 * H, dh,
                         M->bqkv + (long long)l * 3 * H * dh, M->qkv_sh, (long long)T * qkv_ld, (int)qkv_ld, 0, T, 3 * H * dh, Kd, d);
-    p8.M = T;
+    p8.M = T; p8.b16 = M->qbits == 16;
     probs.push_back(p8);
     add_op(OP_GEMM8, pb, 1, T, 3 * H * dh); work_gemm(pb);
     int pf = (int)probs.size();
@@ -497,6 +497,7 @@ struct Builder {
                             M->qkv_codes + ((long long)l * 3 * H * dh + (long long)nb * dh) * Kd, Kd,
                             M->qkv_scale + (long long)l * 3 * H + nb, dh, M->bqkv + (long long)l * 3 * H * dh + (long long)nb * dh,
                             qkv_buf + (long long)nb * dh, (long long)T * qkv_ld, (int)qkv_ld, 0, T, (e - nb) * dh, Kd, d));
+      probs.back().b16 = M->qbits == 16;
       if ((e - nb) * dh > maxN) maxN = (e - nb) * dh;
       nb = e;
     }
@@ -910,7 +911,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
       }
       case OP_COMBINE: HIPCHK(launch_combine(d_cdesc, o.i0, d_csrc, o.i1 ? 1 : n, M->tile, d, st)); break;
       case OP_OPROJ:
-        HIPCHK(launch_oproj_fused(d_odesc, o.i0, d_haux, o.i1, o.i2, M->H, M->dh, M->cfg.mma == PAHQ_MMA_F16_EXACT, st));
+        HIPCHK(launch_oproj_fused(d_odesc, o.i0, d_haux, o.i1, o.i2, M->H, M->dh, M->cfg.mma == PAHQ_MMA_F16_EXACT, M->qbits == 16, st));
         break;
       case OP_HIDQ:
         HIPCHK(launch_hidden_quant(M->hid, o.i0 == 2 ? M->hid2 : nullptr, (long long)T * M->m, M->hcodes, (long long)T * M->Km_o,

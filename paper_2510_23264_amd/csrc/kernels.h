@@ -148,7 +148,7 @@ hipError_t launch_tile_sub(float* out, const float* a, const float* b, long long
 hipError_t launch_gemm_fp8(const GemmProb* probs, int n_probs, int max_M, int max_N, int exact, int b16, hipStream_t s);
 hipError_t launch_gemm_f32(const GemmProb* probs, int n_probs, int max_M, int max_N, hipStream_t s);
 hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const HeadAux* auxs, int M, int N, int H, int dh,
-                              int exact, hipStream_t s);
+                              int exact, int b16, hipStream_t s);
 
 // Causal attention per (instance, sequence, head).  q, k, v: fp32 rows [inst][T][..]; head hl of the
 // launch reads columns hl * head_cols .. + dh of each and writes output head h0 + hl (of H).

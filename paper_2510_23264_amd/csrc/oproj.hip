@@ -182,7 +182,9 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
 // wavefronts of 32 x 64.  A head's partial result is complete after one (d_head 64) or two
 // (d_head 128) 64-byte halves of a slab; it is scaled by z-scale[row][head] * w-scale[head] and
 // added to the running total in registers.  The fp32 head (skip_head) takes part with scale 0.
-template <int DH>
+// DH: bytes of a head's row of codes (64 or 128).  B16: they are bfloat16 patterns (d_head = DH / 2), multiplied
+// without conversion by V_MFMA_F32_16X16X32_BF16, one step per 16-byte operand read; everything else is the same.
+template <int DH, bool B16 = false>
 __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int di, const HeadAux* auxs) {
   constexpr int BM = 128, BN = 64, TM = 2, TN = 4, NI = 6, STAGE = (BM + BN) * 128;
   constexpr int HPS = 128 / DH;            // heads per slab
@@ -293,6 +295,18 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
 #pragma unroll
           for (int j = 0; j < TN; j++) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
       }
+      if constexpr (B16) {
+        union U { uint4 u; v8bf h; };
+#pragma unroll
+        for (int j = 0; j < TN; j++) {
+          U hb; hb.u = rb[q][j];
+#pragma unroll
+          for (int i = 0; i < TM; i++) {
+            U ha; ha.u = ra[q][i];
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hb.h, ha.h, acc[i][j], 0, 0, 0);
+          }
+        }
+      } else {
       v8h ha[TM][2];
 #pragma unroll
       for (int i = 0; i < TM; i++) {
@@ -307,6 +321,7 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb0, ha[i][0], acc[i][j], 0, 0, 0);
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb1, ha[i][1], acc[i][j], 0, 0, 0);
         }
+      }
       }
       if (HPS == 2) fold(2 * s + q, zsc[q]);
       else if (q == 1) fold(s, zsc[0]);
@@ -347,13 +362,20 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
 }
 
 hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const HeadAux* auxs, int M, int N, int H, int dh,
-                              int exact, hipStream_t s) {
+                              int exact, int b16, hipStream_t s) {
   if (M == 0) return hipSuccess;
   int tiles = ((M + 127) / 128) * ((N + 63) / 64);
   dim3 grid((tiles + 7) / 8 * 8);
+  if (b16) {
+    // bfloat16 attention outputs: heads of 32 or 64 values (64 or 128 bytes)
+    if (!exact || (dh != 32 && dh != 64) || N % 4 != 0 || H % (64 / dh) != 0) return hipErrorInvalidValue;
+    if (dh == 32) hipLaunchKernelGGL((oproj_x_k<64, true>), grid, dim3(256), 0, s, descs, desc_index, auxs);
+    else hipLaunchKernelGGL((oproj_x_k<128, true>), grid, dim3(256), 0, s, descs, desc_index, auxs);
+    return hipGetLastError();
+  }
   if (exact && (dh == 64 || dh == 128) && N % 4 == 0 && H % (128 / dh) == 0) {
-    if (dh == 64) hipLaunchKernelGGL(oproj_x_k<64>, grid, dim3(256), 0, s, descs, desc_index, auxs);
-    else hipLaunchKernelGGL(oproj_x_k<128>, grid, dim3(256), 0, s, descs, desc_index, auxs);
+    if (dh == 64) hipLaunchKernelGGL((oproj_x_k<64>), grid, dim3(256), 0, s, descs, desc_index, auxs);
+    else hipLaunchKernelGGL((oproj_x_k<128>), grid, dim3(256), 0, s, descs, desc_index, auxs);
   } else if (exact) hipLaunchKernelGGL(oproj_fused_k<true>, grid, dim3(256), 0, s, descs, desc_index, auxs);
   else hipLaunchKernelGGL(oproj_fused_k<false>, grid, dim3(256), 0, s, descs, desc_index, auxs);
   return hipGetLastError();

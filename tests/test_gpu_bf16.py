@@ -136,3 +136,81 @@ def test_logit_difference_and_exact_zero(name):
         gm.close()
     with pytest.raises(P.PahqError):
         P.Model(shape, w, B, S, precision=P.PAHQ, max_batch_edges=8, nonattn_bf16=True, mma=P.MMA_FP8)
+
+
+# ------------------------------------------------------------------ the 16-bit point: the heads in bfloat16 as well
+@pytest.fixture(scope="module")
+def pairs16():
+    out = {}
+    for name in ("mid_hi", "midllama_hi"):
+        shape, w, clean, corrupt = workloads.make(name)
+        out[name] = Pair(shape, w, clean, corrupt, low_bits=16)
+    yield out
+    for pr in out.values():
+        pr.close()
+
+
+def test_sixteen_bits_weights_and_rows_bit_exact(pairs16):
+    import paper_2510_23264_amd as P
+    for name, pr in pairs16.items():
+        s, om, gm = pr.shape, pr.om, pr.gm
+        for l in range(s.n_layers):
+            for h in range(s.n_heads):
+                for which, nm in ((P.W_Q, "W_Q"), (P.W_K, "W_K"), (P.W_V, "W_V"), (P.W_O, "W_O")):
+                    got = gm.get_weight_bf16(which, l, om.qc[nm][l, h].shape, head=h)
+                    assert np.array_equal(got, om.qc[nm][l, h]), (name, nm, l, h)
+            for which, nm in ((P.W_IN, "W_in"), (P.W_OUT, "W_out")):
+                assert np.array_equal(gm.get_weight_bf16(which, l, om.qc[nm][l].shape), om.qc[nm][l]), (name, nm, l)
+        with pytest.raises(P.PahqError):
+            gm.get_weight_q(P.W_Q, 0, 0, om.qc["W_Q"][0, 0].shape)
+        with pytest.raises(P.PahqError):
+            gm.quantize_rows(np.zeros((2, 64), np.float32))
+    gm = pairs16["mid_hi"].gm
+    rng = np.random.default_rng(3)
+    for cols in (16, 32, 64, 128):                                     # the attention kernel's output rounding
+        x = (rng.standard_normal((19, cols)) * np.exp(rng.normal(size=(19, 1)) * 3)).astype(np.float32)
+        x[2] = 0
+        x[3, : min(cols, 16)] = (1.0 + (np.arange(min(cols, 16)) + 0.5) * 2.0 ** -7).astype(np.float32)
+        assert np.array_equal(gm.round_rows_bf16(x, 2), bf16.encode(x)), cols
+
+
+@pytest.mark.parametrize("name", ["mid_hi", "midllama_hi"])
+def test_sixteen_bits_edges_and_sweeps(pairs16, name):
+    pr = pairs16[name]
+    g = pr.g
+    L, H = pr.shape.n_layers, pr.shape.n_heads
+    cases, got = [], []
+    for i, r in enumerate((g.OUT, g.headin(L - 1, H - 1, 1), g.headin(0, 0, 2), g.mlpin(L - 1), g.headin(1, 0, 0))):
+        R = g.empty_removed() if i % 2 == 0 else random_removed(g, 0.4, 71 + i, from_receiver=r)
+        senders = np.arange(g.n_upstream(r), dtype=np.int32)
+        pr.gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
+        got.append(np.concatenate([[pr.gm.eval_current(r)], pr.gm.eval_edges(r, senders)]))
+        cases.append((r, R, senders))
+    pr.gm.set_removed(np.zeros(g.n_edges(), np.uint8))
+    res = kl_with_spread(pr.om, pr.clean, pr.corrupt, pr.mode, cases, seeds=4)
+    want = np.concatenate([[r["kl_current"]] + list(r["kl_new"]) for r in res])
+    sigma = np.concatenate([[r["sigma_current"]] + list(r["sigma_new"]) for r in res])
+    worst = check_kl_cases(np.concatenate(got), want, sigma, what=name + " at 16 bits")
+    print(name, "16 bits: median KL %.3g, worst |d| / bound %.3f" % (np.median(want), worst))
+    assert compare_sweep(pr, {"mid_hi": 0.01, "midllama_hi": 0.03}[name])[0] == "equal"
+
+
+def test_sixteen_bits_exact_zero_and_limits():
+    import paper_2510_23264_amd as P
+    shape, w, clean, _ = workloads.make("midllama_hi")
+    B, S = clean.shape
+    gm = P.Model(shape, w, B, S, precision=P.PAHQ, max_batch_edges=8, low_bits=16)
+    try:
+        gm.clean_cache(clean, clean.copy())
+        gm.set_dead_node_skipping(False)
+        from oracle.graph import Graph
+        g = Graph(shape.n_layers, shape.n_heads, True)
+        for r in (g.OUT, g.mlpin(1), g.headin(2, 1, 0)):
+            gm.set_removed(g.removed_to_flat(random_removed(g, 0.5, 3, from_receiver=r)).astype(np.uint8))
+            assert (gm.eval_edges(r, np.arange(g.n_upstream(r), dtype=np.int32)) == 0.0).all() and gm.eval_current(r) == 0.0
+    finally:
+        gm.close()
+    small, w1, c1, _ = workloads.make("cfg1_hi")                        # heads of 16 values: no bfloat16 output projection
+    with pytest.raises(P.PahqError) as e:
+        P.Model(small, w1, c1.shape[0], c1.shape[1], low_bits=16)
+    assert e.value.code == -6
