@@ -232,7 +232,7 @@ def main():
     ap.add_argument("--batch", type=int, default=128, help="candidates per device batch")
     ap.add_argument("--mma", type=int, default=1,
                     help="1 (default): e4m3 codes decoded in registers, fp16 matrix cores, exact fp32 sums; "
-                         "0: the FP8 matrix-core instruction (faster, but its adder truncates: KL about 1.3% low)")
+                         "0: the FP8 matrix-core instruction (faster, but its adder truncates: KL about 1.3%% low)")
     ap.add_argument("--precision", default="pahq", choices=("pahq", "all_fp8", "all_fp32"),
                     help="all_fp32: the unaccelerated ACDC of the paper's runtime table (no quantiser anywhere)")
     ap.add_argument("--nonattn-bf16", action="store_true",

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
         const int r = 4 * t + (lane >> 4);
         const float* gp = mats[mtx] + (long long)min(r, S - 1) * lds_[mtx] + (((lane & 15) ^ r) * 4);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
-                                         (__attribute__((address_space(3))) void*)(sq + mtx * 1024 + t * 256), 16, 0, 0);
+                                         (__attribute__((address_space(3))) void*)(sq + mtx * 1024 + t * 256), 16, 0, 2);
       }
     __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): this wave's blocks are in LDS
     __builtin_amdgcn_wave_barrier();
@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
       const int r = 4 * t + (lane >> 4);
       const float* gp = vb + (long long)min(r, S - 1) * src.v_ld + (((lane & 15) ^ r) * 4);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
-                                       (__attribute__((address_space(3))) void*)(sq + t * 256), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void*)(sq + t * 256), 16, 0, 2);
     }
   } else {
 #pragma unroll

@@ -550,7 +550,7 @@ __global__ __launch_bounds__(512, 1) void gemm_p_k(const GemmProb* probs) {
       for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int r = 0; r < 4; r++)
-          addv[i][r] = live[i][r] ? gload4(P.add + inst[i][r] * P.add_is + roff[i][r]) : make_float4(0.f, 0.f, 0.f, 0.f);
+          addv[i][r] = live[i][r] ? gload4_nt(P.add + inst[i][r] * P.add_is + roff[i][r]) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
     for (int i = 0; i < TM; i++) {
@@ -564,10 +564,10 @@ __global__ __launch_bounds__(512, 1) void gemm_p_k(const GemmProb* probs) {
         if (P.bias) { v.x += bias.x; v.y += bias.y; v.z += bias.z; v.w += bias.w; }
         if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
         if (P.add) { v.x += addv[i][r].x; v.y += addv[i][r].y; v.z += addv[i][r].z; v.w += addv[i][r].w; }
-        gstore4(P.C + inst[i][r] * P.c_is + roff[i][r], v);
+        gstore4_nt(P.C + inst[i][r] * P.c_is + roff[i][r], v);
         if (P.aux) {
           if (P.aux_sub) { float4 u = gload4(P.aux_sub + roff[i][r]); val.x -= u.x; val.y -= u.y; val.z -= u.z; val.w -= u.w; }
-          gstore4(P.aux + inst[i][r] * P.aux_is + roff[i][r], val);
+          gstore4_nt(P.aux + inst[i][r] * P.aux_is + roff[i][r], val);
         }
       }
     }

@@ -37,6 +37,16 @@ __device__ __forceinline__ float4 gload4(const float* p) {
 __device__ __forceinline__ void gstore4(float* p, float4 v) {
   *(__attribute__((address_space(1))) v4f*)p = (v4f){v.x, v.y, v.z, v.w};
 }
+// A load marked non-temporal, for data that is read once.
+__device__ __forceinline__ float4 gload4_nt(const float* p) {
+  v4f v = __builtin_nontemporal_load((const __attribute__((address_space(1))) v4f*)p);
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+// The same store marked non-temporal: a result tile that nothing reads again before it has left the L2 anyway
+// should not push the operands the neighbouring tiles still need out of it.
+__device__ __forceinline__ void gstore4_nt(float* p, float4 v) {
+  __builtin_nontemporal_store((v4f){v.x, v.y, v.z, v.w}, (__attribute__((address_space(1))) v4f*)p);
+}
 
 // XCD-aware tile order: workgroup id w runs on XCD w % 8; that XCD gets the
 // contiguous range [x * chunk, (x+1) * chunk) of the linear tile index.

@@ -6,6 +6,7 @@
 #include <algorithm>
 #include "kernels.h"
 #include "device_util.h"
+#include "mma_util.h"
 
 namespace pahq {
 
@@ -587,8 +588,8 @@ __global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const
 #pragma unroll
   for (int j = 0; j < NV; j++) {
     const int e = min((j * TPR + t) * 4, m - 4);
-    v[j] = *(const float4*)(pu + e);
-    if (act == 2) g[j] = *(const float4*)(pg + e);
+    v[j] = gload4_nt(pu + e);
+    if (act == 2) g[j] = gload4_nt(pg + e);
   }
   float am = 0.f;
 #pragma unroll
