@@ -92,6 +92,9 @@ def all_edges_pass(gm, P, cfg, receivers, stride=1):
         rs = sorted(chunks[layer], key=lambda r: (-((r % per_layer) // 3), (r % per_layer) % 3))     # heads descending, q k v ascending
         recv = np.concatenate([np.full(P.n_upstream(cfg, r), r, np.int32) for r in rs])
         send = np.concatenate([np.arange(P.n_upstream(cfg, r), dtype=np.int32) for r in rs])
+        if cfg.fp32_residency and i + 1 < len(chunks):
+            # the caller knows its own order: the layer underneath comes next, its heads' fp32 weights can move now
+            gm.prefetch_heads(sorted(chunks, reverse=True)[i + 1], range(cfg.n_heads))
         gm.eval_edge_list(recv, send)
         n += send.size
         if time.perf_counter() - t_last > 30.0:          # long passes (the large configs) say where they are
@@ -238,6 +241,9 @@ def main():
     ap.add_argument("--nonattn-bf16", action="store_true",
                     help="bfloat16 operands for the MLP matrices and the unembedding (the heads stay on the e4m3 grid)")
     ap.add_argument("--low-bits", type=int, default=8, choices=(4, 8, 16), help="grid of the low-precision operands")
+    ap.add_argument("--fp32-on-host", action="store_true",
+                    help="the heads' fp32 masters stay in pinned host memory and are prefetched into 2 H device slots "
+                         "(the paper's weight scheduler); reports the transfer counters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--only", default=None, choices=(None, "all_edges", "gather_regime", "sweep", "policies"),
@@ -263,13 +269,14 @@ def main():
     precision = {"pahq": P.PAHQ, "all_fp8": P.ALL_FP8, "all_fp32": P.ALL_FP32}[args.precision]
     shape, w, clean, corrupt, spec = synth.make_workload(args.config)
     gm = P.Model(shape, w, spec["B"], spec["S"], precision=precision, max_batch_edges=args.batch, mma=args.mma,
-                 low_bits=args.low_bits, nonattn_bf16=args.nonattn_bf16)
+                 low_bits=args.low_bits, nonattn_bf16=args.nonattn_bf16, fp32_on_host=args.fp32_on_host)
     cfg = gm.cfg
     # configs that name a receiver sample (4 and 5) run the in-edges of that seeded sample
     receivers = synth.make_receiver_sample(P.n_receivers(cfg), spec["n_recv"], spec["seed"])
     gm.clean_cache(clean, corrupt)
     workload_key = f"{args.config} batch={args.batch} mma={args.mma} precision={args.precision}" + \
-        (" nonattn_bf16" if args.nonattn_bf16 else "") + (f" low_bits={args.low_bits}" if args.low_bits != 8 else "")
+        (" nonattn_bf16" if args.nonattn_bf16 else "") + (f" low_bits={args.low_bits}" if args.low_bits != 8 else "") + \
+        (" fp32_on_host" if args.fp32_on_host else "")
     do = lambda what: args.only in (None, what)
 
     out = {"metric": "patched edge evals/sec (GPT-2-small shape)", "value": None, "unit": "edges/s",
@@ -380,6 +387,9 @@ def main():
 
     # what this device does on a pure matrix-core issue loop and on a streaming copy, measured now, next to the
     # published peaks the roofline divides by
+    if args.fp32_on_host:
+        out["fp32_on_host"] = dict(gm.transfer_stats(), workspace_bytes=gm.workspace_bytes,
+                                   note="counters since init, over everything this run evaluated")
     tf, gb = P.measure_ceilings()
     out["ceilings"] = {"mfma_f16_issue_loop_TFLOPs": round(tf, 1), "stream_copy_GBps": round(gb, 1),
                        "note": "micro-kernels of the library (pahq_measure_ceilings), all compute units busy"}

@@ -127,7 +127,22 @@ typedef struct {
                                non-attention components).  Products are exact on the bf16 matrix cores,
                                sums fp32.  Needs PAHQ_MMA_F16_EXACT; ignored with PAHQ_ALL_FP32.
                                0 (default): every quantised product uses low_bits.                   */
+  int32_t fp32_residency;   /* where the fp32 masters live after pahq_init_model (Sec. "Selective Precision
+                               Allocation Strategy", Hierarchical Weight Scheduling; Sec. "Algorithm
+                               Implementation in Practice", Scheduler Implementation):
+                               PAHQ_FP32_IN_HBM (0, default): all of them in the workspace.
+                               PAHQ_FP32_ON_HOST: the heads' W_Q / W_K / W_V / W_O and projection biases
+                               stay in pinned host memory that the library allocates (hipHostMalloc, one
+                               block per head); the device holds 2 * n_heads head slots, filled by a second
+                               stream of the library's own: a pass waits for the heads it computes in fp32
+                               (S_t), and the heads expected next (S_t+1: the following layer of the same
+                               pass, the next head in the sweep's order) are transferred while it runs.
+                               The fp32 masters of the MLPs and the unembedding only pass through a staging
+                               buffer on their way to the quantiser.  The workspace shrinks by those
+                               masters; every result is bit-identical to PAHQ_FP32_IN_HBM.
+                               Not with PAHQ_ALL_FP32 (which multiplies the masters themselves).       */
 } pahq_config;
+enum { PAHQ_FP32_IN_HBM = 0, PAHQ_FP32_ON_HOST = 1 };
 
 /* fp32 master weights, row-major.  All pointers host memory (on_device = 0) or
  * all device memory (on_device = 1); the library copies them into the workspace.
@@ -165,7 +180,7 @@ int pahq_node_of_receiver(const pahq_config*, int32_t receiver, int32_t* sender_
 /* Bytes of device workspace pahq_init_model needs for batches of B sequences
  * of S tokens (paper, Appendix "Integration with ACDC": all low-precision
  * weights resident on the device; here the fp32 masters and every activation
- * cache are resident too).  S <= 64 (S <= 32 for d_head = 128), d_head one of
+ * cache are resident too, unless fp32_residency says otherwise).  S <= 64 (S <= 32 for d_head = 128), d_head one of
  * 16, 32, 64, 128, d_model a multiple of 64 up to 4096, at most 64 heads, d_mlp a
  * multiple of 4: PAHQ_EUNSUPPORTED otherwise. */
 int pahq_workspace_bytes(const pahq_config*, int32_t B, int32_t S, size_t* out);
@@ -285,6 +300,18 @@ int pahq_eval_circuit(pahq_model*, const uint8_t* kept, const uint8_t* f32_heads
  * arithmetic nothing changes; in binary32 the order of a few additions does.  on = 0 computes every node (for
  * comparison and timing).  Takes effect from the next evaluation. */
 int pahq_set_dead_node_skipping(pahq_model*, int32_t on);
+
+/* Host-resident fp32 head weights (pahq_config.fp32_residency = PAHQ_FP32_ON_HOST; both calls return PAHQ_ESTATE
+ * otherwise).
+ * pahq_prefetch_heads: a caller that drives evaluations in an order of its own names the heads it will need next
+ * (Eq. Prefetch(t): the weights of S_t+1 move while step t computes): their transfers are started on the library's
+ * copy stream unless they are on the device or on their way already; nothing waits.  heads: bit h = head h of
+ * `layer`.  The library's own loops (sweeps, edge lists, circuit evaluation) predict by themselves.
+ * pahq_get_transfer_stats: since init, [0] head uses by passes, [1] of those, uses that had to start the transfer
+ * themselves and wait for all of it (demand transfers), [2] transfers started ahead of use, [3] bytes moved from host
+ * memory to the device, [4] bytes of pinned host memory held, [5] bytes of the device slots. */
+int pahq_prefetch_heads(pahq_model*, int32_t layer, uint64_t heads);
+int pahq_get_transfer_stats(pahq_model*, int64_t out[6]);
 
 /* Removed set, canonical edge order, one byte per edge (1 = removed, 0 = kept).  Any set is stored; which
  * sets an evaluation accepts is said at pahq_eval_edges. */

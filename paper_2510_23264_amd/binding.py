@@ -26,16 +26,16 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "n_heads", "d_head", "d_model", "d_mlp", "vocab", "n_ctx",
                                          "norm", "act", "pos")] + \
                [("norm_eps", C.c_float), ("rope_theta", C.c_float)] + \
-               [(n, C.c_int32) for n in ("split_qkv", "precision", "max_batch_edges", "mma", "low_bits", "nonattn_bf16")]
+               [(n, C.c_int32) for n in ("split_qkv", "precision", "max_batch_edges", "mma", "low_bits", "nonattn_bf16", "fp32_residency")]
 
     @classmethod
     def from_shape(cls, shape, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, low_bits=8, nonattn_bf16=False,
-                   split_qkv=True):
+                   split_qkv=True, fp32_on_host=False):
         return cls(n_layers=shape.n_layers, n_heads=shape.n_heads, d_head=shape.d_head, d_model=shape.d_model,
                    d_mlp=shape.d_mlp, vocab=shape.vocab, n_ctx=shape.n_ctx, norm=shape.norm, act=shape.act,
                    pos=shape.pos, norm_eps=shape.norm_eps, rope_theta=shape.rope_theta, split_qkv=1 if split_qkv else 0,
                    precision=precision, max_batch_edges=max_batch_edges, mma=mma, low_bits=low_bits,
-                   nonattn_bf16=1 if nonattn_bf16 else 0)
+                   nonattn_bf16=1 if nonattn_bf16 else 0, fp32_residency=1 if fp32_on_host else 0)
 
 
 _W_NAMES = ("W_E", "W_pos", "W_Q", "W_K", "W_V", "W_O", "b_Q", "b_K", "b_V", "b_O", "ln1_g", "ln1_b", "ln2_g",
@@ -91,6 +91,8 @@ def lib():
             "pahq_set_metric": [C.c_void_p, C.c_int32, i32p, i32p],
             "pahq_set_removed": [C.c_void_p, u8p], "pahq_get_removed": [C.c_void_p, u8p],
             "pahq_set_dead_node_skipping": [C.c_void_p, C.c_int32],
+            "pahq_prefetch_heads": [C.c_void_p, C.c_int32, C.c_uint64],
+            "pahq_get_transfer_stats": [C.c_void_p, i64p],
             "pahq_get_weight_q": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, u8p, f32p],
             "pahq_quantize_rows": [C.c_void_p, f32p, C.c_int32, C.c_int32, u8p, f32p],
             "pahq_quantize_rows_site": [C.c_void_p, C.c_int32, f32p, C.c_int32, C.c_int32, u8p, f32p],
@@ -172,11 +174,11 @@ class Model:
     (layouts as in include/pahq.h)."""
 
     def __init__(self, shape, weights, B, S, precision=PAHQ, max_batch_edges=32, mma=MMA_F16_EXACT, device="cuda:0",
-                 workspace_bytes_override=None, low_bits=8, nonattn_bf16=False, split_qkv=True):
+                 workspace_bytes_override=None, low_bits=8, nonattn_bf16=False, split_qkv=True, fp32_on_host=False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no HIP device: libpahq has no CPU path")
-        self.cfg = Config.from_shape(shape, precision, max_batch_edges, mma, low_bits, nonattn_bf16, split_qkv)
+        self.cfg = Config.from_shape(shape, precision, max_batch_edges, mma, low_bits, nonattn_bf16, split_qkv, fp32_on_host)
         self.B, self.S, self.T = B, S, B * S
         self.n_edges = edge_count(self.cfg)
         nbytes = workspace_bytes(self.cfg, B, S)
@@ -322,6 +324,18 @@ class Model:
 
     def set_dead_node_skipping(self, on):
         _chk(lib().pahq_set_dead_node_skipping(self.h, 1 if on else 0), "pahq_set_dead_node_skipping")
+
+    def prefetch_heads(self, layer, heads):
+        """heads: iterable of head indices of `layer` whose fp32 weights will be needed next (host residency)."""
+        mask = 0
+        for h in heads:
+            mask |= 1 << int(h)
+        _chk(lib().pahq_prefetch_heads(self.h, int(layer), C.c_uint64(mask)), "pahq_prefetch_heads")
+
+    def transfer_stats(self):
+        out = (C.c_int64 * 6)()
+        _chk(lib().pahq_get_transfer_stats(self.h, out), "pahq_get_transfer_stats")
+        return dict(zip(("head_uses", "demand_transfers", "transfers_ahead", "bytes_moved", "host_bytes", "slot_bytes"), out))
 
     def set_removed(self, removed):
         r = np.ascontiguousarray(removed, dtype=np.uint8)

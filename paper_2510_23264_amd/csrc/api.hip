@@ -25,11 +25,13 @@ int check_config(const pahq_config* c) {
   if (c->split_qkv != 0 && c->split_qkv != 1) return PAHQ_EINVAL;
   if (c->low_bits != 0 && c->low_bits != 4 && c->low_bits != 8 && c->low_bits != 16) return PAHQ_EINVAL;
   if (c->nonattn_bf16 != 0 && c->nonattn_bf16 != 1) return PAHQ_EINVAL;
+  if (c->fp32_residency != PAHQ_FP32_IN_HBM && c->fp32_residency != PAHQ_FP32_ON_HOST) return PAHQ_EINVAL;
   return PAHQ_OK;
 }
 // what this build of the kernels supports
 int check_supported(const pahq_config* c, int B, int S) {
   if (c->n_heads > 64) return PAHQ_EUNSUPPORTED;                      // sets of heads are 64-bit masks
+  if (c->fp32_residency == PAHQ_FP32_ON_HOST && c->precision == PAHQ_ALL_FP32) return PAHQ_EUNSUPPORTED;   // that mode multiplies the masters
   if ((c->nonattn_bf16 || c->low_bits == 16) && c->mma != PAHQ_MMA_F16_EXACT && c->precision != PAHQ_ALL_FP32) return PAHQ_EUNSUPPORTED;   // bfloat16 products have no FP8-instruction form
   if (c->low_bits == 16 && c->precision != PAHQ_ALL_FP32 && ((c->d_head != 32 && c->d_head != 64) || c->n_heads % (64 / c->d_head) != 0))
     return PAHQ_EUNSUPPORTED;                                         // the bfloat16 form of the fused output projection
@@ -77,6 +79,14 @@ void set_dims(pahq_model* M, const pahq_config* c, int B, int S) {
   M->f32_heads_max = M->all_f32 ? M->H : 1;
   M->ncap = std::max(M->nmax, 1024);
   M->tile = (long long)M->T * M->d;
+  M->w32.on = c->fp32_residency == PAHQ_FP32_ON_HOST;
+  if (M->w32.on) {
+    // one block per head: W_Q | W_K | W_V | W_O | b_Q | b_K | b_V, every part on a 256-byte boundary
+    const size_t mat = (size_t)M->d * M->dh, vec = ((size_t)M->dh + 63) / 64 * 64;
+    size_t o = 0;
+    for (int i = 0; i < 7; i++) { M->w32.off[i] = o; o += i < 4 ? mat : vec; }
+    M->w32.head_floats = o;
+  }
 }
 
 size_t arena_slot_bytes(const pahq_model* M) {
@@ -96,17 +106,21 @@ size_t layout(pahq_model* M, char* base) {
   const bool mlp = m > 0, swi = M->cfg.act == PAHQ_ACT_SWIGLU, learned = M->cfg.pos == PAHQ_POS_LEARNED;
   M->W_E = b.take<float>(V * d);
   M->W_pos = learned ? b.take<float>((size_t)M->cfg.n_ctx * d) : nullptr;
-  M->W_Q = b.take<float>(L * H * d * dh); M->W_K = b.take<float>(L * H * d * dh); M->W_V = b.take<float>(L * H * d * dh);
-  M->W_O = b.take<float>(L * H * dh * d);
+  const bool on_host = M->w32.on;          // then no fp32 matrix but the embeddings stays on the device
+  M->W_Q = on_host ? nullptr : b.take<float>(L * H * d * dh); M->W_K = on_host ? nullptr : b.take<float>(L * H * d * dh);
+  M->W_V = on_host ? nullptr : b.take<float>(L * H * d * dh);
+  M->W_O = on_host ? nullptr : b.take<float>(L * H * dh * d);
+  M->w32.dev = on_host ? b.take<float>(2 * H * M->w32.head_floats) : nullptr;
+  M->stage = on_host ? b.take<float>(std::max(std::max(H * d * dh, d * m), d * V)) : nullptr;
   M->b_Q = b.take<float>(L * H * dh); M->b_K = b.take<float>(L * H * dh); M->b_V = b.take<float>(L * H * dh);
   M->b_O = b.take<float>(L * d);
   M->ln1_g = b.take<float>(L * d); M->ln1_b = b.take<float>(L * d);
   M->ln2_g = mlp ? b.take<float>(L * d) : nullptr; M->ln2_b = mlp ? b.take<float>(L * d) : nullptr;
-  M->W_in = mlp ? b.take<float>(L * d * m) : nullptr; M->b_in = mlp ? b.take<float>(L * m) : nullptr;
-  M->W_gate = (mlp && swi) ? b.take<float>(L * d * m) : nullptr;
-  M->W_out = mlp ? b.take<float>(L * m * d) : nullptr; M->b_out = mlp ? b.take<float>(L * d) : nullptr;
+  M->W_in = (mlp && !on_host) ? b.take<float>(L * d * m) : nullptr; M->b_in = mlp ? b.take<float>(L * m) : nullptr;
+  M->W_gate = (mlp && swi && !on_host) ? b.take<float>(L * d * m) : nullptr;
+  M->W_out = (mlp && !on_host) ? b.take<float>(L * m * d) : nullptr; M->b_out = mlp ? b.take<float>(L * d) : nullptr;
   M->lnf_g = b.take<float>(d); M->lnf_b = b.take<float>(d);
-  M->W_U = b.take<float>(d * V); M->b_U = b.take<float>(V + 4);     // the GEMM epilogue reads bias in groups of four
+  M->W_U = on_host ? nullptr : b.take<float>(d * V); M->b_U = b.take<float>(V + 4);     // the GEMM epilogue reads bias in groups of four
   M->zeros_d = b.take<float>(d);
   M->rope_tab = M->cfg.pos == PAHQ_POS_ROPE ? b.take<float>((size_t)64 * dh) : nullptr;    // the attention kernel's (up to four) 16-position tiles
   M->bqkv = b.take<float>(L * 3 * H * dh);
@@ -215,7 +229,11 @@ int build_receiver_input(pahq_model* M, int w, int p0, float* dst) {
 // the state of v's fp32 head (corrupted run + reference distribution under that
 // precision set), the receiver plan for the current removed set, and v's
 // current input xv.
-int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
+// What the caller will evaluate after v, for the prediction of the fp32 weights needed next (host residency): receiver
+// ids in the order of their evaluation (repeats allowed); skip_dead: receivers whose node is dead are not evaluated.
+struct Upcoming { const int32_t* ids; int64_t n; bool skip_dead; };
+
+int setup_receiver(pahq_model* M, int v, RecvCtx& ctx, const Upcoming* up = nullptr) {
   const GraphDims& g = M->g;
   int kind, l, h, c;
   g.receiver_info(v, kind, l, h, c);
@@ -229,6 +247,7 @@ int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
   }
   ctx.pl = ctx.ph = -1;
   if (M->cfg.precision == PAHQ_PAHQ && kind == 0) { ctx.pl = l; ctx.ph = h; }
+  const bool layerwise = M->H > 1 && M->H <= M->nmax && M->cfg.mma == PAHQ_MMA_F16_EXACT;
   make_plan(M, ctx.p0, v, M->plan);
   if (ctx.pl >= 0) {
     PassArgs a; a.n = 1; a.p0 = ctx.p0; a.pl = ctx.pl; a.ph = ctx.ph; a.v = -1; a.patch_mode = 0;
@@ -237,7 +256,6 @@ int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
       // The reference distribution under this head's precision set.  The reference runs of all H heads of a layer go
       // as one pass of H instances where the model has room for them (they differ only in which head of that layer is
       // in fp32); the state of head h is then copy h of the arrays that pass fills.
-      const bool layerwise = M->H > 1 && M->H <= M->nmax && M->cfg.mma == PAHQ_MMA_F16_EXACT;
       const int copy = layerwise ? ctx.ph : 0;
       M->ref_logits = M->ref_logits_all + (long long)copy * M->B * M->Vp;
       M->ref_logz = M->ref_logz_all + (long long)copy * M->B;
@@ -271,6 +289,26 @@ int setup_receiver(pahq_model* M, int v, RecvCtx& ctx) {
     // investigated head's two unpatched inputs
     PassArgs a; a.kind = PREFIX; a.p0 = ctx.p0; a.n = 1; a.pl = ctx.pl; a.ph = ctx.ph; a.v = v; a.patch_mode = 0;
     PCHK(run_pass(M, a, &M->plan));
+  }
+  if (M->w32.on && M->cfg.precision == PAHQ_PAHQ) {
+    // Prefetch(t): the fp32 weights needed after this receiver's move while its candidates are evaluated -- those of
+    // the next head the caller's list names (a whole layer where its heads' reference runs will be made together),
+    // or, without a list, of the head that follows in the sweep's order
+    int nl = -1;
+    unsigned long long nm = 0;
+    if (up) {
+      const unsigned long long all = M->H >= 64 ? ~0ull : ((1ull << M->H) - 1ull);
+      for (int64_t q = 0, lim = std::min<int64_t>(up->n, 1 << 16); q < lim; q++) {
+        int k2, l2, h2, c2;
+        g.receiver_info(up->ids[q], k2, l2, h2, c2);
+        if (k2 != 0 || (l2 == ctx.pl && h2 == ctx.ph)) continue;
+        if (up->skip_dead && !node_is_live(M, up->ids[q])) continue;
+        nl = l2;
+        nm = (layerwise && l2 != ctx.pl && M->ref_layer != l2) ? all : (1ull << h2);
+        break;
+      }
+    } else if (ctx.pl >= 0) nl = next_heads_in_sweep_order(M->H, ctx.pl, ctx.ph, nm);
+    PCHK(w32_prefetch(M, nl, nm));
   }
   return PAHQ_OK;
 }
@@ -410,20 +448,73 @@ int pahq_init_model(const pahq_config* c, const pahq_weights* w, int32_t B, int3
       if (hipMemcpyAsync(M->bqkv + (l * 3 + cc) * H * dh, bsrc[cc] + l * H * dh, H * dh * sizeof(float),
                          hipMemcpyDeviceToDevice, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
   if (M->rope_tab && launch_rope_table(M->rope_tab, 64, (int)dh, c->rope_theta, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
-  // e4m3 codes + scales of every weight slice
+  // e4m3 codes + scales of every weight slice.  With the masters in the workspace a class is quantised where it lies;
+  // with host residency it passes through the staging buffer a layer at a time (quantise_class ends with a
+  // synchronisation, so the buffer is free again when it returns).
   const float* wc[3] = {M->W_Q, M->W_K, M->W_V};
+  const float* wsrc[3] = {w->W_Q, w->W_K, w->W_V};
   const int qo = M->nb16 ? 16 : M->qbits;      // the grid of the components that are not attention heads
-  for (size_t l = 0; l < L && rc == PAHQ_OK; l++)
-    for (int cc = 0; cc < 3 && rc == PAHQ_OK; cc++)
-      rc = quantise_class(M, wc[cc] + l * H * d * dh, (int)H, (int)d, (int)dh,
-                          M->qkv_codes + (l * 3 * H * dh + (size_t)cc * H * dh) * M->Kd, (long long)dh * M->Kd, M->Kd,
-                          M->qkv_scale + l * 3 * H + (size_t)cc * H, 1, M->qbits);
-  if (rc == PAHQ_OK) rc = quantise_class(M, M->W_O, (int)(L * H), (int)dh, (int)d, M->o_codes, (long long)d * M->Kh, M->Kh, M->o_scale, 1, M->qbits);
-  if (mlp && rc == PAHQ_OK) rc = quantise_class(M, M->W_in, (int)L, (int)d, (int)m, M->in_codes, (long long)m * M->Kd_o, M->Kd_o, M->in_scale, 1, qo);
-  if (mlp && swi && rc == PAHQ_OK) rc = quantise_class(M, M->W_gate, (int)L, (int)d, (int)m, M->gate_codes, (long long)m * M->Kd_o, M->Kd_o, M->gate_scale, 1, qo);
-  if (mlp && rc == PAHQ_OK) rc = quantise_class(M, M->W_out, (int)L, (int)m, (int)d, M->out_codes, (long long)d * M->Km_o, M->Km_o, M->out_scale, 1, qo);
-  if (rc == PAHQ_OK) rc = quantise_class(M, M->W_U, 1, (int)d, (int)V, M->u_codes, 0, M->Kd_o, M->u_scale, 1, qo);
+  const bool on_host = M->w32.on;
+  auto staged = [&](const float* resident, const float* src, size_t count) -> const float* {
+    if (!on_host) return resident;
+    if (rc == PAHQ_OK) rc = copy_in(M, M->stage, src, count, od);
+    return M->stage;
+  };
+  for (size_t l = 0; l < L && rc == PAHQ_OK; l++) {
+    for (int cc = 0; cc < 3 && rc == PAHQ_OK; cc++) {
+      const float* src = staged(on_host ? nullptr : wc[cc] + l * H * d * dh, wsrc[cc] + l * H * d * dh, H * d * dh);
+      if (rc == PAHQ_OK)
+        rc = quantise_class(M, src, (int)H, (int)d, (int)dh,
+                            M->qkv_codes + (l * 3 * H * dh + (size_t)cc * H * dh) * M->Kd, (long long)dh * M->Kd, M->Kd,
+                            M->qkv_scale + l * 3 * H + (size_t)cc * H, 1, M->qbits);
+    }
+    if (rc == PAHQ_OK) {
+      const float* src = staged(on_host ? nullptr : M->W_O + l * H * dh * d, w->W_O + l * H * dh * d, H * dh * d);
+      if (rc == PAHQ_OK)
+        rc = quantise_class(M, src, (int)H, (int)dh, (int)d, M->o_codes + l * H * d * M->Kh, (long long)d * M->Kh, M->Kh, M->o_scale + l * H, 1, M->qbits);
+    }
+    if (mlp && rc == PAHQ_OK) {
+      const float* src = staged(on_host ? nullptr : M->W_in + l * d * m, w->W_in + l * d * m, d * m);
+      if (rc == PAHQ_OK) rc = quantise_class(M, src, 1, (int)d, (int)m, M->in_codes + l * m * M->Kd_o, 0, M->Kd_o, M->in_scale + l, 1, qo);
+    }
+    if (mlp && swi && rc == PAHQ_OK) {
+      const float* src = staged(on_host ? nullptr : M->W_gate + l * d * m, w->W_gate + l * d * m, d * m);
+      if (rc == PAHQ_OK) rc = quantise_class(M, src, 1, (int)d, (int)m, M->gate_codes + l * m * M->Kd_o, 0, M->Kd_o, M->gate_scale + l, 1, qo);
+    }
+    if (mlp && rc == PAHQ_OK) {
+      const float* src = staged(on_host ? nullptr : M->W_out + l * m * d, w->W_out + l * m * d, m * d);
+      if (rc == PAHQ_OK) rc = quantise_class(M, src, 1, (int)m, (int)d, M->out_codes + l * d * M->Km_o, 0, M->Km_o, M->out_scale + l, 1, qo);
+    }
+  }
+  if (rc == PAHQ_OK) {
+    const float* src = staged(M->W_U, w->W_U, d * V);
+    if (rc == PAHQ_OK) rc = quantise_class(M, src, 1, (int)d, (int)V, M->u_codes, 0, M->Kd_o, M->u_scale, 1, qo);
+  }
   if (rc != PAHQ_OK) return fail(rc);
+  if (on_host) {
+    // the heads' fp32 blocks: pinned host memory, one block per head in the layout of a device slot
+    W32Cache& c32 = M->w32;
+    const size_t hf = c32.head_floats, mat = d * dh;
+    if (hipHostMalloc((void**)&c32.host, L * H * hf * sizeof(float), hipHostMallocDefault) != hipSuccess) return fail(PAHQ_EHIP);
+    memset(c32.host, 0, L * H * hf * sizeof(float));
+    const float* part[7] = {w->W_Q, w->W_K, w->W_V, w->W_O, w->b_Q, w->b_K, w->b_V};
+    for (size_t id = 0; id < L * H; id++)
+      for (int i = 0; i < 7; i++) {
+        const size_t count = i < 4 ? mat : dh;
+        float* dst = c32.host + id * hf + c32.off[i];
+        if (od) { if (hipMemcpy(dst, part[i] + id * count, count * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) return fail(PAHQ_EHIP); }
+        else memcpy(dst, part[i] + id * count, count * sizeof(float));
+      }
+    if (hipStreamCreateWithFlags(&c32.copy_stream, hipStreamNonBlocking) != hipSuccess) { c32.copy_stream = nullptr; return fail(PAHQ_EHIP); }
+    c32.slots.init((int)(2 * H));
+    c32.ready.assign(2 * H, nullptr); c32.released.assign(2 * H, nullptr);
+    for (size_t i = 0; i < 2 * H; i++) {
+      if (hipEventCreateWithFlags(&c32.ready[i], hipEventDisableTiming) != hipSuccess) return fail(PAHQ_EHIP);
+      if (hipEventCreateWithFlags(&c32.released[i], hipEventDisableTiming) != hipSuccess) return fail(PAHQ_EHIP);
+      // recorded once so that the first wait on either finds a completed event
+      if (hipEventRecord(c32.ready[i], M->stream) != hipSuccess || hipEventRecord(c32.released[i], M->stream) != hipSuccess) return fail(PAHQ_EHIP);
+    }
+  }
   // embeddings, biases and norm parameters are used unquantised: check them too
   {
     struct { const float* p; size_t n; } extra[] = {{M->W_E, V * d}, {M->W_pos, learned ? (size_t)c->n_ctx * d : 0},
@@ -451,6 +542,10 @@ int pahq_init_model(const pahq_config* c, const pahq_weights* w, int32_t B, int3
 
 void pahq_free(pahq_model* M) {
   if (!M) return;
+  if (M->w32.copy_stream) { (void)hipStreamSynchronize(M->w32.copy_stream); (void)hipStreamDestroy(M->w32.copy_stream); }
+  for (hipEvent_t e : M->w32.ready) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : M->w32.released) if (e) (void)hipEventDestroy(e);
+  if (M->w32.host) (void)hipHostFree(M->w32.host);
   if (M->kl_host) (void)hipHostFree(M->kl_host);
   if (M->send_host) (void)hipHostFree(M->send_host);
   for (hipEvent_t e : M->prof_ev) (void)hipEventDestroy(e);
@@ -575,7 +670,8 @@ int pahq_eval_edge_list(pahq_model* M, int64_t n, const int32_t* receivers, cons
       if (k != 0) break;
     }
     RecvCtx ctx;
-    PCHK(setup_receiver(M, receivers[i], ctx));
+    const Upcoming up = {receivers + j, n - j, false};
+    PCHK(setup_receiver(M, receivers[i], ctx, &up));
     if (runs == 1) {
       PCHK(eval_candidates(M, ctx, nullptr, nullptr, sender_ids + i, (int)(j - i), kl_out + i));
     } else {
@@ -637,12 +733,14 @@ static int sweep_impl(pahq_model* M, float tau, const int32_t* receivers, int32_
   if (!sweep_order(g, receivers, n_receivers, order)) return PAHQ_EINVAL;
   std::fill(M->removed.begin(), M->removed.end(), 0);
   int64_t evals = 0;
-  for (int v : order) {
+  for (size_t oi = 0; oi < order.size(); oi++) {
+    const int v = order[oi];
     const int n_up = g.n_upstream(v);
     uint8_t* row = M->removed.data() + M->edge_off[v];
     if (!node_is_live(M, v)) { memset(row, 1, n_up); continue; }
     RecvCtx ctx;
-    PCHK(setup_receiver(M, v, ctx));
+    const Upcoming up = {order.data() + oi + 1, (int64_t)(order.size() - oi - 1), true};
+    PCHK(setup_receiver(M, v, ctx, &up));
     double kl_cur;
     PCHK(eval_state(M, ctx, &kl_cur));
     // the accept scan (controller.h) drives the device batches; send_host / kl_host are its work arrays
@@ -1024,6 +1122,23 @@ int pahq_get_sender_output(pahq_model* M, int32_t which, int32_t sender, float* 
 int pahq_get_counters(pahq_model* M, int64_t out[3]) {
   if (!M || !out) return PAHQ_EINVAL;
   out[0] = M->counters[0]; out[1] = M->counters[1]; out[2] = M->counters[2];
+  return PAHQ_OK;
+}
+
+int pahq_prefetch_heads(pahq_model* M, int32_t layer, uint64_t heads) {
+  if (!M) return PAHQ_EINVAL;
+  if (!M->w32.on) return PAHQ_ESTATE;
+  if (layer < 0 || layer >= M->L || (M->H < 64 && (heads >> M->H) != 0)) return PAHQ_EINVAL;
+  return w32_prefetch(M, layer, heads);
+}
+
+int pahq_get_transfer_stats(pahq_model* M, int64_t out[6]) {
+  if (!M || !out) return PAHQ_EINVAL;
+  if (!M->w32.on) return PAHQ_ESTATE;
+  const W32Cache& c = M->w32;
+  out[0] = c.slots.n_acquire; out[1] = c.slots.n_demand; out[2] = c.slots.n_prefetch; out[3] = c.bytes_moved;
+  out[4] = (int64_t)((size_t)M->L * M->H * c.head_floats * sizeof(float));
+  out[5] = (int64_t)((size_t)c.slots.n_slots * c.head_floats * sizeof(float));
   return PAHQ_OK;
 }
 

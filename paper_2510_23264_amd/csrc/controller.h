@@ -179,4 +179,54 @@ int scan_receiver(int n_up, int max_batch, double tau, double& kl_cur, uint8_t* 
   return 0;
 }
 
+// Bookkeeping of the device slots that hold fp32 head weights while the masters stay in host memory
+// (paper, Sec. "Selective Precision Allocation Strategy", Hierarchical Weight Scheduling: S_t, the nodes
+// in fp32 at step t, must be on the device at t, and Prefetch(t) moves S_{t+1} while step t computes;
+// Sec. "Algorithm Implementation in Practice", Scheduler Implementation).
+//
+// Head id = layer * H + head lives in slot id % n_slots (n_slots = 2 H: all heads of two neighbouring
+// layers fit at once, so the heads of the layer the sweep visits next never displace the current one's).
+// The caller does the transfers and the event waits; this keeps who is where:
+//   acquire(id)   a pass is about to use head id; returns true if a transfer has to be issued now
+//                 (a demand transfer: the pass waits for all of it); the slot is busy until release
+//   prefetch(id)  the head is expected next; returns true if a transfer should be issued now (false:
+//                 already there or on its way, or the slot still serves a running pass)
+//   release(id)   the pass has enqueued its last use
+// A slot's contents change only through acquire / prefetch returning true.
+struct HeadSlots {
+  int n_slots = 0;
+  std::vector<int> holds;          // per slot: head id it holds or is being filled with, -1 = nothing yet
+  std::vector<char> busy;          // per slot: acquired and not yet released
+  long long n_acquire = 0, n_demand = 0, n_prefetch = 0;
+  void init(int slots) { n_slots = slots; holds.assign(slots, -1); busy.assign(slots, 0); n_acquire = n_demand = n_prefetch = 0; }
+  int slot_of(int id) const { return id % n_slots; }
+  bool resident(int id) const { return holds[slot_of(id)] == id; }
+  // returns 1 = issue a transfer, 0 = nothing to do, -1 = the slot is in use by another head of the same pass
+  int acquire(int id) {
+    const int s = slot_of(id);
+    n_acquire++;
+    if (holds[s] == id) { busy[s] = 1; return 0; }
+    if (busy[s]) return -1;
+    holds[s] = id; busy[s] = 1; n_demand++;
+    return 1;
+  }
+  bool prefetch(int id) {
+    const int s = slot_of(id);
+    if (holds[s] == id || busy[s]) return false;
+    holds[s] = id; n_prefetch++;
+    return true;
+  }
+  void release(int id) { const int s = slot_of(id); if (holds[s] == id) busy[s] = 0; }
+  void release_all() { std::fill(busy.begin(), busy.end(), 0); }
+};
+
+// The head (or heads) a sweep in descending receiver order needs after head (l, h): the next lower head of the
+// layer, and below head 0 every head of the layer underneath (the reference runs of a layer's heads are made
+// together).  Returns the layer (-1: none) and sets mask to the heads.
+inline int next_heads_in_sweep_order(int H, int l, int h, unsigned long long& mask) {
+  if (h > 0) { mask = 1ull << (h - 1); return l; }
+  mask = H >= 64 ? ~0ull : ((1ull << H) - 1ull);
+  return l - 1;
+}
+
 }  // namespace pahq

@@ -36,6 +36,21 @@ struct Arena {          // descriptor staging: pinned host mirror + device copy,
   int next;
 };
 
+// fp32 head weights kept in pinned host memory (pahq_config.fp32_residency = PAHQ_FP32_ON_HOST): one block per head
+// [W_Q | W_K | W_V | W_O | b_Q | b_K | b_V]; the device holds 2 H blocks (controller.h, HeadSlots) that a second stream
+// fills.  ready[s] is recorded on the copy stream behind a slot's transfer, released[s] on the compute stream behind
+// the last pass that read the slot; each stream waits for the other's event before it touches the slot.
+struct W32Cache {
+  bool on = false;
+  float* host = nullptr;            // pinned, [L * H][head_floats]
+  float* dev = nullptr;             // [2 H][head_floats], inside the workspace
+  size_t head_floats = 0, off[7] = {0, 0, 0, 0, 0, 0, 0};    // offsets of W_Q, W_K, W_V, W_O, b_Q, b_K, b_V in a block
+  HeadSlots slots;
+  std::vector<hipEvent_t> ready, released;
+  hipStream_t copy_stream = nullptr;
+  long long bytes_moved = 0;
+};
+
 }  // namespace pahq
 
 struct pahq_model {
@@ -93,6 +108,8 @@ struct pahq_model {
   int* send_host;                         // pinned
   int ncap;                               // candidates one host round trip can carry (size of the send / kl arrays)
   pahq::Arena arena;
+  pahq::W32Cache w32;
+  float* stage = nullptr;                 // fp32 masters pass through here on their way to the quantiser (host residency)
 
   // host state
   std::vector<uint8_t> removed;           // canonical edge order
@@ -129,5 +146,16 @@ static inline float* corrupt_prefix(pahq_model* M, int p) {
 }
 int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan);
 void make_plan(pahq_model* M, int p0, int v, RecvPlan& out);
+// fp32 matrix (which = 0..3: W_Q, W_K, W_V, W_O) or projection bias (4..6: b_Q, b_K, b_V) of head (l, h): where a pass
+// reads it.  With host residency that is the head's slot, valid between w32_acquire and w32_release.
+static inline const float* w32_ptr(const pahq_model* M, int which, int l, int h) {
+  const long long id = (long long)l * M->H + h;
+  if (M->w32.on) return M->w32.dev + (size_t)M->w32.slots.slot_of((int)id) * M->w32.head_floats + M->w32.off[which];
+  const float* base[7] = {M->W_Q, M->W_K, M->W_V, M->W_O, M->b_Q, M->b_K, M->b_V};
+  return base[which] + id * (which < 3 ? (long long)M->d * M->dh : which == 3 ? (long long)M->dh * M->d : (long long)M->dh);
+}
+int w32_acquire(pahq_model* M, int l, unsigned long long mask);     // before the first launch that reads them
+int w32_release(pahq_model* M, int l, unsigned long long mask);     // behind the last
+int w32_prefetch(pahq_model* M, int l, unsigned long long mask);    // expected next: starts the transfers, waits for nothing
 int prof_harvest(pahq_model* M);     // synchronises the stream and folds recorded event pairs into M->prof
 }  // namespace pahq

@@ -28,9 +28,54 @@ void make_plan(pahq_model* M, int p0, int v, RecvPlan& out) {
   plan_receivers(M->g, M->removed.data(), M->edge_off.data(), M->cfg.precision == PAHQ_PAHQ, p0, v, out, M->skip_dead);
 }
 
+// ---- fp32 head weights resident in host memory: transfers into the heads' device slots
+static int w32_fetch(pahq_model* M, int id) {
+  W32Cache& c = M->w32;
+  const int s = c.slots.slot_of(id);
+  const size_t bytes = c.head_floats * sizeof(float);
+  HIPCHK(hipStreamWaitEvent(c.copy_stream, c.released[s], 0));        // the slot's last readers are done
+  HIPCHK(hipMemcpyAsync(c.dev + (size_t)s * c.head_floats, c.host + (size_t)id * c.head_floats, bytes, hipMemcpyHostToDevice, c.copy_stream));
+  HIPCHK(hipEventRecord(c.ready[s], c.copy_stream));
+  c.bytes_moved += (long long)bytes;
+  return PAHQ_OK;
+}
+int w32_acquire(pahq_model* M, int l, unsigned long long mask) {
+  W32Cache& c = M->w32;
+  if (!c.on) return PAHQ_OK;
+  for (int h = 0; h < M->H; h++) {
+    if (!((mask >> h) & 1ull)) continue;
+    const int id = l * M->H + h, r = c.slots.acquire(id);
+    if (r < 0) return PAHQ_ESTATE;                                     // two heads of one pass in one slot
+    if (r == 1) { int rc = w32_fetch(M, id); if (rc != PAHQ_OK) return rc; }
+    HIPCHK(hipStreamWaitEvent(M->stream, c.ready[c.slots.slot_of(id)], 0));
+  }
+  return PAHQ_OK;
+}
+int w32_release(pahq_model* M, int l, unsigned long long mask) {
+  W32Cache& c = M->w32;
+  if (!c.on) return PAHQ_OK;
+  for (int h = 0; h < M->H; h++) {
+    if (!((mask >> h) & 1ull)) continue;
+    const int id = l * M->H + h;
+    HIPCHK(hipEventRecord(c.released[c.slots.slot_of(id)], M->stream));
+    c.slots.release(id);
+  }
+  return PAHQ_OK;
+}
+int w32_prefetch(pahq_model* M, int l, unsigned long long mask) {
+  W32Cache& c = M->w32;
+  if (!c.on || l < 0 || l >= M->L) return PAHQ_OK;
+  for (int h = 0; h < M->H; h++) {
+    if (!((mask >> h) & 1ull)) continue;
+    const int id = l * M->H + h;
+    if (c.slots.prefetch(id)) { int rc = w32_fetch(M, id); if (rc != PAHQ_OK) return rc; }
+  }
+  return PAHQ_OK;
+}
+
 namespace {
 
-enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH, OP_OPROJ, OP_KLRED, OP_PREF, OP_SWIGLU32, OP_LD };
+enum OpType { OP_BUILD, OP_GEMM8, OP_GEMM32, OP_ATTN, OP_COMBINE, OP_HIDQ, OP_LOGZ, OP_KL, OP_PATCH, OP_OPROJ, OP_KLRED, OP_PREF, OP_SWIGLU32, OP_LD, OP_W32ACQ, OP_W32REL };
 struct Op { OpType t; int i0, i1, i2, i3; void* p0; void* p1; double flops, bytes; unsigned long long u64, u64b; };
 
 struct Stream { float* p; long long is; };
@@ -122,6 +167,10 @@ struct Builder {
     Op o; o.t = t; o.i0 = i0; o.i1 = i1; o.i2 = i2; o.i3 = i3; o.p0 = p0; o.p1 = p1; o.flops = 0; o.bytes = 0; o.u64 = 0; o.u64b = 0;
     ops.push_back(o);
   }
+  // fp32 head weights of layer l that the launches between the two calls read (host residency: the heads' slots are
+  // filled and held in between; nothing otherwise)
+  void w32_begin(int l, unsigned long long mask) { if (M->w32.on && mask) { add_op(OP_W32ACQ, l, -1); ops.back().u64 = mask; } }
+  void w32_end(int l, unsigned long long mask) { if (M->w32.on && mask) { add_op(OP_W32REL, l); ops.back().u64 = mask; } }
   // algorithmic work of the op just added (all instances)
   void work_gemm(int pb) {
     // flops of the contraction; bytes that must move: operand codes once (A: M x K, W: N x K; for
@@ -266,10 +315,10 @@ struct Builder {
     // candidates, or the candidates of all three inputs of the head side by side (they share everything else)
     int cnt[3] = {0, 0, 0};
     const bool multi = a.chan_count[0] + a.chan_count[1] + a.chan_count[2] > 0;
-    const float* Wc[3] = {M->W_Q, M->W_K, M->W_V};
-    const float* bc[3] = {M->b_Q, M->b_K, M->b_V};
-    const long long hoff = (long long)l * H + hv;
+    const float* Wc[3] = {w32_ptr(M, 0, l, hv), w32_ptr(M, 1, l, hv), w32_ptr(M, 2, l, hv)};
+    const float* bc[3] = {w32_ptr(M, 4, l, hv), w32_ptr(M, 5, l, hv), w32_ptr(M, 6, l, hv)};
     const float* shared0 = M->qkv_sh + (long long)hv * dh;
+    w32_begin(l, 1ull << hv);
     const int ld_sh = 3 * H * dh;
     if (cv < 0) {
       // a head with a single input: every instance patches it, and all three projections read the patched rows
@@ -282,7 +331,7 @@ struct Builder {
       const long long blk = (long long)a.n * T * dh;              // q, k, v of all instances one after the other
       int pq = (int)probs.size();
       for (int c = 0; c < 3; c++)
-        probs.push_back(prob8(M->xf32, M->tile, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1, bc[c] + hoff * dh,
+        probs.push_back(prob8(M->xf32, M->tile, d, nullptr, 0, 0, Wc[c], dh, nullptr, 1, bc[c],
                               M->qv + c * blk, (long long)T * dh, dh, 0, T, dh, d, d));
       add_op(OP_GEMM32, pq, 3, T * a.n, dh); work_gemm(pq);
       AttnSrc src; memset(&src, 0, sizeof(src));
@@ -307,8 +356,8 @@ struct Builder {
     int pq0 = (int)probs.size(), np = 0;
     for (int c = 0, off = 0; c < 3; off += cnt[c], c++) {
       if (!cnt[c]) continue;
-      GemmProb pq = prob8(M->xf32 + (long long)off * M->tile, M->tile, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1,
-                          bc[c] + hoff * dh, M->qv + (long long)off * T * dh, (long long)T * dh, dh, 0, T, dh, d, d);
+      GemmProb pq = prob8(M->xf32 + (long long)off * M->tile, M->tile, d, nullptr, 0, 0, Wc[c], dh, nullptr, 1,
+                          bc[c], M->qv + (long long)off * T * dh, (long long)T * dh, dh, 0, T, dh, d, d);
       pq.M = T * cnt[c];
       probs.push_back(pq); np++;
     }
@@ -328,12 +377,13 @@ struct Builder {
     Stream nxt = next_run(2 * l + 1, run.p == M->run_a ? M->run_b : M->run_a);
     int s = g.head(l, hv);
     const int pf = (int)probs.size();
-    GemmProb pp = prob8(M->zf32, (long long)T * dh, dh, nullptr, 0, 0, M->W_O + hoff * dh * d, d, nullptr, 1, nullptr,
+    GemmProb pp = prob8(M->zf32, (long long)T * dh, dh, nullptr, 0, 0, w32_ptr(M, 3, l, hv), d, nullptr, 1, nullptr,
                         nxt.p, nxt.is, d, 0, T, d, dh, dh);
     pp.add = M->oth; pp.add_is = 0;
     if (plan->slot_of[s] >= 0) { pp.aux = slot_ptr(s); pp.aux_is = slot_is(s); pp.aux_sub = corrupt_ref_tile(s); }
     probs.push_back(pp);
     add_op(OP_GEMM32, pf, 1, T * a.n, d); work_gemm(pf);
+    w32_end(l, 1ull << hv);
     run = nxt;
   }
 
@@ -366,12 +416,10 @@ struct Builder {
     probs.push_back(p8);
     add_op(OP_GEMM8, pb, 1, T, 3 * H * dh); work_gemm(pb);
     int pf = (int)probs.size();
-    const float* Wc[3] = {M->W_Q, M->W_K, M->W_V};
-    const float* bc[3] = {M->b_Q, M->b_K, M->b_V};
+    w32_begin(l, all_heads);
     for (int h = 0; h < H; h++)
       for (int c = 0; c < 3; c++) {
-        const long long hoff = (long long)l * H + h;
-        GemmProb pq = prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1, bc[c] + hoff * dh,
+        GemmProb pq = prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, w32_ptr(M, c, l, h), dh, nullptr, 1, w32_ptr(M, 4 + c, l, h),
                             M->qkv + ((long long)c * H + h) * dh, (long long)T * qkv_ld, (int)qkv_ld, 0, T, dh, d, d);
         pq.M = T;
         probs.push_back(pq);
@@ -390,11 +438,12 @@ struct Builder {
     pf = (int)probs.size();
     for (int h = 0; h < H; h++) {
       GemmProb pp = prob8(M->zf32 + (long long)h * dh, (long long)T * H * dh, H * dh, nullptr, 0, 0,
-                          M->W_O + ((long long)l * H + h) * dh * d, d, nullptr, 1, nullptr, M->headout + (long long)h * M->tile, M->tile, d, 0, T, d, dh, dh);
+                          w32_ptr(M, 3, l, h), d, nullptr, 1, nullptr, M->headout + (long long)h * M->tile, M->tile, d, 0, T, d, dh, dh);
       pp.M = T;
       probs.push_back(pp);
     }
     add_op(OP_GEMM32, pf, H, T, d); work_gemm(pf);
+    w32_end(l, all_heads);
     Stream nxt = next_run(2 * l + 1, run.p == M->run_a ? M->run_b : M->run_a);
     for (int h = 0; h < H; h++) {
       OprojDesc od; memset(&od, 0, sizeof(od));
@@ -505,19 +554,18 @@ struct Builder {
     // ---- fp32 projections of the heads in the precision set
     if (nf) {
       int pf = (int)probs.size();
-      const float* Wc[3] = {M->W_Q, M->W_K, M->W_V};
-      const float* bc[3] = {M->b_Q, M->b_K, M->b_V};
+      w32_begin(l, fmask);
       for (int h = 0; h < H; h++) {
         if (!((fmask >> h) & 1ull)) continue;
         for (int c = 0; c < 3; c++) {
           const GroupDesc& gd = groups[grp_of[c * H + h]];
-          long long hoff = (long long)l * H + h;
-          probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, Wc[c] + hoff * d * dh, dh, nullptr, 1,
-                                bc[c] + hoff * dh, qkv_buf + ((long long)c * H + h) * dh, (long long)T * qkv_ld,
+          probs.push_back(prob8(gd.out_f32, gd.out_f32_is, d, nullptr, 0, 0, w32_ptr(M, c, l, h), dh, nullptr, 1,
+                                w32_ptr(M, 4 + c, l, h), qkv_buf + ((long long)c * H + h) * dh, (long long)T * qkv_ld,
                                 (int)qkv_ld, 0, T, dh, d, d));
         }
       }
       add_op(OP_GEMM32, pf, 3 * nf, T * a.n, dh); work_gemm(pf);
+      if (prefix) w32_end(l, fmask);                    // a prefix pass stops before the output projection
     }
     if (prefix && off8 == all_heads) {
       // only the investigated head of this layer is live: what every candidate shares is the stream, the bias and
@@ -569,7 +617,7 @@ struct Builder {
         if (!((fmask >> h) & 1ull)) continue;
         int pf = (int)probs.size();
         GemmProb pp = prob8(M->zf32 + (long long)k * dh, (long long)T * nf * dh, nf * dh, nullptr, 0, 0,
-                            M->W_O + ((long long)l * H + h) * dh * d, d, nullptr, 1, nullptr, M->headout, M->tile, d, 0, T, d, dh, dh);
+                            w32_ptr(M, 3, l, h), d, nullptr, 1, nullptr, M->headout, M->tile, d, 0, T, d, dh, dh);
         if (k > 0) { pp.add = M->headout; pp.add_is = M->tile; }
         else if (deadsum) { pp.add = deadsum; pp.add_is = 0; }          // the chain starts from the dead heads' stand-ins
         pp.aux = hx[h].dst; pp.aux_is = hx[h].dst_is; pp.aux_sub = hx[h].sub;
@@ -577,6 +625,7 @@ struct Builder {
         add_op(OP_GEMM32, pf, 1, T * a.n, d); work_gemm(pf);
         k++;
       }
+      w32_end(l, fmask);
       od.extra = M->headout; od.extra_is = M->tile;
     }
     if (off8 == all_heads && nf && !prefix) {
@@ -810,6 +859,19 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
     b.final_block(run);
   }
 
+  if (M->w32.on) {
+    // a pass that failed half way may have left slots held: nothing of it may still be running when they are reused
+    bool held = false;
+    for (char c : M->w32.slots.busy) held = held || c;
+    if (held) { HIPCHK(hipStreamSynchronize(M->stream)); M->w32.slots.release_all(); }
+    // each acquisition also names the next one of this pass, whose transfers start while this layer computes
+    int nxt = -1;
+    for (int i = (int)b.ops.size() - 1; i >= 0; i--)
+      if (b.ops[i].t == OP_W32ACQ) {
+        if (nxt >= 0) { b.ops[i].i1 = b.ops[nxt].i0; b.ops[i].u64b = b.ops[nxt].u64; }
+        nxt = i;
+      }
+  }
   for (GroupDesc& gd : b.groups) if (!gd.qbits) gd.qbits = M->qbits;      // groups of bfloat16 blocks have said 16
   for (AttnSrc& as : b.asrcs) as.qbits = M->qbits;
   // ---- upload the descriptor tables
@@ -851,6 +913,13 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
   const bool prof_pass = M->prof_on && (M->prof_pass++ % M->prof_every) == 0;
   for (const Op& o : b.ops) {
     int pair = -1;
+    if (o.t == OP_W32ACQ) {
+      int rc = w32_acquire(M, o.i0, o.u64);
+      if (rc == PAHQ_OK && o.i1 >= 0 && o.i1 != o.i0) rc = w32_prefetch(M, o.i1, o.u64b);
+      if (rc != PAHQ_OK) return rc;
+      continue;
+    }
+    if (o.t == OP_W32REL) { int rc = w32_release(M, o.i0, o.u64); if (rc != PAHQ_OK) return rc; continue; }
     if (prof_pass && ((M->prof_mask >> cls_of[o.t]) & 1u)) {
       if (M->prof_used * 2 + 2 > (int)M->prof_ev.size()) { int r = prof_harvest(M); if (r != PAHQ_OK) return r; }
       pair = M->prof_used++;
@@ -927,6 +996,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
         break;
       }
       case OP_LOGZ: HIPCHK(launch_logz((const float*)o.p0, B, M->V, M->Vp, (double*)o.p1, st)); break;
+      case OP_W32ACQ: case OP_W32REL: break;             // handled above
       case OP_KL:
         HIPCHK(launch_kl(M->logits, (long long)B * M->Vp, (const float*)o.p0, (const double*)o.p1, M->row_kl, M->kl_dev + a.io_off,
                          n, B, M->V, M->Vp, st));

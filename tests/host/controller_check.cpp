@@ -201,8 +201,69 @@ static void check_graph_and_plan(uint64_t seed, int L, int H, bool mlp, bool spl
   CHECK(!sweep_order(g, neg, 1, order), "a negative id must be refused");
 }
 
+// Slots of host-resident fp32 head weights: a model of the device (what each slot really contains, which slots a
+// running pass reads) follows the bookkeeping's answers.  A pass must always find its heads in their slots, no
+// transfer may land in a slot a running pass reads, and with the sweep-order prediction only the very first head
+// is fetched on demand.
+static void check_head_slots(int L, int H, uint64_t seed) {
+  HeadSlots hs; hs.init(2 * H);
+  std::vector<int> content(2 * H, -1);      // the model: head id whose weights the slot contains
+  std::vector<char> in_use(2 * H, 0);
+  long demand = 0;
+  auto transfer = [&](int id) { int s = hs.slot_of(id); CHECK(!in_use[s], "transfer into a slot in use (head %d)", id); content[s] = id; };
+  auto use = [&](int l, unsigned long long mask) {
+    for (int h = 0; h < H; h++) if ((mask >> h) & 1ull) {
+      int id = l * H + h, r = hs.acquire(id);
+      CHECK(r >= 0, "two heads of one pass in one slot");
+      if (r == 1) { transfer(id); demand++; }
+      in_use[hs.slot_of(id)] = 1;
+      CHECK(content[hs.slot_of(id)] == id, "head %d not in its slot", id);
+    }
+  };
+  auto done = [&](int l, unsigned long long mask) {
+    for (int h = 0; h < H; h++) if ((mask >> h) & 1ull) { hs.release(l * H + h); in_use[hs.slot_of(l * H + h)] = 0; }
+  };
+  const unsigned long long all = H >= 64 ? ~0ull : ((1ull << H) - 1ull);
+  // the sweep: per layer from the top the reference runs of all heads together, then head by head downwards,
+  // each predicting its successor
+  for (int l = L - 1; l >= 0; l--) {
+    for (int h = H - 1; h >= 0; h--) {
+      if (h == H - 1) { use(l, all); done(l, all); }
+      for (int pass = 0; pass < 3; pass++) {
+        use(l, 1ull << h);
+        unsigned long long nm; int nl = next_heads_in_sweep_order(H, l, h, nm);
+        if (nl >= 0) for (int q = 0; q < H; q++) if ((nm >> q) & 1ull) if (hs.prefetch(nl * H + q)) transfer(nl * H + q);
+        done(l, 1ull << h);
+      }
+    }
+  }
+  CHECK(demand == H, "sweep order: %ld demand transfers, expected the %d of the first layer's joint pass", demand, H);
+  // a forward pass over every layer with a random set of fp32 heads, the next layer's set predicted at each layer
+  std::vector<unsigned long long> masks(L);
+  for (int l = 0; l < L; l++) masks[l] = mix(seed * 131 + l) & all;
+  for (int l = 0; l < L; l++) {
+    use(l, masks[l]);
+    if (l + 1 < L) for (int q = 0; q < H; q++) if ((masks[l + 1] >> q) & 1ull) if (hs.prefetch((l + 1) * H + q)) transfer((l + 1) * H + q);
+    done(l, masks[l]);
+  }
+  // random order, random predictions (some wrong, some into busy slots)
+  for (int it = 0; it < 2000; it++) {
+    int l = (int)(mix(seed + it) % L), h = (int)(mix(seed * 7 + it) % H);
+    use(l, 1ull << h);
+    int pl = (int)(mix(seed * 13 + it) % L), ph = (int)(mix(seed * 17 + it) % H);
+    if (hs.prefetch(pl * H + ph)) transfer(pl * H + ph);
+    done(l, 1ull << h);
+  }
+  CHECK(hs.n_acquire > 0 && hs.n_demand <= hs.n_acquire, "counters");
+  // a failed pass leaves slots busy: release_all frees them
+  use(0, 1ull); hs.release_all(); std::fill(in_use.begin(), in_use.end(), 0);
+  CHECK(hs.prefetch(2 * H) == (2 * H < L * H) || L * H <= 2 * H, "a slot freed by release_all takes a transfer again");
+}
+
 int main() {
   int cases = 0;
+  { const int hs_shapes[][2] = {{1, 1}, {2, 1}, {3, 2}, {4, 4}, {12, 12}, {5, 64}};
+    for (auto& sh : hs_shapes) for (uint64_t seed = 1; seed <= 3; seed++) { check_head_slots(sh[0], sh[1], seed); cases++; } }
   const double taus[] = {-1.0, 0.0, 5e-7, 2e-5, 1.5e-4, 6e-4, 1.0};
   const int sizes[] = {0, 1, 2, 3, 7, 16, 33, 100, 157, 301};
   const int batches[] = {1, 2, 3, 8, 64, 128, 512};
