@@ -256,6 +256,15 @@ int pahq_eval_current(pahq_model*, int32_t receiver, float* kl_out);
 int pahq_acdc_sweep(pahq_model*, float tau, const int32_t* receivers, int32_t n_receivers,
                     uint8_t* kept, int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap);
 
+/* Continues an interrupted sweep: the same pass over `receivers` (NULL/0 = all), starting from the model's CURRENT
+ * removed set instead of the empty one.  A sweep decides receiver by receiver, so its state after any receiver is
+ * the removed set alone: rebuild it from the trace (or keep pahq_get_removed), hand it to pahq_set_removed -- on this
+ * model or, after pahq_clean_cache with the same prompts, on a new one -- and name the receivers not yet decided.
+ * The result is that of the uninterrupted sweep, decision for decision.  PAHQ_ESTATE if a named receiver already
+ * has a removed edge, or if the removed set touches a receiver upstream of a named one. */
+int pahq_acdc_sweep_resume(pahq_model*, float tau, const int32_t* receivers, int32_t n_receivers,
+                           uint8_t* kept, int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap);
+
 /* The same pass for a grid of thresholds (the paper's Experiments section scans 21 log-spaced values of tau in
  * [0.001, 3.16] to trace a ROC curve): every sweep starts from the empty removed set and all of them share the
  * clean / corrupted caches of one pahq_clean_cache call, which is the only part of a sweep that does not depend

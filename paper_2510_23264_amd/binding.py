@@ -84,6 +84,7 @@ def lib():
             "pahq_round_rows_bf16": [C.c_void_p, C.c_int32, f32p, C.c_int32, C.c_int32, C.POINTER(C.c_uint16)],
             "pahq_eval_current": [C.c_void_p, C.c_int32, f32p],
             "pahq_acdc_sweep": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
+            "pahq_acdc_sweep_resume": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
             "pahq_eval_edges_sender_policy": [C.c_void_p, C.c_int32, i32p, C.c_int32, f32p, f32p],
             "pahq_acdc_sweep_sender_policy": [C.c_void_p, C.c_float, i32p, C.c_int32, u8p, i64p, C.POINTER(TraceRec), C.c_int64],
             "pahq_acdc_sweep_grid": [C.c_void_p, f32p, C.c_int32, i32p, C.c_int32, u8p, i64p],
@@ -271,8 +272,8 @@ class Model:
                                                  _ptr(cur, C.c_float)), "pahq_eval_edges_sender_policy")
         return new, cur
 
-    def acdc_sweep(self, tau, receivers=None, trace_cap=None, sender_policy=False):
-        """Returns (kept uint8[n_edges], n_evals, trace structured array)."""
+    def acdc_sweep(self, tau, receivers=None, trace_cap=None, sender_policy=False, resume=False):
+        """Returns (kept uint8[n_edges], n_evals, trace structured array).  resume: start from the current removed set."""
         kept = np.empty(self.n_edges, dtype=np.uint8)
         n_evals = C.c_int64()
         cap = self.n_edges if trace_cap is None else int(trace_cap)
@@ -282,7 +283,8 @@ class Model:
         else:
             r = np.ascontiguousarray(receivers, dtype=np.int32)
             rp, rn = _ptr(r, C.c_int32), r.size
-        fn = lib().pahq_acdc_sweep_sender_policy if sender_policy else lib().pahq_acdc_sweep
+        fn = lib().pahq_acdc_sweep_sender_policy if sender_policy else \
+            (lib().pahq_acdc_sweep_resume if resume else lib().pahq_acdc_sweep)
         _chk(fn(self.h, C.c_float(tau), rp, rn, _ptr(kept, C.c_uint8), C.byref(n_evals), trace, cap), "pahq_acdc_sweep")
         n = min(n_evals.value, cap)
         tr = np.ctypeslib.as_array(trace)[:n].copy() if n else np.zeros(0, dtype=np.dtype(TraceRec))

@@ -697,13 +697,22 @@ int pahq_eval_current(pahq_model* M, int32_t receiver, float* kl_out) {
 }
 
 static int sweep_impl(pahq_model* M, float tau, const int32_t* receivers, int32_t n_receivers, uint8_t* kept,
-                      int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap);
+                      int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap, bool from_current = false);
 
 int pahq_acdc_sweep(pahq_model* M, float tau, const int32_t* receivers, int32_t n_receivers, uint8_t* kept,
                     int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap) {
   if (!M) return PAHQ_EINVAL;
   const std::vector<uint8_t> before = M->removed;       // a failed sweep leaves the removed set as it found it
   int rc = sweep_impl(M, tau, receivers, n_receivers, kept, n_evals, trace, trace_cap);
+  if (rc != PAHQ_OK) M->removed = before;
+  return rc;
+}
+
+int pahq_acdc_sweep_resume(pahq_model* M, float tau, const int32_t* receivers, int32_t n_receivers, uint8_t* kept,
+                           int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap) {
+  if (!M) return PAHQ_EINVAL;
+  const std::vector<uint8_t> before = M->removed;
+  int rc = sweep_impl(M, tau, receivers, n_receivers, kept, n_evals, trace, trace_cap, true);
   if (rc != PAHQ_OK) M->removed = before;
   return rc;
 }
@@ -724,14 +733,21 @@ int pahq_acdc_sweep_grid(pahq_model* M, const float* taus, int32_t n_taus, const
 }
 
 static int sweep_impl(pahq_model* M, float tau, const int32_t* receivers, int32_t n_receivers, uint8_t* kept,
-                      int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap) {
+                      int64_t* n_evals, pahq_trace_rec* trace, int64_t trace_cap, bool from_current) {
   if (!M || n_receivers < 0 || (n_receivers > 0 && !receivers) || trace_cap < 0 || (trace_cap > 0 && !trace)) return PAHQ_EINVAL;
   if (tau != tau) return PAHQ_EINVAL;
   if (!M->has_cache) return PAHQ_ESTATE;
   const GraphDims& g = M->g;
   std::vector<int> order;
   if (!sweep_order(g, receivers, n_receivers, order)) return PAHQ_EINVAL;
-  std::fill(M->removed.begin(), M->removed.end(), 0);
+  if (!from_current) std::fill(M->removed.begin(), M->removed.end(), 0);
+  else {
+    // a resumed sweep decides receivers whose edges are all still kept
+    for (int v : order) {
+      const uint8_t* row = M->removed.data() + M->edge_off[v];
+      for (int s = 0, n_up = g.n_upstream(v); s < n_up; s++) if (row[s]) return PAHQ_ESTATE;
+    }
+  }
   int64_t evals = 0;
   for (size_t oi = 0; oi < order.size(); oi++) {
     const int v = order[oi];
