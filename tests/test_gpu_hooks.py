@@ -72,6 +72,18 @@ def test_exact_matrix_product_on_codes(cfg2_model, m, n, k):
     assert (got2 == ex2).all()
 
 
+@pytest.mark.parametrize("m,n,k", [(8192, 512, 128), (8300, 500, 256), (8200, 260, 768), (9000, 400, 512)])
+def test_exact_matrix_product_large_problems(cfg2_model, m, n, k):
+    """Problems of 8192 rows and more take the 256 x 128 kernel with three LDS stages: full and ragged tiles in both
+    directions, one and several K slabs."""
+    rng = np.random.default_rng(m + n + k)
+    a, w = random_codes(rng, m, k), random_codes(rng, n, k)
+    got = cfg2_model.gemm_codes(a, w).astype(np.float64)
+    exact, mag = exact_and_scale(a, w)
+    err = np.abs(got - exact)
+    assert (err <= k * 2.0 ** -24 * mag).all(), np.argwhere(err > k * 2.0 ** -24 * mag)[:4]
+
+
 def dominant_product_codes(m, n, k):
     """Per sum one product 448 * 448 and k - 1 products 0.125 * 1 (2^-20.6 of it): the exact total,
     200704 + (k - 1) / 8, and every partial sum are binary32 numbers for k <= 2048."""
