@@ -197,3 +197,34 @@ def test_all_fp32_refuses_host_residency():
     shape, w, clean, corrupt = workloads.make("mid_hi")
     with pytest.raises(P.PahqError):
         P.Model(shape, w, clean.shape[0], clean.shape[1], precision=P.ALL_FP32, fp32_on_host=True)
+
+
+def test_config3_shape_edge_lists_and_restricted_sweep():
+    """The GPT-2-small shape: a layer's edge list and a sweep over the output node and the two top layers, bit for bit
+    against the resident model, with every head's weights arriving ahead of its use."""
+    import synth
+    import paper_2510_23264_amd as P
+    shape, w, clean, corrupt, spec = synth.make_workload("cfg3")
+    B, S = spec["B"], spec["S"]
+    L, H = shape.n_layers, shape.n_heads
+    a = P.Model(shape, w, B, S, max_batch_edges=32)
+    b = P.Model(shape, w, B, S, max_batch_edges=32, fp32_on_host=True)
+    try:
+        assert a.workspace_bytes - b.workspace_bytes > 300e6          # the fp32 matrix masters less the slots and the staging buffer
+        for gm in (a, b):
+            gm.clean_cache(clean, corrupt)
+        per_layer = 3 * H + 1
+        recvs = list(range((L - 1) * per_layer, L * per_layer))[::-1]
+        rr = np.concatenate([np.full(P.n_upstream(a.cfg, r), r, np.int32) for r in recvs])[::3]
+        ss = np.concatenate([np.arange(P.n_upstream(a.cfg, r), dtype=np.int32) for r in recvs])[::3]
+        b.prefetch_heads(L - 1, range(H))
+        assert np.array_equal(bits(a.eval_edge_list(rr, ss)), bits(b.eval_edge_list(rr, ss)))
+        assert b.transfer_stats()["demand_transfers"] == 0
+        top = np.arange((L - 2) * per_layer, L * per_layer + 1, dtype=np.int32)
+        ka, na, ta = a.acdc_sweep(1e-4, receivers=top)
+        kb, nb, tb = b.acdc_sweep(1e-4, receivers=top)
+        assert na == nb and np.array_equal(ka, kb) and ta.tobytes() == tb.tobytes()
+        st = b.transfer_stats()
+        assert st["demand_transfers"] <= H and st["transfers_ahead"] >= H, st
+    finally:
+        a.close(); b.close()
