@@ -185,17 +185,21 @@ class Acdc:
             return True
         return any(not removed[r, s] for r in self.g.receivers_downstream_of(s))
 
-    def sweep(self, tau, receivers=None, brute=False, progress=None):
+    def sweep(self, tau, receivers=None, brute=False, progress=None, start=None):
         """One reverse-topological ACDC pass.
 
         receivers: restrict evaluation to these receiver ids (others keep all
         their in-edges and are not visited); None = all.
+        start: removed matrix to begin from instead of the empty one (the
+        state an interrupted pass had reached: the pass decides receiver by
+        receiver, each decision given all earlier ones, so that state is the
+        removed set alone).
         Returns (removed matrix, trace).  trace rows:
         (receiver, sender, kl_new, kl_cur_before, removed?) for evaluated
         edges, in evaluation order.
         """
         g = self.g
-        removed = g.empty_removed()
+        removed = g.empty_removed() if start is None else np.array(start, dtype=bool, copy=True)
         trace = []
         order = range(g.n_receivers - 1, -1, -1) if receivers is None else sorted(receivers, reverse=True)
         ev = self.kl_brute if brute else self.kl_fast

@@ -271,6 +271,20 @@ def test_sweep_semantics_on_tiny_model():
     assert all(abs(kc) == 0.0 for *_, kc, _ in t_none)
 
 
+def test_interrupted_sweep_continues_from_its_removed_set():
+    """The pass decides receiver by receiver, every decision given all earlier ones (Appendix "Preliminaries", pruning
+    rule): cut anywhere between two receivers, the removed set reached so far is the whole state."""
+    m, w, clean, corrupt = tiny(TINY_GELU, B=4)
+    g = m.g
+    a = Acdc(m, clean, corrupt, MODE_PAHQ)
+    for tau in (1e-3, 1e-5):
+        full, t_full = a.sweep(tau)
+        for cut in (g.n_receivers - 1, g.n_receivers // 2, 1):
+            upper, t1 = a.sweep(tau, receivers=range(cut, g.n_receivers))
+            both, t2 = a.sweep(tau, receivers=range(0, cut), start=upper)
+            assert (both == full).all() and t1 + t2 == t_full, (tau, cut)
+
+
 def test_sequence_order_does_not_matter():
     m, w, clean, corrupt = tiny(TINY_LLAMA, B=4)
     g = m.g
