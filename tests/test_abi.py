@@ -73,6 +73,18 @@ def test_argument_validation_without_a_device():
     assert p.workspace_bytes(cfg, 8, 16) > 0
     # the all-fp32 mode needs room for unquantised rows of every receiver group
     assert p.workspace_bytes(p.Config.from_shape(s, precision=p.ALL_FP32), 8, 16) > p.workspace_bytes(cfg, 8, 16)
+    # fp32 masters on the host: a smaller workspace for deep models, refused with the all-fp32 mode and for other values
+    deep = synth.make_shape("cfg3")
+    assert p.workspace_bytes(p.Config.from_shape(deep, fp32_on_host=True), 8, 16) < p.workspace_bytes(p.Config.from_shape(deep), 8, 16)
+    with pytest.raises(p.PahqError) as e:
+        p.workspace_bytes(p.Config.from_shape(s, precision=p.ALL_FP32, fp32_on_host=True), 8, 16)
+    assert e.value.code == -6
+    wrong = p.Config.from_shape(s); wrong.fp32_residency = 2
+    with pytest.raises(p.PahqError) as e:
+        p.workspace_bytes(wrong, 8, 16)
+    assert e.value.code == -1
+    assert p.lib().pahq_prefetch_heads(None, 0, 1) == -1 and p.lib().pahq_get_transfer_stats(None, None) == -1
+    assert p.lib().pahq_acdc_sweep_resume(None, C.c_float(0.1), None, 0, None, None, None, 0) == -1
     assert p.lib().pahq_strerror(-3) == b"workspace too small"
     # null handles are rejected, not dereferenced
     assert p.lib().pahq_clean_cache(None, None, None) == -1
