@@ -180,7 +180,7 @@ int pahq_node_of_receiver(const pahq_config*, int32_t receiver, int32_t* sender_
 /* Bytes of device workspace pahq_init_model needs for batches of B sequences
  * of S tokens (paper, Appendix "Integration with ACDC": all low-precision
  * weights resident on the device; here the fp32 masters and every activation
- * cache are resident too, unless fp32_residency says otherwise).  S <= 64 (S <= 32 for d_head = 128), d_head one of
+ * cache are resident too, unless fp32_residency says otherwise).  S <= 128, d_head one of
  * 16, 32, 64, 128, d_model a multiple of 64 up to 4096, at most 64 heads, d_mlp a
  * multiple of 4: PAHQ_EUNSUPPORTED otherwise. */
 int pahq_workspace_bytes(const pahq_config*, int32_t B, int32_t S, size_t* out);
@@ -360,6 +360,11 @@ int pahq_quantize_rows_site(pahq_model*, int32_t site, const float* x, int32_t r
  * (k contiguous, a multiple of 128), out: host [m][n].  PAHQ_ENOMEM when the model's batch buffers cannot stage
  * the problem, PAHQ_ESTATE in the all-fp32 mode. */
 int pahq_gemm_codes(pahq_model*, const uint8_t* a, const uint8_t* w, int32_t m, int32_t n, int32_t k, float* out);
+/* Attention has two kernels: one wavefront per sequence and head with the whole sequence in registers (S <= 64, S <= 32
+ * for d_head = 128), and one wavefront per tile of 16 queries for longer sequences (S <= 128).  form = 1 takes the
+ * second at every length (0, the default: only where the first does not apply).  Both add the same products in the
+ * same order, so results do not depend on it (a test hook). */
+int pahq_set_attention_form(pahq_model*, int32_t form);
 /* Last-position logits [B][vocab]: PAHQ_LOGITS_CLEAN / PAHQ_LOGITS_CORRUPT of the cached runs;
  * PAHQ_LOGITS_REF of the clean run under the precision set of the head investigated last (the reference
  * distribution its candidates were scored against; PAHQ_ESTATE when no head's state is current). */

@@ -93,6 +93,7 @@ def lib():
             "pahq_set_removed": [C.c_void_p, u8p], "pahq_get_removed": [C.c_void_p, u8p],
             "pahq_set_dead_node_skipping": [C.c_void_p, C.c_int32],
             "pahq_prefetch_heads": [C.c_void_p, C.c_int32, C.c_uint64],
+            "pahq_set_attention_form": [C.c_void_p, C.c_int32],
             "pahq_get_transfer_stats": [C.c_void_p, i64p],
             "pahq_get_weight_q": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, u8p, f32p],
             "pahq_quantize_rows": [C.c_void_p, f32p, C.c_int32, C.c_int32, u8p, f32p],
@@ -326,6 +327,9 @@ class Model:
 
     def set_dead_node_skipping(self, on):
         _chk(lib().pahq_set_dead_node_skipping(self.h, 1 if on else 0), "pahq_set_dead_node_skipping")
+
+    def set_attention_form(self, form):
+        _chk(lib().pahq_set_attention_form(self.h, int(form)), "pahq_set_attention_form")
 
     def prefetch_heads(self, layer, heads):
         """heads: iterable of head indices of `layer` whose fp32 weights will be needed next (host residency)."""

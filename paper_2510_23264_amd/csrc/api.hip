@@ -40,7 +40,7 @@ int check_supported(const pahq_config* c, int B, int S) {
   if (c->d_head != 16 && c->d_head != 32 && c->d_head != 64 && c->d_head != 128) return PAHQ_EUNSUPPORTED;
   if (c->pos == PAHQ_POS_ROPE && (c->d_head & 1)) return PAHQ_EUNSUPPORTED;
   if (c->d_mlp > 0 && c->act == PAHQ_ACT_NONE) return PAHQ_EUNSUPPORTED;
-  if (B < 1 || S < 1 || S > 64 || (S > 32 && c->d_head == 128)) return PAHQ_EUNSUPPORTED;      // the attention kernel's tiles of positions
+  if (B < 1 || S < 1 || S > 128) return PAHQ_EUNSUPPORTED;            // the attention kernels' tiles of positions
   if (c->pos == PAHQ_POS_LEARNED && S > c->n_ctx) return PAHQ_EINVAL;
   return PAHQ_OK;
 }
@@ -122,7 +122,7 @@ size_t layout(pahq_model* M, char* base) {
   M->lnf_g = b.take<float>(d); M->lnf_b = b.take<float>(d);
   M->W_U = on_host ? nullptr : b.take<float>(d * V); M->b_U = b.take<float>(V + 4);     // the GEMM epilogue reads bias in groups of four
   M->zeros_d = b.take<float>(d);
-  M->rope_tab = M->cfg.pos == PAHQ_POS_ROPE ? b.take<float>((size_t)64 * dh) : nullptr;    // the attention kernel's (up to four) 16-position tiles
+  M->rope_tab = M->cfg.pos == PAHQ_POS_ROPE ? b.take<float>((size_t)128 * dh) : nullptr;   // the attention kernels' (up to eight) 16-position tiles
   M->bqkv = b.take<float>(L * 3 * H * dh);
   M->qkv_codes = b.take<uint8_t>(L * 3 * H * dh * Kd); M->qkv_scale = b.take<float>(L * 3 * H);
   M->o_codes = b.take<uint8_t>(L * H * d * Kh); M->o_scale = b.take<float>(L * H);
@@ -447,7 +447,7 @@ int pahq_init_model(const pahq_config* c, const pahq_weights* w, int32_t B, int3
     for (int cc = 0; cc < 3; cc++)
       if (hipMemcpyAsync(M->bqkv + (l * 3 + cc) * H * dh, bsrc[cc] + l * H * dh, H * dh * sizeof(float),
                          hipMemcpyDeviceToDevice, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
-  if (M->rope_tab && launch_rope_table(M->rope_tab, 64, (int)dh, c->rope_theta, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
+  if (M->rope_tab && launch_rope_table(M->rope_tab, 128, (int)dh, c->rope_theta, M->stream) != hipSuccess) return fail(PAHQ_EHIP);
   // e4m3 codes + scales of every weight slice.  With the masters in the workspace a class is quantised where it lies;
   // with host residency it passes through the staging buffer a layer at a time (quantise_class ends with a
   // synchronisation, so the buffer is free again when it returns).
@@ -1138,6 +1138,12 @@ int pahq_get_sender_output(pahq_model* M, int32_t which, int32_t sender, float* 
 int pahq_get_counters(pahq_model* M, int64_t out[3]) {
   if (!M || !out) return PAHQ_EINVAL;
   out[0] = M->counters[0]; out[1] = M->counters[1]; out[2] = M->counters[2];
+  return PAHQ_OK;
+}
+
+int pahq_set_attention_form(pahq_model* M, int32_t form) {
+  if (!M || (form != 0 && form != 1)) return PAHQ_EINVAL;
+  M->attn_form = form;
   return PAHQ_OK;
 }
 

@@ -8,7 +8,7 @@ namespace pahq {
 
 // Causal attention on the fp32 matrix cores, one wavefront per (instance,
 // sequence, head), no LDS.  S <= 64 is covered by ST = 1 .. 4 tiles of 16
-// positions; lane = 16*g + i.
+// positions (longer sequences: attention_qtile_k below); lane = 16*g + i.
 //   scores  S^T = K Q^T with V_MFMA_F32_16X16X4_F32: lane (i, g) feeds row i of a
 //           K tile and of a Q tile (its own d_head/4 consecutive columns, the
 //           same k order for both operands) and receives S[query i][key 4g + r].
@@ -251,6 +251,158 @@ __global__ __launch_bounds__(256) void attention_mfma_k(AttnSrc src, uint8_t* zc
   }
 }
 
+// The same attention for longer sequences: one wavefront per (instance, sequence, head, tile of 16 queries).  The
+// whole-sequence kernel above keeps every tile of q, k, the scores and v of a sequence in registers, which ends at
+// four tiles (two with 128-wide heads); here a wave holds one query tile and its row of score tiles (up to STM key
+// tiles) and fetches the key and value tiles one after the other.  Per output element the products are formed and
+// added in the order of the kernel above -- scores over the head's columns in ascending order, softmax over the key
+// tiles then the lane's four keys then the four lanes, P V over key tiles and keys ascending -- so that for a
+// sequence both kernels accept they give the same bits.
+template <int STM, int DH, bool ROPE>
+__global__ __launch_bounds__(256) void attention_qtile_k(AttnSrc src, uint8_t* zcodes, long long zc_is, float* zscale,
+                                                          long long zs_is, float* zf32, long long zf_is,
+                                                          unsigned long long f32_mask, unsigned long long dead_mask,
+                                                          int n_pairs, int B, int S, int H, int ldz, const float2* rope_tab) {
+  constexpr int CH = DH / 4, NT = DH / 16;
+  const int ST = (S + 15) >> 4;
+  const int job = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (job >= n_pairs * ST) return;
+  const int a = job % ST, pair = job / ST;                             // query tile, (instance, sequence, head)
+  const int hl = pair % src.n_heads, sb = pair / src.n_heads;
+  const int h = src.h0 + hl;
+  if ((dead_mask >> h) & 1ull) return;
+  const int inst = sb / B, b = sb % B;
+  const int lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
+  const float* qb = src.q + inst * src.q_is + (long long)b * S * src.q_ld + hl * src.head_cols;
+  const float* kb = src.k + inst * src.k_is + (long long)b * S * src.k_ld + hl * src.head_cols;
+  const float* vb = src.v + inst * src.v_is + (long long)b * S * src.v_ld + hl * src.head_cols;
+  // row `pos` of a matrix: this lane's CH consecutive columns, rotated when the model has rotary positions
+  auto load_rows = [&](float (&x)[CH], const float* base, int ld, int pos) {
+    const float* row = base + (long long)pos * ld + CH * g;
+#pragma unroll
+    for (int c = 0; c < CH; c += 4) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (pos < S) v = *(const float4*)(row + c);
+      x[c] = v.x; x[c + 1] = v.y; x[c + 2] = v.z; x[c + 3] = v.w;
+    }
+    if (ROPE) {
+#pragma unroll
+      for (int c = 0; c < CH; c++) {
+        const int col = (CH * g + c) % (DH / 2);
+        const float2 t2 = rope_tab[pos * (DH / 2) + col];
+        const float px = __shfl_xor(x[c], 32, 64);
+        const float sg = (g < 2) ? -t2.y : t2.y;
+        x[c] = x[c] * t2.x + px * sg;
+      }
+    }
+  };
+  float q[CH];
+  load_rows(q, qb, src.q_ld, 16 * a + i);
+  v4f_a sc[STM];
+  const float scl = 1.0f / sqrtf((float)DH);
+#pragma unroll
+  for (int bk = 0; bk < STM; bk++) {
+    if (bk > a) continue;                                              // (wave-uniform)
+    float kk[CH];
+    load_rows(kk, kb, src.k_ld, 16 * bk + i);
+    v4f_a acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < CH; c++) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(kk[c], q[c], acc, 0, 0, 0);
+    sc[bk] = acc;
+  }
+  {
+    const int qpos = 16 * a + i;
+    float mx = -3.0e38f;
+#pragma unroll
+    for (int bk = 0; bk < STM; bk++) {
+      if (bk > a) continue;
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int kpos = 16 * bk + 4 * g + r;
+        const float v = sc[bk][r] * scl;
+        const bool ok = kpos <= qpos && kpos < S;
+        sc[bk][r] = ok ? v : -3.0e38f;
+        if (ok) mx = fmaxf(mx, v);
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float sum = 0.f;
+#pragma unroll
+    for (int bk = 0; bk < STM; bk++) {
+      if (bk > a) continue;
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const float e = (sc[bk][r] > -1.0e38f) ? expf(sc[bk][r] - mx) : 0.f;
+        sc[bk][r] = e;
+        sum += e;
+      }
+    }
+    sum += __shfl_xor(sum, 16, 64);
+    sum += __shfl_xor(sum, 32, 64);
+    const float rs = (sum > 0.f) ? 1.0f / sum : 0.f;
+#pragma unroll
+    for (int bk = 0; bk < STM; bk++) {
+      if (bk > a) continue;
+#pragma unroll
+      for (int r = 0; r < 4; r++) sc[bk][r] *= rs;
+    }
+  }
+  v4f_a z[NT];
+#pragma unroll
+  for (int t = 0; t < NT; t++) z[t] = (v4f_a){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int bk = 0; bk < STM; bk++) {
+    if (bk > a) continue;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      const int kpos = 16 * bk + 4 * g + r;
+      const float* row = vb + (long long)kpos * src.v_ld + i;
+#pragma unroll
+      for (int t = 0; t < NT; t++) {
+        const float vv = (kpos < S) ? row[16 * t] : 0.f;
+        z[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(sc[bk][r], vv, z[t], 0, 0, 0);
+      }
+    }
+  }
+  const bool f32 = (f32_mask >> h) & 1ull;
+  const int f32_slot = __popcll(f32_mask & ((1ull << h) - 1ull)), f32_n = __popcll(f32_mask);
+  // lane (i, g) holds Z[query 16a + 4g + rr][16t + i]
+#pragma unroll
+  for (int rr = 0; rr < 4; rr++) {
+    const int pos = 16 * a + 4 * g + rr;
+    const long long tok = (long long)b * S + pos;
+    if (f32) {
+      if (pos < S) {
+        float* o = zf32 + inst * zf_is + (tok * f32_n + f32_slot) * DH + i;
+#pragma unroll
+        for (int t = 0; t < NT; t++) o[16 * t] = z[t][rr];
+      }
+    } else {
+      float am = 0.f;
+#pragma unroll
+      for (int t = 0; t < NT; t++) am = fmaxf(am, fabsf(z[t][rr]));
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) am = fmaxf(am, __shfl_xor(am, o, 64));
+      const float scale = (am == 0.f || src.qbits == 16) ? 1.0f : am / q_top(src.qbits);
+      const float inv = 1.0f / scale;
+      if (pos < S) {
+        if (src.qbits == 16) {
+          uint8_t* o = zcodes + inst * zc_is + (tok * H + h) * ldz + 2 * i;
+#pragma unroll
+          for (int t = 0; t < NT; t++) *(uint16_t*)(o + 32 * t) = (uint16_t)bf16_rne(z[t][rr]);
+          if (i == 0) zscale[inst * zs_is + tok * H + h] = 1.0f;
+        } else {
+          uint8_t* o = zcodes + inst * zc_is + (tok * H + h) * ldz + i;
+#pragma unroll
+          for (int t = 0; t < NT; t++) o[16 * t] = (uint8_t)q_encode(z[t][rr] * inv, src.qbits);
+          if (i == 0) zscale[inst * zs_is + tok * H + h] = scale;
+        }
+      }
+    }
+  }
+}
+
 // tab[pos][col] = (cos, sin) of pos * theta^(-2 col / d_head) for col < d_head / 2: the angle in fp64, rounded
 // once, as the attention kernel used to compute it per element
 __global__ void rope_table_k(float2* tab, int n_pos, int dh, float theta) {
@@ -271,8 +423,22 @@ hipError_t launch_attention(const AttnSrc& src, uint8_t* zcodes, long long zc_is
                             long long zs_is, float* zf32, long long zf_is, unsigned long long f32_mask, unsigned long long dead_mask, int n_inst, int B, int S,
                             int H, int dh, int ldz, int rope, const float* rope_tab, hipStream_t s) {
   if (n_inst == 0) return hipSuccess;
-  if (S > 64 || (S > 32 && dh == 128)) return hipErrorInvalidValue;
+  if (S > 128) return hipErrorInvalidValue;
   int n_pairs = n_inst * B * src.n_heads;
+  if (src.form == 1 || S > 64 || (S > 32 && dh == 128)) {
+    // one wave per tile of 16 queries, up to eight key tiles
+    const long long jobs = (long long)n_pairs * ((S + 15) / 16);
+    if (jobs > 0x7fffffffLL) return hipErrorInvalidValue;
+    dim3 qgrid((unsigned)((jobs + 3) / 4));
+#define ATQ(DH_) do { if (rope) hipLaunchKernelGGL((attention_qtile_k<8, DH_, true>), qgrid, dim3(256), 0, s, src, zcodes, zc_is, zscale, zs_is, zf32, \
+                                                  zf_is, f32_mask, dead_mask, n_pairs, B, S, H, ldz, (const float2*)rope_tab); \
+                      else hipLaunchKernelGGL((attention_qtile_k<8, DH_, false>), qgrid, dim3(256), 0, s, src, zcodes, zc_is, zscale, zs_is, zf32, \
+                                              zf_is, f32_mask, dead_mask, n_pairs, B, S, H, ldz, (const float2*)rope_tab); } while (0)
+    if (dh == 16) ATQ(16); else if (dh == 32) ATQ(32); else if (dh == 64) ATQ(64); else if (dh == 128) ATQ(128);
+    else return hipErrorInvalidValue;
+#undef ATQ
+    return hipGetLastError();
+  }
   dim3 grid((n_pairs + 3) / 4);
   // the staged form (one tile, d_head 64, no rotation) collects one-byte codes in LDS: bfloat16 outputs take the plain form
 #define ATT0(ST_, DH_, R_, G_) hipLaunchKernelGGL((attention_mfma_k<ST_, DH_, R_, G_>), grid, dim3(256), 0, s, src, zcodes, \

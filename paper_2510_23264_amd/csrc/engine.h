@@ -86,6 +86,7 @@ struct pahq_model {
   int qbits;                              // grid of the low-precision operands: 8 = E4M3, 4 = 4-bit round-to-nearest
   bool nb16;                              // the MLP matrices and the unembedding multiply bfloat16 operands instead
   int Kd_o, Km_o;                         // bytes of a d_model / d_mlp row of those operands (= Kd, Km unless nb16)
+  int attn_form = 0;                      // 1: the query-tile attention kernel at every sequence length (AttnSrc.form)
   bool skip_dead;                         // passes over a pruned graph leave out nodes no kept path connects to the output
   bool all_f32;                           // PAHQ_ALL_FP32: every matrix product on the fp32 masters, no quantiser
   int f32_groups;                         // receiver-input groups of a layer that may need fp32 rows (per instance)

@@ -873,7 +873,7 @@ int run_pass(pahq_model* M, const PassArgs& a, const RecvPlan* plan) {
       }
   }
   for (GroupDesc& gd : b.groups) if (!gd.qbits) gd.qbits = M->qbits;      // groups of bfloat16 blocks have said 16
-  for (AttnSrc& as : b.asrcs) as.qbits = M->qbits;
+  for (AttnSrc& as : b.asrcs) { as.qbits = M->qbits; as.form = M->attn_form; }
   // ---- upload the descriptor tables
   Arena& A = M->arena;
   int slot = A.next;

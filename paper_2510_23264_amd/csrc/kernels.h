@@ -156,7 +156,7 @@ hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const Head
 // Heads whose bit is set: z written unquantised to zf32 [inst][T][nf][dh], nf = number of set bits, a head's place
 // = number of set bits below its own.
 struct AttnSrc {
-  const float* q; long long q_is; int q_ld; int pad0_;
+  const float* q; long long q_is; int q_ld; int form;     // form: 1 = the query-tile kernel also where the whole-sequence kernel applies (0: the launcher chooses)
   const float* k; long long k_is; int k_ld; int pad1_;
   const float* v; long long v_is; int v_ld; int pad2_;
   int n_heads, h0, head_cols, qbits;    // qbits: grid of the output codes (device_util.h, q_encode)

@@ -1,6 +1,7 @@
-"""Sequences of 33 to 64 positions (three and four 16-position tiles in the attention kernel) against the oracle:
-cached runs element by element in the all-fp32 mode, per-edge values at the binding bound under mixed precision,
-learned and rotary positions."""
+"""Sequences of 33 to 128 positions against the oracle: three and four 16-position tiles in the whole-sequence
+attention kernel (up to 64 positions), the query-tile kernel beyond (and from 33 positions with 128-wide heads).
+Cached runs element by element in the all-fp32 mode, per-edge values at the binding bound under mixed precision,
+learned and rotary positions; and the two kernels against each other, bit for bit, where both apply."""
 import os
 import sys
 import numpy as np
@@ -19,13 +20,16 @@ pytestmark = pytest.mark.gpu
 
 GPT = dict(n_layers=2, n_heads=3, d_head=32, d_model=64, d_mlp=128, vocab=300)
 LLAMA = dict(n_layers=2, n_heads=2, d_head=64, d_model=128, d_mlp=192, vocab=257, norm=1, act=2, pos=1, norm_eps=1e-6)
+WIDE = dict(n_layers=2, n_heads=1, d_head=128, d_model=128, d_mlp=192, vocab=257, norm=1, act=2, pos=1, norm_eps=1e-6)
+KINDS = {"gpt": (GPT, 0.25), "llama": (LLAMA, 0.12), "wide": (WIDE, 0.12)}
 
 
-@pytest.mark.parametrize("kind,S", [("gpt", 33), ("gpt", 41), ("gpt", 48), ("gpt", 64), ("llama", 40), ("llama", 64)])
+@pytest.mark.parametrize("kind,S", [("gpt", 33), ("gpt", 41), ("gpt", 48), ("gpt", 64), ("llama", 40), ("llama", 64),
+                                    ("gpt", 65), ("gpt", 100), ("gpt", 128), ("llama", 81), ("llama", 128), ("wide", 33), ("wide", 72)])
 def test_long_sequences(kind, S):
     import paper_2510_23264_amd as P
-    shape = ModelShape(n_ctx=S, **(GPT if kind == "gpt" else LLAMA))
-    w = synth.make_weights(shape, 11, std=0.25 if kind == "gpt" else 0.12, affine_std=0.1)
+    shape = ModelShape(n_ctx=S, **KINDS[kind][0])
+    w = synth.make_weights(shape, 11, std=KINDS[kind][1], affine_std=0.1)
     clean, corrupt = synth.make_tokens(shape.vocab, 3, S, "uniform", 5, False, 13)
     B = clean.shape[0]
     # nothing quantised: logits of the cached clean run against a textbook forward
@@ -41,13 +45,15 @@ def test_long_sequences(kind, S):
     try:
         g = pr.g
         cases, got = [], []
-        for i, r in enumerate((g.OUT, g.headin(1, 1, 0), g.headin(1, 0, 2), g.mlpin(0), g.headin(0, 0, 1))):
+        for i, r in enumerate((g.OUT, g.headin(1, shape.n_heads - 1, 0), g.headin(1, 0, 2), g.mlpin(0), g.headin(0, 0, 1))):
             R = g.empty_removed() if i % 2 == 0 else random_removed(g, 0.4, 51 + i, from_receiver=r)
             senders = np.arange(g.n_upstream(r), dtype=np.int32)
             pr.gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
             got.append(np.concatenate([[pr.gm.eval_current(r)], pr.gm.eval_edges(r, senders)]))
             cases.append((r, R, senders))
-        res = kl_with_spread(pr.om, clean, corrupt, MODE_PAHQ, cases, seeds=3)
+        # the spread a moved code leaves is estimated from perturbed oracle runs: a long sequence has many rows in which a
+        # rare move has a large effect (every later position of the sequence attends to the row), and three runs miss it
+        res = kl_with_spread(pr.om, clean, corrupt, MODE_PAHQ, cases, seeds=3 if S <= 64 else 12)
         want = np.concatenate([[r["kl_current"]] + list(r["kl_new"]) for r in res])
         sigma = np.concatenate([[r["sigma_current"]] + list(r["sigma_new"]) for r in res])
         worst = check_kl_cases(np.concatenate(got), want, sigma, what="%s S=%d" % (kind, S))
@@ -57,14 +63,47 @@ def test_long_sequences(kind, S):
         pr.close()
 
 
+def bits(x):
+    return np.asarray(x, dtype=np.float32).view(np.uint32)
+
+
+@pytest.mark.parametrize("kind,S", [("gpt", 16), ("gpt", 41), ("gpt", 64), ("llama", 24), ("llama", 64), ("wide", 32)])
+@pytest.mark.parametrize("low_bits", [8, 16])
+def test_both_attention_kernels_give_the_same_bits(kind, S, low_bits):
+    """Where the whole-sequence kernel applies, the query-tile kernel (forced by the hook) must reproduce it bit for
+    bit: cached sender outputs and logits, per-edge values on the empty and on a pruned state."""
+    import paper_2510_23264_amd as P
+    if low_bits == 16 and kind != "llama":
+        pytest.skip("bfloat16 heads need d_head 32 or 64 and a head count that fills 64-column blocks")
+    shape = ModelShape(n_ctx=S, **KINDS[kind][0])
+    w = synth.make_weights(shape, 11, std=KINDS[kind][1], affine_std=0.1)
+    clean, corrupt = synth.make_tokens(shape.vocab, 3, S, "uniform", 5, False, 13)
+    from oracle.graph import Graph
+    g = Graph(shape.n_layers, shape.n_heads, shape.d_mlp > 0)
+    gm = P.Model(shape, w, clean.shape[0], S, max_batch_edges=4, low_bits=low_bits)
+    try:
+        out = []
+        for form in (0, 1):
+            gm.set_attention_form(form)
+            gm.clean_cache(clean, corrupt)
+            res = [gm.get_logits(0), gm.get_logits(1), gm.get_sender_output(0, g.n_senders - 1), gm.get_sender_output(1, 1)]
+            for i, r in enumerate((g.OUT, g.headin(1, shape.n_heads - 1, 1), g.headin(0, 0, 2), g.mlpin(0))):
+                R = g.empty_removed() if i % 2 == 0 else random_removed(g, 0.4, 7 + i, from_receiver=r)
+                gm.set_removed(g.removed_to_flat(R).astype(np.uint8))
+                res.append(gm.eval_edges(r, np.arange(g.n_upstream(r), dtype=np.int32)))
+            out.append(res)
+        for x, y in zip(*out):
+            assert np.array_equal(bits(x), bits(y)), (kind, S, low_bits)
+    finally:
+        gm.close()
+
+
 def test_limits():
     import paper_2510_23264_amd as P
-    shape = ModelShape(n_ctx=65, **GPT)
+    shape = ModelShape(n_ctx=129, **GPT)
     with pytest.raises(P.PahqError) as e:
-        P.workspace_bytes(P.Config.from_shape(shape), 2, 65)
+        P.workspace_bytes(P.Config.from_shape(shape), 2, 129)
     assert e.value.code == -6
-    wide = ModelShape(n_layers=1, n_heads=1, d_head=128, d_model=128, d_mlp=0, vocab=50, n_ctx=40, act=0)
-    with pytest.raises(P.PahqError) as e:
-        P.workspace_bytes(P.Config.from_shape(wide), 2, 40)      # 128-wide heads: up to 32 positions
-    assert e.value.code == -6
-    assert P.workspace_bytes(P.Config.from_shape(wide), 2, 32) > 0
+    assert P.workspace_bytes(P.Config.from_shape(shape), 2, 128) > 0
+    wide = ModelShape(n_layers=1, n_heads=1, d_head=128, d_model=128, d_mlp=0, vocab=50, n_ctx=128, act=0)
+    assert P.workspace_bytes(P.Config.from_shape(wide), 2, 128) > 0
