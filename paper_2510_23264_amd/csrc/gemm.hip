@@ -562,7 +562,8 @@ __global__ __launch_bounds__(512, 1) void gemm_p_k(const GemmProb* probs) {
         float4 val = make_float4(acc[i][0][r] * s2, acc[i][1][r] * s2, acc[i][2][r] * s2, acc[i][3][r] * s2);
         float4 v = val;
         if (P.bias) { v.x += bias.x; v.y += bias.y; v.z += bias.z; v.w += bias.w; }
-        if (P.act == 1) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
+        // (no activation here: problems that ask for one are refused for this kernel's sizes by gemm8_prob_ok; the code
+        // of 64 inlined GELUs cost every tile's epilogue 1.5-2 % of a K = 768 product although no problem used it)
         if (P.add) { v.x += addv[i][r].x; v.y += addv[i][r].y; v.z += addv[i][r].z; v.w += addv[i][r].w; }
         gstore4_nt(P.C + inst[i][r] * P.c_is + roff[i][r], v);
         if (P.aux) {

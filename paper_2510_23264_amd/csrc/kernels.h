@@ -68,6 +68,7 @@ inline bool gemm8_prob_ok(const GemmProb& p) {
          p.aux_is % 4 == 0 && (p.wscale_block % 4 == 0 || p.wscale_block >= p.N) && a16(p.C) && a16(p.add) && a16(p.aux) && a16(p.aux_sub) &&
          a16(p.bias) && (p.N + 3) / 4 * 4 <= p.ldc && p.lda >= p.K && p.ldw >= p.K &&
          (long long)p.rpi * p.ldc < (1ll << 31) && (p.C || p.kl_part) &&
+         (p.act == 0 || p.M < 8192) &&      // the kernel of the large problems applies no activation (the path asks for none)
          (!p.kl_part || (p.kl_npart == kl_parts_per_row(p.N) && a16(p.kl_part) && a16(p.kl_ref) &&
                          (!p.kl_ref == !p.kl_ref_logz) && !p.add && !p.aux && p.act == 0));
 }
