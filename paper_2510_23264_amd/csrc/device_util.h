@@ -28,7 +28,7 @@ __device__ __forceinline__ double wave_sum_d(double v) {
 // mantissa to 3 bits on the bit pattern and re-bias the exponent (127 -> 7).
 // Below 2^-6 the grid is uniform with step 2^-9, so the code is |y| * 512
 // rounded to the nearest even integer (8 is the first normal code).
-__device__ __forceinline__ uint32_t e4m3_encode(float y) {
+__device__ __forceinline__ uint32_t e4m3_encode_bits(float y) {
   uint32_t sign = (__float_as_uint(y) >> 24) & 0x80u;
   float a = fminf(fabsf(y), 448.0f);
   uint32_t code;
@@ -41,6 +41,20 @@ __device__ __forceinline__ uint32_t e4m3_encode(float y) {
   }
   return code | sign;
 }
+// The same code from the hardware conversion (V_CVT_PK_FP8_F32: two values per instruction instead of a dozen
+// integer operations per value).  With the value clamped to +-448 first it returns e4m3_encode_bits(y) for every
+// finite binary32 pattern -- ties, the subnormal range and the sign of zero included; compared exhaustively on the
+// device -- so the kernels use it and the form above stays as the definition (and for the weights at set-up).
+__device__ __forceinline__ uint32_t e4m3_encode(float y) {
+  const float c = __builtin_amdgcn_fmed3f(y, -448.0f, 448.0f);
+  return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(c, c, 0, false) & 0xFFu;
+}
+// four values -> their codes in the four bytes of a word (byte k = code of y_k)
+__device__ __forceinline__ uint32_t e4m3_encode4(float y0, float y1, float y2, float y3) {
+  int w = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(y0, -448.0f, 448.0f), __builtin_amdgcn_fmed3f(y1, -448.0f, 448.0f), 0, false);
+  w = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(y2, -448.0f, 448.0f), __builtin_amdgcn_fmed3f(y3, -448.0f, 448.0f), w, true);
+  return (uint32_t)w;
+}
 
 // The grid a quantiser rounds to.  bits == 4: the paper's Eq. RTN-Q with N = 4 as printed -- step = max|x| / 2^(N-1),
 // integer multiples of it, round to nearest (ties to even) -- with the multiple k (|k| <= 8) stored as the E4M3
@@ -48,6 +62,10 @@ __device__ __forceinline__ uint32_t e4m3_encode(float y) {
 // Any other value: E4M3 itself (step = max|x| / 448 at the top of the grid).
 __device__ __forceinline__ float q_top(int bits) { return bits == 4 ? 8.0f : 448.0f; }
 __device__ __forceinline__ uint32_t q_encode(float y, int bits) { return e4m3_encode(bits == 4 ? rintf(y) : y); }
+__device__ __forceinline__ uint32_t q_encode4(float y0, float y1, float y2, float y3, int bits) {
+  if (bits == 4) { y0 = rintf(y0); y1 = rintf(y1); y2 = rintf(y2); y3 = rintf(y3); }
+  return e4m3_encode4(y0, y1, y2, y3);
+}
 
 // binary32 -> bfloat16 bit pattern, round to nearest, ties to even (finite input): the 16 dropped mantissa bits
 // round the kept ones up when they exceed half a unit, or equal it and the kept pattern is odd.

@@ -70,7 +70,7 @@ __global__ void quant_transpose_k(const float* w, int K, int N, const unsigned* 
     int n = n0 + r, k = k0 + threadIdx.x;
     if (n < N && k < K) {
       if (qbits == 16) *(uint16_t*)(codes + (long long)n * ldq + 2 * k) = (uint16_t)bf16_rne(tile[threadIdx.x][r]);     // ldq in bytes
-      else codes[(long long)n * ldq + k] = (uint8_t)q_encode(tile[threadIdx.x][r] * inv, qbits);
+      else codes[(long long)n * ldq + k] = (uint8_t)e4m3_encode_bits(qbits == 4 ? rintf(tile[threadIdx.x][r] * inv) : tile[threadIdx.x][r] * inv);
     }
   }
 }
@@ -233,8 +233,7 @@ __device__ __forceinline__ void emit_row(const float (&y)[MAXE], int E, int d, i
     if (VEC) {
 #pragma unroll
       for (int q = 0; q < MAXE / 4; q++) if (4 * q < E) {
-        uint32_t w = q_encode(y[4 * q] * inv, qb) | (q_encode(y[4 * q + 1] * inv, qb) << 8) |
-                     (q_encode(y[4 * q + 2] * inv, qb) << 16) | (q_encode(y[4 * q + 3] * inv, qb) << 24);
+        uint32_t w = q_encode4(y[4 * q] * inv, y[4 * q + 1] * inv, y[4 * q + 2] * inv, y[4 * q + 3] * inv, qb);
         *(uint32_t*)(o + (q * 64 + lane) * 4) = w;
       }
     } else {
@@ -632,8 +631,7 @@ __global__ __launch_bounds__(256) void hidden_quant_vec_k(const float* up, const
   for (int j = 0; j < NV; j++) {
     int e = (j * TPR + t) * 4;
     if (e < m) {
-      uint32_t w = q_encode(v[j].x * inv, qbits) | (q_encode(v[j].y * inv, qbits) << 8) | (q_encode(v[j].z * inv, qbits) << 16) |
-                   (q_encode(v[j].w * inv, qbits) << 24);
+      uint32_t w = q_encode4(v[j].x * inv, v[j].y * inv, v[j].z * inv, v[j].w * inv, qbits);
       *(uint32_t*)(o + e) = w;
     }
   }
