@@ -365,6 +365,11 @@ int pahq_gemm_codes(pahq_model*, const uint8_t* a, const uint8_t* w, int32_t m, 
  * second at every length (0, the default: only where the first does not apply).  Both add the same products in the
  * same order, so results do not depend on it (a test hook). */
 int pahq_set_attention_form(pahq_model*, int32_t form);
+/* The kernels take a value's E4M3 code from the hardware conversion; the code is defined by the round-to-nearest-even
+ * encoder on the bit pattern (Appendix "Quantization", Eq. RTN-Q on the E4M3 grid), which the weights use.  Compares
+ * the two on every finite binary32 pattern on the device: *mismatches must come back 0 (*example: one differing
+ * pattern, may be NULL).  scratch: 16 bytes of device memory, 16-byte aligned.  Needs no model. */
+int pahq_compare_encoders(void* hip_stream, void* scratch, uint64_t* mismatches, uint32_t* example);
 /* Last-position logits [B][vocab]: PAHQ_LOGITS_CLEAN / PAHQ_LOGITS_CORRUPT of the cached runs;
  * PAHQ_LOGITS_REF of the clean run under the precision set of the head investigated last (the reference
  * distribution its candidates were scored against; PAHQ_ESTATE when no head's state is current). */

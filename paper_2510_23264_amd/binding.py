@@ -106,6 +106,7 @@ def lib():
             "pahq_set_profiling_sample": [C.c_void_p, C.c_uint32, C.c_int32],
             "pahq_get_profile": [C.c_void_p, C.POINTER(KernelStat)],
             "pahq_quantize_rows_noalloc": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
+            "pahq_compare_encoders": [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)],
             "pahq_measure_ceilings": [C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double)],
         }
         for name, args in sig.items():
@@ -154,6 +155,16 @@ def measure_ceilings(scratch_mib=1024):
 def tau_grid(n=21, lo=1e-3, hi=10 ** 0.5):
     """The threshold grid of the paper's ROC scans: n log-spaced values from lo to hi (21 values in [0.001, 3.16])."""
     return np.exp(np.linspace(np.log(lo), np.log(hi), n)).astype(np.float32)
+
+
+def compare_encoders():
+    """(mismatches, example pattern) of the hardware E4M3 conversion against the defining encoder over all finite binary32."""
+    import torch
+    buf = torch.zeros(4, dtype=torch.int64, device="cuda:0")
+    n, ex = C.c_uint64(), C.c_uint32()
+    _chk(lib().pahq_compare_encoders(C.c_void_p(torch.cuda.current_stream().cuda_stream), C.c_void_p(buf.data_ptr()),
+                                     C.byref(n), C.byref(ex)), "pahq_compare_encoders")
+    return n.value, ex.value
 
 
 def quantize_rows_noalloc(x, codes, scales, stream=None):

@@ -6,6 +6,7 @@
 #include <stdint.h>
 #include "../../include/pahq.h"
 #include "mma_util.h"
+#include "device_util.h"
 
 namespace pahq {
 
@@ -44,7 +45,37 @@ __global__ __launch_bounds__(256) void stream_copy_k(const uint4* __restrict__ s
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Every binary32 pattern with the given upper 16 bits (one workgroup each): the code the kernels take (hardware
+// conversion) against the encoder on the bit pattern that defines it.  out[0] counts mismatches, out[1] keeps one.
+__global__ __launch_bounds__(256) void encoder_compare_k(unsigned long long* out) {
+  const uint32_t hi = blockIdx.x;
+  for (uint32_t lo = threadIdx.x; lo < 65536u; lo += 256u) {
+    const uint32_t u = (hi << 16) | lo;
+    const float y = __uint_as_float(u);
+    if (!(fabsf(y) <= 3.0e38f)) continue;                       // finite
+    if ((e4m3_encode(y) & 0xFFu) != (e4m3_encode_bits(y) & 0xFFu) ||
+        e4m3_encode4(y, -y, y, -y) != ((e4m3_encode_bits(y) & 0xFFu) * 0x00010001u | (e4m3_encode_bits(-y) & 0xFFu) * 0x01000100u)) {
+      atomicAdd(out, 1ull);
+      out[1] = u;
+    }
+  }
+}
+
 }  // namespace pahq
+
+extern "C" int pahq_compare_encoders(void* hip_stream, void* scratch, uint64_t* mismatches, uint32_t* example) {
+  using namespace pahq;
+  if (!scratch || !mismatches || (((uintptr_t)scratch) & 15)) return PAHQ_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  unsigned long long* out = (unsigned long long*)scratch;
+  unsigned long long h[2] = {0, 0};
+  if (hipMemcpyAsync(out, h, sizeof(h), hipMemcpyHostToDevice, st) != hipSuccess) return PAHQ_EHIP;
+  hipLaunchKernelGGL(encoder_compare_k, dim3(65536), dim3(256), 0, st, out);
+  if (hipMemcpyAsync(h, out, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess) return PAHQ_EHIP;
+  *mismatches = h[0];
+  if (example) *example = (uint32_t)h[1];
+  return hipGetLastError() == hipSuccess ? PAHQ_OK : PAHQ_EHIP;
+}
 
 extern "C" int pahq_measure_ceilings(void* hip_stream, void* scratch, size_t scratch_bytes, double* mfma_f16_tflops,
                                      double* copy_gbs) {

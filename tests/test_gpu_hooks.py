@@ -128,3 +128,12 @@ def test_fp8_matrix_core_adder_truncates():
         assert -2e-5 <= l8.mean() <= -1e-6                 # measured: -4.4e-6 (0.875 of the 15.875 the small products add up to)
     finally:
         g8.close(); gx.close()
+
+
+def test_hardware_conversion_equals_the_defining_encoder_on_every_pattern():
+    """The row kernels take E4M3 codes from the hardware conversion; the round-to-nearest-even encoder on the bit pattern
+    defines them (and is what the oracle's codec is pinned to through the weight and quantiser-site tests).  All finite
+    binary32 patterns, single and packed form."""
+    import paper_2510_23264_amd as P
+    n, example = P.binding.compare_encoders()
+    assert n == 0, hex(example)
