@@ -259,7 +259,9 @@ __global__ __launch_bounds__(256) void build_inputs_k(const GroupDesc* groups, c
   int rows = g.last_only ? B : T;
   if (row >= rows) return;
   long long src = (long long)(g.last_only ? row * S + S - 1 : row) * d;
-  int E = d >> 6;
+  // the vector forms with up to 16 values per lane are launched for exactly that width (PAHQ_DISPATCH_E): the width is
+  // then a constant and every `j < E` below folds away
+  const int E = (VEC && MAXE <= 16) ? MAXE : (d >> 6);
   float x[MAXE];
 #pragma unroll
   for (int j = 0; j < MAXE; j++) x[j] = 0.f;
@@ -305,7 +307,9 @@ __global__ __launch_bounds__(256) void build_inputs_shared_k(const GroupDesc* gr
   int rows = g.last_only ? B : T;
   if (row >= rows) return;
   long long src = (long long)(g.last_only ? row * S + S - 1 : row) * d;
-  int E = d >> 6;
+  // the vector forms with up to 16 values per lane are launched for exactly that width (PAHQ_DISPATCH_E): the width is
+  // then a constant and every `j < E` below folds away
+  const int E = (VEC && MAXE <= 16) ? MAXE : (d >> 6);
   const Term* tt = terms + g.term_begin;
   const bool base_shared = g.base && g.base_is == 0;
   float x0[MAXE];
@@ -348,7 +352,9 @@ __global__ __launch_bounds__(256) void patch_build_k(const GroupDesc* gp, const 
   int rows = g.last_only ? B : T;
   if (row >= rows) return;
   long long src = (long long)(g.last_only ? row * S + S - 1 : row) * d;
-  int E = d >> 6;
+  // the vector forms with up to 16 values per lane are launched for exactly that width (PAHQ_DISPATCH_E): the width is
+  // then a constant and every `j < E` below folds away
+  const int E = (VEC && MAXE <= 16) ? MAXE : (d >> 6);
   float x0[MAXE], y[MAXE];
 #pragma unroll
   for (int j = 0; j < MAXE; j++) x0[j] = 0.f;
@@ -378,7 +384,9 @@ __global__ __launch_bounds__(256) void patch_indep_k(const GroupDesc* gp, const 
   int rows = g.last_only ? B : T;
   if (row >= rows) return;
   long long src = (long long)(g.last_only ? row * S + S - 1 : row) * d;
-  int E = d >> 6;
+  // the vector forms with up to 16 values per lane are launched for exactly that width (PAHQ_DISPATCH_E): the width is
+  // then a constant and every `j < E` below folds away
+  const int E = (VEC && MAXE <= 16) ? MAXE : (d >> 6);
   float x0[MAXE], y[MAXE];
 #pragma unroll
   for (int j = 0; j < MAXE; j++) { x0[j] = 0.f; y[j] = 0.f; }
@@ -683,7 +691,9 @@ __global__ __launch_bounds__(256) void emit_rows_k(const float* x, int rows, int
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
-  const int E = d >> 6;
+  // the vector forms with up to 16 values per lane are launched for exactly that width (PAHQ_DISPATCH_E): the width is
+  // then a constant and every `j < E` below folds away
+  const int E = (VEC && MAXE <= 16) ? MAXE : (d >> 6);
   float y[MAXE];
 #pragma unroll
   for (int j = 0; j < MAXE; j++) y[j] = 0.f;
