@@ -457,19 +457,29 @@ hipError_t launch_patch_build(const GroupDesc* g, const float* xv, const float* 
 }
 
 // ------------------------------------------------------------------ tile arithmetic
-__global__ void xv_advance_k(float* xv, const float* delta0, long long delta_stride, const int* send, int k,
-                             long long n) {
+// Four senders' loads are in flight together; the subtractions keep the senders' order.
+__global__ void xv_advance_k(float4* xv, const float* delta0, long long delta_stride, const int* send, int k,
+                             long long n4) {
   long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  float x = xv[i];
-  for (int j = 0; j < k; j++) x -= delta0[(long long)send[j] * delta_stride + i];
+  if (i >= n4) return;
+  float4 x = xv[i];
+  auto ld = [&](int j) { return *(const float4*)(delta0 + (long long)send[j] * delta_stride + i * 4); };
+  auto sub = [&](const float4& v) { x.x -= v.x; x.y -= v.y; x.z -= v.z; x.w -= v.w; };
+  int j = 0;
+  for (; j + 4 <= k; j += 4) {
+    const float4 v0 = ld(j), v1 = ld(j + 1), v2 = ld(j + 2), v3 = ld(j + 3);
+    sub(v0); sub(v1); sub(v2); sub(v3);
+  }
+  for (; j < k; j++) sub(ld(j));
   xv[i] = x;
 }
 hipError_t launch_xv_advance(float* xv, const float* delta0, long long delta_stride, const int* send, int k,
                              long long n_elem, hipStream_t s) {
   if (k == 0) return hipSuccess;
-  hipLaunchKernelGGL(xv_advance_k, dim3((unsigned)((n_elem + 255) / 256)), dim3(256), 0, s, xv, delta0,
-                     delta_stride, send, k, n_elem);
+  if (n_elem % 4 != 0 || delta_stride % 4 != 0) return hipErrorInvalidValue;
+  const long long n4 = n_elem / 4;
+  hipLaunchKernelGGL(xv_advance_k, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, (float4*)xv, delta0,
+                     delta_stride, send, k, n4);
   return hipGetLastError();
 }
 
@@ -506,36 +516,71 @@ hipError_t launch_tile_sub(float* out, const float* a, const float* b, long long
 }
 
 // run_out = run_in + bias + sum_k src_k ; slot_k = src_k - sub_k
-__global__ void combine_k(const CombineDesc* descs, int di, const CombineSrc* srcs, long long n4, int d) {
+// A thread owns four values of up to four instances.  A dead layer's stand-ins arrive as tens of sources that are
+// the same tile for every instance: each is loaded once for the thread's instances, four sources' loads are in
+// flight together, and every instance's sum keeps the order of the sources.
+__global__ void combine_k(const CombineDesc* descs, int di, const CombineSrc* srcs, long long n4, int d, int n_inst) {
+  constexpr int IPT = 4;
   CombineDesc D = descs[di];
-  int inst = blockIdx.y;
+  const int inst0 = blockIdx.y * IPT, ni = min(IPT, n_inst - inst0);
   long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n4) return;
   long long e = i * 4;
-  float4 acc = *(const float4*)(D.run_in + inst * D.run_in_is + e);
-  if (D.bias) {
-    float4 b = *(const float4*)(D.bias + (e % d));
-    acc.x += b.x; acc.y += b.y; acc.z += b.z; acc.w += b.w;
+  float4 acc[IPT];
+  float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (D.bias) b = *(const float4*)(D.bias + (e % d));
+#pragma unroll
+  for (int q = 0; q < IPT; q++) {
+    acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (q >= ni) continue;
+    acc[q] = *(const float4*)(D.run_in + (inst0 + q) * D.run_in_is + e);
+    if (D.bias) { acc[q].x += b.x; acc[q].y += b.y; acc[q].z += b.z; acc[q].w += b.w; }
   }
-  for (int k = 0; k < D.n_src; k++) {
-    CombineSrc s = srcs[D.src_begin + k];
-    float4 v = s.bcast ? *(const float4*)(s.src + (e % d)) : *(const float4*)(s.src + inst * s.src_is + e);
-    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-    if (s.slot) {
-      if (s.sub) {
-        float4 u = *(const float4*)(s.sub + e);
-        v.x -= u.x; v.y -= u.y; v.z -= u.z; v.w -= u.w;
+  auto shared = [&](const CombineSrc& s) { return (s.bcast || s.src_is == 0) && !s.slot; };
+  auto ld = [&](const CombineSrc& s, int inst) {
+    return s.bcast ? *(const float4*)(s.src + (e % d)) : *(const float4*)(s.src + inst * s.src_is + e);
+  };
+  auto add_all = [&](const float4& v) {
+#pragma unroll
+    for (int q = 0; q < IPT; q++) { acc[q].x += v.x; acc[q].y += v.y; acc[q].z += v.z; acc[q].w += v.w; }
+  };
+  const CombineSrc* sp = srcs + D.src_begin;
+  int k = 0;
+  while (k < D.n_src) {
+    if (k + 4 <= D.n_src) {
+      const CombineSrc s0 = sp[k], s1 = sp[k + 1], s2 = sp[k + 2], s3 = sp[k + 3];
+      if (shared(s0) && shared(s1) && shared(s2) && shared(s3)) {
+        const float4 v0 = ld(s0, 0), v1 = ld(s1, 0), v2 = ld(s2, 0), v3 = ld(s3, 0);
+        add_all(v0); add_all(v1); add_all(v2); add_all(v3);
+        k += 4;
+        continue;
       }
-      *(float4*)(s.slot + inst * s.slot_is + e) = v;
+    }
+    const CombineSrc s0 = sp[k++];
+    if (shared(s0)) { add_all(ld(s0, 0)); continue; }
+#pragma unroll
+    for (int q = 0; q < IPT; q++) {
+      if (q >= ni) continue;
+      float4 v = ld(s0, inst0 + q);
+      acc[q].x += v.x; acc[q].y += v.y; acc[q].z += v.z; acc[q].w += v.w;
+      if (s0.slot) {
+        if (s0.sub) {
+          float4 u = *(const float4*)(s0.sub + e);
+          v.x -= u.x; v.y -= u.y; v.z -= u.z; v.w -= u.w;
+        }
+        *(float4*)(s0.slot + (inst0 + q) * s0.slot_is + e) = v;
+      }
     }
   }
-  *(float4*)(D.run_out + inst * D.run_out_is + e) = acc;
+#pragma unroll
+  for (int q = 0; q < IPT; q++)
+    if (q < ni) *(float4*)(D.run_out + (inst0 + q) * D.run_out_is + e) = acc[q];
 }
 hipError_t launch_combine(const CombineDesc* descs, int desc_index, const CombineSrc* srcs, int n_inst,
                           long long n_elem, int d, hipStream_t s) {
   long long n4 = n_elem / 4;
-  hipLaunchKernelGGL(combine_k, dim3((unsigned)((n4 + 255) / 256), n_inst), dim3(256), 0, s, descs, desc_index,
-                     srcs, n4, d);
+  hipLaunchKernelGGL(combine_k, dim3((unsigned)((n4 + 255) / 256), (n_inst + 3) / 4), dim3(256), 0, s, descs,
+                     desc_index, srcs, n4, d, n_inst);
   return hipGetLastError();
 }
 
