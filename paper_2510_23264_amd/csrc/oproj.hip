@@ -11,6 +11,8 @@
 #include "kernels.h"
 #include "device_util.h"
 #include "mma_util.h"
+#include <atomic>
+#include <type_traits>
 
 namespace pahq {
 
@@ -178,19 +180,35 @@ __global__ __launch_bounds__(256) void oproj_fused_k(const OprojDesc* descs, int
 // ------------------------------------------------------------------ exact sums, d_head 64 or 128
 // The same projection with the slab pipeline of the exact GEMM: slabs of 128 code bytes (one head
 // of 128, or two heads of 64: only the real codes are fetched, the padding of the stored rows is
-// skipped) go straight into swizzled LDS, two stages, one barrier per slab.  128 x 64 tile, four
-// wavefronts of 32 x 64.  A head's partial result is complete after one (d_head 64) or two
-// (d_head 128) 64-byte halves of a slab; it is scaled by z-scale[row][head] * w-scale[head] and
-// added to the running total in registers.  The fp32 head (skip_head) takes part with scale 0.
+// skipped) go straight into swizzled LDS.  128 x 64 tile, eight wavefronts of 32 x 32 (two workgroups
+// per compute unit, four waves per SIMD: a tile is a chain of short dependent steps - six slabs of 16
+// matrix instructions per wave, then the stream tile - and it is the number of waves in flight that
+// hides their latencies; four waves of 32 x 64 took a tenth longer).  A head's
+// partial result is complete after one (d_head 64) or two (d_head 128) 64-byte halves of a slab;
+// it is scaled by z-scale[row][head] * w-scale[head] and added to the running total in registers.
+// A head that is computed in fp32 elsewhere (skip mask) is multiplied like the others and left out of the sum.
+// Three stages of 25 KB, a slab requested two slabs before it is multiplied: with one slab of
+// look-ahead a workgroup waits for memory at every slab (a slab is far less work than the latency
+// of its loads under load).  For the waits to be countable every
+// load inside the loop goes into LDS by the same path, also the row scales of a slab's heads (one
+// dword per lane and wave with each slab) and the weight scales (once, before slab 0): a wave
+// waits for slab s with "at most the four operations of slab s + 1 outstanding".  A layer that
+// hands out per-head results issues stores and loads of its own inside the loop; it drains
+// instead of counting.
 // DH: bytes of a head's row of codes (64 or 128).  B16: they are bfloat16 patterns (d_head = DH / 2), multiplied
 // without conversion by V_MFMA_F32_16X16X32_BF16, one step per 16-byte operand read; everything else is the same.
+constexpr int OPX_STAGES = 3;
+constexpr int OPX_OPER = (128 + 64) * 128;                 // operand bytes of a stage
+constexpr int OPX_STAGE = OPX_OPER + 1024;                 // + row scales [heads of the slab][128]
+constexpr int OPX_LDS = OPX_STAGES * OPX_STAGE + 256;      // + weight scales [64]
 template <int DH, bool B16 = false>
-__global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int di, const HeadAux* auxs) {
-  constexpr int BM = 128, BN = 64, TM = 2, TN = 4, NI = 6, STAGE = (BM + BN) * 128;
+__global__ __launch_bounds__(512, 4) void oproj_x_k(const OprojDesc* descs, int di, const HeadAux* auxs) {
+  constexpr int BM = 128, BN = 64, TM = 2, TN = 2, NI = 3, NS = OPX_STAGES, STAGE = OPX_STAGE;
   constexpr int HPS = 128 / DH;            // heads per slab
   constexpr int CPH = 8 / HPS;             // 16-byte chunks per head
-  __shared__ __attribute__((aligned(1024))) uint8_t st0[STAGE];
-  __shared__ __attribute__((aligned(1024))) uint8_t st1[STAGE];
+  static_assert(NI + 1 == 4, "four loads per slab and wave: the wait counts below assume it");
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+  const float* const e_ws = (const float*)(smem + NS * STAGE);
   const OprojDesc D = descs[di];
   const int mt = (D.M + BM - 1) / BM, nt = (D.N + BN - 1) / BN;
   const int lin = xcd_tile(blockIdx.x, mt * nt);
@@ -198,8 +216,10 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
   const int m0 = (lin / nt) * BM, n0 = (lin % nt) * BN;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
   const int li = lane & 15, lg = lane >> 4;
   const int nslab = D.H / HPS;
+  const uint32_t lds0 = lds_addr_of(smem);
 
   // lane l of a load instruction fills LDS row l >> 3, chunk position l & 7, i.e. logical chunk
   // c = (l & 7) ^ (l >> 3) of the slab: head c / CPH of the slab, bytes 16 (c % CPH) of that head
@@ -220,22 +240,32 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
       stride[t] = (long long)HPS * D.N * D.Kh;
     }
   }
-  auto issue = [&](const uint8_t* st) {      // fetches the next slab and advances
-    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_addr_of(st) + wave * NI * 1024);
+  // row scales of a slab: entry [q][r] (head q of the slab, tile row r) is lane's if 64 wave + lane = 128 q + r;
+  // waves 4 .. 7 repeat what waves 0 .. 3 fetch (so that all waves count alike), and with one head per slab waves 2
+  // and 3 repeat rows 0 .. 127 into the unused half
+  const float* zsrc;
+  {
+    const int q = (HPS == 2) ? ((wave & 3) >> 1) : 0;
+    const int m = min(m0 + (wave & 1) * 64 + lane, D.M - 1);
+    zsrc = D.zs + (long long)(m / D.rpi) * D.zs_is + (long long)(m % D.rpi) * D.H + q;
+  }
+  int si = 0;                              // stage of the next request
+  auto issue = [&]() {                     // fetches the next slab and advances
+    const uint32_t st = lds0 + si * STAGE;
+    const uint32_t base = __builtin_amdgcn_readfirstlane(st + wave * NI * 1024);
 #pragma unroll
     for (int t = 0; t < NI; t++) { slab_load16(src[t], base + t * 1024); src[t] += stride[t]; }
+    lds_load4(zsrc, __builtin_amdgcn_readfirstlane(st + OPX_OPER + (wave & 3) * 256));
+    zsrc += HPS;
+    si = (si == NS - 1) ? 0 : si + 1;
   };
-  issue(st0);
+  const int mbase = m0 + wm * 32, nbase = n0 + wn * 32;
+  // weight scales of all heads, the same 64 dwords from every wave (so that all waves count alike)
+  lds_load4(D.ws + min(lane, D.H - 1), __builtin_amdgcn_readfirstlane(lds0 + NS * STAGE));
+  issue();
+  if (1 < nslab) issue();
 
-  const int mbase = m0 + wave * 32, nbase = n0;
-  const float* zs_p[TM];
-#pragma unroll
-  for (int i = 0; i < TM; i++) {
-    int m = min(mbase + i * 16 + li, D.M - 1);
-    zs_p[i] = D.zs + (long long)(m / D.rpi) * D.zs_is + (long long)(m % D.rpi) * D.H;
-  }
-
-  const int offA = (wave * 32 + li) * 128, offB = (BM + li) * 128;
+  const int offA = (wm * 32 + li) * 128, offB = (BM + wn * 32 + li) * 128;
   const int sw0 = (lg ^ (li & 7)) * 16, sw1 = ((4 + lg) ^ (li & 7)) * 16;
   v4f tot[TM][TN], acc[TM][TN];
 #pragma unroll
@@ -244,20 +274,22 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
     for (int j = 0; j < TN; j++) tot[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 
   // adds head h's finished partial result to the total and hands it out if some receiver needs it
-  auto fold = [&](int h, const float (&zsc)[TM]) {
-    const bool skip = ((D.skip_mask >> h) & 1ull) != 0;      // its codes and scales are whatever an earlier pass left
-    const float sw = skip ? 0.f : GCF(D.ws)[h];
+  auto fold = [&](auto aux_tag, int h, const float (&zsc)[TM]) {
+    constexpr bool AUX = decltype(aux_tag)::value;
+    // a head computed in fp32 elsewhere adds nothing here: its codes and scales are whatever an earlier pass left
+    // (the total starts at +0 and so never is -0: leaving the head out gives the bits of adding zeros)
+    if ((D.skip_mask >> h) & 1ull) return;
+    const float sw = e_ws[h];
     HeadAux ax; ax.dst = nullptr; ax.dst_is = 0; ax.sub = nullptr;
-    if (D.aux_begin >= 0 && !skip) ax = auxs[D.aux_begin + h];
+    if constexpr (AUX) ax = auxs[D.aux_begin + h];
 #pragma unroll
     for (int i = 0; i < TM; i++) {
-      const float sc = skip ? 0.f : zsc[i] * sw;
+      const float sc = zsc[i] * sw;
 #pragma unroll
       for (int j = 0; j < TN; j++) {
         float4 val = make_float4(acc[i][j][0] * sc, acc[i][j][1] * sc, acc[i][j][2] * sc, acc[i][j][3] * sc);
-        if (skip) val = make_float4(0.f, 0.f, 0.f, 0.f);
         tot[i][j][0] += val.x; tot[i][j][1] += val.y; tot[i][j][2] += val.z; tot[i][j][3] += val.w;
-        if (ax.dst) {
+        if constexpr (AUX) if (ax.dst) {
           int m = mbase + i * 16 + li, nb = nbase + j * 16 + lg * 4;
           if (m < D.M && nb < D.N) {
             long long off = (long long)(m % D.rpi) * D.N + nb;
@@ -268,14 +300,15 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
       }
     }
   };
-  auto compute = [&](const uint8_t* st, int s) {
+  auto compute = [&](auto aux_tag, const uint8_t* st, int s) {
     const uint8_t* sA = st + offA;
     const uint8_t* sB = st + offB;
+    const float* zrow = (const float*)(st + OPX_OPER) + wm * 32 + li;
     float zsc[HPS][TM];                      // requested now, used after the MFMAs of the half
 #pragma unroll
     for (int q = 0; q < HPS; q++)
 #pragma unroll
-      for (int i = 0; i < TM; i++) zsc[q][i] = GCF(zs_p[i])[s * HPS + q];
+      for (int i = 0; i < TM; i++) zsc[q][i] = zrow[q * BM + i * 16];
     // all operand reads of the slab first (the scheduler would otherwise sink them to their uses)
     uint4 ra[2][TM], rb[2][TN];
 #pragma unroll
@@ -323,23 +356,33 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
         }
       }
       }
-      if (HPS == 2) fold(2 * s + q, zsc[q]);
-      else if (q == 1) fold(s, zsc[0]);
+      if (HPS == 2) fold(aux_tag, 2 * s + q, zsc[q]);
+      else if (q == 1) fold(aux_tag, s, zsc[0]);
     }
   };
 
-  wait_all_then_barrier();
-  if (1 < nslab) issue(st1);
-  compute(st0, 0);
-  for (int s = 1; s < nslab; s += 2) {
-    wait_all_then_barrier();
-    if (s + 1 < nslab) issue(st0);
-    compute(st1, s);
-    if (s + 1 >= nslab) break;
-    wait_all_then_barrier();
-    if (s + 2 < nslab) issue(st1);
-    compute(st0, s + 1);
+  int sc = 0;                                // stage of the slab about to be multiplied
+  if (D.aux_begin < 0) {
+    // no vector-memory operation inside the loop but the slab requests (the code that hands out per-head results is
+    // not even compiled into this loop: the wait for its descriptor would sit where the two paths merge)
+    for (int s = 0; s < nslab; s++) {
+      // this wave's part of slab s has landed: all but the four operations of slab s + 1 are complete
+      if (s + 1 < nslab) wait_vm<4>(); else wait_vm<0>();
+      wg_barrier();                          // everyone's part has; the stage of slab s - 1 is free
+      if (s + 2 < nslab) issue();
+      compute(std::false_type{}, smem + sc * STAGE, s);
+      sc = (sc == NS - 1) ? 0 : sc + 1;
+    }
+  } else {
+    for (int s = 0; s < nslab; s++) {
+      wait_all_then_barrier();
+      if (s + 2 < nslab) issue();
+      compute(std::true_type{}, smem + sc * STAGE, s);
+      sc = (sc == NS - 1) ? 0 : sc + 1;
+    }
   }
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);        // nothing is outstanding; said with the builtin so that the compiler knows
 
 #pragma unroll
   for (int i = 0; i < TM; i++) {
@@ -355,10 +398,26 @@ __global__ __launch_bounds__(256, 2) void oproj_x_k(const OprojDesc* descs, int 
       if (D.bias) { float4 b = gload4(D.bias + nb); v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w; }
       v.x += tot[i][j][0]; v.y += tot[i][j][1]; v.z += tot[i][j][2]; v.w += tot[i][j][3];
       // the fp32 head goes in last, as in oproj_fused_k
-      if (D.extra) { float4 e = gload4(D.extra + inst_i * D.extra_is + roff + nb); v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w; }
+      if (D.extra) { const float4 e = gload4(D.extra + inst_i * D.extra_is + roff + nb); v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w; }
       gstore4(D.run_out + inst_i * D.run_out_is + roff + nb, v);
     }
   }
+}
+
+// The kernel's 75 KB of dynamic LDS need the attribute, which belongs to the kernel's code object on one device:
+// set once per device and instantiation (atomically: models on several streams or host threads may launch at once).
+template <int DH, bool B16>
+static hipError_t launch_oproj_x(dim3 grid, hipStream_t s, const OprojDesc* descs, int desc_index, const HeadAux* auxs) {
+  static std::atomic<bool> attr_set[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!attr_set[dev].load(std::memory_order_acquire)) {
+    hipError_t e = hipFuncSetAttribute((const void*)oproj_x_k<DH, B16>, hipFuncAttributeMaxDynamicSharedMemorySize, OPX_LDS);
+    if (e != hipSuccess) return e;
+    attr_set[dev].store(true, std::memory_order_release);
+  }
+  hipLaunchKernelGGL((oproj_x_k<DH, B16>), grid, dim3(512), OPX_LDS, s, descs, desc_index, auxs);
+  return hipGetLastError();
 }
 
 hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const HeadAux* auxs, int M, int N, int H, int dh,
@@ -369,13 +428,13 @@ hipError_t launch_oproj_fused(const OprojDesc* descs, int desc_index, const Head
   if (b16) {
     // bfloat16 attention outputs: heads of 32 or 64 values (64 or 128 bytes)
     if (!exact || (dh != 32 && dh != 64) || N % 4 != 0 || H % (64 / dh) != 0) return hipErrorInvalidValue;
-    if (dh == 32) hipLaunchKernelGGL((oproj_x_k<64, true>), grid, dim3(256), 0, s, descs, desc_index, auxs);
-    else hipLaunchKernelGGL((oproj_x_k<128, true>), grid, dim3(256), 0, s, descs, desc_index, auxs);
-    return hipGetLastError();
+    if (H > 64) return hipErrorInvalidValue;
+    if (dh == 32) return launch_oproj_x<64, true>(grid, s, descs, desc_index, auxs);
+    return launch_oproj_x<128, true>(grid, s, descs, desc_index, auxs);
   }
-  if (exact && (dh == 64 || dh == 128) && N % 4 == 0 && H % (128 / dh) == 0) {
-    if (dh == 64) hipLaunchKernelGGL((oproj_x_k<64>), grid, dim3(256), 0, s, descs, desc_index, auxs);
-    else hipLaunchKernelGGL((oproj_x_k<128>), grid, dim3(256), 0, s, descs, desc_index, auxs);
+  if (exact && (dh == 64 || dh == 128) && N % 4 == 0 && H % (128 / dh) == 0 && H <= 64) {
+    if (dh == 64) return launch_oproj_x<64, false>(grid, s, descs, desc_index, auxs);
+    return launch_oproj_x<128, false>(grid, s, descs, desc_index, auxs);
   } else if (exact) hipLaunchKernelGGL(oproj_fused_k<true>, grid, dim3(256), 0, s, descs, desc_index, auxs);
   else hipLaunchKernelGGL(oproj_fused_k<false>, grid, dim3(256), 0, s, descs, desc_index, auxs);
   return hipGetLastError();
